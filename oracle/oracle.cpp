@@ -1,0 +1,1042 @@
+// CPU oracle for the ATen-operator hot path.
+//
+// TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+// HIP library is checked against; the product never calls it.  Only the test
+// suite, the smoke check and the benchmark's cpu_baseline leg load it.  It
+// shares no source, header, table or helper with the HIP side.
+//
+// What it computes: the value an ATen operator returns on strided, typed,
+// broadcast host tensors -- the "reference ATen CPU implementation" that the
+// paper's test runner compares every generated kernel with (Section 3.2,
+// "System Design / Agent": device output vs. CPU reference on identical
+// inputs, dtype-dependent tolerance).  The paper names the operator set and
+// the dtypes (Section 3.3; Table 1 categories Elementwise, Reduction,
+// Indexing & Selection, and softmax from Deep Learning) and delegates the
+// semantics to the PyTorch operator documentation, so every function below
+// is the documented definition of its operator written out as one scalar
+// loop nest over the logical index space: offset = sum_d idx[d]*stride[d].
+// No blocking, no vectorisation, no reordering.
+//
+// Arithmetic policy:
+//   * integer / bool / index results: exact two's-complement arithmetic.
+//   * fp32 add / mul / where / neg / abs / maximum / eq: evaluated in IEEE
+//     binary32 (a single rounding, the same one the device must produce).
+//   * everything else with a floating result (div, transcendentals,
+//     reductions, softmax, cumsum, scatter_add): evaluated in binary64 from
+//     the (already converted) inputs and rounded ONCE to the output dtype.
+//   * fp16 / bf16 operands are first read exactly into binary32; results for
+//     a half output dtype are rounded once from the wider value.
+// Independent output elements may be computed by different OpenMP threads;
+// one accumulation is never split, so results do not depend on thread count.
+//
+// Parity pins: every function here is pinned by tests/test_oracle_*.py
+// (closed forms, invariants, brute force, mpmath); none is "parity unpinned".
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+extern "C" {
+
+enum { ORC_BOOL = 0, ORC_I32 = 1, ORC_I64 = 2, ORC_F16 = 3, ORC_BF16 = 4, ORC_F32 = 5 };
+enum { ORC_MAX_DIMS = 8 };
+
+// Plain descriptor of a host tensor.  strides are in elements.
+typedef struct {
+  void* data;
+  int32_t dtype;
+  int32_t ndim;
+  int64_t sizes[ORC_MAX_DIMS];
+  int64_t strides[ORC_MAX_DIMS];
+} orc_tensor;
+
+// error codes (negative)
+enum {
+  ORC_OK = 0,
+  ORC_ERR_NULL = -1,
+  ORC_ERR_NDIM = -2,
+  ORC_ERR_DTYPE = -3,
+  ORC_ERR_SHAPE = -4,
+  ORC_ERR_DIM = -5,
+  ORC_ERR_EMPTY_REDUCTION = -7,
+  ORC_ERR_SCALAR = -8,
+  ORC_ERR_INDEX = -10,
+};
+
+// op codes
+enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, ORC_GELU };
+enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ };
+enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR };
+
+}  // extern "C"
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// dtype helpers
+// ---------------------------------------------------------------------------
+inline int esize(int dt) {
+  switch (dt) {
+    case ORC_BOOL: return 1;
+    case ORC_I32: return 4;
+    case ORC_I64: return 8;
+    case ORC_F16: return 2;
+    case ORC_BF16: return 2;
+    case ORC_F32: return 4;
+  }
+  return 0;
+}
+inline bool valid_dtype(int dt) { return dt >= ORC_BOOL && dt <= ORC_F32; }
+// category: 0 bool, 1 integer, 2 floating
+inline int category(int dt) { return dt == ORC_BOOL ? 0 : (dt <= ORC_I64 ? 1 : 2); }
+inline bool is_float(int dt) { return category(dt) == 2; }
+
+// Same-rank promotion of two dtypes: within a category the wider type wins,
+// fp16 with bf16 gives fp32; across categories the higher category's type is
+// kept unchanged.
+int promote2(int a, int b) {
+  if (a == b) return a;
+  int ca = category(a), cb = category(b);
+  if (ca != cb) return ca > cb ? a : b;
+  if (ca == 1) return ORC_I64;                       // int32 with int64
+  // two different floating types
+  if (a == ORC_F32 || b == ORC_F32) return ORC_F32;
+  return ORC_F32;                                    // fp16 with bf16
+}
+
+// Result dtype of an n-ary tensor op.  Dimensioned operands (ndim >= 1) and
+// 0-dim operands are promoted as two separate groups; the 0-dim group changes
+// the result only when it is of a strictly higher category.
+int result_type(const orc_tensor* const* ops, int n) {
+  int D = -1, Z = -1;
+  for (int i = 0; i < n; ++i) {
+    if (ops[i]->ndim >= 1) D = D < 0 ? ops[i]->dtype : promote2(D, ops[i]->dtype);
+    else                   Z = Z < 0 ? ops[i]->dtype : promote2(Z, ops[i]->dtype);
+  }
+  if (D < 0) return Z;
+  if (Z < 0) return D;
+  return category(D) >= category(Z) ? D : Z;
+}
+
+// ---------------------------------------------------------------------------
+// binary16 / bfloat16 encodings, written from the IEEE-754 format definition.
+// ---------------------------------------------------------------------------
+// Decode a small binary format with `mb` mantissa bits and `eb` exponent bits.
+double decode_small(uint32_t bits, int eb, int mb) {
+  uint32_t sign = (bits >> (eb + mb)) & 1u;
+  uint32_t e = (bits >> mb) & ((1u << eb) - 1u);
+  uint32_t m = bits & ((1u << mb) - 1u);
+  int bias = (1 << (eb - 1)) - 1;
+  double v;
+  if (e == (1u << eb) - 1u) {
+    v = m ? std::numeric_limits<double>::quiet_NaN() : std::numeric_limits<double>::infinity();
+  } else if (e == 0) {
+    v = std::ldexp((double)m, 1 - bias - mb);        // subnormal (or zero)
+  } else {
+    v = std::ldexp((double)((1u << mb) | m), (int)e - bias - mb);
+  }
+  return sign ? -v : v;
+}
+
+// Round a binary64 value once (nearest, ties to even) into the small format.
+uint32_t encode_small(double v, int eb, int mb) {
+  uint32_t signbit = std::signbit(v) ? (1u << (eb + mb)) : 0u;
+  uint32_t emax_field = (1u << eb) - 1u;
+  int bias = (1 << (eb - 1)) - 1;
+  if (std::isnan(v)) return signbit | (emax_field << mb) | (1u << (mb - 1));
+  double a = std::fabs(v);
+  if (std::isinf(a)) return signbit | (emax_field << mb);
+  if (a == 0.0) return signbit;
+  int e;
+  std::frexp(a, &e);                                 // a = f * 2^e, f in [0.5,1)
+  int E = e - 1;                                     // a = 1.xxx * 2^E
+  int emin = 1 - bias;
+  if (E < emin) E = emin;                            // subnormal quantum
+  // a / 2^(E-mb) is an exact scaling; nearbyint rounds half to even in the
+  // default rounding mode.
+  double q = std::nearbyint(std::ldexp(a, -(E - mb)));
+  // q is in [0, 2^(mb+1)]; renormalise if rounding carried out.
+  if (q >= std::ldexp(1.0, mb + 1)) { q = std::ldexp(q, -1); E += 1; }
+  if (E > bias) return signbit | (emax_field << mb);  // overflow to infinity
+  uint64_t qi = (uint64_t)q;
+  if (qi < (1ull << mb)) {
+    // subnormal (E == emin and no hidden bit) or zero
+    return signbit | (uint32_t)qi;
+  }
+  uint32_t efield = (uint32_t)(E + bias);
+  return signbit | (efield << mb) | (uint32_t)(qi & ((1ull << mb) - 1ull));
+}
+
+inline double f16_to_double(uint16_t h) { return decode_small(h, 5, 10); }
+inline double bf16_to_double(uint16_t h) { return decode_small(h, 8, 7); }
+inline uint16_t double_to_f16(double v) { return (uint16_t)encode_small(v, 5, 10); }
+inline uint16_t double_to_bf16(double v) { return (uint16_t)encode_small(v, 8, 7); }
+
+// ---------------------------------------------------------------------------
+// typed element access
+// ---------------------------------------------------------------------------
+inline const char* cptr(const orc_tensor* t, int64_t off) {
+  return (const char*)t->data + off * esize(t->dtype);
+}
+inline char* mptr(const orc_tensor* t, int64_t off) {
+  return (char*)t->data + off * esize(t->dtype);
+}
+
+// integer-valued read (bool, int32, int64)
+inline int64_t load_int(const orc_tensor* t, int64_t off) {
+  const char* p = cptr(t, off);
+  switch (t->dtype) {
+    case ORC_BOOL: { uint8_t v; std::memcpy(&v, p, 1); return v != 0; }
+    case ORC_I32: { int32_t v; std::memcpy(&v, p, 4); return v; }
+    case ORC_I64: { int64_t v; std::memcpy(&v, p, 8); return v; }
+  }
+  return 0;
+}
+// floating read, exact (fp16, bf16, fp32 are all exactly representable)
+inline double load_flt(const orc_tensor* t, int64_t off) {
+  const char* p = cptr(t, off);
+  switch (t->dtype) {
+    case ORC_F16: { uint16_t v; std::memcpy(&v, p, 2); return f16_to_double(v); }
+    case ORC_BF16: { uint16_t v; std::memcpy(&v, p, 2); return bf16_to_double(v); }
+    case ORC_F32: { float v; std::memcpy(&v, p, 4); return (double)v; }
+  }
+  return 0.0;
+}
+
+// A value in some "common dtype": integers/bools live in `i`, floats in `f`.
+// For a floating common dtype the value held is already rounded to that dtype.
+struct Val {
+  int64_t i;
+  float f;
+};
+
+inline float round_to_float_dtype(double v, int dt) {
+  switch (dt) {
+    case ORC_F16: return (float)f16_to_double(double_to_f16(v));
+    case ORC_BF16: return (float)bf16_to_double(double_to_bf16(v));
+    default: return (float)v;
+  }
+}
+
+// Read operand element and convert it to the common dtype `cd`.
+inline Val load_as(const orc_tensor* t, int64_t off, int cd) {
+  Val r{0, 0.0f};
+  if (is_float(t->dtype)) {
+    double v = load_flt(t, off);
+    // a float operand is only ever converted to another float dtype here
+    r.f = (t->dtype == cd) ? (float)v : round_to_float_dtype(v, cd);
+    return r;
+  }
+  int64_t v = load_int(t, off);
+  switch (cd) {
+    case ORC_BOOL: r.i = v != 0; break;
+    case ORC_I32: r.i = (int64_t)(int32_t)(uint32_t)(uint64_t)v; break;
+    case ORC_I64: r.i = v; break;
+    case ORC_F32: r.f = (float)v; break;              // nearest-even
+    default: r.f = round_to_float_dtype((double)v, cd); break;
+  }
+  return r;
+}
+
+inline void store_int(const orc_tensor* t, int64_t off, int64_t v) {
+  char* p = mptr(t, off);
+  switch (t->dtype) {
+    case ORC_BOOL: { uint8_t b = v != 0; std::memcpy(p, &b, 1); break; }
+    case ORC_I32: { int32_t w = (int32_t)(uint32_t)(uint64_t)v; std::memcpy(p, &w, 4); break; }
+    case ORC_I64: std::memcpy(p, &v, 8); break;
+  }
+}
+// one rounding from binary64 into the floating output dtype
+inline void store_flt(const orc_tensor* t, int64_t off, double v) {
+  char* p = mptr(t, off);
+  switch (t->dtype) {
+    case ORC_F16: { uint16_t h = double_to_f16(v); std::memcpy(p, &h, 2); break; }
+    case ORC_BF16: { uint16_t h = double_to_bf16(v); std::memcpy(p, &h, 2); break; }
+    case ORC_F32: { float f = (float)v; std::memcpy(p, &f, 4); break; }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// shapes
+// ---------------------------------------------------------------------------
+inline int64_t numel(const orc_tensor* t) {
+  int64_t n = 1;
+  for (int d = 0; d < t->ndim; ++d) n *= t->sizes[d];
+  return n;
+}
+int check_tensor(const orc_tensor* t) {
+  if (!t) return ORC_ERR_NULL;
+  if (t->ndim < 0 || t->ndim > ORC_MAX_DIMS) return ORC_ERR_NDIM;
+  if (!valid_dtype(t->dtype)) return ORC_ERR_DTYPE;
+  for (int d = 0; d < t->ndim; ++d)
+    if (t->sizes[d] < 0) return ORC_ERR_SHAPE;
+  if (numel(t) > 0 && !t->data) return ORC_ERR_NULL;
+  return ORC_OK;
+}
+
+// Broadcast a list of shapes (right-aligned).  Returns <0 if incompatible.
+int broadcast_shapes(const orc_tensor* const* ops, int n, int* ondim, int64_t* osizes) {
+  int nd = 0;
+  for (int i = 0; i < n; ++i) nd = std::max(nd, (int)ops[i]->ndim);
+  for (int d = 0; d < nd; ++d) osizes[d] = 1;
+  for (int i = 0; i < n; ++i) {
+    int shift = nd - ops[i]->ndim;
+    for (int d = 0; d < ops[i]->ndim; ++d) {
+      int64_t s = ops[i]->sizes[d];
+      int64_t& o = osizes[d + shift];
+      if (s == o) continue;
+      if (o == 1) o = s;
+      else if (s != 1) return ORC_ERR_SHAPE;
+    }
+  }
+  *ondim = nd;
+  return ORC_OK;
+}
+
+// Turn a linear logical (row-major) index over `sizes` into a multi-index.
+inline void unravel(int64_t lin, int nd, const int64_t* sizes, int64_t* idx) {
+  for (int d = nd - 1; d >= 0; --d) {
+    int64_t s = sizes[d];
+    idx[d] = s ? lin % s : 0;
+    lin = s ? lin / s : 0;
+  }
+}
+inline int64_t offset_of(const orc_tensor* t, const int64_t* idx) {
+  int64_t o = 0;
+  for (int d = 0; d < t->ndim; ++d) o += idx[d] * t->strides[d];
+  return o;
+}
+// offset of operand `t` for output multi-index `idx` of rank `nd`, with
+// broadcasting: right-aligned, size-1 dims of the operand do not move.
+inline int64_t bcast_offset(const orc_tensor* t, int nd, const int64_t* idx) {
+  int shift = nd - t->ndim;
+  int64_t o = 0;
+  for (int d = 0; d < t->ndim; ++d)
+    if (t->sizes[d] != 1) o += idx[d + shift] * t->strides[d];
+  return o;
+}
+bool same_shape(const orc_tensor* t, int nd, const int64_t* sizes) {
+  if (t->ndim != nd) return false;
+  for (int d = 0; d < nd; ++d)
+    if (t->sizes[d] != sizes[d]) return false;
+  return true;
+}
+
+const double kNaN = std::numeric_limits<double>::quiet_NaN();
+const double kInf = std::numeric_limits<double>::infinity();
+
+}  // namespace
+
+extern "C" {
+
+// ===========================================================================
+// Result inference (dtype and shape), usable without data pointers.
+// ===========================================================================
+
+// Result dtype of a unary op given the input dtype, or an error.
+int orc_unary_result_dtype(int op, int in_dtype) {
+  if (!valid_dtype(in_dtype)) return ORC_ERR_DTYPE;
+  switch (op) {
+    case ORC_NEG:
+    case ORC_ABS:
+      return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
+    case ORC_EXP: case ORC_LOG: case ORC_SQRT: case ORC_SIGMOID: case ORC_TANH:
+      return is_float(in_dtype) ? in_dtype : ORC_F32;   // integral input computes in fp32
+    case ORC_GELU:
+      return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+  }
+  return ORC_ERR_DTYPE;
+}
+
+// Result dtype + broadcast shape of a binary op (ADD MUL DIV MAXIMUM EQ).
+int orc_infer_binary(int op, const orc_tensor* a, const orc_tensor* b, int32_t* dtype, int32_t* ndim,
+                     int64_t* sizes) {
+  if (!a || !b) return ORC_ERR_NULL;
+  if (!valid_dtype(a->dtype) || !valid_dtype(b->dtype)) return ORC_ERR_DTYPE;
+  if (a->ndim < 0 || a->ndim > ORC_MAX_DIMS || b->ndim < 0 || b->ndim > ORC_MAX_DIMS) return ORC_ERR_NDIM;
+  const orc_tensor* ops[2] = {a, b};
+  int common = result_type(ops, 2);
+  int res = common;
+  if (op == ORC_DIV && !is_float(common)) res = ORC_F32;   // true division
+  if (op == ORC_EQ) res = ORC_BOOL;
+  int nd;
+  int64_t s[ORC_MAX_DIMS];
+  int rc = broadcast_shapes(ops, 2, &nd, s);
+  if (rc) return rc;
+  if (dtype) *dtype = res;
+  if (ndim) *ndim = nd;
+  if (sizes) for (int d = 0; d < nd; ++d) sizes[d] = s[d];
+  return ORC_OK;
+}
+
+// Result dtype of where(cond, x, y): promotion of x and y only.
+int orc_where_result_dtype(const orc_tensor* x, const orc_tensor* y) {
+  const orc_tensor* ops[2] = {x, y};
+  return result_type(ops, 2);
+}
+
+// ===========================================================================
+// Elementwise: unary
+// ===========================================================================
+// out[i] = f(a[i]).  `out` must have a's shape and the inferred dtype.
+//   neg, abs      : exact; integers wrap (abs(INT_MIN) == INT_MIN); floats
+//                   flip / clear the sign bit (NaN and zeros included).
+//   exp log sqrt sigmoid tanh : binary64 evaluation of the input converted to
+//                   the result dtype, one rounding.  sigmoid = 1/(1+exp(-x)).
+//   gelu (erf form) : x * Phi(x), Phi the standard normal CDF.  Phi is taken
+//                   as erfc(-x/sqrt 2)/2, which is the same function as
+//                   (1+erf(x/sqrt 2))/2 but keeps its relative accuracy in the
+//                   negative tail, so the value rounded here is the true one.
+int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(a))) return rc;
+  int rd = orc_unary_result_dtype(op, a->dtype);
+  if (rd < 0) return rd;
+  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  if (!same_shape(out, a->ndim, a->sizes)) return ORC_ERR_SHAPE;
+  const int64_t n = numel(out);
+  const int nd = a->ndim;
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, out->sizes, idx);
+    int64_t oo = offset_of(out, idx), ao = offset_of(a, idx);
+    if (op == ORC_NEG || op == ORC_ABS) {
+      if (is_float(rd)) {
+        // sign-bit operations on the stored encoding: exact for every input
+        int es = esize(rd);
+        uint32_t bits = 0;
+        std::memcpy(&bits, cptr(a, ao), es);
+        uint32_t sb = 1u << (8 * es - 1);
+        bits = (op == ORC_NEG) ? (bits ^ sb) : (bits & ~sb);
+        std::memcpy(mptr(out, oo), &bits, es);
+      } else {
+        int64_t v = load_int(a, ao);
+        uint64_t u = (uint64_t)v;
+        if (op == ORC_NEG) u = 0 - u;
+        else if (v < 0) u = 0 - u;
+        store_int(out, oo, (int64_t)u);               // store wraps to the dtype
+      }
+      continue;
+    }
+    double x = (double)load_as(a, ao, rd).f;          // converted to result dtype first
+    double y = 0.0;
+    switch (op) {
+      case ORC_EXP: y = std::exp(x); break;
+      case ORC_LOG: y = std::log(x); break;
+      case ORC_SQRT: y = std::sqrt(x); break;
+      case ORC_SIGMOID: y = 1.0 / (1.0 + std::exp(-x)); break;
+      case ORC_TANH: y = std::tanh(x); break;
+      case ORC_GELU: y = x * (0.5 * std::erfc(-x * 0.70710678118654752440)); break;
+    }
+    store_flt(out, oo, y);
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// Elementwise: binary with broadcasting and type promotion
+// ===========================================================================
+// out = a (op) b on the broadcast shape.  Both operands are converted to the
+// common dtype first, then the op is applied.
+//   add     : a + alpha*b.  bool: a OR (alpha!=0 AND b).  integers: wrapping,
+//             alpha must be integral.  floats: alpha==1 is a single IEEE add;
+//             alpha!=1 is a single-rounding fused multiply-add fma(alpha,b,a)
+//             in binary32 (the half types compute in binary32 and round).
+//   mul     : product; bool AND; integers wrap.
+//   div     : true division; bool/integer operands are converted to fp32.
+//   maximum : NaN if either operand is NaN, else the larger (first operand on
+//             ties).
+//   eq      : equality in the common dtype, bool result.
+int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_tensor* b, double alpha_f,
+               int64_t alpha_i, int alpha_is_int) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(a)) || (rc = check_tensor(b))) return rc;
+  int32_t rd, nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = orc_infer_binary(op, a, b, &rd, &nd, sizes))) return rc;
+  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
+  const orc_tensor* ops[2] = {a, b};
+  int cd = result_type(ops, 2);                       // dtype the op is applied in
+  if (op == ORC_DIV && !is_float(cd)) cd = ORC_F32;
+  if (op == ORC_ADD && !is_float(cd) && !alpha_is_int) return ORC_ERR_SCALAR;
+  const double alpha_d = alpha_is_int ? (double)alpha_i : alpha_f;
+  const float alpha32 = (float)alpha_d;
+  const bool alpha_one = alpha_is_int ? (alpha_i == 1) : (alpha_f == 1.0);
+  const int64_t n = numel(out);
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    int64_t oo = offset_of(out, idx);
+    Val x = load_as(a, bcast_offset(a, nd, idx), cd);
+    Val y = load_as(b, bcast_offset(b, nd, idx), cd);
+    if (is_float(cd)) {
+      switch (op) {
+        case ORC_ADD: {
+          float r = alpha_one ? (x.f + y.f) : std::fmaf(alpha32, y.f, x.f);
+          store_flt(out, oo, (double)r);
+          break;
+        }
+        case ORC_MUL: {
+          float r = x.f * y.f;
+          store_flt(out, oo, (double)r);
+          break;
+        }
+        case ORC_DIV:
+          store_flt(out, oo, (double)x.f / (double)y.f);
+          break;
+        case ORC_MAXIMUM: {
+          float r = (std::isnan(x.f) || std::isnan(y.f)) ? std::numeric_limits<float>::quiet_NaN()
+                                                         : (y.f > x.f ? y.f : x.f);
+          store_flt(out, oo, (double)r);
+          break;
+        }
+        case ORC_EQ: store_int(out, oo, x.f == y.f); break;
+      }
+    } else if (cd == ORC_BOOL) {
+      switch (op) {
+        case ORC_ADD: store_int(out, oo, x.i | ((alpha_i != 0) & y.i)); break;
+        case ORC_MUL: store_int(out, oo, x.i & y.i); break;
+        case ORC_MAXIMUM: store_int(out, oo, x.i | y.i); break;
+        case ORC_EQ: store_int(out, oo, x.i == y.i); break;
+      }
+    } else {
+      uint64_t ux = (uint64_t)x.i, uy = (uint64_t)y.i;
+      switch (op) {
+        case ORC_ADD: store_int(out, oo, (int64_t)(ux + (uint64_t)alpha_i * uy)); break;
+        case ORC_MUL: store_int(out, oo, (int64_t)(ux * uy)); break;
+        case ORC_MAXIMUM: store_int(out, oo, y.i > x.i ? y.i : x.i); break;
+        case ORC_EQ: store_int(out, oo, x.i == y.i); break;
+      }
+    }
+  }
+  return ORC_OK;
+}
+
+// where(cond, x, y): cond must be bool; result dtype = promotion of x and y;
+// all three broadcast together.  The selected element is converted to the
+// result dtype; when no conversion is needed its bits are copied unchanged.
+int orc_where(const orc_tensor* out, const orc_tensor* cond, const orc_tensor* x, const orc_tensor* y) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(cond)) || (rc = check_tensor(x)) || (rc = check_tensor(y)))
+    return rc;
+  if (cond->dtype != ORC_BOOL) return ORC_ERR_DTYPE;
+  int rd = orc_where_result_dtype(x, y);
+  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  const orc_tensor* ops[3] = {cond, x, y};
+  int nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(ops, 3, &nd, sizes))) return rc;
+  if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
+  const int64_t n = numel(out);
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    int64_t oo = offset_of(out, idx);
+    bool c = load_int(cond, bcast_offset(cond, nd, idx)) != 0;
+    const orc_tensor* s = c ? x : y;
+    int64_t so = bcast_offset(s, nd, idx);
+    if (s->dtype == rd) {
+      std::memcpy(mptr(out, oo), cptr(s, so), esize(rd));
+    } else {
+      Val v = load_as(s, so, rd);
+      if (is_float(rd)) store_flt(out, oo, (double)v.f);
+      else store_int(out, oo, v.i);
+    }
+  }
+  return ORC_OK;
+}
+
+// masked_fill(self, mask, value): out = mask ? value : self.  mask is bool and
+// broadcasts with self; `value` is cast to self's dtype (a floating value
+// truncates toward zero into an integer dtype; into bool it is value != 0).
+int orc_masked_fill(const orc_tensor* out, const orc_tensor* self, const orc_tensor* mask, double value_f,
+                    int64_t value_i, int value_is_int) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(self)) || (rc = check_tensor(mask))) return rc;
+  if (mask->dtype != ORC_BOOL) return ORC_ERR_DTYPE;
+  if (out->dtype != self->dtype) return ORC_ERR_DTYPE;
+  const orc_tensor* ops[2] = {self, mask};
+  int nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(ops, 2, &nd, sizes))) return rc;
+  if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
+  const int dt = self->dtype;
+  // the fill value in self's dtype, encoded once
+  char fill[8] = {0};
+  {
+    orc_tensor tmp;
+    tmp.data = fill; tmp.dtype = dt; tmp.ndim = 0;
+    if (is_float(dt)) store_flt(&tmp, 0, value_is_int ? (double)value_i : value_f);
+    else if (dt == ORC_BOOL) store_int(&tmp, 0, value_is_int ? (value_i != 0) : (value_f != 0.0));
+    else store_int(&tmp, 0, value_is_int ? value_i : (int64_t)std::trunc(value_f));
+  }
+  const int64_t n = numel(out);
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    int64_t oo = offset_of(out, idx);
+    bool m = load_int(mask, bcast_offset(mask, nd, idx)) != 0;
+    if (m) std::memcpy(mptr(out, oo), fill, esize(dt));
+    else std::memcpy(mptr(out, oo), cptr(self, bcast_offset(self, nd, idx)), esize(dt));
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// Reductions
+// ===========================================================================
+// Normalise a dim list: wrap negatives, reject out-of-range and duplicates.
+// An empty list means all dims.  A 0-dim tensor accepts dim 0 / -1.
+static int normalise_dims(int nd, const int64_t* dims, int ndims, bool* reduced) {
+  for (int d = 0; d < ORC_MAX_DIMS; ++d) reduced[d] = false;
+  if (ndims == 0 || dims == nullptr) {
+    for (int d = 0; d < nd; ++d) reduced[d] = true;
+    return ORC_OK;
+  }
+  int lim = nd == 0 ? 1 : nd;
+  bool seen[ORC_MAX_DIMS] = {false};
+  for (int i = 0; i < ndims; ++i) {
+    int64_t d = dims[i];
+    if (d < -lim || d >= lim) return ORC_ERR_DIM;
+    if (d < 0) d += lim;
+    if (seen[d]) return ORC_ERR_DIM;
+    seen[d] = true;
+    if (nd > 0) reduced[d] = true;
+  }
+  return ORC_OK;
+}
+
+int orc_reduce_result_dtype(int op, int in_dtype) {
+  if (!valid_dtype(in_dtype)) return ORC_ERR_DTYPE;
+  switch (op) {
+    case ORC_SUM: case ORC_PROD: return is_float(in_dtype) ? in_dtype : ORC_I64;
+    case ORC_MEAN: case ORC_VAR: return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_AMAX: return in_dtype;
+    case ORC_ARGMAX: return in_dtype == ORC_BOOL ? (int)ORC_ERR_DTYPE : (int)ORC_I64;
+  }
+  return ORC_ERR_DTYPE;
+}
+
+int orc_infer_reduce(int op, const orc_tensor* x, const int64_t* dims, int32_t ndims, int keepdim, int32_t* dtype,
+                     int32_t* ndim, int64_t* sizes) {
+  if (!x) return ORC_ERR_NULL;
+  if (x->ndim < 0 || x->ndim > ORC_MAX_DIMS) return ORC_ERR_NDIM;
+  int rd = orc_reduce_result_dtype(op, x->dtype);
+  if (rd < 0) return rd;
+  bool all = (ndims == 0 || dims == nullptr);
+  if ((op == ORC_PROD || op == ORC_ARGMAX) && ndims > 1) return ORC_ERR_DIM;  // single dim or all
+  bool red[ORC_MAX_DIMS];
+  int rc = normalise_dims(x->ndim, dims, ndims, red);
+  if (rc) return rc;
+  (void)all;
+  int nd = 0;
+  for (int d = 0; d < x->ndim; ++d) {
+    if (red[d]) { if (keepdim) sizes[nd++] = 1; }
+    else sizes[nd++] = x->sizes[d];
+  }
+  if (dtype) *dtype = rd;
+  if (ndim) *ndim = nd;
+  return ORC_OK;
+}
+
+// Reduce x over `dims` (all dims when ndims == 0).
+//   sum   : integers/bool accumulate exactly in int64 (wrapping); floats
+//           accumulate sequentially in binary64, one rounding.
+//   mean  : that sum divided by the count (NaN for an empty extent).
+//   prod  : like sum with multiplication; empty product = 1.
+//   amax  : maximum, NaN if any element is NaN; empty reduced extent: error.
+//   argmax: index (along the one dim, or flat row-major over the logical
+//           shape) of the maximum; ties -> lowest index; NaN ranks above
+//           everything and the first NaN wins.  int64 result.
+//   var   : two passes in binary64: mean, then sum of squared deviations,
+//           divided by max(0, n - correction).
+// A floating `out` dtype wider than x's (fp32 out for a half x) is allowed for
+// sum / mean / prod / var: the single rounding then goes to that dtype.
+int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
+               double correction) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  int32_t rd, ond;
+  int64_t osz[ORC_MAX_DIMS];
+  if ((rc = orc_infer_reduce(op, x, dims, ndims, keepdim, &rd, &ond, osz))) return rc;
+  bool widen_ok = is_float(rd) && out->dtype == ORC_F32 && op != ORC_AMAX;
+  if (out->dtype != rd && !widen_ok) return ORC_ERR_DTYPE;
+  if (!same_shape(out, ond, osz)) return ORC_ERR_SHAPE;
+  bool red[ORC_MAX_DIMS];
+  normalise_dims(x->ndim, dims, ndims, red);
+  const int nd = x->ndim;
+  // kept and reduced dim lists in logical order
+  int kd[ORC_MAX_DIMS], rdm[ORC_MAX_DIMS], nk = 0, nr = 0;
+  int64_t ksz[ORC_MAX_DIMS], rsz[ORC_MAX_DIMS];
+  for (int d = 0; d < nd; ++d) {
+    if (red[d]) { rdm[nr] = d; rsz[nr++] = x->sizes[d]; }
+    else { kd[nk] = d; ksz[nk++] = x->sizes[d]; }
+  }
+  int64_t nout = 1, nred = 1;
+  for (int i = 0; i < nk; ++i) nout *= ksz[i];
+  for (int i = 0; i < nr; ++i) nred *= rsz[i];
+  if (nout == 0) return ORC_OK;
+  if ((op == ORC_AMAX || op == ORC_ARGMAX) && nred == 0) return ORC_ERR_EMPTY_REDUCTION;
+  const bool flt = is_float(x->dtype);
+  const bool single_dim = (nr == 1);
+
+#pragma omp parallel for schedule(static)
+  for (int64_t o = 0; o < nout; ++o) {
+    int64_t kidx[ORC_MAX_DIMS], ridx[ORC_MAX_DIMS], xi[ORC_MAX_DIMS], oi[ORC_MAX_DIMS];
+    unravel(o, nk, ksz, kidx);
+    for (int i = 0; i < nk; ++i) xi[kd[i]] = kidx[i];
+    // output multi-index
+    {
+      int p = 0, k = 0;
+      for (int d = 0; d < nd; ++d) {
+        if (red[d]) { if (keepdim) oi[p++] = 0; }
+        else oi[p++] = kidx[k++];
+      }
+    }
+    const int64_t oo = offset_of(out, oi);
+
+    double accd = (op == ORC_PROD) ? 1.0 : 0.0;
+    uint64_t acci = (op == ORC_PROD) ? 1u : 0u;
+    bool have = false, isnan_best = false;
+    double bestd = 0.0;
+    int64_t besti = 0, bestpos = 0;
+    double mean = 0.0;
+    if (op == ORC_VAR) {
+      double s = 0.0;
+      for (int64_t r = 0; r < nred; ++r) {
+        unravel(r, nr, rsz, ridx);
+        for (int i = 0; i < nr; ++i) xi[rdm[i]] = ridx[i];
+        s += load_flt(x, offset_of(x, xi));
+      }
+      mean = s / (double)nred;
+    }
+    for (int64_t r = 0; r < nred; ++r) {
+      unravel(r, nr, rsz, ridx);
+      for (int i = 0; i < nr; ++i) xi[rdm[i]] = ridx[i];
+      const int64_t xo = offset_of(x, xi);
+      const int64_t pos = single_dim ? ridx[0] : r;
+      switch (op) {
+        case ORC_SUM: case ORC_MEAN:
+          if (flt) accd += load_flt(x, xo); else acci += (uint64_t)load_int(x, xo);
+          break;
+        case ORC_PROD:
+          if (flt) accd *= load_flt(x, xo); else acci *= (uint64_t)load_int(x, xo);
+          break;
+        case ORC_VAR: {
+          double dlt = load_flt(x, xo) - mean;
+          accd += dlt * dlt;
+          break;
+        }
+        case ORC_AMAX: case ORC_ARGMAX:
+          if (flt) {
+            double v = load_flt(x, xo);
+            if (!have) { bestd = v; bestpos = pos; have = true; isnan_best = std::isnan(v); }
+            else if (!isnan_best && (std::isnan(v) || v > bestd)) { bestd = v; bestpos = pos; isnan_best = std::isnan(v); }
+          } else {
+            int64_t v = load_int(x, xo);
+            if (!have || v > besti) { besti = v; bestpos = pos; have = true; }
+          }
+          break;
+      }
+    }
+    switch (op) {
+      case ORC_SUM: case ORC_PROD:
+        if (flt) store_flt(out, oo, accd); else store_int(out, oo, (int64_t)acci);
+        break;
+      case ORC_MEAN:
+        store_flt(out, oo, nred ? accd / (double)nred : kNaN);
+        break;
+      case ORC_VAR: {
+        double div = (double)nred - correction;
+        if (div < 0.0) div = 0.0;
+        store_flt(out, oo, nred ? accd / div : kNaN);
+        break;
+      }
+      case ORC_AMAX:
+        if (flt) store_flt(out, oo, bestd); else store_int(out, oo, besti);
+        break;
+      case ORC_ARGMAX:
+        store_int(out, oo, bestpos);
+        break;
+    }
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// softmax / log_softmax along one dim
+// ===========================================================================
+// m = max over the slice; softmax = exp(x-m) / sum exp(x-m);
+// log_softmax = (x-m) - log sum exp(x-m).  binary64 throughout, one rounding.
+// IEEE arithmetic gives the special cases: a -inf entry -> 0 / -inf; a slice
+// that is all -inf, or contains +inf or NaN -> all NaN.  `out` may be fp32 for
+// a half input (the dtype= variant).
+int orc_softmax(const orc_tensor* out, const orc_tensor* x, int64_t dim, int is_log) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  if (!is_float(x->dtype)) return ORC_ERR_DTYPE;
+  if (out->dtype != x->dtype && out->dtype != ORC_F32) return ORC_ERR_DTYPE;
+  if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  const int nd = x->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  const int64_t L = nd == 0 ? 1 : x->sizes[dim];
+  const int64_t xs = nd == 0 ? 0 : x->strides[dim], os = nd == 0 ? 0 : out->strides[dim];
+  // the other dims
+  int64_t osz[ORC_MAX_DIMS];
+  int od[ORC_MAX_DIMS], nod = 0;
+  for (int d = 0; d < nd; ++d) if (d != dim) { od[nod] = d; osz[nod++] = x->sizes[d]; }
+  int64_t nslices = 1;
+  for (int i = 0; i < nod; ++i) nslices *= osz[i];
+  if (nslices == 0 || L == 0) return ORC_OK;
+#pragma omp parallel for schedule(static)
+  for (int64_t s = 0; s < nslices; ++s) {
+    int64_t sidx[ORC_MAX_DIMS], xi[ORC_MAX_DIMS] = {0};
+    unravel(s, nod, osz, sidx);
+    for (int i = 0; i < nod; ++i) xi[od[i]] = sidx[i];
+    const int64_t xb = offset_of(x, xi), ob = offset_of(out, xi);
+    double m = -kInf;
+    bool anynan = false;
+    for (int64_t j = 0; j < L; ++j) {
+      double v = load_flt(x, xb + j * xs);
+      if (std::isnan(v)) anynan = true;
+      if (v > m) m = v;
+    }
+    if (anynan) m = kNaN;
+    double sum = 0.0;
+    for (int64_t j = 0; j < L; ++j) sum += std::exp(load_flt(x, xb + j * xs) - m);
+    const double lsum = std::log(sum);
+    for (int64_t j = 0; j < L; ++j) {
+      double d = load_flt(x, xb + j * xs) - m;
+      store_flt(out, ob + j * os, is_log ? d - lsum : std::exp(d) / sum);
+    }
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// cumsum along one dim (inclusive)
+// ===========================================================================
+// bool / int32 / int64 input -> int64 output, exact wrapping sums.  Floating
+// input: running binary64 accumulator, each prefix rounded independently to
+// the output dtype (x's dtype, or fp32 for a half x).
+int orc_cumsum(const orc_tensor* out, const orc_tensor* x, int64_t dim) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  const bool flt = is_float(x->dtype);
+  if (flt) { if (out->dtype != x->dtype && out->dtype != ORC_F32) return ORC_ERR_DTYPE; }
+  else if (out->dtype != ORC_I64) return ORC_ERR_DTYPE;
+  if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  const int nd = x->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  const int64_t L = nd == 0 ? 1 : x->sizes[dim];
+  const int64_t xs = nd == 0 ? 0 : x->strides[dim], os = nd == 0 ? 0 : out->strides[dim];
+  int64_t osz[ORC_MAX_DIMS];
+  int od[ORC_MAX_DIMS], nod = 0;
+  for (int d = 0; d < nd; ++d) if (d != dim) { od[nod] = d; osz[nod++] = x->sizes[d]; }
+  int64_t nslices = 1;
+  for (int i = 0; i < nod; ++i) nslices *= osz[i];
+  if (nslices == 0 || L == 0) return ORC_OK;
+#pragma omp parallel for schedule(static)
+  for (int64_t s = 0; s < nslices; ++s) {
+    int64_t sidx[ORC_MAX_DIMS], xi[ORC_MAX_DIMS] = {0};
+    unravel(s, nod, osz, sidx);
+    for (int i = 0; i < nod; ++i) xi[od[i]] = sidx[i];
+    const int64_t xb = offset_of(x, xi), ob = offset_of(out, xi);
+    double accd = 0.0;
+    uint64_t acci = 0;
+    for (int64_t j = 0; j < L; ++j) {
+      if (flt) { accd += load_flt(x, xb + j * xs); store_flt(out, ob + j * os, accd); }
+      else { acci += (uint64_t)load_int(x, xb + j * xs); store_int(out, ob + j * os, (int64_t)acci); }
+    }
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// Indexing
+// ===========================================================================
+static inline bool index_dtype_ok(int dt) { return dt == ORC_I32 || dt == ORC_I64; }
+
+// gather: out[i0..] = src[i0.. with coordinate `dim` replaced by index[i0..]].
+// out has index's shape and src's dtype.  No negative-index wrap-around.
+int orc_gather(const orc_tensor* out, const orc_tensor* src, int64_t dim, const orc_tensor* index) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(src)) || (rc = check_tensor(index))) return rc;
+  if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
+  if (out->dtype != src->dtype) return ORC_ERR_DTYPE;
+  if (index->ndim != src->ndim) return ORC_ERR_SHAPE;
+  const int nd = src->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  for (int d = 0; d < nd; ++d)
+    if (d != dim && index->sizes[d] > src->sizes[d]) return ORC_ERR_SHAPE;
+  if (!same_shape(out, index->ndim, index->sizes)) return ORC_ERR_SHAPE;
+  const int64_t n = numel(out);
+  const int64_t extent = nd == 0 ? 1 : src->sizes[dim];
+  const int es = esize(src->dtype);
+  int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, out->sizes, idx);
+    int64_t oo = offset_of(out, idx);
+    int64_t k = load_int(index, offset_of(index, idx));
+    if (k < 0 || k >= extent) { bad |= 1; continue; }
+    if (nd) idx[dim] = k;
+    std::memcpy(mptr(out, oo), cptr(src, offset_of(src, idx)), es);
+  }
+  return bad ? ORC_ERR_INDEX : ORC_OK;
+}
+
+// index_select: out = src with extent `dim` replaced by len(index); slice j of
+// out along dim is slice index[j] of src.  index is 1-D (or 0-dim = length 1).
+int orc_index_select(const orc_tensor* out, const orc_tensor* src, int64_t dim, const orc_tensor* index) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(src)) || (rc = check_tensor(index))) return rc;
+  if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
+  if (out->dtype != src->dtype) return ORC_ERR_DTYPE;
+  if (index->ndim > 1) return ORC_ERR_SHAPE;
+  const int nd = src->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  const int64_t ni = index->ndim == 0 ? 1 : index->sizes[0];
+  const int64_t istride = index->ndim == 0 ? 0 : index->strides[0];
+  if (nd == 0) {
+    if (ni != 1 || out->ndim != 0) return ORC_ERR_SHAPE;
+  } else {
+    if (out->ndim != nd) return ORC_ERR_SHAPE;
+    for (int d = 0; d < nd; ++d)
+      if (out->sizes[d] != (d == dim ? ni : src->sizes[d])) return ORC_ERR_SHAPE;
+  }
+  const int64_t n = numel(out);
+  const int64_t extent = nd == 0 ? 1 : src->sizes[dim];
+  const int es = esize(src->dtype);
+  int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, out->sizes, idx);
+    int64_t oo = offset_of(out, idx);
+    int64_t j = nd ? idx[dim] : 0;
+    int64_t k = load_int(index, j * istride);
+    if (k < 0 || k >= extent) { bad |= 1; continue; }
+    if (nd) idx[dim] = k;
+    std::memcpy(mptr(out, oo), cptr(src, offset_of(src, idx)), es);
+  }
+  return bad ? ORC_ERR_INDEX : ORC_OK;
+}
+
+// scatter_add_ (in place on self): for every position p of index,
+//   self[p with coordinate dim = index[p]] += src[p].
+// integers / bool: exact, in position order (bool: OR).  Floating dtypes: the
+// contributions of each destination element are accumulated in binary64 in
+// position order, the initial value of self is added, one rounding.
+int orc_scatter_add(const orc_tensor* self, int64_t dim, const orc_tensor* index, const orc_tensor* src) {
+  int rc;
+  if ((rc = check_tensor(self)) || (rc = check_tensor(index)) || (rc = check_tensor(src))) return rc;
+  if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
+  if (self->dtype != src->dtype) return ORC_ERR_DTYPE;
+  if (index->ndim != self->ndim || src->ndim != self->ndim) return ORC_ERR_SHAPE;
+  const int nd = self->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  for (int d = 0; d < nd; ++d) {
+    if (index->sizes[d] > src->sizes[d]) return ORC_ERR_SHAPE;
+    if (d != dim && index->sizes[d] > self->sizes[d]) return ORC_ERR_SHAPE;
+  }
+  const int64_t n = numel(index);
+  if (n == 0) return ORC_OK;
+  const int64_t extent = nd == 0 ? 1 : self->sizes[dim];
+  // validate all indices first so that nothing is written on error
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, index->sizes, idx);
+    int64_t k = load_int(index, offset_of(index, idx));
+    if (k < 0 || k >= extent) return ORC_ERR_INDEX;
+  }
+  const bool flt = is_float(self->dtype);
+  const int64_t nself = numel(self);
+  std::vector<double> acc;
+  std::vector<uint8_t> touched;
+  int64_t lstr[ORC_MAX_DIMS];                          // row-major strides of self's logical shape
+  if (flt) {
+    acc.assign((size_t)nself, 0.0);
+    touched.assign((size_t)nself, 0);
+    int64_t s = 1;
+    for (int d = nd - 1; d >= 0; --d) { lstr[d] = s; s *= self->sizes[d]; }
+  }
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, index->sizes, idx);
+    int64_t k = load_int(index, offset_of(index, idx));
+    int64_t so = offset_of(src, idx);
+    if (nd) idx[dim] = k;
+    if (flt) {
+      int64_t l = 0;
+      for (int d = 0; d < nd; ++d) l += idx[d] * lstr[d];
+      acc[(size_t)l] += load_flt(src, so);
+      touched[(size_t)l] = 1;
+    } else {
+      int64_t d = offset_of(self, idx);
+      if (self->dtype == ORC_BOOL) store_int(self, d, load_int(self, d) | load_int(src, so));
+      else store_int(self, d, (int64_t)((uint64_t)load_int(self, d) + (uint64_t)load_int(src, so)));
+    }
+  }
+  if (flt) {
+    for (int64_t l = 0; l < nself; ++l) {
+      if (!touched[(size_t)l]) continue;               // untouched elements keep their bits
+      int64_t idx[ORC_MAX_DIMS] = {0};
+      unravel(l, nd, self->sizes, idx);
+      int64_t d = offset_of(self, idx);
+      store_flt(self, d, load_flt(self, d) + acc[(size_t)l]);
+    }
+  }
+  return ORC_OK;
+}
+
+// Test hooks for the format codecs: encode a binary64 value into `dtype`
+// (F16 / BF16 / F32) with one rounding, and decode a bit pattern exactly.
+uint32_t orc_encode(double v, int dtype) {
+  if (dtype == ORC_F16) return double_to_f16(v);
+  if (dtype == ORC_BF16) return double_to_bf16(v);
+  float f = (float)v;
+  uint32_t b;
+  std::memcpy(&b, &f, 4);
+  return b;
+}
+double orc_decode(uint32_t bits, int dtype) {
+  if (dtype == ORC_F16) return f16_to_double((uint16_t)bits);
+  if (dtype == ORC_BF16) return bf16_to_double((uint16_t)bits);
+  float f;
+  std::memcpy(&f, &bits, 4);
+  return (double)f;
+}
+
+// Number of OpenMP threads a parallel region will use (for reporting).
+int orc_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+}  // extern "C"

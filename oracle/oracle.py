@@ -1,0 +1,233 @@
+"""ctypes front end of the CPU oracle (test infrastructure only).
+
+Takes torch CPU tensors (torch is used purely as a typed host buffer that can
+hold bf16 / fp16), describes them to liboracle.so and returns new CPU tensors.
+Nothing in the product imports this module.
+"""
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+MAX_DIMS = 8
+BOOL, I32, I64, F16, BF16, F32 = range(6)
+DTYPE_CODE = {torch.bool: BOOL, torch.int32: I32, torch.int64: I64, torch.float16: F16,
+              torch.bfloat16: BF16, torch.float32: F32}
+CODE_DTYPE = {v: k for k, v in DTYPE_CODE.items()}
+
+UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7}
+BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4}
+REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5}
+
+ERRORS = {-1: "null", -2: "ndim", -3: "dtype", -4: "shape", -5: "dim", -7: "empty_reduction",
+          -8: "scalar", -10: "index"}
+
+
+class OracleError(Exception):
+    def __init__(self, code):
+        super().__init__("oracle error %d (%s)" % (code, ERRORS.get(code, "?")))
+        self.code = code
+        self.kind = ERRORS.get(code, "?")
+
+
+class OrcTensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("ndim", ctypes.c_int32),
+                ("sizes", ctypes.c_int64 * MAX_DIMS), ("strides", ctypes.c_int64 * MAX_DIMS)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        _lib = ctypes.CDLL(path)
+        P = ctypes.POINTER(OrcTensor)
+        I64P = ctypes.POINTER(ctypes.c_int64)
+        I32P = ctypes.POINTER(ctypes.c_int32)
+        _lib.orc_unary.argtypes = [ctypes.c_int, P, P]
+        _lib.orc_binary.argtypes = [ctypes.c_int, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
+        _lib.orc_where.argtypes = [P, P, P, P]
+        _lib.orc_masked_fill.argtypes = [P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
+        _lib.orc_reduce.argtypes = [ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int, ctypes.c_double]
+        _lib.orc_softmax.argtypes = [P, P, ctypes.c_int64, ctypes.c_int]
+        _lib.orc_cumsum.argtypes = [P, P, ctypes.c_int64]
+        _lib.orc_gather.argtypes = [P, P, ctypes.c_int64, P]
+        _lib.orc_index_select.argtypes = [P, P, ctypes.c_int64, P]
+        _lib.orc_scatter_add.argtypes = [P, ctypes.c_int64, P, P]
+        _lib.orc_infer_binary.argtypes = [ctypes.c_int, P, P, I32P, I32P, I64P]
+        _lib.orc_infer_reduce.argtypes = [ctypes.c_int, P, I64P, ctypes.c_int32, ctypes.c_int, I32P, I32P, I64P]
+        _lib.orc_unary_result_dtype.argtypes = [ctypes.c_int, ctypes.c_int]
+        _lib.orc_where_result_dtype.argtypes = [P, P]
+        _lib.orc_reduce_result_dtype.argtypes = [ctypes.c_int, ctypes.c_int]
+        _lib.orc_encode.argtypes = [ctypes.c_double, ctypes.c_int]
+        _lib.orc_encode.restype = ctypes.c_uint32
+        _lib.orc_decode.argtypes = [ctypes.c_uint32, ctypes.c_int]
+        _lib.orc_decode.restype = ctypes.c_double
+    return _lib
+
+
+def desc(t):
+    assert t.device.type == "cpu", "the oracle works on host memory"
+    d = OrcTensor()
+    d.data = t.data_ptr()
+    d.dtype = DTYPE_CODE[t.dtype]
+    d.ndim = t.dim()
+    for i in range(t.dim()):
+        d.sizes[i] = t.size(i)
+        d.strides[i] = t.stride(i)
+    return d
+
+
+def _check(rc):
+    if rc != 0:
+        raise OracleError(rc)
+
+
+def _scalar(v):
+    """(double, int64, is_int) triple for a Python scalar."""
+    if isinstance(v, bool):
+        return float(v), int(v), 1
+    if isinstance(v, int):
+        return float(v), v, 1
+    return float(v), 0, 0
+
+
+def num_threads():
+    return lib().orc_num_threads()
+
+
+# --------------------------------------------------------------------------- inference
+def infer_binary(op, a, b):
+    dt, nd = ctypes.c_int32(), ctypes.c_int32()
+    sizes = (ctypes.c_int64 * MAX_DIMS)()
+    _check(lib().orc_infer_binary(BINARY[op], desc(a), desc(b), ctypes.byref(dt), ctypes.byref(nd), sizes))
+    return CODE_DTYPE[dt.value], tuple(sizes[i] for i in range(nd.value))
+
+
+def infer_reduce(op, x, dims=None, keepdim=False):
+    dims = _dims(dims)
+    arr = (ctypes.c_int64 * max(1, len(dims)))(*dims)
+    dt, nd = ctypes.c_int32(), ctypes.c_int32()
+    sizes = (ctypes.c_int64 * MAX_DIMS)()
+    _check(lib().orc_infer_reduce(REDUCE[op], desc(x), arr, len(dims), int(keepdim), ctypes.byref(dt),
+                                  ctypes.byref(nd), sizes))
+    return CODE_DTYPE[dt.value], tuple(sizes[i] for i in range(nd.value))
+
+
+def unary_result_dtype(op, dtype):
+    rc = lib().orc_unary_result_dtype(UNARY[op], DTYPE_CODE[dtype])
+    _check(min(rc, 0))
+    return CODE_DTYPE[rc]
+
+
+def where_result_dtype(x, y):
+    return CODE_DTYPE[lib().orc_where_result_dtype(desc(x), desc(y))]
+
+
+# --------------------------------------------------------------------------- elementwise
+def unary(op, a, out=None):
+    if out is None:
+        out = torch.empty(a.shape, dtype=unary_result_dtype(op, a.dtype))
+    _check(lib().orc_unary(UNARY[op], desc(out), desc(a)))
+    return out
+
+
+def binary(op, a, b, alpha=1, out=None):
+    if out is None:
+        dt, shape = infer_binary(op, a, b)
+        out = torch.empty(shape, dtype=dt)
+    af, ai, isint = _scalar(alpha)
+    _check(lib().orc_binary(BINARY[op], desc(out), desc(a), desc(b), af, ai, isint))
+    return out
+
+
+def where(cond, x, y, out=None):
+    if out is None:
+        shape = torch.broadcast_shapes(cond.shape, x.shape, y.shape)
+        out = torch.empty(shape, dtype=where_result_dtype(x, y))
+    _check(lib().orc_where(desc(out), desc(cond), desc(x), desc(y)))
+    return out
+
+
+def masked_fill(self, mask, value, out=None):
+    if out is None:
+        out = torch.empty(torch.broadcast_shapes(self.shape, mask.shape), dtype=self.dtype)
+    vf, vi, isint = _scalar(value)
+    _check(lib().orc_masked_fill(desc(out), desc(self), desc(mask), vf, vi, isint))
+    return out
+
+
+# --------------------------------------------------------------------------- reductions
+def _dims(dims):
+    if dims is None:
+        return []
+    if isinstance(dims, int):
+        return [dims]
+    return list(dims)
+
+
+def reduce(op, x, dims=None, keepdim=False, correction=1.0, out=None, out_dtype=None):
+    dl = _dims(dims)
+    if out is None:
+        dt, shape = infer_reduce(op, x, dl, keepdim)
+        out = torch.empty(shape, dtype=out_dtype or dt)
+    arr = (ctypes.c_int64 * max(1, len(dl)))(*dl)
+    _check(lib().orc_reduce(REDUCE[op], desc(out), desc(x), arr, len(dl), int(keepdim), float(correction)))
+    return out
+
+
+def softmax(x, dim=-1, log=False, out=None, out_dtype=None):
+    if out is None:
+        out = torch.empty(x.shape, dtype=out_dtype or x.dtype)
+    _check(lib().orc_softmax(desc(out), desc(x), dim, int(log)))
+    return out
+
+
+def cumsum(x, dim=-1, out=None, out_dtype=None):
+    if out is None:
+        dt = x.dtype if x.dtype.is_floating_point else torch.int64
+        out = torch.empty(x.shape, dtype=out_dtype or dt)
+    _check(lib().orc_cumsum(desc(out), desc(x), dim))
+    return out
+
+
+# --------------------------------------------------------------------------- indexing
+def gather(src, dim, index, out=None):
+    if out is None:
+        out = torch.empty(index.shape, dtype=src.dtype)
+    _check(lib().orc_gather(desc(out), desc(src), dim, desc(index)))
+    return out
+
+
+def index_select(src, dim, index, out=None):
+    if out is None:
+        if src.dim() == 0:
+            shape = ()
+        else:
+            shape = list(src.shape)
+            if not -src.dim() <= dim < src.dim():
+                raise OracleError(-5)
+            shape[dim] = index.numel()
+        out = torch.empty(shape, dtype=src.dtype)
+    _check(lib().orc_index_select(desc(out), desc(src), dim, desc(index)))
+    return out
+
+
+def scatter_add_(self, dim, index, src):
+    _check(lib().orc_scatter_add(desc(self), dim, desc(index), desc(src)))
+    return self
+
+
+# --------------------------------------------------------------------------- codec hooks
+def encode(v, dtype):
+    return lib().orc_encode(float(v), DTYPE_CODE[dtype])
+
+
+def decode(bits, dtype):
+    return lib().orc_decode(int(bits), DTYPE_CODE[dtype])
