@@ -1,0 +1,222 @@
+/*
+ * txops.h -- C ABI of the MI355X (gfx950) ATen-semantics operator library.
+ *
+ * The library executes the operator classes that the paper's agent generates
+ * kernels for (Section 3.3: the ATen operator set exercised by OpInfo, dtypes
+ * bf16 / fp16 / fp32 / int32 / int64, here plus bool; Table 1 categories
+ * Elementwise, Reduction, Indexing & Selection, and softmax from Deep
+ * Learning).  A call must return what the ATen CPU operator returns on the
+ * same strided, typed operands (Section 3.2, the test runner's criterion);
+ * the paper delegates the per-operator semantics to the PyTorch operator
+ * documentation, and the comments below restate the parts that matter.
+ *
+ * General conventions
+ *   - Every tensor argument is a host pointer to a tx_tensor descriptor whose
+ *     `data` member is a DEVICE pointer to element [0,...,0] (storage offset
+ *     applied).  Sizes are >= 0, strides are in ELEMENTS, 0 strides are
+ *     allowed on inputs (broadcast views), negative strides are not allowed.
+ *     ndim == 0 describes a one-element tensor.
+ *   - Ownership: the caller owns every buffer, workspace included.  The
+ *     library allocates no device memory and keeps no pointer after return.
+ *   - `stream` is a hipStream_t (pass NULL for the default stream).  All work
+ *     is enqueued on it and the call returns without synchronising; buffers
+ *     and workspace must stay alive until the stream has passed the call.
+ *   - Errors: every semantic check happens on the host before any launch.  A
+ *     negative tx_status is returned, nothing is written, and
+ *     tx_last_error() holds a thread-local detail string.
+ *   - numel(out) == 0 returns TX_OK without launching.
+ *   - `out` must have exactly the inferred shape.  Its dtype must be the
+ *     inferred result dtype, except where a function says a wider float is
+ *     accepted.  `out` may have any non-overlapping strides.  It may alias an
+ *     input exactly (same pointer, sizes and strides: in-place); any other
+ *     overlap between `out` and an input, and any self-overlap inside `out`,
+ *     is TX_ERR_OVERLAP.
+ *   - Type promotion (binary ops, where): categories bool < integer <
+ *     floating.  Operands with ndim >= 1 are promoted among themselves and
+ *     0-dim operands among themselves (wider wins inside a category, fp16
+ *     with bf16 gives fp32, a higher category wins unchanged); the 0-dim group
+ *     decides only when its category is strictly higher.  Operands are
+ *     converted to the common dtype first, then the operator is applied;
+ *     fp16 / bf16 arithmetic is carried out in fp32 and rounded once
+ *     (nearest-even) on store.
+ */
+#ifndef TXOPS_H
+#define TXOPS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types; bool is one byte holding 0 or 1 */
+enum { TX_BOOL = 0, TX_I32 = 1, TX_I64 = 2, TX_F16 = 3, TX_BF16 = 4, TX_F32 = 5 };
+
+#define TX_MAX_DIMS 8
+
+typedef struct {
+  void* data;                   /* device pointer */
+  int32_t dtype;                /* TX_* element type */
+  int32_t ndim;                 /* 0..TX_MAX_DIMS */
+  int64_t sizes[TX_MAX_DIMS];
+  int64_t strides[TX_MAX_DIMS]; /* in elements */
+} tx_tensor;
+
+typedef int32_t tx_status;
+enum {
+  TX_OK = 0,
+  TX_ERR_NULL = -1,            /* null descriptor, or null data with numel > 0 */
+  TX_ERR_NDIM = -2,            /* ndim outside 0..TX_MAX_DIMS */
+  TX_ERR_DTYPE = -3,           /* dtype not valid for the op, or out dtype != inferred */
+  TX_ERR_SHAPE = -4,           /* not broadcastable, wrong out shape, index shape rules, negative size/stride */
+  TX_ERR_DIM = -5,             /* dim out of range or repeated; several dims for prod / argmax */
+  TX_ERR_OVERLAP = -6,         /* out overlaps itself or partially overlaps an input */
+  TX_ERR_EMPTY_REDUCTION = -7, /* amax / argmax over an empty reduced extent */
+  TX_ERR_SCALAR = -8,          /* non-integral alpha with an integer / bool result */
+  TX_ERR_WORKSPACE = -9,       /* workspace missing or smaller than tx_*_workspace_bytes() */
+  TX_ERR_INDEX = -10,          /* reserved: index validation (indices are not checked on the device) */
+  TX_ERR_LAUNCH = -11,         /* HIP reported an error at launch; see tx_last_error() */
+  TX_ERR_UNSUPPORTED = -12     /* valid request that this build has no kernel for */
+};
+
+/* operator codes */
+enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF };
+enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ };
+enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR };
+
+/* ------------------------------------------------------------------ elementwise
+ * (Table 1 "Elementwise"; the flat masked kernels of Appendix B are the paper's
+ * form of this class, the `outer` listing its broadcasting form.)
+ */
+
+/* out[i] = f(a[i]); out has a's shape.
+ *   NEG, ABS : result dtype = a's; bool is TX_ERR_DTYPE; integers wrap; floats
+ *              flip / clear the sign bit exactly.
+ *   EXP LOG SQRT SIGMOID TANH : float a keeps its dtype; bool / integer a is
+ *              converted to fp32 and the result is fp32.  fp32 results are
+ *              within 2 ulp of the correctly rounded value.
+ *   GELU_ERF : x * Phi(x); float dtypes only. */
+tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream);
+
+/* out = a + alpha * b with broadcasting and type promotion.  alpha is given
+ * both ways: alpha_is_int selects alpha_i, else alpha_f.  bool: a OR (alpha!=0
+ * AND b).  Integer result: wrapping arithmetic, alpha must be integral
+ * (TX_ERR_SCALAR otherwise).  Float result: alpha == 1 is one IEEE add;
+ * alpha != 1 is one fused multiply-add fma(alpha, b, a) in fp32. */
+tx_status tx_add(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f, int64_t alpha_i,
+                 int alpha_is_int, void* stream);
+
+/* out = a (op) b with broadcasting and type promotion, op in MUL DIV MAXIMUM EQ
+ * (TX_ADD is accepted too, with alpha = 1).
+ *   MUL: bool AND, integers wrap.  DIV: true division, bool / integer pairs are
+ *   computed and returned in fp32.  MAXIMUM: NaN if either operand is NaN.
+ *   EQ: compares in the common dtype, result dtype bool. */
+tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream);
+
+/* out = cond ? x : y.  cond must be bool; result dtype = promotion of x and y;
+ * the three operands broadcast together.  With no conversion the selected
+ * element's bits are copied unchanged (NaN payloads survive). */
+tx_status tx_where(const tx_tensor* out, const tx_tensor* cond, const tx_tensor* x, const tx_tensor* y, void* stream);
+
+/* out = mask ? value : self.  mask is bool and broadcasts with self; out has
+ * the broadcast shape and self's dtype.  value is cast to self's dtype
+ * (floating value into an integer dtype truncates toward zero). */
+tx_status tx_masked_fill(const tx_tensor* out, const tx_tensor* self, const tx_tensor* mask, double value_f,
+                         int64_t value_i, int value_is_int, void* stream);
+
+/* ------------------------------------------------------------------ reductions
+ * (Table 1 "Reduction"; the row mean / variance kernels of the layer_norm
+ * listing in Appendix B are the paper's form of the inner-dim case.)
+ *
+ * Reduce x over dims[0..ndims) (negative dims wrap; ndims == 0 or dims == NULL:
+ * all dims).  keepdim keeps reduced dims with size 1.
+ *   SUM   bool / integer x -> int64 result (exact, wrapping); float x keeps its
+ *         dtype, accumulated in fp32.
+ *   MEAN  float only; sum / count; NaN for an empty extent.
+ *   PROD  like SUM; one dim or all dims only; empty product = 1.
+ *   AMAX  keeps dtype; NaN if any NaN; several dims allowed.
+ *   ARGMAX int64 index along the one dim, or flat row-major index over x's
+ *         logical shape with no dim; ties -> lowest index; NaN outranks
+ *         everything, first NaN wins; bool is TX_ERR_DTYPE.
+ *   VAR   float only; sum of squared deviations / max(0, n - correction).
+ * For SUM / MEAN / PROD / VAR on fp16 / bf16 input, out may be fp32.
+ * ws / ws_bytes: device scratch of at least tx_reduce_workspace_bytes() for the
+ * same arguments (0 when the reduction is not split across workgroups; the
+ * data pointers of out / x are not dereferenced by the query). */
+tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
+                    double correction, void* ws, size_t ws_bytes, void* stream);
+size_t tx_reduce_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
+                                 int keepdim);
+
+/* softmax (is_log == 0) or log_softmax (is_log != 0) of x along `dim`.
+ * Float dtypes only; out has x's shape and dtype, or fp32 for a half x.
+ * m = max; softmax = exp(x-m)/sum exp(x-m); log_softmax = (x-m) - log sum.
+ * A slice that is all -inf, or holds +inf or NaN, is all NaN. */
+tx_status tx_softmax(const tx_tensor* out, const tx_tensor* x, int64_t dim, int is_log, void* stream);
+
+/* Inclusive prefix sum of x along `dim`.  bool / int32 / int64 x -> int64 out
+ * (exact, wrapping); float x keeps its dtype (or fp32 out for a half x),
+ * accumulated in fp32.  ws / ws_bytes: device scratch of at least
+ * tx_cumsum_workspace_bytes() (tile status words for the single-pass scan). */
+tx_status tx_cumsum(const tx_tensor* out, const tx_tensor* x, int64_t dim, void* ws, size_t ws_bytes, void* stream);
+size_t tx_cumsum_workspace_bytes(const tx_tensor* x, int64_t dim);
+
+/* ------------------------------------------------------------------ indexing
+ * (Table 1 "Indexing & Selection".)  Index tensors are int64 or int32 and are
+ * NOT range-checked on the device: an index outside [0, extent) is undefined
+ * behaviour.  There is no negative-index wrap-around.
+ */
+
+/* out[i...] = src[i... with coordinate `dim` replaced by index[i...]].
+ * index.ndim == src.ndim; index.size(d) <= src.size(d) for d != dim; out has
+ * index's shape and src's dtype. */
+tx_status tx_gather(const tx_tensor* out, const tx_tensor* src, int64_t dim, const tx_tensor* index, void* stream);
+
+/* out = src with extent `dim` replaced by len(index); slice j of out is slice
+ * index[j] of src.  index is 1-D (0-dim counts as length 1). */
+tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t dim, const tx_tensor* index,
+                          void* stream);
+
+/* In place: for every position p of index, self[p with coordinate dim =
+ * index[p]] += src[p].  self, index, src have the same ndim; index.size(d) <=
+ * src.size(d) for all d and <= self.size(d) for d != dim; self.dtype ==
+ * src.dtype.  index may be a stride-0 expanded view.  Integer dtypes use
+ * device atomics (exact, order-free); bool ORs.  Float dtypes: with
+ * deterministic != 0 the contributions are sorted by destination and summed in
+ * a fixed order (bitwise reproducible run to run); with deterministic == 0
+ * float atomics are used.  ws / ws_bytes: device scratch of at least
+ * tx_scatter_add_workspace_bytes() (needed by the deterministic path only). */
+tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
+                          int deterministic, void* ws, size_t ws_bytes, void* stream);
+size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index,
+                                      const tx_tensor* src, int deterministic);
+
+/* ------------------------------------------------------------------ host-only helpers */
+
+/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_EQ). */
+tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_t* dtype, int32_t* ndim,
+                          int64_t* sizes);
+/* Result dtype of where(cond, x, y). */
+tx_status tx_infer_where(const tx_tensor* x, const tx_tensor* y, int32_t* dtype);
+/* Result dtype of a unary op for an input dtype (negative = error). */
+int32_t tx_infer_unary_dtype(int op, int32_t in_dtype);
+/* Result dtype and shape of a reduction. */
+tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim, int32_t* dtype,
+                          int32_t* ndim, int64_t* sizes);
+
+/* Name of the kernel path the last call on this thread dispatched to
+ * ("" if it launched nothing).  For tests and profiling. */
+const char* tx_last_path(void);
+/* Force a kernel path by name for the elementwise iterator ("" or NULL = automatic):
+ * "vec", "tile", "generic".  Requests that a path cannot serve fall back to the
+ * automatic choice.  Process-wide; meant for A/B profiling. */
+void tx_force_path(const char* name);
+
+const char* tx_strerror(tx_status status);
+const char* tx_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TXOPS_H */

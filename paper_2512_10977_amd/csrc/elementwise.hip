@@ -1,0 +1,893 @@
+// Elementwise operators: the operand iterator's three kernel paths and the
+// functors for unary / binary / where / masked_fill.
+//
+//   vec     : output inner dim contiguous, every input inner stride 0 or 1.  A
+//             workgroup owns one tile of one inner row; lanes move 16-byte
+//             vectors; outer offsets are computed once per workgroup in SALU.
+//   tile    : 2-D problems where some input runs contiguously along the
+//             output's OUTER dim (a transposed view).  64x64 tiles are staged
+//             through LDS so both the global reads and writes are coalesced.
+//   generic : one element per lane-slot, offsets from a full index
+//             decomposition with magic-number division.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <type_traits>
+
+#include "common.h"
+#include "iter.h"
+#include "math_fp.h"
+
+namespace tx {
+namespace {
+
+constexpr int kBlock = 256;
+
+// Marker for an operand whose storage dtype is only known at run time and that
+// the kernel converts to the compute type CT on load (or from CT on store).
+template <class CT> struct Dyn {};
+
+template <class T> struct Elem {
+  using value_t = T;
+  static constexpr bool dynamic = false;
+  static constexpr int static_size = sizeof(T);
+  __device__ __forceinline__ static T load(const char* base, int64_t idx, int) { return ((const T*)base)[idx]; }
+  template <int E> __device__ __forceinline__ static void load_vec(const char* base, int64_t idx, int, T (&out)[E]) {
+    Vec<T, E> v = *(const Vec<T, E>*)(base + idx * (int64_t)sizeof(T));
+#pragma unroll
+    for (int e = 0; e < E; ++e) out[e] = v.v[e];
+  }
+  __device__ __forceinline__ static void store(char* base, int64_t idx, int, T v) { ((T*)base)[idx] = v; }
+  template <int E> __device__ __forceinline__ static void store_vec(char* base, int64_t idx, int, const T (&in)[E]) {
+    Vec<T, E> v;
+#pragma unroll
+    for (int e = 0; e < E; ++e) v.v[e] = in[e];
+    *(Vec<T, E>*)(base + idx * (int64_t)sizeof(T)) = v;
+  }
+};
+
+template <class S, class CT, int E>
+__device__ __forceinline__ void load_cvt_vec(const char* base, int64_t idx, CT (&out)[E]) {
+  Vec<S, E> v = *(const Vec<S, E>*)(base + idx * (int64_t)sizeof(S));
+#pragma unroll
+  for (int e = 0; e < E; ++e) out[e] = cvt<CT>(v.v[e]);
+}
+template <class S, class CT, int E>
+__device__ __forceinline__ void store_cvt_vec(char* base, int64_t idx, const CT (&in)[E]) {
+  Vec<S, E> v;
+#pragma unroll
+  for (int e = 0; e < E; ++e) v.v[e] = cvt<S>(in[e]);
+  *(Vec<S, E>*)(base + idx * (int64_t)sizeof(S)) = v;
+}
+
+template <> struct Elem<Dyn<float>> {
+  using value_t = float;
+  static constexpr bool dynamic = true;
+  static constexpr int static_size = 0;
+  __device__ __forceinline__ static float load(const char* b, int64_t i, int dt) {
+    switch (dt) {
+      case TX_F32: return ((const float*)b)[i];
+      case TX_BF16: return bf16_to_float(((const bf16*)b)[i]);
+      case TX_F16: return (float)((const f16*)b)[i];
+      case TX_I64: return (float)((const int64_t*)b)[i];
+      case TX_I32: return (float)((const int32_t*)b)[i];
+      default: return (float)((const uint8_t*)b)[i];
+    }
+  }
+  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, float (&o)[E]) {
+    switch (dt) {
+      case TX_F32: load_cvt_vec<float, float, E>(b, i, o); break;
+      case TX_BF16: load_cvt_vec<bf16, float, E>(b, i, o); break;
+      case TX_F16: load_cvt_vec<f16, float, E>(b, i, o); break;
+      case TX_I64: load_cvt_vec<int64_t, float, E>(b, i, o); break;
+      case TX_I32: load_cvt_vec<int32_t, float, E>(b, i, o); break;
+      default: load_cvt_vec<uint8_t, float, E>(b, i, o); break;
+    }
+  }
+  __device__ __forceinline__ static void store(char* b, int64_t i, int dt, float v) {
+    switch (dt) {
+      case TX_F32: ((float*)b)[i] = v; break;
+      case TX_BF16: ((bf16*)b)[i] = float_to_bf16(v); break;
+      default: ((f16*)b)[i] = (f16)v; break;
+    }
+  }
+  template <int E> __device__ __forceinline__ static void store_vec(char* b, int64_t i, int dt, const float (&in)[E]) {
+    switch (dt) {
+      case TX_F32: store_cvt_vec<float, float, E>(b, i, in); break;
+      case TX_BF16: store_cvt_vec<bf16, float, E>(b, i, in); break;
+      default: store_cvt_vec<f16, float, E>(b, i, in); break;
+    }
+  }
+};
+
+template <> struct Elem<Dyn<int64_t>> {
+  using value_t = int64_t;
+  static constexpr bool dynamic = true;
+  static constexpr int static_size = 0;
+  __device__ __forceinline__ static int64_t load(const char* b, int64_t i, int dt) {
+    switch (dt) {
+      case TX_I64: return ((const int64_t*)b)[i];
+      case TX_I32: return ((const int32_t*)b)[i];
+      default: return ((const uint8_t*)b)[i];
+    }
+  }
+  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, int64_t (&o)[E]) {
+    switch (dt) {
+      case TX_I64: load_cvt_vec<int64_t, int64_t, E>(b, i, o); break;
+      case TX_I32: load_cvt_vec<int32_t, int64_t, E>(b, i, o); break;
+      default: load_cvt_vec<uint8_t, int64_t, E>(b, i, o); break;
+    }
+  }
+  __device__ __forceinline__ static void store(char* b, int64_t i, int dt, int64_t v) {
+    if (dt == TX_I64) ((int64_t*)b)[i] = v;
+    else ((int32_t*)b)[i] = (int32_t)v;
+  }
+  template <int E> __device__ __forceinline__ static void store_vec(char* b, int64_t i, int dt, const int64_t (&in)[E]) {
+    if (dt == TX_I64) store_cvt_vec<int64_t, int64_t, E>(b, i, in);
+    else store_cvt_vec<int32_t, int64_t, E>(b, i, in);
+  }
+};
+
+// ---------------------------------------------------------------------------
+// functor plumbing: every functor declares Out, In0, In1, In2 (unused inputs
+// are `void`) and NIN, and is called with the converted input values.
+// ---------------------------------------------------------------------------
+template <class T> struct ValueOf { using type = typename Elem<T>::value_t; };
+template <> struct ValueOf<void> { using type = uint8_t; };
+template <class T> constexpr int static_size_of() {
+  if constexpr (std::is_void<T>::value) return 0;
+  else return Elem<T>::static_size;
+}
+template <class T> constexpr bool is_dynamic() {
+  if constexpr (std::is_void<T>::value) return false;
+  else return Elem<T>::dynamic;
+}
+
+template <class F> struct Shape {
+  static constexpr bool dynamic = is_dynamic<typename F::Out>() || is_dynamic<typename F::In0>() ||
+                                  is_dynamic<typename F::In1>() || is_dynamic<typename F::In2>();
+  static constexpr int s0 = static_size_of<typename F::Out>(), s1 = static_size_of<typename F::In0>(),
+                       s2 = static_size_of<typename F::In1>(), s3 = static_size_of<typename F::In2>();
+  static constexpr int cmin(int a, int b) { return b == 0 ? a : (a < b ? a : b); }
+  static constexpr int cmax(int a, int b) { return a > b ? a : b; }
+  static constexpr int min_size = cmin(cmin(cmin(s0 ? s0 : 16, s1), s2), s3);
+  static constexpr int max_size = cmax(cmax(cmax(s0, s1), s2), s3);
+  // elements per lane per vector: the narrowest operand moves 16 bytes
+  static constexpr int E = dynamic ? 4 : (16 / min_size);
+  // vectors per lane: about 64 bytes of the widest operand in flight
+  static constexpr int per_vec = E * max_size;
+  static constexpr int U = dynamic ? 2 : (per_vec >= 64 ? 1 : (64 / per_vec > 4 ? 4 : 64 / per_vec));
+};
+
+template <class F, class A, class B, class C>
+__device__ __forceinline__ typename ValueOf<typename F::Out>::type apply(const F& f, A a, B b, C c) {
+  if constexpr (F::NIN == 1) return f(a);
+  else if constexpr (F::NIN == 2) return f(a, b);
+  else return f(a, b, c);
+}
+
+// ---------------------------------------------------------------------------
+// vec path
+// ---------------------------------------------------------------------------
+template <int NOPS> struct VecArgs {
+  char* data[NOPS];
+  int dtype[NOPS];
+  int inner_stride[NOPS];                    // 0 or 1 (operand 0 = out: always 1)
+  int nouter;
+  FastDiv tiles_per_row;
+  FastDiv osize[TX_MAX_DIMS - 1];            // outer sizes, outer -> inner
+  int64_t ostride[NOPS][TX_MAX_DIMS - 1];    // elements
+  int64_t n0;                                // inner extent
+};
+
+template <class In, int E, int NOPS>
+__device__ __forceinline__ void vec_fetch(const VecArgs<NOPS>& a, int o, int64_t base, int64_t i, int valid,
+                                          typename ValueOf<In>::type (&x)[E]) {
+  if constexpr (!std::is_void<In>::value) {
+    using EL = Elem<In>;
+    if (a.inner_stride[o] == 0) {
+      typename EL::value_t v = EL::load(a.data[o], base, a.dtype[o]);
+#pragma unroll
+      for (int e = 0; e < E; ++e) x[e] = v;
+    } else if (valid == E) {
+      EL::template load_vec<E>(a.data[o], base + i, a.dtype[o], x);
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (e < valid) x[e] = EL::load(a.data[o], base + i + e, a.dtype[o]);
+    }
+  }
+}
+
+template <class F, int E, int U>
+__global__ __launch_bounds__(kBlock) void ew_vec_kernel(const F f, const VecArgs<F::NIN + 1> a) {
+  constexpr int NOPS = F::NIN + 1;
+  uint32_t outer, tile;
+  a.tiles_per_row.divmod(blockIdx.x, outer, tile);
+  int64_t base[NOPS];
+#pragma unroll
+  for (int o = 0; o < NOPS; ++o) base[o] = 0;
+  for (int d = a.nouter - 1; d >= 0; --d) {
+    uint32_t q, r;
+    a.osize[d].divmod(outer, q, r);
+    outer = q;
+#pragma unroll
+    for (int o = 0; o < NOPS; ++o) base[o] += (int64_t)r * a.ostride[o][d];
+  }
+  const int64_t i0 = (int64_t)tile * (kBlock * E * U) + (int64_t)threadIdx.x * E;
+  typename ValueOf<typename F::In0>::type x0[U][E];
+  typename ValueOf<typename F::In1>::type x1[U][E];
+  typename ValueOf<typename F::In2>::type x2[U][E];
+  int valid[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int64_t i = i0 + (int64_t)u * kBlock * E;
+    const int64_t left = a.n0 - i;
+    valid[u] = left >= E ? E : (left > 0 ? (int)left : 0);
+    if (valid[u] > 0) {
+      vec_fetch<typename F::In0, E>(a, 1, base[1], i, valid[u], x0[u]);
+      if constexpr (F::NIN >= 2) vec_fetch<typename F::In1, E>(a, 2, base[2], i, valid[u], x1[u]);
+      if constexpr (F::NIN >= 3) vec_fetch<typename F::In2, E>(a, 3, base[3], i, valid[u], x2[u]);
+    }
+  }
+  using EO = Elem<typename F::Out>;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (valid[u] == 0) continue;
+    const int64_t i = i0 + (int64_t)u * kBlock * E;
+    typename EO::value_t y[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) y[e] = apply(f, x0[u][e], x1[u][e], x2[u][e]);
+    if (valid[u] == E) {
+      EO::template store_vec<E>(a.data[0], base[0] + i, a.dtype[0], y);
+    } else {
+#pragma unroll
+      for (int e = 0; e < E; ++e)
+        if (e < valid[u]) EO::store(a.data[0], base[0] + i + e, a.dtype[0], y[e]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// generic path
+// ---------------------------------------------------------------------------
+template <int NOPS> struct GenArgs {
+  char* data[NOPS];
+  int dtype[NOPS];
+  int ndim;
+  FastDiv fsize[TX_MAX_DIMS];
+  int64_t size[TX_MAX_DIMS];
+  int64_t stride[NOPS][TX_MAX_DIMS];
+  int64_t numel;
+};
+
+template <class F, class IndexT, int U>
+__global__ __launch_bounds__(kBlock) void ew_generic_kernel(const F f, const GenArgs<F::NIN + 1> a) {
+  constexpr int NOPS = F::NIN + 1;
+  const IndexT first = (IndexT)blockIdx.x * (kBlock * U) + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const IndexT lin = first + (IndexT)u * kBlock;
+    if ((int64_t)lin >= a.numel) break;
+    int64_t off[NOPS];
+#pragma unroll
+    for (int o = 0; o < NOPS; ++o) off[o] = 0;
+    IndexT rem = lin;
+    for (int d = a.ndim - 1; d >= 0; --d) {
+      IndexT q, r;
+      if constexpr (sizeof(IndexT) == 4) {
+        a.fsize[d].divmod(rem, q, r);
+      } else {
+        q = rem / (IndexT)a.size[d];
+        r = rem - q * (IndexT)a.size[d];
+      }
+      rem = q;
+#pragma unroll
+      for (int o = 0; o < NOPS; ++o) off[o] += (int64_t)r * a.stride[o][d];
+    }
+    typename ValueOf<typename F::In0>::type v0 = Elem<typename F::In0>::load(a.data[1], off[1], a.dtype[1]);
+    typename ValueOf<typename F::In1>::type v1{};
+    typename ValueOf<typename F::In2>::type v2{};
+    if constexpr (F::NIN >= 2) v1 = Elem<typename F::In1>::load(a.data[2], off[2], a.dtype[2]);
+    if constexpr (F::NIN >= 3) v2 = Elem<typename F::In2>::load(a.data[3], off[3], a.dtype[3]);
+    Elem<typename F::Out>::store(a.data[0], off[0], a.dtype[0], apply(f, v0, v1, v2));
+  }
+}
+
+// ---------------------------------------------------------------------------
+// tile path: out[r][c] over a 2-D (optionally batched) problem where the
+// output is contiguous along c and at least one input is contiguous along r.
+// A 64x64 tile of each such input is read with lanes running along r, parked
+// in LDS, and read back with lanes running along c.
+// ---------------------------------------------------------------------------
+// tile edge: 64 for value types up to 4 bytes, 32 for 8-byte values (keeps three staged operands inside 64 KB of LDS)
+template <class F> constexpr int tile_edge() {
+  return (sizeof(typename ValueOf<typename F::In0>::type) > 4 || sizeof(typename ValueOf<typename F::In1>::type) > 4 ||
+          sizeof(typename ValueOf<typename F::In2>::type) > 4) ? 32 : 64;
+}
+
+template <int NOPS> struct TileArgs {
+  char* data[NOPS];
+  int dtype[NOPS];
+  int64_t stride_r[NOPS], stride_c[NOPS], stride_b[NOPS];   // elements
+  int transposed[NOPS];                                       // 1: stage through LDS
+  int64_t rows, cols;
+  FastDiv tiles_c, tiles_r;
+};
+
+template <class In, class V, int T, int NOPS>
+__device__ __forceinline__ void tile_stage(const TileArgs<NOPS>& a, int o, int64_t boff, int64_t r0, int64_t c0,
+                                           V (*lds)[T + 1]) {
+  // lanes run along r (this operand's unit-stride dim): thread (tx, ty) reads row r0+tx, cols c0+ty+k*(256/T)
+  constexpr int P = kBlock / T;
+  const int tx = threadIdx.x % T, ty = threadIdx.x / T;
+  const int64_t r = r0 + tx;
+#pragma unroll 4
+  for (int k = 0; k < T / P; ++k) {
+    const int c = ty + P * k;
+    if (r < a.rows && c0 + c < a.cols)
+      lds[c][tx] = Elem<In>::load(a.data[o], boff + r * a.stride_r[o] + (c0 + c) * a.stride_c[o], a.dtype[o]);
+  }
+}
+
+template <class In, class V, int T, int NOPS>
+__device__ __forceinline__ V tile_fetch(const TileArgs<NOPS>& a, int o, int64_t boff, int64_t r, int64_t c, int lr,
+                                        int lc, V (*lds)[T + 1]) {
+  if (a.transposed[o]) return lds[lc][lr];
+  return Elem<In>::load(a.data[o], boff + r * a.stride_r[o] + c * a.stride_c[o], a.dtype[o]);
+}
+
+template <class F>
+__global__ __launch_bounds__(kBlock) void ew_tile_kernel(const F f, const TileArgs<F::NIN + 1> a) {
+  constexpr int NOPS = F::NIN + 1;
+  constexpr int kTile = tile_edge<F>();
+  constexpr int P = kBlock / kTile;
+  using V0 = typename ValueOf<typename F::In0>::type;
+  using V1 = typename ValueOf<typename F::In1>::type;
+  using V2 = typename ValueOf<typename F::In2>::type;
+  __shared__ V0 l0[kTile][kTile + 1];
+  __shared__ V1 l1[F::NIN >= 2 ? kTile : 1][kTile + 1];
+  __shared__ V2 l2[F::NIN >= 3 ? kTile : 1][kTile + 1];
+  uint32_t rest, tc, batch, tr;
+  a.tiles_c.divmod(blockIdx.x, rest, tc);
+  a.tiles_r.divmod(rest, batch, tr);
+  const int64_t r0 = (int64_t)tr * kTile, c0 = (int64_t)tc * kTile;
+  int64_t boff[NOPS];
+#pragma unroll
+  for (int o = 0; o < NOPS; ++o) boff[o] = (int64_t)batch * a.stride_b[o];
+  if (a.transposed[1]) tile_stage<typename F::In0, V0, kTile>(a, 1, boff[1], r0, c0, l0);
+  if constexpr (F::NIN >= 2)
+    if (a.transposed[2]) tile_stage<typename F::In1, V1, kTile>(a, 2, boff[2], r0, c0, l1);
+  if constexpr (F::NIN >= 3)
+    if (a.transposed[3]) tile_stage<typename F::In2, V2, kTile>(a, 3, boff[3], r0, c0, l2);
+  __syncthreads();
+  // lanes run along c: thread (tx, ty) writes col c0+tx, rows r0+ty+k*(256/T)
+  const int tx = threadIdx.x % kTile, ty = threadIdx.x / kTile;
+  const int64_t c = c0 + tx;
+#pragma unroll 4
+  for (int k = 0; k < kTile / P; ++k) {
+    const int lr = ty + P * k;
+    const int64_t r = r0 + lr;
+    if (r < a.rows && c < a.cols) {
+      V0 v0 = tile_fetch<typename F::In0, V0, kTile>(a, 1, boff[1], r, c, lr, tx, l0);
+      V1 v1{};
+      V2 v2{};
+      if constexpr (F::NIN >= 2) v1 = tile_fetch<typename F::In1, V1, kTile>(a, 2, boff[2], r, c, lr, tx, l1);
+      if constexpr (F::NIN >= 3) v2 = tile_fetch<typename F::In2, V2, kTile>(a, 3, boff[3], r, c, lr, tx, l2);
+      Elem<typename F::Out>::store(a.data[0], boff[0] + r * a.stride_r[0] + c * a.stride_c[0], a.dtype[0],
+                                   apply(f, v0, v1, v2));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// path selection + launch
+// ---------------------------------------------------------------------------
+inline bool aligned_to(const void* p, int bytes) { return ((uintptr_t)p % (uintptr_t)bytes) == 0; }
+
+template <class F> bool vec_path_ok(const Iter& it, int E) {
+  const int in = it.ndim - 1;
+  if (it.op[0].stride[in] != 1 && it.size[in] != 1) return false;
+  for (int o = 0; o < it.nops; ++o) {
+    const int64_t s = it.op[o].stride[in];
+    if (s != 0 && s != 1) return false;
+    if (s == 1) {
+      const int es = dtype_size(it.op[o].dtype);
+      const int al = std::min(16, E * es);
+      if (!aligned_to(it.op[o].data, al)) return false;
+      for (int d = 0; d < in; ++d)
+        if ((it.op[o].stride[d] * es) % al != 0) return false;
+    }
+  }
+  int64_t outer = 1;
+  for (int d = 0; d < in; ++d) outer *= it.size[d];
+  const int64_t tile = (int64_t)kBlock * E * Shape<F>::U;
+  const int64_t tiles = (it.size[in] + tile - 1) / tile;
+  if (outer >= (1ll << 31) || tiles >= (1ll << 31) || outer * tiles >= (1ll << 31)) return false;
+  return true;
+}
+
+// 2-D (+ batch) problem in which some input has unit stride along the output's outer dim
+bool tile_path_ok(const Iter& it, int kTile) {
+  if (it.ndim < 2 || it.ndim > 3) return false;
+  const int c = it.ndim - 1, r = it.ndim - 2;
+  if (it.op[0].stride[c] != 1) return false;
+  bool any = false;
+  for (int o = 1; o < it.nops; ++o)
+    if (it.op[o].stride[r] == 1 && it.op[o].stride[c] != 1 && it.op[o].stride[c] != 0) any = true;
+  if (!any) return false;
+  const int64_t tr = (it.size[r] + kTile - 1) / kTile, tc = (it.size[c] + kTile - 1) / kTile;
+  const int64_t nb = it.ndim == 3 ? it.size[0] : 1;
+  return tr * tc < (1ll << 31) && tr * tc * nb < (1ll << 31);
+}
+
+template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t stream) {
+  constexpr int NOPS = F::NIN + 1;
+  constexpr int E = Shape<F>::E, U = Shape<F>::U;
+  const char* forced = forced_path();
+  const int in = it.ndim - 1;
+  bool can_vec = vec_path_ok<F>(it, E);
+  constexpr int kTile = tile_edge<F>();
+  bool can_tile = tile_path_ok(it, kTile);
+  // automatic choice: vec unless rows are too short to fill a wave's worth of vectors
+  bool use_vec = can_vec && (it.ndim == 1 || it.size[in] >= 64 * E);
+  bool use_tile = !use_vec && can_tile;
+  if (!strcmp(forced, "vec") && can_vec) { use_vec = true; use_tile = false; }
+  if (!strcmp(forced, "tile") && can_tile) { use_vec = false; use_tile = true; }
+  if (!strcmp(forced, "generic")) { use_vec = false; use_tile = false; }
+
+  if (use_vec) {
+    VecArgs<NOPS> a;
+    for (int o = 0; o < NOPS; ++o) {
+      a.data[o] = it.op[o].data;
+      a.dtype[o] = it.op[o].dtype;
+      a.inner_stride[o] = (int)it.op[o].stride[in];
+      for (int d = 0; d < in; ++d) a.ostride[o][d] = it.op[o].stride[d];
+    }
+    a.inner_stride[0] = 1;
+    a.nouter = in;
+    int64_t outer = 1;
+    for (int d = 0; d < in; ++d) { a.osize[d] = FastDiv((uint32_t)it.size[d]); outer *= it.size[d]; }
+    a.n0 = it.size[in];
+    const int64_t tile = (int64_t)kBlock * E * U;
+    const int64_t tiles = (a.n0 + tile - 1) / tile;
+    a.tiles_per_row = FastDiv((uint32_t)tiles);
+    set_path("vec");
+    hipLaunchKernelGGL((ew_vec_kernel<F, E, U>), dim3((unsigned)(outer * tiles)), dim3(kBlock), 0, stream, f, a);
+    return check_launch("elementwise vec kernel");
+  }
+  if (use_tile) {
+    TileArgs<NOPS> a;
+    const int c = it.ndim - 1, r = it.ndim - 2;
+    for (int o = 0; o < NOPS; ++o) {
+      a.data[o] = it.op[o].data;
+      a.dtype[o] = it.op[o].dtype;
+      a.stride_r[o] = it.op[o].stride[r];
+      a.stride_c[o] = it.op[o].stride[c];
+      a.stride_b[o] = it.ndim == 3 ? it.op[o].stride[0] : 0;
+      a.transposed[o] = o > 0 && a.stride_r[o] == 1 && a.stride_c[o] != 1 && a.stride_c[o] != 0;
+    }
+    a.rows = it.size[r];
+    a.cols = it.size[c];
+    const int64_t tr = (a.rows + kTile - 1) / kTile, tc = (a.cols + kTile - 1) / kTile;
+    const int64_t nb = it.ndim == 3 ? it.size[0] : 1;
+    a.tiles_c = FastDiv((uint32_t)tc);
+    a.tiles_r = FastDiv((uint32_t)tr);
+    set_path("tile");
+    hipLaunchKernelGGL((ew_tile_kernel<F>), dim3((unsigned)(tr * tc * nb)), dim3(kBlock), 0, stream, f, a);
+    return check_launch("elementwise tile kernel");
+  }
+  GenArgs<NOPS> a;
+  for (int o = 0; o < NOPS; ++o) {
+    a.data[o] = it.op[o].data;
+    a.dtype[o] = it.op[o].dtype;
+    for (int d = 0; d < it.ndim; ++d) a.stride[o][d] = it.op[o].stride[d];
+  }
+  a.ndim = it.ndim;
+  a.numel = it.numel;
+  bool small = it.numel < (1ll << 31);
+  for (int d = 0; d < it.ndim; ++d) {
+    a.size[d] = it.size[d];
+    a.fsize[d] = FastDiv((uint32_t)std::min<int64_t>(it.size[d], 0x7fffffff));
+  }
+  constexpr int GU = 4;
+  const int64_t per_block = (int64_t)kBlock * GU;
+  const int64_t blocks = (it.numel + per_block - 1) / per_block;
+  if (blocks >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "tensor too large for the generic elementwise path");
+  set_path("generic");
+  if (small)
+    hipLaunchKernelGGL((ew_generic_kernel<F, uint32_t, GU>), dim3((unsigned)blocks), dim3(kBlock), 0, stream, f, a);
+  else
+    hipLaunchKernelGGL((ew_generic_kernel<F, uint64_t, GU>), dim3((unsigned)blocks), dim3(kBlock), 0, stream, f, a);
+  return check_launch("elementwise generic kernel");
+}
+
+// ---------------------------------------------------------------------------
+// functors
+// ---------------------------------------------------------------------------
+// round a float to the common half dtype and back (identity for fp32)
+__device__ __forceinline__ float quantize(float v, int common) {
+  if (common == TX_BF16) return bf16_to_float(float_to_bf16(v));
+  if (common == TX_F16) return (float)(f16)v;
+  return v;
+}
+
+struct OpExp { __device__ static float run(float x) { return expf(x); } };
+struct OpLog { __device__ static float run(float x) { return logf(x); } };
+struct OpSqrt { __device__ static float run(float x) { return sqrtf(x); } };
+struct OpSigmoid { __device__ static float run(float x) { return sigmoid_f32(x); } };
+struct OpTanh { __device__ static float run(float x) { return tanh_f32(x); } };
+struct OpGelu { __device__ static float run(float x) { return gelu_erf_f32(x); } };
+
+// float math op on a statically typed float tensor (computes in fp32)
+template <class Op, class T> struct MathStatic {
+  using Out = T; using In0 = T; using In1 = void; using In2 = void;
+  static constexpr int NIN = 1;
+  __device__ __forceinline__ T operator()(T x) const { return cvt<T>(Op::run(cvt<float>(x))); }
+};
+// float math op on a bool / integer tensor: convert to fp32, fp32 result
+template <class Op> struct MathDyn {
+  using Out = float; using In0 = Dyn<float>; using In1 = void; using In2 = void;
+  static constexpr int NIN = 1;
+  __device__ __forceinline__ float operator()(float x) const { return Op::run(x); }
+};
+// sign-bit operations on the stored encoding of a float type
+template <class B, bool NEG> struct SignBits {
+  using Out = B; using In0 = B; using In1 = void; using In2 = void;
+  static constexpr int NIN = 1;
+  __device__ __forceinline__ B operator()(B x) const {
+    constexpr B sb = (B)1 << (8 * sizeof(B) - 1);
+    return NEG ? (B)(x ^ sb) : (B)(x & (B)~sb);
+  }
+};
+template <class T, bool NEG> struct IntSign {
+  using Out = T; using In0 = T; using In1 = void; using In2 = void;
+  static constexpr int NIN = 1;
+  __device__ __forceinline__ T operator()(T x) const {
+    using UT = typename std::make_unsigned<T>::type;
+    UT u = (UT)x;
+    if (NEG || x < 0) u = (UT)0 - u;
+    return (T)u;
+  }
+};
+
+enum { kAdd = TX_ADD, kMul = TX_MUL, kDiv = TX_DIV, kMax = TX_MAXIMUM, kEq = TX_EQ };
+
+__device__ __forceinline__ float fmax_nan(float a, float b) {
+  return (a != a || b != b) ? __uint_as_float(0x7fc00000u) : (b > a ? b : a);
+}
+
+// same-dtype float binary op (fp32 arithmetic, one rounding to T)
+template <int OP, class T> struct BinFloat {
+  using Out = T; using In0 = T; using In1 = T; using In2 = void;
+  static constexpr int NIN = 2;
+  float alpha;
+  int alpha_one;
+  __device__ __forceinline__ T operator()(T xa, T xb) const {
+    float a = cvt<float>(xa), b = cvt<float>(xb), r;
+    if constexpr (OP == kAdd) r = alpha_one ? a + b : __fmaf_rn(alpha, b, a);
+    else if constexpr (OP == kMul) r = a * b;
+    else if constexpr (OP == kDiv) r = a / b;
+    else r = fmax_nan(a, b);
+    return cvt<T>(r);
+  }
+};
+template <class T> struct EqStatic {
+  using Out = uint8_t; using In0 = T; using In1 = T; using In2 = void;
+  static constexpr int NIN = 2;
+  __device__ __forceinline__ uint8_t operator()(T a, T b) const {
+    if constexpr (std::is_integral<T>::value) return a == b;
+    else return cvt<float>(a) == cvt<float>(b);
+  }
+};
+template <int OP, class T> struct BinInt {
+  using Out = T; using In0 = T; using In1 = T; using In2 = void;
+  static constexpr int NIN = 2;
+  int64_t alpha;
+  __device__ __forceinline__ T operator()(T a, T b) const {
+    using UT = typename std::make_unsigned<T>::type;
+    if constexpr (OP == kAdd) return (T)((UT)a + (UT)alpha * (UT)b);
+    else if constexpr (OP == kMul) return (T)((UT)a * (UT)b);
+    else return b > a ? b : a;
+  }
+};
+template <int OP> struct BinBool {
+  using Out = uint8_t; using In0 = uint8_t; using In1 = uint8_t; using In2 = void;
+  static constexpr int NIN = 2;
+  int alpha_nonzero;
+  __device__ __forceinline__ uint8_t operator()(uint8_t a, uint8_t b) const {
+    a = a != 0; b = b != 0;
+    if constexpr (OP == kAdd) return a | (b & (uint8_t)alpha_nonzero);
+    else if constexpr (OP == kMul) return a & b;
+    else if constexpr (OP == kMax) return a | b;
+    else return a == b;
+  }
+};
+// mixed-dtype float-result binary op: operands converted to the common dtype first
+template <int OP> struct BinDynFloat {
+  using Out = Dyn<float>; using In0 = Dyn<float>; using In1 = Dyn<float>; using In2 = void;
+  static constexpr int NIN = 2;
+  float alpha;
+  int alpha_one, common;
+  __device__ __forceinline__ float operator()(float a, float b) const {
+    a = quantize(a, common);
+    b = quantize(b, common);
+    if constexpr (OP == kAdd) return alpha_one ? a + b : __fmaf_rn(alpha, b, a);
+    else if constexpr (OP == kMul) return a * b;
+    else if constexpr (OP == kDiv) return a / b;
+    else return fmax_nan(a, b);
+  }
+};
+struct EqDynFloat {
+  using Out = uint8_t; using In0 = Dyn<float>; using In1 = Dyn<float>; using In2 = void;
+  static constexpr int NIN = 2;
+  int common;
+  __device__ __forceinline__ uint8_t operator()(float a, float b) const {
+    return quantize(a, common) == quantize(b, common);
+  }
+};
+template <int OP> struct BinDynInt {
+  using Out = Dyn<int64_t>; using In0 = Dyn<int64_t>; using In1 = Dyn<int64_t>; using In2 = void;
+  static constexpr int NIN = 2;
+  int64_t alpha;
+  int common;
+  __device__ __forceinline__ int64_t operator()(int64_t a, int64_t b) const {
+    if (common == TX_I32) { a = (int32_t)a; b = (int32_t)b; }
+    if constexpr (OP == kAdd) return (int64_t)((uint64_t)a + (uint64_t)alpha * (uint64_t)b);
+    else if constexpr (OP == kMul) return (int64_t)((uint64_t)a * (uint64_t)b);
+    else return b > a ? b : a;
+  }
+};
+struct EqDynInt {
+  using Out = uint8_t; using In0 = Dyn<int64_t>; using In1 = Dyn<int64_t>; using In2 = void;
+  static constexpr int NIN = 2;
+  int common;
+  __device__ __forceinline__ uint8_t operator()(int64_t a, int64_t b) const {
+    if (common == TX_I32) { a = (int32_t)a; b = (int32_t)b; }
+    return a == b;
+  }
+};
+
+// where / masked_fill on raw storage words (no conversion: bits are copied)
+template <class B> struct SelectBits {
+  using Out = B; using In0 = uint8_t; using In1 = B; using In2 = B;
+  static constexpr int NIN = 3;
+  __device__ __forceinline__ B operator()(uint8_t c, B x, B y) const { return c ? x : y; }
+};
+template <class CT> struct SelectDyn {
+  using Out = Dyn<CT>; using In0 = uint8_t; using In1 = Dyn<CT>; using In2 = Dyn<CT>;
+  static constexpr int NIN = 3;
+  __device__ __forceinline__ CT operator()(uint8_t c, CT x, CT y) const { return c ? x : y; }
+};
+template <class B> struct FillBits {
+  using Out = B; using In0 = B; using In1 = uint8_t; using In2 = void;
+  static constexpr int NIN = 2;
+  B value;
+  __device__ __forceinline__ B operator()(B s, uint8_t m) const { return m ? value : s; }
+};
+
+// ---------------------------------------------------------------------------
+// host-side scalar encoding (masked_fill value -> storage bits)
+// ---------------------------------------------------------------------------
+uint16_t host_float_to_bf16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+uint16_t host_float_to_f16(float f) {
+  _Float16 h = (_Float16)f;
+  uint16_t b;
+  memcpy(&b, &h, 2);
+  return b;
+}
+
+template <class Op> tx_status dispatch_math(const Iter& it, int in_dtype, hipStream_t s) {
+  switch (in_dtype) {
+    case TX_F32: return launch_ew(it, MathStatic<Op, float>{}, s);
+    case TX_BF16: return launch_ew(it, MathStatic<Op, bf16>{}, s);
+    case TX_F16: return launch_ew(it, MathStatic<Op, f16>{}, s);
+    default: return launch_ew(it, MathDyn<Op>{}, s);
+  }
+}
+
+template <int OP> tx_status dispatch_binary(const Iter& it, int da, int db, int common, double alpha_f, int64_t alpha_i,
+                                            int alpha_is_int, hipStream_t s) {
+  const double ad = alpha_is_int ? (double)alpha_i : alpha_f;
+  const bool one = alpha_is_int ? alpha_i == 1 : alpha_f == 1.0;
+  const bool same = da == common && db == common;
+  if (dtype_is_float(common)) {
+    if constexpr (OP == kEq) {
+      if (same) {
+        if (common == TX_F32) return launch_ew(it, EqStatic<float>{}, s);
+        if (common == TX_BF16) return launch_ew(it, EqStatic<bf16>{}, s);
+        return launch_ew(it, EqStatic<f16>{}, s);
+      }
+      return launch_ew(it, EqDynFloat{common}, s);
+    } else {
+      if (same) {
+        if (common == TX_F32) return launch_ew(it, BinFloat<OP, float>{(float)ad, one}, s);
+        if (common == TX_BF16) return launch_ew(it, BinFloat<OP, bf16>{(float)ad, one}, s);
+        return launch_ew(it, BinFloat<OP, f16>{(float)ad, one}, s);
+      }
+      return launch_ew(it, BinDynFloat<OP>{(float)ad, one, common}, s);
+    }
+  }
+  if constexpr (OP != kDiv) {
+    if (common == TX_BOOL) return launch_ew(it, BinBool<OP>{alpha_is_int ? alpha_i != 0 : alpha_f != 0.0}, s);
+    if constexpr (OP == kEq) {
+      if (same && common == TX_I32) return launch_ew(it, EqStatic<int32_t>{}, s);
+      if (same && common == TX_I64) return launch_ew(it, EqStatic<int64_t>{}, s);
+      return launch_ew(it, EqDynInt{common}, s);
+    } else {
+      if (same && common == TX_I32) return launch_ew(it, BinInt<OP, int32_t>{alpha_i}, s);
+      if (same && common == TX_I64) return launch_ew(it, BinInt<OP, int64_t>{alpha_i}, s);
+      return launch_ew(it, BinDynInt<OP>{alpha_i, common}, s);
+    }
+  }
+  return fail(TX_ERR_UNSUPPORTED, "no kernel for this binary op / dtype");
+}
+
+tx_status binary_impl(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f,
+                      int64_t alpha_i, int alpha_is_int, void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(a, "a")) || (rc = check_tensor(b, "b"))) return rc;
+  int32_t rd, nd;
+  int64_t shape[TX_MAX_DIMS];
+  if ((rc = tx_infer_binary(op, a, b, &rd, &nd, shape))) return rc;
+  if (out->dtype != rd)
+    return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
+  if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the broadcast shape");
+  const tx_tensor* ins[2] = {a, b};
+  int common = result_type(ins, 2);
+  if (op == TX_DIV && !dtype_is_float(common)) common = TX_F32;
+  if (op == TX_ADD && !dtype_is_float(common) && !alpha_is_int)
+    return fail(TX_ERR_SCALAR, "floating alpha with an integer / bool result");
+  if ((rc = check_out_overlap(out, ins, 2))) return rc;
+  set_path("");
+  if (numel(out) == 0) return TX_OK;
+  const tx_tensor* ops[3] = {out, a, b};
+  Iter it;
+  iter_build(&it, nd, shape, ops, 3);
+  hipStream_t s = as_stream(stream);
+  switch (op) {
+    case TX_ADD: return dispatch_binary<kAdd>(it, a->dtype, b->dtype, common, alpha_f, alpha_i, alpha_is_int, s);
+    case TX_MUL: return dispatch_binary<kMul>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
+    case TX_DIV: return dispatch_binary<kDiv>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
+    case TX_MAXIMUM: return dispatch_binary<kMax>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
+    case TX_EQ: return dispatch_binary<kEq>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
+  }
+  return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
+}
+
+}  // namespace
+}  // namespace tx
+
+using namespace tx;
+
+extern "C" {
+
+tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(a, "a"))) return rc;
+  int32_t rd = tx_infer_unary_dtype(op, a->dtype);
+  if (rd < 0) return rd;
+  if (out->dtype != rd) return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
+  if (!same_sizes(out, a->ndim, a->sizes)) return fail(TX_ERR_SHAPE, "out does not have a's shape");
+  const tx_tensor* ins[1] = {a};
+  if ((rc = check_out_overlap(out, ins, 1))) return rc;
+  set_path("");
+  if (numel(out) == 0) return TX_OK;
+  const tx_tensor* ops[2] = {out, a};
+  Iter it;
+  iter_build(&it, a->ndim, a->sizes, ops, 2);
+  hipStream_t s = as_stream(stream);
+  if (op == TX_NEG || op == TX_ABS) {
+    const bool neg = op == TX_NEG;
+    switch (a->dtype) {
+      case TX_I32: return neg ? launch_ew(it, IntSign<int32_t, true>{}, s) : launch_ew(it, IntSign<int32_t, false>{}, s);
+      case TX_I64: return neg ? launch_ew(it, IntSign<int64_t, true>{}, s) : launch_ew(it, IntSign<int64_t, false>{}, s);
+      case TX_F32: return neg ? launch_ew(it, SignBits<uint32_t, true>{}, s) : launch_ew(it, SignBits<uint32_t, false>{}, s);
+      default: return neg ? launch_ew(it, SignBits<uint16_t, true>{}, s) : launch_ew(it, SignBits<uint16_t, false>{}, s);
+    }
+  }
+  switch (op) {
+    case TX_EXP: return dispatch_math<OpExp>(it, a->dtype, s);
+    case TX_LOG: return dispatch_math<OpLog>(it, a->dtype, s);
+    case TX_SQRT: return dispatch_math<OpSqrt>(it, a->dtype, s);
+    case TX_SIGMOID: return dispatch_math<OpSigmoid>(it, a->dtype, s);
+    case TX_TANH: return dispatch_math<OpTanh>(it, a->dtype, s);
+    case TX_GELU_ERF: return dispatch_math<OpGelu>(it, a->dtype, s);
+  }
+  return fail(TX_ERR_DTYPE, "unknown unary op %d", op);
+}
+
+tx_status tx_add(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f, int64_t alpha_i,
+                 int alpha_is_int, void* stream) {
+  return binary_impl(TX_ADD, out, a, b, alpha_f, alpha_i, alpha_is_int, stream);
+}
+
+tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream) {
+  return binary_impl(op, out, a, b, 1.0, 1, 1, stream);
+}
+
+tx_status tx_where(const tx_tensor* out, const tx_tensor* cond, const tx_tensor* x, const tx_tensor* y, void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(cond, "cond")) || (rc = check_tensor(x, "x")) ||
+      (rc = check_tensor(y, "y")))
+    return rc;
+  if (cond->dtype != TX_BOOL) return fail(TX_ERR_DTYPE, "where: cond must be bool");
+  const tx_tensor* xy[2] = {x, y};
+  const int rd = result_type(xy, 2);
+  if (out->dtype != rd) return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
+  const tx_tensor* ins[3] = {cond, x, y};
+  int nd;
+  int64_t shape[TX_MAX_DIMS];
+  if ((rc = broadcast_shapes(ins, 3, &nd, shape))) return rc;
+  if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the broadcast shape");
+  if ((rc = check_out_overlap(out, ins, 3))) return rc;
+  set_path("");
+  if (numel(out) == 0) return TX_OK;
+  const tx_tensor* ops[4] = {out, cond, x, y};
+  Iter it;
+  iter_build(&it, nd, shape, ops, 4);
+  hipStream_t s = as_stream(stream);
+  if (x->dtype == rd && y->dtype == rd) {
+    switch (dtype_size(rd)) {
+      case 1: return launch_ew(it, SelectBits<uint8_t>{}, s);
+      case 2: return launch_ew(it, SelectBits<uint16_t>{}, s);
+      case 4: return launch_ew(it, SelectBits<uint32_t>{}, s);
+      default: return launch_ew(it, SelectBits<uint64_t>{}, s);
+    }
+  }
+  if (dtype_is_float(rd)) return launch_ew(it, SelectDyn<float>{}, s);
+  return launch_ew(it, SelectDyn<int64_t>{}, s);
+}
+
+tx_status tx_masked_fill(const tx_tensor* out, const tx_tensor* self, const tx_tensor* mask, double value_f,
+                         int64_t value_i, int value_is_int, void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(self, "self")) || (rc = check_tensor(mask, "mask")))
+    return rc;
+  if (mask->dtype != TX_BOOL) return fail(TX_ERR_DTYPE, "masked_fill: mask must be bool");
+  if (out->dtype != self->dtype) return fail(TX_ERR_DTYPE, "masked_fill: out must have self's dtype");
+  const tx_tensor* ins[2] = {self, mask};
+  int nd;
+  int64_t shape[TX_MAX_DIMS];
+  if ((rc = broadcast_shapes(ins, 2, &nd, shape))) return rc;
+  if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the broadcast shape");
+  if ((rc = check_out_overlap(out, ins, 2))) return rc;
+  set_path("");
+  if (numel(out) == 0) return TX_OK;
+  const tx_tensor* ops[3] = {out, self, mask};
+  Iter it;
+  iter_build(&it, nd, shape, ops, 3);
+  hipStream_t s = as_stream(stream);
+  const double vd = value_is_int ? (double)value_i : value_f;
+  switch (self->dtype) {
+    case TX_BOOL: return launch_ew(it, FillBits<uint8_t>{(uint8_t)(value_is_int ? value_i != 0 : value_f != 0.0)}, s);
+    case TX_I32: {
+      int32_t v = (int32_t)(uint32_t)(uint64_t)(value_is_int ? value_i : (int64_t)std::trunc(value_f));
+      uint32_t b;
+      memcpy(&b, &v, 4);
+      return launch_ew(it, FillBits<uint32_t>{b}, s);
+    }
+    case TX_I64: {
+      int64_t v = value_is_int ? value_i : (int64_t)std::trunc(value_f);
+      uint64_t b;
+      memcpy(&b, &v, 8);
+      return launch_ew(it, FillBits<uint64_t>{b}, s);
+    }
+    case TX_F32: {
+      float v = (float)vd;
+      uint32_t b;
+      memcpy(&b, &v, 4);
+      return launch_ew(it, FillBits<uint32_t>{b}, s);
+    }
+    case TX_BF16: return launch_ew(it, FillBits<uint16_t>{host_float_to_bf16((float)vd)}, s);
+    default: return launch_ew(it, FillBits<uint16_t>{host_float_to_f16((float)vd)}, s);
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// fp32 transcendental functors that must land within 2 ulp of the correctly
+// rounded result.  sigmoid, tanh and gelu are composed in binary64 (the chip's
+// fp64 vector rate is half its fp32 rate, and these kernels are HBM-bound), so
+// the only rounding that matters is the final conversion to fp32.
+#pragma once
+#include "common.h"
+
+namespace tx {
+
+// 1/x to ~1e-15 relative: hardware reciprocal estimate + one Newton step
+__device__ __forceinline__ double rcp_d(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  return __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+}
+
+// exp(y) = 2^n * (1 + p(r)), r = y - n ln2, |r| <= ln2/2; *p_out receives p(r)
+// (= expm1(r)), *n_out receives n.  Degree-10 Taylor polynomial: remainder
+// below 3e-13 relative.  y must be finite and within [-708, 708].
+__device__ __forceinline__ void exp_parts_d(double y, double* p_out, int* n_out) {
+  const double kLog2e = 1.4426950408889634074, kLn2Hi = 6.93147180369123816490e-01,
+               kLn2Lo = 1.90821492927058770002e-10;
+  double nf = __builtin_rint(y * kLog2e);
+  double r = __builtin_fma(-nf, kLn2Hi, y);
+  r = __builtin_fma(-nf, kLn2Lo, r);
+  double p = 1.0 / 3628800.0;
+  p = __builtin_fma(p, r, 1.0 / 362880.0);
+  p = __builtin_fma(p, r, 1.0 / 40320.0);
+  p = __builtin_fma(p, r, 1.0 / 5040.0);
+  p = __builtin_fma(p, r, 1.0 / 720.0);
+  p = __builtin_fma(p, r, 1.0 / 120.0);
+  p = __builtin_fma(p, r, 1.0 / 24.0);
+  p = __builtin_fma(p, r, 1.0 / 6.0);
+  p = __builtin_fma(p, r, 0.5);
+  p = __builtin_fma(p, r, 1.0);
+  *p_out = p * r;
+  *n_out = (int)nf;
+}
+__device__ __forceinline__ double pow2_d(int n) {   // 2^n for n in the normal range
+  return __longlong_as_double((long long)(n + 1023) << 52);
+}
+__device__ __forceinline__ double exp_d(double y) {  // y clamped by the caller
+  double p;
+  int n;
+  exp_parts_d(y, &p, &n);
+  return __builtin_fma(p, pow2_d(n), pow2_d(n));
+}
+
+__device__ __forceinline__ float sigmoid_f32(float xf) {
+  if (xf != xf) return xf;
+  double x = (double)xf;
+  x = x > 708.0 ? 708.0 : (x < -708.0 ? -708.0 : x);
+  return (float)rcp_d(1.0 + exp_d(-x));
+}
+
+__device__ __forceinline__ float tanh_f32(float xf) {
+  if (xf != xf) return xf;
+  double y = 2.0 * (double)xf;
+  y = y > 60.0 ? 60.0 : (y < -60.0 ? -60.0 : y);      // tanh saturates to +-1 in fp32 well before
+  double p;
+  int n;
+  exp_parts_d(y, &p, &n);
+  // em = expm1(y): exact polynomial form when n == 0, else 2^n (1+p) - 1 (no cancellation there)
+  double s = pow2_d(n);
+  double em = n == 0 ? p : __builtin_fma(p, s, s - 1.0);
+  double t = em * rcp_d(em + 2.0);
+  float r = (float)t;
+  return xf == 0.0f ? xf : r;                          // keeps -0
+}
+
+// gelu(x) = x * Phi(x), Phi(x) = erfc(-x / sqrt 2) / 2.  erfc(z) for z >= 0 is
+// exp(-z^2) * P(t) / (z + 1.5) with t = (z - 1.5) / (z + 1.5); the coefficients
+// come from fit_erfcx.py (max relative error 2.1e-11).
+__device__ __forceinline__ float gelu_erf_f32(float xf) {
+  if (xf != xf) return xf;
+  double x = (double)xf;
+  double z = __builtin_fabs(x) * 0.70710678118654752440;
+  double zc = z > 26.0 ? 26.0 : z;                     // erfc(26) ~ 1e-296; beyond, Phi is 0 or 1 in fp32 anyway
+  double r = rcp_d(zc + 1.5);
+  double t = (zc - 1.5) * r;
+  double p = -4.48026131500465495e-06;
+  p = __builtin_fma(p, t, -7.46861071228703220e-06);
+  p = __builtin_fma(p, t, 1.83404688284764924e-05);
+  p = __builtin_fma(p, t, 5.22830653440947734e-05);
+  p = __builtin_fma(p, t, 9.80220151046439906e-06);
+  p = __builtin_fma(p, t, -1.35548154522782059e-04);
+  p = __builtin_fma(p, t, -2.62789064962181502e-04);
+  p = __builtin_fma(p, t, -4.25510922534018304e-05);
+  p = __builtin_fma(p, t, 8.86380580260421398e-04);
+  p = __builtin_fma(p, t, 1.77098141754734092e-03);
+  p = __builtin_fma(p, t, -8.10762765167988568e-04);
+  p = __builtin_fma(p, t, -9.46125727689550895e-03);
+  p = __builtin_fma(p, t, -8.11975334549758232e-03);
+  p = __builtin_fma(p, t, 4.77683625279125348e-02);
+  p = __builtin_fma(p, t, 7.56218045754478568e-02);
+  p = __builtin_fma(p, t, -5.07850010103267802e-01);
+  p = __builtin_fma(p, t, 9.64756249373572294e-01);
+  double half_erfc = z > 26.0 ? 0.0 : 0.5 * exp_d(-zc * zc) * p * r;    // Phi(-|x|)
+  double phi = x < 0.0 ? half_erfc : 1.0 - half_erfc;
+  // x = +-inf: +inf * 1 = +inf, -inf * 0 = NaN, as IEEE evaluation of x * Phi(x) gives
+  return (float)(x * phi);
+}
+
+}  // namespace tx

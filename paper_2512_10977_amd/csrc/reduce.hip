@@ -1,0 +1,264 @@
+// tx_reduce: validation, planning and dispatch; instantiates the sum / mean /
+// var policies (reduce_b.hip holds prod / amax / argmax).
+#include "reduce_impl.h"
+
+namespace tx {
+namespace red {
+
+tx_status normalise_dims(int nd, const int64_t* dims, int ndims, bool* reduced) {
+  for (int d = 0; d < TX_MAX_DIMS; ++d) reduced[d] = false;
+  if (ndims == 0 || dims == nullptr) {
+    for (int d = 0; d < nd; ++d) reduced[d] = true;
+    return TX_OK;
+  }
+  bool seen[TX_MAX_DIMS] = {false};
+  for (int i = 0; i < ndims; ++i) {
+    int d;
+    tx_status rc = wrap_dim(dims[i], nd, &d);
+    if (rc) return rc;
+    if (seen[d]) return fail(TX_ERR_DIM, "dim %d appears twice", d);
+    seen[d] = true;
+    if (nd > 0) reduced[d] = true;
+  }
+  return TX_OK;
+}
+
+void plan_dims(Plan* p, const tx_tensor* x, const tx_tensor* out, const bool* reduced, int keepdim) {
+  p->nk = p->nr = 0;
+  p->nout = p->nred = 1;
+  int nred_dims = 0;
+  int od = 0;   // running output dim
+  for (int d = 0; d < x->ndim; ++d) {
+    const int64_t sz = x->sizes[d], xs = x->strides[d];
+    if (reduced[d]) {
+      ++nred_dims;
+      p->nred *= sz;
+      if (keepdim) ++od;
+      if (sz == 1) continue;
+      if (p->nr > 0 && p->rxs[p->nr - 1] == xs * sz) {          // merge into the previous (outer) reduced dim
+        p->rsize[p->nr - 1] *= sz;
+        p->rxs[p->nr - 1] = xs;
+      } else {
+        p->rsize[p->nr] = sz;
+        p->rxs[p->nr] = xs;
+        ++p->nr;
+      }
+    } else {
+      const int64_t os = out->strides[od];
+      ++od;
+      p->nout *= sz;
+      if (sz == 1) continue;
+      if (p->nk > 0 && p->kxs[p->nk - 1] == xs * sz && p->kos[p->nk - 1] == os * sz) {
+        p->ksize[p->nk - 1] *= sz;
+        p->kxs[p->nk - 1] = xs;
+        p->kos[p->nk - 1] = os;
+      } else {
+        p->ksize[p->nk] = sz;
+        p->kxs[p->nk] = xs;
+        p->kos[p->nk] = os;
+        ++p->nk;
+      }
+    }
+  }
+  p->single_dim = nred_dims == 1;
+  if (p->nr == 0) { p->nr = 1; p->rsize[0] = 1; p->rxs[0] = 0; }
+}
+
+static bool multiple_of(int64_t v, int64_t m) { return v % m == 0; }
+
+void plan_launch(Plan* p, const tx_tensor* x, int esize, bool) {
+  const int V = 16 / esize;
+  const bool red_contig = p->rxs[p->nr - 1] == 1 && p->rsize[p->nr - 1] > 1;
+  const bool kept_contig = p->nk > 0 && p->kxs[p->nk - 1] == 1 && p->kos[p->nk - 1] == 1;
+  p->kind = (kept_contig && !red_contig && p->ksize[p->nk - 1] >= 16) ? 1 : 0;
+  const bool base_al = ((uintptr_t)x->data % 16) == 0;
+  p->vec = 1;
+  p->split = 1;
+  p->chunk = p->nred;
+  if (p->kind == 0) {
+    bool ok = red_contig && base_al && multiple_of(p->rsize[p->nr - 1], V);
+    for (int d = 0; ok && d < p->nr - 1; ++d) ok = multiple_of(p->rxs[d] * esize, 16);
+    for (int d = 0; ok && d < p->nk; ++d) ok = multiple_of(p->kxs[d] * esize, 16);
+    if (ok) p->vec = V;
+    p->group = (p->nred * esize >= 16384) ? kBlock : kWave;
+    const int gpb = kBlock / p->group;
+    p->blocks_x = (p->nout + gpb - 1) / gpb;
+    const int64_t step = (int64_t)p->group * p->vec;
+    if (p->blocks_x < 512 && p->nred >= step * 16) {
+      int64_t s = std::min<int64_t>(kMaxSplit, (2048 + p->blocks_x - 1) / p->blocks_x);
+      s = std::min<int64_t>(s, p->nred / (step * 8));
+      if (s > 1) {
+        int64_t chunk = (p->nred + s - 1) / s;
+        chunk = (chunk + step - 1) / step * step;
+        p->chunk = chunk;
+        p->split = (int)((p->nred + chunk - 1) / chunk);
+      }
+    }
+  } else {
+    bool ok = base_al && multiple_of(p->ksize[p->nk - 1], V);
+    for (int d = 0; ok && d < p->nr; ++d) ok = multiple_of(p->rxs[d] * esize, 16);
+    for (int d = 0; ok && d < p->nk - 1; ++d) ok = multiple_of(p->kxs[d] * esize, 16);
+    if (ok) p->vec = V;
+    p->group = 1;
+    const int64_t threads = (p->nout + p->vec - 1) / p->vec;
+    p->blocks_x = (threads + kBlock - 1) / kBlock;
+    if (p->blocks_x < 512 && p->nred >= 64) {
+      int64_t s = std::min<int64_t>(kMaxSplit, (1024 + p->blocks_x - 1) / p->blocks_x);
+      s = std::min<int64_t>(s, p->nred / 16);
+      if (s > 1) {
+        p->chunk = (p->nred + s - 1) / s;
+        p->split = (int)((p->nred + p->chunk - 1) / p->chunk);
+      }
+    }
+  }
+}
+
+size_t plan_ws_bytes(const Plan& p, size_t acc) { return p.split > 1 ? (size_t)p.nout * p.split * acc : 0; }
+
+size_t acc_size(int op, int dtype) {
+  const bool flt = dtype_is_float(dtype);
+  switch (op) {
+    case TX_SUM: case TX_MEAN: return flt ? 4 : 8;
+    case TX_PROD: return 8;
+    case TX_AMAX: return flt ? 4 : 8;
+    case TX_ARGMAX: return 16;
+    case TX_VAR: return 16;
+  }
+  return 16;
+}
+
+#define TX_DISPATCH_DTYPE(POLICY, ...)                                                               \
+  switch (x->dtype) {                                                                                \
+    case TX_F32: return launch<POLICY<float __VA_ARGS__>>(p, x, out, c, ws, wsb, s);                  \
+    case TX_BF16: return launch<POLICY<bf16 __VA_ARGS__>>(p, x, out, c, ws, wsb, s);                  \
+    case TX_F16: return launch<POLICY<f16 __VA_ARGS__>>(p, x, out, c, ws, wsb, s);                    \
+    default: break;                                                                                  \
+  }
+
+tx_status launch_sum(bool mean, const Plan& p, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb,
+                     hipStream_t s) {
+  if (mean) {
+#define COMMA_TRUE , true
+    TX_DISPATCH_DTYPE(SumPolicy, COMMA_TRUE)
+    return fail(TX_ERR_DTYPE, "mean takes floating dtypes only");
+  }
+#define COMMA_FALSE , false
+  TX_DISPATCH_DTYPE(SumPolicy, COMMA_FALSE)
+  switch (x->dtype) {
+    case TX_I64: return launch<SumPolicy<int64_t, false>>(p, x, out, c, ws, wsb, s);
+    case TX_I32: return launch<SumPolicy<int32_t, false>>(p, x, out, c, ws, wsb, s);
+    default: return launch<SumPolicy<uint8_t, false>>(p, x, out, c, ws, wsb, s);
+  }
+}
+
+tx_status launch_var(const Plan& p, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb,
+                     hipStream_t s) {
+  TX_DISPATCH_DTYPE(VarPolicy)
+  return fail(TX_ERR_DTYPE, "var takes floating dtypes only");
+}
+
+tx_status build_plan(int op, const tx_tensor* x, const tx_tensor* out, const int64_t* dims, int32_t ndims, int keepdim,
+                     Plan* p) {
+  bool reduced[TX_MAX_DIMS];
+  tx_status rc = normalise_dims(x->ndim, dims, ndims, reduced);
+  if (rc) return rc;
+  plan_dims(p, x, out, reduced, keepdim);
+  if ((p->nk > 1 && p->nout >= (1ll << 31)) || (p->nr > 1 && p->nred >= (1ll << 31)))
+    return fail(TX_ERR_UNSUPPORTED, "reduction extents beyond 2^31 with non-mergeable dims");
+  plan_launch(p, x, dtype_size(x->dtype), op == TX_VAR);
+  if (p->blocks_x >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "too many outputs for one launch");
+  return TX_OK;
+}
+
+}  // namespace red
+}  // namespace tx
+
+using namespace tx;
+using namespace tx::red;
+
+extern "C" {
+
+tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim, int32_t* dtype,
+                          int32_t* ndim, int64_t* sizes) {
+  if (!x) return fail(TX_ERR_NULL, "infer_reduce: null descriptor");
+  if (x->ndim < 0 || x->ndim > TX_MAX_DIMS) return fail(TX_ERR_NDIM, "infer_reduce: bad ndim");
+  if (!dtype_valid(x->dtype)) return fail(TX_ERR_DTYPE, "infer_reduce: bad dtype code");
+  const bool flt = dtype_is_float(x->dtype);
+  int rd;
+  switch (op) {
+    case TX_SUM: case TX_PROD: rd = flt ? x->dtype : TX_I64; break;
+    case TX_MEAN: case TX_VAR:
+      if (!flt) return fail(TX_ERR_DTYPE, "mean / var take floating dtypes only");
+      rd = x->dtype;
+      break;
+    case TX_AMAX: rd = x->dtype; break;
+    case TX_ARGMAX:
+      if (x->dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "argmax does not take bool");
+      rd = TX_I64;
+      break;
+    default: return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
+  }
+  if ((op == TX_PROD || op == TX_ARGMAX) && ndims > 1 && dims)
+    return fail(TX_ERR_DIM, "prod / argmax reduce one dim or all dims");
+  bool reduced[TX_MAX_DIMS];
+  tx_status rc = normalise_dims(x->ndim, dims, ndims, reduced);
+  if (rc) return rc;
+  int nd = 0;
+  for (int d = 0; d < x->ndim; ++d) {
+    if (reduced[d]) { if (keepdim) { if (sizes) sizes[nd] = 1; ++nd; } }
+    else { if (sizes) sizes[nd] = x->sizes[d]; ++nd; }
+  }
+  if (dtype) *dtype = rd;
+  if (ndim) *ndim = nd;
+  return TX_OK;
+}
+
+static tx_status reduce_checks(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
+                               int keepdim) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(x, "x"))) return rc;
+  int32_t rd, nd;
+  int64_t shape[TX_MAX_DIMS];
+  if ((rc = tx_infer_reduce(op, x, dims, ndims, keepdim, &rd, &nd, shape))) return rc;
+  const bool widen = dtype_is_float(rd) && out->dtype == TX_F32 && op != TX_AMAX;
+  if (out->dtype != rd && !widen)
+    return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
+  if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the reduced shape");
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  if (partial_overlap(out, x) || (out->data == x->data && numel(out) && numel(x)))
+    return fail(TX_ERR_OVERLAP, "out overlaps the input");
+  return TX_OK;
+}
+
+tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
+                    double correction, void* ws, size_t ws_bytes, void* stream) {
+  tx_status rc = reduce_checks(op, out, x, dims, ndims, keepdim);
+  if (rc) return rc;
+  set_path("");
+  Plan p;
+  // a dummy out for planning is not needed: out is validated above
+  if ((rc = build_plan(op, x, out, dims, ndims, keepdim, &p))) return rc;
+  if (p.nout == 0) return TX_OK;
+  if ((op == TX_AMAX || op == TX_ARGMAX) && p.nred == 0)
+    return fail(TX_ERR_EMPTY_REDUCTION, "amax / argmax over an empty extent");
+  hipStream_t s = as_stream(stream);
+  switch (op) {
+    case TX_SUM: return launch_sum(false, p, x, out, correction, ws, ws_bytes, s);
+    case TX_MEAN: return launch_sum(true, p, x, out, correction, ws, ws_bytes, s);
+    case TX_VAR: return launch_var(p, x, out, correction, ws, ws_bytes, s);
+    case TX_PROD: return launch_prod(p, x, out, correction, ws, ws_bytes, s);
+    case TX_AMAX: return launch_amax(p, x, out, correction, ws, ws_bytes, s);
+    case TX_ARGMAX: return launch_argmax(p, x, out, correction, ws, ws_bytes, s);
+  }
+  return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
+}
+
+size_t tx_reduce_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
+                                 int keepdim) {
+  if (reduce_checks(op, out, x, dims, ndims, keepdim)) return 0;
+  Plan p;
+  if (build_plan(op, x, out, dims, ndims, keepdim, &p)) return 0;
+  return plan_ws_bytes(p, acc_size(op, x->dtype));
+}
+
+}  // extern "C"

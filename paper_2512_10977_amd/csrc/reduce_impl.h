@@ -1,0 +1,405 @@
+// Dimension reductions: planner, kernels and launch code.  Included by the
+// translation units that instantiate groups of (op, dtype) policies.
+//
+// A reduction is described as outputs o in [0, nout) x reduced elements r in
+// [0, nred); kept dims and reduced dims each stay in logical order (argmax
+// needs the logical position) and adjacent dims are merged where strides
+// allow.  Two kernels cover every case:
+//   rows : a group of G lanes (a wave, or the whole 256-lane workgroup) owns
+//          one output and strides through the reduced elements with 16-byte
+//          loads when the innermost reduced dim is contiguous; wave-level
+//          shuffles, then LDS across waves, combine the lanes.
+//   cols : lanes run along the contiguous KEPT dim, each lane owning VEC
+//          adjacent outputs and looping over the reduced elements, so every
+//          load is coalesced and no cross-lane combine exists.
+// When there are too few outputs to fill the chip the reduced range is split
+// S ways: pass 1 writes accumulator partials to the workspace, pass 2 (a tiny
+// kernel) combines the S partials per output and finalises.
+#pragma once
+#include <algorithm>
+#include <cstring>
+#include <type_traits>
+
+#include "common.h"
+
+namespace tx {
+namespace red {
+
+constexpr int kBlock = 256;
+constexpr int kMaxSplit = 1024;
+
+struct Plan {
+  int kind;                         // 0 rows, 1 cols
+  int nk, nr;                       // merged kept / reduced dims
+  int64_t ksize[TX_MAX_DIMS], kxs[TX_MAX_DIMS], kos[TX_MAX_DIMS];
+  int64_t rsize[TX_MAX_DIMS], rxs[TX_MAX_DIMS];
+  int64_t nout, nred;
+  int single_dim;                   // argmax position = coordinate along the one reduced dim (== r)
+  int vec;                          // elements per load (1 or 16/sizeof(T))
+  int group;                        // rows: lanes per output (64 or 256)
+  int split;                        // S
+  int64_t chunk;                    // reduced elements per split
+  int64_t blocks_x;
+};
+
+struct Args {
+  const char* x;
+  char* out;
+  char* ws;
+  int out_dtype;
+  int nk, nr;
+  FastDiv kdiv[TX_MAX_DIMS];
+  int64_t kxs[TX_MAX_DIMS], kos[TX_MAX_DIMS];
+  FastDiv rdiv[TX_MAX_DIMS];
+  int64_t rxs[TX_MAX_DIMS];
+  int64_t nout, nred, chunk;
+  int split, group;
+  double correction;
+};
+
+// ---------------------------------------------------------------------------
+// accumulator policies.  value_t is what an element is converted to on load.
+// ---------------------------------------------------------------------------
+template <class T> struct IsFloatT { static constexpr bool value = std::is_same<T, float>::value || std::is_same<T, f16>::value || std::is_same<T, bf16>::value; };
+
+template <class T, bool MEAN> struct SumPolicy {
+  using In = T;
+  static constexpr bool flt = IsFloatT<T>::value;
+  using Acc = typename std::conditional<flt, float, int64_t>::type;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() { return Acc(0); }
+  __device__ static void step(Acc& a, T x, int64_t, double) { a += cvt<Acc>(x); }
+  __device__ static void merge(Acc& a, const Acc& b) { a += b; }
+  __device__ static Acc shfl(const Acc& a, int m) { return shfl_xor(a, m); }
+  __device__ static void finish(const Acc& a, int64_t n, double, double, double* f, int64_t* i) {
+    if constexpr (flt) *f = MEAN ? (n ? (double)a / (double)n : __longlong_as_double(0x7ff8000000000000ll)) : (double)a;
+    else *i = a;
+  }
+};
+
+template <class T> struct ProdPolicy {
+  using In = T;
+  static constexpr bool flt = IsFloatT<T>::value;
+  using Acc = typename std::conditional<flt, double, int64_t>::type;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() { return Acc(1); }
+  __device__ static void step(Acc& a, T x, int64_t, double) {
+    if constexpr (flt) a *= cvt<double>(x);
+    else a = (int64_t)((uint64_t)a * (uint64_t)cvt<int64_t>(x));
+  }
+  __device__ static void merge(Acc& a, const Acc& b) {
+    if constexpr (flt) a *= b;
+    else a = (int64_t)((uint64_t)a * (uint64_t)b);
+  }
+  __device__ static Acc shfl(const Acc& a, int m) { return shfl_xor(a, m); }
+  __device__ static void finish(const Acc& a, int64_t, double, double, double* f, int64_t* i) {
+    if constexpr (flt) *f = a; else *i = a;
+  }
+};
+
+template <class T> struct AmaxPolicy {
+  using In = T;
+  static constexpr bool flt = IsFloatT<T>::value;
+  using Acc = typename std::conditional<flt, float, int64_t>::type;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() {
+    if constexpr (flt) return __uint_as_float(0xff800000u);
+    else return (Acc)0x8000000000000000ll;
+  }
+  __device__ static void merge(Acc& a, const Acc& b) {
+    if constexpr (flt) a = (a != a) ? a : ((b != b) ? b : (b > a ? b : a));
+    else a = b > a ? b : a;
+  }
+  __device__ static void step(Acc& a, T x, int64_t, double) { merge(a, cvt<Acc>(x)); }
+  __device__ static Acc shfl(const Acc& a, int m) { return shfl_xor(a, m); }
+  __device__ static void finish(const Acc& a, int64_t, double, double, double* f, int64_t* i) {
+    if constexpr (flt) *f = a; else *i = a;
+  }
+};
+
+template <class V> struct ArgAcc { V v; int64_t i; };
+template <class T> struct ArgmaxPolicy {
+  using In = T;
+  static constexpr bool flt = IsFloatT<T>::value;
+  using V = typename std::conditional<flt, float, int64_t>::type;
+  using Acc = ArgAcc<V>;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() {
+    Acc a;
+    if constexpr (flt) a.v = __uint_as_float(0xff800000u);
+    else a.v = (V)0x8000000000000000ll;
+    a.i = 0x7fffffffffffffffll;
+    return a;
+  }
+  // does (v1,i1) outrank (v2,i2)?  NaN outranks everything; ties go to the lower index
+  __device__ static bool better(V v1, int64_t i1, V v2, int64_t i2) {
+    if constexpr (flt) {
+      bool n1 = v1 != v1, n2 = v2 != v2;
+      if (n1 || n2) return (n1 && n2) ? i1 < i2 : n1;
+    }
+    return v1 > v2 || (v1 == v2 && i1 < i2);
+  }
+  __device__ static void merge(Acc& a, const Acc& b) { if (better(b.v, b.i, a.v, a.i)) a = b; }
+  __device__ static void step(Acc& a, T x, int64_t pos, double) {
+    V v = cvt<V>(x);
+    if (better(v, pos, a.v, a.i)) { a.v = v; a.i = pos; }
+  }
+  __device__ static Acc shfl(const Acc& a, int m) { Acc r; r.v = shfl_xor(a.v, m); r.i = shfl_xor(a.i, m); return r; }
+  __device__ static void finish(const Acc& a, int64_t, double, double, double*, int64_t* i) { *i = a.i; }
+};
+
+// variance from sums of (x - K) and (x - K)^2 in binary64; K is the first
+// element of the reduced range, which keeps the two sums small
+struct VarAcc { double s1, s2; };
+template <class T> struct VarPolicy {
+  using In = T;
+  static constexpr bool flt = true;
+  using Acc = VarAcc;
+  static constexpr bool needs_shift = true;
+  __device__ static Acc init() { return Acc{0.0, 0.0}; }
+  __device__ static void step(Acc& a, T x, int64_t, double K) {
+    double d = cvt<double>(x) - K;
+    a.s1 += d;
+    a.s2 = __builtin_fma(d, d, a.s2);
+  }
+  __device__ static void merge(Acc& a, const Acc& b) { a.s1 += b.s1; a.s2 += b.s2; }
+  __device__ static Acc shfl(const Acc& a, int m) { return Acc{shfl_xor(a.s1, m), shfl_xor(a.s2, m)}; }
+  __device__ static void finish(const Acc& a, int64_t n, double correction, double, double* f, int64_t*) {
+    double nn = (double)n;
+    double div = nn - correction;
+    if (div < 0.0) div = 0.0;
+    double m2 = a.s2 - a.s1 * a.s1 / nn;
+    if (m2 < 0.0) m2 = 0.0;
+    *f = n ? m2 / div : __longlong_as_double(0x7ff8000000000000ll);
+  }
+};
+
+// store a finished value in the run-time output dtype
+template <bool FLT> __device__ __forceinline__ void store_result(char* out, int64_t off, int dt, double f, int64_t i) {
+  if constexpr (FLT) {
+    switch (dt) {
+      case TX_F32: ((float*)out)[off] = (float)f; break;
+      case TX_BF16: ((bf16*)out)[off] = float_to_bf16((float)f); break;
+      case TX_F16: ((f16*)out)[off] = (f16)(float)f; break;
+      default: ((int64_t*)out)[off] = i; break;
+    }
+  } else {
+    switch (dt) {
+      case TX_I64: ((int64_t*)out)[off] = i; break;
+      case TX_I32: ((int32_t*)out)[off] = (int32_t)i; break;
+      default: ((uint8_t*)out)[off] = (uint8_t)(i != 0); break;
+    }
+  }
+}
+
+template <class P> __device__ __forceinline__ void emit(const Args& a, const typename P::Acc& acc, int64_t oo) {
+  double f = 0.0;
+  int64_t i = 0;
+  P::finish(acc, a.nred, a.correction, 0.0, &f, &i);
+  // argmax produces an index even for float input
+  if constexpr (std::is_same<typename P::Acc, ArgAcc<float>>::value || std::is_same<typename P::Acc, ArgAcc<int64_t>>::value)
+    ((int64_t*)a.out)[oo] = i;
+  else
+    store_result<P::flt>(a.out, oo, a.out_dtype, f, i);
+}
+
+__device__ __forceinline__ int64_t reduced_offset(const Args& a, int64_t r) {
+  if (a.nr == 1) return r * a.rxs[0];
+  int64_t off = 0;
+  uint32_t rem = (uint32_t)r;
+  for (int d = a.nr - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.rdiv[d].divmod(rem, q, m);
+    rem = q;
+    off += (int64_t)m * a.rxs[d];
+  }
+  return off;
+}
+__device__ __forceinline__ void kept_offsets(const Args& a, int64_t o, int64_t* xo, int64_t* oo) {
+  int64_t x = 0, y = 0;
+  if (a.nk == 1) { x = o * a.kxs[0]; y = o * a.kos[0]; }
+  else {
+    uint32_t rem = (uint32_t)o;
+    for (int d = a.nk - 1; d >= 0; --d) {
+      uint32_t q, m;
+      a.kdiv[d].divmod(rem, q, m);
+      rem = q;
+      x += (int64_t)m * a.kxs[d];
+      y += (int64_t)m * a.kos[d];
+    }
+  }
+  *xo = x;
+  *oo = y;
+}
+
+// ---------------------------------------------------------------------------
+// rows kernel: grid.x = ceil(nout / groups_per_block), grid.y = split
+// ---------------------------------------------------------------------------
+template <class P, int VEC>
+__global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const Args a) {
+  using T = typename P::In;
+  using Acc = typename P::Acc;
+  __shared__ Acc lds[kBlock / kWave];
+  const int G = a.group;
+  const int gpb = kBlock / G;                          // outputs per workgroup
+  const int gidx = threadIdx.x / G, lane = threadIdx.x % G;
+  const int64_t o = (int64_t)blockIdx.x * gpb + gidx;
+  const bool live = o < a.nout;
+  int64_t xo = 0, oo = 0;
+  if (live) kept_offsets(a, o, &xo, &oo);
+  const int64_t begin = (int64_t)blockIdx.y * a.chunk;
+  int64_t end = begin + a.chunk;
+  if (end > a.nred) end = a.nred;
+  const T* x = (const T*)a.x + xo;
+  double K = 0.0;
+  if constexpr (P::needs_shift)
+    if (live && a.nred > 0) K = cvt<double>(x[reduced_offset(a, 0)]);
+  Acc acc = P::init();
+  if (live) {
+#pragma unroll 4
+    for (int64_t r = begin + (int64_t)lane * VEC; r < end; r += (int64_t)G * VEC) {
+      const int64_t off = reduced_offset(a, r);
+      if constexpr (VEC == 1) {
+        P::step(acc, x[off], r, K);
+      } else {
+        Vec<T, VEC> v = *(const Vec<T, VEC>*)(x + off);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) P::step(acc, v.v[e], r + e, K);
+      }
+    }
+  }
+  // lanes of a wave
+#pragma unroll
+  for (int m = kWave / 2; m >= 1; m >>= 1) { Acc other = P::shfl(acc, m); P::merge(acc, other); }
+  if (G == kBlock) {
+    const int w = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) lds[w] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      acc = lds[0];
+      for (int k = 1; k < kBlock / kWave; ++k) P::merge(acc, lds[k]);
+    }
+  }
+  if (lane == 0 && live) {
+    if (a.split == 1) emit<P>(a, acc, oo);
+    else ((Acc*)a.ws)[o * a.split + blockIdx.y] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// cols kernel: lanes along the innermost kept dim; grid.y = split
+// ---------------------------------------------------------------------------
+template <class P, int VEC>
+__global__ __launch_bounds__(kBlock) void reduce_cols_kernel(const Args a) {
+  using T = typename P::In;
+  using Acc = typename P::Acc;
+  const int64_t o0 = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * VEC;
+  if (o0 >= a.nout) return;
+  int64_t xo, oo;
+  kept_offsets(a, o0, &xo, &oo);
+  const T* x = (const T*)a.x + xo;
+  const int64_t begin = (int64_t)blockIdx.y * a.chunk;
+  int64_t end = begin + a.chunk;
+  if (end > a.nred) end = a.nred;
+  double K[VEC];
+  Acc acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { acc[e] = P::init(); K[e] = 0.0; }
+  if constexpr (P::needs_shift) {
+    if (a.nred > 0) {
+      const int64_t off = reduced_offset(a, 0);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) K[e] = cvt<double>(x[off + e]);
+    }
+  }
+#pragma unroll 8
+  for (int64_t r = begin; r < end; ++r) {
+    const int64_t off = reduced_offset(a, r);
+    Vec<T, VEC> v = *(const Vec<T, VEC>*)(x + off);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) P::step(acc[e], v.v[e], r, K[e]);
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    if (a.split == 1) emit<P>(a, acc[e], oo + e);          // innermost kept dim has unit output stride when VEC > 1
+    else ((Acc*)a.ws)[(o0 + e) * a.split + blockIdx.y] = acc[e];
+  }
+}
+
+// pass 2: one lane per output walks its S partials in order
+template <class P>
+__global__ __launch_bounds__(kBlock) void reduce_final_kernel(const Args a) {
+  using Acc = typename P::Acc;
+  const int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (o >= a.nout) return;
+  int64_t xo, oo;
+  kept_offsets(a, o, &xo, &oo);
+  const Acc* p = (const Acc*)a.ws + o * a.split;
+  Acc acc = p[0];
+  for (int s = 1; s < a.split; ++s) P::merge(acc, p[s]);
+  emit<P>(a, acc, oo);
+}
+
+// ---------------------------------------------------------------------------
+// host: planning
+// ---------------------------------------------------------------------------
+tx_status normalise_dims(int nd, const int64_t* dims, int ndims, bool* reduced);
+// Fills the dim lists of `p` from x / out and the reduced-dim mask.
+void plan_dims(Plan* p, const tx_tensor* x, const tx_tensor* out, const bool* reduced, int keepdim);
+// Chooses kernel kind, vector width, group, split.  esize = sizeof(input element), acc_size = sizeof(Acc).
+void plan_launch(Plan* p, const tx_tensor* x, int esize, bool shift_needs_first);
+size_t plan_ws_bytes(const Plan& p, size_t acc_size);
+
+template <class P> tx_status launch(const Plan& p, const tx_tensor* x, const tx_tensor* out, double correction, void* ws,
+                                    size_t ws_bytes, hipStream_t stream) {
+  using T = typename P::In;
+  constexpr int V = 16 / sizeof(T);
+  Args a;
+  a.x = (const char*)x->data;
+  a.out = (char*)out->data;
+  a.ws = (char*)ws;
+  a.out_dtype = out->dtype;
+  a.nk = p.nk;
+  a.nr = p.nr;
+  for (int d = 0; d < p.nk; ++d) { a.kdiv[d] = FastDiv((uint32_t)p.ksize[d]); a.kxs[d] = p.kxs[d]; a.kos[d] = p.kos[d]; }
+  for (int d = 0; d < p.nr; ++d) { a.rdiv[d] = FastDiv((uint32_t)p.rsize[d]); a.rxs[d] = p.rxs[d]; }
+  a.nout = p.nout;
+  a.nred = p.nred;
+  a.chunk = p.chunk;
+  a.split = p.split;
+  a.group = p.group;
+  a.correction = correction;
+  if (p.split > 1) {
+    size_t need = plan_ws_bytes(p, sizeof(typename P::Acc));
+    if (!ws || ws_bytes < need) return fail(TX_ERR_WORKSPACE, "reduce needs %zu workspace bytes, got %zu", need, ws_bytes);
+  }
+  dim3 grid((unsigned)p.blocks_x, (unsigned)p.split);
+  if (p.kind == 0) {
+    set_path(p.split > 1 ? "rows-split" : (p.group == kBlock ? "rows-block" : "rows-wave"));
+    if (p.vec > 1) hipLaunchKernelGGL((reduce_rows_kernel<P, V>), grid, dim3(kBlock), 0, stream, a);
+    else hipLaunchKernelGGL((reduce_rows_kernel<P, 1>), grid, dim3(kBlock), 0, stream, a);
+  } else {
+    set_path(p.split > 1 ? "cols-split" : "cols");
+    if (p.vec > 1) hipLaunchKernelGGL((reduce_cols_kernel<P, V>), grid, dim3(kBlock), 0, stream, a);
+    else hipLaunchKernelGGL((reduce_cols_kernel<P, 1>), grid, dim3(kBlock), 0, stream, a);
+  }
+  tx_status rc = check_launch("reduce kernel");
+  if (rc) return rc;
+  if (p.split > 1) {
+    hipLaunchKernelGGL((reduce_final_kernel<P>), dim3((unsigned)((p.nout + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                       stream, a);
+    rc = check_launch("reduce finalise kernel");
+  }
+  return rc;
+}
+
+// per-dtype dispatch for one op family; defined in the translation units
+tx_status launch_sum(bool mean, const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_var(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_prod(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_amax(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_argmax(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+size_t acc_size(int op, int dtype);
+
+}  // namespace red
+}  // namespace tx

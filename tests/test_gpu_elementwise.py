@@ -1,0 +1,317 @@
+"""GPU parity: elementwise operators (HIP library through the C ABI) vs. the CPU oracle.
+
+Covers the broadcast-add workload bit for bit and the elementwise sweep: unary
+and binary ops x dtypes (with promotion for mixed pairs) x shapes ([0], 0-dim,
+[7,13,5], multi-tile ragged shapes, [8192,8192]) x views (contiguous,
+transposed, step-2 sliced, broadcast-expanded), floats carrying 1 % NaN / inf.
+"""
+import itertools
+
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2512_10977_amd import binding as B
+from paper_2512_10977_amd import inputs as I
+from tests.parity import (HALF_MAX, assert_exact, assert_exact_fp, assert_rel, assert_ulp, empty_like_layout,
+                          to_device_view)
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
+ALL = [F32, BF16, F16, I32, I64, BOOL]
+UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu"]
+BINARY = ["add", "mul", "div", "maximum", "eq"]
+MIXED = [(I32, I64), (I64, F32), (BF16, F32), (F16, BF16), (BOOL, I32), (I64, F16)]
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+def check_unary(op, a_cpu, layout="contig", path=None, what=""):
+    try:
+        want = O.unary(op, a_cpu)
+    except O.OracleError as e:
+        a = to_device_view(a_cpu)
+        with pytest.raises(B.TxError) as g:
+            B.tx_unary(op, torch.empty(a.shape, dtype=a.dtype, device="cuda"), a)
+        assert g.value.kind.lower() == e.kind
+        return None
+    a = to_device_view(a_cpu)
+    out = empty_like_layout(a, want.dtype, layout=layout)
+    B.tx_force_path(path)
+    try:
+        B.tx_unary(op, out, a)
+        used = B.tx_last_path()
+    finally:
+        B.tx_force_path(None)
+    sync()
+    what = "%s %s %s %s %s [%s]" % (op, a_cpu.dtype, tuple(a_cpu.shape), what, layout, used)
+    if op in ("neg", "abs"):
+        assert_exact_fp(out, want, what)
+    elif want.dtype == F32:
+        assert_ulp(out, want, 2, what)
+    else:
+        assert_rel(out, want, 1e-2, scale=6.2e-5 if want.dtype == F16 else FLT_TINY, what=what,
+                   overflow_max=HALF_MAX[want.dtype])
+    return used
+
+
+FLT_TINY = 1.2e-38
+
+
+def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what=""):
+    want = O.binary(op, a_cpu, b_cpu, alpha=alpha)
+    a, b = to_device_view(a_cpu), to_device_view(b_cpu)
+    ref_layout = a if tuple(a.shape) == tuple(want.shape) else torch.empty(want.shape, device="meta")
+    out = empty_like_layout(ref_layout, want.dtype, layout=layout)
+    B.tx_force_path(path)
+    try:
+        if op == "add":
+            B.tx_add(out, a, b, alpha)
+        else:
+            B.tx_binary(op, out, a, b)
+        used = B.tx_last_path()
+    finally:
+        B.tx_force_path(None)
+    sync()
+    what = "%s %s,%s %s %s %s [%s]" % (op, a_cpu.dtype, b_cpu.dtype, tuple(want.shape), what, layout, used)
+    if op == "eq":
+        assert_exact(out, want, what)
+    elif op == "div":
+        if want.dtype == F32:
+            assert_ulp(out, want, 2, what)
+        else:
+            assert_rel(out, want, 1e-2, scale=6.2e-5 if want.dtype == F16 else FLT_TINY, what=what,
+                       overflow_max=HALF_MAX[want.dtype])
+    else:
+        assert_exact_fp(out, want, what)
+    return used
+
+
+# --------------------------------------------------------------------------- workload 1: broadcast add
+def test_broadcast_add_4096_bit_exact():
+    a, b = I.broadcast_add_inputs(4096, 4096, seed=0)
+    used = check_binary("add", a, b)
+    assert used == "vec"
+
+
+def test_broadcast_add_small_and_alpha():
+    a, b = I.broadcast_add_inputs(64, 48, seed=0)
+    check_binary("add", a, b)
+    check_binary("add", a, b, alpha=0.1)
+    check_binary("add", a, b, alpha=-3)
+
+
+# --------------------------------------------------------------------------- sweep on [7,13,5], [0], 0-dim
+@pytest.mark.parametrize("op", UNARY)
+def test_unary_sweep_small(op):
+    for dt, kind, layout in itertools.product(ALL, I.VIEW_KINDS, ["contig", "like_input"]):
+        a = I.make_view((7, 13, 5), dt, kind, seed=101, specials=0.01)
+        check_unary(op, a, layout, what=kind)
+    for dt in ALL:
+        check_unary(op, I.typed((0,), dt, seed=1))
+        check_unary(op, I.typed((), dt, seed=2))
+        check_unary(op, I.typed((5, 0, 3), dt, seed=3))
+
+
+@pytest.mark.parametrize("op", BINARY)
+def test_binary_sweep_small_same_dtype(op):
+    for dt, kind, layout in itertools.product(ALL, I.VIEW_KINDS, ["contig", "like_input"]):
+        a = I.make_view((7, 13, 5), dt, kind, seed=102, specials=0.01)
+        b = I.make_view((7, 13, 5), dt, "contig", seed=103, specials=0.01)
+        check_binary(op, a, b, layout=layout, what=kind)
+        check_binary(op, b, a, layout="contig", what="rev-" + kind)
+    for dt in ALL:
+        check_binary(op, I.typed((0,), dt, seed=1), I.typed((0,), dt, seed=2))
+        check_binary(op, I.typed((), dt, seed=3), I.typed((), dt, seed=4))
+        check_binary(op, I.typed((7, 1, 5), dt, seed=5), I.typed((13, 1), dt, seed=6))
+
+
+@pytest.mark.parametrize("op", BINARY)
+def test_binary_sweep_small_mixed_dtypes(op):
+    for (da, db), kind in itertools.product(MIXED, ["contig", "transposed", "step2_inner", "expand_col"]):
+        a = I.make_view((7, 13, 5), da, kind, seed=104, specials=0.01)
+        b = I.make_view((7, 13, 5), db, "contig", seed=105, specials=0.01)
+        check_binary(op, a, b, what=kind)
+        check_binary(op, b, a, what="rev-" + kind)
+    # 0-dim mixes: the 0-dim operand only matters when its category is higher
+    for da, db in itertools.product(ALL, ALL):
+        a = I.typed((33,), da, seed=106)
+        z = I.typed((), db, seed=107)
+        check_binary(op, a, z, what="0-dim b")
+        check_binary(op, z, a, what="0-dim a")
+
+
+def test_add_alpha_variants():
+    for dt in (F32, BF16, F16):
+        a = I.typed((300, 77), dt, seed=108, specials=0.01)
+        b = I.typed((300, 77), dt, seed=109, specials=0.01)
+        for alpha in (0.1, -2.5, 3):
+            check_binary("add", a, b, alpha=alpha)
+    for dt in (I32, I64):
+        a = I.typed((300, 77), dt, seed=110)
+        b = I.typed((300, 77), dt, seed=111)
+        check_binary("add", a, b, alpha=-7)
+    check_binary("add", I.typed((50,), BOOL, seed=1), I.typed((50,), BOOL, seed=2), alpha=0)
+    check_binary("add", I.typed((50,), I64, seed=1), I.typed((50,), F16, seed=2), alpha=0.5)
+
+
+# --------------------------------------------------------------------------- multi-tile, ragged, every path
+@pytest.mark.parametrize("dt", ALL)
+def test_multi_tile_ragged_shapes_all_paths(dt):
+    shape = (300, 1027)
+    uop = "exp" if dt.is_floating_point else ("neg" if dt != BOOL else "sigmoid")
+    for kind in I.VIEW_KINDS:
+        a = I.make_view(shape, dt, kind, seed=120, specials=0.01)
+        b = I.make_view(shape, dt, "contig", seed=121, specials=0.01)
+        paths = {check_binary("add", a, b, path=p, what=kind + "/" + str(p)) for p in (None, "vec", "tile", "generic")}
+        assert "generic" in paths
+        check_unary(uop, a, path=None, what=kind)
+        check_unary(uop, a, "like_input", what=kind)
+    long1d = I.typed(((1 << 20) + 3,), dt, seed=122, specials=0.01)
+    assert check_unary(uop, long1d) == "vec"
+    assert check_binary("mul", long1d, long1d.flip(0).contiguous()) == "vec"
+    # misaligned base pointer (slice off one element): must still be correct
+    check_binary("add", long1d[1:], long1d[:-1], what="misaligned")
+
+
+def test_path_selection():
+    n = 512
+    a = I.make_view((n, n), F32, "contig", seed=130)
+    assert check_binary("add", a, a) == "vec"
+    t = I.make_view((n, n), F32, "transposed", seed=131)
+    assert check_binary("add", t, a) == "tile"
+    assert check_binary("add", t, a, layout="like_input") == "tile"       # out in t's layout: now `a` is transposed
+    assert check_unary("exp", t, "like_input") == "vec"                    # same layout in and out collapses to 1-D
+    s = I.make_view((n, n), F32, "step2_inner", seed=132)
+    assert check_binary("add", s, a) == "generic"
+    assert check_binary("add", I.make_view((n, n), F32, "step2_outer", seed=133), a) == "vec"
+    assert check_binary("add", I.make_view((n, n), F32, "expand_row", seed=134), a) == "vec"
+    assert check_binary("add", I.make_view((n, n), F32, "expand_col", seed=135), a) == "vec"
+    b3 = I.make_view((6, 200, 300), BF16, "contig", seed=136).transpose(1, 2)       # batched transpose
+    assert check_binary("mul", b3, I.make_view((6, 300, 200), BF16, "contig", seed=137)) == "tile"
+
+
+# --------------------------------------------------------------------------- where / masked_fill
+def check_where(c, x, y, what=""):
+    want = O.where(c, x, y)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_where(out, to_device_view(c), to_device_view(x), to_device_view(y))
+    sync()
+    assert_exact_fp(out, want, "where %s %s %s %s" % (x.dtype, y.dtype, tuple(want.shape), what))
+    if x.dtype == y.dtype:
+        assert_exact(out, want, "where bits " + what)
+
+
+def test_where_sweep():
+    for dt, kind in itertools.product(ALL, I.VIEW_KINDS):
+        for shape in [(7, 13, 5), (130, 517)]:
+            c = I.booleans(shape, 0.5, seed=140)
+            x = I.make_view(shape, dt, kind, seed=141, specials=0.01)
+            y = I.make_view(shape, dt, "contig", seed=142, specials=0.01)
+            check_where(c, x, y, kind)
+    for da, db in MIXED:
+        c = I.booleans((7, 13, 5), 0.5, seed=143)
+        check_where(c, I.typed((7, 13, 5), da, seed=144), I.typed((7, 13, 5), db, seed=145), "mixed")
+        check_where(c, I.typed((7, 13, 5), da, seed=144), I.typed((), db, seed=146), "0-dim y")
+    check_where(I.booleans((7, 1, 5), 0.5, seed=147), I.typed((13, 1), F32, seed=148), I.typed((5,), F32, seed=149), "bcast")
+    check_where(I.booleans((0,), 0.5, seed=1), I.typed((0,), F32, seed=2), I.typed((0,), F32, seed=3), "empty")
+    with pytest.raises(B.TxError) as e:
+        B.tx_where(torch.empty(3, device="cuda"), torch.zeros(3, dtype=I32, device="cuda"),
+                   torch.zeros(3, device="cuda"), torch.zeros(3, device="cuda"))
+    assert e.value.kind == "DTYPE"
+
+
+def check_masked_fill(s, m, value, what=""):
+    want = O.masked_fill(s, m, value)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_masked_fill(out, to_device_view(s), to_device_view(m), value)
+    sync()
+    assert_exact(out, want, "masked_fill %s %s %r %s" % (s.dtype, tuple(want.shape), value, what)) if value == value \
+        else assert_exact_fp(out, want, "masked_fill nan")
+
+
+def test_masked_fill_sweep():
+    for dt, kind in itertools.product(ALL, I.VIEW_KINDS):
+        for shape in [(7, 13, 5), (257, 300)]:
+            s = I.make_view(shape, dt, kind, seed=150, specials=0.01)
+            m = I.bernoulli_mask(shape, 0.3, seed=4)
+            check_masked_fill(s, m, -1.0 if dt.is_floating_point else -1, kind)
+    s = I.typed((64, 256), F32, seed=151)
+    check_masked_fill(s, I.bernoulli_mask((256,), 0.3, seed=5), 2.5, "row mask")
+    check_masked_fill(s, I.bernoulli_mask((64, 1), 0.3, seed=6), 2.5, "column mask")
+    check_masked_fill(s, I.bernoulli_mask((64, 256), 0.3, seed=7), float("nan"), "nan")
+    check_masked_fill(I.typed((64, 256), I32, seed=152), I.bernoulli_mask((64, 256), 0.3, seed=8), 2.5, "truncating")
+    check_masked_fill(I.typed((64, 256), BF16, seed=153), I.bernoulli_mask((64, 256), 0.3, seed=9), 1.00390625, "bf16 tie")
+    check_masked_fill(I.typed((), F32, seed=1), torch.tensor(True), 3.0, "0-dim")
+
+
+# --------------------------------------------------------------------------- error behaviour through the ABI
+def test_error_codes():
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    with pytest.raises(B.TxError) as e:
+        B.tx_add(d(3, 3), d(3, 2), d(3))
+    assert e.value.kind == "SHAPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_add(d(3, 4), d(3, 1), d(4), 1)
+        B.tx_add(d(3, 4, dt=I32), d(3, 1), d(4))
+    assert e.value.kind == "DTYPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_add(d(2, 3), d(3), d(3))
+    assert e.value.kind == "SHAPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_add(d(3, dt=I32), d(3, dt=I32), d(3, dt=I32), 0.5)
+    assert e.value.kind == "SCALAR"
+    with pytest.raises(B.TxError) as e:
+        B.tx_add(d(1).expand(3), d(3), d(3))
+    assert e.value.kind == "OVERLAP"
+    buf = d(10)
+    with pytest.raises(B.TxError) as e:
+        B.tx_add(buf[1:9], buf[0:8], buf[0:8])
+    assert e.value.kind == "OVERLAP"
+    B.tx_add(buf, buf, buf)                      # exact alias is in-place use
+    with pytest.raises(B.TxError) as e:
+        B.tx_unary("gelu", d(3, dt=I32), d(3, dt=I32))
+    assert e.value.kind == "DTYPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_unary("neg", d(3, dt=BOOL), d(3, dt=BOOL))
+    assert e.value.kind == "DTYPE"
+
+
+def test_in_place_alias():
+    a = I.typed((1000,), F32, seed=160)
+    b = I.typed((1000,), F32, seed=161)
+    da, db = a.cuda(), b.cuda()
+    B.tx_add(da, da, db)
+    sync()
+    assert_exact_fp(da, O.binary("add", a, b), "in-place add")
+
+
+# --------------------------------------------------------------------------- full size [8192,8192]
+FULL = (8192, 8192)
+
+
+@pytest.mark.parametrize("op,dt", [("exp", F32), ("gelu", F32), ("tanh", BF16), ("sigmoid", F16), ("neg", I64)])
+def test_unary_full_size(op, dt):
+    a = I.typed(FULL, dt, seed=170, specials=0.01)
+    assert check_unary(op, a) == "vec"
+
+
+@pytest.mark.parametrize("op,da,db,kind", [
+    ("add", F32, F32, "contig"), ("mul", BF16, BF16, "contig"), ("add", I64, I64, "contig"),
+    ("eq", F32, F32, "contig"), ("maximum", F32, F32, "transposed"), ("add", BF16, F32, "contig"),
+    ("div", F32, F32, "step2_inner"), ("mul", F32, F32, "step2_outer"), ("add", F16, F16, "expand_row"),
+    ("add", I32, I64, "expand_col"),
+])
+def test_binary_full_size(op, da, db, kind):
+    a = I.make_view(FULL, da, kind, seed=171, specials=0.01)
+    b = I.make_view(FULL, db, "contig", seed=172, specials=0.01)
+    check_binary(op, a, b, what=kind)
+
+
+def test_where_and_masked_fill_full_size():
+    c = I.booleans(FULL, 0.5, seed=173)
+    check_where(c, I.typed(FULL, F32, seed=174, specials=0.01), I.typed(FULL, F32, seed=175, specials=0.01), "full")
+    check_masked_fill(I.typed(FULL, F32, seed=176), I.bernoulli_mask(FULL, 0.3, seed=4), -1.0, "full")
