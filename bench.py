@@ -1,0 +1,259 @@
+"""Benchmark: one "step" = one pass over every operator class of the hot path at full workload size.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints ONE JSON line.  `value` is the whole-step throughput: algorithmic HBM bytes of all operators in the
+step divided by the wall-clock time of the step (inputs already resident in HBM).  `per_op` gives each
+operator's own time (HIP events inside the timed region), GB/s, fraction of the 8 TB/s peak and elements/s.
+`roofline` describes the operator that takes the largest share of the step.  `cpu_baseline` is the CPU oracle
+timed on a bounded sample of the same step.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_GBPS = 8000.0
+MiB = 1 << 20
+
+
+def build_ops(torch, B):
+    """Returns a list of dicts: name, kernel, row (scope-table step), bytes, elems, fn."""
+    dev = "cuda"
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    F32, BF16, I64, I32 = torch.float32, torch.bfloat16, torch.int64, torch.int32
+
+    def randn(shape, dtype=F32, std=1.0):
+        x = torch.randn(shape, device=dev, dtype=F32, generator=g)
+        if std != 1.0:
+            x.mul_(std)
+        return x.to(dtype)
+
+    def randint(shape, lo, hi, dtype=I64):
+        return torch.randint(lo, hi + 1, shape, device=dev, dtype=I64, generator=g).to(dtype)
+
+    ops = []
+
+    def add(name, row, kernel, nbytes, elems, fn):
+        ops.append(dict(name=name, row=row, kernel=kernel, bytes=int(nbytes), elems=int(elems), fn=fn))
+
+    # ---- workload 1: broadcast add, rotating outputs so the 64 MiB result is not an Infinity-Cache hit
+    a1, b1 = randn((4096, 1)), randn((1, 4096))
+    outs1 = [torch.empty((4096, 4096), device=dev) for _ in range(9)]
+    state = {"i": 0}
+
+    def f_bcast():
+        state["i"] = (state["i"] + 1) % len(outs1)
+        B.tx_add(outs1[state["i"]], a1, b1, 1)
+    add("add_bcast_f32[4096,1]+[1,4096]", "a3", "ew_vec_kernel", 4096 * 4096 * 4 + 2 * 4096 * 4, 4096 * 4096, f_bcast)
+
+    # ---- workload 2: elementwise sweep at [8192,8192]
+    N = 8192
+    n2 = N * N
+    xf, yf, of = randn((N, N), std=3.0), randn((N, N), std=3.0), torch.empty((N, N), device=dev)
+    xb, ob = xf.to(BF16), torch.empty((N, N), device=dev, dtype=BF16)
+    xi, yi, oi = randint((N, N), -1000, 1000), randint((N, N), -1000, 1000), torch.empty((N, N), device=dev, dtype=I64)
+    obool = torch.empty((N, N), device=dev, dtype=torch.bool)
+    cond = torch.rand((N, N), device=dev, generator=g) < 0.5
+    add("exp_f32", "a3", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("exp", of, xf))
+    add("add_f32", "a3", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_add(of, xf, yf, 1))
+    add("gelu_bf16", "a3", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("gelu", ob, xb))
+    add("gelu_f32", "a3", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("gelu", of, xf))
+    add("add_i64", "a3", "ew_vec_kernel", n2 * 24, n2, lambda: B.tx_add(oi, xi, yi, 1))
+    add("eq_f32", "a3", "ew_vec_kernel", n2 * 9, n2, lambda: B.tx_binary("eq", obool, xf, yf))
+    add("where_f32", "a3", "ew_vec_kernel", n2 * 13, n2, lambda: B.tx_where(of, cond, xf, yf))
+    add("add_bf16+f32_mixed", "a4", "ew_vec_kernel", n2 * 10, n2, lambda: B.tx_add(of, xb, yf, 1))
+    wide = randn((N, 2 * N), std=3.0)
+    tall = randn((2 * N, N), std=3.0)
+    add("add_f32_step2_inner", "a4", "ew_generic_kernel", n2 * 12, n2, lambda: B.tx_add(of, wide[:, ::2], yf, 1))
+    add("add_f32_step2_outer", "a4", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_add(of, tall[::2], yf, 1))
+    col = randn((N, 1), std=3.0)
+    add("add_f32_expand_row", "a4", "ew_vec_kernel", n2 * 8 + N * 4, n2, lambda: B.tx_add(of, col.expand(N, N), yf, 1))
+    add("add_f32_transposed", "a5", "ew_tile_kernel", n2 * 12, n2, lambda: B.tx_add(of, xf.t(), yf, 1))
+    add("mul_bf16_transposed", "a5", "ew_tile_kernel", n2 * 6, n2, lambda: B.tx_binary("mul", ob, xb.t(), xb))
+
+    # ---- workload 3: reductions over x[64,4096,1024]
+    R = (64, 4096, 1024)
+    nr = 64 * 4096 * 1024
+    rf = randn(R)
+    rb = rf.to(BF16)
+    ri = randint(R, -(2 ** 20), 2 ** 20)
+
+    def reducer(op, x, dims, out_shape, out_dtype):
+        out = torch.empty(out_shape, device=dev, dtype=out_dtype)
+        nb = B.tx_reduce_workspace_bytes(op, out, x, dims)
+        ws = B.workspace(nb) if nb else None
+        return lambda: B.tx_reduce(op, out, x, dims, False, 1.0, ws)
+
+    add("sum_f32_dim-1", "a6", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("sum", rf, -1, (64, 4096), F32))
+    add("argmax_f32_dim-1", "a6", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 8, nr, reducer("argmax", rf, -1, (64, 4096), I64))
+    add("var_f32_dim-1", "a6", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("var", rf, -1, (64, 4096), F32))
+    add("sum_bf16_dim-1", "a6", "reduce_rows_kernel", nr * 2 + 64 * 4096 * 2, nr, reducer("sum", rb, -1, (64, 4096), BF16))
+    add("sum_f32_dim0", "a7", "reduce_cols_kernel", nr * 4 + 4096 * 1024 * 4, nr, reducer("sum", rf, 0, (4096, 1024), F32))
+    add("amax_bf16_dim0", "a7", "reduce_cols_kernel", nr * 2 + 4096 * 1024 * 2, nr, reducer("amax", rb, 0, (4096, 1024), BF16))
+    add("sum_f32_dims(0,2)", "a8", "reduce_rows_kernel", nr * 4 + 4096 * 4, nr, reducer("sum", rf, (0, 2), (4096,), F32))
+    add("sum_f32_all", "a9", "reduce_rows_kernel", nr * 4 + 4, nr, reducer("sum", rf, None, (), F32))
+    add("sum_i64_all", "a9", "reduce_rows_kernel", nr * 8 + 8, nr, reducer("sum", ri, None, (), I64))
+    add("prod_f32_all", "a9", "reduce_rows_kernel", nr * 4 + 4, nr, reducer("prod", rf, None, (), F32))
+
+    # ---- workload 4: softmax [32768,4096], cumsum [4096,65536]
+    S = (32768, 4096)
+    ns = S[0] * S[1]
+    sf = randn(S, std=4.0)
+    sf[torch.rand(S, device=dev, generator=g) < 0.001] = float("-inf")
+    sb = sf.to(BF16)
+    osf, osb = torch.empty(S, device=dev), torch.empty(S, device=dev, dtype=BF16)
+    add("softmax_f32", "a10", "softmax_wave_kernel", ns * 8, ns, lambda: B.tx_softmax(osf, sf, -1, False))
+    add("log_softmax_bf16", "a10", "softmax_wave_kernel", ns * 4, ns, lambda: B.tx_softmax(osb, sb, -1, True))
+    C = (4096, 65536)
+    nc = C[0] * C[1]
+    cf, ci = randn(C), randint(C, -100, 100)
+    ocf, oci = torch.empty(C, device=dev), torch.empty(C, device=dev, dtype=I64)
+    wsf = B.workspace(B.tx_cumsum_workspace_bytes(ocf, cf, -1))
+    wsi = B.workspace(B.tx_cumsum_workspace_bytes(oci, ci, -1))
+    add("cumsum_f32", "a11", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_cumsum(ocf, cf, -1, wsf))
+    add("cumsum_i64", "a11", "cumsum_lookback_kernel", nc * 16, nc, lambda: B.tx_cumsum(oci, ci, -1, wsi))
+
+    # ---- workload 5: indexing on src[1048576,256]
+    NS, W, ND = 1048576, 256, 65536
+    src = rf.view(-1)[: NS * W].view(NS, W)           # 1 GiB of N(0,1): reuse the reduction input
+    nidx = 4194304
+    idx = torch.randint(0, NS, (nidx,), device=dev, dtype=I64, generator=g)
+    osel = torch.empty((nidx, W), device=dev)
+    add("index_select_f32", "a12", "index_select_rows_kernel", nidx * (8 + 2 * W * 4), nidx * W,
+        lambda: B.tx_index_select(osel, src, 0, idx))
+    gidx = torch.randint(0, NS, (16384, W), device=dev, dtype=I64, generator=g)
+    ogat = torch.empty((16384, W), device=dev)
+    add("gather_f32", "a13", "gather_kernel", 16384 * W * 16, 16384 * W, lambda: B.tx_gather(ogat, src, 0, gidx))
+    from paper_2512_10977_amd import inputs as I
+    rows = I.zipf_rows(NS, ND, 1.1, seed=4).to(dev)
+    eidx = rows.unsqueeze(1).expand(NS, W)
+    src_i = ri.view(-1)[: NS * W].view(NS, W).to(I32)
+    dst_i = torch.zeros((ND, W), device=dev, dtype=I32)
+    add("scatter_add_i32_atomic", "a14", "scatter_add_atomic_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
+        lambda: B.tx_scatter_add_(dst_i, 0, eidx, src_i, True, None))
+    dst_f = torch.zeros((ND, W), device=dev)
+    wss = B.workspace(B.tx_scatter_add_workspace_bytes(dst_f, 0, eidx, src, True))
+    add("scatter_add_f32_sorted", "a15", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
+        lambda: B.tx_scatter_add_(dst_f, 0, eidx, src, True, wss))
+    mask = torch.rand((NS, W), device=dev, generator=g) < 0.3
+    omf = osel[:NS]
+    add("masked_fill_f32", "a16", "ew_vec_kernel", NS * W * 9, NS * W, lambda: B.tx_masked_fill(omf, src, mask, -1.0))
+    return ops
+
+
+def cpu_baseline(torch):
+    """The oracle on a bounded sample of the same step (same op classes, 1/8 .. 1/64 of each workload)."""
+    from oracle import oracle as O
+    from paper_2512_10977_amd import inputs as I
+    F32, I64 = torch.float32, torch.int64
+    items = []
+    a, b = I.broadcast_add_inputs(4096, 4096, 0)
+    items.append((4096 * 4096 * 4, lambda: O.binary("add", a, b)))
+    x = I.typed((1024, 8192), F32, seed=1)
+    y = I.typed((1024, 8192), F32, seed=2)
+    n = x.numel()
+    items.append((n * 8, lambda: O.unary("exp", x)))
+    items.append((n * 12, lambda: O.binary("add", x, y)))
+    y2 = y.reshape(8192, 1024)
+    items.append((n * 12, lambda: O.binary("add", x.t(), y2)))          # transposed input, contiguous output
+    r = I.reduction_input((8, 4096, 1024), F32, seed=2)
+    items.append((r.numel() * 4, lambda: O.reduce("sum", r, -1)))
+    items.append((r.numel() * 4, lambda: O.reduce("sum", r, 0)))
+    s = I.softmax_logits((2048, 4096), F32, seed=3)
+    items.append((s.numel() * 8, lambda: O.softmax(s)))
+    c = I.cumsum_input((256, 65536), F32, seed=3)
+    items.append((c.numel() * 8, lambda: O.cumsum(c)))
+    src = r.view(-1, 256)[:65536]
+    idx = I.uniform_indices(262144, 65536, seed=4)
+    items.append((262144 * (8 + 2048), lambda: O.index_select(src, 0, idx)))
+    rows = I.zipf_rows(65536, 4096, 1.1, seed=4)
+    dst = torch.zeros((4096, 256))
+    items.append((65536 * (1024 + 8) + 2 * 4096 * 1024, lambda: O.scatter_add_(dst, 0, rows.unsqueeze(1).expand(65536, 256), src)))
+    m = I.bernoulli_mask((65536, 256), 0.3, seed=4)
+    items.append((65536 * 256 * 9, lambda: O.masked_fill(src, m, -1.0)))
+    total_bytes = 0
+    t0 = time.perf_counter()
+    for nbytes, fn in items:
+        fn()
+        total_bytes += nbytes
+    dt = time.perf_counter() - t0
+    return {"value": total_bytes / dt / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": "one pass of the CPU oracle over 11 operators of the step at 1/8-1/64 of the workload sizes "
+                      "(broadcast add full size; exp/add on [1024,8192]; sums on [8,4096,1024]; softmax [2048,4096]; "
+                      "cumsum [256,65536]; index_select 262144 rows; scatter_add 65536 rows; masked_fill [65536,256])"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X: every operator here runs on a single GPU; --gpus %d is not supported "
+              "(see DESIGN.md for how the path would shard)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_10977_amd import binding as B
+    B.lib()
+    torch.cuda.set_device(0)
+    ops = build_ops(torch, B)
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        for op in ops:
+            op["fn"]()
+    torch.cuda.synchronize()
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
+              for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for j, op in enumerate(ops):
+            e0, e1 = events[k][j]
+            e0.record()
+            op["fn"]()
+            e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    step_bytes = sum(op["bytes"] for op in ops)
+    step_elems = sum(op["elems"] for op in ops)
+    per_op = []
+    for j, op in enumerate(ops):
+        ms = sum(events[k][j][0].elapsed_time(events[k][j][1]) for k in range(args.steps)) / args.steps
+        gbps = op["bytes"] / (ms * 1e-3) / 1e9
+        per_op.append({"op": op["name"], "row": op["row"], "kernel": op["kernel"], "us": round(ms * 1e3, 2),
+                       "GB/s": round(gbps, 1), "frac_of_peak": round(gbps / PEAK_GBPS, 4),
+                       "Gelem/s": round(op["elems"] / (ms * 1e-3) / 1e9, 2), "bytes": op["bytes"]})
+    dom = max(per_op, key=lambda r: r["us"])
+    ms_step = wall / args.steps * 1e3
+    value = step_bytes / (wall / args.steps) / 1e9
+    result = {
+        "metric": "achieved HBM GB/s (algorithmic bytes / time) over one pass of all operator classes on one GPU",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "all five operator workloads at full size: broadcast add [4096,1]+[1,4096]; elementwise "
+                               "sweep [8192,8192]; reductions x[64,4096,1024]; softmax [32768,4096] + cumsum "
+                               "[4096,65536]; indexing on src[1048576,256]", "ops_per_step": len(ops)},
+        "frac_of_peak": round(value / PEAK_GBPS, 4),
+        "elements_per_s": round(step_elems / (wall / args.steps), 1),
+        "roofline": {"bound": "hbm", "kernel": dom["kernel"], "op": dom["op"], "achieved": dom["GB/s"],
+                     "peak": PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_of_peak"], "traffic": None,
+                     "avg_us": dom["us"]},
+        "per_op": per_op,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(torch)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

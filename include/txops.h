@@ -160,7 +160,7 @@ tx_status tx_softmax(const tx_tensor* out, const tx_tensor* x, int64_t dim, int 
  * accumulated in fp32.  ws / ws_bytes: device scratch of at least
  * tx_cumsum_workspace_bytes() (tile status words for the single-pass scan). */
 tx_status tx_cumsum(const tx_tensor* out, const tx_tensor* x, int64_t dim, void* ws, size_t ws_bytes, void* stream);
-size_t tx_cumsum_workspace_bytes(const tx_tensor* x, int64_t dim);
+size_t tx_cumsum_workspace_bytes(const tx_tensor* out, const tx_tensor* x, int64_t dim);
 
 /* ------------------------------------------------------------------ indexing
  * (Table 1 "Indexing & Selection".)  Index tensors are int64 or int32 and are
@@ -184,9 +184,11 @@ tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t di
  * src.dtype.  index may be a stride-0 expanded view.  Integer dtypes use
  * device atomics (exact, order-free); bool ORs.  Float dtypes: with
  * deterministic != 0 the contributions are sorted by destination and summed in
- * a fixed order (bitwise reproducible run to run); with deterministic == 0
- * float atomics are used.  ws / ws_bytes: device scratch of at least
- * tx_scatter_add_workspace_bytes() (needed by the deterministic path only). */
+ * a fixed order with fp32 accumulation (bitwise reproducible run to run); with
+ * deterministic == 0, fp32 uses float atomics (fp16 / bf16 keep the sorted
+ * path: 16-bit atomics would round every partial sum).  ws / ws_bytes: device
+ * scratch of at least tx_scatter_add_workspace_bytes() for the same arguments
+ * (0 for the atomic paths). */
 tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
                           int deterministic, void* ws, size_t ws_bytes, void* stream);
 size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index,

@@ -71,7 +71,7 @@ def lib():
         "tx_reduce_workspace_bytes": ([ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int], ctypes.c_size_t),
         "tx_softmax": ([P, P, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_cumsum": ([P, P, ctypes.c_int64, V, ctypes.c_size_t, V], ctypes.c_int32),
-        "tx_cumsum_workspace_bytes": ([P, ctypes.c_int64], ctypes.c_size_t),
+        "tx_cumsum_workspace_bytes": ([P, P, ctypes.c_int64], ctypes.c_size_t),
         "tx_gather": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
         "tx_index_select": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
         "tx_scatter_add_": ([P, ctypes.c_int64, P, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
@@ -86,9 +86,7 @@ def lib():
         "tx_last_error": ([], ctypes.c_char_p),
     }
     for name, (args, res) in sig.items():
-        if not hasattr(L, name):  # TEMP until every entry point is built
-            continue
-        fn = getattr(L, name)
+        fn = getattr(L, name)   # raises if the library does not export an entry point
         fn.argtypes = args
         fn.restype = res
     _lib = L
@@ -109,6 +107,10 @@ def desc(t):
 
 def current_stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _stream(stream):
+    return current_stream() if stream is None else stream
 
 
 def _check(status):
@@ -141,32 +143,32 @@ def _ws(ws):
 
 # --------------------------------------------------------------------------- entry points (same names as the C ABI)
 def tx_unary(op, out, a, stream=None):
-    _check(lib().tx_unary(UNARY[op], desc(out), desc(a), stream or current_stream()))
+    _check(lib().tx_unary(UNARY[op], desc(out), desc(a), _stream(stream)))
 
 
 def tx_add(out, a, b, alpha=1, stream=None):
     af, ai, isint = _scalar(alpha)
-    _check(lib().tx_add(desc(out), desc(a), desc(b), af, ai, isint, stream or current_stream()))
+    _check(lib().tx_add(desc(out), desc(a), desc(b), af, ai, isint, _stream(stream)))
 
 
 def tx_binary(op, out, a, b, stream=None):
-    _check(lib().tx_binary(BINARY[op], desc(out), desc(a), desc(b), stream or current_stream()))
+    _check(lib().tx_binary(BINARY[op], desc(out), desc(a), desc(b), _stream(stream)))
 
 
 def tx_where(out, cond, x, y, stream=None):
-    _check(lib().tx_where(desc(out), desc(cond), desc(x), desc(y), stream or current_stream()))
+    _check(lib().tx_where(desc(out), desc(cond), desc(x), desc(y), _stream(stream)))
 
 
 def tx_masked_fill(out, self, mask, value, stream=None):
     vf, vi, isint = _scalar(value)
-    _check(lib().tx_masked_fill(desc(out), desc(self), desc(mask), vf, vi, isint, stream or current_stream()))
+    _check(lib().tx_masked_fill(desc(out), desc(self), desc(mask), vf, vi, isint, _stream(stream)))
 
 
 def tx_reduce(op, out, x, dims=None, keepdim=False, correction=1.0, ws=None, stream=None):
     arr, n = _dims(dims)
     wp, wb = _ws(ws)
     _check(lib().tx_reduce(REDUCE[op], desc(out), desc(x), arr, n, int(keepdim), float(correction), wp, wb,
-                           stream or current_stream()))
+                           _stream(stream)))
 
 
 def tx_reduce_workspace_bytes(op, out, x, dims=None, keepdim=False):
@@ -175,30 +177,30 @@ def tx_reduce_workspace_bytes(op, out, x, dims=None, keepdim=False):
 
 
 def tx_softmax(out, x, dim=-1, log=False, stream=None):
-    _check(lib().tx_softmax(desc(out), desc(x), dim, int(log), stream or current_stream()))
+    _check(lib().tx_softmax(desc(out), desc(x), dim, int(log), _stream(stream)))
 
 
 def tx_cumsum(out, x, dim=-1, ws=None, stream=None):
     wp, wb = _ws(ws)
-    _check(lib().tx_cumsum(desc(out), desc(x), dim, wp, wb, stream or current_stream()))
+    _check(lib().tx_cumsum(desc(out), desc(x), dim, wp, wb, _stream(stream)))
 
 
-def tx_cumsum_workspace_bytes(x, dim=-1):
-    return lib().tx_cumsum_workspace_bytes(desc(x), dim)
+def tx_cumsum_workspace_bytes(out, x, dim=-1):
+    return lib().tx_cumsum_workspace_bytes(desc(out), desc(x), dim)
 
 
 def tx_gather(out, src, dim, index, stream=None):
-    _check(lib().tx_gather(desc(out), desc(src), dim, desc(index), stream or current_stream()))
+    _check(lib().tx_gather(desc(out), desc(src), dim, desc(index), _stream(stream)))
 
 
 def tx_index_select(out, src, dim, index, stream=None):
-    _check(lib().tx_index_select(desc(out), desc(src), dim, desc(index), stream or current_stream()))
+    _check(lib().tx_index_select(desc(out), desc(src), dim, desc(index), _stream(stream)))
 
 
 def tx_scatter_add_(self, dim, index, src, deterministic=True, ws=None, stream=None):
     wp, wb = _ws(ws)
     _check(lib().tx_scatter_add_(desc(self), dim, desc(index), desc(src), int(deterministic), wp, wb,
-                                 stream or current_stream()))
+                                 _stream(stream)))
 
 
 def tx_scatter_add_workspace_bytes(self, dim, index, src, deterministic=True):

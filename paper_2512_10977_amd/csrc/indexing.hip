@@ -1,0 +1,863 @@
+// Indexing operators: gather, index_select, scatter_add_.
+//
+//   index_select : when the slice below `dim` is one contiguous, 16-byte
+//                  granular run in both src and out, a wave copies whole
+//                  slices with 16-byte lanes (several slices in flight per
+//                  wave); otherwise one lane per output element.
+//   gather       : one lane per output element (index reads are coalesced,
+//                  the src reads are data-dependent).
+//   scatter_add_ : integer / bool dtypes use device atomics (order-free, so
+//                  exact).  Floating dtypes, deterministic: the (destination,
+//                  position) pairs are radix-sorted by destination (stable,
+//                  so positions stay ascending), then summed per destination
+//                  in a fixed order.  When the index is a row id broadcast
+//                  over the trailing dims ("row mode": whole rows of src go
+//                  to rows of self) the sort runs over rows only and a wave
+//                  sums a chunk of sorted rows with 16-byte lanes; long runs
+//                  are cut at fixed chunk boundaries and their partial rows
+//                  combined in chunk order, so the association order depends
+//                  on the data alone.
+#include <algorithm>
+#include <cstring>
+
+#include "common.h"
+
+namespace tx {
+namespace {
+
+constexpr int kBlock = 256;
+
+struct Dims {
+  int n;
+  FastDiv div[TX_MAX_DIMS];
+  int64_t numel;
+};
+
+__device__ __forceinline__ int64_t load_index(const char* p, int64_t off, int is64) {
+  return is64 ? ((const int64_t*)p)[off] : (int64_t)((const int32_t*)p)[off];
+}
+
+// ---------------------------------------------------------------------------
+// gather / generic index_select / atomic scatter_add share one addressing
+// scheme: iterate a shape (the index's, or out's), compute up to three
+// strided offsets, and replace coordinate `dim` for one operand by the index.
+// ---------------------------------------------------------------------------
+struct ElemArgs {
+  Dims shape;
+  int dim;
+  int index_is64;
+  const char* index;
+  const char* src;
+  char* dst;
+  int64_t istride[TX_MAX_DIMS];    // index strides (index_select: only [dim] is used)
+  int64_t sstride[TX_MAX_DIMS];    // source strides
+  int64_t dstride[TX_MAX_DIMS];    // destination strides
+};
+
+template <class B>
+__global__ __launch_bounds__(kBlock) void gather_kernel(const ElemArgs a, int index_1d) {
+  const int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lin >= a.shape.numel) return;
+  int64_t io = 0, so = 0, d_o = 0, dimcoord = 0;
+  uint32_t rem = (uint32_t)lin;
+  for (int d = a.shape.n - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.shape.div[d].divmod(rem, q, m);
+    rem = q;
+    d_o += (int64_t)m * a.dstride[d];
+    if (d == a.dim) dimcoord = m;
+    else so += (int64_t)m * a.sstride[d];
+    if (!index_1d) io += (int64_t)m * a.istride[d];
+  }
+  if (index_1d) io = dimcoord * a.istride[a.dim];
+  const int64_t k = load_index(a.index, io, a.index_is64);
+  so += k * a.sstride[a.dim];
+  ((B*)a.dst)[d_o] = ((const B*)a.src)[so];
+}
+
+// index_select fast path: slice r = (outer o, picked j) is `vecs` 16-byte vectors
+struct RowCopyArgs {
+  const char* index;
+  const char* src;
+  char* dst;
+  int index_is64;
+  int64_t istride;
+  int64_t nsel;               // number of indices
+  FastDiv nsel_div;
+  int64_t rows;               // outer * nsel
+  int64_t src_outer, dst_outer;   // byte strides of the outer dim
+  int64_t src_dim, dst_dim;       // byte strides of `dim`
+  int64_t vecs;               // 16-byte vectors per slice
+};
+
+constexpr int kRowsPerWave = 4;
+
+__global__ __launch_bounds__(kBlock) void index_select_rows_kernel(const RowCopyArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+  const int64_t r0 = wave * kRowsPerWave;
+  const char* sp[kRowsPerWave];
+  char* dp[kRowsPerWave];
+#pragma unroll
+  for (int i = 0; i < kRowsPerWave; ++i) {
+    const int64_t r = r0 + i;
+    sp[i] = nullptr;
+    dp[i] = nullptr;
+    if (r < a.rows) {
+      uint32_t o, j;
+      a.nsel_div.divmod((uint32_t)r, o, j);
+      const int64_t k = load_index(a.index, (int64_t)j * a.istride, a.index_is64);
+      sp[i] = a.src + (int64_t)o * a.src_outer + k * a.src_dim;
+      dp[i] = a.dst + (int64_t)o * a.dst_outer + (int64_t)j * a.dst_dim;
+    }
+  }
+  using V16 = Vec<uint32_t, 4>;
+  for (int64_t v = lane; v < a.vecs; v += kWave) {
+    V16 t[kRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i)
+      if (sp[i]) t[i] = ((const V16*)sp[i])[v];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i)
+      if (dp[i]) ((V16*)dp[i])[v] = t[i];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// scatter_add with atomics
+// ---------------------------------------------------------------------------
+template <class T> __device__ __forceinline__ void atomic_accumulate(T* p, T v);
+template <> __device__ __forceinline__ void atomic_accumulate<int32_t>(int32_t* p, int32_t v) { atomicAdd(p, v); }
+template <> __device__ __forceinline__ void atomic_accumulate<int64_t>(int64_t* p, int64_t v) {
+  atomicAdd((unsigned long long*)p, (unsigned long long)v);
+}
+template <> __device__ __forceinline__ void atomic_accumulate<float>(float* p, float v) { atomicAdd(p, v); }
+template <> __device__ __forceinline__ void atomic_accumulate<uint8_t>(uint8_t* p, uint8_t v) {
+  if (!v) return;
+  const uintptr_t addr = (uintptr_t)p;
+  unsigned int* word = (unsigned int*)(addr & ~(uintptr_t)3);
+  atomicOr(word, 1u << (8 * (addr & 3)));
+}
+template <class T>
+__global__ __launch_bounds__(kBlock) void scatter_add_atomic_kernel(const ElemArgs a) {
+  const int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lin >= a.shape.numel) return;
+  int64_t io = 0, so = 0, d_o = 0;
+  uint32_t rem = (uint32_t)lin;
+  for (int d = a.shape.n - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.shape.div[d].divmod(rem, q, m);
+    rem = q;
+    io += (int64_t)m * a.istride[d];
+    so += (int64_t)m * a.sstride[d];
+    if (d != a.dim) d_o += (int64_t)m * a.dstride[d];
+  }
+  const int64_t k = load_index(a.index, io, a.index_is64);
+  d_o += k * a.dstride[a.dim];
+  atomic_accumulate<T>((T*)a.dst + d_o, ((const T*)a.src)[so]);
+}
+
+// ---------------------------------------------------------------------------
+// stable LSD radix sort of (key, value) pairs, 8 bits per pass
+// ---------------------------------------------------------------------------
+constexpr int kSortItems = 8;
+constexpr int kSortTile = kBlock * kSortItems;          // 2048 entries per workgroup
+constexpr int kWaves = kBlock / kWave;
+
+// keys for the element mode: destination element offset of every index position
+__global__ __launch_bounds__(kBlock) void scatter_keys_kernel(const ElemArgs a, uint32_t* keys, uint32_t* vals) {
+  const int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lin >= a.shape.numel) return;
+  int64_t io = 0, d_o = 0;
+  uint32_t rem = (uint32_t)lin;
+  for (int d = a.shape.n - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.shape.div[d].divmod(rem, q, m);
+    rem = q;
+    io += (int64_t)m * a.istride[d];
+    if (d != a.dim) d_o += (int64_t)m * a.dstride[d];
+  }
+  d_o += load_index(a.index, io, a.index_is64) * a.dstride[a.dim];
+  keys[lin] = (uint32_t)d_o;
+  vals[lin] = (uint32_t)lin;
+}
+// keys for the row mode: the row id of every source row
+__global__ __launch_bounds__(kBlock) void row_keys_kernel(const char* index, int is64, int64_t istride, int64_t n,
+                                                          uint32_t* keys, uint32_t* vals) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i >= n) return;
+  keys[i] = (uint32_t)load_index(index, i * istride, is64);
+  vals[i] = (uint32_t)i;
+}
+
+__global__ __launch_bounds__(kBlock) void sort_hist_kernel(const uint32_t* keys, int64_t n, int shift, uint32_t* hist,
+                                                           int nblocks) {
+  __shared__ unsigned int h[256];
+  h[threadIdx.x] = 0;
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+  for (int k = 0; k < kSortItems; ++k) {
+    const int64_t i = base + k * kBlock + threadIdx.x;
+    if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255u], 1u);
+  }
+  __syncthreads();
+  hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+}
+
+// one workgroup per digit: exclusive scan of that digit's per-block counts, plus the digit total
+__global__ __launch_bounds__(kBlock) void sort_rowscan_kernel(uint32_t* hist, int nblocks, uint32_t* totals) {
+  __shared__ unsigned int wsum[kWaves];
+  __shared__ unsigned int carry;
+  uint32_t* row = hist + (int64_t)blockIdx.x * nblocks;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < nblocks; base += kBlock) {
+    const int i = base + threadIdx.x;
+    const unsigned int v = i < nblocks ? row[i] : 0u;
+    unsigned int incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      unsigned int o = __shfl_up(incl, d, kWave);
+      if (lane >= d) incl += o;
+    }
+    if (lane == kWave - 1) wsum[w] = incl;
+    __syncthreads();
+    unsigned int before = carry;
+    for (int ww = 0; ww < w; ++ww) before += wsum[ww];
+    if (i < nblocks) row[i] = before + incl - v;
+    __syncthreads();
+    if (threadIdx.x == kBlock - 1) carry = before + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) totals[blockIdx.x] = carry;
+}
+
+__global__ __launch_bounds__(kBlock) void sort_scatter_kernel(const uint32_t* keys_in, const uint32_t* vals_in,
+                                                              uint32_t* keys_out, uint32_t* vals_out, int64_t n, int shift,
+                                                              const uint32_t* hist, const uint32_t* totals, int nblocks) {
+  __shared__ unsigned int digit_base[256];
+  __shared__ unsigned int cnt[kWaves][256];
+  __shared__ unsigned int wsum[kWaves];
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  {  // exclusive scan of the 256 digit totals
+    const unsigned int v = totals[threadIdx.x];
+    unsigned int incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      unsigned int o = __shfl_up(incl, d, kWave);
+      if (lane >= d) incl += o;
+    }
+    if (lane == kWave - 1) wsum[w] = incl;
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) cnt[ww][threadIdx.x] = 0;
+    __syncthreads();
+    unsigned int before = 0;
+    for (int ww = 0; ww < w; ++ww) before += wsum[ww];
+    digit_base[threadIdx.x] = before + incl - v;
+  }
+  __syncthreads();
+  // wave w owns entries [base + w*512, +512) as 8 runs of 64, taken in order
+  const int64_t base = (int64_t)blockIdx.x * kSortTile + (int64_t)w * (kWave * kSortItems);
+  uint32_t key[kSortItems], val[kSortItems], off[kSortItems];
+  const unsigned long long lt = (1ull << lane) - 1ull;
+#pragma unroll
+  for (int s = 0; s < kSortItems; ++s) {
+    const int64_t i = base + s * kWave + lane;
+    const bool valid = i < n;
+    key[s] = valid ? keys_in[i] : 0u;
+    val[s] = valid ? vals_in[i] : 0u;
+    const uint32_t dg = (key[s] >> shift) & 255u;
+    unsigned long long peers = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const unsigned long long bal = __ballot((dg >> b) & 1u);
+      peers &= ((dg >> b) & 1u) ? bal : ~bal;
+    }
+    const unsigned int rank = __popcll(peers & lt);
+    unsigned int old = 0;
+    if (valid) old = cnt[w][dg];
+    __builtin_amdgcn_wave_barrier();
+    if (valid && rank == 0) cnt[w][dg] = old + __popcll(peers);
+    __builtin_amdgcn_wave_barrier();
+    off[s] = old + rank;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < kSortItems; ++s) {
+    const int64_t i = base + s * kWave + lane;
+    if (i < n) {
+      const uint32_t dg = (key[s] >> shift) & 255u;
+      unsigned int pos = digit_base[dg] + hist[(int64_t)dg * nblocks + blockIdx.x] + off[s];
+      for (int ww = 0; ww < w; ++ww) pos += cnt[ww][dg];
+      keys_out[pos] = key[s];
+      vals_out[pos] = val[s];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// deterministic segmented sums
+// ---------------------------------------------------------------------------
+// element mode: the first entry of each run of equal keys sums the run in order (binary64 accumulator)
+template <class T>
+__global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
+                                                          const ElemArgs a) {
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= n) return;
+  const uint32_t k = keys[j];
+  if (j > 0 && keys[j - 1] == k) return;
+  double acc = 0.0;
+  for (int64_t e = j; e < n && keys[e] == k; ++e) {
+    // source offset of index position vals[e]
+    int64_t so = 0;
+    uint32_t rem = vals[e];
+    for (int d = a.shape.n - 1; d >= 0; --d) {
+      uint32_t q, m;
+      a.shape.div[d].divmod(rem, q, m);
+      rem = q;
+      so += (int64_t)m * a.sstride[d];
+    }
+    acc += cvt<double>(((const T*)a.src)[so]);
+  }
+  T* dst = (T*)a.dst + k;
+  *dst = cvt<T>((float)(cvt<double>(*dst) + acc));
+}
+
+constexpr int kChunk = 128;                 // sorted rows per wave
+constexpr int kCombineWaves = 16;
+enum { kNone = 0, kEnd = 1, kThrough = 2 };
+
+struct SegRowArgs {
+  const uint32_t* keys;
+  const uint32_t* vals;
+  int64_t n, nchunks;
+  const char* src;
+  char* self;
+  int64_t src_row, self_row;     // element strides between rows
+  int64_t width;                 // elements per row
+  float* part_a;                 // [nchunks][width] piece that continues from the previous chunk
+  float* part_b;                 // [nchunks][width] piece that continues into the next chunk
+  uint8_t* flag_a;               // kNone / kEnd / kThrough
+  uint8_t* flag_b;               // 0 / 1
+  uint32_t* key_b;
+};
+
+template <class T, int VEC>
+__device__ __forceinline__ void seg_flush(const SegRowArgs& a, int64_t chunk, uint32_t key, const float (&acc)[VEC],
+                                          int64_t col, bool active, bool from_before, bool to_after) {
+  if (!active) return;
+  if (!from_before && !to_after) {
+    T* d = (T*)a.self + (int64_t)key * a.self_row + col;
+    Vec<T, VEC> t = *(Vec<T, VEC>*)d;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) t.v[e] = cvt<T>(cvt<float>(t.v[e]) + acc[e]);
+    *(Vec<T, VEC>*)d = t;
+  } else {
+    float* p = (from_before ? a.part_a : a.part_b) + chunk * a.width + col;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) p[e] = acc[e];
+  }
+}
+
+template <class T, int VEC>
+__global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t chunk = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (chunk >= a.nchunks) return;
+  const int64_t j0 = chunk * kChunk;
+  const int cnt = (int)std::min<int64_t>(kChunk, a.n - j0);
+  const uint32_t first_key = a.keys[j0], last_key = a.keys[j0 + cnt - 1];
+  const bool from_before = j0 > 0 && a.keys[j0 - 1] == first_key;
+  const bool to_after = j0 + cnt < a.n && a.keys[j0 + cnt] == last_key;
+  const T* src = (const T*)a.src;
+  constexpr int kBatch = 8;
+  for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
+    const int64_t col = cb + (int64_t)lane * VEC;
+    const bool active = col < a.width;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+    uint32_t cur = first_key;
+    bool first_piece = true;
+    for (int e0 = 0; e0 < cnt; e0 += kBatch) {
+      uint32_t k[kBatch];
+      Vec<T, VEC> row[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int e = e0 + b;
+        if (e < cnt) {
+          k[b] = a.keys[j0 + e];
+          const uint32_t p = a.vals[j0 + e];
+          if (active) row[b] = *(const Vec<T, VEC>*)(src + (int64_t)p * a.src_row + col);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int e = e0 + b;
+        if (e < cnt) {
+          if (k[b] != cur) {
+            seg_flush<T, VEC>(a, chunk, cur, acc, col, active, first_piece && from_before, false);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
+            cur = k[b];
+            first_piece = false;
+          }
+          if (active) {
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] += cvt<float>(row[b].v[q]);
+          }
+        }
+      }
+    }
+    seg_flush<T, VEC>(a, chunk, cur, acc, col, active, first_piece && from_before, to_after);
+  }
+  if (lane == 0) {
+    // first piece continues from before: END if it stops inside this chunk, THROUGH if the whole chunk is one run that goes on
+    const bool single = first_key == last_key;
+    a.flag_a[chunk] = from_before ? ((single && to_after) ? kThrough : kEnd) : kNone;
+    const bool start = to_after && !(single && from_before);
+    a.flag_b[chunk] = start ? 1 : 0;
+    a.key_b[chunk] = last_key;
+  }
+}
+
+// one workgroup per chunk that STARTS a run continuing into later chunks: adds, in chunk order,
+// the start piece and the continuation pieces of the following chunks, then updates self once
+template <class T, int VEC>
+__global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(const SegRowArgs a) {
+  __shared__ long long end_chunk;
+  __shared__ float sub[kCombineWaves][kWave * VEC];
+  const int64_t c = blockIdx.x;
+  if (!a.flag_b[c]) return;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  if (threadIdx.x == 0) end_chunk = a.nchunks - 1;
+  __syncthreads();
+  // first chunk after c whose continuation piece is not THROUGH
+  for (int64_t base = c + 1; base < a.nchunks; base += kCombineWaves * kWave) {
+    const int64_t i = base + threadIdx.x;
+    const bool stop = i < a.nchunks && a.flag_a[i] != kThrough;
+    const bool any = __syncthreads_or(stop);
+    if (stop) atomicMin((unsigned long long*)&end_chunk, (unsigned long long)i);
+    if (any) break;
+  }
+  __syncthreads();
+  const int64_t cend = end_chunk;
+  const int64_t nparts = cend - c;                       // continuation pieces c+1 .. cend
+  const int64_t per = (nparts + kCombineWaves - 1) / kCombineWaves;
+  const int64_t p0 = c + 1 + (int64_t)w * per;
+  const int64_t p1 = std::min<int64_t>(p0 + per, cend + 1);
+  const uint32_t key = a.key_b[c];
+  for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
+    const int64_t col = cb + (int64_t)lane * VEC;
+    const bool active = col < a.width;
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+    if (active) {
+#pragma unroll 8
+      for (int64_t p = p0; p < p1; ++p) {
+        const float* src = a.part_a + p * a.width + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += src[e];
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) sub[w][lane * VEC + e] = acc[e];
+    __syncthreads();
+    if (w == 0 && active) {
+      const float* b = a.part_b + c * a.width + col;
+      T* d = (T*)a.self + (int64_t)key * a.self_row + col;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        float t = b[e];
+        for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
+        d[e] = cvt<T>(cvt<float>(d[e]) + t);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------
+// host helpers
+// ---------------------------------------------------------------------------
+void fill_dims(Dims* d, int nd, const int64_t* sizes) {
+  d->n = nd;
+  d->numel = 1;
+  for (int i = 0; i < nd; ++i) {
+    d->div[i] = FastDiv((uint32_t)std::min<int64_t>(sizes[i], 0x7fffffff));
+    d->numel *= sizes[i];
+  }
+}
+bool index_dtype_ok(int dt) { return dt == TX_I32 || dt == TX_I64; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+int bits_for(uint64_t max_value) {
+  int b = 1;
+  while (b < 64 && (max_value >> b)) ++b;
+  return b;
+}
+
+struct ScatterPlan {
+  bool row_mode;
+  int64_t n;            // sorted entries
+  int64_t width;        // row mode: elements per row
+  int passes;
+  int nblocks;          // sort workgroups
+  int64_t nchunks;
+  size_t off_keys[2], off_vals[2], off_hist, off_totals, off_part_a, off_part_b, off_flag_a, off_flag_b, off_key_b;
+  size_t bytes;
+};
+
+// row mode: dim 0; index is a row id broadcast over the trailing dims; the trailing dims of
+// index, src and self agree and are laid out contiguously in src and self
+bool is_row_mode(const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src) {
+  if (dim != 0 || self->ndim < 2) return false;
+  int64_t inner = 1;
+  for (int d = self->ndim - 1; d >= 1; --d) {
+    if (index->sizes[d] != self->sizes[d] || index->sizes[d] != src->sizes[d]) return false;
+    if (index->sizes[d] > 1 && index->strides[d] != 0) return false;
+    if (self->sizes[d] > 1 && (self->strides[d] != inner || src->strides[d] != inner)) return false;
+    inner *= self->sizes[d];
+  }
+  return inner >= 16 && index->sizes[0] < (1ll << 31) && self->sizes[0] < (1ll << 32);
+}
+
+tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src, ScatterPlan* p) {
+  memset(p, 0, sizeof(*p));
+  p->row_mode = is_row_mode(self, dim, index, src);
+  uint64_t max_key;
+  if (p->row_mode) {
+    p->n = index->sizes[0];
+    p->width = 1;
+    for (int d = 1; d < self->ndim; ++d) p->width *= self->sizes[d];
+    max_key = (uint64_t)std::max<int64_t>(self->sizes[0], 1) - 1;
+  } else {
+    p->n = numel(index);
+    uintptr_t lo, hi;
+    byte_extent(self, &lo, &hi);
+    const uint64_t extent = (hi - lo) / dtype_size(self->dtype);
+    if (p->n >= (1ll << 32) || extent >= (1ull << 32))
+      return fail(TX_ERR_UNSUPPORTED, "deterministic scatter_add: more than 2^32 positions or destination elements");
+    max_key = extent ? extent - 1 : 0;
+  }
+  p->passes = (bits_for(max_key) + 7) / 8;
+  p->nblocks = (int)((p->n + kSortTile - 1) / kSortTile);
+  p->nchunks = p->row_mode ? (p->n + kChunk - 1) / kChunk : 0;
+  size_t o = 0;
+  for (int i = 0; i < 2; ++i) { p->off_keys[i] = o; o = align_up(o + (size_t)p->n * 4, 256); }
+  for (int i = 0; i < 2; ++i) { p->off_vals[i] = o; o = align_up(o + (size_t)p->n * 4, 256); }
+  p->off_hist = o; o = align_up(o + (size_t)256 * p->nblocks * 4, 256);
+  p->off_totals = o; o = align_up(o + 256 * 4, 256);
+  if (p->row_mode) {
+    p->off_part_a = o; o = align_up(o + (size_t)p->nchunks * p->width * 4, 256);
+    p->off_part_b = o; o = align_up(o + (size_t)p->nchunks * p->width * 4, 256);
+    p->off_flag_a = o; o = align_up(o + (size_t)p->nchunks, 256);
+    p->off_flag_b = o; o = align_up(o + (size_t)p->nchunks, 256);
+    p->off_key_b = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
+  }
+  p->bytes = o;
+  return TX_OK;
+}
+
+void fill_scatter_elem_args(ElemArgs* a, const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src) {
+  fill_dims(&a->shape, index->ndim, index->sizes);
+  a->dim = dim;
+  a->index_is64 = index->dtype == TX_I64;
+  a->index = (const char*)index->data;
+  a->src = (const char*)src->data;
+  a->dst = (char*)self->data;
+  for (int d = 0; d < index->ndim; ++d) {
+    a->istride[d] = index->strides[d];
+    a->sstride[d] = src->strides[d];
+    a->dstride[d] = self->strides[d];
+  }
+  if (index->ndim == 0) {   // 0-dim: one element, destination offset index * 0
+    a->shape.n = 0;
+    a->istride[0] = a->sstride[0] = a->dstride[0] = 0;
+  }
+}
+
+tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_buffer) {
+  uint32_t* keys[2] = {(uint32_t*)(ws + p.off_keys[0]), (uint32_t*)(ws + p.off_keys[1])};
+  uint32_t* vals[2] = {(uint32_t*)(ws + p.off_vals[0]), (uint32_t*)(ws + p.off_vals[1])};
+  uint32_t* hist = (uint32_t*)(ws + p.off_hist);
+  uint32_t* totals = (uint32_t*)(ws + p.off_totals);
+  int cur = 0;
+  for (int pass = 0; pass < p.passes; ++pass) {
+    const int shift = 8 * pass;
+    hipLaunchKernelGGL(sort_hist_kernel, dim3(p.nblocks), dim3(kBlock), 0, s, keys[cur], p.n, shift, hist, p.nblocks);
+    hipLaunchKernelGGL(sort_rowscan_kernel, dim3(256), dim3(kBlock), 0, s, hist, p.nblocks, totals);
+    hipLaunchKernelGGL(sort_scatter_kernel, dim3(p.nblocks), dim3(kBlock), 0, s, keys[cur], vals[cur], keys[1 - cur],
+                       vals[1 - cur], p.n, shift, hist, totals, p.nblocks);
+    cur = 1 - cur;
+  }
+  *result_buffer = cur;
+  return check_launch("radix sort");
+}
+
+template <class T>
+tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int dim, const tx_tensor* index,
+                                const tx_tensor* src, char* ws, hipStream_t s) {
+  constexpr int V = 16 / sizeof(T);
+  uint32_t* keys0 = (uint32_t*)(ws + p.off_keys[0]);
+  uint32_t* vals0 = (uint32_t*)(ws + p.off_vals[0]);
+  ElemArgs ea;
+  fill_scatter_elem_args(&ea, self, dim, index, src);
+  const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
+  if (p.row_mode)
+    hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
+                       index->strides[0], p.n, keys0, vals0);
+  else
+    hipLaunchKernelGGL(scatter_keys_kernel, dim3(nb), dim3(kBlock), 0, s, ea, keys0, vals0);
+  int cur;
+  tx_status rc = run_sort(p, ws, s, &cur);
+  if (rc) return rc;
+  const uint32_t* keys = (const uint32_t*)(ws + p.off_keys[cur]);
+  const uint32_t* vals = (const uint32_t*)(ws + p.off_vals[cur]);
+  if (!p.row_mode) {
+    set_path("scatter-sort-elem");
+    hipLaunchKernelGGL((seg_elem_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, vals, p.n, ea);
+    return check_launch("segmented sum");
+  }
+  SegRowArgs a;
+  a.keys = keys;
+  a.vals = vals;
+  a.n = p.n;
+  a.nchunks = p.nchunks;
+  a.src = (const char*)src->data;
+  a.self = (char*)self->data;
+  a.src_row = src->strides[0];
+  a.self_row = self->strides[0];
+  a.width = p.width;
+  a.part_a = (float*)(ws + p.off_part_a);
+  a.part_b = (float*)(ws + p.off_part_b);
+  a.flag_a = (uint8_t*)(ws + p.off_flag_a);
+  a.flag_b = (uint8_t*)(ws + p.off_flag_b);
+  a.key_b = (uint32_t*)(ws + p.off_key_b);
+  const bool al = p.width % V == 0 && (uintptr_t)src->data % 16 == 0 && (uintptr_t)self->data % 16 == 0 &&
+                  (a.src_row * (int64_t)sizeof(T)) % 16 == 0 && (a.self_row * (int64_t)sizeof(T)) % 16 == 0;
+  const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
+  set_path(al ? "scatter-sort-rows" : "scatter-sort-rows-scalar");
+  if (al) {
+    hipLaunchKernelGGL((seg_rows_kernel<T, V>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_combine_kernel<T, V>), dim3((unsigned)p.nchunks), dim3(kCombineWaves * kWave), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((seg_rows_kernel<T, 1>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_combine_kernel<T, 1>), dim3((unsigned)p.nchunks), dim3(kCombineWaves * kWave), 0, s, a);
+  }
+  return check_launch("segmented row sum");
+}
+
+tx_status scatter_checks(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src, int* d) {
+  tx_status rc;
+  if ((rc = check_tensor(self, "self")) || (rc = check_tensor(index, "index")) || (rc = check_tensor(src, "src")))
+    return rc;
+  if (!index_dtype_ok(index->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
+  if (self->dtype != src->dtype) return fail(TX_ERR_DTYPE, "scatter_add_: self and src dtypes differ");
+  if (index->ndim != self->ndim || src->ndim != self->ndim)
+    return fail(TX_ERR_SHAPE, "scatter_add_: self, index and src must have the same rank");
+  if ((rc = wrap_dim(dim, self->ndim, d))) return rc;
+  for (int i = 0; i < self->ndim; ++i) {
+    if (index->sizes[i] > src->sizes[i]) return fail(TX_ERR_SHAPE, "scatter_add_: index larger than src in dim %d", i);
+    if (i != *d && index->sizes[i] > self->sizes[i])
+      return fail(TX_ERR_SHAPE, "scatter_add_: index larger than self in dim %d", i);
+  }
+  if (!no_internal_overlap(self)) return fail(TX_ERR_OVERLAP, "self has overlapping elements");
+  if (partial_overlap(self, src) || partial_overlap(self, index) || (self->data == src->data && numel(src) && numel(self)))
+    return fail(TX_ERR_OVERLAP, "self overlaps src or index");
+  return TX_OK;
+}
+
+}  // namespace
+}  // namespace tx
+
+using namespace tx;
+
+extern "C" {
+
+tx_status tx_gather(const tx_tensor* out, const tx_tensor* src, int64_t dim, const tx_tensor* index, void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(src, "src")) || (rc = check_tensor(index, "index"))) return rc;
+  if (!index_dtype_ok(index->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
+  if (out->dtype != src->dtype) return fail(TX_ERR_DTYPE, "gather: out must have src's dtype");
+  if (index->ndim != src->ndim) return fail(TX_ERR_SHAPE, "gather: index and src must have the same rank");
+  int d;
+  if ((rc = wrap_dim(dim, src->ndim, &d))) return rc;
+  for (int i = 0; i < src->ndim; ++i)
+    if (i != d && index->sizes[i] > src->sizes[i]) return fail(TX_ERR_SHAPE, "gather: index larger than src in dim %d", i);
+  if (!same_sizes(out, index->ndim, index->sizes)) return fail(TX_ERR_SHAPE, "gather: out must have index's shape");
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  if (partial_overlap(out, src) || partial_overlap(out, index) || (out->data == src->data && numel(out) && numel(src)))
+    return fail(TX_ERR_OVERLAP, "out overlaps src or index");
+  set_path("");
+  const int64_t n = numel(out);
+  if (n == 0) return TX_OK;
+  if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "gather: more than 2^31 output elements");
+  ElemArgs a;
+  fill_dims(&a.shape, index->ndim, index->sizes);
+  a.dim = src->ndim ? d : 0;
+  a.index_is64 = index->dtype == TX_I64;
+  a.index = (const char*)index->data;
+  a.src = (const char*)src->data;
+  a.dst = (char*)out->data;
+  for (int i = 0; i < index->ndim; ++i) {
+    a.istride[i] = index->strides[i];
+    a.sstride[i] = src->strides[i];
+    a.dstride[i] = out->strides[i];
+  }
+  if (index->ndim == 0) a.sstride[0] = a.istride[0] = a.dstride[0] = 0;
+  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  hipStream_t s = as_stream(stream);
+  set_path("gather");
+  switch (dtype_size(src->dtype)) {
+    case 1: hipLaunchKernelGGL((gather_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a, 0); break;
+    case 2: hipLaunchKernelGGL((gather_kernel<uint16_t>), grid, dim3(kBlock), 0, s, a, 0); break;
+    case 4: hipLaunchKernelGGL((gather_kernel<uint32_t>), grid, dim3(kBlock), 0, s, a, 0); break;
+    default: hipLaunchKernelGGL((gather_kernel<uint64_t>), grid, dim3(kBlock), 0, s, a, 0); break;
+  }
+  return check_launch("gather kernel");
+}
+
+tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t dim, const tx_tensor* index,
+                          void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(src, "src")) || (rc = check_tensor(index, "index"))) return rc;
+  if (!index_dtype_ok(index->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
+  if (out->dtype != src->dtype) return fail(TX_ERR_DTYPE, "index_select: out must have src's dtype");
+  if (index->ndim > 1) return fail(TX_ERR_SHAPE, "index_select: index must be 1-D or 0-dim");
+  int d;
+  if ((rc = wrap_dim(dim, src->ndim, &d))) return rc;
+  const int64_t nsel = index->ndim ? index->sizes[0] : 1;
+  const int64_t istride = index->ndim ? index->strides[0] : 0;
+  if (src->ndim == 0) {
+    if (nsel != 1 || out->ndim != 0) return fail(TX_ERR_SHAPE, "index_select on a 0-dim src takes one index");
+  } else {
+    if (out->ndim != src->ndim) return fail(TX_ERR_SHAPE, "index_select: out rank");
+    for (int i = 0; i < src->ndim; ++i)
+      if (out->sizes[i] != (i == d ? nsel : src->sizes[i])) return fail(TX_ERR_SHAPE, "index_select: out shape");
+  }
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  if (partial_overlap(out, src) || partial_overlap(out, index) || (out->data == src->data && numel(out) && numel(src)))
+    return fail(TX_ERR_OVERLAP, "out overlaps src or index");
+  set_path("");
+  const int64_t n = numel(out);
+  if (n == 0) return TX_OK;
+  hipStream_t s = as_stream(stream);
+  const int es = dtype_size(src->dtype);
+  // fast path: dims below `dim` form one contiguous run in src and out; dims above collapse to one stride
+  if (src->ndim >= 1) {
+    int64_t inner = 1;
+    bool ok = true;
+    for (int i = src->ndim - 1; i > d; --i) {
+      if (src->sizes[i] > 1 && (src->strides[i] != inner || out->strides[i] != inner)) ok = false;
+      inner *= src->sizes[i];
+    }
+    int64_t outer = 1, so = 0, oo = 0;
+    for (int i = d - 1; i >= 0; --i) {
+      if (src->sizes[i] > 1) {
+        if (outer == 1) { so = src->strides[i]; oo = out->strides[i]; }
+        else if (src->strides[i] != so * outer || out->strides[i] != oo * outer) ok = false;
+      }
+      outer *= src->sizes[i];
+    }
+    const int64_t bytes = inner * es;
+    ok = ok && bytes >= 64 && bytes % 16 == 0 && (uintptr_t)src->data % 16 == 0 && (uintptr_t)out->data % 16 == 0 &&
+         (src->strides[d] * es) % 16 == 0 && (out->strides[d] * es) % 16 == 0 && (so * es) % 16 == 0 && (oo * es) % 16 == 0 &&
+         outer * nsel < (1ll << 31);
+    if (ok) {
+      RowCopyArgs a;
+      a.index = (const char*)index->data;
+      a.src = (const char*)src->data;
+      a.dst = (char*)out->data;
+      a.index_is64 = index->dtype == TX_I64;
+      a.istride = istride;
+      a.nsel = nsel;
+      a.nsel_div = FastDiv((uint32_t)nsel);
+      a.rows = outer * nsel;
+      a.src_outer = so * es;
+      a.dst_outer = oo * es;
+      a.src_dim = src->strides[d] * es;
+      a.dst_dim = out->strides[d] * es;
+      a.vecs = bytes / 16;
+      const int64_t waves = (a.rows + kRowsPerWave - 1) / kRowsPerWave;
+      set_path("index-select-rows");
+      hipLaunchKernelGGL(index_select_rows_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(kBlock), 0, s, a);
+      return check_launch("index_select row kernel");
+    }
+  }
+  if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "index_select: more than 2^31 elements on the generic path");
+  ElemArgs a;
+  fill_dims(&a.shape, out->ndim, out->sizes);
+  a.dim = d;
+  a.index_is64 = index->dtype == TX_I64;
+  a.index = (const char*)index->data;
+  a.src = (const char*)src->data;
+  a.dst = (char*)out->data;
+  for (int i = 0; i < out->ndim; ++i) {
+    a.istride[i] = 0;
+    a.sstride[i] = src->strides[i];
+    a.dstride[i] = out->strides[i];
+  }
+  a.istride[d] = istride;
+  if (out->ndim == 0) { a.dim = 0; a.sstride[0] = a.dstride[0] = a.istride[0] = 0; }
+  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  set_path("index-select-generic");
+  switch (es) {
+    case 1: hipLaunchKernelGGL((gather_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a, 1); break;
+    case 2: hipLaunchKernelGGL((gather_kernel<uint16_t>), grid, dim3(kBlock), 0, s, a, 1); break;
+    case 4: hipLaunchKernelGGL((gather_kernel<uint32_t>), grid, dim3(kBlock), 0, s, a, 1); break;
+    default: hipLaunchKernelGGL((gather_kernel<uint64_t>), grid, dim3(kBlock), 0, s, a, 1); break;
+  }
+  return check_launch("index_select generic kernel");
+}
+
+size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
+                                      int deterministic) {
+  int d;
+  if (scatter_checks(self, dim, index, src, &d)) return 0;
+  if (!dtype_is_float(self->dtype) || numel(index) == 0) return 0;
+  if (!deterministic && self->dtype == TX_F32) return 0;
+  ScatterPlan p;
+  if (scatter_plan(self, d, index, src, &p)) return 0;
+  return p.bytes;
+}
+
+tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
+                          int deterministic, void* ws, size_t ws_bytes, void* stream) {
+  int d;
+  tx_status rc = scatter_checks(self, dim, index, src, &d);
+  if (rc) return rc;
+  set_path("");
+  const int64_t n = numel(index);
+  if (n == 0) return TX_OK;
+  hipStream_t s = as_stream(stream);
+  // fp16 / bf16 always take the sorted path: 16-bit atomics would round every partial sum to the half type
+  if (dtype_is_float(self->dtype) && (deterministic || self->dtype != TX_F32)) {
+    ScatterPlan p;
+    if ((rc = scatter_plan(self, d, index, src, &p))) return rc;
+    if (!ws || ws_bytes < p.bytes)
+      return fail(TX_ERR_WORKSPACE, "scatter_add_ needs %zu workspace bytes, got %zu", p.bytes, ws_bytes);
+    if ((uintptr_t)ws % 16) return fail(TX_ERR_WORKSPACE, "scatter_add_ workspace must be 16-byte aligned");
+    switch (self->dtype) {
+      case TX_F32: return scatter_deterministic<float>(p, self, d, index, src, (char*)ws, s);
+      case TX_BF16: return scatter_deterministic<bf16>(p, self, d, index, src, (char*)ws, s);
+      default: return scatter_deterministic<f16>(p, self, d, index, src, (char*)ws, s);
+    }
+  }
+  if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "scatter_add_: more than 2^31 index elements");
+  ElemArgs a;
+  fill_scatter_elem_args(&a, self, d, index, src);
+  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  set_path("scatter-atomic");
+  switch (self->dtype) {
+    case TX_BOOL: hipLaunchKernelGGL((scatter_add_atomic_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a); break;
+    case TX_I32: hipLaunchKernelGGL((scatter_add_atomic_kernel<int32_t>), grid, dim3(kBlock), 0, s, a); break;
+    case TX_I64: hipLaunchKernelGGL((scatter_add_atomic_kernel<int64_t>), grid, dim3(kBlock), 0, s, a); break;
+    default: hipLaunchKernelGGL((scatter_add_atomic_kernel<float>), grid, dim3(kBlock), 0, s, a); break;
+  }
+  return check_launch("scatter_add atomic kernel");
+}
+
+}  // extern "C"

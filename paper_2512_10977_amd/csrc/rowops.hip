@@ -1,0 +1,616 @@
+// Row operators: softmax / log_softmax and cumsum along one dim.
+//
+// softmax, last dim contiguous:
+//   wave  : one wave64 owns a row and keeps it in registers (up to 1024
+//           16-byte vectors, i.e. 4096 fp32 or 8192 half elements): one HBM
+//           read, two wave reductions (max, sum), one HBM write.
+//   block : longer rows; a 256-lane workgroup makes three passes over the row
+//           (the re-reads are served by L2).
+// softmax / cumsum along any other dim or over a strided slice:
+//   strided: one lane per slice, walking the dim with its stride (lanes run
+//           along the innermost other dim, so accesses stay coalesced when
+//           that dim is contiguous).
+// cumsum, last dim contiguous: single-pass scan with decoupled look-back.  A
+//   row is cut into tiles; a workgroup takes tiles in ticket order, scans its
+//   tile, publishes the tile aggregate, and resolves its exclusive prefix by
+//   looking back over predecessor tiles' published aggregates / inclusive
+//   prefixes.  Each element is read once and written once.
+#include <algorithm>
+#include <cstring>
+
+#include "common.h"
+
+namespace tx {
+namespace {
+
+constexpr int kBlock = 256;
+
+// the dims other than `dim`, merged where both tensors allow, inner-most last
+struct Slices {
+  int n;
+  FastDiv div[TX_MAX_DIMS];
+  int64_t size[TX_MAX_DIMS], xs[TX_MAX_DIMS], os[TX_MAX_DIMS];
+  int64_t count;
+};
+
+void build_slices(Slices* s, const tx_tensor* x, const tx_tensor* out, int dim) {
+  s->n = 0;
+  s->count = 1;
+  for (int d = 0; d < x->ndim; ++d) {
+    if (d == dim) continue;
+    const int64_t sz = x->sizes[d];
+    s->count *= sz;
+    if (sz == 1) continue;
+    if (s->n > 0 && s->xs[s->n - 1] == x->strides[d] * sz && s->os[s->n - 1] == out->strides[d] * sz) {
+      s->size[s->n - 1] *= sz;
+      s->xs[s->n - 1] = x->strides[d];
+      s->os[s->n - 1] = out->strides[d];
+    } else {
+      s->size[s->n] = sz;
+      s->xs[s->n] = x->strides[d];
+      s->os[s->n] = out->strides[d];
+      ++s->n;
+    }
+  }
+  for (int d = 0; d < s->n; ++d) s->div[d] = FastDiv((uint32_t)std::min<int64_t>(s->size[d], 0x7fffffff));
+}
+
+__device__ __forceinline__ void slice_offsets(const Slices& s, int64_t idx, int64_t* xo, int64_t* oo) {
+  int64_t x = 0, o = 0;
+  if (s.n == 1) { x = idx * s.xs[0]; o = idx * s.os[0]; }
+  else {
+    uint32_t rem = (uint32_t)idx;
+    for (int d = s.n - 1; d >= 0; --d) {
+      uint32_t q, m;
+      s.div[d].divmod(rem, q, m);
+      rem = q;
+      x += (int64_t)m * s.xs[d];
+      o += (int64_t)m * s.os[d];
+    }
+  }
+  *xo = x;
+  *oo = o;
+}
+
+template <class O> __device__ __forceinline__ O from_float(float v) { return cvt<O>(v); }
+
+// ---------------------------------------------------------------------------
+// softmax
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int m = kWave / 2; m >= 1; m >>= 1) v = fmaxf(v, shfl_xor(v, m));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = kWave / 2; m >= 1; m >>= 1) v += shfl_xor(v, m);
+  return v;
+}
+constexpr float kNegInf = -__builtin_huge_valf();
+
+struct SoftmaxArgs {
+  const char* x;
+  char* out;
+  int64_t rows, len;
+  int64_t xrow, orow;     // row strides in elements
+  int is_log;
+};
+
+// one wave per row, CH vectors of VEC elements per lane
+template <class T, class O, int VEC, int CH>
+__global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t row = (int64_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x / kWave);
+  if (row >= a.rows) return;
+  const T* x = (const T*)a.x + row * a.xrow;
+  O* out = (O*)a.out + row * a.orow;
+  float v[CH][VEC];
+  float m = kNegInf;
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {
+    const int64_t c = ((int64_t)k * kWave + lane) * VEC;
+    if (c < a.len) {                      // len is a multiple of VEC on this path
+      Vec<T, VEC> t = *(const Vec<T, VEC>*)(x + c);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { v[k][e] = cvt<float>(t.v[e]); m = fmaxf(m, v[k][e]); }
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[k][e] = kNegInf;
+    }
+  }
+  m = wave_max(m);
+  float s = 0.0f;
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {
+    const int64_t c = ((int64_t)k * kWave + lane) * VEC;
+    if (c < a.len) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        v[k][e] -= m;
+        const float ex = expf(v[k][e]);
+        s += ex;
+        if (!a.is_log) v[k][e] = ex;
+      }
+    }
+  }
+  s = wave_sum(s);
+  const float inv = 1.0f / s, ls = logf(s);
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {
+    const int64_t c = ((int64_t)k * kWave + lane) * VEC;
+    if (c < a.len) {
+      Vec<O, VEC> t;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) t.v[e] = from_float<O>(a.is_log ? v[k][e] - ls : v[k][e] * inv);
+      *(Vec<O, VEC>*)(out + c) = t;
+    }
+  }
+}
+
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* lds) {
+  v = is_max ? wave_max(v) : wave_sum(v);
+  const int w = threadIdx.x / kWave;
+  __syncthreads();                          // protects lds reuse between calls
+  if ((threadIdx.x & (kWave - 1)) == 0) lds[w] = v;
+  __syncthreads();
+  float r = lds[0];
+#pragma unroll
+  for (int k = 1; k < kBlock / kWave; ++k) r = is_max ? fmaxf(r, lds[k]) : r + lds[k];
+  return r;
+}
+
+// one workgroup per row, three passes
+template <class T, class O>
+__global__ __launch_bounds__(kBlock) void softmax_block_kernel(const SoftmaxArgs a) {
+  __shared__ float lds[kBlock / kWave];
+  const int64_t row = blockIdx.x;
+  const T* x = (const T*)a.x + row * a.xrow;
+  O* out = (O*)a.out + row * a.orow;
+  float m = kNegInf;
+  for (int64_t c = threadIdx.x; c < a.len; c += kBlock) m = fmaxf(m, cvt<float>(x[c]));
+  m = block_reduce(m, true, lds);
+  float s = 0.0f;
+  for (int64_t c = threadIdx.x; c < a.len; c += kBlock) s += expf(cvt<float>(x[c]) - m);
+  s = block_reduce(s, false, lds);
+  const float inv = 1.0f / s, ls = logf(s);
+  for (int64_t c = threadIdx.x; c < a.len; c += kBlock) {
+    const float d = cvt<float>(x[c]) - m;
+    out[c] = from_float<O>(a.is_log ? d - ls : expf(d) * inv);
+  }
+}
+
+struct StridedArgs {
+  const char* x;
+  char* out;
+  Slices sl;
+  int64_t len, xs, os;    // extent and strides of the operated dim
+  int is_log;
+};
+
+template <class T, class O>
+__global__ __launch_bounds__(kBlock) void softmax_strided_kernel(const StridedArgs a) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (idx >= a.sl.count) return;
+  int64_t xo, oo;
+  slice_offsets(a.sl, idx, &xo, &oo);
+  const T* x = (const T*)a.x + xo;
+  O* out = (O*)a.out + oo;
+  float m = kNegInf;
+  for (int64_t j = 0; j < a.len; ++j) m = fmaxf(m, cvt<float>(x[j * a.xs]));
+  float s = 0.0f;
+  for (int64_t j = 0; j < a.len; ++j) s += expf(cvt<float>(x[j * a.xs]) - m);
+  const float inv = 1.0f / s, ls = logf(s);
+  for (int64_t j = 0; j < a.len; ++j) {
+    const float d = cvt<float>(x[j * a.xs]) - m;
+    out[j * a.os] = from_float<O>(a.is_log ? d - ls : expf(d) * inv);
+  }
+}
+
+template <class T, class O>
+tx_status softmax_launch(const tx_tensor* out, const tx_tensor* x, int dim, int is_log, hipStream_t stream) {
+  constexpr int V = 16 / sizeof(T);
+  const int nd = x->ndim;
+  const int64_t len = nd ? x->sizes[dim] : 1;
+  const int64_t xs = nd ? x->strides[dim] : 1, os = nd ? out->strides[dim] : 1;
+  Slices sl;
+  build_slices(&sl, x, out, nd ? dim : -1);
+  if (sl.count >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "softmax: too many slices");
+  const bool rows = (len == 1 || (xs == 1 && os == 1)) && sl.n <= 1 && len > 1;
+  if (rows) {
+    SoftmaxArgs a;
+    a.x = (const char*)x->data;
+    a.out = (char*)out->data;
+    a.rows = sl.count;
+    a.len = len;
+    a.xrow = sl.n ? sl.xs[0] : 0;
+    a.orow = sl.n ? sl.os[0] : 0;
+    a.is_log = is_log;
+    const bool al = len % V == 0 && (uintptr_t)x->data % 16 == 0 && (uintptr_t)out->data % (V * sizeof(O) >= 16 ? 16 : V * sizeof(O)) == 0 &&
+                    (a.xrow * (int64_t)sizeof(T)) % 16 == 0 && (a.orow * (int64_t)sizeof(O)) % 16 == 0;
+    const dim3 grid((unsigned)((a.rows + 3) / 4));
+    if (al && len <= 64 * V) {
+      set_path("softmax-wave");
+      hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 1>), grid, dim3(kBlock), 0, stream, a);
+    } else if (al && len <= 256 * V) {
+      set_path("softmax-wave");
+      hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 4>), grid, dim3(kBlock), 0, stream, a);
+    } else if (al && len <= 1024 * V) {
+      set_path("softmax-wave");
+      hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 16>), grid, dim3(kBlock), 0, stream, a);
+    } else if (len <= 64 * 16) {
+      set_path("softmax-wave-scalar");
+      hipLaunchKernelGGL((softmax_wave_kernel<T, O, 1, 16>), grid, dim3(kBlock), 0, stream, a);
+    } else {
+      set_path("softmax-block");
+      hipLaunchKernelGGL((softmax_block_kernel<T, O>), dim3((unsigned)a.rows), dim3(kBlock), 0, stream, a);
+    }
+    return check_launch("softmax kernel");
+  }
+  StridedArgs a;
+  a.x = (const char*)x->data;
+  a.out = (char*)out->data;
+  a.sl = sl;
+  a.len = len;
+  a.xs = xs;
+  a.os = os;
+  a.is_log = is_log;
+  set_path("softmax-strided");
+  hipLaunchKernelGGL((softmax_strided_kernel<T, O>), dim3((unsigned)((sl.count + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                     stream, a);
+  return check_launch("softmax strided kernel");
+}
+
+// ---------------------------------------------------------------------------
+// cumsum: decoupled look-back scan
+// ---------------------------------------------------------------------------
+constexpr int kNV = 4;                       // vectors per lane per tile
+constexpr uint32_t kEmpty = 0, kAggregate = 1, kPrefix = 2;
+constexpr int kSpinLimit = 1 << 24;          // bounded wait: a stuck predecessor sets the error word instead of hanging
+
+struct ScanHeader {                           // first 256 bytes of the workspace
+  unsigned int ticket;
+  unsigned int error;
+};
+
+// Tile status.  4-byte accumulators travel with their flag in one 64-bit word.
+// 8-byte accumulators use two flagged words per value, and separate slots for
+// the aggregate and the inclusive prefix so that every word is written once.
+template <class Acc> struct TileState;
+template <> struct TileState<float> {
+  static constexpr int words = 1;
+  __device__ static void publish(unsigned long long* st, int64_t tile, uint32_t flag, float v) {
+    unsigned long long w = ((unsigned long long)flag << 32) | __float_as_uint(v);
+    __hip_atomic_store(st + tile, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __device__ static uint32_t read(unsigned long long* st, int64_t tile, float* v) {
+    unsigned long long w = __hip_atomic_load(st + tile, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *v = __uint_as_float((uint32_t)w);
+    return (uint32_t)(w >> 32);
+  }
+};
+template <> struct TileState<int64_t> {
+  static constexpr int words = 4;
+  __device__ static void publish(unsigned long long* st, int64_t tile, uint32_t flag, int64_t v) {
+    unsigned long long* p = st + tile * 4 + (flag == kPrefix ? 2 : 0);
+    const unsigned long long f = 1ull << 32;
+    __hip_atomic_store(p, f | (uint32_t)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, f | (uint32_t)((unsigned long long)v >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __device__ static uint32_t read(unsigned long long* st, int64_t tile, int64_t* v) {
+    unsigned long long* p = st + tile * 4;
+    unsigned long long lo = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long hi = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((lo >> 32) && (hi >> 32)) { *v = (int64_t)((hi << 32) | (uint32_t)lo); return kPrefix; }
+    lo = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    hi = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((lo >> 32) && (hi >> 32)) { *v = (int64_t)((hi << 32) | (uint32_t)lo); return kAggregate; }
+    *v = 0;
+    return kEmpty;
+  }
+};
+
+__global__ void scan_clear_kernel(unsigned long long* ws, int64_t words) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < words) ws[i] = 0ull;
+}
+
+struct ScanArgs {
+  const char* x;
+  char* out;
+  char* ws;
+  int64_t rows, len, xrow, orow;
+  int64_t tiles_per_row, total_tiles;
+};
+
+template <class Acc> __device__ __forceinline__ Acc wave_inclusive(Acc v) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+  for (int d = 1; d < kWave; d <<= 1) {
+    Acc o = shfl_up(v, d);
+    if (lane >= d) v += o;
+  }
+  return v;
+}
+
+template <class T, class O, class Acc, int VEC>
+__global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs a) {
+  constexpr int kTileElems = kBlock * kNV * VEC;
+  constexpr int kWaves = kBlock / kWave;
+  __shared__ Acc wave_tot[kNV][kWaves];
+  __shared__ Acc tile_prefix;
+  __shared__ unsigned int my_ticket;
+  ScanHeader* hdr = (ScanHeader*)a.ws;
+  unsigned long long* status = (unsigned long long*)(a.ws + 256);
+
+  if (threadIdx.x == 0) my_ticket = atomicAdd(&hdr->ticket, 1u);
+  __syncthreads();
+  const int64_t ticket = my_ticket;
+  if (ticket >= a.total_tiles) return;
+  const int64_t row = ticket / a.tiles_per_row, t = ticket - row * a.tiles_per_row;
+  const T* x = (const T*)a.x + row * a.xrow + t * kTileElems;
+  O* out = (O*)a.out + row * a.orow + t * kTileElems;
+  const int64_t left = a.len - t * kTileElems;      // valid elements in this tile (may exceed the tile)
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+
+  Acc v[kNV][VEC];
+#pragma unroll
+  for (int k = 0; k < kNV; ++k) {
+    const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+    if (c + VEC <= left) {
+      Vec<T, VEC> tv = *(const Vec<T, VEC>*)(x + c);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[k][e] = cvt<Acc>(tv.v[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[k][e] = (c + e < left) ? cvt<Acc>(x[c + e]) : Acc(0);
+    }
+  }
+  Acc excl[kNV];
+#pragma unroll
+  for (int k = 0; k < kNV; ++k) {
+#pragma unroll
+    for (int e = 1; e < VEC; ++e) v[k][e] += v[k][e - 1];
+    const Acc incl = wave_inclusive(v[k][VEC - 1]);
+    Acc up = shfl_up(incl, 1);
+    excl[k] = lane == 0 ? Acc(0) : up;
+    if (lane == kWave - 1) wave_tot[k][w] = incl;
+  }
+  __syncthreads();
+  // prefix of (k, w) in tile order: all of sub-tiles k' < k, then waves w' < w of sub-tile k
+  Acc running = Acc(0);
+  Acc base[kNV];
+#pragma unroll
+  for (int k = 0; k < kNV; ++k) {
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) {
+      if (ww == w) base[k] = running;
+      running += wave_tot[k][ww];
+    }
+  }
+  const Acc tile_total = running;
+  if (w == 0) {
+    // wave 0 resolves the tile's exclusive prefix
+    Acc prefix = Acc(0);
+    if (t == 0) {
+      if (lane == 0) TileState<Acc>::publish(status, ticket, kPrefix, tile_total);
+    } else {
+      if (lane == 0) TileState<Acc>::publish(status, ticket, kAggregate, tile_total);
+      int64_t look = t - 1;                    // nearest predecessor not yet folded in (row-local index)
+      bool done = false;
+      while (!done) {
+        const int64_t mine = look - lane;      // lane i inspects predecessor look - i
+        Acc val = Acc(0);
+        uint32_t flag = kPrefix;               // positions before the row start count as a zero prefix
+        if (mine >= 0) {
+          int spins = 0;
+          do {
+            flag = TileState<Acc>::read(status, ticket - t + mine, &val);
+            if (flag != kEmpty) break;
+            __builtin_amdgcn_s_sleep(2);
+          } while (++spins < kSpinLimit);
+          if (flag == kEmpty) { hdr->error = 1; flag = kPrefix; val = Acc(0); }
+        }
+        const unsigned long long has_prefix = __ballot(flag == kPrefix);
+        const int stop = __ffsll((long long)has_prefix) - 1;      // nearest predecessor holding a full prefix
+        Acc contrib = (stop < 0 || lane <= stop) ? val : Acc(0);
+#pragma unroll
+        for (int m = kWave / 2; m >= 1; m >>= 1) contrib += shfl_xor(contrib, m);
+        prefix += contrib;
+        if (stop >= 0) done = true;
+        else look -= kWave;
+      }
+      if (lane == 0) TileState<Acc>::publish(status, ticket, kPrefix, prefix + tile_total);
+    }
+    if (lane == 0) tile_prefix = prefix;
+  }
+  __syncthreads();
+  const Acc p = tile_prefix;
+#pragma unroll
+  for (int k = 0; k < kNV; ++k) {
+    const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+    const Acc add = p + base[k] + excl[k];
+    if (c + VEC <= left) {
+      Vec<O, VEC> tv;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) tv.v[e] = cvt<O>((Acc)(v[k][e] + add));
+      *(Vec<O, VEC>*)(out + c) = tv;
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (c + e < left) out[c + e] = cvt<O>((Acc)(v[k][e] + add));
+    }
+  }
+}
+
+template <class T, class O, class Acc>
+__global__ __launch_bounds__(kBlock) void cumsum_strided_kernel(const StridedArgs a) {
+  const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (idx >= a.sl.count) return;
+  int64_t xo, oo;
+  slice_offsets(a.sl, idx, &xo, &oo);
+  const T* x = (const T*)a.x + xo;
+  O* out = (O*)a.out + oo;
+  Acc acc = Acc(0);
+  for (int64_t j = 0; j < a.len; ++j) {
+    acc += cvt<Acc>(x[j * a.xs]);
+    out[j * a.os] = cvt<O>(acc);
+  }
+}
+
+struct ScanPlan {
+  bool lookback;
+  int vec;
+  int64_t rows, len, xrow, orow, tiles_per_row, total_tiles;
+  size_t ws_bytes;
+};
+
+template <class T, class O, class Acc> ScanPlan scan_plan(const tx_tensor* out, const tx_tensor* x, int dim, const Slices& sl) {
+  constexpr int V = 16 / sizeof(T);
+  ScanPlan p;
+  memset(&p, 0, sizeof(p));
+  const int nd = x->ndim;
+  p.len = nd ? x->sizes[dim] : 1;
+  const int64_t xs = nd ? x->strides[dim] : 1, os = nd ? out->strides[dim] : 1;
+  p.lookback = p.len > 1 && xs == 1 && os == 1 && sl.n <= 1;
+  if (!p.lookback) return p;
+  p.rows = sl.count;
+  p.xrow = sl.n ? sl.xs[0] : 0;
+  p.orow = sl.n ? sl.os[0] : 0;
+  constexpr int out_al = V * sizeof(O) >= 16 ? 16 : V * sizeof(O);
+  const bool al = (uintptr_t)x->data % 16 == 0 && (uintptr_t)out->data % out_al == 0 &&
+                  (p.xrow * (int64_t)sizeof(T)) % 16 == 0 && (p.orow * (int64_t)sizeof(O)) % out_al == 0;
+  p.vec = al ? V : 1;
+  const int64_t tile = (int64_t)kBlock * kNV * p.vec;
+  p.tiles_per_row = (p.len + tile - 1) / tile;
+  p.total_tiles = p.tiles_per_row * p.rows;
+  p.ws_bytes = 256 + (size_t)p.total_tiles * TileState<Acc>::words * 8;
+  return p;
+}
+
+template <class T, class O, class Acc>
+tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void* ws, size_t ws_bytes, hipStream_t stream,
+                        size_t* query) {
+  constexpr int V = 16 / sizeof(T);
+  Slices sl;
+  build_slices(&sl, x, out, x->ndim ? dim : -1);
+  ScanPlan p = scan_plan<T, O, Acc>(out, x, dim, sl);
+  if (query) { *query = p.lookback ? p.ws_bytes : 0; return TX_OK; }
+  if (sl.count >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "cumsum: too many slices");
+  if (p.lookback) {
+    if (p.total_tiles >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "cumsum: too many tiles");
+    if (!ws || ws_bytes < p.ws_bytes)
+      return fail(TX_ERR_WORKSPACE, "cumsum needs %zu workspace bytes, got %zu", p.ws_bytes, ws_bytes);
+    if ((uintptr_t)ws % 8) return fail(TX_ERR_WORKSPACE, "cumsum workspace must be 8-byte aligned");
+    ScanArgs a;
+    a.x = (const char*)x->data;
+    a.out = (char*)out->data;
+    a.ws = (char*)ws;
+    a.rows = p.rows;
+    a.len = p.len;
+    a.xrow = p.xrow;
+    a.orow = p.orow;
+    a.tiles_per_row = p.tiles_per_row;
+    a.total_tiles = p.total_tiles;
+    const int64_t words = (int64_t)(p.ws_bytes / 8);
+    hipLaunchKernelGGL(scan_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
+                       (unsigned long long*)ws, words);
+    set_path(p.vec > 1 ? "scan-lookback" : "scan-lookback-scalar");
+    if (p.vec > 1)
+      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, V>), dim3((unsigned)p.total_tiles), dim3(kBlock), 0, stream, a);
+    else
+      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, 1>), dim3((unsigned)p.total_tiles), dim3(kBlock), 0, stream, a);
+    return check_launch("cumsum look-back kernel");
+  }
+  StridedArgs a;
+  a.x = (const char*)x->data;
+  a.out = (char*)out->data;
+  a.sl = sl;
+  a.len = x->ndim ? x->sizes[dim] : 1;
+  a.xs = x->ndim ? x->strides[dim] : 1;
+  a.os = x->ndim ? out->strides[dim] : 1;
+  a.is_log = 0;
+  set_path("scan-strided");
+  hipLaunchKernelGGL((cumsum_strided_kernel<T, O, Acc>), dim3((unsigned)((sl.count + kBlock - 1) / kBlock)), dim3(kBlock),
+                     0, stream, a);
+  return check_launch("cumsum strided kernel");
+}
+
+tx_status cumsum_dispatch(const tx_tensor* out, const tx_tensor* x, int dim, void* ws, size_t wsb, hipStream_t s,
+                          size_t* query) {
+  const bool wide = out->dtype == TX_F32;
+  switch (x->dtype) {
+    case TX_BOOL: return cumsum_launch<uint8_t, int64_t, int64_t>(out, x, dim, ws, wsb, s, query);
+    case TX_I32: return cumsum_launch<int32_t, int64_t, int64_t>(out, x, dim, ws, wsb, s, query);
+    case TX_I64: return cumsum_launch<int64_t, int64_t, int64_t>(out, x, dim, ws, wsb, s, query);
+    case TX_F32: return cumsum_launch<float, float, float>(out, x, dim, ws, wsb, s, query);
+    case TX_BF16:
+      return wide ? cumsum_launch<bf16, float, float>(out, x, dim, ws, wsb, s, query)
+                  : cumsum_launch<bf16, bf16, float>(out, x, dim, ws, wsb, s, query);
+    default:
+      return wide ? cumsum_launch<f16, float, float>(out, x, dim, ws, wsb, s, query)
+                  : cumsum_launch<f16, f16, float>(out, x, dim, ws, wsb, s, query);
+  }
+}
+
+tx_status rowop_checks(const char* name, const tx_tensor* out, const tx_tensor* x, int64_t dim, int* d, bool softmax) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(x, "x"))) return rc;
+  const bool flt = dtype_is_float(x->dtype);
+  if (softmax) {
+    if (!flt) return fail(TX_ERR_DTYPE, "%s takes floating dtypes only", name);
+    if (out->dtype != x->dtype && out->dtype != TX_F32) return fail(TX_ERR_DTYPE, "%s: out dtype", name);
+  } else if (flt) {
+    if (out->dtype != x->dtype && out->dtype != TX_F32) return fail(TX_ERR_DTYPE, "%s: out dtype", name);
+  } else if (out->dtype != TX_I64) {
+    return fail(TX_ERR_DTYPE, "%s of bool / integer input returns int64", name);
+  }
+  if (!same_sizes(out, x->ndim, x->sizes)) return fail(TX_ERR_SHAPE, "%s: out must have x's shape", name);
+  if ((rc = wrap_dim(dim, x->ndim, d))) return rc;
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  if (partial_overlap(out, x) || (out->data == x->data && numel(x) > 0))
+    return fail(TX_ERR_OVERLAP, "%s: out must not alias x", name);
+  return TX_OK;
+}
+
+}  // namespace
+}  // namespace tx
+
+using namespace tx;
+
+extern "C" {
+
+tx_status tx_softmax(const tx_tensor* out, const tx_tensor* x, int64_t dim, int is_log, void* stream) {
+  int d;
+  tx_status rc = rowop_checks("softmax", out, x, dim, &d, true);
+  if (rc) return rc;
+  set_path("");
+  if (numel(x) == 0) return TX_OK;
+  hipStream_t s = as_stream(stream);
+  const bool wide = out->dtype == TX_F32;
+  switch (x->dtype) {
+    case TX_F32: return softmax_launch<float, float>(out, x, d, is_log, s);
+    case TX_BF16: return wide ? softmax_launch<bf16, float>(out, x, d, is_log, s) : softmax_launch<bf16, bf16>(out, x, d, is_log, s);
+    default: return wide ? softmax_launch<f16, float>(out, x, d, is_log, s) : softmax_launch<f16, f16>(out, x, d, is_log, s);
+  }
+}
+
+tx_status tx_cumsum(const tx_tensor* out, const tx_tensor* x, int64_t dim, void* ws, size_t ws_bytes, void* stream) {
+  int d;
+  tx_status rc = rowop_checks("cumsum", out, x, dim, &d, false);
+  if (rc) return rc;
+  set_path("");
+  if (numel(x) == 0) return TX_OK;
+  return cumsum_dispatch(out, x, d, ws, ws_bytes, as_stream(stream), nullptr);
+}
+
+size_t tx_cumsum_workspace_bytes(const tx_tensor* out, const tx_tensor* x, int64_t dim) {
+  int d;
+  if (rowop_checks("cumsum", out, x, dim, &d, false)) return 0;
+  if (numel(x) == 0) return 0;
+  size_t q = 0;
+  cumsum_dispatch(out, x, d, nullptr, 0, nullptr, &q);
+  return q;
+}
+
+}  // extern "C"

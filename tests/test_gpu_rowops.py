@@ -1,0 +1,157 @@
+"""GPU parity: softmax / log_softmax and cumsum (HIP library through the C ABI) vs. the CPU oracle."""
+import itertools
+
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2512_10977_amd import binding as B
+from paper_2512_10977_amd import inputs as I
+from tests.parity import assert_exact, assert_rel, to_device_view
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
+FLT_MIN = 1.1754943508222875e-38
+
+
+def check_softmax(x_cpu, dim=-1, log=False, out_dtype=None, what=""):
+    want = O.softmax(x_cpu, dim, log, out_dtype=out_dtype)
+    x = to_device_view(x_cpu)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_softmax(out, x, dim, log)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    what = "%s %s %s dim=%d %s [%s]" % ("log_softmax" if log else "softmax", x_cpu.dtype, tuple(x_cpu.shape), dim, what, used)
+    rel = 1e-5 if want.dtype == F32 else 1e-2
+    # softmax outputs are non-negative (no cancellation): the floor is the smallest normal of the output format
+    floor = 6.2e-5 if want.dtype == F16 else FLT_MIN
+    assert_rel(out, want, rel, 1.0 if log else floor, what)
+    return used
+
+
+def check_cumsum(x_cpu, dim=-1, out_dtype=None, what=""):
+    want = O.cumsum(x_cpu, dim, out_dtype=out_dtype)
+    x = to_device_view(x_cpu)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    nbytes = B.tx_cumsum_workspace_bytes(out, x, dim)
+    ws = B.workspace(nbytes) if nbytes else None
+    B.tx_cumsum(out, x, dim, ws)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    what = "cumsum %s %s dim=%d %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), dim, what, used)
+    if not want.dtype.is_floating_point:
+        assert_exact(out, want, what)
+    else:
+        xd = x_cpu.double()
+        xd = torch.where(xd.isfinite(), xd, torch.zeros_like(xd))
+        scale = (xd * xd).cumsum(dim if x_cpu.dim() else 0).sqrt() if x_cpu.dim() else xd.abs()
+        assert_rel(out, want, 1e-5 if want.dtype == F32 else 1e-2, scale, what)
+    if ws is not None:
+        assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
+    return used
+
+
+# --------------------------------------------------------------------------- softmax
+@pytest.mark.parametrize("log", [False, True])
+def test_softmax_shapes_and_paths(log):
+    paths = set()
+    for dt in (F32, BF16, F16):
+        for shape in [(7, 13, 5), (33, 64), (33, 300), (9, 1000), (5, 4096), (3, 5000), (2, 70001), (1, 17), (40, 1)]:
+            x = I.softmax_logits(shape, dt, seed=3)
+            paths.add(check_softmax(x, -1, log))
+        x = I.softmax_logits((6, 50, 7), dt, seed=301)
+        for dim in (0, 1, 2, -3):
+            paths.add(check_softmax(x, dim, log))
+        paths.add(check_softmax(I.make_view((30, 257), dt, "transposed", seed=302), -1, log, what="transposed"))
+        paths.add(check_softmax(I.make_view((30, 256), dt, "step2_outer", seed=303), -1, log, what="step2_outer"))
+        paths.add(check_softmax(I.make_view((30, 256), dt, "step2_inner", seed=304), -1, log, what="step2_inner"))
+    assert {"softmax-wave", "softmax-wave-scalar", "softmax-block", "softmax-strided"} <= paths, paths
+    check_softmax(I.softmax_logits((64, 512), BF16, seed=305), -1, log, out_dtype=F32, what="fp32 out")
+
+
+def test_softmax_special_rows_and_edges():
+    inf, nan = float("inf"), float("nan")
+    rows = torch.tensor([[0.0, -inf, 1.0, 2.0], [-inf, -inf, -inf, -inf], [0.0, inf, 1.0, 0.5], [0.0, nan, 1.0, 0.5],
+                         [5.0, 5.0, 5.0, 5.0]])
+    for log in (False, True):
+        check_softmax(rows, -1, log, what="specials")
+        check_softmax(rows.repeat(1, 300), -1, log, what="specials wide")
+        check_softmax(rows.t().contiguous(), 0, log, what="specials dim0")
+        check_softmax(torch.tensor(2.5), 0, log)
+        check_softmax(torch.zeros((3, 0)), -1, log)
+        check_softmax(torch.zeros((0, 3)), -1, log)
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    with pytest.raises(B.TxError) as e:
+        B.tx_softmax(d(2, 2, dt=I32), d(2, 2, dt=I32))
+    assert e.value.kind == "DTYPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_softmax(d(2, 2), d(2, 2), 2)
+    assert e.value.kind == "DIM"
+
+
+@pytest.mark.parametrize("dt", [F32, BF16])
+@pytest.mark.parametrize("log", [False, True])
+def test_softmax_full_size(dt, log):
+    x = I.softmax_logits((32768, 4096), dt, seed=3)
+    assert check_softmax(x, -1, log) == "softmax-wave"
+
+
+# --------------------------------------------------------------------------- cumsum
+def test_cumsum_shapes_and_paths():
+    paths = set()
+    for dt in (F32, BF16, F16, I32, I64, BOOL):
+        for shape in [(7, 13, 5), (33, 64), (9, 1000), (5, 4096), (3, 5000), (2, 70001), (1, 17), (40, 1), (4100,),
+                      (1, 300000)]:
+            x = I.cumsum_input(shape, dt, seed=3) if dt != BOOL else I.booleans(shape, 0.5, seed=3)
+            paths.add(check_cumsum(x, -1))
+        x = I.cumsum_input((6, 50, 7), dt, seed=310) if dt != BOOL else I.booleans((6, 50, 7), 0.5, seed=310)
+        for dim in (0, 1, 2, -3):
+            paths.add(check_cumsum(x, dim))
+        paths.add(check_cumsum(I.make_view((30, 257), dt, "transposed", seed=311, std=1.0), -1, what="transposed"))
+        paths.add(check_cumsum(I.make_view((30, 2048), dt, "step2_outer", seed=312, std=1.0), -1, what="step2_outer"))
+        paths.add(check_cumsum(I.make_view((30, 256), dt, "step2_inner", seed=313, std=1.0), -1, what="step2_inner"))
+    assert {"scan-lookback", "scan-lookback-scalar", "scan-strided"} <= paths, paths
+    check_cumsum(I.cumsum_input((16, 9000), BF16, seed=314), -1, out_dtype=F32, what="fp32 out")
+
+
+def test_cumsum_many_tiles_per_row_repeated():
+    # long rows: many look-back hops; run several times with the same workspace to cover re-use
+    x_cpu = I.cumsum_input((3, 1 << 20), I64, seed=315)
+    want = O.cumsum(x_cpu, -1)
+    x = x_cpu.cuda()
+    out = torch.empty_like(x)
+    ws = B.workspace(B.tx_cumsum_workspace_bytes(out, x, -1))
+    for _ in range(5):
+        out.zero_()
+        B.tx_cumsum(out, x, -1, ws)
+        torch.cuda.synchronize()
+        assert_exact(out, want, "cumsum int64 repeated")
+        assert ws[4:8].view(torch.int32).item() == 0
+    xf = I.cumsum_input((2, 1 << 21), F32, seed=316)
+    check_cumsum(xf, -1)
+
+
+def test_cumsum_edges_and_errors():
+    inf = float("inf")
+    check_cumsum(torch.tensor([1.0, inf, 2.0, -inf, 5.0]), 0)
+    check_cumsum(torch.tensor(4.0), 0)
+    check_cumsum(torch.zeros((0, 4)), 1)
+    check_cumsum(torch.zeros((4, 0)), 1)
+    check_cumsum(torch.tensor([2 ** 62, 2 ** 62, 2 ** 62]), 0)
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    with pytest.raises(B.TxError) as e:
+        B.tx_cumsum(d(4, dt=I32), d(4, dt=I32), 0)
+    assert e.value.kind == "DTYPE"                     # integer input needs an int64 out
+    with pytest.raises(B.TxError) as e:
+        B.tx_cumsum(d(4, 4), d(4, 4), 2)
+    assert e.value.kind == "DIM"
+    with pytest.raises(B.TxError) as e:
+        B.tx_cumsum(d(4, 4), d(4, 4), 1, ws=None)
+    assert e.value.kind == "WORKSPACE"
+
+
+@pytest.mark.parametrize("dt", [F32, I64])
+def test_cumsum_full_size(dt):
+    x = I.cumsum_input((4096, 65536), dt, seed=3)
+    assert check_cumsum(x, -1) == "scan-lookback"
