@@ -48,10 +48,14 @@ def build_ops(torch, B):
     outs1 = [torch.empty((4096, 4096), device=dev) for _ in range(9)]
     state = {"i": 0}
 
+    REP1 = 8     # an 8 us kernel between two events mostly measures the events: launch it 8 times back to back
+
     def f_bcast():
-        state["i"] = (state["i"] + 1) % len(outs1)
-        B.tx_add(outs1[state["i"]], a1, b1, 1)
-    add("add_bcast_f32[4096,1]+[1,4096]", "a3", "ew_vec_kernel", 4096 * 4096 * 4 + 2 * 4096 * 4, 4096 * 4096, f_bcast)
+        for _ in range(REP1):
+            state["i"] = (state["i"] + 1) % len(outs1)
+            B.tx_add(outs1[state["i"]], a1, b1, 1)
+    add("add_bcast_f32[4096,1]+[1,4096] x8", "a3", "ew_vec_kernel", REP1 * (4096 * 4096 * 4 + 2 * 4096 * 4),
+        REP1 * 4096 * 4096, f_bcast)
 
     # ---- workload 2: elementwise sweep at [8192,8192]
     N = 8192
@@ -136,8 +140,9 @@ def build_ops(torch, B):
     eidx = rows.unsqueeze(1).expand(NS, W)
     src_i = ri.view(-1)[: NS * W].view(NS, W).to(I32)
     dst_i = torch.zeros((ND, W), device=dev, dtype=I32)
-    add("scatter_add_i32_atomic", "a14", "scatter_add_atomic_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
-        lambda: B.tx_scatter_add_(dst_i, 0, eidx, src_i, True, None))
+    wsi32 = B.workspace(B.tx_scatter_add_workspace_bytes(dst_i, 0, eidx, src_i, True))
+    add("scatter_add_i32_atomic", "a14", "seg_rows_atomic_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
+        lambda: B.tx_scatter_add_(dst_i, 0, eidx, src_i, True, wsi32))
     dst_f = torch.zeros((ND, W), device=dev)
     wss = B.workspace(B.tx_scatter_add_workspace_bytes(dst_f, 0, eidx, src, True))
     add("scatter_add_f32_sorted", "a15", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,

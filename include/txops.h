@@ -182,7 +182,10 @@ tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t di
  * index[p]] += src[p].  self, index, src have the same ndim; index.size(d) <=
  * src.size(d) for all d and <= self.size(d) for d != dim; self.dtype ==
  * src.dtype.  index may be a stride-0 expanded view.  Integer dtypes use
- * device atomics (exact, order-free); bool ORs.  Float dtypes: with
+ * device atomics (exact, order-free); bool ORs.  When the index is a row id
+ * broadcast over the trailing dims and a workspace is given, int32 / int64
+ * rows are first grouped by destination so that one atomic is issued per run
+ * and column instead of one per element.  Float dtypes: with
  * deterministic != 0 the contributions are sorted by destination and summed in
  * a fixed order with fp32 accumulation (bitwise reproducible run to run); with
  * deterministic == 0, fp32 uses float atomics (fp16 / bf16 keep the sorted
@@ -210,9 +213,10 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
 /* Name of the kernel path the last call on this thread dispatched to
  * ("" if it launched nothing).  For tests and profiling. */
 const char* tx_last_path(void);
-/* Force a kernel path by name for the elementwise iterator ("" or NULL = automatic):
- * "vec", "tile", "generic".  Requests that a path cannot serve fall back to the
- * automatic choice.  Process-wide; meant for A/B profiling. */
+/* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
+ * "vec", "tile", "generic".  cumsum along a contiguous dim: "scan-lookback",
+ * "scan-carry".  Requests that a path cannot serve fall back to the automatic
+ * choice.  Process-wide; meant for A/B profiling. */
 void tx_force_path(const char* name);
 
 const char* tx_strerror(tx_status status);

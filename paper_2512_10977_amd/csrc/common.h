@@ -69,15 +69,10 @@ struct bf16 {
 
 __device__ __forceinline__ float bf16_to_float(bf16 h) { return __uint_as_float(((uint32_t)h.bits) << 16); }
 // round-to-nearest-even fp32 -> bf16; NaN stays NaN (quiet)
+// (gfx950 has a hardware conversion; the compiler selects it for the __bf16 cast)
 __device__ __forceinline__ bf16 float_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
   bf16 r;
-  if ((u & 0x7fffffffu) > 0x7f800000u) {
-    r.bits = (uint16_t)((u >> 16) | 0x0040u);
-  } else {
-    u += 0x7fffu + ((u >> 16) & 1u);
-    r.bits = (uint16_t)(u >> 16);
-  }
+  r.bits = __builtin_bit_cast(uint16_t, (__bf16)f);
   return r;
 }
 
@@ -130,6 +125,56 @@ template <int BYTES> struct VecAlign { static constexpr int value = BYTES >= 16 
 template <class T, int N> struct alignas(VecAlign<sizeof(T) * N>::value) Vec {
   T v[N];
 };
+
+// Whole-vector loads and stores.  `nt` marks the access as streaming (non-temporal):
+// data that is touched once should not displace lines other kernels may still want.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+template <class T, int N> __device__ __forceinline__ Vec<T, N> vec_load(const T* p, bool nt) {
+  constexpr int BYTES = sizeof(T) * N;
+  Vec<T, N> r;
+  if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+    for (int i = 0; i < BYTES / 16; ++i) {
+      const u32x4* q = (const u32x4*)p + i;
+      u32x4 c = nt ? __builtin_nontemporal_load(q) : *q;
+      __builtin_memcpy((char*)&r + 16 * i, &c, 16);
+    }
+  } else if constexpr (BYTES == 8) {
+    const u32x2* q = (const u32x2*)p;
+    u32x2 c = nt ? __builtin_nontemporal_load(q) : *q;
+    __builtin_memcpy(&r, &c, 8);
+  } else if constexpr (BYTES == 4) {
+    const uint32_t* q = (const uint32_t*)p;
+    uint32_t c = nt ? __builtin_nontemporal_load(q) : *q;
+    __builtin_memcpy(&r, &c, 4);
+  } else {
+    r = *(const Vec<T, N>*)p;
+  }
+  return r;
+}
+template <class T, int N> __device__ __forceinline__ void vec_store(T* p, const Vec<T, N>& v, bool nt) {
+  constexpr int BYTES = sizeof(T) * N;
+  if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+    for (int i = 0; i < BYTES / 16; ++i) {
+      u32x4 c;
+      __builtin_memcpy(&c, (const char*)&v + 16 * i, 16);
+      u32x4* q = (u32x4*)p + i;
+      if (nt) __builtin_nontemporal_store(c, q); else *q = c;
+    }
+  } else if constexpr (BYTES == 8) {
+    u32x2 c;
+    __builtin_memcpy(&c, &v, 8);
+    if (nt) __builtin_nontemporal_store(c, (u32x2*)p); else *(u32x2*)p = c;
+  } else if constexpr (BYTES == 4) {
+    uint32_t c;
+    __builtin_memcpy(&c, &v, 4);
+    if (nt) __builtin_nontemporal_store(c, (uint32_t*)p); else *(uint32_t*)p = c;
+  } else {
+    *(Vec<T, N>*)p = v;
+  }
+}
 
 // ---------------------------------------------------------------------------
 // division by a run-time constant (32-bit dividends), magic-number form:

@@ -32,8 +32,8 @@ template <class T> struct Elem {
   static constexpr bool dynamic = false;
   static constexpr int static_size = sizeof(T);
   __device__ __forceinline__ static T load(const char* base, int64_t idx, int) { return ((const T*)base)[idx]; }
-  template <int E> __device__ __forceinline__ static void load_vec(const char* base, int64_t idx, int, T (&out)[E]) {
-    Vec<T, E> v = *(const Vec<T, E>*)(base + idx * (int64_t)sizeof(T));
+  template <int E> __device__ __forceinline__ static void load_vec(const char* base, int64_t idx, int, T (&out)[E], bool nt) {
+    Vec<T, E> v = vec_load<T, E>((const T*)base + idx, nt);
 #pragma unroll
     for (int e = 0; e < E; ++e) out[e] = v.v[e];
   }
@@ -42,13 +42,13 @@ template <class T> struct Elem {
     Vec<T, E> v;
 #pragma unroll
     for (int e = 0; e < E; ++e) v.v[e] = in[e];
-    *(Vec<T, E>*)(base + idx * (int64_t)sizeof(T)) = v;
+    vec_store<T, E>((T*)base + idx, v, true);
   }
 };
 
 template <class S, class CT, int E>
-__device__ __forceinline__ void load_cvt_vec(const char* base, int64_t idx, CT (&out)[E]) {
-  Vec<S, E> v = *(const Vec<S, E>*)(base + idx * (int64_t)sizeof(S));
+__device__ __forceinline__ void load_cvt_vec(const char* base, int64_t idx, CT (&out)[E], bool nt) {
+  Vec<S, E> v = vec_load<S, E>((const S*)base + idx, nt);
 #pragma unroll
   for (int e = 0; e < E; ++e) out[e] = cvt<CT>(v.v[e]);
 }
@@ -57,7 +57,7 @@ __device__ __forceinline__ void store_cvt_vec(char* base, int64_t idx, const CT 
   Vec<S, E> v;
 #pragma unroll
   for (int e = 0; e < E; ++e) v.v[e] = cvt<S>(in[e]);
-  *(Vec<S, E>*)(base + idx * (int64_t)sizeof(S)) = v;
+  vec_store<S, E>((S*)base + idx, v, true);
 }
 
 template <> struct Elem<Dyn<float>> {
@@ -74,14 +74,14 @@ template <> struct Elem<Dyn<float>> {
       default: return (float)((const uint8_t*)b)[i];
     }
   }
-  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, float (&o)[E]) {
+  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, float (&o)[E], bool nt) {
     switch (dt) {
-      case TX_F32: load_cvt_vec<float, float, E>(b, i, o); break;
-      case TX_BF16: load_cvt_vec<bf16, float, E>(b, i, o); break;
-      case TX_F16: load_cvt_vec<f16, float, E>(b, i, o); break;
-      case TX_I64: load_cvt_vec<int64_t, float, E>(b, i, o); break;
-      case TX_I32: load_cvt_vec<int32_t, float, E>(b, i, o); break;
-      default: load_cvt_vec<uint8_t, float, E>(b, i, o); break;
+      case TX_F32: load_cvt_vec<float, float, E>(b, i, o, nt); break;
+      case TX_BF16: load_cvt_vec<bf16, float, E>(b, i, o, nt); break;
+      case TX_F16: load_cvt_vec<f16, float, E>(b, i, o, nt); break;
+      case TX_I64: load_cvt_vec<int64_t, float, E>(b, i, o, nt); break;
+      case TX_I32: load_cvt_vec<int32_t, float, E>(b, i, o, nt); break;
+      default: load_cvt_vec<uint8_t, float, E>(b, i, o, nt); break;
     }
   }
   __device__ __forceinline__ static void store(char* b, int64_t i, int dt, float v) {
@@ -111,11 +111,11 @@ template <> struct Elem<Dyn<int64_t>> {
       default: return ((const uint8_t*)b)[i];
     }
   }
-  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, int64_t (&o)[E]) {
+  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, int64_t (&o)[E], bool nt) {
     switch (dt) {
-      case TX_I64: load_cvt_vec<int64_t, int64_t, E>(b, i, o); break;
-      case TX_I32: load_cvt_vec<int32_t, int64_t, E>(b, i, o); break;
-      default: load_cvt_vec<uint8_t, int64_t, E>(b, i, o); break;
+      case TX_I64: load_cvt_vec<int64_t, int64_t, E>(b, i, o, nt); break;
+      case TX_I32: load_cvt_vec<int32_t, int64_t, E>(b, i, o, nt); break;
+      default: load_cvt_vec<uint8_t, int64_t, E>(b, i, o, nt); break;
     }
   }
   __device__ __forceinline__ static void store(char* b, int64_t i, int dt, int64_t v) {
@@ -154,9 +154,10 @@ template <class F> struct Shape {
   static constexpr int max_size = cmax(cmax(cmax(s0, s1), s2), s3);
   // elements per lane per vector: the narrowest operand moves 16 bytes
   static constexpr int E = dynamic ? 4 : (16 / min_size);
-  // vectors per lane: about 64 bytes of the widest operand in flight
+  // vectors per lane: one.  On this chip a streaming kernel is fastest with many small waves (a plain copy
+  // moves 6.5 TB/s with one 16-byte vector per lane and 5.8 TB/s with four)
   static constexpr int per_vec = E * max_size;
-  static constexpr int U = dynamic ? 2 : (per_vec >= 64 ? 1 : (64 / per_vec > 4 ? 4 : 64 / per_vec));
+  static constexpr int U = dynamic ? 2 : 1;
 };
 
 template <class F, class A, class B, class C>
@@ -173,6 +174,7 @@ template <int NOPS> struct VecArgs {
   char* data[NOPS];
   int dtype[NOPS];
   int inner_stride[NOPS];                    // 0 or 1 (operand 0 = out: always 1)
+  int stream[NOPS];                          // operand is read exactly once (no broadcast dim): non-temporal loads
   int nouter;
   FastDiv tiles_per_row;
   FastDiv osize[TX_MAX_DIMS - 1];            // outer sizes, outer -> inner
@@ -190,7 +192,7 @@ __device__ __forceinline__ void vec_fetch(const VecArgs<NOPS>& a, int o, int64_t
 #pragma unroll
       for (int e = 0; e < E; ++e) x[e] = v;
     } else if (valid == E) {
-      EL::template load_vec<E>(a.data[o], base + i, a.dtype[o], x);
+      EL::template load_vec<E>(a.data[o], base + i, a.dtype[o], x, a.stream[o] != 0);
     } else {
 #pragma unroll
       for (int e = 0; e < E; ++e)
@@ -380,6 +382,108 @@ __global__ __launch_bounds__(kBlock) void ew_tile_kernel(const F f, const TileAr
   }
 }
 
+// Vectorised tile kernel for functors whose operands all have the same static element size S (2, 4 or
+// 8 bytes): every global access is a 16-byte vector of V = 16/S elements.  A transposed operand is read
+// with lanes along r (its unit-stride dim), written element-wise into a padded LDS tile, and read back
+// transposed as V scalars per lane; the other operands and the output move as vectors along c.
+template <class F> struct TileVec {
+  static constexpr bool eligible =
+      !Shape<F>::dynamic && Shape<F>::min_size == Shape<F>::max_size && Shape<F>::min_size >= 2 &&
+      (F::NIN < 2 || static_size_of<typename F::In1>() == Shape<F>::min_size) &&
+      (F::NIN < 3 || static_size_of<typename F::In2>() == Shape<F>::min_size);
+  static constexpr int S = eligible ? Shape<F>::min_size : 4;
+  static constexpr int V = 16 / S;
+  static constexpr int T = S == 8 ? 32 : 64;            // tile edge in elements
+  static constexpr int PITCH = T + (S >= 4 ? 1 : 4 / S);  // LDS row pitch (odd number of 4-byte words for S <= 4)
+  static constexpr int LANES = T / V;                   // lanes that cover one tile row with vectors
+  static constexpr int ROWS_PER_PASS = kBlock / LANES;
+  static constexpr int PASSES = T / ROWS_PER_PASS;
+};
+
+template <class In, class F, int NOPS>
+__device__ __forceinline__ void tilev_stage(const TileArgs<NOPS>& a, int o, int64_t boff, int64_t r0, int64_t c0,
+                                            typename ValueOf<In>::type* lds) {
+  using TV = TileVec<F>;
+  using E = typename ValueOf<In>::type;
+  const int rv = threadIdx.x % TV::LANES, cl = threadIdx.x / TV::LANES;
+  const int64_t r = r0 + rv * TV::V;
+#pragma unroll
+  for (int k = 0; k < TV::PASSES; ++k) {
+    const int c = cl + TV::ROWS_PER_PASS * k;
+    if (r < a.rows && c0 + c < a.cols) {       // rows is a multiple of V on this path
+      Vec<E, TV::V> t = vec_load<E, TV::V>((const E*)a.data[o] + boff + r + (c0 + c) * a.stride_c[o], true);
+#pragma unroll
+      for (int j = 0; j < TV::V; ++j) lds[c * TV::PITCH + rv * TV::V + j] = t.v[j];
+    }
+  }
+}
+
+template <class In, class F, int NOPS>
+__device__ __forceinline__ void tilev_fetch(const TileArgs<NOPS>& a, int o, int64_t boff, int64_t r, int64_t c, int lr,
+                                            int lc, const typename ValueOf<In>::type* lds,
+                                            typename ValueOf<In>::type (&x)[TileVec<F>::V]) {
+  using TV = TileVec<F>;
+  using E = typename ValueOf<In>::type;
+  if (a.transposed[o]) {
+#pragma unroll
+    for (int j = 0; j < TV::V; ++j) x[j] = lds[(lc + j) * TV::PITCH + lr];
+  } else if (a.stride_c[o] == 1) {
+    Vec<E, TV::V> t = vec_load<E, TV::V>((const E*)a.data[o] + boff + r * a.stride_r[o] + c, a.stride_r[o] != 0);
+#pragma unroll
+    for (int j = 0; j < TV::V; ++j) x[j] = t.v[j];
+  } else {                                      // broadcast along c
+    const E v = ((const E*)a.data[o])[boff + r * a.stride_r[o]];
+#pragma unroll
+    for (int j = 0; j < TV::V; ++j) x[j] = v;
+  }
+}
+
+template <class F>
+__global__ __launch_bounds__(kBlock) void ew_tile_vec_kernel(const F f, const TileArgs<F::NIN + 1> a) {
+  using TV = TileVec<F>;
+  constexpr int NOPS = F::NIN + 1;
+  using V0 = typename ValueOf<typename F::In0>::type;
+  using V1 = typename ValueOf<typename F::In1>::type;
+  using V2 = typename ValueOf<typename F::In2>::type;
+  using VO = typename ValueOf<typename F::Out>::type;
+  __shared__ V0 l0[TV::T * TV::PITCH];
+  __shared__ V1 l1[F::NIN >= 2 ? TV::T * TV::PITCH : 1];
+  __shared__ V2 l2[F::NIN >= 3 ? TV::T * TV::PITCH : 1];
+  uint32_t rest, tc, batch, tr;
+  a.tiles_c.divmod(blockIdx.x, rest, tc);
+  a.tiles_r.divmod(rest, batch, tr);
+  const int64_t r0 = (int64_t)tr * TV::T, c0 = (int64_t)tc * TV::T;
+  int64_t boff[NOPS];
+#pragma unroll
+  for (int o = 0; o < NOPS; ++o) boff[o] = (int64_t)batch * a.stride_b[o];
+  if (a.transposed[1]) tilev_stage<typename F::In0, F>(a, 1, boff[1], r0, c0, l0);
+  if constexpr (F::NIN >= 2)
+    if (a.transposed[2]) tilev_stage<typename F::In1, F>(a, 2, boff[2], r0, c0, l1);
+  if constexpr (F::NIN >= 3)
+    if (a.transposed[3]) tilev_stage<typename F::In2, F>(a, 3, boff[3], r0, c0, l2);
+  __syncthreads();
+  const int cv = threadIdx.x % TV::LANES, rl = threadIdx.x / TV::LANES;
+  const int lc = cv * TV::V;
+  const int64_t c = c0 + lc;
+#pragma unroll
+  for (int k = 0; k < TV::PASSES; ++k) {
+    const int lr = rl + TV::ROWS_PER_PASS * k;
+    const int64_t r = r0 + lr;
+    if (r < a.rows && c < a.cols) {             // cols is a multiple of V on this path
+      V0 x0[TV::V];
+      V1 x1[TV::V];
+      V2 x2[TV::V];
+      tilev_fetch<typename F::In0, F>(a, 1, boff[1], r, c, lr, lc, l0, x0);
+      if constexpr (F::NIN >= 2) tilev_fetch<typename F::In1, F>(a, 2, boff[2], r, c, lr, lc, l1, x1);
+      if constexpr (F::NIN >= 3) tilev_fetch<typename F::In2, F>(a, 3, boff[3], r, c, lr, lc, l2, x2);
+      Vec<VO, TV::V> y;
+#pragma unroll
+      for (int j = 0; j < TV::V; ++j) y.v[j] = apply(f, x0[j], x1[j], x2[j]);
+      vec_store<VO, TV::V>((VO*)a.data[0] + boff[0] + r * a.stride_r[0] + c, y, true);
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // path selection + launch
 // ---------------------------------------------------------------------------
@@ -442,7 +546,11 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
       a.data[o] = it.op[o].data;
       a.dtype[o] = it.op[o].dtype;
       a.inner_stride[o] = (int)it.op[o].stride[in];
-      for (int d = 0; d < in; ++d) a.ostride[o][d] = it.op[o].stride[d];
+      a.stream[o] = a.inner_stride[o] == 1;
+      for (int d = 0; d < in; ++d) {
+        a.ostride[o][d] = it.op[o].stride[d];
+        if (it.op[o].stride[d] == 0) a.stream[o] = 0;
+      }
     }
     a.inner_stride[0] = 1;
     a.nouter = in;
@@ -469,6 +577,25 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     }
     a.rows = it.size[r];
     a.cols = it.size[c];
+    if constexpr (TileVec<F>::eligible) {
+      using TV = TileVec<F>;
+      bool ok = a.rows % TV::V == 0 && a.cols % TV::V == 0;
+      for (int o = 0; ok && o < NOPS; ++o) {
+        ok = aligned_to(a.data[o], 16) && (a.stride_b[o] * TV::S) % 16 == 0;
+        if (a.transposed[o]) ok = ok && (a.stride_c[o] * TV::S) % 16 == 0;
+        else if (a.stride_c[o] == 1) ok = ok && (a.stride_r[o] * TV::S) % 16 == 0;
+        else if (a.stride_c[o] != 0) ok = false;
+      }
+      const int64_t vtr = (a.rows + TV::T - 1) / TV::T, vtc = (a.cols + TV::T - 1) / TV::T;
+      const int64_t vnb = it.ndim == 3 ? it.size[0] : 1;
+      if (ok && vtr * vtc * vnb < (1ll << 31)) {
+        a.tiles_c = FastDiv((uint32_t)vtc);
+        a.tiles_r = FastDiv((uint32_t)vtr);
+        set_path("tile");
+        hipLaunchKernelGGL((ew_tile_vec_kernel<F>), dim3((unsigned)(vtr * vtc * vnb)), dim3(kBlock), 0, stream, f, a);
+        return check_launch("elementwise vector tile kernel");
+      }
+    }
     const int64_t tr = (a.rows + kTile - 1) / kTile, tc = (a.cols + kTile - 1) / kTile;
     const int64_t nb = it.ndim == 3 ? it.size[0] : 1;
     a.tiles_c = FastDiv((uint32_t)tc);
@@ -512,18 +639,42 @@ __device__ __forceinline__ float quantize(float v, int common) {
   return v;
 }
 
-struct OpExp { __device__ static float run(float x) { return expf(x); } };
-struct OpLog { __device__ static float run(float x) { return logf(x); } };
-struct OpSqrt { __device__ static float run(float x) { return sqrtf(x); } };
-struct OpSigmoid { __device__ static float run(float x) { return sigmoid_f32(x); } };
-struct OpTanh { __device__ static float run(float x) { return tanh_f32(x); } };
-struct OpGelu { __device__ static float run(float x) { return gelu_erf_f32(x); } };
+// run(): fp32 result within 2 ulp.  run_half(): for fp16 / bf16 results, which are rounded to 8-11 bits
+// anyway, plain fp32 compositions are accurate enough and several times cheaper than the binary64 forms.
+struct OpExp {
+  __device__ static float run(float x) { return expf(x); }
+  __device__ static float run_half(float x) { return expf(x); }
+};
+struct OpLog {
+  __device__ static float run(float x) { return logf(x); }
+  __device__ static float run_half(float x) { return logf(x); }
+};
+struct OpSqrt {
+  __device__ static float run(float x) { return sqrtf(x); }
+  __device__ static float run_half(float x) { return sqrtf(x); }
+};
+struct OpSigmoid {
+  __device__ static float run(float x) { return sigmoid_f32(x); }
+  __device__ static float run_half(float x) { return 1.0f / (1.0f + expf(-x)); }
+};
+struct OpTanh {
+  __device__ static float run(float x) { return tanh_f32(x); }
+  __device__ static float run_half(float x) { return tanhf(x); }
+};
+struct OpGelu {
+  __device__ static float run(float x) { return gelu_erf_f32(x); }
+  // x * erfc(-x / sqrt 2) / 2: erfc keeps its relative accuracy in the negative tail
+  __device__ static float run_half(float x) { return x * (0.5f * erfcf(-x * 0.70710678118654752440f)); }
+};
 
 // float math op on a statically typed float tensor (computes in fp32)
 template <class Op, class T> struct MathStatic {
   using Out = T; using In0 = T; using In1 = void; using In2 = void;
   static constexpr int NIN = 1;
-  __device__ __forceinline__ T operator()(T x) const { return cvt<T>(Op::run(cvt<float>(x))); }
+  __device__ __forceinline__ T operator()(T x) const {
+    if constexpr (sizeof(T) == 2) return cvt<T>(Op::run_half(cvt<float>(x)));
+    else return cvt<T>(Op::run(cvt<float>(x)));
+  }
 };
 // float math op on a bool / integer tensor: convert to fp32, fp32 result
 template <class Op> struct MathDyn {

@@ -326,6 +326,7 @@ __global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, 
 }
 
 constexpr int kChunk = 128;                 // sorted rows per wave
+constexpr int64_t kIntRowModeMin = 4096;    // integer row mode pays for its sort from about this many rows
 constexpr int kCombineWaves = 16;
 enum { kNone = 0, kEnd = 1, kThrough = 2 };
 
@@ -597,6 +598,98 @@ tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_bu
   return check_launch("radix sort");
 }
 
+// Integer row mode: rows are grouped by destination with the same sort, a wave adds up each run of a
+// 128-row chunk in registers and issues ONE atomic per destination element per run (integer addition is
+// associative, so runs that cross chunk boundaries may simply be flushed twice).  This cuts the atomic
+// count from one per source element to one per (run, column).
+template <class T, int VEC>
+__global__ __launch_bounds__(kBlock) void seg_rows_atomic_kernel(const SegRowArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t chunk = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+  if (chunk >= a.nchunks) return;
+  const int64_t j0 = chunk * kChunk;
+  const int cnt = (int)std::min<int64_t>(kChunk, a.n - j0);
+  const T* src = (const T*)a.src;
+  constexpr int kBatch = 8;
+  using UT = typename std::make_unsigned<T>::type;
+  for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
+    const int64_t col = cb + (int64_t)lane * VEC;
+    const bool active = col < a.width;
+    UT acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0;
+    uint32_t cur = a.keys[j0];
+    auto flush = [&](uint32_t key) {
+      if (!active) return;
+      T* d = (T*)a.self + (int64_t)key * a.self_row + col;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (acc[e] != 0) atomic_accumulate<T>(d + e, (T)acc[e]);
+    };
+    for (int e0 = 0; e0 < cnt; e0 += kBatch) {
+      uint32_t k[kBatch];
+      Vec<T, VEC> row[kBatch];
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int e = e0 + b;
+        if (e < cnt) {
+          k[b] = a.keys[j0 + e];
+          const uint32_t p = a.vals[j0 + e];
+          if (active) row[b] = vec_load<T, VEC>(src + (int64_t)p * a.src_row + col, true);
+        }
+      }
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        const int e = e0 + b;
+        if (e < cnt) {
+          if (k[b] != cur) {
+            flush(cur);
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] = 0;
+            cur = k[b];
+          }
+          if (active) {
+#pragma unroll
+            for (int q = 0; q < VEC; ++q) acc[q] += (UT)row[b].v[q];
+          }
+        }
+      }
+    }
+    flush(cur);
+  }
+}
+
+template <class T>
+tx_status scatter_rows_atomic(const ScatterPlan& p, const tx_tensor* self, const tx_tensor* index, const tx_tensor* src,
+                              char* ws, hipStream_t s) {
+  constexpr int V = 16 / sizeof(T);
+  uint32_t* keys0 = (uint32_t*)(ws + p.off_keys[0]);
+  uint32_t* vals0 = (uint32_t*)(ws + p.off_vals[0]);
+  const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
+  hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
+                     index->strides[0], p.n, keys0, vals0);
+  int cur;
+  tx_status rc = run_sort(p, ws, s, &cur);
+  if (rc) return rc;
+  SegRowArgs a;
+  memset(&a, 0, sizeof(a));
+  a.keys = (const uint32_t*)(ws + p.off_keys[cur]);
+  a.vals = (const uint32_t*)(ws + p.off_vals[cur]);
+  a.n = p.n;
+  a.nchunks = p.nchunks;
+  a.src = (const char*)src->data;
+  a.self = (char*)self->data;
+  a.src_row = src->strides[0];
+  a.self_row = self->strides[0];
+  a.width = p.width;
+  const bool al = p.width % V == 0 && (uintptr_t)src->data % 16 == 0 && (a.src_row * (int64_t)sizeof(T)) % 16 == 0;
+  const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
+  set_path("scatter-sort-atomic");
+  if (al) hipLaunchKernelGGL((seg_rows_atomic_kernel<T, V>), dim3(gb), dim3(kBlock), 0, s, a);
+  else hipLaunchKernelGGL((seg_rows_atomic_kernel<T, 1>), dim3(gb), dim3(kBlock), 0, s, a);
+  return check_launch("aggregated atomic row sum");
+}
+
 template <class T>
 tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int dim, const tx_tensor* index,
                                 const tx_tensor* src, char* ws, hipStream_t s) {
@@ -817,11 +910,14 @@ size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const 
                                       int deterministic) {
   int d;
   if (scatter_checks(self, dim, index, src, &d)) return 0;
-  if (!dtype_is_float(self->dtype) || numel(index) == 0) return 0;
+  if (numel(index) == 0) return 0;
+  const bool int_rows = (self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
+                        index->sizes[0] >= kIntRowModeMin;
+  if (!dtype_is_float(self->dtype) && !int_rows) return 0;
   if (!deterministic && self->dtype == TX_F32) return 0;
   ScatterPlan p;
   if (scatter_plan(self, d, index, src, &p)) return 0;
-  return p.bytes;
+  return int_rows ? p.off_part_a : p.bytes;            // the integer path needs only the sort buffers
 }
 
 tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
@@ -844,6 +940,16 @@ tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* i
       case TX_F32: return scatter_deterministic<float>(p, self, d, index, src, (char*)ws, s);
       case TX_BF16: return scatter_deterministic<bf16>(p, self, d, index, src, (char*)ws, s);
       default: return scatter_deterministic<f16>(p, self, d, index, src, (char*)ws, s);
+    }
+  }
+  // int32 / int64 with a broadcast row index: group rows by destination first, one atomic per run and column.
+  // Needs the sort buffers; without them (or for small inputs) fall through to one atomic per element.
+  if ((self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
+      index->sizes[0] >= kIntRowModeMin && strcmp(forced_path(), "scatter-atomic") != 0) {
+    ScatterPlan p;
+    if (!scatter_plan(self, d, index, src, &p) && ws && ws_bytes >= p.off_part_a && (uintptr_t)ws % 16 == 0) {
+      if (self->dtype == TX_I32) return scatter_rows_atomic<int32_t>(p, self, index, src, (char*)ws, s);
+      return scatter_rows_atomic<int64_t>(p, self, index, src, (char*)ws, s);
     }
   }
   if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "scatter_add_: more than 2^31 index elements");

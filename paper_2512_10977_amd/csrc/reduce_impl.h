@@ -140,12 +140,20 @@ template <class T> struct ArgmaxPolicy {
     return v1 > v2 || (v1 == v2 && i1 < i2);
   }
   __device__ static void merge(Acc& a, const Acc& b) { if (better(b.v, b.i, a.v, a.i)) a = b; }
+  // a lane meets its elements in increasing position, so within a lane a strict comparison keeps the
+  // earliest of equal values (and the first NaN) without looking at the index
   __device__ static void step(Acc& a, T x, int64_t pos, double) {
     V v = cvt<V>(x);
-    if (better(v, pos, a.v, a.i)) { a.v = v; a.i = pos; }
+    bool take;
+    if constexpr (flt) take = !(a.v != a.v) && (v > a.v || v != v);
+    else take = v > a.v;
+    if (take) { a.v = v; a.i = pos; }
   }
   __device__ static Acc shfl(const Acc& a, int m) { Acc r; r.v = shfl_xor(a.v, m); r.i = shfl_xor(a.i, m); return r; }
-  __device__ static void finish(const Acc& a, int64_t, double, double, double*, int64_t* i) { *i = a.i; }
+  // an untouched index means nothing exceeded the initial lowest value: every element equals it, the first one wins
+  __device__ static void finish(const Acc& a, int64_t, double, double, double*, int64_t* i) {
+    *i = a.i == 0x7fffffffffffffffll ? 0 : a.i;
+  }
 };
 
 // variance from sums of (x - K) and (x - K)^2 in binary64; K is the first
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const Args a) {
       if constexpr (VEC == 1) {
         P::step(acc, x[off], r, K);
       } else {
-        Vec<T, VEC> v = *(const Vec<T, VEC>*)(x + off);
+        Vec<T, VEC> v = vec_load<T, VEC>(x + off, true);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) P::step(acc, v.v[e], r + e, K);
       }
@@ -315,7 +323,7 @@ __global__ __launch_bounds__(kBlock) void reduce_cols_kernel(const Args a) {
 #pragma unroll 8
   for (int64_t r = begin; r < end; ++r) {
     const int64_t off = reduced_offset(a, r);
-    Vec<T, VEC> v = *(const Vec<T, VEC>*)(x + off);
+    Vec<T, VEC> v = vec_load<T, VEC>(x + off, true);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) P::step(acc[e], v.v[e], r, K[e]);
   }
@@ -326,18 +334,23 @@ __global__ __launch_bounds__(kBlock) void reduce_cols_kernel(const Args a) {
   }
 }
 
-// pass 2: one lane per output walks its S partials in order
+// pass 2: one wave per output; lanes stride over its S partials, then a shuffle tree
 template <class P>
 __global__ __launch_bounds__(kBlock) void reduce_final_kernel(const Args a) {
   using Acc = typename P::Acc;
-  const int64_t o = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (o >= a.nout) return;
-  int64_t xo, oo;
-  kept_offsets(a, o, &xo, &oo);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t o = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+  if (o >= a.nout) return;                               // whole waves leave together
   const Acc* p = (const Acc*)a.ws + o * a.split;
-  Acc acc = p[0];
-  for (int s = 1; s < a.split; ++s) P::merge(acc, p[s]);
-  emit<P>(a, acc, oo);
+  Acc acc = P::init();
+  for (int s = lane; s < a.split; s += kWave) P::merge(acc, p[s]);
+#pragma unroll
+  for (int m = kWave / 2; m >= 1; m >>= 1) { Acc other = P::shfl(acc, m); P::merge(acc, other); }
+  if (lane == 0) {
+    int64_t xo, oo;
+    kept_offsets(a, o, &xo, &oo);
+    emit<P>(a, acc, oo);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -386,7 +399,7 @@ template <class P> tx_status launch(const Plan& p, const tx_tensor* x, const tx_
   tx_status rc = check_launch("reduce kernel");
   if (rc) return rc;
   if (p.split > 1) {
-    hipLaunchKernelGGL((reduce_final_kernel<P>), dim3((unsigned)((p.nout + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+    hipLaunchKernelGGL((reduce_final_kernel<P>), dim3((unsigned)((p.nout + kBlock / kWave - 1) / (kBlock / kWave))), dim3(kBlock), 0,
                        stream, a);
     rc = check_launch("reduce finalise kernel");
   }

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs 
   for (int k = 0; k < CH; ++k) {
     const int64_t c = ((int64_t)k * kWave + lane) * VEC;
     if (c < a.len) {                      // len is a multiple of VEC on this path
-      Vec<T, VEC> t = *(const Vec<T, VEC>*)(x + c);
+      Vec<T, VEC> t = vec_load<T, VEC>(x + c, true);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) { v[k][e] = cvt<float>(t.v[e]); m = fmaxf(m, v[k][e]); }
     } else {
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs 
       Vec<O, VEC> t;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) t.v[e] = from_float<O>(a.is_log ? v[k][e] - ls : v[k][e] * inv);
-      *(Vec<O, VEC>*)(out + c) = t;
+      vec_store<O, VEC>(out + c, t, true);
     }
   }
 }
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs 
   for (int k = 0; k < kNV; ++k) {
     const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
     if (c + VEC <= left) {
-      Vec<T, VEC> tv = *(const Vec<T, VEC>*)(x + c);
+      Vec<T, VEC> tv = vec_load<T, VEC>(x + c, true);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] = cvt<Acc>(tv.v[e]);
     } else {
@@ -434,11 +434,93 @@ __global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs 
       Vec<O, VEC> tv;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) tv.v[e] = cvt<O>((Acc)(v[k][e] + add));
-      *(Vec<O, VEC>*)(out + c) = tv;
+      vec_store<O, VEC>(out + c, tv, true);
     } else {
 #pragma unroll
       for (int e = 0; e < VEC; ++e)
         if (c + e < left) out[c + e] = cvt<O>((Acc)(v[k][e] + add));
+    }
+  }
+}
+
+// Row-carry scan: one workgroup walks a whole row tile by tile and carries the running total in registers.
+// No inter-workgroup traffic at all, so it is the better choice whenever there are enough rows to fill the
+// chip; the next tile's loads are issued before the current tile is scanned.
+template <class T, class O, class Acc, int VEC>
+__global__ __launch_bounds__(kBlock) void cumsum_carry_kernel(const ScanArgs a) {
+  constexpr int kTileElems = kBlock * kNV * VEC;
+  constexpr int kWaves = kBlock / kWave;
+  __shared__ Acc wave_tot[2][kNV][kWaves];
+  const int64_t row = blockIdx.x;
+  const T* x = (const T*)a.x + row * a.xrow;
+  O* out = (O*)a.out + row * a.orow;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  Acc carry = Acc(0);
+  Acc v[kNV][VEC], nxt[kNV][VEC];
+
+  auto fetch = [&](int64_t t, Acc (&dst)[kNV][VEC]) {
+    const int64_t left = a.len - t * kTileElems;
+    const T* xt = x + t * kTileElems;
+#pragma unroll
+    for (int k = 0; k < kNV; ++k) {
+      const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+      if (c + VEC <= left) {
+        Vec<T, VEC> tv = vec_load<T, VEC>(xt + c, true);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[k][e] = cvt<Acc>(tv.v[e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) dst[k][e] = (c + e < left) ? cvt<Acc>(xt[c + e]) : Acc(0);
+      }
+    }
+  };
+
+  fetch(0, nxt);
+  for (int64_t t = 0; t < a.tiles_per_row; ++t) {
+#pragma unroll
+    for (int k = 0; k < kNV; ++k)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[k][e] = nxt[k][e];
+    if (t + 1 < a.tiles_per_row) fetch(t + 1, nxt);
+    const int buf = (int)(t & 1);
+    Acc excl[kNV];
+#pragma unroll
+    for (int k = 0; k < kNV; ++k) {
+#pragma unroll
+      for (int e = 1; e < VEC; ++e) v[k][e] += v[k][e - 1];
+      const Acc incl = wave_inclusive(v[k][VEC - 1]);
+      Acc up = shfl_up(incl, 1);
+      excl[k] = lane == 0 ? Acc(0) : up;
+      if (lane == kWave - 1) wave_tot[buf][k][w] = incl;
+    }
+    __syncthreads();                       // one barrier per tile: the two LDS buffers alternate
+    Acc running = carry;
+    Acc base[kNV];
+#pragma unroll
+    for (int k = 0; k < kNV; ++k) {
+#pragma unroll
+      for (int ww = 0; ww < kWaves; ++ww) {
+        if (ww == w) base[k] = running;
+        running += wave_tot[buf][k][ww];
+      }
+    }
+    carry = running;
+    const int64_t left = a.len - t * kTileElems;
+    O* ot = out + t * kTileElems;
+#pragma unroll
+    for (int k = 0; k < kNV; ++k) {
+      const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+      const Acc add = base[k] + excl[k];
+      if (c + VEC <= left) {
+        Vec<O, VEC> tv;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) tv.v[e] = cvt<O>((Acc)(v[k][e] + add));
+        vec_store<O, VEC>(ot + c, tv, true);
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (c + e < left) ot[c + e] = cvt<O>((Acc)(v[k][e] + add));
+      }
     }
   }
 }
@@ -512,6 +594,18 @@ tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void*
     a.orow = p.orow;
     a.tiles_per_row = p.tiles_per_row;
     a.total_tiles = p.total_tiles;
+    // enough rows to fill the chip (4 per CU): one workgroup per row with a register carry; else look-back
+    bool carry = p.rows >= 1024 || p.tiles_per_row == 1;
+    if (!strcmp(forced_path(), "scan-lookback")) carry = false;
+    if (!strcmp(forced_path(), "scan-carry")) carry = true;
+    if (carry) {
+      set_path(p.vec > 1 ? "scan-carry" : "scan-carry-scalar");
+      if (p.vec > 1)
+        hipLaunchKernelGGL((cumsum_carry_kernel<T, O, Acc, V>), dim3((unsigned)p.rows), dim3(kBlock), 0, stream, a);
+      else
+        hipLaunchKernelGGL((cumsum_carry_kernel<T, O, Acc, 1>), dim3((unsigned)p.rows), dim3(kBlock), 0, stream, a);
+      return check_launch("cumsum row-carry kernel");
+    }
     const int64_t words = (int64_t)(p.ws_bytes / 8);
     hipLaunchKernelGGL(scan_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
                        (unsigned long long*)ws, words);

@@ -190,6 +190,12 @@ def test_path_selection():
     assert check_binary("add", I.make_view((n, n), F32, "step2_outer", seed=133), a) == "vec"
     assert check_binary("add", I.make_view((n, n), F32, "expand_row", seed=134), a) == "vec"
     assert check_binary("add", I.make_view((n, n), F32, "expand_col", seed=135), a) == "vec"
+    for dt, shp in [(BF16, (5, 264, 328)), (I64, (3, 130, 258)), (F32, (2, 516, 260)), (F16, (1, 72, 1032))]:
+        v = I.make_view(shp, dt, "contig", seed=138).transpose(1, 2)                 # 16-byte-granular: vector tiles
+        w = I.make_view((shp[0], shp[2], shp[1]), dt, "contig", seed=139)
+        assert check_binary("add", v, w, what="vector tile") == "tile"
+        assert check_binary("maximum", w, v, what="vector tile, transposed second") == "tile"
+        assert check_binary("mul", v, v, what="vector tile, both transposed", layout="contig") == "tile"
     b3 = I.make_view((6, 200, 300), BF16, "contig", seed=136).transpose(1, 2)       # batched transpose
     assert check_binary("mul", b3, I.make_view((6, 300, 200), BF16, "contig", seed=137)) == "tile"
 

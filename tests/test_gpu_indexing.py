@@ -198,7 +198,12 @@ def test_scatter_add_full_size(big_src):
     assert check_scatter_add(dst, 0, idx, big_src, what="fp32 full") == "scatter-sort-rows"
     src_i = I.integers((1048576, 256), -1000, 1000, seed=7, dtype=I32)
     dst_i = I.integers((65536, 256), -1000, 1000, seed=8, dtype=I32)
-    assert check_scatter_add(dst_i, 0, idx, src_i, what="int32 full") == "scatter-atomic"
+    assert check_scatter_add(dst_i, 0, idx, src_i, what="int32 full") == "scatter-sort-atomic"
+    B.tx_force_path("scatter-atomic")          # the same workload with one atomic per element
+    try:
+        assert check_scatter_add(dst_i, 0, idx, src_i, what="int32 full, plain atomics") == "scatter-atomic"
+    finally:
+        B.tx_force_path(None)
     # materialised index, one Zipf draw per element (general path)
     full = I.zipf_rows(131072 * 256, 65536, 1.1, seed=9).reshape(131072, 256)
     check_scatter_add(dst_i, 0, full, src_i[:131072], what="int32 materialised")

@@ -47,7 +47,7 @@ def check_cumsum(x_cpu, dim=-1, out_dtype=None, what=""):
         xd = torch.where(xd.isfinite(), xd, torch.zeros_like(xd))
         scale = (xd * xd).cumsum(dim if x_cpu.dim() else 0).sqrt() if x_cpu.dim() else xd.abs()
         assert_rel(out, want, 1e-5 if want.dtype == F32 else 1e-2, scale, what)
-    if ws is not None:
+    if ws is not None and used.startswith("scan-lookback"):
         assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
     return used
 
@@ -111,8 +111,25 @@ def test_cumsum_shapes_and_paths():
         paths.add(check_cumsum(I.make_view((30, 257), dt, "transposed", seed=311, std=1.0), -1, what="transposed"))
         paths.add(check_cumsum(I.make_view((30, 2048), dt, "step2_outer", seed=312, std=1.0), -1, what="step2_outer"))
         paths.add(check_cumsum(I.make_view((30, 256), dt, "step2_inner", seed=313, std=1.0), -1, what="step2_inner"))
-    assert {"scan-lookback", "scan-lookback-scalar", "scan-strided"} <= paths, paths
+    assert {"scan-lookback", "scan-lookback-scalar", "scan-carry", "scan-carry-scalar", "scan-strided"} <= paths, paths
     check_cumsum(I.cumsum_input((16, 9000), BF16, seed=314), -1, out_dtype=F32, what="fp32 out")
+
+
+def test_cumsum_both_row_kernels_agree_with_oracle():
+    for dt in (F32, I64, BF16):
+        x = I.cumsum_input((1500, 9000), dt, seed=317)
+        assert check_cumsum(x, -1).startswith("scan-carry")
+        B.tx_force_path("scan-lookback")
+        try:
+            assert check_cumsum(x, -1).startswith("scan-lookback")
+        finally:
+            B.tx_force_path(None)
+        y = I.cumsum_input((3, 50000), dt, seed=318)
+        B.tx_force_path("scan-carry")
+        try:
+            assert check_cumsum(y, -1).startswith("scan-carry")
+        finally:
+            B.tx_force_path(None)
 
 
 def test_cumsum_many_tiles_per_row_repeated():
@@ -154,4 +171,9 @@ def test_cumsum_edges_and_errors():
 @pytest.mark.parametrize("dt", [F32, I64])
 def test_cumsum_full_size(dt):
     x = I.cumsum_input((4096, 65536), dt, seed=3)
-    assert check_cumsum(x, -1) == "scan-lookback"
+    assert check_cumsum(x, -1) == "scan-carry"           # 4096 rows fill the chip: one workgroup per row
+    B.tx_force_path("scan-lookback")                     # the same workload through the single-pass look-back scan
+    try:
+        assert check_cumsum(x, -1) == "scan-lookback"
+    finally:
+        B.tx_force_path(None)
