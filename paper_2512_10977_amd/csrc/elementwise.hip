@@ -152,12 +152,15 @@ template <class F> struct Shape {
   static constexpr int cmax(int a, int b) { return a > b ? a : b; }
   static constexpr int min_size = cmin(cmin(cmin(s0 ? s0 : 16, s1), s2), s3);
   static constexpr int max_size = cmax(cmax(cmax(s0, s1), s2), s3);
-  // elements per lane per vector: the narrowest operand moves 16 bytes
-  static constexpr int E = dynamic ? 4 : (16 / min_size);
+  // elements per lane per vector: the WIDEST operand moves 16 bytes, so every access of a wave is one
+  // contiguous run (narrower operands move 2-8 bytes per lane, still fully coalesced).  Letting the
+  // narrowest operand set the width made the wide operands 64-byte-strided per instruction, which halves
+  // the throughput of streaming loads.
+  static constexpr int E = dynamic ? 4 : (max_size >= 16 ? 1 : 16 / max_size);
   // vectors per lane: one.  On this chip a streaming kernel is fastest with many small waves (a plain copy
   // moves 6.5 TB/s with one 16-byte vector per lane and 5.8 TB/s with four)
   static constexpr int per_vec = E * max_size;
-  static constexpr int U = dynamic ? 2 : 1;
+  static constexpr int U = 1;
 };
 
 template <class F, class A, class B, class C>
@@ -530,11 +533,18 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
   constexpr int E = Shape<F>::E, U = Shape<F>::U;
   const char* forced = forced_path();
   const int in = it.ndim - 1;
-  bool can_vec = vec_path_ok<F>(it, E);
+  // run-time dtypes: the widest operand actually present sets the vector width (2 elements for 8-byte operands)
+  int e_rt = E;
+  if constexpr (Shape<F>::dynamic) {
+    int widest = 1;
+    for (int o = 0; o < it.nops; ++o) widest = std::max(widest, dtype_size(it.op[o].dtype));
+    e_rt = widest >= 8 ? 2 : 4;
+  }
+  bool can_vec = vec_path_ok<F>(it, e_rt);
   constexpr int kTile = tile_edge<F>();
   bool can_tile = tile_path_ok(it, kTile);
   // automatic choice: vec unless rows are too short to fill a wave's worth of vectors
-  bool use_vec = can_vec && (it.ndim == 1 || it.size[in] >= 64 * E);
+  bool use_vec = can_vec && (it.ndim == 1 || it.size[in] >= 64 * e_rt);
   bool use_tile = !use_vec && can_tile;
   if (!strcmp(forced, "vec") && can_vec) { use_vec = true; use_tile = false; }
   if (!strcmp(forced, "tile") && can_tile) { use_vec = false; use_tile = true; }
@@ -557,11 +567,17 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     int64_t outer = 1;
     for (int d = 0; d < in; ++d) { a.osize[d] = FastDiv((uint32_t)it.size[d]); outer *= it.size[d]; }
     a.n0 = it.size[in];
-    const int64_t tile = (int64_t)kBlock * E * U;
+    const int64_t tile = (int64_t)kBlock * e_rt * U;
     const int64_t tiles = (a.n0 + tile - 1) / tile;
     a.tiles_per_row = FastDiv((uint32_t)tiles);
     set_path("vec");
-    hipLaunchKernelGGL((ew_vec_kernel<F, E, U>), dim3((unsigned)(outer * tiles)), dim3(kBlock), 0, stream, f, a);
+    const dim3 grid((unsigned)(outer * tiles));
+    if constexpr (Shape<F>::dynamic) {
+      if (e_rt == 2) hipLaunchKernelGGL((ew_vec_kernel<F, 2, U>), grid, dim3(kBlock), 0, stream, f, a);
+      else hipLaunchKernelGGL((ew_vec_kernel<F, 4, U>), grid, dim3(kBlock), 0, stream, f, a);
+    } else {
+      hipLaunchKernelGGL((ew_vec_kernel<F, E, U>), grid, dim3(kBlock), 0, stream, f, a);
+    }
     return check_launch("elementwise vec kernel");
   }
   if (use_tile) {

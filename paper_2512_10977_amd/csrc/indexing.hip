@@ -183,8 +183,9 @@ __global__ __launch_bounds__(kBlock) void scatter_keys_kernel(const ElemArgs a, 
 }
 // keys for the row mode: the row id of every source row
 __global__ __launch_bounds__(kBlock) void row_keys_kernel(const char* index, int is64, int64_t istride, int64_t n,
-                                                          uint32_t* keys, uint32_t* vals) {
+                                                          uint32_t* keys, uint32_t* vals, unsigned int* counter) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i == 0 && counter) *counter = 0u;      // start-list length for the row-mode combine pass
   if (i >= n) return;
   keys[i] = (uint32_t)load_index(index, i * istride, is64);
   vals[i] = (uint32_t)i;
@@ -327,7 +328,8 @@ __global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, 
 
 constexpr int kChunk = 128;                 // sorted rows per wave
 constexpr int64_t kIntRowModeMin = 4096;    // integer row mode pays for its sort from about this many rows
-constexpr int kCombineWaves = 16;
+constexpr int kCombineWaves = 4;
+constexpr int kCombineBlocks = 2048;
 enum { kNone = 0, kEnd = 1, kThrough = 2 };
 
 struct SegRowArgs {
@@ -341,57 +343,92 @@ struct SegRowArgs {
   float* part_a;                 // [nchunks][width] piece that continues from the previous chunk
   float* part_b;                 // [nchunks][width] piece that continues into the next chunk
   uint8_t* flag_a;               // kNone / kEnd / kThrough
-  uint8_t* flag_b;               // 0 / 1
-  uint32_t* key_b;
+  uint32_t* key_b;               // destination row of the chunk's start piece
+  uint32_t* start_list;          // chunks that hold the start piece of a run that goes on
+  unsigned int* nstart;          // length of start_list (cleared by row_keys_kernel)
 };
 
-template <class T, int VEC>
-__device__ __forceinline__ void seg_flush(const SegRowArgs& a, int64_t chunk, uint32_t key, const float (&acc)[VEC],
-                                          int64_t col, bool active, bool from_before, bool to_after) {
-  if (!active) return;
-  if (!from_before && !to_after) {
-    T* d = (T*)a.self + (int64_t)key * a.self_row + col;
-    Vec<T, VEC> t = *(Vec<T, VEC>*)d;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) t.v[e] = cvt<T>(cvt<float>(t.v[e]) + acc[e]);
-    *(Vec<T, VEC>*)d = t;
-  } else {
-    float* p = (from_before ? a.part_a : a.part_b) + chunk * a.width + col;
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) p[e] = acc[e];
-  }
-}
-
-template <class T, int VEC>
+// Segmented row sums over sorted (destination row, source row) pairs.  One wave owns a chunk of 128
+// consecutive pairs.  The wave first reads its 128 keys and source-row ids with two coalesced loads each
+// and hands them out with readlane, so the row loads never wait on an index load.  Rows are fetched in
+// batches of 8 non-temporal 16-byte-per-lane loads; where a run begins inside the batch, the destination
+// row is fetched in the same batch so that finishing the run costs no extra round trip.
+//   ATOMIC == false (floating dtypes): fp32 accumulation in a fixed order.  A run that lies inside the
+//     chunk updates self directly; the pieces of a run that crosses chunk boundaries are parked in
+//     part_a / part_b and added by seg_combine_kernel in chunk order.
+//   ATOMIC == true (int32 / int64): every finished piece is added with one atomic per element.
+template <class T, int VEC, bool ATOMIC>
 __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
+  using Acc = typename std::conditional<ATOMIC, typename std::make_unsigned<
+                  typename std::conditional<ATOMIC, T, int>::type>::type, float>::type;
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t chunk = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+  const int64_t chunk = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   if (chunk >= a.nchunks) return;
   const int64_t j0 = chunk * kChunk;
   const int cnt = (int)std::min<int64_t>(kChunk, a.n - j0);
-  const uint32_t first_key = a.keys[j0], last_key = a.keys[j0 + cnt - 1];
-  const bool from_before = j0 > 0 && a.keys[j0 - 1] == first_key;
-  const bool to_after = j0 + cnt < a.n && a.keys[j0 + cnt] == last_key;
+  // lane l holds entries l and 64 + l of the chunk
+  uint32_t kreg[2], vreg[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int e = h * kWave + lane;
+    kreg[h] = e < cnt ? a.keys[j0 + e] : 0u;
+    vreg[h] = e < cnt ? a.vals[j0 + e] : 0u;
+  }
+  auto key_at = [&](int e) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)(e < kWave ? kreg[0] : kreg[1]), e & (kWave - 1)); };
+  auto val_at = [&](int e) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)(e < kWave ? vreg[0] : vreg[1]), e & (kWave - 1)); };
+  const uint32_t first_key = key_at(0), last_key = key_at(cnt - 1);
+  bool from_before = false, to_after = false;
+  if constexpr (!ATOMIC) {
+    from_before = j0 > 0 && a.keys[j0 - 1] == first_key;
+    to_after = j0 + cnt < a.n && a.keys[j0 + cnt] == last_key;
+  }
   const T* src = (const T*)a.src;
   constexpr int kBatch = 8;
   for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
     const int64_t col = cb + (int64_t)lane * VEC;
     const bool active = col < a.width;
-    float acc[VEC];
+    Acc acc[VEC];
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+    for (int e = 0; e < VEC; ++e) acc[e] = Acc(0);
     uint32_t cur = first_key;
     bool first_piece = true;
+    Vec<T, VEC> cur_self;                      // destination row of the run being summed (ATOMIC == false)
+#pragma unroll
+    for (int q = 0; q < VEC; ++q) cur_self.v[q] = T();
+
+    auto flush = [&](uint32_t key, bool fb, bool ta) {
+      if (!active) return;
+      if constexpr (ATOMIC) {
+        T* d = (T*)a.self + (int64_t)key * a.self_row + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (acc[e] != 0) atomic_accumulate<T>(d + e, (T)acc[e]);
+      } else if (!fb && !ta) {
+        Vec<T, VEC> t;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) t.v[e] = cvt<T>(cvt<float>(cur_self.v[e]) + (float)acc[e]);
+        vec_store<T, VEC>((T*)a.self + (int64_t)key * a.self_row + col, t, false);
+      } else {
+        float* p = (fb ? a.part_a : a.part_b) + chunk * a.width + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) p[e] = (float)acc[e];
+      }
+    };
+
     for (int e0 = 0; e0 < cnt; e0 += kBatch) {
       uint32_t k[kBatch];
-      Vec<T, VEC> row[kBatch];
+      Vec<T, VEC> row[kBatch], dst[kBatch];
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
         const int e = e0 + b;
         if (e < cnt) {
-          k[b] = a.keys[j0 + e];
-          const uint32_t p = a.vals[j0 + e];
-          if (active) row[b] = *(const Vec<T, VEC>*)(src + (int64_t)p * a.src_row + col);
+          k[b] = key_at(e);
+          const uint32_t p = val_at(e);
+          if (active) row[b] = vec_load<T, VEC>(src + (int64_t)p * a.src_row + col, true);
+          if constexpr (!ATOMIC) {
+            const bool starts = e == 0 ? !from_before : k[b] != key_at(e - 1);
+            if (starts && active) dst[b] = vec_load<T, VEC>((const T*)a.self + (int64_t)k[b] * a.self_row + col, false);
+          }
         }
       }
 #pragma unroll
@@ -399,85 +436,95 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
         const int e = e0 + b;
         if (e < cnt) {
           if (k[b] != cur) {
-            seg_flush<T, VEC>(a, chunk, cur, acc, col, active, first_piece && from_before, false);
+            flush(cur, first_piece && from_before, false);
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] = 0.0f;
+            for (int q = 0; q < VEC; ++q) acc[q] = Acc(0);
             cur = k[b];
             first_piece = false;
+            if constexpr (!ATOMIC) cur_self = dst[b];
+          } else if constexpr (!ATOMIC) {
+            if (e == 0 && !from_before) cur_self = dst[b];
           }
           if (active) {
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] += cvt<float>(row[b].v[q]);
+            for (int q = 0; q < VEC; ++q) acc[q] += cvt<Acc>(row[b].v[q]);
           }
         }
       }
     }
-    seg_flush<T, VEC>(a, chunk, cur, acc, col, active, first_piece && from_before, to_after);
+    flush(cur, first_piece && from_before, to_after);
   }
-  if (lane == 0) {
-    // first piece continues from before: END if it stops inside this chunk, THROUGH if the whole chunk is one run that goes on
-    const bool single = first_key == last_key;
-    a.flag_a[chunk] = from_before ? ((single && to_after) ? kThrough : kEnd) : kNone;
-    const bool start = to_after && !(single && from_before);
-    a.flag_b[chunk] = start ? 1 : 0;
-    a.key_b[chunk] = last_key;
+  if constexpr (!ATOMIC) {
+    if (lane == 0) {
+      // first piece continues from before: END if it stops inside this chunk, THROUGH if the whole chunk is one run that goes on
+      const bool single = first_key == last_key;
+      a.flag_a[chunk] = from_before ? ((single && to_after) ? kThrough : kEnd) : kNone;
+      const bool start = to_after && !(single && from_before);
+      a.key_b[chunk] = last_key;
+      if (start) a.start_list[atomicAdd(a.nstart, 1u)] = (uint32_t)chunk;
+    }
   }
 }
 
-// one workgroup per chunk that STARTS a run continuing into later chunks: adds, in chunk order,
-// the start piece and the continuation pieces of the following chunks, then updates self once
+// For every chunk that STARTS a run continuing into later chunks: add, in chunk order, the start piece and
+// the continuation pieces of the following chunks, then update self once.  A fixed number of 16-wave
+// workgroups walk the start list; each run is handled by one workgroup whose waves take contiguous
+// sub-ranges of the pieces and are then added in wave order, so the order of additions depends only on
+// the data.
 template <class T, int VEC>
 __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(const SegRowArgs a) {
   __shared__ long long end_chunk;
   __shared__ float sub[kCombineWaves][kWave * VEC];
-  const int64_t c = blockIdx.x;
-  if (!a.flag_b[c]) return;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-  if (threadIdx.x == 0) end_chunk = a.nchunks - 1;
-  __syncthreads();
-  // first chunk after c whose continuation piece is not THROUGH
-  for (int64_t base = c + 1; base < a.nchunks; base += kCombineWaves * kWave) {
-    const int64_t i = base + threadIdx.x;
-    const bool stop = i < a.nchunks && a.flag_a[i] != kThrough;
-    const bool any = __syncthreads_or(stop);
-    if (stop) atomicMin((unsigned long long*)&end_chunk, (unsigned long long)i);
-    if (any) break;
-  }
-  __syncthreads();
-  const int64_t cend = end_chunk;
-  const int64_t nparts = cend - c;                       // continuation pieces c+1 .. cend
-  const int64_t per = (nparts + kCombineWaves - 1) / kCombineWaves;
-  const int64_t p0 = c + 1 + (int64_t)w * per;
-  const int64_t p1 = std::min<int64_t>(p0 + per, cend + 1);
-  const uint32_t key = a.key_b[c];
-  for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
-    const int64_t col = cb + (int64_t)lane * VEC;
-    const bool active = col < a.width;
-    float acc[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-    if (active) {
-#pragma unroll 8
-      for (int64_t p = p0; p < p1; ++p) {
-        const float* src = a.part_a + p * a.width + col;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += src[e];
-      }
-    }
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) sub[w][lane * VEC + e] = acc[e];
+  const unsigned int nstart = *a.nstart;
+  for (unsigned int s = blockIdx.x; s < nstart; s += gridDim.x) {
+    const int64_t c = a.start_list[s];
+    if (threadIdx.x == 0) end_chunk = a.nchunks - 1;
     __syncthreads();
-    if (w == 0 && active) {
-      const float* b = a.part_b + c * a.width + col;
-      T* d = (T*)a.self + (int64_t)key * a.self_row + col;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        float t = b[e];
-        for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
-        d[e] = cvt<T>(cvt<float>(d[e]) + t);
-      }
+    // first chunk after c whose continuation piece is not THROUGH
+    for (int64_t base = c + 1; base < a.nchunks; base += kCombineWaves * kWave) {
+      const int64_t i = base + threadIdx.x;
+      const bool stop = i < a.nchunks && a.flag_a[i] != kThrough;
+      const bool any = __syncthreads_or(stop);
+      if (stop) atomicMin((unsigned long long*)&end_chunk, (unsigned long long)i);
+      if (any) break;
     }
     __syncthreads();
+    const int64_t cend = end_chunk;
+    const int64_t nparts = cend - c;                       // continuation pieces c+1 .. cend
+    const int64_t per = (nparts + kCombineWaves - 1) / kCombineWaves;
+    const int64_t p0 = c + 1 + (int64_t)w * per;
+    const int64_t p1 = std::min<int64_t>(p0 + per, cend + 1);
+    const uint32_t key = a.key_b[c];
+    for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
+      const int64_t col = cb + (int64_t)lane * VEC;
+      const bool active = col < a.width;
+      float acc[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+      if (active) {
+#pragma unroll 16
+        for (int64_t p = p0; p < p1; ++p) {
+          const float* src = a.part_a + p * a.width + col;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) acc[e] += src[e];
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sub[w][lane * VEC + e] = acc[e];
+      __syncthreads();
+      if (w == 0 && active) {
+        const float* b = a.part_b + c * a.width + col;
+        T* d = (T*)a.self + (int64_t)key * a.self_row + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          float t = b[e];
+          for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
+          d[e] = cvt<T>(cvt<float>(d[e]) + t);
+        }
+      }
+      __syncthreads();
+    }
   }
 }
 
@@ -507,7 +554,8 @@ struct ScatterPlan {
   int passes;
   int nblocks;          // sort workgroups
   int64_t nchunks;
-  size_t off_keys[2], off_vals[2], off_hist, off_totals, off_part_a, off_part_b, off_flag_a, off_flag_b, off_key_b;
+  size_t off_keys[2], off_vals[2], off_hist, off_totals, off_part_a, off_part_b, off_flag_a, off_key_b, off_start_list,
+      off_counter;
   size_t bytes;
 };
 
@@ -555,8 +603,9 @@ tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, c
     p->off_part_a = o; o = align_up(o + (size_t)p->nchunks * p->width * 4, 256);
     p->off_part_b = o; o = align_up(o + (size_t)p->nchunks * p->width * 4, 256);
     p->off_flag_a = o; o = align_up(o + (size_t)p->nchunks, 256);
-    p->off_flag_b = o; o = align_up(o + (size_t)p->nchunks, 256);
     p->off_key_b = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
+    p->off_start_list = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
+    p->off_counter = o; o += 256;
   }
   p->bytes = o;
   return TX_OK;
@@ -602,63 +651,6 @@ tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_bu
 // 128-row chunk in registers and issues ONE atomic per destination element per run (integer addition is
 // associative, so runs that cross chunk boundaries may simply be flushed twice).  This cuts the atomic
 // count from one per source element to one per (run, column).
-template <class T, int VEC>
-__global__ __launch_bounds__(kBlock) void seg_rows_atomic_kernel(const SegRowArgs a) {
-  const int lane = threadIdx.x & (kWave - 1);
-  const int64_t chunk = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
-  if (chunk >= a.nchunks) return;
-  const int64_t j0 = chunk * kChunk;
-  const int cnt = (int)std::min<int64_t>(kChunk, a.n - j0);
-  const T* src = (const T*)a.src;
-  constexpr int kBatch = 8;
-  using UT = typename std::make_unsigned<T>::type;
-  for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
-    const int64_t col = cb + (int64_t)lane * VEC;
-    const bool active = col < a.width;
-    UT acc[VEC];
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = 0;
-    uint32_t cur = a.keys[j0];
-    auto flush = [&](uint32_t key) {
-      if (!active) return;
-      T* d = (T*)a.self + (int64_t)key * a.self_row + col;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (acc[e] != 0) atomic_accumulate<T>(d + e, (T)acc[e]);
-    };
-    for (int e0 = 0; e0 < cnt; e0 += kBatch) {
-      uint32_t k[kBatch];
-      Vec<T, VEC> row[kBatch];
-#pragma unroll
-      for (int b = 0; b < kBatch; ++b) {
-        const int e = e0 + b;
-        if (e < cnt) {
-          k[b] = a.keys[j0 + e];
-          const uint32_t p = a.vals[j0 + e];
-          if (active) row[b] = vec_load<T, VEC>(src + (int64_t)p * a.src_row + col, true);
-        }
-      }
-#pragma unroll
-      for (int b = 0; b < kBatch; ++b) {
-        const int e = e0 + b;
-        if (e < cnt) {
-          if (k[b] != cur) {
-            flush(cur);
-#pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] = 0;
-            cur = k[b];
-          }
-          if (active) {
-#pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] += (UT)row[b].v[q];
-          }
-        }
-      }
-    }
-    flush(cur);
-  }
-}
-
 template <class T>
 tx_status scatter_rows_atomic(const ScatterPlan& p, const tx_tensor* self, const tx_tensor* index, const tx_tensor* src,
                               char* ws, hipStream_t s) {
@@ -667,7 +659,7 @@ tx_status scatter_rows_atomic(const ScatterPlan& p, const tx_tensor* self, const
   uint32_t* vals0 = (uint32_t*)(ws + p.off_vals[0]);
   const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
   hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
-                     index->strides[0], p.n, keys0, vals0);
+                     index->strides[0], p.n, keys0, vals0, (unsigned int*)nullptr);
   int cur;
   tx_status rc = run_sort(p, ws, s, &cur);
   if (rc) return rc;
@@ -685,8 +677,8 @@ tx_status scatter_rows_atomic(const ScatterPlan& p, const tx_tensor* self, const
   const bool al = p.width % V == 0 && (uintptr_t)src->data % 16 == 0 && (a.src_row * (int64_t)sizeof(T)) % 16 == 0;
   const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
   set_path("scatter-sort-atomic");
-  if (al) hipLaunchKernelGGL((seg_rows_atomic_kernel<T, V>), dim3(gb), dim3(kBlock), 0, s, a);
-  else hipLaunchKernelGGL((seg_rows_atomic_kernel<T, 1>), dim3(gb), dim3(kBlock), 0, s, a);
+  if (al) hipLaunchKernelGGL((seg_rows_kernel<T, V, true>), dim3(gb), dim3(kBlock), 0, s, a);
+  else hipLaunchKernelGGL((seg_rows_kernel<T, 1, true>), dim3(gb), dim3(kBlock), 0, s, a);
   return check_launch("aggregated atomic row sum");
 }
 
@@ -701,7 +693,7 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
   if (p.row_mode)
     hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
-                       index->strides[0], p.n, keys0, vals0);
+                       index->strides[0], p.n, keys0, vals0, (unsigned int*)(ws + p.off_counter));
   else
     hipLaunchKernelGGL(scatter_keys_kernel, dim3(nb), dim3(kBlock), 0, s, ea, keys0, vals0);
   int cur;
@@ -727,18 +719,20 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   a.part_a = (float*)(ws + p.off_part_a);
   a.part_b = (float*)(ws + p.off_part_b);
   a.flag_a = (uint8_t*)(ws + p.off_flag_a);
-  a.flag_b = (uint8_t*)(ws + p.off_flag_b);
   a.key_b = (uint32_t*)(ws + p.off_key_b);
+  a.start_list = (uint32_t*)(ws + p.off_start_list);
+  a.nstart = (unsigned int*)(ws + p.off_counter);
   const bool al = p.width % V == 0 && (uintptr_t)src->data % 16 == 0 && (uintptr_t)self->data % 16 == 0 &&
                   (a.src_row * (int64_t)sizeof(T)) % 16 == 0 && (a.self_row * (int64_t)sizeof(T)) % 16 == 0;
   const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
   set_path(al ? "scatter-sort-rows" : "scatter-sort-rows-scalar");
+  const unsigned cg = (unsigned)std::min<int64_t>(kCombineBlocks, p.nchunks);
   if (al) {
-    hipLaunchKernelGGL((seg_rows_kernel<T, V>), dim3(gb), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL((seg_combine_kernel<T, V>), dim3((unsigned)p.nchunks), dim3(kCombineWaves * kWave), 0, s, a);
+    hipLaunchKernelGGL((seg_rows_kernel<T, V, false>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_combine_kernel<T, V>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
   } else {
-    hipLaunchKernelGGL((seg_rows_kernel<T, 1>), dim3(gb), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL((seg_combine_kernel<T, 1>), dim3((unsigned)p.nchunks), dim3(kCombineWaves * kWave), 0, s, a);
+    hipLaunchKernelGGL((seg_rows_kernel<T, 1, false>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_combine_kernel<T, 1>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
   }
   return check_launch("segmented row sum");
 }
