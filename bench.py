@@ -121,8 +121,22 @@ def build_ops(torch, B):
     ocf, oci = torch.empty(C, device=dev), torch.empty(C, device=dev, dtype=I64)
     wsf = B.workspace(B.tx_cumsum_workspace_bytes(ocf, cf, -1))
     wsi = B.workspace(B.tx_cumsum_workspace_bytes(oci, ci, -1))
-    add("cumsum_f32", "a11", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_cumsum(ocf, cf, -1, wsf))
-    add("cumsum_i64", "a11", "cumsum_lookback_kernel", nc * 16, nc, lambda: B.tx_cumsum(oci, ci, -1, wsi))
+    add("cumsum_f32", "a11", "cumsum_carry_kernel", nc * 8, nc, lambda: B.tx_cumsum(ocf, cf, -1, wsf))
+    add("cumsum_i64", "a11", "cumsum_carry_kernel", nc * 16, nc, lambda: B.tx_cumsum(oci, ci, -1, wsi))
+
+    def lookback_f32():      # the same scan forced through the single-pass decoupled look-back kernel
+        B.tx_force_path("scan-lookback")
+        try:
+            B.tx_cumsum(ocf, cf, -1, wsf)
+        finally:
+            B.tx_force_path(None)
+    add("cumsum_f32_lookback", "a11", "cumsum_lookback_kernel", nc * 8, nc, lookback_f32)
+    # few long rows: the shape the look-back scan exists for
+    cl = randn((8, 1 << 24))
+    ocl = torch.empty_like(cl)
+    wsl = B.workspace(B.tx_cumsum_workspace_bytes(ocl, cl, -1))
+    add("cumsum_f32_8_long_rows", "a11", "cumsum_lookback_kernel", cl.numel() * 8, cl.numel(),
+        lambda: B.tx_cumsum(ocl, cl, -1, wsl))
 
     # ---- workload 5: indexing on src[1048576,256]
     NS, W, ND = 1048576, 256, 65536
@@ -202,6 +216,10 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", default="", help="comma-separated substrings: run only the operators whose name matches "
+                                               "(for profiling single kernels; the JSON line then covers that subset)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="add a plain 1 GiB device-to-device copy to the step (known traffic, to scale profiler counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: every operator here runs on a single GPU; --gpus %d is not supported "
@@ -212,6 +230,14 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     ops = build_ops(torch, B)
+    if args.only:
+        pats = [p for p in args.only.split(",") if p]
+        ops = [o for o in ops if any(p in o["name"] for p in pats)]
+    if args.calibrate:
+        ca = torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_()
+        cb = torch.empty_like(ca)
+        ops.append(dict(name="calibration_copy_1GiB", row="-", kernel="device copy", bytes=2 << 30, elems=1 << 28,
+                        fn=lambda: cb.copy_(ca)))
     torch.cuda.synchronize()
     for _ in range(args.warmup):
         for op in ops:

@@ -567,8 +567,15 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     int64_t outer = 1;
     for (int d = 0; d < in; ++d) { a.osize[d] = FastDiv((uint32_t)it.size[d]); outer *= it.size[d]; }
     a.n0 = it.size[in];
-    const int64_t tile = (int64_t)kBlock * e_rt * U;
+    // write-dominated case (every input is a broadcast that stays in cache): a wave's lifetime is one load
+    // round trip whatever it stores, so let it store four vectors instead of one
+    bool wide = !Shape<F>::dynamic;
+    for (int o = 1; o < NOPS; ++o) wide = wide && !a.stream[o];
+    constexpr int UW = 4;
+    const int u_rt = wide ? UW : U;
+    const int64_t tile = (int64_t)kBlock * e_rt * u_rt;
     const int64_t tiles = (a.n0 + tile - 1) / tile;
+    if (outer * tiles >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "tensor too large for one launch");
     a.tiles_per_row = FastDiv((uint32_t)tiles);
     set_path("vec");
     const dim3 grid((unsigned)(outer * tiles));
@@ -576,7 +583,8 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
       if (e_rt == 2) hipLaunchKernelGGL((ew_vec_kernel<F, 2, U>), grid, dim3(kBlock), 0, stream, f, a);
       else hipLaunchKernelGGL((ew_vec_kernel<F, 4, U>), grid, dim3(kBlock), 0, stream, f, a);
     } else {
-      hipLaunchKernelGGL((ew_vec_kernel<F, E, U>), grid, dim3(kBlock), 0, stream, f, a);
+      if (wide) hipLaunchKernelGGL((ew_vec_kernel<F, E, UW>), grid, dim3(kBlock), 0, stream, f, a);
+      else hipLaunchKernelGGL((ew_vec_kernel<F, E, U>), grid, dim3(kBlock), 0, stream, f, a);
     }
     return check_launch("elementwise vec kernel");
   }
@@ -680,7 +688,7 @@ struct OpTanh {
 struct OpGelu {
   __device__ static float run(float x) { return gelu_erf_f32(x); }
   // x * erfc(-x / sqrt 2) / 2: erfc keeps its relative accuracy in the negative tail
-  __device__ static float run_half(float x) { return x * (0.5f * erfcf(-x * 0.70710678118654752440f)); }
+  __device__ static float run_half(float x) { return gelu_erf_half(x); }
 };
 
 // float math op on a statically typed float tensor (computes in fp32)

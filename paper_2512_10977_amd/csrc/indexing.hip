@@ -54,25 +54,42 @@ struct ElemArgs {
   int64_t dstride[TX_MAX_DIMS];    // destination strides
 };
 
+// Each lane handles kGatherU elements (a workgroup covers kGatherU consecutive runs of 256): all index loads
+// are issued first, then all data-dependent source loads, so several random accesses are in flight per lane.
+constexpr int kGatherU = 4;
 template <class B>
 __global__ __launch_bounds__(kBlock) void gather_kernel(const ElemArgs a, int index_1d) {
-  const int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (lin >= a.shape.numel) return;
-  int64_t io = 0, so = 0, d_o = 0, dimcoord = 0;
-  uint32_t rem = (uint32_t)lin;
-  for (int d = a.shape.n - 1; d >= 0; --d) {
-    uint32_t q, m;
-    a.shape.div[d].divmod(rem, q, m);
-    rem = q;
-    d_o += (int64_t)m * a.dstride[d];
-    if (d == a.dim) dimcoord = m;
-    else so += (int64_t)m * a.sstride[d];
-    if (!index_1d) io += (int64_t)m * a.istride[d];
+  int64_t so[kGatherU], d_o[kGatherU], k[kGatherU];
+  bool live[kGatherU];
+#pragma unroll
+  for (int u = 0; u < kGatherU; ++u) {
+    const int64_t lin = ((int64_t)blockIdx.x * kGatherU + u) * kBlock + threadIdx.x;
+    live[u] = lin < a.shape.numel;
+    int64_t io = 0, dimcoord = 0;
+    so[u] = 0;
+    d_o[u] = 0;
+    k[u] = 0;
+    if (!live[u]) continue;
+    uint32_t rem = (uint32_t)lin;
+    for (int d = a.shape.n - 1; d >= 0; --d) {
+      uint32_t q, m;
+      a.shape.div[d].divmod(rem, q, m);
+      rem = q;
+      d_o[u] += (int64_t)m * a.dstride[d];
+      if (d == a.dim) dimcoord = m;
+      else so[u] += (int64_t)m * a.sstride[d];
+      if (!index_1d) io += (int64_t)m * a.istride[d];
+    }
+    if (index_1d) io = dimcoord * a.istride[a.dim];
+    k[u] = load_index(a.index, io, a.index_is64);
   }
-  if (index_1d) io = dimcoord * a.istride[a.dim];
-  const int64_t k = load_index(a.index, io, a.index_is64);
-  so += k * a.sstride[a.dim];
-  ((B*)a.dst)[d_o] = ((const B*)a.src)[so];
+  B v[kGatherU];
+#pragma unroll
+  for (int u = 0; u < kGatherU; ++u)
+    if (live[u]) v[u] = ((const B*)a.src)[so[u] + k[u] * a.sstride[a.dim]];
+#pragma unroll
+  for (int u = 0; u < kGatherU; ++u)
+    if (live[u]) ((B*)a.dst)[d_o[u]] = v[u];
 }
 
 // index_select fast path: slice r = (outer o, picked j) is `vecs` 16-byte vectors
@@ -795,7 +812,7 @@ tx_status tx_gather(const tx_tensor* out, const tx_tensor* src, int64_t dim, con
     a.dstride[i] = out->strides[i];
   }
   if (index->ndim == 0) a.sstride[0] = a.istride[0] = a.dstride[0] = 0;
-  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  const dim3 grid((unsigned)((n + kBlock * kGatherU - 1) / (kBlock * kGatherU)));
   hipStream_t s = as_stream(stream);
   set_path("gather");
   switch (dtype_size(src->dtype)) {
@@ -889,7 +906,7 @@ tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t di
   }
   a.istride[d] = istride;
   if (out->ndim == 0) { a.dim = 0; a.sstride[0] = a.dstride[0] = a.istride[0] = 0; }
-  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  const dim3 grid((unsigned)((n + kBlock * kGatherU - 1) / (kBlock * kGatherU)));
   set_path("index-select-generic");
   switch (es) {
     case 1: hipLaunchKernelGGL((gather_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a, 1); break;
