@@ -20,6 +20,12 @@ if ROOT not in sys.path:
 
 PEAK_GBPS = 8000.0
 MiB = 1 << 20
+# HBM bytes per launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE; the text summary under
+# profiles/ has the commands and the copy calibration: bytes = 2.0 x FETCH_SIZE KiB + 1.0 x WRITE_SIZE KiB).  An entry
+# is valid only for the kernel version it was measured on: remove it when that kernel changes.
+PMC_TRAFFIC_BYTES = {
+    "index_select_f32": (2 * 2109603 + 4194304) * 1024,
+}
 
 
 def build_ops(torch, B):
@@ -277,7 +283,8 @@ def main():
         "frac_of_peak": round(value / PEAK_GBPS, 4),
         "elements_per_s": round(step_elems / (wall / args.steps), 1),
         "roofline": {"bound": "hbm", "kernel": dom["kernel"], "op": dom["op"], "achieved": dom["GB/s"],
-                     "peak": PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_of_peak"], "traffic": None,
+                     "peak": PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_of_peak"],
+                     "traffic": PMC_TRAFFIC_BYTES.get(dom["op"]), "algorithmic_bytes": dom["bytes"],
                      "avg_us": dom["us"]},
         "per_op": per_op,
     }
