@@ -161,8 +161,14 @@ def build_ops(torch, B):
     src_i = ri.view(-1)[: NS * W].view(NS, W).to(I32)
     dst_i = torch.zeros((ND, W), device=dev, dtype=I32)
     wsi32 = B.workspace(B.tx_scatter_add_workspace_bytes(dst_i, 0, eidx, src_i, True))
-    add("scatter_add_i32_atomic", "a14", "seg_rows_atomic_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
+    add("scatter_add_i32_rows", "a14", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
         lambda: B.tx_scatter_add_(dst_i, 0, eidx, src_i, True, wsi32))
+    # materialised index, one Zipf draw per element (the secondary scatter_add configuration): one atomic per element
+    NE = 131072
+    midx = I.zipf_rows(NE * W, ND, 1.1, seed=9).reshape(NE, W).to(dev)
+    src_e = src_i[:NE]
+    add("scatter_add_i32_atomic_elem_index", "a14", "scatter_add_atomic_kernel", NE * W * (4 + 8 + 8), NE * W,
+        lambda: B.tx_scatter_add_(dst_i, 0, midx, src_e, True, None))
     dst_f = torch.zeros((ND, W), device=dev)
     wss = B.workspace(B.tx_scatter_add_workspace_bytes(dst_f, 0, eidx, src, True))
     add("scatter_add_f32_sorted", "a15", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,

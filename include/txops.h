@@ -214,8 +214,8 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
  * ("" if it launched nothing).  For tests and profiling. */
 const char* tx_last_path(void);
 /* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
- * "vec", "tile", "generic".  cumsum along a contiguous dim: "scan-lookback",
- * "scan-carry".  Requests that a path cannot serve fall back to the automatic
+ * "vec", "tile", "generic".  cumsum along a contiguous dim: "scan-lookback"
+ * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".  Requests that a path cannot serve fall back to the automatic
  * choice.  Process-wide; meant for A/B profiling. */
 void tx_force_path(const char* name);
 

@@ -357,29 +357,50 @@ struct SegRowArgs {
   char* self;
   int64_t src_row, self_row;     // element strides between rows
   int64_t width;                 // elements per row
-  float* part_a;                 // [nchunks][width] piece that continues from the previous chunk
-  float* part_b;                 // [nchunks][width] piece that continues into the next chunk
+  char* part_a;                  // [nchunks][width] accumulators: piece that continues from the previous chunk
+  char* part_b;                  // [nchunks][width] accumulators: piece that continues into the next chunk
   uint8_t* flag_a;               // kNone / kEnd / kThrough
   uint32_t* key_b;               // destination row of the chunk's start piece
   uint32_t* start_list;          // chunks that hold the start piece of a run that goes on
   unsigned int* nstart;          // length of start_list (cleared by row_keys_kernel)
 };
 
+// Accumulator of a segmented row sum: fp32 for the floating dtypes, wrapping unsigned arithmetic for integers.
+template <class T> struct SegAcc { using type = float; };
+template <> struct SegAcc<int32_t> { using type = uint32_t; };
+template <> struct SegAcc<int64_t> { using type = unsigned long long; };
+template <class T, class Acc> __device__ __forceinline__ T seg_add(T old, Acc sum) {
+  if constexpr (std::is_integral<T>::value) return (T)((Acc)old + sum);
+  else return cvt<T>(cvt<float>(old) + sum);
+}
+
 // Segmented row sums over sorted (destination row, source row) pairs.  One wave owns a chunk of 128
 // consecutive pairs.  The wave first reads its 128 keys and source-row ids with two coalesced loads each
 // and hands them out with readlane, so the row loads never wait on an index load.  Rows are fetched in
-// batches of 8 non-temporal 16-byte-per-lane loads; where a run begins inside the batch, the destination
-// row is fetched in the same batch so that finishing the run costs no extra round trip.
-//   ATOMIC == false (floating dtypes): fp32 accumulation in a fixed order.  A run that lies inside the
-//     chunk updates self directly; the pieces of a run that crosses chunk boundaries are parked in
-//     part_a / part_b and added by seg_combine_kernel in chunk order.
-//   ATOMIC == true (int32 / int64): every finished piece is added with one atomic per element.
-template <class T, int VEC, bool ATOMIC>
+// batches of 8 non-temporal loads, one batch ahead of the batch being summed.  Every row load is issued
+// unconditionally (entries past the end of the chunk and lanes past the end of the row re-read a valid
+// address and are ignored later), so the number of loads in flight is known at compile time and the wave
+// waits once per batch, not once per load.
+// The sum of a run that ends inside the chunk is parked in LDS (8 slots per wave, each lane keeps its own
+// columns, so no barrier is involved).  The slots are written back together - destination rows fetched
+// with up to 8 loads in flight, added, stored - only when the next batch could overflow them, and at the
+// end of the chunk: the read-modify-write round trips, whose store acknowledgements every later wait of
+// the wave has to sit out, are paid once or twice per chunk instead of once per finished run.
+// The accumulation order is fixed (fp32 for the floating dtypes), and every destination row is updated by
+// exactly one wave: a run that lies inside the chunk updates self here; the pieces of a run that crosses
+// chunk boundaries are parked in part_a / part_b and added by seg_combine_kernel in chunk order.
+constexpr int kSegSlots = 8;
+
+template <class T, int VEC>
 __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
-  using Acc = typename std::conditional<ATOMIC, typename std::make_unsigned<
-                  typename std::conditional<ATOMIC, T, int>::type>::type, float>::type;
+  using Acc = typename SegAcc<T>::type;
+  constexpr int kBatch = 8;
+  static_assert(kSegSlots >= kBatch, "a drained buffer must take every run that can end in one batch");
+  static_assert(sizeof(Acc) * VEC <= 16, "one slot is at most 1 KiB per wave");
+  __shared__ Vec<Acc, VEC> done_rows[kWaves][kSegSlots][kWave];
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t chunk = (int64_t)blockIdx.x * kWaves + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int64_t chunk = (int64_t)blockIdx.x * kWaves + w;
   if (chunk >= a.nchunks) return;
   const int64_t j0 = chunk * kChunk;
   const int cnt = (int)std::min<int64_t>(kChunk, a.n - j0);
@@ -394,104 +415,134 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
   auto key_at = [&](int e) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)(e < kWave ? kreg[0] : kreg[1]), e & (kWave - 1)); };
   auto val_at = [&](int e) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)(e < kWave ? vreg[0] : vreg[1]), e & (kWave - 1)); };
   const uint32_t first_key = key_at(0), last_key = key_at(cnt - 1);
-  bool from_before = false, to_after = false;
-  if constexpr (!ATOMIC) {
-    from_before = j0 > 0 && a.keys[j0 - 1] == first_key;
-    to_after = j0 + cnt < a.n && a.keys[j0 + cnt] == last_key;
-  }
-  const T* src = (const T*)a.src;
-  constexpr int kBatch = 8;
+  const bool from_before = j0 > 0 && a.keys[j0 - 1] == first_key;
+  const bool to_after = j0 + cnt < a.n && a.keys[j0 + cnt] == last_key;
+  Acc* const part_a = (Acc*)a.part_a;
+  Acc* const part_b = (Acc*)a.part_b;
   for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
     const int64_t col = cb + (int64_t)lane * VEC;
     const bool active = col < a.width;
-    Acc acc[VEC];
+    const T* src_col = (const T*)a.src + (active ? col : 0);        // inactive lanes re-read column 0
+    T* self_col = (T*)a.self + (active ? col : 0);
+    Vec<Acc, VEC> acc;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] = Acc(0);
+    for (int e = 0; e < VEC; ++e) acc.v[e] = Acc(0);
     uint32_t cur = first_key;
     bool first_piece = true;
-    Vec<T, VEC> cur_self;                      // destination row of the run being summed (ATOMIC == false)
-#pragma unroll
-    for (int q = 0; q < VEC; ++q) cur_self.v[q] = T();
+    int nbuf = 0;                              // finished runs waiting in done_rows[w]
+    int kbuf = 0;                              // their destination rows: lane i holds the key of slot i
 
-    auto flush = [&](uint32_t key, bool fb, bool ta) {
-      if (!active) return;
-      if constexpr (ATOMIC) {
-        T* d = (T*)a.self + (int64_t)key * a.self_row + col;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-          if (acc[e] != 0) atomic_accumulate<T>(d + e, (T)acc[e]);
-      } else if (!fb && !ta) {
-        Vec<T, VEC> t;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) t.v[e] = cvt<T>(cvt<float>(cur_self.v[e]) + (float)acc[e]);
-        vec_store<T, VEC>((T*)a.self + (int64_t)key * a.self_row + col, t, false);
-      } else {
-        float* p = (fb ? a.part_a : a.part_b) + chunk * a.width + col;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) p[e] = (float)acc[e];
-      }
+    auto park = [&](Acc* part) {               // a piece of a run that crosses a chunk boundary
+      if (active) vec_store<Acc, VEC>(part + chunk * a.width + col, acc, false);      // read again soon by seg_combine_kernel
     };
 
-    for (int e0 = 0; e0 < cnt; e0 += kBatch) {
-      uint32_t k[kBatch];
-      Vec<T, VEC> row[kBatch], dst[kBatch];
+    Vec<T, VEC> row[kBatch], nrow[kBatch];
+    uint32_t k[kBatch], nk[kBatch];
+    // issues the loads of entries e0 .. e0 + 7, clamped to the last entry of the chunk
+    auto fetch = [&](int e0) {
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
-        const int e = e0 + b;
-        if (e < cnt) {
-          k[b] = key_at(e);
-          const uint32_t p = val_at(e);
-          if (active) row[b] = vec_load<T, VEC>(src + (int64_t)p * a.src_row + col, true);
-          if constexpr (!ATOMIC) {
-            const bool starts = e == 0 ? !from_before : k[b] != key_at(e - 1);
-            if (starts && active) dst[b] = vec_load<T, VEC>((const T*)a.self + (int64_t)k[b] * a.self_row + col, false);
-          }
-        }
+        const int e = std::min(e0 + b, cnt - 1);
+        nk[b] = key_at(e);
+        nrow[b] = vec_load<T, VEC>(src_col + (int64_t)val_at(e) * a.src_row, true);
       }
+    };
+    // writes the parked sums back: all destination rows first (row[] is free between batches), then add and store
+    auto drain = [&]() {
+#pragma unroll
+      for (int i = 0; i < kSegSlots; ++i)
+        if (i < nbuf) {
+          const uint32_t key = (uint32_t)__builtin_amdgcn_readlane(kbuf, i);
+          row[i] = vec_load<T, VEC>(self_col + (int64_t)key * a.self_row, true);
+        }
+#pragma unroll
+      for (int i = 0; i < kSegSlots; ++i)
+        if (i < nbuf) {
+          const uint32_t key = (uint32_t)__builtin_amdgcn_readlane(kbuf, i);
+          const Vec<Acc, VEC> sum = done_rows[w][i][lane];
+          Vec<T, VEC> t;
+#pragma unroll
+          for (int q = 0; q < VEC; ++q) t.v[q] = seg_add<T, Acc>(row[i].v[q], sum.v[q]);
+          if (active) vec_store<T, VEC>(self_col + (int64_t)key * a.self_row, t, true);
+        }
+      nbuf = 0;
+    };
+
+    fetch(0);
+    for (int e0 = 0; e0 < cnt; e0 += kBatch) {
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b) {
+        k[b] = nk[b];
+        row[b] = nrow[b];
+      }
+      fetch(e0 + kBatch);                      // past the end: re-reads the last entry, never used
 #pragma unroll
       for (int b = 0; b < kBatch; ++b) {
         const int e = e0 + b;
         if (e < cnt) {
           if (k[b] != cur) {
-            flush(cur, first_piece && from_before, false);
+            if (first_piece && from_before) {
+              park(part_a);
+            } else {
+              done_rows[w][nbuf][lane] = acc;
+              kbuf = lane == nbuf ? (int)cur : kbuf;
+              nbuf = __builtin_amdgcn_readfirstlane(nbuf + 1);
+            }
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] = Acc(0);
+            for (int q = 0; q < VEC; ++q) acc.v[q] = Acc(0);
             cur = k[b];
             first_piece = false;
-            if constexpr (!ATOMIC) cur_self = dst[b];
-          } else if constexpr (!ATOMIC) {
-            if (e == 0 && !from_before) cur_self = dst[b];
           }
-          if (active) {
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) acc[q] += cvt<Acc>(row[b].v[q]);
-          }
+          for (int q = 0; q < VEC; ++q) acc.v[q] += cvt<Acc>(row[b].v[q]);
         }
       }
+      // runs that will end in the next batch (its keys are already here): make room if they might not fit
+      int ends = 0;
+      uint32_t prev = cur;
+#pragma unroll
+      for (int b = 0; b < kBatch; ++b)
+        if (e0 + kBatch + b < cnt) {
+          ends += nk[b] != prev;
+          prev = nk[b];
+        }
+      if (nbuf + ends > kSegSlots) drain();
     }
-    flush(cur, first_piece && from_before, to_after);
+    // last piece of the chunk
+    if (first_piece && from_before) {
+      park(part_a);
+    } else if (to_after) {
+      park(part_b);
+    } else {
+      if (nbuf == kSegSlots) drain();
+      done_rows[w][nbuf][lane] = acc;
+      kbuf = lane == nbuf ? (int)cur : kbuf;
+      nbuf = __builtin_amdgcn_readfirstlane(nbuf + 1);
+    }
+    drain();
   }
-  if constexpr (!ATOMIC) {
-    if (lane == 0) {
-      // first piece continues from before: END if it stops inside this chunk, THROUGH if the whole chunk is one run that goes on
-      const bool single = first_key == last_key;
-      a.flag_a[chunk] = from_before ? ((single && to_after) ? kThrough : kEnd) : kNone;
-      const bool start = to_after && !(single && from_before);
-      a.key_b[chunk] = last_key;
-      if (start) a.start_list[atomicAdd(a.nstart, 1u)] = (uint32_t)chunk;
-    }
+  if (lane == 0) {
+    // first piece continues from before: END if it stops inside this chunk, THROUGH if the whole chunk is one run that goes on
+    const bool single = first_key == last_key;
+    a.flag_a[chunk] = from_before ? ((single && to_after) ? kThrough : kEnd) : kNone;
+    const bool start = to_after && !(single && from_before);
+    a.key_b[chunk] = last_key;
+    if (start) a.start_list[atomicAdd(a.nstart, 1u)] = (uint32_t)chunk;
   }
 }
 
 // For every chunk that STARTS a run continuing into later chunks: add, in chunk order, the start piece and
-// the continuation pieces of the following chunks, then update self once.  A fixed number of 16-wave
+// the continuation pieces of the following chunks, then update self once.  A fixed number of 4-wave
 // workgroups walk the start list; each run is handled by one workgroup whose waves take contiguous
 // sub-ranges of the pieces and are then added in wave order, so the order of additions depends only on
 // the data.
 template <class T, int VEC>
 __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(const SegRowArgs a) {
+  using Acc = typename SegAcc<T>::type;
   __shared__ long long end_chunk;
-  __shared__ float sub[kCombineWaves][kWave * VEC];
+  __shared__ Acc sub[kCombineWaves][kWave * VEC];
+  const Acc* const part_a = (const Acc*)a.part_a;
+  const Acc* const part_b = (const Acc*)a.part_b;
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   const unsigned int nstart = *a.nstart;
   for (unsigned int s = blockIdx.x; s < nstart; s += gridDim.x) {
@@ -516,13 +567,13 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
     for (int64_t cb = 0; cb < a.width; cb += kWave * VEC) {
       const int64_t col = cb + (int64_t)lane * VEC;
       const bool active = col < a.width;
-      float acc[VEC];
+      Acc acc[VEC];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+      for (int e = 0; e < VEC; ++e) acc[e] = Acc(0);
       if (active) {
 #pragma unroll 16
         for (int64_t p = p0; p < p1; ++p) {
-          const float* src = a.part_a + p * a.width + col;
+          const Acc* src = part_a + p * a.width + col;
 #pragma unroll
           for (int e = 0; e < VEC; ++e) acc[e] += src[e];
         }
@@ -531,13 +582,13 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
       for (int e = 0; e < VEC; ++e) sub[w][lane * VEC + e] = acc[e];
       __syncthreads();
       if (w == 0 && active) {
-        const float* b = a.part_b + c * a.width + col;
+        const Acc* b = part_b + c * a.width + col;
         T* d = (T*)a.self + (int64_t)key * a.self_row + col;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-          float t = b[e];
+          Acc t = b[e];
           for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
-          d[e] = cvt<T>(cvt<float>(d[e]) + t);
+          d[e] = seg_add<T, Acc>(d[e], t);
         }
       }
       __syncthreads();
@@ -617,8 +668,9 @@ tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, c
   p->off_hist = o; o = align_up(o + (size_t)256 * p->nblocks * 4, 256);
   p->off_totals = o; o = align_up(o + 256 * 4, 256);
   if (p->row_mode) {
-    p->off_part_a = o; o = align_up(o + (size_t)p->nchunks * p->width * 4, 256);
-    p->off_part_b = o; o = align_up(o + (size_t)p->nchunks * p->width * 4, 256);
+    const size_t acc_size = self->dtype == TX_I64 ? 8 : 4;     // fp32 accumulators for floats, the dtype itself for integers
+    p->off_part_a = o; o = align_up(o + (size_t)p->nchunks * p->width * acc_size, 256);
+    p->off_part_b = o; o = align_up(o + (size_t)p->nchunks * p->width * acc_size, 256);
     p->off_flag_a = o; o = align_up(o + (size_t)p->nchunks, 256);
     p->off_key_b = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
     p->off_start_list = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
@@ -664,45 +716,14 @@ tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_bu
   return check_launch("radix sort");
 }
 
-// Integer row mode: rows are grouped by destination with the same sort, a wave adds up each run of a
-// 128-row chunk in registers and issues ONE atomic per destination element per run (integer addition is
-// associative, so runs that cross chunk boundaries may simply be flushed twice).  This cuts the atomic
-// count from one per source element to one per (run, column).
-template <class T>
-tx_status scatter_rows_atomic(const ScatterPlan& p, const tx_tensor* self, const tx_tensor* index, const tx_tensor* src,
-                              char* ws, hipStream_t s) {
-  constexpr int V = 16 / sizeof(T);
-  uint32_t* keys0 = (uint32_t*)(ws + p.off_keys[0]);
-  uint32_t* vals0 = (uint32_t*)(ws + p.off_vals[0]);
-  const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
-  hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
-                     index->strides[0], p.n, keys0, vals0, (unsigned int*)nullptr);
-  int cur;
-  tx_status rc = run_sort(p, ws, s, &cur);
-  if (rc) return rc;
-  SegRowArgs a;
-  memset(&a, 0, sizeof(a));
-  a.keys = (const uint32_t*)(ws + p.off_keys[cur]);
-  a.vals = (const uint32_t*)(ws + p.off_vals[cur]);
-  a.n = p.n;
-  a.nchunks = p.nchunks;
-  a.src = (const char*)src->data;
-  a.self = (char*)self->data;
-  a.src_row = src->strides[0];
-  a.self_row = self->strides[0];
-  a.width = p.width;
-  const bool al = p.width % V == 0 && (uintptr_t)src->data % 16 == 0 && (a.src_row * (int64_t)sizeof(T)) % 16 == 0;
-  const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
-  set_path("scatter-sort-atomic");
-  if (al) hipLaunchKernelGGL((seg_rows_kernel<T, V, true>), dim3(gb), dim3(kBlock), 0, s, a);
-  else hipLaunchKernelGGL((seg_rows_kernel<T, 1, true>), dim3(gb), dim3(kBlock), 0, s, a);
-  return check_launch("aggregated atomic row sum");
-}
-
+// Sorted scatter_add.  Floating dtypes: every index layout (row mode or element mode).  int32 / int64: row
+// mode only - integer addition needs no fixed order, but grouping rows by destination replaces one atomic
+// per source element by plain row sums, and hot destination rows no longer serialise on atomics.
 template <class T>
 tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int dim, const tx_tensor* index,
                                 const tx_tensor* src, char* ws, hipStream_t s) {
-  constexpr int V = 16 / sizeof(T);
+  constexpr int V = sizeof(T) == 2 ? 4 : 16 / sizeof(T);     // row kernels: at most 16 bytes of accumulators per lane
+  constexpr int kVecBytes = V * (int)sizeof(T);
   uint32_t* keys0 = (uint32_t*)(ws + p.off_keys[0]);
   uint32_t* vals0 = (uint32_t*)(ws + p.off_vals[0]);
   ElemArgs ea;
@@ -719,9 +740,13 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   const uint32_t* keys = (const uint32_t*)(ws + p.off_keys[cur]);
   const uint32_t* vals = (const uint32_t*)(ws + p.off_vals[cur]);
   if (!p.row_mode) {
-    set_path("scatter-sort-elem");
-    hipLaunchKernelGGL((seg_elem_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, vals, p.n, ea);
-    return check_launch("segmented sum");
+    if constexpr (std::is_integral<T>::value) {
+      return fail(TX_ERR_UNSUPPORTED, "sorted integer scatter_add needs a broadcast row index");
+    } else {
+      set_path("scatter-sort-elem");
+      hipLaunchKernelGGL((seg_elem_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, vals, p.n, ea);
+      return check_launch("segmented sum");
+    }
   }
   SegRowArgs a;
   a.keys = keys;
@@ -733,22 +758,22 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   a.src_row = src->strides[0];
   a.self_row = self->strides[0];
   a.width = p.width;
-  a.part_a = (float*)(ws + p.off_part_a);
-  a.part_b = (float*)(ws + p.off_part_b);
+  a.part_a = ws + p.off_part_a;
+  a.part_b = ws + p.off_part_b;
   a.flag_a = (uint8_t*)(ws + p.off_flag_a);
   a.key_b = (uint32_t*)(ws + p.off_key_b);
   a.start_list = (uint32_t*)(ws + p.off_start_list);
   a.nstart = (unsigned int*)(ws + p.off_counter);
-  const bool al = p.width % V == 0 && (uintptr_t)src->data % 16 == 0 && (uintptr_t)self->data % 16 == 0 &&
-                  (a.src_row * (int64_t)sizeof(T)) % 16 == 0 && (a.self_row * (int64_t)sizeof(T)) % 16 == 0;
+  const bool al = p.width % V == 0 && (uintptr_t)src->data % kVecBytes == 0 && (uintptr_t)self->data % kVecBytes == 0 &&
+                  (a.src_row * (int64_t)sizeof(T)) % kVecBytes == 0 && (a.self_row * (int64_t)sizeof(T)) % kVecBytes == 0;
   const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
   set_path(al ? "scatter-sort-rows" : "scatter-sort-rows-scalar");
   const unsigned cg = (unsigned)std::min<int64_t>(kCombineBlocks, p.nchunks);
   if (al) {
-    hipLaunchKernelGGL((seg_rows_kernel<T, V, false>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_rows_kernel<T, V>), dim3(gb), dim3(kBlock), 0, s, a);
     hipLaunchKernelGGL((seg_combine_kernel<T, V>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
   } else {
-    hipLaunchKernelGGL((seg_rows_kernel<T, 1, false>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_rows_kernel<T, 1>), dim3(gb), dim3(kBlock), 0, s, a);
     hipLaunchKernelGGL((seg_combine_kernel<T, 1>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
   }
   return check_launch("segmented row sum");
@@ -928,7 +953,7 @@ size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const 
   if (!deterministic && self->dtype == TX_F32) return 0;
   ScatterPlan p;
   if (scatter_plan(self, d, index, src, &p)) return 0;
-  return int_rows ? p.off_part_a : p.bytes;            // the integer path needs only the sort buffers
+  return p.bytes;
 }
 
 tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
@@ -953,14 +978,14 @@ tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* i
       default: return scatter_deterministic<f16>(p, self, d, index, src, (char*)ws, s);
     }
   }
-  // int32 / int64 with a broadcast row index: group rows by destination first, one atomic per run and column.
-  // Needs the sort buffers; without them (or for small inputs) fall through to one atomic per element.
+  // int32 / int64 with a broadcast row index: group rows by destination first and add whole rows.
+  // Needs the workspace; without it (or for small inputs) fall through to one atomic per element.
   if ((self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
       index->sizes[0] >= kIntRowModeMin && strcmp(forced_path(), "scatter-atomic") != 0) {
     ScatterPlan p;
-    if (!scatter_plan(self, d, index, src, &p) && ws && ws_bytes >= p.off_part_a && (uintptr_t)ws % 16 == 0) {
-      if (self->dtype == TX_I32) return scatter_rows_atomic<int32_t>(p, self, index, src, (char*)ws, s);
-      return scatter_rows_atomic<int64_t>(p, self, index, src, (char*)ws, s);
+    if (!scatter_plan(self, d, index, src, &p) && ws && ws_bytes >= p.bytes && (uintptr_t)ws % 16 == 0) {
+      if (self->dtype == TX_I32) return scatter_deterministic<int32_t>(p, self, d, index, src, (char*)ws, s);
+      return scatter_deterministic<int64_t>(p, self, d, index, src, (char*)ws, s);
     }
   }
   if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "scatter_add_: more than 2^31 index elements");

@@ -333,11 +333,17 @@ template <class Acc> __device__ __forceinline__ Acc wave_inclusive(Acc v) {
   return v;
 }
 
-template <class T, class O, class Acc, int VEC>
-__global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs a) {
-  constexpr int kTileElems = kBlock * kNV * VEC;
-  constexpr int kWaves = kBlock / kWave;
-  __shared__ Acc wave_tot[kNV][kWaves];
+// THREADS is 256 or 1024.  Every workgroup draws one ticket from a single counter, and same-address atomics
+// retire at roughly one per 12 ns on this chip, so a 16 KiB tile (256 lanes) caps the kernel near 2.7 TB/s of
+// traffic; 64 KiB tiles (1024 lanes, same registers per lane) keep the ticket off the critical path.  The
+// smaller tile is kept for inputs with too few tiles to fill the chip.
+template <class T, class O, class Acc, int VEC, int THREADS, int NV>
+__global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs a) {
+  constexpr int kTileElems = THREADS * NV * VEC;
+  constexpr int kWaves = THREADS / kWave;
+  constexpr int kTotals = NV * kWaves;          // wave totals of a tile, in tile order; one wave scans them
+  static_assert(kTotals <= kWave, "wave 0 scans all wave totals in one pass");
+  __shared__ Acc wave_tot[kTotals];              // first the totals, then their exclusive prefix sums
   __shared__ Acc tile_prefix;
   __shared__ unsigned int my_ticket;
   ScanHeader* hdr = (ScanHeader*)a.ws;
@@ -353,10 +359,10 @@ __global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs 
   const int64_t left = a.len - t * kTileElems;      // valid elements in this tile (may exceed the tile)
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
 
-  Acc v[kNV][VEC];
+  Acc v[NV][VEC];
 #pragma unroll
-  for (int k = 0; k < kNV; ++k) {
-    const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+  for (int k = 0; k < NV; ++k) {
+    const int64_t c = ((int64_t)k * THREADS + threadIdx.x) * VEC;
     if (c + VEC <= left) {
       Vec<T, VEC> tv = vec_load<T, VEC>(x + c, true);
 #pragma unroll
@@ -366,31 +372,24 @@ __global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs 
       for (int e = 0; e < VEC; ++e) v[k][e] = (c + e < left) ? cvt<Acc>(x[c + e]) : Acc(0);
     }
   }
-  Acc excl[kNV];
+  Acc excl[NV];
 #pragma unroll
-  for (int k = 0; k < kNV; ++k) {
+  for (int k = 0; k < NV; ++k) {
 #pragma unroll
     for (int e = 1; e < VEC; ++e) v[k][e] += v[k][e - 1];
     const Acc incl = wave_inclusive(v[k][VEC - 1]);
     Acc up = shfl_up(incl, 1);
     excl[k] = lane == 0 ? Acc(0) : up;
-    if (lane == kWave - 1) wave_tot[k][w] = incl;
+    if (lane == kWave - 1) wave_tot[k * kWaves + w] = incl;     // tile order: sub-tile k, then wave w
   }
   __syncthreads();
-  // prefix of (k, w) in tile order: all of sub-tiles k' < k, then waves w' < w of sub-tile k
-  Acc running = Acc(0);
-  Acc base[kNV];
-#pragma unroll
-  for (int k = 0; k < kNV; ++k) {
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) {
-      if (ww == w) base[k] = running;
-      running += wave_tot[k][ww];
-    }
-  }
-  const Acc tile_total = running;
   if (w == 0) {
-    // wave 0 resolves the tile's exclusive prefix
+    // exclusive scan of the wave totals, then the tile's exclusive prefix by look-back
+    const Acc tot = lane < kTotals ? wave_tot[lane] : Acc(0);
+    const Acc incl = wave_inclusive(tot);
+    const Acc up = shfl_up(incl, 1);
+    if (lane < kTotals) wave_tot[lane] = lane == 0 ? Acc(0) : up;
+    const Acc tile_total = shfl_idx(incl, kTotals - 1);
     Acc prefix = Acc(0);
     if (t == 0) {
       if (lane == 0) TileState<Acc>::publish(status, ticket, kPrefix, tile_total);
@@ -427,9 +426,9 @@ __global__ __launch_bounds__(kBlock) void cumsum_lookback_kernel(const ScanArgs 
   __syncthreads();
   const Acc p = tile_prefix;
 #pragma unroll
-  for (int k = 0; k < kNV; ++k) {
-    const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
-    const Acc add = p + base[k] + excl[k];
+  for (int k = 0; k < NV; ++k) {
+    const int64_t c = ((int64_t)k * THREADS + threadIdx.x) * VEC;
+    const Acc add = p + wave_tot[k * kWaves + w] + excl[k];
     if (c + VEC <= left) {
       Vec<O, VEC> tv;
 #pragma unroll
@@ -596,7 +595,7 @@ tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void*
     a.total_tiles = p.total_tiles;
     // enough rows to fill the chip (4 per CU): one workgroup per row with a register carry; else look-back
     bool carry = p.rows >= 1024 || p.tiles_per_row == 1;
-    if (!strcmp(forced_path(), "scan-lookback")) carry = false;
+    if (!strncmp(forced_path(), "scan-lookback", 13)) carry = false;
     if (!strcmp(forced_path(), "scan-carry")) carry = true;
     if (carry) {
       set_path(p.vec > 1 ? "scan-carry" : "scan-carry-scalar");
@@ -606,14 +605,27 @@ tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void*
         hipLaunchKernelGGL((cumsum_carry_kernel<T, O, Acc, 1>), dim3((unsigned)p.rows), dim3(kBlock), 0, stream, a);
       return check_launch("cumsum row-carry kernel");
     }
-    const int64_t words = (int64_t)(p.ws_bytes / 8);
+    // 64 KiB tiles once the 16 KiB tiling has enough tiles for the ticket counter to be the limit
+    constexpr int kBig = 1024, kBigNV = 4;
+    const bool big = p.total_tiles >= 2048 && strcmp(forced_path(), "scan-lookback-narrow") != 0;
+    if (big) {
+      const int64_t tile = (int64_t)kBig * kBigNV * p.vec;
+      a.tiles_per_row = (p.len + tile - 1) / tile;
+      a.total_tiles = a.tiles_per_row * p.rows;
+    }
+    const int64_t words = (int64_t)((256 + (size_t)a.total_tiles * TileState<Acc>::words * 8) / 8);   // <= p.ws_bytes / 8
     hipLaunchKernelGGL(scan_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
                        (unsigned long long*)ws, words);
-    set_path(p.vec > 1 ? "scan-lookback" : "scan-lookback-scalar");
-    if (p.vec > 1)
-      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, V>), dim3((unsigned)p.total_tiles), dim3(kBlock), 0, stream, a);
+    set_path(p.vec > 1 ? (big ? "scan-lookback-wide" : "scan-lookback") : (big ? "scan-lookback-wide-scalar" : "scan-lookback-scalar"));
+    const dim3 grid((unsigned)a.total_tiles);
+    if (p.vec > 1 && big)
+      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, V, kBig, kBigNV>), grid, dim3(kBig), 0, stream, a);
+    else if (p.vec > 1)
+      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, V, kBlock, kNV>), grid, dim3(kBlock), 0, stream, a);
+    else if (big)
+      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, 1, kBig, kBigNV>), grid, dim3(kBig), 0, stream, a);
     else
-      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, 1>), dim3((unsigned)p.total_tiles), dim3(kBlock), 0, stream, a);
+      hipLaunchKernelGGL((cumsum_lookback_kernel<T, O, Acc, 1, kBlock, kNV>), grid, dim3(kBlock), 0, stream, a);
     return check_launch("cumsum look-back kernel");
   }
   StridedArgs a;

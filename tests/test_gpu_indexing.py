@@ -117,6 +117,32 @@ def test_scatter_add_integer_atomics():
     check_scatter_add(torch.zeros((1, 1), dtype=I32), 0, torch.zeros((4, 1), dtype=I64), big, what="wrap")
 
 
+@pytest.mark.parametrize("dt", [I32, I64])
+def test_scatter_add_integer_rows_sorted(dt):
+    # broadcast row index with at least 4096 rows: grouped by destination, whole-row sums, no atomics
+    for n, rows, w in [(5000, 64, 256), (20000, 700, 64), (4100, 70000, 32), (9000, 4, 20), (4096, 3, 16)]:
+        r = I.zipf_rows(n, rows, 1.1, seed=460)
+        src = I.integers((n, w), -1000, 1000, seed=461, dtype=dt)
+        dst = I.integers((rows, w), -1000, 1000, seed=462, dtype=dt)
+        assert check_scatter_add(dst, 0, r.unsqueeze(1).expand(n, w), src, what="row mode").startswith("scatter-sort-rows")
+    n, w = 9000, 64                                      # one destination for everything: a single run over all chunks
+    src = I.integers((n, w), -1000, 1000, seed=463, dtype=dt)
+    dst = I.integers((4, w), -1000, 1000, seed=464, dtype=dt)
+    assert check_scatter_add(dst, 0, torch.full((n, 1), 2).expand(n, w), src, what="one run") == "scatter-sort-rows"
+    big = torch.full((5000, 16), 2 ** 30 if dt == I32 else 2 ** 62, dtype=dt)      # wraps like two's complement
+    assert check_scatter_add(torch.zeros((2, 16), dtype=dt), 0, torch.ones((5000, 1), dtype=I64).expand(5000, 16), big,
+                             what="wrap") == "scatter-sort-rows"
+    # without a workspace the same call falls back to one atomic per element
+    r = I.zipf_rows(5000, 64, 1.1, seed=465)
+    src = I.integers((5000, 32), -1000, 1000, seed=466, dtype=dt)
+    want = O.scatter_add_(torch.zeros((64, 32), dtype=dt), 0, r.unsqueeze(1).expand(5000, 32), src)
+    dst = torch.zeros((64, 32), dtype=dt, device="cuda")
+    B.tx_scatter_add_(dst, 0, r.cuda().unsqueeze(1).expand(5000, 32), src.cuda(), True, None)
+    assert B.tx_last_path() == "scatter-atomic"
+    torch.cuda.synchronize()
+    assert_exact(dst, want, "no workspace")
+
+
 @pytest.mark.parametrize("dt", [F32, BF16, F16])
 def test_scatter_add_float_deterministic(dt):
     paths = set()
@@ -198,7 +224,7 @@ def test_scatter_add_full_size(big_src):
     assert check_scatter_add(dst, 0, idx, big_src, what="fp32 full") == "scatter-sort-rows"
     src_i = I.integers((1048576, 256), -1000, 1000, seed=7, dtype=I32)
     dst_i = I.integers((65536, 256), -1000, 1000, seed=8, dtype=I32)
-    assert check_scatter_add(dst_i, 0, idx, src_i, what="int32 full") == "scatter-sort-atomic"
+    assert check_scatter_add(dst_i, 0, idx, src_i, what="int32 full") == "scatter-sort-rows"
     B.tx_force_path("scatter-atomic")          # the same workload with one atomic per element
     try:
         assert check_scatter_add(dst_i, 0, idx, src_i, what="int32 full, plain atomics") == "scatter-atomic"

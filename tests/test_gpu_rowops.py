@@ -134,19 +134,32 @@ def test_cumsum_both_row_kernels_agree_with_oracle():
 
 def test_cumsum_many_tiles_per_row_repeated():
     # long rows: many look-back hops; run several times with the same workspace to cover re-use
-    x_cpu = I.cumsum_input((3, 1 << 20), I64, seed=315)
-    want = O.cumsum(x_cpu, -1)
-    x = x_cpu.cuda()
-    out = torch.empty_like(x)
-    ws = B.workspace(B.tx_cumsum_workspace_bytes(out, x, -1))
-    for _ in range(5):
-        out.zero_()
-        B.tx_cumsum(out, x, -1, ws)
-        torch.cuda.synchronize()
-        assert_exact(out, want, "cumsum int64 repeated")
-        assert ws[4:8].view(torch.int32).item() == 0
+    for n, path in ((1 << 20, "scan-lookback"), ((1 << 22) + 12344, "scan-lookback-wide")):   # 16 KiB and 64 KiB tiles
+        x_cpu = I.cumsum_input((3, n), I64, seed=315)
+        want = O.cumsum(x_cpu, -1)
+        x = x_cpu.cuda()
+        out = torch.empty_like(x)
+        ws = B.workspace(B.tx_cumsum_workspace_bytes(out, x, -1))
+        for _ in range(5):
+            out.zero_()
+            B.tx_cumsum(out, x, -1, ws)
+            torch.cuda.synchronize()
+            assert B.tx_last_path() == path
+            assert_exact(out, want, "cumsum int64 repeated")
+            assert ws[4:8].view(torch.int32).item() == 0
     xf = I.cumsum_input((2, 1 << 21), F32, seed=316)
-    check_cumsum(xf, -1)
+    assert check_cumsum(xf, -1) == "scan-lookback"
+    xf = I.cumsum_input((5, (1 << 22) + 776), F32, seed=319)
+    assert check_cumsum(xf, -1) == "scan-lookback-wide"
+    B.tx_force_path("scan-lookback-narrow")
+    try:
+        assert check_cumsum(xf, -1) == "scan-lookback"
+    finally:
+        B.tx_force_path(None)
+    xh = I.cumsum_input((2, (1 << 23) + 64), BF16, seed=320)     # half input, 8-element vectors
+    assert check_cumsum(xh, -1) == "scan-lookback-wide"
+    xs = I.cumsum_input((3, 3000001), F32, seed=321)             # rows not 16-byte aligned: scalar accesses
+    assert check_cumsum(xs, -1) == "scan-lookback-wide-scalar"
 
 
 def test_cumsum_edges_and_errors():
@@ -174,6 +187,6 @@ def test_cumsum_full_size(dt):
     assert check_cumsum(x, -1) == "scan-carry"           # 4096 rows fill the chip: one workgroup per row
     B.tx_force_path("scan-lookback")                     # the same workload through the single-pass look-back scan
     try:
-        assert check_cumsum(x, -1) == "scan-lookback"
+        assert check_cumsum(x, -1) == "scan-lookback-wide"
     finally:
         B.tx_force_path(None)
