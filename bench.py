@@ -24,7 +24,6 @@ MiB = 1 << 20
 # profiles/ has the commands and the copy calibration: bytes = 2.0 x FETCH_SIZE KiB + 1.0 x WRITE_SIZE KiB).  An entry
 # is valid only for the kernel version it was measured on: remove it when that kernel changes.
 PMC_TRAFFIC_BYTES = {
-    "index_select_f32": (2 * 2109603 + 4194304) * 1024,
 }
 
 
@@ -46,8 +45,12 @@ def build_ops(torch, B):
 
     ops = []
 
-    def add(name, row, kernel, nbytes, elems, fn):
-        ops.append(dict(name=name, row=row, kernel=kernel, bytes=int(nbytes), elems=int(elems), fn=fn))
+    def add(name, row, kernel, nbytes, elems, fn, extra=False):
+        ops.append(dict(name=name, row=row, kernel=kernel, bytes=int(nbytes), elems=int(elems), fn=fn, extra=extra))
+
+    def extra(name, row, kernel, nbytes, elems, fn):
+        """An alternative kernel for a workload the step already covers: timed after the step, not part of `value`."""
+        add(name, row, kernel, nbytes, elems, fn, extra=True)
 
     # ---- workload 1: broadcast add, rotating outputs so the 64 MiB result is not an Infinity-Cache hit
     a1, b1 = randn((4096, 1)), randn((1, 4096))
@@ -163,12 +166,22 @@ def build_ops(torch, B):
     wsi32 = B.workspace(B.tx_scatter_add_workspace_bytes(dst_i, 0, eidx, src_i, True))
     add("scatter_add_i32_rows", "a14", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
         lambda: B.tx_scatter_add_(dst_i, 0, eidx, src_i, True, wsi32))
-    # materialised index, one Zipf draw per element (the secondary scatter_add configuration): one atomic per element
+    # integer atomics, timed outside the step (the dispatcher does not choose them for the row-index workload):
+    # the same workload with one atomic per element, and the secondary configuration with a materialised index
     NE = 131072
     midx = I.zipf_rows(NE * W, ND, 1.1, seed=9).reshape(NE, W).to(dev)
     src_e = src_i[:NE]
-    add("scatter_add_i32_atomic_elem_index", "a14", "scatter_add_atomic_kernel", NE * W * (4 + 8 + 8), NE * W,
-        lambda: B.tx_scatter_add_(dst_i, 0, midx, src_e, True, None))
+
+    def forced_atomic():
+        B.tx_force_path("scatter-atomic")
+        try:
+            B.tx_scatter_add_(dst_i, 0, eidx, src_i, True, wsi32)
+        finally:
+            B.tx_force_path(None)
+    extra("scatter_add_i32_atomic_per_element", "a14", "scatter_add_atomic_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4,
+          NS * W, forced_atomic)
+    extra("scatter_add_i32_atomic_elem_index[131072,256]", "a14", "scatter_add_atomic_kernel", NE * W * (4 + 8 + 8), NE * W,
+          lambda: B.tx_scatter_add_(dst_i, 0, midx, src_e, True, None))
     dst_f = torch.zeros((ND, W), device=dev)
     wss = B.workspace(B.tx_scatter_add_workspace_bytes(dst_f, 0, eidx, src, True))
     add("scatter_add_f32_sorted", "a15", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
@@ -245,11 +258,13 @@ def main():
     if args.only:
         pats = [p for p in args.only.split(",") if p]
         ops = [o for o in ops if any(p in o["name"] for p in pats)]
+    extras = [o for o in ops if o["extra"]]
+    ops = [o for o in ops if not o["extra"]]
     if args.calibrate:
         ca = torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_()
         cb = torch.empty_like(ca)
         ops.append(dict(name="calibration_copy_1GiB", row="-", kernel="device copy", bytes=2 << 30, elems=1 << 28,
-                        fn=lambda: cb.copy_(ca)))
+                        fn=lambda: cb.copy_(ca), extra=False))
     torch.cuda.synchronize()
     for _ in range(args.warmup):
         for op in ops:
@@ -266,6 +281,20 @@ def main():
             e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    outside = []
+    for op in extras:                        # alternatives the dispatcher did not choose: one warm-up, two timed launches
+        op["fn"]()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        op["fn"]()
+        op["fn"]()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 2
+        gbps = op["bytes"] / (ms * 1e-3) / 1e9
+        outside.append({"op": op["name"], "row": op["row"], "kernel": op["kernel"], "us": round(ms * 1e3, 2),
+                        "GB/s": round(gbps, 1), "frac_of_peak": round(gbps / PEAK_GBPS, 4),
+                        "Gelem/s": round(op["elems"] / (ms * 1e-3) / 1e9, 2), "bytes": op["bytes"]})
     step_bytes = sum(op["bytes"] for op in ops)
     step_elems = sum(op["elems"] for op in ops)
     per_op = []
@@ -293,6 +322,7 @@ def main():
                      "traffic": PMC_TRAFFIC_BYTES.get(dom["op"]), "algorithmic_bytes": dom["bytes"],
                      "avg_us": dom["us"]},
         "per_op": per_op,
+        "per_op_outside_step": outside,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(torch)

@@ -126,53 +126,69 @@ template <class T, int N> struct alignas(VecAlign<sizeof(T) * N>::value) Vec {
   T v[N];
 };
 
-// Whole-vector loads and stores.  `nt` marks the access as streaming (non-temporal):
-// data that is touched once should not displace lines other kernels may still want.
+// Whole-vector loads and stores.  `nt` marks the access as streaming (non-temporal): data that is touched once
+// should not displace lines other kernels may still want.  The access is made with a vector of the element's
+// own machine type: when the bytes are loaded as integers and re-typed afterwards, the optimiser rewrites the
+// load with the final type and the non-temporal hint is lost on the way.  NT is a template parameter for the
+// same reason: a hint that depends on a run-time value (or on a function argument, before inlining) is
+// dropped when the optimiser merges the two branches.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-template <class T, int N> __device__ __forceinline__ Vec<T, N> vec_load(const T* p, bool nt) {
+template <class T> struct NativeElem { using type = T; };
+template <> struct NativeElem<bf16> { using type = uint16_t; };
+template <class T, int N> struct NativeVec {
+  typedef typename NativeElem<T>::type type __attribute__((ext_vector_type(N)));
+};
+
+template <class T, int N, bool NT> __device__ __forceinline__ Vec<T, N> vec_load(const T* p) {
+  using E = typename NativeElem<T>::type;
   constexpr int BYTES = sizeof(T) * N;
+  static_assert(BYTES <= 16 || BYTES % 16 == 0, "vectors longer than 16 bytes are moved in 16-byte pieces");
+  constexpr int M = BYTES > 16 ? 16 / (int)sizeof(T) : N;       // elements per access
   Vec<T, N> r;
-  if constexpr (BYTES % 16 == 0) {
+  if constexpr (M == 1) {
 #pragma unroll
-    for (int i = 0; i < BYTES / 16; ++i) {
-      const u32x4* q = (const u32x4*)p + i;
-      u32x4 c = nt ? __builtin_nontemporal_load(q) : *q;
-      __builtin_memcpy((char*)&r + 16 * i, &c, 16);
+    for (int i = 0; i < N; ++i) {
+      const E* q = (const E*)p + i;
+      E c;
+      if constexpr (NT) c = __builtin_nontemporal_load(q); else c = *q;
+      r.v[i] = __builtin_bit_cast(T, c);
     }
-  } else if constexpr (BYTES == 8) {
-    const u32x2* q = (const u32x2*)p;
-    u32x2 c = nt ? __builtin_nontemporal_load(q) : *q;
-    __builtin_memcpy(&r, &c, 8);
-  } else if constexpr (BYTES == 4) {
-    const uint32_t* q = (const uint32_t*)p;
-    uint32_t c = nt ? __builtin_nontemporal_load(q) : *q;
-    __builtin_memcpy(&r, &c, 4);
   } else {
-    r = *(const Vec<T, N>*)p;
+    using NV = typename NativeVec<T, M>::type;
+#pragma unroll
+    for (int i = 0; i < N / M; ++i) {
+      const NV* q = (const NV*)p + i;
+      NV c;
+      if constexpr (NT) c = __builtin_nontemporal_load(q); else c = *q;
+#pragma unroll
+      for (int e = 0; e < M; ++e) r.v[i * M + e] = __builtin_bit_cast(T, (E)c[e]);
+    }
   }
   return r;
 }
-template <class T, int N> __device__ __forceinline__ void vec_store(T* p, const Vec<T, N>& v, bool nt) {
+template <class T, int N, bool NT> __device__ __forceinline__ void vec_store(T* p, const Vec<T, N>& v) {
+  using E = typename NativeElem<T>::type;
   constexpr int BYTES = sizeof(T) * N;
-  if constexpr (BYTES % 16 == 0) {
+  static_assert(BYTES <= 16 || BYTES % 16 == 0, "vectors longer than 16 bytes are moved in 16-byte pieces");
+  constexpr int M = BYTES > 16 ? 16 / (int)sizeof(T) : N;
+  if constexpr (M == 1) {
 #pragma unroll
-    for (int i = 0; i < BYTES / 16; ++i) {
-      u32x4 c;
-      __builtin_memcpy(&c, (const char*)&v + 16 * i, 16);
-      u32x4* q = (u32x4*)p + i;
-      if (nt) __builtin_nontemporal_store(c, q); else *q = c;
+    for (int i = 0; i < N; ++i) {
+      E* q = (E*)p + i;
+      const E c = __builtin_bit_cast(E, v.v[i]);
+      if constexpr (NT) __builtin_nontemporal_store(c, q); else *q = c;
     }
-  } else if constexpr (BYTES == 8) {
-    u32x2 c;
-    __builtin_memcpy(&c, &v, 8);
-    if (nt) __builtin_nontemporal_store(c, (u32x2*)p); else *(u32x2*)p = c;
-  } else if constexpr (BYTES == 4) {
-    uint32_t c;
-    __builtin_memcpy(&c, &v, 4);
-    if (nt) __builtin_nontemporal_store(c, (uint32_t*)p); else *(uint32_t*)p = c;
   } else {
-    *(Vec<T, N>*)p = v;
+    using NV = typename NativeVec<T, M>::type;
+#pragma unroll
+    for (int i = 0; i < N / M; ++i) {
+      NV c;
+#pragma unroll
+      for (int e = 0; e < M; ++e) c[e] = __builtin_bit_cast(E, v.v[i * M + e]);
+      NV* q = (NV*)p + i;
+      if constexpr (NT) __builtin_nontemporal_store(c, q); else *q = c;
+    }
   }
 }
 

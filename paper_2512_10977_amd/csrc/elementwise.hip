@@ -32,8 +32,8 @@ template <class T> struct Elem {
   static constexpr bool dynamic = false;
   static constexpr int static_size = sizeof(T);
   __device__ __forceinline__ static T load(const char* base, int64_t idx, int) { return ((const T*)base)[idx]; }
-  template <int E> __device__ __forceinline__ static void load_vec(const char* base, int64_t idx, int, T (&out)[E], bool nt) {
-    Vec<T, E> v = vec_load<T, E>((const T*)base + idx, nt);
+  template <int E, bool NT> __device__ __forceinline__ static void load_vec(const char* base, int64_t idx, int, T (&out)[E]) {
+    Vec<T, E> v = vec_load<T, E, NT>((const T*)base + idx);
 #pragma unroll
     for (int e = 0; e < E; ++e) out[e] = v.v[e];
   }
@@ -42,13 +42,13 @@ template <class T> struct Elem {
     Vec<T, E> v;
 #pragma unroll
     for (int e = 0; e < E; ++e) v.v[e] = in[e];
-    vec_store<T, E>((T*)base + idx, v, true);
+    vec_store<T, E, true>((T*)base + idx, v);
   }
 };
 
-template <class S, class CT, int E>
-__device__ __forceinline__ void load_cvt_vec(const char* base, int64_t idx, CT (&out)[E], bool nt) {
-  Vec<S, E> v = vec_load<S, E>((const S*)base + idx, nt);
+template <class S, class CT, int E, bool NT>
+__device__ __forceinline__ void load_cvt_vec(const char* base, int64_t idx, CT (&out)[E]) {
+  Vec<S, E> v = vec_load<S, E, NT>((const S*)base + idx);
 #pragma unroll
   for (int e = 0; e < E; ++e) out[e] = cvt<CT>(v.v[e]);
 }
@@ -57,7 +57,7 @@ __device__ __forceinline__ void store_cvt_vec(char* base, int64_t idx, const CT 
   Vec<S, E> v;
 #pragma unroll
   for (int e = 0; e < E; ++e) v.v[e] = cvt<S>(in[e]);
-  vec_store<S, E>((S*)base + idx, v, true);
+  vec_store<S, E, true>((S*)base + idx, v);
 }
 
 template <> struct Elem<Dyn<float>> {
@@ -74,14 +74,14 @@ template <> struct Elem<Dyn<float>> {
       default: return (float)((const uint8_t*)b)[i];
     }
   }
-  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, float (&o)[E], bool nt) {
+  template <int E, bool NT> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, float (&o)[E]) {
     switch (dt) {
-      case TX_F32: load_cvt_vec<float, float, E>(b, i, o, nt); break;
-      case TX_BF16: load_cvt_vec<bf16, float, E>(b, i, o, nt); break;
-      case TX_F16: load_cvt_vec<f16, float, E>(b, i, o, nt); break;
-      case TX_I64: load_cvt_vec<int64_t, float, E>(b, i, o, nt); break;
-      case TX_I32: load_cvt_vec<int32_t, float, E>(b, i, o, nt); break;
-      default: load_cvt_vec<uint8_t, float, E>(b, i, o, nt); break;
+      case TX_F32: load_cvt_vec<float, float, E, NT>(b, i, o); break;
+      case TX_BF16: load_cvt_vec<bf16, float, E, NT>(b, i, o); break;
+      case TX_F16: load_cvt_vec<f16, float, E, NT>(b, i, o); break;
+      case TX_I64: load_cvt_vec<int64_t, float, E, NT>(b, i, o); break;
+      case TX_I32: load_cvt_vec<int32_t, float, E, NT>(b, i, o); break;
+      default: load_cvt_vec<uint8_t, float, E, NT>(b, i, o); break;
     }
   }
   __device__ __forceinline__ static void store(char* b, int64_t i, int dt, float v) {
@@ -111,11 +111,11 @@ template <> struct Elem<Dyn<int64_t>> {
       default: return ((const uint8_t*)b)[i];
     }
   }
-  template <int E> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, int64_t (&o)[E], bool nt) {
+  template <int E, bool NT> __device__ __forceinline__ static void load_vec(const char* b, int64_t i, int dt, int64_t (&o)[E]) {
     switch (dt) {
-      case TX_I64: load_cvt_vec<int64_t, int64_t, E>(b, i, o, nt); break;
-      case TX_I32: load_cvt_vec<int32_t, int64_t, E>(b, i, o, nt); break;
-      default: load_cvt_vec<uint8_t, int64_t, E>(b, i, o, nt); break;
+      case TX_I64: load_cvt_vec<int64_t, int64_t, E, NT>(b, i, o); break;
+      case TX_I32: load_cvt_vec<int32_t, int64_t, E, NT>(b, i, o); break;
+      default: load_cvt_vec<uint8_t, int64_t, E, NT>(b, i, o); break;
     }
   }
   __device__ __forceinline__ static void store(char* b, int64_t i, int dt, int64_t v) {
@@ -185,7 +185,9 @@ template <int NOPS> struct VecArgs {
   int64_t n0;                                // inner extent
 };
 
-template <class In, int E, int NOPS>
+// STREAM is a compile-time flag on purpose: a load whose non-temporal hint depends on a run-time value is
+// compiled as a plain load (the two sides of the branch are merged and the hint is dropped).
+template <class In, int E, bool STREAM, int NOPS>
 __device__ __forceinline__ void vec_fetch(const VecArgs<NOPS>& a, int o, int64_t base, int64_t i, int valid,
                                           typename ValueOf<In>::type (&x)[E]) {
   if constexpr (!std::is_void<In>::value) {
@@ -195,7 +197,7 @@ __device__ __forceinline__ void vec_fetch(const VecArgs<NOPS>& a, int o, int64_t
 #pragma unroll
       for (int e = 0; e < E; ++e) x[e] = v;
     } else if (valid == E) {
-      EL::template load_vec<E>(a.data[o], base + i, a.dtype[o], x, a.stream[o] != 0);
+      EL::template load_vec<E, STREAM>(a.data[o], base + i, a.dtype[o], x);
     } else {
 #pragma unroll
       for (int e = 0; e < E; ++e)
@@ -204,7 +206,9 @@ __device__ __forceinline__ void vec_fetch(const VecArgs<NOPS>& a, int o, int64_t
   }
 }
 
-template <class F, int E, int U>
+// STREAM: every input that is read along the inner dim is read exactly once (no broadcast dim anywhere), so
+// its loads are marked non-temporal.
+template <class F, int E, int U, bool STREAM>
 __global__ __launch_bounds__(kBlock) void ew_vec_kernel(const F f, const VecArgs<F::NIN + 1> a) {
   constexpr int NOPS = F::NIN + 1;
   uint32_t outer, tile;
@@ -230,9 +234,9 @@ __global__ __launch_bounds__(kBlock) void ew_vec_kernel(const F f, const VecArgs
     const int64_t left = a.n0 - i;
     valid[u] = left >= E ? E : (left > 0 ? (int)left : 0);
     if (valid[u] > 0) {
-      vec_fetch<typename F::In0, E>(a, 1, base[1], i, valid[u], x0[u]);
-      if constexpr (F::NIN >= 2) vec_fetch<typename F::In1, E>(a, 2, base[2], i, valid[u], x1[u]);
-      if constexpr (F::NIN >= 3) vec_fetch<typename F::In2, E>(a, 3, base[3], i, valid[u], x2[u]);
+      vec_fetch<typename F::In0, E, STREAM>(a, 1, base[1], i, valid[u], x0[u]);
+      if constexpr (F::NIN >= 2) vec_fetch<typename F::In1, E, STREAM>(a, 2, base[2], i, valid[u], x1[u]);
+      if constexpr (F::NIN >= 3) vec_fetch<typename F::In2, E, STREAM>(a, 3, base[3], i, valid[u], x2[u]);
     }
   }
   using EO = Elem<typename F::Out>;
@@ -414,7 +418,8 @@ __device__ __forceinline__ void tilev_stage(const TileArgs<NOPS>& a, int o, int6
   for (int k = 0; k < TV::PASSES; ++k) {
     const int c = cl + TV::ROWS_PER_PASS * k;
     if (r < a.rows && c0 + c < a.cols) {       // rows is a multiple of V on this path
-      Vec<E, TV::V> t = vec_load<E, TV::V>((const E*)a.data[o] + boff + r + (c0 + c) * a.stride_c[o], true);
+      // cached loads: a 128-byte line of the transposed operand is consumed by several of these 16-byte accesses
+      Vec<E, TV::V> t = vec_load<E, TV::V, false>((const E*)a.data[o] + boff + r + (c0 + c) * a.stride_c[o]);
 #pragma unroll
       for (int j = 0; j < TV::V; ++j) lds[c * TV::PITCH + rv * TV::V + j] = t.v[j];
     }
@@ -431,7 +436,7 @@ __device__ __forceinline__ void tilev_fetch(const TileArgs<NOPS>& a, int o, int6
 #pragma unroll
     for (int j = 0; j < TV::V; ++j) x[j] = lds[(lc + j) * TV::PITCH + lr];
   } else if (a.stride_c[o] == 1) {
-    Vec<E, TV::V> t = vec_load<E, TV::V>((const E*)a.data[o] + boff + r * a.stride_r[o] + c, a.stride_r[o] != 0);
+    Vec<E, TV::V> t = vec_load<E, TV::V, false>((const E*)a.data[o] + boff + r * a.stride_r[o] + c);   // measured: the hint costs 10 % here
 #pragma unroll
     for (int j = 0; j < TV::V; ++j) x[j] = t.v[j];
   } else {                                      // broadcast along c
@@ -482,7 +487,7 @@ __global__ __launch_bounds__(kBlock) void ew_tile_vec_kernel(const F f, const Ti
       Vec<VO, TV::V> y;
 #pragma unroll
       for (int j = 0; j < TV::V; ++j) y.v[j] = apply(f, x0[j], x1[j], x2[j]);
-      vec_store<VO, TV::V>((VO*)a.data[0] + boff[0] + r * a.stride_r[0] + c, y, true);
+      vec_store<VO, TV::V, true>((VO*)a.data[0] + boff[0] + r * a.stride_r[0] + c, y);
     }
   }
 }
@@ -579,12 +584,18 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     a.tiles_per_row = FastDiv((uint32_t)tiles);
     set_path("vec");
     const dim3 grid((unsigned)(outer * tiles));
+    // all inputs streamed (a stride-0 inner operand is one scalar load and does not count)
+    bool all_stream = true;
+    for (int o = 1; o < NOPS; ++o) all_stream = all_stream && (a.stream[o] || a.inner_stride[o] == 0);
     if constexpr (Shape<F>::dynamic) {
-      if (e_rt == 2) hipLaunchKernelGGL((ew_vec_kernel<F, 2, U>), grid, dim3(kBlock), 0, stream, f, a);
-      else hipLaunchKernelGGL((ew_vec_kernel<F, 4, U>), grid, dim3(kBlock), 0, stream, f, a);
+      if (e_rt == 2 && all_stream) hipLaunchKernelGGL((ew_vec_kernel<F, 2, U, true>), grid, dim3(kBlock), 0, stream, f, a);
+      else if (e_rt == 2) hipLaunchKernelGGL((ew_vec_kernel<F, 2, U, false>), grid, dim3(kBlock), 0, stream, f, a);
+      else if (all_stream) hipLaunchKernelGGL((ew_vec_kernel<F, 4, U, true>), grid, dim3(kBlock), 0, stream, f, a);
+      else hipLaunchKernelGGL((ew_vec_kernel<F, 4, U, false>), grid, dim3(kBlock), 0, stream, f, a);
     } else {
-      if (wide) hipLaunchKernelGGL((ew_vec_kernel<F, E, UW>), grid, dim3(kBlock), 0, stream, f, a);
-      else hipLaunchKernelGGL((ew_vec_kernel<F, E, U>), grid, dim3(kBlock), 0, stream, f, a);
+      if (wide) hipLaunchKernelGGL((ew_vec_kernel<F, E, UW, false>), grid, dim3(kBlock), 0, stream, f, a);
+      else if (all_stream) hipLaunchKernelGGL((ew_vec_kernel<F, E, U, true>), grid, dim3(kBlock), 0, stream, f, a);
+      else hipLaunchKernelGGL((ew_vec_kernel<F, E, U, false>), grid, dim3(kBlock), 0, stream, f, a);
     }
     return check_launch("elementwise vec kernel");
   }

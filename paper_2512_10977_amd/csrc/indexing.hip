@@ -107,36 +107,44 @@ struct RowCopyArgs {
   int64_t vecs;               // 16-byte vectors per slice
 };
 
-constexpr int kRowsPerWave = 4;
+constexpr int kRowsPerWave = 8;
 
+// One wave copies 8 selected slices at a time, 16 bytes per lane.  Lane i resolves slice r0 + i (index
+// load, offsets) and the byte offsets are handed out with readlane, so the copy loop has no index
+// dependence; slices past the end are clamped to the last one (the same bytes are then written twice),
+// which keeps every load and store unconditional and their number known at compile time.
 __global__ __launch_bounds__(kBlock) void index_select_rows_kernel(const RowCopyArgs a) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+  const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
   const int64_t r0 = wave * kRowsPerWave;
-  const char* sp[kRowsPerWave];
-  char* dp[kRowsPerWave];
+  if (r0 >= a.rows) return;
+  int64_t so, d_o;
+  {
+    const int64_t r = std::min<int64_t>(r0 + (lane < kRowsPerWave ? lane : 0), a.rows - 1);
+    uint32_t o, j;
+    a.nsel_div.divmod((uint32_t)r, o, j);
+    const int64_t k = load_index(a.index, (int64_t)j * a.istride, a.index_is64);
+    so = (int64_t)o * a.src_outer + k * a.src_dim;
+    d_o = (int64_t)o * a.dst_outer + (int64_t)j * a.dst_dim;
+  }
+  auto lane_value = [&](int64_t v, int i) -> int64_t {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, i);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), i);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+  };
+  const u32x4* sp[kRowsPerWave];
+  u32x4* dp[kRowsPerWave];
 #pragma unroll
   for (int i = 0; i < kRowsPerWave; ++i) {
-    const int64_t r = r0 + i;
-    sp[i] = nullptr;
-    dp[i] = nullptr;
-    if (r < a.rows) {
-      uint32_t o, j;
-      a.nsel_div.divmod((uint32_t)r, o, j);
-      const int64_t k = load_index(a.index, (int64_t)j * a.istride, a.index_is64);
-      sp[i] = a.src + (int64_t)o * a.src_outer + k * a.src_dim;
-      dp[i] = a.dst + (int64_t)o * a.dst_outer + (int64_t)j * a.dst_dim;
-    }
+    sp[i] = (const u32x4*)(a.src + lane_value(so, i));
+    dp[i] = (u32x4*)(a.dst + lane_value(d_o, i));
   }
-  using V16 = Vec<uint32_t, 4>;
   for (int64_t v = lane; v < a.vecs; v += kWave) {
-    V16 t[kRowsPerWave];
+    u32x4 t[kRowsPerWave];
 #pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i)
-      if (sp[i]) t[i] = ((const V16*)sp[i])[v];
+    for (int i = 0; i < kRowsPerWave; ++i) t[i] = sp[i][v];                          // selected rows may be read again
 #pragma unroll
-    for (int i = 0; i < kRowsPerWave; ++i)
-      if (dp[i]) ((V16*)dp[i])[v] = t[i];
+    for (int i = 0; i < kRowsPerWave; ++i) __builtin_nontemporal_store(t[i], dp[i] + v);   // the output is written once
   }
 }
 
@@ -433,7 +441,7 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
     int kbuf = 0;                              // their destination rows: lane i holds the key of slot i
 
     auto park = [&](Acc* part) {               // a piece of a run that crosses a chunk boundary
-      if (active) vec_store<Acc, VEC>(part + chunk * a.width + col, acc, false);      // read again soon by seg_combine_kernel
+      if (active) vec_store<Acc, VEC, false>(part + chunk * a.width + col, acc);      // read again soon by seg_combine_kernel
     };
 
     Vec<T, VEC> row[kBatch], nrow[kBatch];
@@ -444,7 +452,7 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
       for (int b = 0; b < kBatch; ++b) {
         const int e = std::min(e0 + b, cnt - 1);
         nk[b] = key_at(e);
-        nrow[b] = vec_load<T, VEC>(src_col + (int64_t)val_at(e) * a.src_row, true);
+        nrow[b] = vec_load<T, VEC, true>(src_col + (int64_t)val_at(e) * a.src_row);
       }
     };
     // writes the parked sums back: all destination rows first (row[] is free between batches), then add and store
@@ -453,7 +461,7 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
       for (int i = 0; i < kSegSlots; ++i)
         if (i < nbuf) {
           const uint32_t key = (uint32_t)__builtin_amdgcn_readlane(kbuf, i);
-          row[i] = vec_load<T, VEC>(self_col + (int64_t)key * a.self_row, true);
+          row[i] = vec_load<T, VEC, true>(self_col + (int64_t)key * a.self_row);
         }
 #pragma unroll
       for (int i = 0; i < kSegSlots; ++i)
@@ -463,7 +471,7 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
           Vec<T, VEC> t;
 #pragma unroll
           for (int q = 0; q < VEC; ++q) t.v[q] = seg_add<T, Acc>(row[i].v[q], sum.v[q]);
-          if (active) vec_store<T, VEC>(self_col + (int64_t)key * a.self_row, t, true);
+          if (active) vec_store<T, VEC, true>(self_col + (int64_t)key * a.self_row, t);
         }
       nbuf = 0;
     };
@@ -912,7 +920,7 @@ tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t di
       a.vecs = bytes / 16;
       const int64_t waves = (a.rows + kRowsPerWave - 1) / kRowsPerWave;
       set_path("index-select-rows");
-      hipLaunchKernelGGL(index_select_rows_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(kBlock), 0, s, a);
+      hipLaunchKernelGGL(index_select_rows_kernel, dim3((unsigned)((waves + kBlock / kWave - 1) / (kBlock / kWave))), dim3(kBlock), 0, s, a);
       return check_launch("index_select row kernel");
     }
   }

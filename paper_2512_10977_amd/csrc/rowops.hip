@@ -107,16 +107,27 @@ __global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs 
   O* out = (O*)a.out + row * a.orow;
   float v[CH][VEC];
   float m = kNegInf;
+  // Loads go out in groups of up to 8, every one of them unconditional (a vector past the end of the row
+  // re-reads the row's first vector and is replaced by -inf afterwards): a load inside `if (c < len)` is
+  // waited for inside that branch, which leaves one load in flight per wave.
+  constexpr int kGroup = CH < 8 ? CH : 8;
 #pragma unroll
-  for (int k = 0; k < CH; ++k) {
-    const int64_t c = ((int64_t)k * kWave + lane) * VEC;
-    if (c < a.len) {                      // len is a multiple of VEC on this path
-      Vec<T, VEC> t = vec_load<T, VEC>(x + c, true);
+  for (int k0 = 0; k0 < CH; k0 += kGroup) {
+    Vec<T, VEC> t[kGroup];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) { v[k][e] = cvt<float>(t.v[e]); m = fmaxf(m, v[k][e]); }
-    } else {
+    for (int j = 0; j < kGroup; ++j) {
+      const int64_t c = ((int64_t)(k0 + j) * kWave + lane) * VEC;
+      t[j] = vec_load<T, VEC, true>(x + (c < a.len ? c : 0));      // len is a multiple of VEC on this path
+    }
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) v[k][e] = kNegInf;
+    for (int j = 0; j < kGroup; ++j) {
+      const int64_t c = ((int64_t)(k0 + j) * kWave + lane) * VEC;
+      const bool in = c < a.len;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        v[k0 + j][e] = in ? cvt<float>(t[j].v[e]) : kNegInf;
+        m = fmaxf(m, v[k0 + j][e]);
+      }
     }
   }
   m = wave_max(m);
@@ -143,7 +154,7 @@ __global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs 
       Vec<O, VEC> t;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) t.v[e] = from_float<O>(a.is_log ? v[k][e] - ls : v[k][e] * inv);
-      vec_store<O, VEC>(out + c, t, true);
+      vec_store<O, VEC, true>(out + c, t);
     }
   }
 }
@@ -235,6 +246,9 @@ tx_status softmax_launch(const tx_tensor* out, const tx_tensor* x, int dim, int 
     } else if (al && len <= 256 * V) {
       set_path("softmax-wave");
       hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 4>), grid, dim3(kBlock), 0, stream, a);
+    } else if (al && len <= 512 * V) {
+      set_path("softmax-wave");
+      hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 8>), grid, dim3(kBlock), 0, stream, a);
     } else if (al && len <= 1024 * V) {
       set_path("softmax-wave");
       hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 16>), grid, dim3(kBlock), 0, stream, a);
@@ -333,6 +347,57 @@ template <class Acc> __device__ __forceinline__ Acc wave_inclusive(Acc v) {
   return v;
 }
 
+// Loads one tile (NV vectors per lane, lanes interleaved) into accumulators.  A tile that lies wholly inside the
+// row takes the first branch (uniform for the workgroup): NV unconditional vector loads, all in flight before
+// the first conversion.  Only a ragged last tile takes the element-wise branch.
+template <class T, class Acc, int VEC, int THREADS, int NV>
+__device__ __forceinline__ void scan_tile_load_full(const T* xt, Acc (&dst)[NV][VEC]) {
+  Vec<T, VEC> raw[NV];
+#pragma unroll
+  for (int k = 0; k < NV; ++k) raw[k] = vec_load<T, VEC, true>(xt + ((int64_t)k * THREADS + threadIdx.x) * VEC);
+#pragma unroll
+  for (int k = 0; k < NV; ++k)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) dst[k][e] = cvt<Acc>(raw[k].v[e]);
+}
+template <class T, class Acc, int VEC, int THREADS, int NV>
+__device__ __forceinline__ void scan_tile_load(const T* xt, int64_t left, Acc (&dst)[NV][VEC]) {
+  if (left >= (int64_t)THREADS * NV * VEC) {
+    scan_tile_load_full<T, Acc, VEC, THREADS, NV>(xt, dst);
+  } else {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int64_t c = ((int64_t)k * THREADS + threadIdx.x) * VEC;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) dst[k][e] = (c + e < left) ? cvt<Acc>(xt[c + e]) : Acc(0);
+    }
+  }
+}
+template <class O, class Acc, int VEC, int THREADS, int NV>
+__device__ __forceinline__ void scan_tile_store_full(O* ot, const Acc (&v)[NV][VEC], const Acc (&add)[NV]) {
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    Vec<O, VEC> tv;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) tv.v[e] = cvt<O>((Acc)(v[k][e] + add[k]));
+    vec_store<O, VEC, true>(ot + ((int64_t)k * THREADS + threadIdx.x) * VEC, tv);
+  }
+}
+template <class O, class Acc, int VEC, int THREADS, int NV>
+__device__ __forceinline__ void scan_tile_store(O* ot, int64_t left, const Acc (&v)[NV][VEC], const Acc (&add)[NV]) {
+  if (left >= (int64_t)THREADS * NV * VEC) {
+    scan_tile_store_full<O, Acc, VEC, THREADS, NV>(ot, v, add);
+  } else {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      const int64_t c = ((int64_t)k * THREADS + threadIdx.x) * VEC;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (c + e < left) ot[c + e] = cvt<O>((Acc)(v[k][e] + add[k]));
+    }
+  }
+}
+
 // THREADS is 256 or 1024.  Every workgroup draws one ticket from a single counter, and same-address atomics
 // retire at roughly one per 12 ns on this chip, so a 16 KiB tile (256 lanes) caps the kernel near 2.7 TB/s of
 // traffic; 64 KiB tiles (1024 lanes, same registers per lane) keep the ticket off the critical path.  The
@@ -360,18 +425,7 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
 
   Acc v[NV][VEC];
-#pragma unroll
-  for (int k = 0; k < NV; ++k) {
-    const int64_t c = ((int64_t)k * THREADS + threadIdx.x) * VEC;
-    if (c + VEC <= left) {
-      Vec<T, VEC> tv = vec_load<T, VEC>(x + c, true);
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) v[k][e] = cvt<Acc>(tv.v[e]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) v[k][e] = (c + e < left) ? cvt<Acc>(x[c + e]) : Acc(0);
-    }
-  }
+  scan_tile_load<T, Acc, VEC, THREADS, NV>(x, left, v);
   Acc excl[NV];
 #pragma unroll
   for (int k = 0; k < NV; ++k) {
@@ -425,26 +479,17 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
   }
   __syncthreads();
   const Acc p = tile_prefix;
+  Acc add[NV];
 #pragma unroll
-  for (int k = 0; k < NV; ++k) {
-    const int64_t c = ((int64_t)k * THREADS + threadIdx.x) * VEC;
-    const Acc add = p + wave_tot[k * kWaves + w] + excl[k];
-    if (c + VEC <= left) {
-      Vec<O, VEC> tv;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) tv.v[e] = cvt<O>((Acc)(v[k][e] + add));
-      vec_store<O, VEC>(out + c, tv, true);
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e)
-        if (c + e < left) out[c + e] = cvt<O>((Acc)(v[k][e] + add));
-    }
-  }
+  for (int k = 0; k < NV; ++k) add[k] = p + wave_tot[k * kWaves + w] + excl[k];
+  scan_tile_store<O, Acc, VEC, THREADS, NV>(out, left, v, add);
 }
 
 // Row-carry scan: one workgroup walks a whole row tile by tile and carries the running total in registers.
 // No inter-workgroup traffic at all, so it is the better choice whenever there are enough rows to fill the
-// chip; the next tile's loads are issued before the current tile is scanned.
+// chip.  The next tile's loads are issued before the current tile is scanned; for tiles that lie wholly
+// inside the row every load and store is unconditional, so the wait for the prefetched tile can leave the
+// previous tile's stores in flight.
 template <class T, class O, class Acc, int VEC>
 __global__ __launch_bounds__(kBlock) void cumsum_carry_kernel(const ScanArgs a) {
   constexpr int kTileElems = kBlock * kNV * VEC;
@@ -457,30 +502,17 @@ __global__ __launch_bounds__(kBlock) void cumsum_carry_kernel(const ScanArgs a) 
   Acc carry = Acc(0);
   Acc v[kNV][VEC], nxt[kNV][VEC];
 
-  auto fetch = [&](int64_t t, Acc (&dst)[kNV][VEC]) {
-    const int64_t left = a.len - t * kTileElems;
-    const T* xt = x + t * kTileElems;
-#pragma unroll
-    for (int k = 0; k < kNV; ++k) {
-      const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
-      if (c + VEC <= left) {
-        Vec<T, VEC> tv = vec_load<T, VEC>(xt + c, true);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) dst[k][e] = cvt<Acc>(tv.v[e]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) dst[k][e] = (c + e < left) ? cvt<Acc>(xt[c + e]) : Acc(0);
-      }
-    }
-  };
-
-  fetch(0, nxt);
-  for (int64_t t = 0; t < a.tiles_per_row; ++t) {
+  // scans the tile held in nxt (tile t).  steady == true: tiles t and t + 1 are both wholly inside the row, the
+  // prefetch and the stores are branch-free; otherwise t + 1 may be ragged or absent.
+  auto tile = [&](int64_t t, auto steady) {
 #pragma unroll
     for (int k = 0; k < kNV; ++k)
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] = nxt[k][e];
-    if (t + 1 < a.tiles_per_row) fetch(t + 1, nxt);
+    if constexpr (decltype(steady)::value)
+      scan_tile_load_full<T, Acc, VEC, kBlock, kNV>(x + (t + 1) * kTileElems, nxt);
+    else if (t + 1 < a.tiles_per_row)
+      scan_tile_load<T, Acc, VEC, kBlock, kNV>(x + (t + 1) * kTileElems, a.len - (t + 1) * kTileElems, nxt);
     const int buf = (int)(t & 1);
     Acc excl[kNV];
 #pragma unroll
@@ -494,34 +526,29 @@ __global__ __launch_bounds__(kBlock) void cumsum_carry_kernel(const ScanArgs a) 
     }
     __syncthreads();                       // one barrier per tile: the two LDS buffers alternate
     Acc running = carry;
-    Acc base[kNV];
+    Acc add[kNV];
 #pragma unroll
     for (int k = 0; k < kNV; ++k) {
 #pragma unroll
       for (int ww = 0; ww < kWaves; ++ww) {
-        if (ww == w) base[k] = running;
+        if (ww == w) add[k] = running + excl[k];
         running += wave_tot[buf][k][ww];
       }
     }
     carry = running;
-    const int64_t left = a.len - t * kTileElems;
-    O* ot = out + t * kTileElems;
-#pragma unroll
-    for (int k = 0; k < kNV; ++k) {
-      const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
-      const Acc add = base[k] + excl[k];
-      if (c + VEC <= left) {
-        Vec<O, VEC> tv;
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) tv.v[e] = cvt<O>((Acc)(v[k][e] + add));
-        vec_store<O, VEC>(ot + c, tv, true);
-      } else {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e)
-          if (c + e < left) ot[c + e] = cvt<O>((Acc)(v[k][e] + add));
-      }
-    }
-  }
+    if constexpr (decltype(steady)::value) scan_tile_store_full<O, Acc, VEC, kBlock, kNV>(out + t * kTileElems, v, add);
+    else scan_tile_store<O, Acc, VEC, kBlock, kNV>(out + t * kTileElems, a.len - t * kTileElems, v, add);
+  };
+
+  scan_tile_load<T, Acc, VEC, kBlock, kNV>(x, a.len, nxt);
+  // The first tile must have landed before the steady loop is entered: otherwise the loop's own wait has to
+  // cover "loads still pending, nothing issued after them" as well and becomes a full drain, which would also
+  // sit out the previous tile's stores on every iteration.  (vmcnt = 0; the other counters are left alone.)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  const int64_t nfull = a.len / kTileElems;          // tiles wholly inside the row: the branch-free path
+  int64_t t = 0;
+  for (; t + 1 < nfull; ++t) tile(t, std::true_type{});
+  for (; t < a.tiles_per_row; ++t) tile(t, std::false_type{});
 }
 
 template <class T, class O, class Acc>
