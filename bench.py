@@ -130,17 +130,17 @@ def build_ops(torch, B):
     ocf, oci = torch.empty(C, device=dev), torch.empty(C, device=dev, dtype=I64)
     wsf = B.workspace(B.tx_cumsum_workspace_bytes(ocf, cf, -1))
     wsi = B.workspace(B.tx_cumsum_workspace_bytes(oci, ci, -1))
-    add("cumsum_f32", "a11", "cumsum_carry_kernel", nc * 8, nc, lambda: B.tx_cumsum(ocf, cf, -1, wsf))
-    add("cumsum_i64", "a11", "cumsum_carry_kernel", nc * 16, nc, lambda: B.tx_cumsum(oci, ci, -1, wsi))
+    add("cumsum_f32", "a11", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_cumsum(ocf, cf, -1, wsf))
+    add("cumsum_i64", "a11", "cumsum_lookback_kernel", nc * 16, nc, lambda: B.tx_cumsum(oci, ci, -1, wsi))
 
-    def lookback_f32():      # the same scan forced through the single-pass decoupled look-back kernel
-        B.tx_force_path("scan-lookback")
+    def carry_f32():         # the same scan forced through the one-workgroup-per-row kernel (register carry)
+        B.tx_force_path("scan-carry")
         try:
             B.tx_cumsum(ocf, cf, -1, wsf)
         finally:
             B.tx_force_path(None)
-    add("cumsum_f32_lookback", "a11", "cumsum_lookback_kernel", nc * 8, nc, lookback_f32)
-    # few long rows: the shape the look-back scan exists for
+    extra("cumsum_f32_row_carry", "a11", "cumsum_carry_kernel", nc * 8, nc, carry_f32)
+    # few long rows: every row has to be spread over the whole chip
     cl = randn((8, 1 << 24))
     ocl = torch.empty_like(cl)
     wsl = B.workspace(B.tx_cumsum_workspace_bytes(ocl, cl, -1))
