@@ -24,6 +24,7 @@ MiB = 1 << 20
 # profiles/ has the commands and the copy calibration: bytes = 2.0 x FETCH_SIZE KiB + 1.0 x WRITE_SIZE KiB).  An entry
 # is valid only for the kernel version it was measured on: remove it when that kernel changes.
 PMC_TRAFFIC_BYTES = {
+    "index_select_f32": (2 * 2122607 + 4194434) * 1024,
 }
 
 
