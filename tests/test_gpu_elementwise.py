@@ -218,6 +218,13 @@ def test_where_sweep():
             x = I.make_view(shape, dt, kind, seed=141, specials=0.01)
             y = I.make_view(shape, dt, "contig", seed=142, specials=0.01)
             check_where(c, x, y, kind)
+    # which operands are the transposed ones: every combination, tall and wide tile grids (diagonal tile walk)
+    for shape in [(520, 136), (72, 1032)]:
+        for tc, tx, ty in itertools.product((False, True), repeat=3):
+            mk = lambda dt, t, seed: (I.make_view(shape, dt, "transposed", seed=seed) if t
+                                      else I.make_view(shape, dt, "contig", seed=seed))
+            c = I.booleans((shape[1], shape[0]), 0.5, seed=150).t() if tc else I.booleans(shape, 0.5, seed=150)
+            check_where(c, mk(F32, tx, 151), mk(F32, ty, 152), "transposed c/x/y = %d%d%d" % (tc, tx, ty))
     for da, db in MIXED:
         c = I.booleans((7, 13, 5), 0.5, seed=143)
         check_where(c, I.typed((7, 13, 5), da, seed=144), I.typed((7, 13, 5), db, seed=145), "mixed")
