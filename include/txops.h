@@ -183,9 +183,10 @@ tx_status tx_index_select(const tx_tensor* out, const tx_tensor* src, int64_t di
  * src.size(d) for all d and <= self.size(d) for d != dim; self.dtype ==
  * src.dtype.  index may be a stride-0 expanded view.  Integer dtypes use
  * device atomics (exact, order-free); bool ORs.  When the index is a row id
- * broadcast over the trailing dims and a workspace is given, int32 / int64
- * rows are first grouped by destination so that one atomic is issued per run
- * and column instead of one per element.  Float dtypes: with
+ * broadcast over the trailing dims (at least 4096 rows) and a workspace is
+ * given, int32 / int64 rows are instead grouped by destination with the same
+ * sort as the float path and added as whole rows, without atomics; without a
+ * workspace the call falls back to atomics.  Float dtypes: with
  * deterministic != 0 the contributions are sorted by destination and summed in
  * a fixed order with fp32 accumulation (bitwise reproducible run to run); with
  * deterministic == 0, fp32 uses float atomics (fp16 / bf16 keep the sorted
@@ -215,8 +216,12 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
 const char* tx_last_path(void);
 /* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
  * "vec", "tile", "generic".  cumsum along a contiguous dim: "scan-lookback"
- * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".  Requests that a path cannot serve fall back to the automatic
- * choice.  Process-wide; meant for A/B profiling. */
+ * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".
+ * Reduction with lanes along the kept dim: "cols-nv1", "cols-nv2", "cols-nv4"
+ * (vectors per thread).  Integer scatter_add_: "scatter-atomic" (one atomic
+ * per element even when a workspace is given).  Requests that a path cannot
+ * serve fall back to the automatic choice.  Process-wide; meant for A/B
+ * profiling. */
 void tx_force_path(const char* name);
 
 const char* tx_strerror(tx_status status);
