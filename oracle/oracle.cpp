@@ -70,9 +70,11 @@ enum {
 };
 
 // op codes
-enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, ORC_GELU };
-enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ };
-enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR };
+enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, ORC_GELU, ORC_LOG1P, ORC_EXPM1,
+       ORC_LOGSIGMOID };
+enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM, ORC_NE, ORC_LT, ORC_LE, ORC_GT, ORC_GE };
+enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
+       ORC_LOGSUMEXP };
 
 }  // extern "C"
 
@@ -346,9 +348,9 @@ int orc_unary_result_dtype(int op, int in_dtype) {
     case ORC_NEG:
     case ORC_ABS:
       return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
-    case ORC_EXP: case ORC_LOG: case ORC_SQRT: case ORC_SIGMOID: case ORC_TANH:
+    case ORC_EXP: case ORC_LOG: case ORC_SQRT: case ORC_SIGMOID: case ORC_TANH: case ORC_LOG1P: case ORC_EXPM1:
       return is_float(in_dtype) ? in_dtype : ORC_F32;   // integral input computes in fp32
-    case ORC_GELU:
+    case ORC_GELU: case ORC_LOGSIGMOID:
       return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
   }
   return ORC_ERR_DTYPE;
@@ -363,8 +365,10 @@ int orc_infer_binary(int op, const orc_tensor* a, const orc_tensor* b, int32_t* 
   const orc_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
+  if (op < ORC_ADD || op > ORC_GE) return ORC_ERR_DTYPE;
   if (op == ORC_DIV && !is_float(common)) res = ORC_F32;   // true division
-  if (op == ORC_EQ) res = ORC_BOOL;
+  if (op == ORC_EQ || op >= ORC_NE) res = ORC_BOOL;        // the comparison family
+  if (op == ORC_SUB && (a->dtype == ORC_BOOL || b->dtype == ORC_BOOL)) return ORC_ERR_DTYPE;   // no bool subtraction
   int nd;
   int64_t s[ORC_MAX_DIMS];
   int rc = broadcast_shapes(ops, 2, &nd, s);
@@ -434,6 +438,10 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
       case ORC_SIGMOID: y = 1.0 / (1.0 + std::exp(-x)); break;
       case ORC_TANH: y = std::tanh(x); break;
       case ORC_GELU: y = x * (0.5 * std::erfc(-x * 0.70710678118654752440)); break;
+      case ORC_LOG1P: y = std::log1p(x); break;
+      case ORC_EXPM1: y = std::expm1(x); break;
+      // log(1 / (1 + exp(-x))) written so that neither tail overflows or cancels: min(x, 0) - log1p(exp(-|x|))
+      case ORC_LOGSIGMOID: y = (x < 0.0 ? x : 0.0) - std::log1p(std::exp(-std::fabs(x))); break;
     }
     store_flt(out, oo, y);
   }
@@ -454,6 +462,12 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
 //   maximum : NaN if either operand is NaN, else the larger (first operand on
 //             ties).
 //   eq      : equality in the common dtype, bool result.
+//   sub     : a - alpha*b with the rules of add (one IEEE subtraction, or one
+//             fma(-alpha, b, a)); any bool operand is a dtype error.
+//   minimum : NaN if either operand is NaN, else the smaller (first operand on
+//             ties); bool AND.
+//   ne lt le gt ge : IEEE comparisons in the common dtype, bool result (every
+//             ordered comparison with a NaN is false, ne is true).
 int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_tensor* b, double alpha_f,
                int64_t alpha_i, int alpha_is_int) {
   int rc;
@@ -466,7 +480,7 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
   const orc_tensor* ops[2] = {a, b};
   int cd = result_type(ops, 2);                       // dtype the op is applied in
   if (op == ORC_DIV && !is_float(cd)) cd = ORC_F32;
-  if (op == ORC_ADD && !is_float(cd) && !alpha_is_int) return ORC_ERR_SCALAR;
+  if ((op == ORC_ADD || op == ORC_SUB) && !is_float(cd) && !alpha_is_int) return ORC_ERR_SCALAR;
   const double alpha_d = alpha_is_int ? (double)alpha_i : alpha_f;
   const float alpha32 = (float)alpha_d;
   const bool alpha_one = alpha_is_int ? (alpha_i == 1) : (alpha_f == 1.0);
@@ -500,6 +514,22 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
           break;
         }
         case ORC_EQ: store_int(out, oo, x.f == y.f); break;
+        case ORC_SUB: {                               // a - alpha*b: one IEEE subtraction, or one fma(-alpha, b, a)
+          float r = alpha_one ? (x.f - y.f) : std::fmaf(-alpha32, y.f, x.f);
+          store_flt(out, oo, (double)r);
+          break;
+        }
+        case ORC_MINIMUM: {
+          float r = (std::isnan(x.f) || std::isnan(y.f)) ? std::numeric_limits<float>::quiet_NaN()
+                                                         : (y.f < x.f ? y.f : x.f);
+          store_flt(out, oo, (double)r);
+          break;
+        }
+        case ORC_NE: store_int(out, oo, x.f != y.f); break;    // IEEE: every ordered comparison with NaN is false,
+        case ORC_LT: store_int(out, oo, x.f < y.f); break;     // != is true
+        case ORC_LE: store_int(out, oo, x.f <= y.f); break;
+        case ORC_GT: store_int(out, oo, x.f > y.f); break;
+        case ORC_GE: store_int(out, oo, x.f >= y.f); break;
       }
     } else if (cd == ORC_BOOL) {
       switch (op) {
@@ -507,6 +537,12 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_MUL: store_int(out, oo, x.i & y.i); break;
         case ORC_MAXIMUM: store_int(out, oo, x.i | y.i); break;
         case ORC_EQ: store_int(out, oo, x.i == y.i); break;
+        case ORC_MINIMUM: store_int(out, oo, x.i & y.i); break;
+        case ORC_NE: store_int(out, oo, x.i != y.i); break;
+        case ORC_LT: store_int(out, oo, x.i < y.i); break;
+        case ORC_LE: store_int(out, oo, x.i <= y.i); break;
+        case ORC_GT: store_int(out, oo, x.i > y.i); break;
+        case ORC_GE: store_int(out, oo, x.i >= y.i); break;
       }
     } else {
       uint64_t ux = (uint64_t)x.i, uy = (uint64_t)y.i;
@@ -515,6 +551,13 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_MUL: store_int(out, oo, (int64_t)(ux * uy)); break;
         case ORC_MAXIMUM: store_int(out, oo, y.i > x.i ? y.i : x.i); break;
         case ORC_EQ: store_int(out, oo, x.i == y.i); break;
+        case ORC_SUB: store_int(out, oo, (int64_t)(ux - (uint64_t)alpha_i * uy)); break;
+        case ORC_MINIMUM: store_int(out, oo, y.i < x.i ? y.i : x.i); break;
+        case ORC_NE: store_int(out, oo, x.i != y.i); break;
+        case ORC_LT: store_int(out, oo, x.i < y.i); break;
+        case ORC_LE: store_int(out, oo, x.i <= y.i); break;
+        case ORC_GT: store_int(out, oo, x.i > y.i); break;
+        case ORC_GE: store_int(out, oo, x.i >= y.i); break;
       }
     }
   }
@@ -621,9 +664,10 @@ int orc_reduce_result_dtype(int op, int in_dtype) {
   if (!valid_dtype(in_dtype)) return ORC_ERR_DTYPE;
   switch (op) {
     case ORC_SUM: case ORC_PROD: return is_float(in_dtype) ? in_dtype : ORC_I64;
-    case ORC_MEAN: case ORC_VAR: return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
-    case ORC_AMAX: return in_dtype;
-    case ORC_ARGMAX: return in_dtype == ORC_BOOL ? (int)ORC_ERR_DTYPE : (int)ORC_I64;
+    case ORC_MEAN: case ORC_VAR: case ORC_STD: case ORC_LOGSUMEXP: return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_AMAX: case ORC_AMIN: return in_dtype;
+    case ORC_ARGMAX: case ORC_ARGMIN: return in_dtype == ORC_BOOL ? (int)ORC_ERR_DTYPE : (int)ORC_I64;
+    case ORC_ANY: case ORC_ALL: return ORC_BOOL;
   }
   return ORC_ERR_DTYPE;
 }
@@ -635,7 +679,7 @@ int orc_infer_reduce(int op, const orc_tensor* x, const int64_t* dims, int32_t n
   int rd = orc_reduce_result_dtype(op, x->dtype);
   if (rd < 0) return rd;
   bool all = (ndims == 0 || dims == nullptr);
-  if ((op == ORC_PROD || op == ORC_ARGMAX) && ndims > 1) return ORC_ERR_DIM;  // single dim or all
+  if ((op == ORC_PROD || op == ORC_ARGMAX || op == ORC_ARGMIN) && ndims > 1) return ORC_ERR_DIM;  // single dim or all
   bool red[ORC_MAX_DIMS];
   int rc = normalise_dims(x->ndim, dims, ndims, red);
   if (rc) return rc;
@@ -661,6 +705,13 @@ int orc_infer_reduce(int op, const orc_tensor* x, const int64_t* dims, int32_t n
 //           everything and the first NaN wins.  int64 result.
 //   var   : two passes in binary64: mean, then sum of squared deviations,
 //           divided by max(0, n - correction).
+//   std   : the square root of that variance.
+//   amin / argmin : amax / argmax with the order reversed (NaN still wins,
+//           ties still go to the lowest index).
+//   any / all : whether some / every element is non-zero (NaN is non-zero);
+//           any input dtype, bool result; empty extent: any = false, all = true.
+//   logsumexp : max + log(sum exp(x - max)) in binary64; an infinite maximum is
+//           the result (-inf for an empty or all -inf slice), NaN is sticky.
 // A floating `out` dtype wider than x's (fp32 out for a half x) is allowed for
 // sum / mean / prod / var: the single rounding then goes to that dtype.
 int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
@@ -670,7 +721,7 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
   int32_t rd, ond;
   int64_t osz[ORC_MAX_DIMS];
   if ((rc = orc_infer_reduce(op, x, dims, ndims, keepdim, &rd, &ond, osz))) return rc;
-  bool widen_ok = is_float(rd) && out->dtype == ORC_F32 && op != ORC_AMAX;
+  bool widen_ok = is_float(rd) && out->dtype == ORC_F32 && op != ORC_AMAX && op != ORC_AMIN;
   if (out->dtype != rd && !widen_ok) return ORC_ERR_DTYPE;
   if (!same_shape(out, ond, osz)) return ORC_ERR_SHAPE;
   bool red[ORC_MAX_DIMS];
@@ -687,7 +738,8 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
   for (int i = 0; i < nk; ++i) nout *= ksz[i];
   for (int i = 0; i < nr; ++i) nred *= rsz[i];
   if (nout == 0) return ORC_OK;
-  if ((op == ORC_AMAX || op == ORC_ARGMAX) && nred == 0) return ORC_ERR_EMPTY_REDUCTION;
+  if ((op == ORC_AMAX || op == ORC_ARGMAX || op == ORC_AMIN || op == ORC_ARGMIN) && nred == 0)
+    return ORC_ERR_EMPTY_REDUCTION;
   const bool flt = is_float(x->dtype);
   const bool single_dim = (nr == 1);
 
@@ -712,7 +764,19 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
     double bestd = 0.0;
     int64_t besti = 0, bestpos = 0;
     double mean = 0.0;
-    if (op == ORC_VAR) {
+    bool any_true = false, all_true = true;            // any / all: an element counts as true when it is not zero (NaN is)
+    double lse_max = -std::numeric_limits<double>::infinity();
+    bool lse_nan = false;
+    if (op == ORC_LOGSUMEXP) {                         // first pass: the maximum (NaN is sticky)
+      for (int64_t r = 0; r < nred; ++r) {
+        unravel(r, nr, rsz, ridx);
+        for (int i = 0; i < nr; ++i) xi[rdm[i]] = ridx[i];
+        double v = load_flt(x, offset_of(x, xi));
+        if (std::isnan(v)) lse_nan = true;
+        else if (v > lse_max) lse_max = v;
+      }
+    }
+    if (op == ORC_VAR || op == ORC_STD) {
       double s = 0.0;
       for (int64_t r = 0; r < nred; ++r) {
         unravel(r, nr, rsz, ridx);
@@ -733,11 +797,30 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
         case ORC_PROD:
           if (flt) accd *= load_flt(x, xo); else acci *= (uint64_t)load_int(x, xo);
           break;
-        case ORC_VAR: {
+        case ORC_VAR: case ORC_STD: {
           double dlt = load_flt(x, xo) - mean;
           accd += dlt * dlt;
           break;
         }
+        case ORC_ANY: case ORC_ALL: {
+          bool t = flt ? (load_flt(x, xo) != 0.0) : (load_int(x, xo) != 0);     // NaN != 0 is true
+          any_true = any_true || t;
+          all_true = all_true && t;
+          break;
+        }
+        case ORC_LOGSUMEXP:                            // second pass: sum of exp(x - max); skipped when max is infinite
+          if (std::isfinite(lse_max)) accd += std::exp(load_flt(x, xo) - lse_max);
+          break;
+        case ORC_AMIN: case ORC_ARGMIN:
+          if (flt) {
+            double v = load_flt(x, xo);
+            if (!have) { bestd = v; bestpos = pos; have = true; isnan_best = std::isnan(v); }
+            else if (!isnan_best && (std::isnan(v) || v < bestd)) { bestd = v; bestpos = pos; isnan_best = std::isnan(v); }
+          } else {
+            int64_t v = load_int(x, xo);
+            if (!have || v < besti) { besti = v; bestpos = pos; have = true; }
+          }
+          break;
         case ORC_AMAX: case ORC_ARGMAX:
           if (flt) {
             double v = load_flt(x, xo);
@@ -763,10 +846,25 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
         store_flt(out, oo, nred ? accd / div : kNaN);
         break;
       }
-      case ORC_AMAX:
+      case ORC_STD: {
+        double div = (double)nred - correction;
+        if (div < 0.0) div = 0.0;
+        store_flt(out, oo, nred ? std::sqrt(accd / div) : kNaN);
+        break;
+      }
+      case ORC_ANY: store_int(out, oo, any_true); break;
+      case ORC_ALL: store_int(out, oo, all_true); break;
+      case ORC_LOGSUMEXP:
+        // log sum exp(x) = max + log sum exp(x - max); an infinite maximum is the result itself
+        // (-inf for an empty or all -inf slice, +inf when +inf is present), NaN is sticky
+        if (lse_nan) store_flt(out, oo, kNaN);
+        else if (!std::isfinite(lse_max)) store_flt(out, oo, lse_max);
+        else store_flt(out, oo, lse_max + std::log(accd));
+        break;
+      case ORC_AMAX: case ORC_AMIN:
         if (flt) store_flt(out, oo, bestd); else store_int(out, oo, besti);
         break;
-      case ORC_ARGMAX:
+      case ORC_ARGMAX: case ORC_ARGMIN:
         store_int(out, oo, bestpos);
         break;
     }

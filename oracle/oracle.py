@@ -17,9 +17,12 @@ DTYPE_CODE = {torch.bool: BOOL, torch.int32: I32, torch.int64: I64, torch.float1
               torch.bfloat16: BF16, torch.float32: F32}
 CODE_DTYPE = {v: k for k, v in DTYPE_CODE.items()}
 
-UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7}
-BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4}
-REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5}
+UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7, "log1p": 8, "expm1": 9,
+         "logsigmoid": 10}
+BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimum": 6, "ne": 7, "lt": 8, "le": 9, "gt": 10,
+          "ge": 11}
+REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
+          "all": 10, "logsumexp": 11}
 
 ERRORS = {-1: "null", -2: "ndim", -3: "dtype", -4: "shape", -5: "dim", -7: "empty_reduction",
           -8: "scalar", -10: "index"}
