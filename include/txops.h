@@ -81,8 +81,8 @@ enum {
 };
 
 /* operator codes */
-enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF };
-enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ };
+enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF, TX_LOG1P, TX_EXPM1, TX_LOGSIGMOID };
+enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE };
 enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR };
 
 /* ------------------------------------------------------------------ elementwise
@@ -93,10 +93,12 @@ enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR };
 /* out[i] = f(a[i]); out has a's shape.
  *   NEG, ABS : result dtype = a's; bool is TX_ERR_DTYPE; integers wrap; floats
  *              flip / clear the sign bit exactly.
- *   EXP LOG SQRT SIGMOID TANH : float a keeps its dtype; bool / integer a is
- *              converted to fp32 and the result is fp32.  fp32 results are
- *              within 2 ulp of the correctly rounded value.
- *   GELU_ERF : x * Phi(x); float dtypes only. */
+ *   EXP LOG SQRT SIGMOID TANH LOG1P EXPM1 : float a keeps its dtype; bool /
+ *              integer a is converted to fp32 and the result is fp32.  fp32
+ *              results are within 2 ulp of the correctly rounded value.
+ *   GELU_ERF : x * Phi(x); float dtypes only.
+ *   LOGSIGMOID : log(1 / (1 + exp(-x))) (Appendix D's worked example), float
+ *              dtypes only, evaluated as min(x, 0) - log1p(exp(-|x|)). */
 tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream);
 
 /* out = a + alpha * b with broadcasting and type promotion.  alpha is given
@@ -107,11 +109,19 @@ tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* strea
 tx_status tx_add(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f, int64_t alpha_i,
                  int alpha_is_int, void* stream);
 
-/* out = a (op) b with broadcasting and type promotion, op in MUL DIV MAXIMUM EQ
- * (TX_ADD is accepted too, with alpha = 1).
+/* out = a - alpha * b: tx_add's rules with the sign of the second term
+ * reversed (float result: alpha == 1 is one IEEE subtraction, otherwise one
+ * fma(-alpha, b, a) in fp32).  A bool operand is TX_ERR_DTYPE. */
+tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f, int64_t alpha_i,
+                 int alpha_is_int, void* stream);
+
+/* out = a (op) b with broadcasting and type promotion, op in MUL DIV MAXIMUM
+ * MINIMUM EQ NE LT LE GT GE (TX_ADD and TX_SUB are accepted too, with alpha = 1).
  *   MUL: bool AND, integers wrap.  DIV: true division, bool / integer pairs are
- *   computed and returned in fp32.  MAXIMUM: NaN if either operand is NaN.
- *   EQ: compares in the common dtype, result dtype bool. */
+ *   computed and returned in fp32.  MAXIMUM / MINIMUM: NaN if either operand is
+ *   NaN; on ties the first operand; bool OR / AND.
+ *   EQ NE LT LE GT GE: compare in the common dtype, result dtype bool (IEEE:
+ *   every ordered comparison with a NaN is false, NE is true). */
 tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream);
 
 /* out = cond ? x : y.  cond must be bool; result dtype = promotion of x and y;

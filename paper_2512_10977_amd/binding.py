@@ -17,8 +17,10 @@ DTYPE_CODE = {torch.bool: BOOL, torch.int32: I32, torch.int64: I64, torch.float1
               torch.bfloat16: BF16, torch.float32: F32}
 CODE_DTYPE = {v: k for k, v in DTYPE_CODE.items()}
 
-UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7}
-BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4}
+UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7, "log1p": 8, "expm1": 9,
+         "logsigmoid": 10}
+BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimum": 6, "ne": 7, "lt": 8, "le": 9, "gt": 10,
+          "ge": 11}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5}
 
 STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", -6: "OVERLAP",
@@ -26,7 +28,7 @@ STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", 
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so")
 
-EXPORTS = ["tx_unary", "tx_add", "tx_binary", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
+EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
            "tx_softmax", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
@@ -63,6 +65,7 @@ def lib():
     sig = {
         "tx_unary": ([ctypes.c_int, P, P, V], ctypes.c_int32),
         "tx_add": ([P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
+        "tx_sub": ([P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_binary": ([ctypes.c_int, P, P, P, V], ctypes.c_int32),
         "tx_where": ([P, P, P, P, V], ctypes.c_int32),
         "tx_masked_fill": ([P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
@@ -149,6 +152,11 @@ def tx_unary(op, out, a, stream=None):
 def tx_add(out, a, b, alpha=1, stream=None):
     af, ai, isint = _scalar(alpha)
     _check(lib().tx_add(desc(out), desc(a), desc(b), af, ai, isint, _stream(stream)))
+
+
+def tx_sub(out, a, b, alpha=1, stream=None):
+    af, ai, isint = _scalar(alpha)
+    _check(lib().tx_sub(desc(out), desc(a), desc(b), af, ai, isint, _stream(stream)))
 
 
 def tx_binary(op, out, a, b, stream=None):

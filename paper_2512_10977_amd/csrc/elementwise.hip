@@ -754,6 +754,20 @@ struct OpGelu {
   __device__ static float run_half(float x) { return gelu_erf_half(x); }
 };
 
+struct OpLog1p {
+  __device__ static float run(float x) { return log1pf(x); }
+  __device__ static float run_half(float x) { return log1pf(x); }
+};
+struct OpExpm1 {
+  __device__ static float run(float x) { return expm1f(x); }
+  __device__ static float run_half(float x) { return expm1f(x); }
+};
+// log(sigmoid(x)) = min(x, 0) - log1p(exp(-|x|)): neither tail overflows or cancels
+struct OpLogSigmoid {
+  __device__ static float run(float x) { return logsigmoid_f32(x); }
+  __device__ static float run_half(float x) { return fminf(x, 0.0f) - log1pf(expf(-fabsf(x))); }
+};
+
 // float math op on a statically typed float tensor (computes in fp32)
 template <class Op, class T> struct MathStatic {
   using Out = T; using In0 = T; using In1 = void; using In2 = void;
@@ -794,51 +808,66 @@ enum { kAdd = TX_ADD, kMul = TX_MUL, kDiv = TX_DIV, kMax = TX_MAXIMUM, kEq = TX_
 __device__ __forceinline__ float fmax_nan(float a, float b) {
   return (a != a || b != b) ? __uint_as_float(0x7fc00000u) : (b > a ? b : a);
 }
+__device__ __forceinline__ float fmin_nan(float a, float b) {
+  return (a != a || b != b) ? __uint_as_float(0x7fc00000u) : (b < a ? b : a);
+}
+// the comparison family, selected at run time (wave-uniform): one set of kernels serves all six
+template <class V> __device__ __forceinline__ uint8_t compare(int code, V a, V b) {
+  switch (code) {
+    case TX_EQ: return a == b;
+    case TX_NE: return a != b;
+    case TX_LT: return a < b;
+    case TX_LE: return a <= b;
+    case TX_GT: return a > b;
+    default: return a >= b;
+  }
+}
 
 // same-dtype float binary op (fp32 arithmetic, one rounding to T)
 template <int OP, class T> struct BinFloat {
   using Out = T; using In0 = T; using In1 = T; using In2 = void;
   static constexpr int NIN = 2;
   float alpha;
-  int alpha_one;
+  int flag;                 // kAdd: alpha == 1 (plain add); kMax: 1 = minimum
   __device__ __forceinline__ T operator()(T xa, T xb) const {
     float a = cvt<float>(xa), b = cvt<float>(xb), r;
-    if constexpr (OP == kAdd) r = alpha_one ? a + b : __fmaf_rn(alpha, b, a);
+    if constexpr (OP == kAdd) r = flag ? a + b : __fmaf_rn(alpha, b, a);
     else if constexpr (OP == kMul) r = a * b;
     else if constexpr (OP == kDiv) r = a / b;
-    else r = fmax_nan(a, b);
+    else r = flag ? fmin_nan(a, b) : fmax_nan(a, b);
     return cvt<T>(r);
   }
 };
 template <class T> struct EqStatic {
   using Out = uint8_t; using In0 = T; using In1 = T; using In2 = void;
   static constexpr int NIN = 2;
+  int code;                 // TX_EQ ... TX_GE
   __device__ __forceinline__ uint8_t operator()(T a, T b) const {
-    if constexpr (std::is_integral<T>::value) return a == b;
-    else return cvt<float>(a) == cvt<float>(b);
+    if constexpr (std::is_integral<T>::value) return compare(code, a, b);
+    else return compare(code, cvt<float>(a), cvt<float>(b));
   }
 };
 template <int OP, class T> struct BinInt {
   using Out = T; using In0 = T; using In1 = T; using In2 = void;
   static constexpr int NIN = 2;
-  int64_t alpha;
+  int64_t alpha;            // kMax: 1 = minimum
   __device__ __forceinline__ T operator()(T a, T b) const {
     using UT = typename std::make_unsigned<T>::type;
     if constexpr (OP == kAdd) return (T)((UT)a + (UT)alpha * (UT)b);
     else if constexpr (OP == kMul) return (T)((UT)a * (UT)b);
-    else return b > a ? b : a;
+    else return alpha ? (b < a ? b : a) : (b > a ? b : a);
   }
 };
 template <int OP> struct BinBool {
   using Out = uint8_t; using In0 = uint8_t; using In1 = uint8_t; using In2 = void;
   static constexpr int NIN = 2;
-  int alpha_nonzero;
+  int flag;                 // kAdd: alpha != 0; kMax: 1 = minimum; kEq: comparison code
   __device__ __forceinline__ uint8_t operator()(uint8_t a, uint8_t b) const {
     a = a != 0; b = b != 0;
-    if constexpr (OP == kAdd) return a | (b & (uint8_t)alpha_nonzero);
+    if constexpr (OP == kAdd) return a | (b & (uint8_t)flag);
     else if constexpr (OP == kMul) return a & b;
-    else if constexpr (OP == kMax) return a | b;
-    else return a == b;
+    else if constexpr (OP == kMax) return flag ? (a & b) : (a | b);
+    else return compare(flag, a, b);
   }
 };
 // mixed-dtype float-result binary op: operands converted to the common dtype first
@@ -846,43 +875,43 @@ template <int OP> struct BinDynFloat {
   using Out = Dyn<float>; using In0 = Dyn<float>; using In1 = Dyn<float>; using In2 = void;
   static constexpr int NIN = 2;
   float alpha;
-  int alpha_one, common;
+  int flag, common;         // flag as in BinFloat
   __device__ __forceinline__ float operator()(float a, float b) const {
     a = quantize(a, common);
     b = quantize(b, common);
-    if constexpr (OP == kAdd) return alpha_one ? a + b : __fmaf_rn(alpha, b, a);
+    if constexpr (OP == kAdd) return flag ? a + b : __fmaf_rn(alpha, b, a);
     else if constexpr (OP == kMul) return a * b;
     else if constexpr (OP == kDiv) return a / b;
-    else return fmax_nan(a, b);
+    else return flag ? fmin_nan(a, b) : fmax_nan(a, b);
   }
 };
 struct EqDynFloat {
   using Out = uint8_t; using In0 = Dyn<float>; using In1 = Dyn<float>; using In2 = void;
   static constexpr int NIN = 2;
-  int common;
+  int common, code;
   __device__ __forceinline__ uint8_t operator()(float a, float b) const {
-    return quantize(a, common) == quantize(b, common);
+    return compare(code, quantize(a, common), quantize(b, common));
   }
 };
 template <int OP> struct BinDynInt {
   using Out = Dyn<int64_t>; using In0 = Dyn<int64_t>; using In1 = Dyn<int64_t>; using In2 = void;
   static constexpr int NIN = 2;
-  int64_t alpha;
+  int64_t alpha;            // kMax: 1 = minimum
   int common;
   __device__ __forceinline__ int64_t operator()(int64_t a, int64_t b) const {
     if (common == TX_I32) { a = (int32_t)a; b = (int32_t)b; }
     if constexpr (OP == kAdd) return (int64_t)((uint64_t)a + (uint64_t)alpha * (uint64_t)b);
     else if constexpr (OP == kMul) return (int64_t)((uint64_t)a * (uint64_t)b);
-    else return b > a ? b : a;
+    else return alpha ? (b < a ? b : a) : (b > a ? b : a);
   }
 };
 struct EqDynInt {
   using Out = uint8_t; using In0 = Dyn<int64_t>; using In1 = Dyn<int64_t>; using In2 = void;
   static constexpr int NIN = 2;
-  int common;
+  int common, code;
   __device__ __forceinline__ uint8_t operator()(int64_t a, int64_t b) const {
     if (common == TX_I32) { a = (int32_t)a; b = (int32_t)b; }
-    return a == b;
+    return compare(code, a, b);
   }
 };
 
@@ -930,38 +959,42 @@ template <class Op> tx_status dispatch_math(const Iter& it, int in_dtype, hipStr
   }
 }
 
+// `variant`: kMax: 1 = minimum; kEq: the comparison code (TX_EQ ... TX_GE); unused otherwise
 template <int OP> tx_status dispatch_binary(const Iter& it, int da, int db, int common, double alpha_f, int64_t alpha_i,
-                                            int alpha_is_int, hipStream_t s) {
+                                            int alpha_is_int, hipStream_t s, int variant = 0) {
   const double ad = alpha_is_int ? (double)alpha_i : alpha_f;
   const bool one = alpha_is_int ? alpha_i == 1 : alpha_f == 1.0;
+  const int fflag = OP == kMax ? variant : (int)one;                 // BinFloat / BinDynFloat flag
+  const int64_t ialpha = OP == kMax ? (int64_t)variant : alpha_i;     // BinInt / BinDynInt field
   const bool same = da == common && db == common;
   if (dtype_is_float(common)) {
     if constexpr (OP == kEq) {
       if (same) {
-        if (common == TX_F32) return launch_ew(it, EqStatic<float>{}, s);
-        if (common == TX_BF16) return launch_ew(it, EqStatic<bf16>{}, s);
-        return launch_ew(it, EqStatic<f16>{}, s);
+        if (common == TX_F32) return launch_ew(it, EqStatic<float>{variant}, s);
+        if (common == TX_BF16) return launch_ew(it, EqStatic<bf16>{variant}, s);
+        return launch_ew(it, EqStatic<f16>{variant}, s);
       }
-      return launch_ew(it, EqDynFloat{common}, s);
+      return launch_ew(it, EqDynFloat{common, variant}, s);
     } else {
       if (same) {
-        if (common == TX_F32) return launch_ew(it, BinFloat<OP, float>{(float)ad, one}, s);
-        if (common == TX_BF16) return launch_ew(it, BinFloat<OP, bf16>{(float)ad, one}, s);
-        return launch_ew(it, BinFloat<OP, f16>{(float)ad, one}, s);
+        if (common == TX_F32) return launch_ew(it, BinFloat<OP, float>{(float)ad, fflag}, s);
+        if (common == TX_BF16) return launch_ew(it, BinFloat<OP, bf16>{(float)ad, fflag}, s);
+        return launch_ew(it, BinFloat<OP, f16>{(float)ad, fflag}, s);
       }
-      return launch_ew(it, BinDynFloat<OP>{(float)ad, one, common}, s);
+      return launch_ew(it, BinDynFloat<OP>{(float)ad, fflag, common}, s);
     }
   }
   if constexpr (OP != kDiv) {
-    if (common == TX_BOOL) return launch_ew(it, BinBool<OP>{alpha_is_int ? alpha_i != 0 : alpha_f != 0.0}, s);
+    if (common == TX_BOOL)
+      return launch_ew(it, BinBool<OP>{OP == kAdd ? (int)(alpha_is_int ? alpha_i != 0 : alpha_f != 0.0) : variant}, s);
     if constexpr (OP == kEq) {
-      if (same && common == TX_I32) return launch_ew(it, EqStatic<int32_t>{}, s);
-      if (same && common == TX_I64) return launch_ew(it, EqStatic<int64_t>{}, s);
-      return launch_ew(it, EqDynInt{common}, s);
+      if (same && common == TX_I32) return launch_ew(it, EqStatic<int32_t>{variant}, s);
+      if (same && common == TX_I64) return launch_ew(it, EqStatic<int64_t>{variant}, s);
+      return launch_ew(it, EqDynInt{common, variant}, s);
     } else {
-      if (same && common == TX_I32) return launch_ew(it, BinInt<OP, int32_t>{alpha_i}, s);
-      if (same && common == TX_I64) return launch_ew(it, BinInt<OP, int64_t>{alpha_i}, s);
-      return launch_ew(it, BinDynInt<OP>{alpha_i, common}, s);
+      if (same && common == TX_I32) return launch_ew(it, BinInt<OP, int32_t>{ialpha}, s);
+      if (same && common == TX_I64) return launch_ew(it, BinInt<OP, int64_t>{ialpha}, s);
+      return launch_ew(it, BinDynInt<OP>{ialpha, common}, s);
     }
   }
   return fail(TX_ERR_UNSUPPORTED, "no kernel for this binary op / dtype");
@@ -980,7 +1013,7 @@ tx_status binary_impl(int op, const tx_tensor* out, const tx_tensor* a, const tx
   const tx_tensor* ins[2] = {a, b};
   int common = result_type(ins, 2);
   if (op == TX_DIV && !dtype_is_float(common)) common = TX_F32;
-  if (op == TX_ADD && !dtype_is_float(common) && !alpha_is_int)
+  if ((op == TX_ADD || op == TX_SUB) && !dtype_is_float(common) && !alpha_is_int)
     return fail(TX_ERR_SCALAR, "floating alpha with an integer / bool result");
   if ((rc = check_out_overlap(out, ins, 2))) return rc;
   set_path("");
@@ -993,8 +1026,14 @@ tx_status binary_impl(int op, const tx_tensor* out, const tx_tensor* a, const tx
     case TX_ADD: return dispatch_binary<kAdd>(it, a->dtype, b->dtype, common, alpha_f, alpha_i, alpha_is_int, s);
     case TX_MUL: return dispatch_binary<kMul>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
     case TX_DIV: return dispatch_binary<kDiv>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
-    case TX_MAXIMUM: return dispatch_binary<kMax>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
-    case TX_EQ: return dispatch_binary<kEq>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s);
+    case TX_MAXIMUM: return dispatch_binary<kMax>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s, 0);
+    case TX_MINIMUM: return dispatch_binary<kMax>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s, 1);
+    // a - alpha * b = a + (-alpha) * b: one fma(-alpha, b, a) for floats (alpha = 1: the exactly rounded a - b),
+    // wrapping arithmetic for integers
+    case TX_SUB:
+      return dispatch_binary<kAdd>(it, a->dtype, b->dtype, common, -alpha_f, (int64_t)(0 - (uint64_t)alpha_i), alpha_is_int, s);
+    case TX_EQ: case TX_NE: case TX_LT: case TX_LE: case TX_GT: case TX_GE:
+      return dispatch_binary<kEq>(it, a->dtype, b->dtype, common, 1.0, 1, 1, s, op);
   }
   return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
 }
@@ -1037,6 +1076,9 @@ tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* strea
     case TX_SIGMOID: return dispatch_math<OpSigmoid>(it, a->dtype, s);
     case TX_TANH: return dispatch_math<OpTanh>(it, a->dtype, s);
     case TX_GELU_ERF: return dispatch_math<OpGelu>(it, a->dtype, s);
+    case TX_LOG1P: return dispatch_math<OpLog1p>(it, a->dtype, s);
+    case TX_EXPM1: return dispatch_math<OpExpm1>(it, a->dtype, s);
+    case TX_LOGSIGMOID: return dispatch_math<OpLogSigmoid>(it, a->dtype, s);
   }
   return fail(TX_ERR_DTYPE, "unknown unary op %d", op);
 }
@@ -1044,6 +1086,11 @@ tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* strea
 tx_status tx_add(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f, int64_t alpha_i,
                  int alpha_is_int, void* stream) {
   return binary_impl(TX_ADD, out, a, b, alpha_f, alpha_i, alpha_is_int, stream);
+}
+
+tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, double alpha_f, int64_t alpha_i,
+                 int alpha_is_int, void* stream) {
+  return binary_impl(TX_SUB, out, a, b, alpha_f, alpha_i, alpha_is_int, stream);
 }
 
 tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream) {

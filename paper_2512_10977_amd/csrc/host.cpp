@@ -180,10 +180,10 @@ int32_t tx_infer_unary_dtype(int op, int32_t in) {
     case TX_ABS:
       if (in == TX_BOOL) return fail(TX_ERR_DTYPE, "neg/abs do not take bool");
       return in;
-    case TX_EXP: case TX_LOG: case TX_SQRT: case TX_SIGMOID: case TX_TANH:
+    case TX_EXP: case TX_LOG: case TX_SQRT: case TX_SIGMOID: case TX_TANH: case TX_LOG1P: case TX_EXPM1:
       return dtype_is_float(in) ? in : TX_F32;
-    case TX_GELU_ERF:
-      if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "gelu takes floating dtypes only");
+    case TX_GELU_ERF: case TX_LOGSIGMOID:
+      if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "gelu / logsigmoid take floating dtypes only");
       return in;
   }
   return fail(TX_ERR_DTYPE, "unknown unary op %d", op);
@@ -195,12 +195,14 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (a->ndim < 0 || a->ndim > TX_MAX_DIMS || b->ndim < 0 || b->ndim > TX_MAX_DIMS)
     return fail(TX_ERR_NDIM, "infer_binary: bad ndim");
   if (!dtype_valid(a->dtype) || !dtype_valid(b->dtype)) return fail(TX_ERR_DTYPE, "infer_binary: bad dtype code");
-  if (op < TX_ADD || op > TX_EQ) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
+  if (op < TX_ADD || op > TX_GE) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
   const tx_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
   if (op == TX_DIV && !dtype_is_float(common)) res = TX_F32;
-  if (op == TX_EQ) res = TX_BOOL;
+  if (op == TX_EQ || op >= TX_NE) res = TX_BOOL;
+  if (op == TX_SUB && (a->dtype == TX_BOOL || b->dtype == TX_BOOL))
+    return fail(TX_ERR_DTYPE, "sub does not take bool operands");
   int nd;
   int64_t s[TX_MAX_DIMS];
   tx_status rc = broadcast_shapes(ops, 2, &nd, s);

@@ -100,6 +100,16 @@ __device__ __forceinline__ float gelu_erf_f32(float xf) {
   return (float)(x * phi);
 }
 
+// log(sigmoid(x)) = min(x, 0) - log1p(exp(-|x|)), composed in binary64 like the functions above
+__device__ __forceinline__ float logsigmoid_f32(float xf) {
+  if (xf != xf) return xf;
+  const double x = (double)xf;
+  double m = -__builtin_fabs(x);
+  m = m < -708.0 ? -708.0 : m;                         // exp(-708) ~ 3e-308: far below one ulp of |x| there
+  const double e = exp_d(m);
+  return (float)((x < 0.0 ? x : 0.0) - log1p(e));
+}
+
 // gelu for fp16 / bf16 results (8-11 significant bits): the same erfc form in plain fp32 with a degree-5
 // fit (relative error 5.5e-5, same fit_erfcx.py recipe) and the hardware exp2 / reciprocal.
 __device__ __forceinline__ float gelu_erf_half(float x) {

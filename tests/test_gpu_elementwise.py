@@ -20,8 +20,9 @@ pytestmark = pytest.mark.gpu
 
 F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
 ALL = [F32, BF16, F16, I32, I64, BOOL]
-UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu"]
-BINARY = ["add", "mul", "div", "maximum", "eq"]
+UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu", "log1p", "expm1", "logsigmoid"]
+BINARY = ["add", "mul", "div", "maximum", "eq", "sub", "minimum", "ne", "lt", "le", "gt", "ge"]
+COMPARE = ("eq", "ne", "lt", "le", "gt", "ge")
 MIXED = [(I32, I64), (I64, F32), (BF16, F32), (F16, BF16), (BOOL, I32), (I64, F16)]
 
 
@@ -62,7 +63,15 @@ FLT_TINY = 1.2e-38
 
 
 def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what=""):
-    want = O.binary(op, a_cpu, b_cpu, alpha=alpha)
+    try:
+        want = O.binary(op, a_cpu, b_cpu, alpha=alpha)
+    except O.OracleError as err:                  # the library must refuse what the oracle refuses, with the same class
+        with pytest.raises(B.TxError) as e:
+            out = torch.empty(torch.broadcast_shapes(a_cpu.shape, b_cpu.shape), dtype=a_cpu.dtype, device="cuda")
+            (B.tx_sub(out, to_device_view(a_cpu), to_device_view(b_cpu), alpha) if op == "sub"
+             else B.tx_binary(op, out, to_device_view(a_cpu), to_device_view(b_cpu)))
+        assert e.value.kind.lower() == err.kind, (op, a_cpu.dtype, b_cpu.dtype, e.value.kind, err.kind)
+        return "refused"
     a, b = to_device_view(a_cpu), to_device_view(b_cpu)
     ref_layout = a if tuple(a.shape) == tuple(want.shape) else torch.empty(want.shape, device="meta")
     out = empty_like_layout(ref_layout, want.dtype, layout=layout)
@@ -70,6 +79,8 @@ def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what="")
     try:
         if op == "add":
             B.tx_add(out, a, b, alpha)
+        elif op == "sub":
+            B.tx_sub(out, a, b, alpha)
         else:
             B.tx_binary(op, out, a, b)
         used = B.tx_last_path()
@@ -77,7 +88,7 @@ def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what="")
         B.tx_force_path(None)
     sync()
     what = "%s %s,%s %s %s %s [%s]" % (op, a_cpu.dtype, b_cpu.dtype, tuple(want.shape), what, layout, used)
-    if op == "eq":
+    if op in COMPARE:
         assert_exact(out, want, what)
     elif op == "div":
         if want.dtype == F32:
@@ -156,6 +167,38 @@ def test_add_alpha_variants():
         check_binary("add", a, b, alpha=-7)
     check_binary("add", I.typed((50,), BOOL, seed=1), I.typed((50,), BOOL, seed=2), alpha=0)
     check_binary("add", I.typed((50,), I64, seed=1), I.typed((50,), F16, seed=2), alpha=0.5)
+
+
+def test_sub_alpha_variants_and_binary_entry():
+    for dt in (F32, BF16, F16):
+        a = I.typed((300, 77), dt, seed=112, specials=0.01)
+        b = I.typed((300, 77), dt, seed=113, specials=0.01)
+        for alpha in (0.1, -2.5, 3, -1):
+            check_binary("sub", a, b, alpha=alpha)
+    for dt in (I32, I64):
+        a = I.typed((300, 77), dt, seed=114)
+        b = I.typed((300, 77), dt, seed=115)
+        check_binary("sub", a, b, alpha=-7)
+        check_binary("sub", a, b, alpha=2 ** 31 + 5)
+    check_binary("sub", I.typed((50,), I64, seed=1), I.typed((50,), F16, seed=2), alpha=0.5)
+    # tx_binary(SUB) is alpha = 1
+    a, b = I.typed((40, 9), F32, seed=116).cuda(), I.typed((9,), F32, seed=117).cuda()
+    out = torch.empty((40, 9), device="cuda")
+    B.tx_binary("sub", out, a, b)
+    sync()
+    assert_exact_fp(out, O.binary("sub", a.cpu(), b.cpu()), "tx_binary sub")
+    with pytest.raises(B.TxError) as e:
+        B.tx_sub(torch.empty(3, dtype=I64, device="cuda"), torch.zeros(3, dtype=I64, device="cuda"),
+                 torch.zeros(3, dtype=I64, device="cuda"), 0.5)
+    assert e.value.kind == "SCALAR"
+
+
+@pytest.mark.parametrize("op", ["minimum", "lt", "ge", "ne"])
+def test_new_binary_ops_full_size(op):
+    a = I.typed((8192, 8192), F32, seed=2, specials=0.01)
+    b = I.typed((8192, 8192), F32, seed=3, specials=0.01)
+    b[::3] = a[::3]                                   # real ties
+    assert check_binary(op, a, b) == "vec"
 
 
 # --------------------------------------------------------------------------- multi-tile, ragged, every path
@@ -312,7 +355,21 @@ def test_unary_full_size(op, dt):
     assert check_unary(op, a) == "vec"
 
 
+@pytest.mark.parametrize("op", ["log1p", "expm1", "logsigmoid"])
+def test_new_unary_full_size_and_wide_range(op):
+    a = I.typed(FULL, F32, seed=176, specials=0.01)
+    assert check_unary(op, a) == "vec"
+    # magnitudes from 1e-30 to 1e3, both signs: the small-argument and the saturating ends of each function
+    g = torch.Generator().manual_seed(177)
+    mag = torch.pow(10.0, torch.rand(1 << 22, generator=g, dtype=torch.float64) * 33 - 30)
+    x = (mag * (torch.randint(0, 2, mag.shape, generator=g) * 2 - 1)).float()
+    check_unary(op, x, what="log-uniform magnitudes")
+    check_unary(op, I.typed((1 << 20,), BF16, seed=178, specials=0.01), what="bf16")
+    check_unary(op, I.typed((1 << 20,), F16, seed=179, specials=0.01), what="f16")
+
+
 @pytest.mark.parametrize("op,da,db,kind", [
+    ("sub", F32, F32, "transposed"), ("minimum", BF16, BF16, "contig"), ("le", I64, I64, "contig"), ("gt", BF16, F32, "contig"),
     ("add", F32, F32, "contig"), ("mul", BF16, BF16, "contig"), ("add", I64, I64, "contig"),
     ("eq", F32, F32, "contig"), ("maximum", F32, F32, "transposed"), ("add", BF16, F32, "contig"),
     ("div", F32, F32, "step2_inner"), ("mul", F32, F32, "step2_outer"), ("add", F16, F16, "expand_row"),
