@@ -92,6 +92,15 @@ def build_ops(torch, B):
     add("add_f32_transposed", "a5", "ew_tile_kernel", n2 * 12, n2, lambda: B.tx_add(of, xf.t(), yf, 1))
     add("mul_bf16_transposed", "a5", "ew_tile_kernel", n2 * 6, n2, lambda: B.tx_binary("mul", ob, xb.t(), xb))
 
+    # second batch of elementwise operators (same iterator paths), timed outside the step
+    extra("sub_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_sub(of, xf, yf, 1))
+    extra("minimum_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("minimum", of, xf, yf))
+    extra("lt_f32", "f1", "ew_vec_kernel", n2 * 9, n2, lambda: B.tx_binary("lt", obool, xf, yf))
+    extra("log1p_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("log1p", of, xf))
+    extra("expm1_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("expm1", of, xf))
+    extra("logsigmoid_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("logsigmoid", of, xf))
+    extra("logsigmoid_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("logsigmoid", ob, xb))
+
     # ---- workload 3: reductions over x[64,4096,1024]
     R = (64, 4096, 1024)
     nr = 64 * 4096 * 1024
@@ -115,6 +124,16 @@ def build_ops(torch, B):
     add("sum_f32_all", "a9", "reduce_rows_kernel", nr * 4 + 4, nr, reducer("sum", rf, None, (), F32))
     add("sum_i64_all", "a9", "reduce_rows_kernel", nr * 8 + 8, nr, reducer("sum", ri, None, (), I64))
     add("prod_f32_all", "a9", "reduce_rows_kernel", nr * 4 + 4, nr, reducer("prod", rf, None, (), F32))
+    # second batch of reductions, timed outside the step
+    extra("amin_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("amin", rf, -1, (64, 4096), F32))
+    extra("argmin_f32_dim0", "f1", "reduce_cols_kernel", nr * 4 + 4096 * 1024 * 8, nr, reducer("argmin", rf, 0, (4096, 1024), I64))
+    extra("std_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("std", rf, -1, (64, 4096), F32))
+    extra("logsumexp_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr,
+          reducer("logsumexp", rf, -1, (64, 4096), F32))
+    extra("logsumexp_bf16_dim0", "f1", "reduce_cols_kernel", nr * 2 + 4096 * 1024 * 2, nr,
+          reducer("logsumexp", rb, 0, (4096, 1024), BF16))
+    extra("all_i64_all_dims", "f1", "reduce_rows_kernel", nr * 8 + 1, nr, reducer("all", ri, None, (), torch.bool))
+    extra("any_f32_dims(0,2)", "f1", "reduce_rows_kernel", nr * 4 + 4096, nr, reducer("any", rf, (0, 2), (4096,), torch.bool))
 
     # ---- workload 4: softmax [32768,4096], cumsum [4096,65536]
     S = (32768, 4096)

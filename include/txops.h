@@ -72,7 +72,7 @@ enum {
   TX_ERR_SHAPE = -4,           /* not broadcastable, wrong out shape, index shape rules, negative size/stride */
   TX_ERR_DIM = -5,             /* dim out of range or repeated; several dims for prod / argmax */
   TX_ERR_OVERLAP = -6,         /* out overlaps itself or partially overlaps an input */
-  TX_ERR_EMPTY_REDUCTION = -7, /* amax / argmax over an empty reduced extent */
+  TX_ERR_EMPTY_REDUCTION = -7, /* amax / amin / argmax / argmin over an empty reduced extent */
   TX_ERR_SCALAR = -8,          /* non-integral alpha with an integer / bool result */
   TX_ERR_WORKSPACE = -9,       /* workspace missing or smaller than tx_*_workspace_bytes() */
   TX_ERR_INDEX = -10,          /* reserved: index validation (indices are not checked on the device) */
@@ -83,7 +83,8 @@ enum {
 /* operator codes */
 enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF, TX_LOG1P, TX_EXPM1, TX_LOGSIGMOID };
 enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE };
-enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR };
+enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARGMIN, TX_STD, TX_ANY, TX_ALL,
+       TX_LOGSUMEXP };
 
 /* ------------------------------------------------------------------ elementwise
  * (Table 1 "Elementwise"; the flat masked kernels of Appendix B are the paper's
@@ -150,7 +151,16 @@ tx_status tx_masked_fill(const tx_tensor* out, const tx_tensor* self, const tx_t
  *         logical shape with no dim; ties -> lowest index; NaN outranks
  *         everything, first NaN wins; bool is TX_ERR_DTYPE.
  *   VAR   float only; sum of squared deviations / max(0, n - correction).
- * For SUM / MEAN / PROD / VAR on fp16 / bf16 input, out may be fp32.
+ *   STD   the square root of VAR.
+ *   AMIN / ARGMIN  AMAX / ARGMAX with the order reversed (NaN still wins, ties
+ *         still go to the lowest index).
+ *   ANY / ALL  any input dtype, bool result: some / every element is non-zero
+ *         (NaN is non-zero); empty extent: ANY false, ALL true.
+ *   LOGSUMEXP  float only; log of the sum of exp(x), computed as a running
+ *         (maximum, scaled sum) pair; -inf for an empty or all -inf extent,
+ *         +inf if +inf is present, NaN is sticky.
+ * For SUM / MEAN / PROD / VAR / STD / LOGSUMEXP on fp16 / bf16 input, out may
+ * be fp32.
  * ws / ws_bytes: device scratch of at least tx_reduce_workspace_bytes() for the
  * same arguments (0 when the reduction is not split across workgroups; the
  * data pointers of out / x are not dereferenced by the query). */

@@ -21,7 +21,8 @@ UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh"
          "logsigmoid": 10}
 BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimum": 6, "ne": 7, "lt": 8, "le": 9, "gt": 10,
           "ge": 11}
-REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5}
+REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
+          "all": 10, "logsumexp": 11}
 
 STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", -6: "OVERLAP",
           -7: "EMPTY_REDUCTION", -8: "SCALAR", -9: "WORKSPACE", -10: "INDEX", -11: "LAUNCH", -12: "UNSUPPORTED"}

@@ -765,7 +765,7 @@ struct OpExpm1 {
 // log(sigmoid(x)) = min(x, 0) - log1p(exp(-|x|)): neither tail overflows or cancels
 struct OpLogSigmoid {
   __device__ static float run(float x) { return logsigmoid_f32(x); }
-  __device__ static float run_half(float x) { return fminf(x, 0.0f) - log1pf(expf(-fabsf(x))); }
+  __device__ static float run_half(float x) { return logsigmoid_half(x); }
 };
 
 // float math op on a statically typed float tensor (computes in fp32)

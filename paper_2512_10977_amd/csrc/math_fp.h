@@ -100,14 +100,39 @@ __device__ __forceinline__ float gelu_erf_f32(float xf) {
   return (float)(x * phi);
 }
 
-// log(sigmoid(x)) = min(x, 0) - log1p(exp(-|x|)), composed in binary64 like the functions above
+// log(sigmoid(x)) = min(x, 0) - log1p(e), e = exp(-|x|) in (0, 1], composed in binary64 like the functions above.
+// log1p(e) = 2 atanh(z) with z = e / (2 + e) <= 1/3: z (1 + w/3 + w^2/5 + ... + w^10/21), w = z^2 <= 1/9; the first
+// dropped term is below 1e-12 relative.
 __device__ __forceinline__ float logsigmoid_f32(float xf) {
   if (xf != xf) return xf;
   const double x = (double)xf;
   double m = -__builtin_fabs(x);
   m = m < -708.0 ? -708.0 : m;                         // exp(-708) ~ 3e-308: far below one ulp of |x| there
   const double e = exp_d(m);
-  return (float)((x < 0.0 ? x : 0.0) - log1p(e));
+  const double z = e * rcp_d(2.0 + e);
+  const double w = z * z;
+  double p = 1.0 / 21.0;
+  p = __builtin_fma(p, w, 1.0 / 19.0);
+  p = __builtin_fma(p, w, 1.0 / 17.0);
+  p = __builtin_fma(p, w, 1.0 / 15.0);
+  p = __builtin_fma(p, w, 1.0 / 13.0);
+  p = __builtin_fma(p, w, 1.0 / 11.0);
+  p = __builtin_fma(p, w, 1.0 / 9.0);
+  p = __builtin_fma(p, w, 1.0 / 7.0);
+  p = __builtin_fma(p, w, 1.0 / 5.0);
+  p = __builtin_fma(p, w, 1.0 / 3.0);
+  p = __builtin_fma(p, w, 1.0);
+  const double l1p = 2.0 * z * p;
+  return (float)((x < 0.0 ? x : 0.0) - l1p);
+}
+
+// the same for fp16 / bf16 results in plain fp32: log1p(e) = log(u) e / (u - 1) with u = 1 + e rounded (exact
+// when u == 1), hardware exp2 / log2
+__device__ __forceinline__ float logsigmoid_half(float x) {
+  const float e = __expf(-__builtin_fabsf(x));
+  const float u = 1.0f + e;
+  const float l1p = u == 1.0f ? e : __logf(u) * e * __builtin_amdgcn_rcpf(u - 1.0f);
+  return __builtin_fminf(x, 0.0f) - l1p;
 }
 
 // gelu for fp16 / bf16 results (8-11 significant bits): the same erfc form in plain fp32 with a degree-5

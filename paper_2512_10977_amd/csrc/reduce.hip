@@ -133,8 +133,11 @@ size_t acc_size(int op, int dtype) {
     case TX_SUM: case TX_MEAN: return flt ? 4 : 8;
     case TX_PROD: return 8;
     case TX_AMAX: return flt ? 4 : 8;
-    case TX_ARGMAX: return 16;
-    case TX_VAR: return 16;
+    case TX_ARGMAX: case TX_ARGMIN: return 16;
+    case TX_VAR: case TX_STD: return 16;
+    case TX_AMIN: return flt ? 4 : 8;
+    case TX_ANY: case TX_ALL: return 8;
+    case TX_LOGSUMEXP: return 8;
   }
   return 16;
 }
@@ -177,7 +180,8 @@ tx_status build_plan(int op, const tx_tensor* x, const tx_tensor* out, const int
   plan_dims(p, x, out, reduced, keepdim);
   if ((p->nk > 1 && p->nout >= (1ll << 31)) || (p->nr > 1 && p->nred >= (1ll << 31)))
     return fail(TX_ERR_UNSUPPORTED, "reduction extents beyond 2^31 with non-mergeable dims");
-  plan_launch(p, x, dtype_size(x->dtype), op == TX_VAR);
+  plan_launch(p, x, dtype_size(x->dtype), op == TX_VAR || op == TX_STD);
+  p->aux = (op == TX_STD || op == TX_ALL) ? 1.0 : 0.0;
   if (p->blocks_x >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "too many outputs for one launch");
   return TX_OK;
 }
@@ -199,19 +203,20 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
   int rd;
   switch (op) {
     case TX_SUM: case TX_PROD: rd = flt ? x->dtype : TX_I64; break;
-    case TX_MEAN: case TX_VAR:
-      if (!flt) return fail(TX_ERR_DTYPE, "mean / var take floating dtypes only");
+    case TX_MEAN: case TX_VAR: case TX_STD: case TX_LOGSUMEXP:
+      if (!flt) return fail(TX_ERR_DTYPE, "mean / var / std / logsumexp take floating dtypes only");
       rd = x->dtype;
       break;
-    case TX_AMAX: rd = x->dtype; break;
-    case TX_ARGMAX:
-      if (x->dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "argmax does not take bool");
+    case TX_AMAX: case TX_AMIN: rd = x->dtype; break;
+    case TX_ARGMAX: case TX_ARGMIN:
+      if (x->dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "argmax / argmin do not take bool");
       rd = TX_I64;
       break;
+    case TX_ANY: case TX_ALL: rd = TX_BOOL; break;
     default: return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
   }
-  if ((op == TX_PROD || op == TX_ARGMAX) && ndims > 1 && dims)
-    return fail(TX_ERR_DIM, "prod / argmax reduce one dim or all dims");
+  if ((op == TX_PROD || op == TX_ARGMAX || op == TX_ARGMIN) && ndims > 1 && dims)
+    return fail(TX_ERR_DIM, "prod / argmax / argmin reduce one dim or all dims");
   bool reduced[TX_MAX_DIMS];
   tx_status rc = normalise_dims(x->ndim, dims, ndims, reduced);
   if (rc) return rc;
@@ -232,7 +237,7 @@ static tx_status reduce_checks(int op, const tx_tensor* out, const tx_tensor* x,
   int32_t rd, nd;
   int64_t shape[TX_MAX_DIMS];
   if ((rc = tx_infer_reduce(op, x, dims, ndims, keepdim, &rd, &nd, shape))) return rc;
-  const bool widen = dtype_is_float(rd) && out->dtype == TX_F32 && op != TX_AMAX;
+  const bool widen = dtype_is_float(rd) && out->dtype == TX_F32 && op != TX_AMAX && op != TX_AMIN;
   if (out->dtype != rd && !widen)
     return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
   if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the reduced shape");
@@ -251,8 +256,8 @@ tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int6
   // a dummy out for planning is not needed: out is validated above
   if ((rc = build_plan(op, x, out, dims, ndims, keepdim, &p))) return rc;
   if (p.nout == 0) return TX_OK;
-  if ((op == TX_AMAX || op == TX_ARGMAX) && p.nred == 0)
-    return fail(TX_ERR_EMPTY_REDUCTION, "amax / argmax over an empty extent");
+  if ((op == TX_AMAX || op == TX_ARGMAX || op == TX_AMIN || op == TX_ARGMIN) && p.nred == 0)
+    return fail(TX_ERR_EMPTY_REDUCTION, "amax / amin / argmax / argmin over an empty extent");
   hipStream_t s = as_stream(stream);
   switch (op) {
     case TX_SUM: return launch_sum(false, p, x, out, correction, ws, ws_bytes, s);
@@ -261,6 +266,11 @@ tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int6
     case TX_PROD: return launch_prod(p, x, out, correction, ws, ws_bytes, s);
     case TX_AMAX: return launch_amax(p, x, out, correction, ws, ws_bytes, s);
     case TX_ARGMAX: return launch_argmax(p, x, out, correction, ws, ws_bytes, s);
+    case TX_STD: return launch_var(p, x, out, correction, ws, ws_bytes, s);          // Plan::aux asks for the square root
+    case TX_AMIN: return launch_amin(p, x, out, correction, ws, ws_bytes, s);
+    case TX_ARGMIN: return launch_argmin(p, x, out, correction, ws, ws_bytes, s);
+    case TX_ANY: case TX_ALL: return launch_anyall(p, x, out, correction, ws, ws_bytes, s);
+    case TX_LOGSUMEXP: return launch_logsumexp(p, x, out, correction, ws, ws_bytes, s);
   }
   return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
 }

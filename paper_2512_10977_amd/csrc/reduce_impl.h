@@ -38,6 +38,7 @@ struct Plan {
   int vec;                          // elements per load (1 or 16/sizeof(T))
   int group;                        // rows: lanes per output (64 or 256)
   int nv;                           // cols: vectors per thread (1, 2 or 4)
+  double aux;                       // per-op switch handed to Policy::finish (std: 1 = square root; any / all: 1 = all)
   int split;                        // S
   int64_t chunk;                    // reduced elements per split
   int64_t blocks_x;
@@ -56,6 +57,7 @@ struct Args {
   int64_t nout, nred, chunk;
   int split, group;
   double correction;
+  double aux;                   // see Plan::aux
 };
 
 // ---------------------------------------------------------------------------
@@ -98,18 +100,20 @@ template <class T> struct ProdPolicy {
   }
 };
 
-template <class T> struct AmaxPolicy {
+// MIN = true: amin (the same policy with the order reversed)
+template <class T, bool MIN = false> struct AmaxPolicy {
   using In = T;
   static constexpr bool flt = IsFloatT<T>::value;
   using Acc = typename std::conditional<flt, float, int64_t>::type;
   static constexpr bool needs_shift = false;
   __device__ static Acc init() {
-    if constexpr (flt) return __uint_as_float(0xff800000u);
-    else return (Acc)0x8000000000000000ll;
+    if constexpr (flt) return __uint_as_float(MIN ? 0x7f800000u : 0xff800000u);
+    else return MIN ? (Acc)0x7fffffffffffffffll : (Acc)0x8000000000000000ll;
   }
+  __device__ static bool beats(Acc b, Acc a) { return MIN ? b < a : b > a; }
   __device__ static void merge(Acc& a, const Acc& b) {
-    if constexpr (flt) a = (a != a) ? a : ((b != b) ? b : (b > a ? b : a));
-    else a = b > a ? b : a;
+    if constexpr (flt) a = (a != a) ? a : ((b != b) ? b : (beats(b, a) ? b : a));
+    else a = beats(b, a) ? b : a;
   }
   __device__ static void step(Acc& a, T x, int64_t, double) { merge(a, cvt<Acc>(x)); }
   __device__ static Acc shfl(const Acc& a, int m) { return shfl_xor(a, m); }
@@ -119,7 +123,8 @@ template <class T> struct AmaxPolicy {
 };
 
 template <class V> struct ArgAcc { V v; int64_t i; };
-template <class T> struct ArgmaxPolicy {
+// MIN = true: argmin
+template <class T, bool MIN = false> struct ArgmaxPolicy {
   using In = T;
   static constexpr bool flt = IsFloatT<T>::value;
   using V = typename std::conditional<flt, float, int64_t>::type;
@@ -127,18 +132,19 @@ template <class T> struct ArgmaxPolicy {
   static constexpr bool needs_shift = false;
   __device__ static Acc init() {
     Acc a;
-    if constexpr (flt) a.v = __uint_as_float(0xff800000u);
-    else a.v = (V)0x8000000000000000ll;
+    if constexpr (flt) a.v = __uint_as_float(MIN ? 0x7f800000u : 0xff800000u);
+    else a.v = MIN ? (V)0x7fffffffffffffffll : (V)0x8000000000000000ll;
     a.i = 0x7fffffffffffffffll;
     return a;
   }
+  __device__ static bool beats(V v1, V v2) { return MIN ? v1 < v2 : v1 > v2; }
   // does (v1,i1) outrank (v2,i2)?  NaN outranks everything; ties go to the lower index
   __device__ static bool better(V v1, int64_t i1, V v2, int64_t i2) {
     if constexpr (flt) {
       bool n1 = v1 != v1, n2 = v2 != v2;
       if (n1 || n2) return (n1 && n2) ? i1 < i2 : n1;
     }
-    return v1 > v2 || (v1 == v2 && i1 < i2);
+    return beats(v1, v2) || (v1 == v2 && i1 < i2);
   }
   __device__ static void merge(Acc& a, const Acc& b) { if (better(b.v, b.i, a.v, a.i)) a = b; }
   // a lane meets its elements in increasing position, so within a lane a strict comparison keeps the
@@ -146,14 +152,77 @@ template <class T> struct ArgmaxPolicy {
   __device__ static void step(Acc& a, T x, int64_t pos, double) {
     V v = cvt<V>(x);
     bool take;
-    if constexpr (flt) take = !(a.v != a.v) && (v > a.v || v != v);
-    else take = v > a.v;
+    if constexpr (flt) take = !(a.v != a.v) && (beats(v, a.v) || v != v);
+    else take = beats(v, a.v);
     if (take) { a.v = v; a.i = pos; }
   }
   __device__ static Acc shfl(const Acc& a, int m) { Acc r; r.v = shfl_xor(a.v, m); r.i = shfl_xor(a.i, m); return r; }
-  // an untouched index means nothing exceeded the initial lowest value: every element equals it, the first one wins
+  // an untouched index means nothing beat the initial extreme value: every element equals it, the first one wins
   __device__ static void finish(const Acc& a, int64_t, double, double, double*, int64_t* i) {
     *i = a.i == 0x7fffffffffffffffll ? 0 : a.i;
+  }
+};
+
+// any / all: two bits per accumulator (some element non-zero, every element non-zero); finish picks one.
+// NaN counts as non-zero.
+struct AnyAllAcc { uint32_t any, all; };
+template <class T> struct AnyAllPolicy {
+  using In = T;
+  static constexpr bool flt = false;                 // integer-style store (bool out)
+  using Acc = AnyAllAcc;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() { return Acc{0u, 1u}; }
+  __device__ static void step(Acc& a, T x, int64_t, double) {
+    uint32_t t;
+    if constexpr (IsFloatT<T>::value) t = cvt<float>(x) != 0.0f;
+    else t = x != 0;
+    a.any |= t;
+    a.all &= t;
+  }
+  __device__ static void merge(Acc& a, const Acc& b) { a.any |= b.any; a.all &= b.all; }
+  __device__ static Acc shfl(const Acc& a, int m) { return Acc{shfl_xor(a.any, m), shfl_xor(a.all, m)}; }
+  __device__ static void finish(const Acc& a, int64_t, double, double want_all, double*, int64_t* i) {
+    *i = want_all != 0.0 ? a.all : a.any;
+  }
+};
+
+// logsumexp as a running (maximum, sum of exp(x - maximum)) pair; pairs merge by rescaling the smaller side.
+// A NaN maximum is sticky; an infinite maximum is the result itself.
+struct LseAcc { float m, s; };
+template <class T> struct LsePolicy {
+  using In = T;
+  static constexpr bool flt = true;
+  using Acc = LseAcc;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() { return Acc{__uint_as_float(0xff800000u), 0.0f}; }
+  // a NaN seen so far lives in s (step) or in m; merge makes both NaN
+  __device__ static void merge(Acc& a, const Acc& b) {
+    if (a.m != a.m || a.s != a.s || b.m != b.m || b.s != b.s) {
+      a.m = a.s = __uint_as_float(0x7fc00000u);
+      return;
+    }
+    const float M = b.m > a.m ? b.m : a.m;
+    if (M == __uint_as_float(0xff800000u)) return;             // both empty / all -inf so far
+    if (M == __uint_as_float(0x7f800000u)) { a.m = M; a.s = 1.0f; return; }
+    a.s = a.s * expf(a.m - M) + b.s * expf(b.m - M);            // exp(-inf) = 0 for a side that is still empty
+    a.m = M;
+  }
+  // one element without branches: e = exp(-|v - m|) (1 when v == m, which covers equal infinities);
+  // v <= m: s += e, else s = s e + 1 and m = v.  exp(-inf) = 0 handles the empty state and +inf; a NaN element
+  // makes s NaN for good.  Hardware exp2: its relative error (~1e-7 |v - m|) only matters for terms near 1.
+  __device__ static void step(Acc& a, T x, int64_t, double) {
+    const float v = cvt<float>(x);
+    const float d = v == a.m ? 0.0f : -__builtin_fabsf(v - a.m);
+    const float e = __expf(d);
+    const bool le = v <= a.m;
+    a.s = __builtin_fmaf(e, le ? 1.0f : a.s, le ? a.s : 1.0f);
+    a.m = __builtin_fmaxf(a.m, v);
+  }
+  __device__ static Acc shfl(const Acc& a, int m) { return Acc{shfl_xor(a.m, m), shfl_xor(a.s, m)}; }
+  __device__ static void finish(const Acc& a, int64_t, double, double, double* f, int64_t*) {
+    const bool inf = a.m == __uint_as_float(0x7f800000u) || a.m == __uint_as_float(0xff800000u);
+    const bool nan = a.m != a.m || a.s != a.s;
+    *f = nan ? (double)__uint_as_float(0x7fc00000u) : inf ? (double)a.m : (double)a.m + (double)logf(a.s);
   }
 };
 
@@ -173,13 +242,14 @@ template <class T> struct VarPolicy {
   }
   __device__ static void merge(Acc& a, const Acc& b) { a.s1 += b.s1; a.s2 += b.s2; }
   __device__ static Acc shfl(const Acc& a, int m) { return Acc{shfl_xor(a.s1, m), shfl_xor(a.s2, m)}; }
-  __device__ static void finish(const Acc& a, int64_t n, double correction, double, double* f, int64_t*) {
+  __device__ static void finish(const Acc& a, int64_t n, double correction, double take_sqrt, double* f, int64_t*) {
     double nn = (double)n;
     double div = nn - correction;
     if (div < 0.0) div = 0.0;
     double m2 = a.s2 - a.s1 * a.s1 / nn;
     if (m2 < 0.0) m2 = 0.0;
-    *f = n ? m2 / div : __longlong_as_double(0x7ff8000000000000ll);
+    double v = n ? m2 / div : __longlong_as_double(0x7ff8000000000000ll);
+    *f = take_sqrt != 0.0 ? __builtin_sqrt(v) : v;           // std
   }
 };
 
@@ -204,7 +274,7 @@ template <bool FLT> __device__ __forceinline__ void store_result(char* out, int6
 template <class P> __device__ __forceinline__ void emit(const Args& a, const typename P::Acc& acc, int64_t oo) {
   double f = 0.0;
   int64_t i = 0;
-  P::finish(acc, a.nred, a.correction, 0.0, &f, &i);
+  P::finish(acc, a.nred, a.correction, a.aux, &f, &i);
   // argmax produces an index even for float input
   if constexpr (std::is_same<typename P::Acc, ArgAcc<float>>::value || std::is_same<typename P::Acc, ArgAcc<int64_t>>::value)
     ((int64_t*)a.out)[oo] = i;
@@ -477,6 +547,7 @@ template <class P> tx_status launch(const Plan& p, const tx_tensor* x, const tx_
   a.split = p.split;
   a.group = p.group;
   a.correction = correction;
+  a.aux = p.aux;
   if (p.split > 1) {
     size_t need = plan_ws_bytes(p, sizeof(typename P::Acc));
     if (!ws || ws_bytes < need) return fail(TX_ERR_WORKSPACE, "reduce needs %zu workspace bytes, got %zu", need, ws_bytes);
@@ -512,6 +583,10 @@ tx_status launch_var(const Plan&, const tx_tensor* x, const tx_tensor* out, doub
 tx_status launch_prod(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
 tx_status launch_amax(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
 tx_status launch_argmax(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_amin(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_argmin(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_anyall(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_logsumexp(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
 size_t acc_size(int op, int dtype);
 
 }  // namespace red

@@ -17,7 +17,7 @@ from tests.parity import assert_exact, assert_exact_fp, assert_rel, to_device_vi
 pytestmark = pytest.mark.gpu
 
 F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
-OPS = ["sum", "mean", "amax", "argmax", "prod", "var"]
+OPS = ["sum", "mean", "amax", "argmax", "prod", "var", "amin", "argmin", "std", "any", "all", "logsumexp"]
 FLT_MIN = 1.1754943508222875e-38
 
 
@@ -38,6 +38,8 @@ def natural_scale(op, x, dims, keepdim):
         return s / max(n, 1) if op == "mean" else s
     if op == "prod":
         return FLT_MIN
+    if op == "logsumexp":
+        return 1.0             # max + log(sum): the absolute error scales with |max|, floor one
     return 0.0
 
 
@@ -59,9 +61,9 @@ def check_reduce(op, x_cpu, dims=None, keepdim=False, correction=1.0, out_dtype=
     used = B.tx_last_path()
     torch.cuda.synchronize()
     what = "%s %s %s dims=%s keepdim=%s %s [%s]" % (op, x_cpu.dtype, tuple(x_cpu.shape), dims, keepdim, what, used)
-    if op == "argmax" or not want.dtype.is_floating_point:
+    if op in ("argmax", "argmin") or not want.dtype.is_floating_point:
         assert_exact(out, want, what)
-    elif op == "amax":
+    elif op in ("amax", "amin"):
         assert_exact_fp(out, want, what)
     else:
         rel = 1e-5 if want.dtype == F32 and x_cpu.dtype == F32 else (1e-5 if want.dtype == F32 else 1e-2)
@@ -107,10 +109,20 @@ def test_reduce_error_codes():
         with pytest.raises(B.TxError) as e:
             B.tx_reduce("sum", d(), d(2, 3, 4), bad)
         assert e.value.kind == "DIM"
-    for op in ("prod", "argmax"):
+    for op in ("prod", "argmax", "argmin"):
         with pytest.raises(B.TxError) as e:
-            B.tx_reduce(op, d(3, dt=I64 if op == "argmax" else F32), d(2, 3, 4), (0, 2))
+            B.tx_reduce(op, d(3, dt=I64 if op != "prod" else F32), d(2, 3, 4), (0, 2))
         assert e.value.kind == "DIM"
+    for op in ("std", "logsumexp"):
+        with pytest.raises(B.TxError) as e:
+            B.tx_reduce(op, d(dt=I64), d(4, dt=I64))
+        assert e.value.kind == "DTYPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_reduce("any", d(3), d(3, 4), 1)                 # any / all return bool
+    assert e.value.kind == "DTYPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_reduce("amin", d(3), d(3, 0), 1)
+    assert e.value.kind == "EMPTY_REDUCTION"
     with pytest.raises(B.TxError) as e:
         B.tx_reduce("mean", d(dt=I64), d(4, dt=I64))
     assert e.value.kind == "DTYPE"
@@ -147,7 +159,7 @@ def test_reduce_multi_tile_ragged(op):
         paths.add(check_reduce(op, I.typed((600, 9001), dt, seed=215, std=1.0), 1))   # long rows, enough of them: block per row
     paths.discard(None)
     assert {"rows-wave", "rows-block", "rows-split", "cols"} <= paths, paths
-    if op != "argmax" and op != "amax":
+    if op in ("sum", "mean", "prod", "var", "std", "logsumexp"):
         check_reduce(op, I.typed((64, 300), BF16, seed=213, std=1.0), 1, out_dtype=F32, what="fp32 out")
 
 
@@ -172,10 +184,41 @@ def full_inputs():
 @pytest.mark.parametrize("dt", [F32, BF16, I64])
 def test_reduce_full_size(full_inputs, dt, dims):
     x = full_inputs[dt]
-    ops = ["sum", "amax", "argmax"] if dt == I64 else OPS
+    ops = ["sum", "amax", "argmax"] if dt == I64 else OPS[:6]
     if dims is None:        # the oracle walks all 2.7e8 elements on one core per op: keep the all-dims list short
         ops = {F32: ["sum", "argmax", "var"], BF16: ["mean", "amax", "prod"], I64: ["sum", "argmax"]}[dt]
     for op in ops:
         if dims == (0, 2) and op in ("prod", "argmax"):
             continue
         check_reduce(op, x, dims, keepdim=(op == "sum"))
+
+
+@pytest.mark.parametrize("dims", [0, -1])
+def test_new_reductions_full_size(full_inputs, dims):
+    for op in ("amin", "argmin", "std", "logsumexp"):
+        check_reduce(op, full_inputs[F32], dims)
+    for op in ("logsumexp", "amin"):
+        check_reduce(op, full_inputs[BF16], dims)
+    x = full_inputs[I64]
+    check_reduce("argmin", x, dims)
+    z = (x % 7 != 0).to(torch.int32)                         # mostly non-zero: "all" has to see every zero
+    z[:, 5, 9] = 1
+    z[3, :, 11] = 1
+    check_reduce("all", z, dims)
+    check_reduce("any", (x % 1000003 == 0), dims)
+
+
+def test_std_and_logsumexp_details():
+    x = I.typed((33, 257), F32, seed=216, std=1.0)
+    for c in (0.0, 1.0, 2.5, 300.0):
+        check_reduce("std", x, 1, correction=c)
+    check_reduce("std", x + 1024.0, 1)
+    big = I.typed((40, 3000), F32, seed=217, std=30.0)       # spread of 100+ in the exponent: rescaling matters
+    check_reduce("logsumexp", big, 1)
+    check_reduce("logsumexp", big - 20000.0, 1)
+    check_reduce("logsumexp", big + 20000.0, None)
+    inf = float("inf")
+    sp = torch.tensor([[1.0, -inf, 2.0], [-inf, -inf, -inf], [inf, 1.0, 2.0], [float("nan"), inf, 0.0], [inf, -inf, inf]])
+    check_reduce("logsumexp", sp, 1)
+    check_reduce("logsumexp", sp, 0)
+    check_reduce("logsumexp", sp.repeat(1, 500), 1)          # across lanes and waves
