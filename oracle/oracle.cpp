@@ -71,8 +71,9 @@ enum {
 
 // op codes
 enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, ORC_GELU, ORC_LOG1P, ORC_EXPM1,
-       ORC_LOGSIGMOID };
-enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM, ORC_NE, ORC_LT, ORC_LE, ORC_GT, ORC_GE };
+       ORC_LOGSIGMOID, ORC_LOGICAL_NOT };
+enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM, ORC_NE, ORC_LT, ORC_LE, ORC_GT, ORC_GE,
+       ORC_LOGICAL_AND, ORC_LOGICAL_OR, ORC_LOGICAL_XOR, ORC_POW };
 enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
        ORC_LOGSUMEXP };
 
@@ -264,6 +265,25 @@ inline void store_flt(const orc_tensor* t, int64_t off, double v) {
   }
 }
 
+// `out=` casting.  An operator's result is formed in its result dtype `rd` and then converted to the dtype of
+// the tensor it is written to; the conversion must not lose the value's kind: a floating result cannot go to an
+// integer or bool tensor, an integer result cannot go to a bool tensor, everything else is allowed.
+inline bool can_cast(int from, int to) {
+  if (is_float(from) && !is_float(to)) return false;
+  if (from != ORC_BOOL && to == ORC_BOOL) return false;
+  return true;
+}
+// floating result: round to rd (once, from binary64), then to out's dtype (exact when out is wider)
+inline void put_flt(const orc_tensor* out, int64_t off, int rd, double v) {
+  store_flt(out, off, out->dtype == rd ? v : (double)round_to_float_dtype(v, rd));
+}
+// integer / bool result: wrap to rd, then convert; an integer goes to a floating dtype through binary32
+inline void put_int(const orc_tensor* out, int64_t off, int rd, int64_t v) {
+  int64_t w = rd == ORC_BOOL ? (int64_t)(v != 0) : rd == ORC_I32 ? (int64_t)(int32_t)(uint32_t)(uint64_t)v : v;
+  if (is_float(out->dtype)) store_flt(out, off, (double)(float)w);
+  else store_int(out, off, w);
+}
+
 // ---------------------------------------------------------------------------
 // shapes
 // ---------------------------------------------------------------------------
@@ -330,6 +350,22 @@ bool same_shape(const orc_tensor* t, int nd, const int64_t* sizes) {
   return true;
 }
 
+// integer power with wrapping multiplication: the product of e copies of b, written as the plain loop for small
+// e and by squaring for large e (the two agree modulo 2^64); negative e is the truncated reciprocal
+int64_t int_pow(int64_t b, int64_t e) {
+  if (e < 0) {
+    if (b == 1) return 1;
+    if (b == -1) return (e % 2 != 0) ? -1 : 1;
+    return 0;
+  }
+  uint64_t r = 1, m = (uint64_t)b;
+  for (uint64_t k = (uint64_t)e; k; k >>= 1) {
+    if (k & 1) r *= m;
+    m *= m;
+  }
+  return (int64_t)r;
+}
+
 const double kNaN = std::numeric_limits<double>::quiet_NaN();
 const double kInf = std::numeric_limits<double>::infinity();
 
@@ -352,6 +388,8 @@ int orc_unary_result_dtype(int op, int in_dtype) {
       return is_float(in_dtype) ? in_dtype : ORC_F32;   // integral input computes in fp32
     case ORC_GELU: case ORC_LOGSIGMOID:
       return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_LOGICAL_NOT:
+      return ORC_BOOL;
   }
   return ORC_ERR_DTYPE;
 }
@@ -365,9 +403,10 @@ int orc_infer_binary(int op, const orc_tensor* a, const orc_tensor* b, int32_t* 
   const orc_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
-  if (op < ORC_ADD || op > ORC_GE) return ORC_ERR_DTYPE;
+  if (op < ORC_ADD || op > ORC_POW) return ORC_ERR_DTYPE;
   if (op == ORC_DIV && !is_float(common)) res = ORC_F32;   // true division
-  if (op == ORC_EQ || op >= ORC_NE) res = ORC_BOOL;        // the comparison family
+  if (op == ORC_EQ || (op >= ORC_NE && op <= ORC_LOGICAL_XOR)) res = ORC_BOOL;   // comparison and logical families
+  if (op == ORC_POW && common == ORC_BOOL) return ORC_ERR_DTYPE;                 // no bool power
   if (op == ORC_SUB && (a->dtype == ORC_BOOL || b->dtype == ORC_BOOL)) return ORC_ERR_DTYPE;   // no bool subtraction
   int nd;
   int64_t s[ORC_MAX_DIMS];
@@ -388,7 +427,9 @@ int orc_where_result_dtype(const orc_tensor* x, const orc_tensor* y) {
 // ===========================================================================
 // Elementwise: unary
 // ===========================================================================
-// out[i] = f(a[i]).  `out` must have a's shape and the inferred dtype.
+// out[i] = f(a[i]).  `out` must have a's shape; its dtype is the inferred one or any dtype that one can be cast to
+// (see can_cast): the result is rounded to the inferred dtype first, then converted.
+//   logical_not   : x == 0 for any dtype, bool result.
 //   neg, abs      : exact; integers wrap (abs(INT_MIN) == INT_MIN); floats
 //                   flip / clear the sign bit (NaN and zeros included).
 //   exp log sqrt sigmoid tanh : binary64 evaluation of the input converted to
@@ -402,7 +443,7 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
   if ((rc = check_tensor(out)) || (rc = check_tensor(a))) return rc;
   int rd = orc_unary_result_dtype(op, a->dtype);
   if (rd < 0) return rd;
-  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  if (!can_cast(rd, out->dtype)) return ORC_ERR_DTYPE;
   if (!same_shape(out, a->ndim, a->sizes)) return ORC_ERR_SHAPE;
   const int64_t n = numel(out);
   const int nd = a->ndim;
@@ -411,6 +452,11 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
     int64_t idx[ORC_MAX_DIMS];
     unravel(lin, nd, out->sizes, idx);
     int64_t oo = offset_of(out, idx), ao = offset_of(a, idx);
+    if (op == ORC_LOGICAL_NOT) {                      // x == 0 (a NaN is not zero)
+      bool zero = is_float(a->dtype) ? load_flt(a, ao) == 0.0 : load_int(a, ao) == 0;
+      put_int(out, oo, ORC_BOOL, zero);
+      continue;
+    }
     if (op == ORC_NEG || op == ORC_ABS) {
       if (is_float(rd)) {
         // sign-bit operations on the stored encoding: exact for every input
@@ -419,13 +465,19 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
         std::memcpy(&bits, cptr(a, ao), es);
         uint32_t sb = 1u << (8 * es - 1);
         bits = (op == ORC_NEG) ? (bits ^ sb) : (bits & ~sb);
-        std::memcpy(mptr(out, oo), &bits, es);
+        if (out->dtype == rd) {
+          std::memcpy(mptr(out, oo), &bits, es);
+        } else {                                      // out= casting: the value, converted
+          double v = rd == ORC_F16 ? f16_to_double((uint16_t)bits) : rd == ORC_BF16 ? bf16_to_double((uint16_t)bits) : 0.0;
+          if (rd == ORC_F32) { float f; std::memcpy(&f, &bits, 4); v = (double)f; }
+          store_flt(out, oo, v);
+        }
       } else {
         int64_t v = load_int(a, ao);
         uint64_t u = (uint64_t)v;
         if (op == ORC_NEG) u = 0 - u;
         else if (v < 0) u = 0 - u;
-        store_int(out, oo, (int64_t)u);               // store wraps to the dtype
+        put_int(out, oo, rd, (int64_t)u);             // wraps to the result dtype
       }
       continue;
     }
@@ -443,7 +495,7 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
       // log(1 / (1 + exp(-x))) written so that neither tail overflows or cancels: min(x, 0) - log1p(exp(-|x|))
       case ORC_LOGSIGMOID: y = (x < 0.0 ? x : 0.0) - std::log1p(std::exp(-std::fabs(x))); break;
     }
-    store_flt(out, oo, y);
+    put_flt(out, oo, rd, y);
   }
   return ORC_OK;
 }
@@ -468,6 +520,17 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
 //             ties); bool AND.
 //   ne lt le gt ge : IEEE comparisons in the common dtype, bool result (every
 //             ordered comparison with a NaN is false, ne is true).
+//   logical_and / or / xor : (a != 0) op (b != 0) in the common dtype, bool
+//             result; a NaN counts as non-zero.
+//   pow     : a to the power b.  Floating common dtype: the binary64 power of
+//             the converted operands (C Annex F special values: anything^0 = 1,
+//             1^anything = 1, negative base with a non-integer exponent = NaN,
+//             ...), one rounding.  Integer common dtype: wrapping product of b
+//             copies of a; for b < 0 the truncated reciprocal: 1 for a == 1,
+//             +-1 for a == -1 by b's parity, 0 otherwise (0^negative included).
+//             Two bool operands are a dtype error.
+// `out` may have any dtype the result dtype can be cast to (can_cast): the
+// value is formed in the result dtype, then converted.
 int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_tensor* b, double alpha_f,
                int64_t alpha_i, int alpha_is_int) {
   int rc;
@@ -475,7 +538,7 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
   int32_t rd, nd;
   int64_t sizes[ORC_MAX_DIMS];
   if ((rc = orc_infer_binary(op, a, b, &rd, &nd, sizes))) return rc;
-  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  if (!can_cast(rd, out->dtype)) return ORC_ERR_DTYPE;
   if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
   const orc_tensor* ops[2] = {a, b};
   int cd = result_type(ops, 2);                       // dtype the op is applied in
@@ -496,68 +559,79 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
       switch (op) {
         case ORC_ADD: {
           float r = alpha_one ? (x.f + y.f) : std::fmaf(alpha32, y.f, x.f);
-          store_flt(out, oo, (double)r);
+          put_flt(out, oo, rd, (double)r);
           break;
         }
         case ORC_MUL: {
           float r = x.f * y.f;
-          store_flt(out, oo, (double)r);
+          put_flt(out, oo, rd, (double)r);
           break;
         }
         case ORC_DIV:
-          store_flt(out, oo, (double)x.f / (double)y.f);
+          put_flt(out, oo, rd, (double)x.f / (double)y.f);
           break;
         case ORC_MAXIMUM: {
           float r = (std::isnan(x.f) || std::isnan(y.f)) ? std::numeric_limits<float>::quiet_NaN()
                                                          : (y.f > x.f ? y.f : x.f);
-          store_flt(out, oo, (double)r);
+          put_flt(out, oo, rd, (double)r);
           break;
         }
-        case ORC_EQ: store_int(out, oo, x.f == y.f); break;
+        case ORC_EQ: put_int(out, oo, rd, x.f == y.f); break;
         case ORC_SUB: {                               // a - alpha*b: one IEEE subtraction, or one fma(-alpha, b, a)
           float r = alpha_one ? (x.f - y.f) : std::fmaf(-alpha32, y.f, x.f);
-          store_flt(out, oo, (double)r);
+          put_flt(out, oo, rd, (double)r);
           break;
         }
         case ORC_MINIMUM: {
           float r = (std::isnan(x.f) || std::isnan(y.f)) ? std::numeric_limits<float>::quiet_NaN()
                                                          : (y.f < x.f ? y.f : x.f);
-          store_flt(out, oo, (double)r);
+          put_flt(out, oo, rd, (double)r);
           break;
         }
-        case ORC_NE: store_int(out, oo, x.f != y.f); break;    // IEEE: every ordered comparison with NaN is false,
-        case ORC_LT: store_int(out, oo, x.f < y.f); break;     // != is true
-        case ORC_LE: store_int(out, oo, x.f <= y.f); break;
-        case ORC_GT: store_int(out, oo, x.f > y.f); break;
-        case ORC_GE: store_int(out, oo, x.f >= y.f); break;
+        case ORC_NE: put_int(out, oo, rd, x.f != y.f); break;    // IEEE: every ordered comparison with NaN is false,
+        case ORC_LT: put_int(out, oo, rd, x.f < y.f); break;     // != is true
+        case ORC_LE: put_int(out, oo, rd, x.f <= y.f); break;
+        case ORC_GT: put_int(out, oo, rd, x.f > y.f); break;
+        case ORC_GE: put_int(out, oo, rd, x.f >= y.f); break;
+        case ORC_LOGICAL_AND: put_int(out, oo, rd, (x.f != 0.0f) && (y.f != 0.0f)); break;   // a NaN is not zero
+        case ORC_LOGICAL_OR: put_int(out, oo, rd, (x.f != 0.0f) || (y.f != 0.0f)); break;
+        case ORC_LOGICAL_XOR: put_int(out, oo, rd, (x.f != 0.0f) != (y.f != 0.0f)); break;
+        case ORC_POW: put_flt(out, oo, rd, std::pow((double)x.f, (double)y.f)); break;       // C Annex F special cases
       }
     } else if (cd == ORC_BOOL) {
       switch (op) {
-        case ORC_ADD: store_int(out, oo, x.i | ((alpha_i != 0) & y.i)); break;
-        case ORC_MUL: store_int(out, oo, x.i & y.i); break;
-        case ORC_MAXIMUM: store_int(out, oo, x.i | y.i); break;
-        case ORC_EQ: store_int(out, oo, x.i == y.i); break;
-        case ORC_MINIMUM: store_int(out, oo, x.i & y.i); break;
-        case ORC_NE: store_int(out, oo, x.i != y.i); break;
-        case ORC_LT: store_int(out, oo, x.i < y.i); break;
-        case ORC_LE: store_int(out, oo, x.i <= y.i); break;
-        case ORC_GT: store_int(out, oo, x.i > y.i); break;
-        case ORC_GE: store_int(out, oo, x.i >= y.i); break;
+        case ORC_ADD: put_int(out, oo, rd, x.i | ((alpha_i != 0) & y.i)); break;
+        case ORC_MUL: put_int(out, oo, rd, x.i & y.i); break;
+        case ORC_MAXIMUM: put_int(out, oo, rd, x.i | y.i); break;
+        case ORC_EQ: put_int(out, oo, rd, x.i == y.i); break;
+        case ORC_MINIMUM: put_int(out, oo, rd, x.i & y.i); break;
+        case ORC_NE: put_int(out, oo, rd, x.i != y.i); break;
+        case ORC_LT: put_int(out, oo, rd, x.i < y.i); break;
+        case ORC_LE: put_int(out, oo, rd, x.i <= y.i); break;
+        case ORC_GT: put_int(out, oo, rd, x.i > y.i); break;
+        case ORC_GE: put_int(out, oo, rd, x.i >= y.i); break;
+        case ORC_LOGICAL_AND: put_int(out, oo, rd, x.i & y.i); break;
+        case ORC_LOGICAL_OR: put_int(out, oo, rd, x.i | y.i); break;
+        case ORC_LOGICAL_XOR: put_int(out, oo, rd, x.i ^ y.i); break;
       }
     } else {
       uint64_t ux = (uint64_t)x.i, uy = (uint64_t)y.i;
       switch (op) {
-        case ORC_ADD: store_int(out, oo, (int64_t)(ux + (uint64_t)alpha_i * uy)); break;
-        case ORC_MUL: store_int(out, oo, (int64_t)(ux * uy)); break;
-        case ORC_MAXIMUM: store_int(out, oo, y.i > x.i ? y.i : x.i); break;
-        case ORC_EQ: store_int(out, oo, x.i == y.i); break;
-        case ORC_SUB: store_int(out, oo, (int64_t)(ux - (uint64_t)alpha_i * uy)); break;
-        case ORC_MINIMUM: store_int(out, oo, y.i < x.i ? y.i : x.i); break;
-        case ORC_NE: store_int(out, oo, x.i != y.i); break;
-        case ORC_LT: store_int(out, oo, x.i < y.i); break;
-        case ORC_LE: store_int(out, oo, x.i <= y.i); break;
-        case ORC_GT: store_int(out, oo, x.i > y.i); break;
-        case ORC_GE: store_int(out, oo, x.i >= y.i); break;
+        case ORC_ADD: put_int(out, oo, rd, (int64_t)(ux + (uint64_t)alpha_i * uy)); break;
+        case ORC_MUL: put_int(out, oo, rd, (int64_t)(ux * uy)); break;
+        case ORC_MAXIMUM: put_int(out, oo, rd, y.i > x.i ? y.i : x.i); break;
+        case ORC_EQ: put_int(out, oo, rd, x.i == y.i); break;
+        case ORC_SUB: put_int(out, oo, rd, (int64_t)(ux - (uint64_t)alpha_i * uy)); break;
+        case ORC_MINIMUM: put_int(out, oo, rd, y.i < x.i ? y.i : x.i); break;
+        case ORC_NE: put_int(out, oo, rd, x.i != y.i); break;
+        case ORC_LT: put_int(out, oo, rd, x.i < y.i); break;
+        case ORC_LE: put_int(out, oo, rd, x.i <= y.i); break;
+        case ORC_GT: put_int(out, oo, rd, x.i > y.i); break;
+        case ORC_GE: put_int(out, oo, rd, x.i >= y.i); break;
+        case ORC_LOGICAL_AND: put_int(out, oo, rd, (x.i != 0) && (y.i != 0)); break;
+        case ORC_LOGICAL_OR: put_int(out, oo, rd, (x.i != 0) || (y.i != 0)); break;
+        case ORC_LOGICAL_XOR: put_int(out, oo, rd, (x.i != 0) != (y.i != 0)); break;
+        case ORC_POW: put_int(out, oo, rd, int_pow(x.i, y.i)); break;
       }
     }
   }
@@ -632,6 +706,60 @@ int orc_masked_fill(const orc_tensor* out, const orc_tensor* self, const orc_ten
     bool m = load_int(mask, bcast_offset(mask, nd, idx)) != 0;
     if (m) std::memcpy(mptr(out, oo), fill, esize(dt));
     else std::memcpy(mptr(out, oo), cptr(self, bcast_offset(self, nd, idx)), esize(dt));
+  }
+  return ORC_OK;
+}
+
+// clamp(x, lo, hi) with scalar bounds, either of which may be absent (not both): min(max(x, lo), hi), so a lower
+// bound above the upper bound gives the upper bound everywhere.  Result dtype: x's, except that an integer x with
+// a floating bound gives fp32; bool x is a dtype error.  x and the bounds are converted to the result dtype first
+// (an integer bound that does not fit an integer result dtype is a scalar error); a NaN in x stays, a NaN bound
+// makes every output NaN.
+int orc_clamp_result_dtype(int x_dtype, int has_lo, int lo_is_int, int has_hi, int hi_is_int) {
+  if (!valid_dtype(x_dtype) || x_dtype == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (!has_lo && !has_hi) return ORC_ERR_SCALAR;
+  if (is_float(x_dtype)) return x_dtype;
+  return ((has_lo && !lo_is_int) || (has_hi && !hi_is_int)) ? ORC_F32 : x_dtype;
+}
+int orc_clamp(const orc_tensor* out, const orc_tensor* x, int has_lo, double lo_f, int64_t lo_i, int lo_is_int,
+              int has_hi, double hi_f, int64_t hi_i, int hi_is_int) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  int rd = orc_clamp_result_dtype(x->dtype, has_lo, lo_is_int, has_hi, hi_is_int);
+  if (rd < 0) return rd;
+  if (!can_cast(rd, out->dtype)) return ORC_ERR_DTYPE;
+  if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  float lof = 0.0f, hif = 0.0f;
+  if (is_float(rd)) {
+    lof = round_to_float_dtype(lo_is_int ? (double)lo_i : lo_f, rd);
+    hif = round_to_float_dtype(hi_is_int ? (double)hi_i : hi_f, rd);
+  } else if (rd == ORC_I32) {
+    if ((has_lo && (lo_i < INT32_MIN || lo_i > INT32_MAX)) || (has_hi && (hi_i < INT32_MIN || hi_i > INT32_MAX)))
+      return ORC_ERR_SCALAR;
+  }
+  const bool nan_bound = is_float(rd) && ((has_lo && std::isnan(lof)) || (has_hi && std::isnan(hif)));
+  const int64_t n = numel(out);
+  const int nd = x->ndim;
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, out->sizes, idx);
+    int64_t oo = offset_of(out, idx);
+    Val v = load_as(x, offset_of(x, idx), rd);
+    if (is_float(rd)) {
+      float r = v.f;
+      if (nan_bound) r = std::numeric_limits<float>::quiet_NaN();
+      else if (!std::isnan(r)) {
+        if (has_lo && r < lof) r = lof;
+        if (has_hi && r > hif) r = hif;
+      }
+      put_flt(out, oo, rd, (double)r);
+    } else {
+      int64_t r = v.i;
+      if (has_lo && r < lo_i) r = lo_i;
+      if (has_hi && r > hi_i) r = hi_i;
+      put_int(out, oo, rd, r);
+    }
   }
   return ORC_OK;
 }

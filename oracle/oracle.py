@@ -18,9 +18,9 @@ DTYPE_CODE = {torch.bool: BOOL, torch.int32: I32, torch.int64: I64, torch.float1
 CODE_DTYPE = {v: k for k, v in DTYPE_CODE.items()}
 
 UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7, "log1p": 8, "expm1": 9,
-         "logsigmoid": 10}
+         "logsigmoid": 10, "logical_not": 11}
 BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimum": 6, "ne": 7, "lt": 8, "le": 9, "gt": 10,
-          "ge": 11}
+          "ge": 11, "logical_and": 12, "logical_or": 13, "logical_xor": 14, "pow": 15}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
           "all": 10, "logsumexp": 11}
 
@@ -56,6 +56,9 @@ def lib():
         _lib.orc_unary.argtypes = [ctypes.c_int, P, P]
         _lib.orc_binary.argtypes = [ctypes.c_int, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
         _lib.orc_where.argtypes = [P, P, P, P]
+        _lib.orc_clamp.argtypes = [P, P, ctypes.c_int, ctypes.c_double, ctypes.c_int64, ctypes.c_int,
+                                   ctypes.c_int, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
+        _lib.orc_clamp_result_dtype.argtypes = [ctypes.c_int] * 5
         _lib.orc_masked_fill.argtypes = [P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
         _lib.orc_reduce.argtypes = [ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int, ctypes.c_double]
         _lib.orc_softmax.argtypes = [P, P, ctypes.c_int64, ctypes.c_int]
@@ -134,19 +137,30 @@ def where_result_dtype(x, y):
 
 
 # --------------------------------------------------------------------------- elementwise
-def unary(op, a, out=None):
+def unary(op, a, out=None, out_dtype=None):
     if out is None:
-        out = torch.empty(a.shape, dtype=unary_result_dtype(op, a.dtype))
+        out = torch.empty(a.shape, dtype=out_dtype or unary_result_dtype(op, a.dtype))
     _check(lib().orc_unary(UNARY[op], desc(out), desc(a)))
     return out
 
 
-def binary(op, a, b, alpha=1, out=None):
+def binary(op, a, b, alpha=1, out=None, out_dtype=None):
     if out is None:
         dt, shape = infer_binary(op, a, b)
-        out = torch.empty(shape, dtype=dt)
+        out = torch.empty(shape, dtype=out_dtype or dt)
     af, ai, isint = _scalar(alpha)
     _check(lib().orc_binary(BINARY[op], desc(out), desc(a), desc(b), af, ai, isint))
+    return out
+
+
+def clamp(x, lo=None, hi=None, out=None, out_dtype=None):
+    lf, li, lint = _scalar(0 if lo is None else lo)
+    hf, hi_i, hint = _scalar(0 if hi is None else hi)
+    if out is None:
+        rc = lib().orc_clamp_result_dtype(DTYPE_CODE[x.dtype], lo is not None, lint, hi is not None, hint)
+        _check(min(rc, 0))
+        out = torch.empty(x.shape, dtype=out_dtype or CODE_DTYPE[rc])
+    _check(lib().orc_clamp(desc(out), desc(x), lo is not None, lf, li, lint, hi is not None, hf, hi_i, hint))
     return out
 
 
