@@ -100,6 +100,13 @@ def build_ops(torch, B):
     extra("expm1_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("expm1", of, xf))
     extra("logsigmoid_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("logsigmoid", of, xf))
     extra("logsigmoid_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("logsigmoid", ob, xb))
+    extra("pow_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("pow", of, xf, yf))
+    extra("clamp_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_clamp(of, xf, -0.5, 0.75))
+    extra("clamp_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_clamp(ob, xb, -0.5, 0.75))
+    extra("logical_and_f32", "f1", "ew_vec_kernel", n2 * 9, n2, lambda: B.tx_binary("logical_and", obool, xf, yf))
+    extra("logical_not_f32", "f1", "ew_vec_kernel", n2 * 5, n2, lambda: B.tx_unary("logical_not", obool, xf))
+    extra("add_bf16_out_f32_cast", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_add(of, xb, xb, 1))
+    extra("add_bf16_f32_in_place", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_add(ob, ob, xf, 1))
 
     # ---- workload 3: reductions over x[64,4096,1024]
     R = (64, 4096, 1024)

@@ -26,11 +26,17 @@
  *     tx_last_error() holds a thread-local detail string.
  *   - numel(out) == 0 returns TX_OK without launching.
  *   - `out` must have exactly the inferred shape.  Its dtype must be the
- *     inferred result dtype, except where a function says a wider float is
- *     accepted.  `out` may have any non-overlapping strides.  It may alias an
- *     input exactly (same pointer, sizes and strides: in-place); any other
- *     overlap between `out` and an input, and any self-overlap inside `out`,
- *     is TX_ERR_OVERLAP.
+ *     inferred result dtype, except where a function says otherwise: tx_unary,
+ *     tx_add / tx_sub / tx_binary and tx_clamp accept any out dtype the result
+ *     dtype can be cast to (ATen's `out=` rule: no floating result into an
+ *     integer or bool tensor, no integer result into a bool tensor); the
+ *     result is formed and rounded in the result dtype first, then converted
+ *     (integers narrow by wrapping and reach a half dtype through fp32).
+ *     `out` may have any non-overlapping strides.  It may alias an input
+ *     exactly (same pointer, sizes and strides).  Together these give the
+ *     in-place variants: a.add_(b) is tx_add(out = a, a, b), legal whenever
+ *     the promoted dtype can be cast to a's.  Any other overlap between `out`
+ *     and an input, and any self-overlap inside `out`, is TX_ERR_OVERLAP.
  *   - Type promotion (binary ops, where): categories bool < integer <
  *     floating.  Operands with ndim >= 1 are promoted among themselves and
  *     0-dim operands among themselves (wider wins inside a category, fp16
@@ -81,8 +87,10 @@ enum {
 };
 
 /* operator codes */
-enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF, TX_LOG1P, TX_EXPM1, TX_LOGSIGMOID };
-enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE };
+enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF, TX_LOG1P, TX_EXPM1, TX_LOGSIGMOID,
+       TX_LOGICAL_NOT };
+enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE,
+       TX_LOGICAL_AND, TX_LOGICAL_OR, TX_LOGICAL_XOR, TX_POW };
 enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARGMIN, TX_STD, TX_ANY, TX_ALL,
        TX_LOGSUMEXP };
 
@@ -99,7 +107,8 @@ enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARG
  *              results are within 2 ulp of the correctly rounded value.
  *   GELU_ERF : x * Phi(x); float dtypes only.
  *   LOGSIGMOID : log(1 / (1 + exp(-x))) (Appendix D's worked example), float
- *              dtypes only, evaluated as min(x, 0) - log1p(exp(-|x|)). */
+ *              dtypes only, evaluated as min(x, 0) - log1p(exp(-|x|)).
+ *   LOGICAL_NOT : x == 0 for any dtype (a NaN is not zero), bool result. */
 tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream);
 
 /* out = a + alpha * b with broadcasting and type promotion.  alpha is given
@@ -117,13 +126,31 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
                  int alpha_is_int, void* stream);
 
 /* out = a (op) b with broadcasting and type promotion, op in MUL DIV MAXIMUM
- * MINIMUM EQ NE LT LE GT GE (TX_ADD and TX_SUB are accepted too, with alpha = 1).
+ * MINIMUM EQ NE LT LE GT GE LOGICAL_AND LOGICAL_OR LOGICAL_XOR POW (TX_ADD and
+ * TX_SUB are accepted too, with alpha = 1).
  *   MUL: bool AND, integers wrap.  DIV: true division, bool / integer pairs are
  *   computed and returned in fp32.  MAXIMUM / MINIMUM: NaN if either operand is
  *   NaN; on ties the first operand; bool OR / AND.
  *   EQ NE LT LE GT GE: compare in the common dtype, result dtype bool (IEEE:
- *   every ordered comparison with a NaN is false, NE is true). */
+ *   every ordered comparison with a NaN is false, NE is true).
+ *   LOGICAL_AND / OR / XOR: (a != 0) op (b != 0) in the common dtype, result
+ *   dtype bool; a NaN counts as non-zero.
+ *   POW: a to the power b.  Floating common dtype: IEEE pow with the C Annex F
+ *   special values (x^0 = 1 and 1^y = 1 even for NaN, negative base with a
+ *   non-integer exponent = NaN), fp32 results within 2 ulp.  Integer common
+ *   dtype: wrapping product; a negative exponent gives the truncated
+ *   reciprocal (1 for base 1, +-1 for base -1 by parity, else 0).  Two bool
+ *   operands are TX_ERR_DTYPE. */
 tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream);
+
+/* out = min(max(x, lo), hi) with scalar bounds; has_lo / has_hi say which are
+ * present (neither: TX_ERR_SCALAR), each given both ways like alpha.  Result
+ * dtype: x's, except integer x with a floating bound gives fp32; bool x is
+ * TX_ERR_DTYPE.  x and the bounds are converted to the result dtype first (an
+ * integer bound outside an int32 result's range is TX_ERR_SCALAR).  lo > hi
+ * gives hi everywhere; a NaN in x stays; a NaN bound makes every output NaN. */
+tx_status tx_clamp(const tx_tensor* out, const tx_tensor* x, int has_lo, double lo_f, int64_t lo_i, int lo_is_int,
+                   int has_hi, double hi_f, int64_t hi_i, int hi_is_int, void* stream);
 
 /* out = cond ? x : y.  cond must be bool; result dtype = promotion of x and y;
  * the three operands broadcast together.  With no conversion the selected
@@ -220,13 +247,15 @@ size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const 
 
 /* ------------------------------------------------------------------ host-only helpers */
 
-/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_EQ). */
+/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_POW). */
 tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_t* dtype, int32_t* ndim,
                           int64_t* sizes);
 /* Result dtype of where(cond, x, y). */
 tx_status tx_infer_where(const tx_tensor* x, const tx_tensor* y, int32_t* dtype);
 /* Result dtype of a unary op for an input dtype (negative = error). */
 int32_t tx_infer_unary_dtype(int op, int32_t in_dtype);
+/* Result dtype of tx_clamp (a TX_* dtype code >= 0) or a negative tx_status. */
+int32_t tx_infer_clamp_dtype(int32_t x_dtype, int has_lo, int lo_is_int, int has_hi, int hi_is_int);
 /* Result dtype and shape of a reduction. */
 tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim, int32_t* dtype,
                           int32_t* ndim, int64_t* sizes);

@@ -18,9 +18,9 @@ DTYPE_CODE = {torch.bool: BOOL, torch.int32: I32, torch.int64: I64, torch.float1
 CODE_DTYPE = {v: k for k, v in DTYPE_CODE.items()}
 
 UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7, "log1p": 8, "expm1": 9,
-         "logsigmoid": 10}
+         "logsigmoid": 10, "logical_not": 11}
 BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimum": 6, "ne": 7, "lt": 8, "le": 9, "gt": 10,
-          "ge": 11}
+          "ge": 11, "logical_and": 12, "logical_or": 13, "logical_xor": 14, "pow": 15}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
           "all": 10, "logsumexp": 11}
 
@@ -29,7 +29,7 @@ STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", 
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so")
 
-EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
+EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
            "tx_softmax", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
@@ -68,6 +68,9 @@ def lib():
         "tx_add": ([P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_sub": ([P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_binary": ([ctypes.c_int, P, P, P, V], ctypes.c_int32),
+        "tx_clamp": ([P, P, ctypes.c_int, ctypes.c_double, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                      ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
+        "tx_infer_clamp_dtype": ([ctypes.c_int32] + [ctypes.c_int] * 4, ctypes.c_int32),
         "tx_where": ([P, P, P, P, V], ctypes.c_int32),
         "tx_masked_fill": ([P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_reduce": ([ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int, ctypes.c_double, V, ctypes.c_size_t, V],
@@ -162,6 +165,20 @@ def tx_sub(out, a, b, alpha=1, stream=None):
 
 def tx_binary(op, out, a, b, stream=None):
     _check(lib().tx_binary(BINARY[op], desc(out), desc(a), desc(b), _stream(stream)))
+
+
+def tx_clamp(out, x, lo=None, hi=None, stream=None):
+    lf, li, lint = _scalar(0 if lo is None else lo)
+    hf, hi_i, hint = _scalar(0 if hi is None else hi)
+    _check(lib().tx_clamp(desc(out), desc(x), lo is not None, lf, li, lint, hi is not None, hf, hi_i, hint,
+                          _stream(stream)))
+
+
+def tx_infer_clamp_dtype(dtype, lo=None, hi=None):
+    rc = lib().tx_infer_clamp_dtype(DTYPE_CODE[dtype], lo is not None, _scalar(0 if lo is None else lo)[2],
+                                    hi is not None, _scalar(0 if hi is None else hi)[2])
+    _check(rc)
+    return CODE_DTYPE[rc]
 
 
 def tx_where(out, cond, x, y, stream=None):

@@ -27,6 +27,11 @@ inline bool dtype_valid(int dt) { return dt >= TX_BOOL && dt <= TX_F32; }
 inline int dtype_category(int dt) { return dt == TX_BOOL ? 0 : (dt <= TX_I64 ? 1 : 2); }
 inline bool dtype_is_float(int dt) { return dt >= TX_F16; }
 inline bool dtype_is_half(int dt) { return dt == TX_F16 || dt == TX_BF16; }
+// may a result of dtype `from` be written to a tensor of dtype `to`: not a floating value into an integer or
+// bool tensor, not an integer into a bool tensor
+inline bool can_cast(int from, int to) {
+  return !(dtype_is_float(from) && !dtype_is_float(to)) && !(from != TX_BOOL && to == TX_BOOL);
+}
 const char* dtype_name(int dt);
 
 // ---------------------------------------------------------------------------

@@ -185,6 +185,8 @@ int32_t tx_infer_unary_dtype(int op, int32_t in) {
     case TX_GELU_ERF: case TX_LOGSIGMOID:
       if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "gelu / logsigmoid take floating dtypes only");
       return in;
+    case TX_LOGICAL_NOT:
+      return TX_BOOL;
   }
   return fail(TX_ERR_DTYPE, "unknown unary op %d", op);
 }
@@ -195,12 +197,13 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (a->ndim < 0 || a->ndim > TX_MAX_DIMS || b->ndim < 0 || b->ndim > TX_MAX_DIMS)
     return fail(TX_ERR_NDIM, "infer_binary: bad ndim");
   if (!dtype_valid(a->dtype) || !dtype_valid(b->dtype)) return fail(TX_ERR_DTYPE, "infer_binary: bad dtype code");
-  if (op < TX_ADD || op > TX_GE) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
+  if (op < TX_ADD || op > TX_POW) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
   const tx_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
   if (op == TX_DIV && !dtype_is_float(common)) res = TX_F32;
-  if (op == TX_EQ || op >= TX_NE) res = TX_BOOL;
+  if (op == TX_EQ || (op >= TX_NE && op <= TX_LOGICAL_XOR)) res = TX_BOOL;
+  if (op == TX_POW && common == TX_BOOL) return fail(TX_ERR_DTYPE, "pow does not take two bool operands");
   if (op == TX_SUB && (a->dtype == TX_BOOL || b->dtype == TX_BOOL))
     return fail(TX_ERR_DTYPE, "sub does not take bool operands");
   int nd;
@@ -211,6 +214,14 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (ndim) *ndim = nd;
   if (sizes) std::copy(s, s + nd, sizes);
   return TX_OK;
+}
+
+int32_t tx_infer_clamp_dtype(int32_t x_dtype, int has_lo, int lo_is_int, int has_hi, int hi_is_int) {
+  if (!dtype_valid(x_dtype)) return fail(TX_ERR_DTYPE, "clamp: dtype code %d", x_dtype);
+  if (x_dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "clamp does not take bool");
+  if (!has_lo && !has_hi) return fail(TX_ERR_SCALAR, "clamp needs at least one bound");
+  if (dtype_is_float(x_dtype)) return x_dtype;
+  return ((has_lo && !lo_is_int) || (has_hi && !hi_is_int)) ? TX_F32 : x_dtype;
 }
 
 tx_status tx_infer_where(const tx_tensor* x, const tx_tensor* y, int32_t* dtype) {

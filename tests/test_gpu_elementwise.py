@@ -20,9 +20,11 @@ pytestmark = pytest.mark.gpu
 
 F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
 ALL = [F32, BF16, F16, I32, I64, BOOL]
-UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu", "log1p", "expm1", "logsigmoid"]
-BINARY = ["add", "mul", "div", "maximum", "eq", "sub", "minimum", "ne", "lt", "le", "gt", "ge"]
-COMPARE = ("eq", "ne", "lt", "le", "gt", "ge")
+UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu", "log1p", "expm1", "logsigmoid", "logical_not"]
+BINARY = ["add", "mul", "div", "maximum", "eq", "sub", "minimum", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or",
+          "logical_xor", "pow"]
+COMPARE = ("eq", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or", "logical_xor")
+CAST_OK = lambda src, dst: not (src.is_floating_point and not dst.is_floating_point) and not (src != BOOL and dst == BOOL)
 MIXED = [(I32, I64), (I64, F32), (BF16, F32), (F16, BF16), (BOOL, I32), (I64, F16)]
 
 
@@ -49,7 +51,7 @@ def check_unary(op, a_cpu, layout="contig", path=None, what=""):
         B.tx_force_path(None)
     sync()
     what = "%s %s %s %s %s [%s]" % (op, a_cpu.dtype, tuple(a_cpu.shape), what, layout, used)
-    if op in ("neg", "abs"):
+    if op in ("neg", "abs", "logical_not"):
         assert_exact_fp(out, want, what)
     elif want.dtype == F32:
         assert_ulp(out, want, 2, what)
@@ -90,7 +92,7 @@ def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what="")
     what = "%s %s,%s %s %s %s [%s]" % (op, a_cpu.dtype, b_cpu.dtype, tuple(want.shape), what, layout, used)
     if op in COMPARE:
         assert_exact(out, want, what)
-    elif op == "div":
+    elif op in ("div", "pow") and want.dtype.is_floating_point:
         if want.dtype == F32:
             assert_ulp(out, want, 2, what)
         else:
@@ -385,3 +387,156 @@ def test_where_and_masked_fill_full_size():
     c = I.booleans(FULL, 0.5, seed=173)
     check_where(c, I.typed(FULL, F32, seed=174, specials=0.01), I.typed(FULL, F32, seed=175, specials=0.01), "full")
     check_masked_fill(I.typed(FULL, F32, seed=176), I.bernoulli_mask(FULL, 0.3, seed=4), -1.0, "full")
+
+
+# --------------------------------------------------------------------------- pow, clamp, out= casting, in-place variants
+def test_pow_special_values_and_integer_rules():
+    nan, inf = float("nan"), float("inf")
+    base = [nan, 1.0, -1.0, 0.0, -0.0, -0.0, -2.0, -2.0, 0.5, 2.0, inf, -inf, -inf, 2.0, 10.0, 10.0, 2.0, 3.0]
+    expo = [0.0, nan, inf, -1.0, -3.0, 2.0, 3.0, 0.5, inf, -inf, -1.0, 3.0, -3.0, 10.0, 38.0, 39.0, -140.0, 0.5]
+    check_binary("pow", torch.tensor(base, dtype=F32), torch.tensor(expo, dtype=F32), what="special values")
+    check_binary("pow", torch.tensor(base, dtype=BF16), torch.tensor(expo, dtype=BF16), what="special values")
+    b = torch.tensor([1, -1, -1, 2, 0, -5, 3, -3, 7, 2], dtype=I64)
+    e = torch.tensor([-7, -3, -4, -1, -2, -1, 41, 41, 0, 63], dtype=I64)
+    check_binary("pow", b, e, what="integer rules")
+    check_binary("pow", b.to(I32), e.to(I32), what="integer rules")
+    check_binary("pow", torch.tensor([True, False]), torch.tensor([True, True]))      # refused: two bools
+
+
+@pytest.mark.parametrize("dt", [F32, BF16, I32])
+def test_pow_full_size(dt):
+    if dt == I32:
+        a = torch.randint(-9, 10, FULL, generator=torch.Generator().manual_seed(1), dtype=I32)
+        b = torch.randint(-2, 12, FULL, generator=torch.Generator().manual_seed(2), dtype=I32)
+    else:
+        a = I.typed(FULL, dt, seed=4, specials=0.01).abs_() + 0.05
+        b = I.typed(FULL, dt, seed=5, specials=0.01) * 3
+    assert check_binary("pow", a, b) == "vec"
+
+
+def check_clamp(x_cpu, lo, hi, layout="contig", out_dtype=None, what=""):
+    try:
+        want = O.clamp(x_cpu, lo, hi, out_dtype=out_dtype)
+    except O.OracleError as err:
+        with pytest.raises(B.TxError) as e:
+            B.tx_clamp(torch.empty(x_cpu.shape, dtype=out_dtype or x_cpu.dtype, device="cuda"), to_device_view(x_cpu), lo, hi)
+        assert e.value.kind.lower() == err.kind, (x_cpu.dtype, lo, hi, e.value.kind, err.kind)
+        return "refused"
+    x = to_device_view(x_cpu)
+    out = empty_like_layout(x, want.dtype, layout=layout)
+    B.tx_clamp(out, x, lo, hi)
+    used = B.tx_last_path()
+    sync()
+    assert_exact_fp(out, want, "clamp %s %s lo=%r hi=%r %s -> %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), lo, hi, what,
+                                                                       want.dtype, used))
+    return used
+
+
+def test_clamp_sweep():
+    bounds = [(-0.5, 0.75), (None, 0.1), (0.1, None), (1.0, -1.0), (-1, 2), (float("nan"), 1.0), (None, None)]
+    for dt, kind, (lo, hi) in itertools.product([F32, BF16, F16, I32, I64, BOOL], I.VIEW_KINDS, bounds):
+        x = I.make_view((7, 13, 5), dt, kind, seed=170, specials=0.01)
+        check_clamp(x, lo, hi, layout="like_input", what=kind)
+    for dt in (F32, I64):
+        check_clamp(I.typed((0,), dt, seed=1), -1, 1)
+        check_clamp(I.typed((), dt, seed=2), -1, 1)
+    check_clamp(I.typed((50,), I32, seed=3), 2 ** 31, None)          # bound outside int32: refused
+    check_clamp(I.typed((50,), I64, seed=3), -2 ** 40, 2 ** 41)
+    for src, dst in itertools.product([F32, BF16, I32, I64], ALL):
+        check_clamp(I.typed((33, 9), src, seed=171, specials=0.01), -1, 1, out_dtype=dst, what="cast")
+    assert B.tx_infer_clamp_dtype(I32, 0.5, None) == F32 and B.tx_infer_clamp_dtype(I32, 1, 2) == I32
+
+
+@pytest.mark.parametrize("dt", [F32, BF16, I64])
+def test_clamp_full_size(dt):
+    x = I.typed(FULL, dt, seed=6, specials=0.01)
+    assert check_clamp(x, -1 if dt == I64 else -0.5, 2 if dt == I64 else 0.75) == "vec"
+    if dt == F32:
+        assert check_clamp(I.make_view(FULL, dt, "transposed", seed=7), -0.5, None) in ("tile-vec", "tile")
+
+
+def check_cast(fn_oracle, fn_lib, want_dtype_class, what):
+    want = fn_oracle()
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    fn_lib(out)
+    sync()
+    if want_dtype_class == "exact":
+        assert_exact_fp(out, want, what)
+    else:
+        assert_rel(out, want, 1e-2 if want_dtype_class == "half" else 3e-7, scale=FLT_TINY, what=what,
+                   overflow_max=HALF_MAX.get(want.dtype))
+
+
+@pytest.mark.parametrize("op", ["add", "sub", "mul", "div", "maximum", "minimum", "lt", "logical_or", "pow"])
+def test_binary_out_casting(op):
+    pairs = [(F32, F32), (BF16, BF16), (F16, BF16), (I32, I32), (I32, I64), (I64, F32), (BOOL, BOOL), (BOOL, I32)]
+    for (da, db), dst, kind in itertools.product(pairs, ALL, ["contig", "transposed"]):
+        if op == "sub" and BOOL in (da, db) or op == "pow" and (da, db) == (BOOL, BOOL):
+            continue
+        a = I.make_view((9, 14, 5), da, kind, seed=180, specials=0.01)
+        b = I.make_view((9, 14, 5), db, "contig", seed=181, specials=0.01)
+        if op == "pow" and not (da.is_floating_point or db.is_floating_point):
+            b = b % 7
+        rd, _ = O.infer_binary(op, a, b)
+        da_, db_ = to_device_view(a), to_device_view(b)
+        call = (lambda o: B.tx_add(o, da_, db_)) if op == "add" else (lambda o: B.tx_sub(o, da_, db_)) if op == "sub" \
+            else (lambda o: B.tx_binary(op, o, da_, db_))
+        if not CAST_OK(rd, dst):
+            with pytest.raises(B.TxError) as e:
+                call(torch.empty(a.shape, dtype=dst, device="cuda"))
+            assert e.value.kind == "DTYPE"
+            with pytest.raises(O.OracleError):
+                O.binary(op, a, b, out_dtype=dst)
+            continue
+        cls = "exact" if op not in ("div", "pow") or not rd.is_floating_point else "half" if rd != F32 or dst != F32 else "f32"
+        check_cast(lambda: O.binary(op, a, b, out_dtype=dst), call, cls, "%s %s,%s -> %s %s" % (op, da, db, dst, kind))
+
+
+def test_unary_out_casting():
+    for op, src, dst in itertools.product(UNARY, ALL, ALL):
+        a = I.typed((40, 11), src, seed=182, specials=0.01)
+        da_ = to_device_view(a)
+        try:
+            rd = O.unary_result_dtype(op, src)
+        except O.OracleError:
+            continue
+        if not CAST_OK(rd, dst):
+            with pytest.raises(B.TxError) as e:
+                B.tx_unary(op, torch.empty(a.shape, dtype=dst, device="cuda"), da_)
+            assert e.value.kind == "DTYPE"
+            continue
+        cls = "exact" if op in ("neg", "abs", "logical_not") else "half" if (rd != F32 or dst != F32) else "f32"
+        check_cast(lambda: O.unary(op, a, out_dtype=dst), lambda o: B.tx_unary(op, o, da_), cls,
+                   "%s %s -> %s" % (op, src, dst))
+
+
+def test_in_place_variants_with_promotion():
+    # a.add_(b): the promoted result goes back into a when it can be cast to a's dtype
+    for da, db in [(BF16, F32), (F16, BF16), (F32, I64), (I64, I32), (I32, I64), (F32, BOOL), (I32, BOOL)]:
+        a, b = I.typed((300, 41), da, seed=183, specials=0.01), I.typed((300, 41), db, seed=184, specials=0.01)
+        for op in ("add", "mul", "maximum"):
+            dev = a.cuda()
+            (B.tx_add(dev, dev, b.cuda()) if op == "add" else B.tx_binary(op, dev, dev, b.cuda()))
+            sync()
+            assert_exact_fp(dev, O.binary(op, a, b, out_dtype=da), "in-place %s %s,%s" % (op, da, db))
+    for da, db in [(I32, F32), (BOOL, I32), (I64, BF16)]:          # promoted dtype cannot be cast back: refused
+        dev = I.typed((8,), da, seed=1).cuda()
+        with pytest.raises(B.TxError) as e:
+            B.tx_add(dev, dev, I.typed((8,), db, seed=2).cuda())
+        assert e.value.kind == "DTYPE"
+    x = I.typed((1000,), BF16, seed=185)
+    dev = x.cuda()
+    B.tx_unary("exp", dev, dev)
+    B.tx_clamp(dev, dev, 0.5, 2.0)
+    sync()
+    assert_rel(dev, O.clamp(O.unary("exp", x), 0.5, 2.0), 1e-2, scale=FLT_TINY, what="in-place exp, clamp")
+
+
+def test_binary_out_casting_full_size():
+    a, b = I.typed(FULL, BF16, seed=8, specials=0.01), I.typed(FULL, BF16, seed=9, specials=0.01)
+    da_, db_ = a.cuda(), b.cuda()
+    out = torch.empty(FULL, dtype=F32, device="cuda")
+    B.tx_add(out, da_, db_)
+    assert B.tx_last_path() == "vec"
+    sync()
+    assert_exact_fp(out, O.binary("add", a, b, out_dtype=F32), "bf16 + bf16 -> f32 out")
