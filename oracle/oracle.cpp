@@ -1053,6 +1053,113 @@ int orc_softmax(const orc_tensor* out, const orc_tensor* x, int64_t dim, int is_
 }
 
 // ===========================================================================
+// layer_norm over the last k dims (the listing of Appendix B.3 is the paper's kernel for this operator)
+// ===========================================================================
+// The last `norm_ndim` dims of x form one row of M elements; for every row
+//   mean = sum x / M,  var = sum (x - mean)^2 / M  (biased),
+//   y = (x - mean) / sqrt(var + eps) * weight + bias,
+// weight and bias optional (null), each with exactly the shape of the normalised dims, floating dtype.  binary64
+// throughout, two passes over the row, one rounding to out's dtype (= x's).  Rows of no elements give no output.
+int orc_layer_norm(const orc_tensor* out, const orc_tensor* x, int32_t norm_ndim, const orc_tensor* weight,
+                   const orc_tensor* bias, double eps) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  if (weight && (rc = check_tensor(weight))) return rc;
+  if (bias && (rc = check_tensor(bias))) return rc;
+  if (!is_float(x->dtype) || out->dtype != x->dtype) return ORC_ERR_DTYPE;
+  if ((weight && !is_float(weight->dtype)) || (bias && !is_float(bias->dtype))) return ORC_ERR_DTYPE;
+  if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  const int nd = x->ndim;
+  if (norm_ndim < 1 || norm_ndim > nd) return ORC_ERR_DIM;
+  const int lead = nd - norm_ndim;
+  if (weight && !same_shape(weight, norm_ndim, x->sizes + lead)) return ORC_ERR_SHAPE;
+  if (bias && !same_shape(bias, norm_ndim, x->sizes + lead)) return ORC_ERR_SHAPE;
+  int64_t rows = 1, M = 1;
+  for (int d = 0; d < lead; ++d) rows *= x->sizes[d];
+  for (int d = lead; d < nd; ++d) M *= x->sizes[d];
+  if (rows == 0 || M == 0) return ORC_OK;
+#pragma omp parallel for schedule(static)
+  for (int64_t r = 0; r < rows; ++r) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(r, lead, x->sizes, idx);
+    double sum = 0.0;
+    for (int64_t j = 0; j < M; ++j) {
+      unravel(j, norm_ndim, x->sizes + lead, idx + lead);
+      sum += load_flt(x, offset_of(x, idx));
+    }
+    const double mean = sum / (double)M;
+    double sq = 0.0;
+    for (int64_t j = 0; j < M; ++j) {
+      unravel(j, norm_ndim, x->sizes + lead, idx + lead);
+      const double d = load_flt(x, offset_of(x, idx)) - mean;
+      sq += d * d;
+    }
+    const double rstd = 1.0 / std::sqrt(sq / (double)M + eps);
+    for (int64_t j = 0; j < M; ++j) {
+      unravel(j, norm_ndim, x->sizes + lead, idx + lead);
+      double y = (load_flt(x, offset_of(x, idx)) - mean) * rstd;
+      if (weight) y *= load_flt(weight, offset_of(weight, idx + lead));
+      if (bias) y += load_flt(bias, offset_of(bias, idx + lead));
+      store_flt(out, offset_of(out, idx), y);
+    }
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// binary_cross_entropy (the listing of Appendix B.1 is the paper's kernel for this operator)
+// ===========================================================================
+// loss = -weight * (t * max(ln x, -100) + (1 - t) * max(ln(1 - x), -100)); the clamp at -100 keeps x = 0 and
+// x = 1 finite; a NaN passes through.  x and t have the same shape and floating dtype; weight is optional (null)
+// and broadcasts to that shape.  x is meant to lie in [0, 1]; this is not checked, the formula is applied as it
+// stands.  reduction: 0 none (out has x's shape), 1 mean, 2 sum (out is 0-dim; the mean of no elements is NaN,
+// the sum 0).  ln(1 - x) is taken as log1p(-x).  binary64 throughout (the sum is one running binary64
+// accumulator), one rounding to out's dtype (= x's).
+int orc_bce(const orc_tensor* out, const orc_tensor* x, const orc_tensor* t, const orc_tensor* weight, int reduction) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x)) || (rc = check_tensor(t))) return rc;
+  if (weight && (rc = check_tensor(weight))) return rc;
+  if (!is_float(x->dtype) || t->dtype != x->dtype || out->dtype != x->dtype) return ORC_ERR_DTYPE;
+  if (weight && !is_float(weight->dtype)) return ORC_ERR_DTYPE;
+  if (reduction < 0 || reduction > 2) return ORC_ERR_SCALAR;
+  if (!same_shape(t, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  if (weight) {
+    const orc_tensor* ops[2] = {x, weight};
+    int nd;
+    int64_t sizes[ORC_MAX_DIMS];
+    if ((rc = broadcast_shapes(ops, 2, &nd, sizes))) return rc;
+    if (!same_shape(x, nd, sizes)) return ORC_ERR_SHAPE;           // weight may not enlarge the shape
+  }
+  if (reduction == 0 ? !same_shape(out, x->ndim, x->sizes) : out->ndim != 0) return ORC_ERR_SHAPE;
+  const int64_t n = numel(x);
+  const int nd = x->ndim;
+  auto loss_at = [&](int64_t lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, x->sizes, idx);
+    const double xv = load_flt(x, offset_of(x, idx)), tv = load_flt(t, offset_of(t, idx));
+    double lx = std::log(xv), l1x = std::log1p(-xv);
+    if (lx < -100.0) lx = -100.0;
+    if (l1x < -100.0) l1x = -100.0;
+    double l = -(tv * lx + (1.0 - tv) * l1x);
+    if (weight) l *= load_flt(weight, bcast_offset(weight, nd, idx));
+    return l;
+  };
+  if (reduction == 0) {
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < n; ++lin) {
+      int64_t idx[ORC_MAX_DIMS];
+      unravel(lin, nd, x->sizes, idx);
+      store_flt(out, offset_of(out, idx), loss_at(lin));
+    }
+    return ORC_OK;
+  }
+  double sum = 0.0;
+  for (int64_t lin = 0; lin < n; ++lin) sum += loss_at(lin);
+  store_flt(out, 0, reduction == 1 ? sum / (double)n : sum);
+  return ORC_OK;
+}
+
+// ===========================================================================
 // cumsum along one dim (inclusive)
 // ===========================================================================
 // bool / int32 / int64 input -> int64 output, exact wrapping sums.  Floating

@@ -63,6 +63,8 @@ def lib():
         _lib.orc_reduce.argtypes = [ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int, ctypes.c_double]
         _lib.orc_softmax.argtypes = [P, P, ctypes.c_int64, ctypes.c_int]
         _lib.orc_cumsum.argtypes = [P, P, ctypes.c_int64]
+        _lib.orc_layer_norm.argtypes = [P, P, ctypes.c_int32, P, P, ctypes.c_double]
+        _lib.orc_bce.argtypes = [P, P, P, P, ctypes.c_int]
         _lib.orc_gather.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_index_select.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_scatter_add.argtypes = [P, ctypes.c_int64, P, P]
@@ -203,6 +205,27 @@ def softmax(x, dim=-1, log=False, out=None, out_dtype=None):
     if out is None:
         out = torch.empty(x.shape, dtype=out_dtype or x.dtype)
     _check(lib().orc_softmax(desc(out), desc(x), dim, int(log)))
+    return out
+
+
+REDUCTION = {"none": 0, "mean": 1, "sum": 2}
+
+
+def _opt(t):
+    return desc(t) if t is not None else None
+
+
+def layer_norm(x, norm_ndim, weight=None, bias=None, eps=1e-5, out=None):
+    if out is None:
+        out = torch.empty(x.shape, dtype=x.dtype)
+    _check(lib().orc_layer_norm(desc(out), desc(x), norm_ndim, _opt(weight), _opt(bias), float(eps)))
+    return out
+
+
+def binary_cross_entropy(x, target, weight=None, reduction="mean", out=None):
+    if out is None:
+        out = torch.empty(x.shape if reduction == "none" else (), dtype=x.dtype)
+    _check(lib().orc_bce(desc(out), desc(x), desc(target), _opt(weight), REDUCTION.get(reduction, 9)))
     return out
 
 
