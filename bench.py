@@ -151,6 +151,36 @@ def build_ops(torch, B):
     osf, osb = torch.empty(S, device=dev), torch.empty(S, device=dev, dtype=BF16)
     add("softmax_f32", "a10", "softmax_wave_kernel", ns * 8, ns, lambda: B.tx_softmax(osf, sf, -1, False))
     add("log_softmax_bf16", "a10", "softmax_wave_kernel", ns * 4, ns, lambda: B.tx_softmax(osb, sb, -1, True))
+    # fused row-normalisation and loss operators (Appendix B.3, B.1), timed outside the step; the softmax
+    # tensors double as inputs (layer_norm) and the sweep tensors as probabilities (binary_cross_entropy)
+    lw, lb = randn((S[1],)), randn((S[1],))
+    lwb, lbb = lw.to(BF16), lb.to(BF16)
+    lx = randn(S, std=2.0)
+    lxb = lx.to(BF16)
+    extra("layer_norm_f32[32768,4096]", "f2", "layer_norm_wave_kernel", ns * 8, ns, lambda: B.tx_layer_norm(osf, lx, 1, lw, lb))
+    extra("layer_norm_bf16[32768,4096]", "f2", "layer_norm_wave_kernel", ns * 4, ns,
+          lambda: B.tx_layer_norm(osb, lxb, 1, lwb, lbb))
+    l2 = lx.view(131072, 1024)
+    o2 = osf.view(131072, 1024)
+    extra("layer_norm_f32[131072,1024]", "f2", "layer_norm_wave_kernel", ns * 8, ns,
+          lambda: B.tx_layer_norm(o2, l2, 1, lw[:1024], lb[:1024]))
+    l3 = lx.view(8192, 16384)
+    o3 = osf.view(8192, 16384)
+    extra("layer_norm_f32[8192,16384]_long_rows", "f2", "layer_norm_generic_kernel", ns * 8, ns,
+          lambda: B.tx_layer_norm(o3, l3, 1))
+    px, pt = torch.sigmoid(xf), torch.rand((N, N), device=dev, generator=g)
+    pxb, ptb = px.to(BF16), pt.to(BF16)
+    pw = torch.rand((N,), device=dev, generator=g)
+    oscalar, oscalar_b = torch.empty((), device=dev), torch.empty((), device=dev, dtype=BF16)
+    wsb = B.workspace(B.tx_binary_cross_entropy_workspace_bytes(oscalar, px, pt, pw, "mean"))
+    extra("bce_mean_f32", "f2", "bce_partial_kernel", n2 * 8, n2,
+          lambda: B.tx_binary_cross_entropy(oscalar, px, pt, None, "mean", wsb))
+    extra("bce_mean_f32_class_weight", "f2", "bce_partial_kernel", n2 * 8, n2,
+          lambda: B.tx_binary_cross_entropy(oscalar, px, pt, pw, "mean", wsb))
+    extra("bce_sum_bf16", "f2", "bce_partial_kernel", n2 * 4, n2,
+          lambda: B.tx_binary_cross_entropy(oscalar_b, pxb, ptb, None, "sum", wsb))
+    extra("bce_none_f32", "f2", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary_cross_entropy(of, px, pt, None, "none"))
+
     C = (4096, 65536)
     nc = C[0] * C[1]
     cf, ci = randn(C), randint(C, -100, 100)

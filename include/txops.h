@@ -163,6 +163,41 @@ tx_status tx_where(const tx_tensor* out, const tx_tensor* cond, const tx_tensor*
 tx_status tx_masked_fill(const tx_tensor* out, const tx_tensor* self, const tx_tensor* mask, double value_f,
                          int64_t value_i, int value_is_int, void* stream);
 
+/* ------------------------------------------------------------------ fused row / loss operators
+ * (Table 1 "Deep Learning"; Appendix B.3 and B.1 print the paper's kernels
+ * for these two operators.)
+ */
+
+/* layer_norm over the last norm_ndim dims of x (1 <= norm_ndim <= x.ndim, else
+ * TX_ERR_DIM): per row of those dims, mean and biased variance, then
+ *   out = (x - mean) / sqrt(var + eps) * weight + bias.
+ * weight and bias are optional (NULL); each must have exactly the shape of the
+ * normalised dims (TX_ERR_SHAPE) and x's dtype or fp32.  Floating dtypes only;
+ * out has x's shape and dtype and may not alias an input (TX_ERR_OVERLAP).
+ * Any strides; statistics are accumulated in fp32 (two passes over the row). */
+tx_status tx_layer_norm(const tx_tensor* out, const tx_tensor* x, int32_t norm_ndim, const tx_tensor* weight,
+                        const tx_tensor* bias, double eps, void* stream);
+
+enum { TX_REDUCTION_NONE = 0, TX_REDUCTION_MEAN = 1, TX_REDUCTION_SUM = 2 };
+
+/* loss = -weight * (target * max(ln input, -100) + (1 - target) * max(ln(1 - input), -100)).
+ * input and target have the same shape and floating dtype; weight is optional
+ * (NULL), floating, and broadcasts to input's shape.  input is meant to lie in
+ * [0, 1]; this is not checked on the device (values outside give NaN).
+ * reduction NONE: out has input's shape and dtype (it may alias an input
+ * exactly); no workspace.  MEAN / SUM: out is 0-dim (mean of no elements: NaN),
+ * accumulated in fp32 per lane and binary64 across lanes; needs a 16-byte
+ * aligned device workspace of tx_binary_cross_entropy_workspace_bytes() bytes
+ * (TX_ERR_WORKSPACE otherwise): partial sums, plus the losses themselves when
+ * the operands cannot be read linearly (input and target not laid out alike,
+ * or a weight that is neither laid out like input nor one value per element
+ * of the last dim).  Other reduction codes are TX_ERR_SCALAR. */
+tx_status tx_binary_cross_entropy(const tx_tensor* out, const tx_tensor* input, const tx_tensor* target,
+                                  const tx_tensor* weight, int reduction, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+size_t tx_binary_cross_entropy_workspace_bytes(const tx_tensor* out, const tx_tensor* input, const tx_tensor* target,
+                                               const tx_tensor* weight, int reduction);
+
 /* ------------------------------------------------------------------ reductions
  * (Table 1 "Reduction"; the row mean / variance kernels of the layer_norm
  * listing in Appendix B are the paper's form of the inner-dim case.)

@@ -30,7 +30,7 @@ STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so")
 
 EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
-           "tx_softmax", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
+           "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
 
@@ -77,6 +77,9 @@ def lib():
                       ctypes.c_int32),
         "tx_reduce_workspace_bytes": ([ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int], ctypes.c_size_t),
         "tx_softmax": ([P, P, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
+        "tx_layer_norm": ([P, P, ctypes.c_int32, P, P, ctypes.c_double, V], ctypes.c_int32),
+        "tx_binary_cross_entropy": ([P, P, P, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_binary_cross_entropy_workspace_bytes": ([P, P, P, P, ctypes.c_int], ctypes.c_size_t),
         "tx_cumsum": ([P, P, ctypes.c_int64, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_cumsum_workspace_bytes": ([P, P, ctypes.c_int64], ctypes.c_size_t),
         "tx_gather": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
@@ -179,6 +182,28 @@ def tx_infer_clamp_dtype(dtype, lo=None, hi=None):
                                     hi is not None, _scalar(0 if hi is None else hi)[2])
     _check(rc)
     return CODE_DTYPE[rc]
+
+
+REDUCTION = {"none": 0, "mean": 1, "sum": 2}
+
+
+def _opt(t):
+    return desc(t) if t is not None else None
+
+
+def tx_layer_norm(out, x, norm_ndim, weight=None, bias=None, eps=1e-5, stream=None):
+    _check(lib().tx_layer_norm(desc(out), desc(x), norm_ndim, _opt(weight), _opt(bias), float(eps), _stream(stream)))
+
+
+def tx_binary_cross_entropy_workspace_bytes(out, input, target, weight=None, reduction="mean"):
+    return lib().tx_binary_cross_entropy_workspace_bytes(desc(out), desc(input), desc(target), _opt(weight),
+                                                         REDUCTION.get(reduction, 9))
+
+
+def tx_binary_cross_entropy(out, input, target, weight=None, reduction="mean", ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tx_binary_cross_entropy(desc(out), desc(input), desc(target), _opt(weight), REDUCTION.get(reduction, 9),
+                                         p, n, _stream(stream)))
 
 
 def tx_where(out, cond, x, y, stream=None):

@@ -135,6 +135,31 @@ __device__ __forceinline__ float logsigmoid_half(float x) {
   return __builtin_fminf(x, 0.0f) - l1p;
 }
 
+// one term of binary_cross_entropy: -(t max(ln x, -100) + (1 - t) max(ln(1 - x), -100)) in fp32.
+// log(1 - x) as log1p(-x): log(u) * (-x) / (u - 1) with u = 1 - x rounded recovers the bits the rounding of u
+// dropped (exact when u == 1)
+__device__ __forceinline__ float log1m(float x) {
+  const float u = 1.0f - x;
+  return u == 1.0f ? -x : logf(u) * (-x) / (u - 1.0f);
+}
+__device__ __forceinline__ float bce_term(float x, float t) {
+  float lx = logf(x), l1 = log1m(x);
+  lx = lx < -100.0f ? -100.0f : lx;                  // written so that a NaN stays a NaN
+  l1 = l1 < -100.0f ? -100.0f : l1;
+  return -(t * lx + (1.0f - t) * l1);
+}
+
+// the same with the hardware log2 and reciprocal: for sums of many terms, where a term near zero (input within a
+// few ulp of the target) may carry a larger relative error because it does not matter to the sum
+__device__ __forceinline__ float bce_term_fast(float x, float t) {
+  const float u = 1.0f - x;
+  float lx = __logf(x);
+  float l1 = u == 1.0f ? -x : __logf(u) * (-x) * __builtin_amdgcn_rcpf(u - 1.0f);
+  lx = lx < -100.0f ? -100.0f : lx;
+  l1 = l1 < -100.0f ? -100.0f : l1;
+  return -(t * lx + (1.0f - t) * l1);
+}
+
 // gelu for fp16 / bf16 results (8-11 significant bits): the same erfc form in plain fp32 with a degree-5
 // fit (relative error 5.5e-5, same fit_erfcx.py recipe) and the hardware exp2 / reciprocal.
 __device__ __forceinline__ float gelu_erf_half(float x) {

@@ -19,76 +19,16 @@
 #include <cstring>
 
 #include "common.h"
+#include "rows.h"
 
 namespace tx {
 namespace {
-
-constexpr int kBlock = 256;
-
-// the dims other than `dim`, merged where both tensors allow, inner-most last
-struct Slices {
-  int n;
-  FastDiv div[TX_MAX_DIMS];
-  int64_t size[TX_MAX_DIMS], xs[TX_MAX_DIMS], os[TX_MAX_DIMS];
-  int64_t count;
-};
-
-void build_slices(Slices* s, const tx_tensor* x, const tx_tensor* out, int dim) {
-  s->n = 0;
-  s->count = 1;
-  for (int d = 0; d < x->ndim; ++d) {
-    if (d == dim) continue;
-    const int64_t sz = x->sizes[d];
-    s->count *= sz;
-    if (sz == 1) continue;
-    if (s->n > 0 && s->xs[s->n - 1] == x->strides[d] * sz && s->os[s->n - 1] == out->strides[d] * sz) {
-      s->size[s->n - 1] *= sz;
-      s->xs[s->n - 1] = x->strides[d];
-      s->os[s->n - 1] = out->strides[d];
-    } else {
-      s->size[s->n] = sz;
-      s->xs[s->n] = x->strides[d];
-      s->os[s->n] = out->strides[d];
-      ++s->n;
-    }
-  }
-  for (int d = 0; d < s->n; ++d) s->div[d] = FastDiv((uint32_t)std::min<int64_t>(s->size[d], 0x7fffffff));
-}
-
-__device__ __forceinline__ void slice_offsets(const Slices& s, int64_t idx, int64_t* xo, int64_t* oo) {
-  int64_t x = 0, o = 0;
-  if (s.n == 1) { x = idx * s.xs[0]; o = idx * s.os[0]; }
-  else {
-    uint32_t rem = (uint32_t)idx;
-    for (int d = s.n - 1; d >= 0; --d) {
-      uint32_t q, m;
-      s.div[d].divmod(rem, q, m);
-      rem = q;
-      x += (int64_t)m * s.xs[d];
-      o += (int64_t)m * s.os[d];
-    }
-  }
-  *xo = x;
-  *oo = o;
-}
 
 template <class O> __device__ __forceinline__ O from_float(float v) { return cvt<O>(v); }
 
 // ---------------------------------------------------------------------------
 // softmax
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int m = kWave / 2; m >= 1; m >>= 1) v = fmaxf(v, shfl_xor(v, m));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = kWave / 2; m >= 1; m >>= 1) v += shfl_xor(v, m);
-  return v;
-}
-constexpr float kNegInf = -__builtin_huge_valf();
-
 struct SoftmaxArgs {
   const char* x;
   char* out;
@@ -157,18 +97,6 @@ __global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs 
       vec_store<O, VEC, true>(out + c, t);
     }
   }
-}
-
-__device__ __forceinline__ float block_reduce(float v, bool is_max, float* lds) {
-  v = is_max ? wave_max(v) : wave_sum(v);
-  const int w = threadIdx.x / kWave;
-  __syncthreads();                          // protects lds reuse between calls
-  if ((threadIdx.x & (kWave - 1)) == 0) lds[w] = v;
-  __syncthreads();
-  float r = lds[0];
-#pragma unroll
-  for (int k = 1; k < kBlock / kWave; ++k) r = is_max ? fmaxf(r, lds[k]) : r + lds[k];
-  return r;
 }
 
 // one workgroup per row, three passes

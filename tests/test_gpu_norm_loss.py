@@ -1,0 +1,223 @@
+"""GPU parity: layer_norm and binary_cross_entropy (HIP library through the C ABI) vs. the CPU oracle.
+
+Tolerances: fp32 within rel 1e-5 of max(|oracle|, scale) and fp16 / bf16 within rel 1e-2, where `scale` is the
+magnitude of the terms the value is made of (for layer_norm (|x| + |mean|) * rstd * |w| + |b|, so that outputs
+near zero are judged against what cancelled; for the loss its terms are all of one sign and scale is 0).
+"""
+import itertools
+
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2512_10977_amd import binding as B
+from paper_2512_10977_amd import inputs as I
+from tests.parity import HALF_MAX, assert_rel, to_device_view
+
+pytestmark = pytest.mark.gpu
+F32, BF16, F16, I64 = torch.float32, torch.bfloat16, torch.float16, torch.int64
+FLT_TINY = 1.2e-38
+
+
+def rel_of(dt):
+    return 1e-5 if dt == F32 else 1e-2
+
+
+def ln_scale(x, k, w, b, eps):
+    xd = x.double()
+    dims = tuple(range(x.dim() - k, x.dim()))
+    mean = xd.mean(dims, keepdim=True)
+    rstd = 1.0 / (xd.var(dims, unbiased=False, keepdim=True) + eps).sqrt()
+    s = (xd.abs() + mean.abs()) * rstd
+    if w is not None:
+        s = s * w.double().abs()
+    if b is not None:
+        s = s + b.double().abs()
+    return s
+
+
+def check_layer_norm(x_cpu, k, w_cpu=None, b_cpu=None, eps=1e-5, path=None, out_like=None, what=""):
+    want = O.layer_norm(x_cpu, k, w_cpu, b_cpu, eps)
+    x = to_device_view(x_cpu)
+    w = to_device_view(w_cpu) if w_cpu is not None else None
+    b = to_device_view(b_cpu) if b_cpu is not None else None
+    out = torch.empty(x.shape, dtype=x.dtype, device="cuda") if out_like is None else to_device_view(out_like)
+    B.tx_force_path(path)
+    try:
+        B.tx_layer_norm(out, x, k, w, b, eps)
+        used = B.tx_last_path()
+    finally:
+        B.tx_force_path(None)
+    torch.cuda.synchronize()
+    assert_rel(out, want, rel_of(x_cpu.dtype), scale=ln_scale(x_cpu, k, w_cpu, b_cpu, eps),
+               what="layer_norm %s %s k=%d %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), k, what, used))
+    return used
+
+
+@pytest.mark.parametrize("dt", [F32, BF16, F16])
+def test_layer_norm_row_lengths_and_paths(dt):
+    V = 16 // torch.empty(0, dtype=dt).element_size()
+    for rows, length in [(37, 4), (5, 64 * V), (9, 64 * V + V), (6, 200 * V), (5, 512 * V), (3, 1024 * V), (2, 1024 * V + V),
+                         (2, 2048 * V), (2, 4096 * V), (2, 4096 * V + V), (7, 333), (3, 5000), (1, 1), (4, 2)]:
+        x = I.typed((rows, length), dt, seed=300 + length) * 2 + 0.5
+        w, b = I.typed((length,), dt, seed=301), I.typed((length,), dt, seed=302)
+        used = check_layer_norm(x, 1, w, b)
+        expect = "layer-norm-generic" if length % V or length > 4096 * V else \
+            "layer-norm-wave" if length <= 1024 * V else "layer-norm-block"
+        assert used == expect, (rows, length, used)
+        check_layer_norm(x, 1, w, b, path="layer-norm-generic", what="forced generic")
+        if length % V == 0 and length <= 4096 * V:
+            assert check_layer_norm(x, 1, w, b, path="layer-norm-block", what="forced block") == "layer-norm-block"
+        check_layer_norm(x, 1, None, None, what="no affine")
+        check_layer_norm(x, 1, w, None, eps=0.1, what="weight only")
+        check_layer_norm(x, 1, None, b, what="bias only")
+
+
+def test_layer_norm_views_and_several_dims():
+    for dt in (F32, BF16):
+        x = I.typed((6, 5, 8, 16), dt, seed=310) * 3
+        w, b = I.typed((8, 16), dt, seed=311), I.typed((8, 16), dt, seed=312)
+        assert check_layer_norm(x, 2, w, b) == "layer-norm-wave"
+        check_layer_norm(x, 4, what="all dims")
+        check_layer_norm(x, 3, I.typed((5, 8, 16), dt, seed=313), None)
+        # leading dims permuted / sliced: rows are still contiguous
+        assert check_layer_norm(x.permute(1, 0, 2, 3), 2, w, b, what="permuted lead") == "layer-norm-wave"
+        assert check_layer_norm(x[::2, 1:4], 2, w, b, what="sliced lead") == "layer-norm-wave"
+        # normalised dims strided or permuted, strided weight, permuted out
+        assert check_layer_norm(x.transpose(2, 3), 2, w.t(), b.t(), what="permuted inner") == "layer-norm-generic"
+        assert check_layer_norm(x[..., ::2], 2, w[:, ::2], b[:, ::2], what="step-2 inner") == "layer-norm-generic"
+        wide = I.typed((8, 32), dt, seed=314)
+        assert check_layer_norm(x, 2, wide[:, ::2], b, what="strided weight") == "layer-norm-generic"
+        check_layer_norm(x, 2, w, b, out_like=torch.empty((6, 5, 16, 8), dtype=dt).transpose(2, 3), what="permuted out")
+        if dt == BF16:                                              # fp32 affine parameters with a half input
+            assert check_layer_norm(x, 2, w.float(), b.float(), what="fp32 affine") == "layer-norm-wave"
+            check_layer_norm(x, 2, w.float(), b, path="layer-norm-generic", what="fp32 weight, generic")
+
+
+def test_layer_norm_special_rows_and_errors():
+    x = I.typed((6, 256), F32, seed=320)
+    x[1] = 3.25                                     # constant row: variance 0, output = bias
+    x[2, 7] = float("nan")
+    x[3, 9] = float("inf")
+    x[4] = x[4] * 1e-3 + 1000.0                    # small spread on a large offset (the two-pass variance matters)
+    b = I.typed((256,), F32, seed=321)
+    check_layer_norm(x, 1, None, b)
+    check_layer_norm(x, 1, None, b, path="layer-norm-generic")
+    check_layer_norm(x, 1, None, b, path="layer-norm-block")
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    for args, kind in (((d(3, 4), d(3, 4), 0), "DIM"), ((d(3, 4), d(3, 4), 3), "DIM"), ((d(3, 4), d(3, 4), 1, d(3)), "SHAPE"),
+                       ((d(3, 4), d(3, 4), 1, None, d(4, 1)), "SHAPE"), ((d(3, 4, dt=I64), d(3, 4, dt=I64), 1), "DTYPE"),
+                       ((d(3, 4, dt=BF16), d(3, 4), 1), "DTYPE"), ((d(4, 3), d(3, 4), 1), "SHAPE"),
+                       ((d(3, 4), d(3, 4), 1, d(4, dt=I64)), "DTYPE")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_layer_norm(*args)
+        assert e.value.kind == kind, (kind, e.value.kind)
+    buf = d(3, 4)
+    with pytest.raises(B.TxError) as e:
+        B.tx_layer_norm(buf, buf, 1)
+    assert e.value.kind == "OVERLAP"
+    B.tx_layer_norm(d(0, 4), d(0, 4), 1)
+    B.tx_layer_norm(d(3, 0), d(3, 0), 1)
+
+
+@pytest.mark.parametrize("dt,shape", [(F32, (65536, 1024)), (BF16, (16384, 4096)), (F32, (8192, 8192))])
+def test_layer_norm_full_size(dt, shape):
+    x = I.typed(shape, dt, seed=330) * 2 + 0.25
+    w, b = I.typed(shape[-1:], dt, seed=331), I.typed(shape[-1:], dt, seed=332)
+    used = check_layer_norm(x, 1, w, b)
+    assert used == ("layer-norm-wave" if shape[1] <= 4096 else "layer-norm-block")
+
+
+# --------------------------------------------------------------------------- binary_cross_entropy
+def bce_inputs(shape, dt, seed, hard_targets=False):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.sigmoid(torch.randn(shape, generator=g) * 4)
+    t = torch.rand(shape, generator=g)
+    if hard_targets:
+        t = (t > 0.5).float()
+    flat = x.view(-1)
+    if flat.numel() >= 8:
+        flat[0], flat[1], flat[2], flat[3] = 0.0, 1.0, 1e-30, 1 - 2.0 ** -24
+    return x.to(dt), t.to(dt)
+
+
+def check_bce(x_cpu, t_cpu, w_cpu=None, reduction="mean", path=None, what=""):
+    want = O.binary_cross_entropy(x_cpu, t_cpu, w_cpu, reduction)
+    x, t = to_device_view(x_cpu), to_device_view(t_cpu)
+    w = to_device_view(w_cpu) if w_cpu is not None else None
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_force_path(path)
+    try:
+        ws = B.workspace(B.tx_binary_cross_entropy_workspace_bytes(out, x, t, w, reduction))
+        B.tx_binary_cross_entropy(out, x, t, w, reduction, ws)
+        used = B.tx_last_path()
+    finally:
+        B.tx_force_path(None)
+    torch.cuda.synchronize()
+    assert_rel(out, want, rel_of(x_cpu.dtype), scale=FLT_TINY, overflow_max=HALF_MAX.get(x_cpu.dtype),
+               what="bce %s %s %s %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), reduction, what, used))
+    return used
+
+
+@pytest.mark.parametrize("dt", [F32, BF16, F16])
+def test_bce_sweep(dt):
+    for shape, red in itertools.product([(7, 13, 5), (300, 64), (4097,), (3, 1024), ()], ["none", "mean", "sum"]):
+        x, t = bce_inputs(shape, dt, seed=340)
+        used = check_bce(x, t, None, red)
+        if red != "none":
+            assert used.startswith("bce-fused"), used
+            check_bce(x, t, None, red, path="bce-two-pass", what="forced two-pass")
+        if len(shape) >= 1:
+            g = torch.Generator().manual_seed(341)
+            last = torch.rand(shape[-1:], generator=g).to(dt)
+            full = torch.rand(shape, generator=g).to(dt)
+            assert check_bce(x, t, last, red, what="last-dim weight") in ("vec", "generic", "bce-fused", "bce-fused-scalar")
+            check_bce(x, t, full, red, what="full weight")
+            check_bce(x, t, full.float(), red, what="fp32 weight")
+            if len(shape) >= 2:
+                col = torch.rand(shape[:-1] + (1,), generator=g).to(dt)
+                used = check_bce(x, t, col, red, what="column weight")
+                assert red == "none" or used == "bce-two-pass"
+    x, t = bce_inputs((64, 48), dt, seed=342, hard_targets=True)
+    for red in ("none", "mean", "sum"):
+        check_bce(x, t, None, red, what="hard targets")
+        # views: the same permutation of both operands can be read linearly, different layouts cannot
+        used = check_bce(x.t(), t.t(), None, red, what="both transposed")
+        assert red == "none" or used.startswith("bce-fused")
+        used = check_bce(x.t(), t.t().contiguous(), None, red, what="one transposed")
+        assert red == "none" or used == "bce-two-pass"
+        check_bce(x[:, ::2], t[:, ::2], None, red, what="step-2")
+
+
+def test_bce_nan_empty_and_errors():
+    x = torch.tensor([0.5, float("nan"), -0.5, 2.0, 0.25])
+    t = torch.tensor([1.0, 1.0, 1.0, 0.0, float("nan")])
+    for red in ("none", "mean", "sum"):
+        check_bce(x, t, None, red)
+    e0 = torch.zeros((0, 3))
+    for red in ("none", "mean", "sum"):
+        check_bce(e0, e0, None, red)
+    d = lambda *s, dt=F32: torch.full(s, 0.5, dtype=dt, device="cuda")
+    ws = B.workspace(1 << 16)
+    for args, kind in (((d(3, 4), d(3, 4), d(4, 3)), "SHAPE"), ((d(3, 4), d(3, 4), d(4)), "SHAPE"),
+                       ((d(3, 4), d(3, 4), d(3, 4), d(2, 3, 4)), "SHAPE"), ((d(3, 4), d(3, 4), d(3, 4), d(3)), "SHAPE"),
+                       ((d(3, 4, dt=I64), d(3, 4, dt=I64), d(3, 4, dt=I64)), "DTYPE"),
+                       ((d(3, 4), d(3, 4), d(3, 4, dt=BF16)), "DTYPE"), ((d(3, 4), d(3, 4), d(3, 4), None, "median"), "SCALAR")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_binary_cross_entropy(args[0], args[1], args[2], args[3] if len(args) > 3 else None,
+                                      args[4] if len(args) > 4 else "none", ws)
+        assert e.value.kind == kind, (kind, e.value.kind)
+    with pytest.raises(B.TxError) as e:
+        B.tx_binary_cross_entropy(d(), d(3, 4), d(3, 4), None, "mean", None)
+    assert e.value.kind == "WORKSPACE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_binary_cross_entropy(d(3), d(3, 4), d(3, 4), None, "sum", ws)
+    assert e.value.kind == "SHAPE"
+
+
+@pytest.mark.parametrize("dt,red", [(F32, "mean"), (F32, "none"), (BF16, "sum"), (BF16, "none")])
+def test_bce_full_size(dt, red):
+    x, t = bce_inputs((8192, 8192), dt, seed=350)
+    w = torch.rand(8192, generator=torch.Generator().manual_seed(351)).to(dt)
+    assert check_bce(x, t, None, red) == ("vec" if red == "none" else "bce-fused")
+    assert check_bce(x, t, w, red, what="last-dim weight") == ("vec" if red == "none" else "bce-fused")
