@@ -181,6 +181,18 @@ def build_ops(torch, B):
           lambda: B.tx_binary_cross_entropy(oscalar_b, pxb, ptb, None, "sum", wsb))
     extra("bce_none_f32", "f2", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary_cross_entropy(of, px, pt, None, "none"))
 
+    # softmax / cumsum along a dim that is not the innermost one (column kernels), timed outside the step
+    sT, oT = sf.view(4096, 32768), osf.view(4096, 32768)
+    extra("softmax_f32_dim0[4096,32768]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(oT, sT, 0, False))
+    s3, o3d = sf.view(64, 4096, 512), osf.view(64, 4096, 512)
+    extra("log_softmax_f32_dim1[64,4096,512]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(o3d, s3, 1, True))
+    wsc = B.workspace(max(B.tx_cumsum_workspace_bytes(oT, lx.view(4096, 32768), 0),
+                          B.tx_cumsum_workspace_bytes(osf.view(65536, 2048), lx.view(65536, 2048), 0)))
+    extra("cumsum_f32_dim0[4096,32768]", "f3", "colscan_apply_kernel", ns * 8, ns,
+          lambda: B.tx_cumsum(oT, lx.view(4096, 32768), 0, wsc))
+    extra("cumsum_f32_dim0[65536,2048]", "f3", "colscan_apply_kernel", ns * 8, ns,
+          lambda: B.tx_cumsum(osf.view(65536, 2048), lx.view(65536, 2048), 0, wsc))
+
     C = (4096, 65536)
     nc = C[0] * C[1]
     cf, ci = randn(C), randint(C, -100, 100)

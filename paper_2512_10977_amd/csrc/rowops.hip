@@ -6,7 +6,8 @@
 //           read, two wave reductions (max, sum), one HBM write.
 //   block : longer rows; a 256-lane workgroup makes three passes over the row
 //           (the re-reads are served by L2).
-// softmax / cumsum along any other dim or over a strided slice:
+// softmax / cumsum along another dim whose trailing dims are contiguous: the column kernels of colops.hip.
+// Anything else (strided slices, short trailing runs):
 //   strided: one lane per slice, walking the dim with its stride (lanes run
 //           along the innermost other dim, so accesses stay coalesced when
 //           that dim is contiguous).
@@ -189,6 +190,7 @@ tx_status softmax_launch(const tx_tensor* out, const tx_tensor* x, int dim, int 
     }
     return check_launch("softmax kernel");
   }
+  if (nd && strcmp(forced_path(), "softmax-strided") && cols_path_ok(out, x, dim)) return softmax_cols(out, x, dim, is_log, stream);
   StridedArgs a;
   a.x = (const char*)x->data;
   a.out = (char*)out->data;
@@ -531,6 +533,8 @@ tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void*
   Slices sl;
   build_slices(&sl, x, out, x->ndim ? dim : -1);
   ScanPlan p = scan_plan<T, O, Acc>(out, x, dim, sl);
+  if (!p.lookback && x->ndim && strcmp(forced_path(), "scan-strided") && cols_path_ok(out, x, dim))
+    return cumsum_cols(out, x, dim, ws, ws_bytes, stream, query);
   if (query) { *query = p.lookback ? p.ws_bytes : 0; return TX_OK; }
   if (sl.count >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "cumsum: too many slices");
   if (p.lookback) {

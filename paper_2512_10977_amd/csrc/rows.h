@@ -6,6 +6,13 @@
 #include "common.h"
 
 namespace tx {
+
+// column forms (colops.hip): the operated dim is not the innermost one and the dims after it are one contiguous run
+bool cols_path_ok(const tx_tensor* out, const tx_tensor* x, int dim);
+tx_status softmax_cols(const tx_tensor* out, const tx_tensor* x, int dim, int is_log, hipStream_t stream);
+tx_status cumsum_cols(const tx_tensor* out, const tx_tensor* x, int dim, void* ws, size_t ws_bytes, hipStream_t stream,
+                      size_t* query);
+
 namespace {
 
 constexpr int kBlock = 256;

@@ -190,3 +190,62 @@ def test_cumsum_full_size(dt):
         assert check_cumsum(x, -1) == "scan-carry"
     finally:
         B.tx_force_path(None)
+
+
+# --------------------------------------------------------------------------- column forms (dim is not the innermost)
+COL_SHAPES = [((1, 2, 16), 1), ((3, 65, 64), 1), ((2, 257, 100), 1), ((1000, 300), 0), ((64, 1028), 0), ((63, 17), 0),
+              ((2, 3, 130, 8, 4), 2), ((5, 1, 40), 1), ((129, 2, 256), 0), ((4, 2100, 36), 1)]
+
+
+@pytest.mark.parametrize("log", [False, True])
+def test_softmax_column_form(log):
+    for dt in (F32, BF16, F16):
+        for shape, dim in COL_SHAPES:
+            x = I.softmax_logits(shape, dt, seed=330 + len(shape))
+            used = check_softmax(x, dim, log)
+            assert used == ("softmax-cols" if shape[dim] >= 2 else "softmax-strided"), (shape, dim, used)
+        x = I.softmax_logits((6, 70, 48), dt, seed=331)
+        assert check_softmax(x.transpose(0, 1), 1, log, what="outer stride") == "softmax-cols"
+        assert check_softmax(x[:, ::2], 1, log, what="strided L") == "softmax-cols"
+        assert check_softmax(x[..., 1:33], 1, log, what="offset columns") == "softmax-cols"
+        assert check_softmax(x[..., ::2], 1, log, what="strided inner") == "softmax-strided"
+    check_softmax(I.softmax_logits((300, 512), BF16, seed=332), 0, log, out_dtype=F32, what="fp32 out")
+    inf, nan = float("inf"), float("nan")
+    cols = torch.tensor([[0.0, -inf, 1.0, 2.0], [-inf, -inf, -inf, -inf], [0.0, inf, 1.0, 0.5], [0.0, nan, 1.0, 0.5],
+                         [5.0, 5.0, 5.0, 5.0], [-inf, 1.0, inf, nan]]).t().contiguous()        # one case per column
+    assert check_softmax(cols.repeat(40, 8), 0, log, what="special columns") == "softmax-cols"
+    B.tx_force_path("softmax-strided")
+    try:
+        assert check_softmax(I.softmax_logits((40, 64), F32, seed=333), 0, log) == "softmax-strided"
+    finally:
+        B.tx_force_path(None)
+
+
+def test_cumsum_column_form():
+    for dt in (F32, BF16, F16, I32, I64, BOOL):
+        for shape, dim in COL_SHAPES:
+            x = I.cumsum_input(shape, dt, seed=340) if dt != BOOL else I.booleans(shape, 0.5, seed=340)
+            used = check_cumsum(x, dim)
+            assert used.startswith("scan-cols" if shape[dim] >= 2 else "scan-strided"), (shape, dim, used)
+        x = I.cumsum_input((6, 70, 48), dt, seed=341) if dt != BOOL else I.booleans((6, 70, 48), 0.5, seed=341)
+        assert check_cumsum(x.transpose(0, 1), 1, what="outer stride").startswith("scan-cols")
+        assert check_cumsum(x[:, ::2], 1, what="strided L").startswith("scan-cols")
+        assert check_cumsum(x[..., 1:33], 1, what="offset columns") == "scan-cols-scalar"
+        assert check_cumsum(x[..., ::2], 1, what="strided inner") == "scan-strided"
+    check_cumsum(I.cumsum_input((3000, 64), BF16, seed=342), 0, out_dtype=F32, what="fp32 out")
+    # long columns on few strips: several tiles per column (the three-pass form) and the workspace check
+    x = I.cumsum_input((70000, 128), F32, seed=343)
+    assert check_cumsum(x, 0) == "scan-cols"
+    dx, out = x.cuda(), torch.empty(x.shape, device="cuda")
+    assert B.tx_cumsum_workspace_bytes(out, dx, 0) > 0
+    with pytest.raises(B.TxError) as e:
+        B.tx_cumsum(out, dx, 0, None)
+    assert e.value.kind == "WORKSPACE"
+    check_cumsum(I.cumsum_input((70000, 48), I64, seed=344), 0)
+
+
+@pytest.mark.parametrize("shape,dim", [((4096, 32768), 0), ((64, 4096, 512), 1), ((65536, 2048), 0)])
+def test_column_forms_full_size(shape, dim):
+    x = I.softmax_logits(shape, F32, seed=350)
+    assert check_softmax(x, dim, False) == "softmax-cols"
+    assert check_cumsum(x, dim) == "scan-cols"
