@@ -1345,6 +1345,149 @@ int orc_scatter_add(const orc_tensor* self, int64_t dim, const orc_tensor* index
   return ORC_OK;
 }
 
+// index_add_ (in place on self): for every i, self[..., index[i], ...] += alpha * source[..., i, ...] along `dim`.
+// index is 1-D (or 0-dim) int32 / int64 with source.size(dim) entries in [0, self.size(dim)); source has self's
+// shape except along dim; both have the same dtype (bool is refused).  Integers: exact wrapping arithmetic, alpha
+// must be integral.  Floating dtypes: the products alpha * source are accumulated per destination element in
+// binary64 in index order, the initial value of self is added, one rounding.
+int orc_index_add(const orc_tensor* self, int64_t dim, const orc_tensor* index, const orc_tensor* source, double alpha_f,
+                  int64_t alpha_i, int alpha_is_int) {
+  int rc;
+  if ((rc = check_tensor(self)) || (rc = check_tensor(index)) || (rc = check_tensor(source))) return rc;
+  if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
+  if (self->dtype != source->dtype || self->dtype == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (index->ndim > 1 || source->ndim != self->ndim) return ORC_ERR_SHAPE;
+  const int nd = self->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  const int64_t ni = numel(index);
+  if ((nd == 0 ? 1 : source->sizes[dim]) != ni) return ORC_ERR_SHAPE;
+  for (int d = 0; d < nd; ++d)
+    if (d != dim && source->sizes[d] != self->sizes[d]) return ORC_ERR_SHAPE;
+  const bool flt = is_float(self->dtype);
+  if (!flt && !alpha_is_int) return ORC_ERR_SCALAR;
+  const int64_t extent = nd == 0 ? 1 : self->sizes[dim];
+  const int64_t istride = index->ndim ? index->strides[0] : 0;
+  for (int64_t i = 0; i < ni; ++i) {
+    int64_t k = load_int(index, i * istride);
+    if (k < 0 || k >= extent) return ORC_ERR_INDEX;      // checked first: nothing is written on error
+  }
+  const double alpha = alpha_is_int ? (double)alpha_i : alpha_f;
+  // one destination element at a time: its contributions in index order
+  const int64_t nself = numel(self);
+  for (int64_t lin = 0; lin < nself; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, self->sizes, idx);
+    const int64_t d_o = offset_of(self, idx);
+    const int64_t row = nd ? idx[dim] : 0;
+    double acc = 0.0;
+    uint64_t iacc = 0;
+    bool touched = false;
+    for (int64_t i = 0; i < ni; ++i) {
+      if (load_int(index, i * istride) != row) continue;
+      if (nd) idx[dim] = i;
+      const int64_t so = offset_of(source, idx);
+      if (flt) acc += alpha * load_flt(source, so);
+      else iacc += (uint64_t)alpha_i * (uint64_t)load_int(source, so);
+      touched = true;
+    }
+    if (!touched) continue;                              // untouched elements keep their bits
+    if (flt) store_flt(self, d_o, load_flt(self, d_o) + acc);
+    else store_int(self, d_o, (int64_t)((uint64_t)load_int(self, d_o) + iacc));
+  }
+  return ORC_OK;
+}
+
+// take(input, index): out[p] = input viewed as a 1-D tensor in logical (row-major) order, at index[p]; negative
+// indices count from the end.  out has index's shape and input's dtype.  An index outside [-n, n) is an error.
+int orc_take(const orc_tensor* out, const orc_tensor* input, const orc_tensor* index) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(input)) || (rc = check_tensor(index))) return rc;
+  if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
+  if (out->dtype != input->dtype) return ORC_ERR_DTYPE;
+  if (!same_shape(out, index->ndim, index->sizes)) return ORC_ERR_SHAPE;
+  const int64_t n = numel(input), m = numel(index);
+  const int es = esize(input->dtype);
+  for (int pass = 0; pass < 2; ++pass) {                 // pass 0 validates, pass 1 writes
+    for (int64_t lin = 0; lin < m; ++lin) {
+      int64_t idx[ORC_MAX_DIMS] = {0};
+      unravel(lin, index->ndim, index->sizes, idx);
+      int64_t k = load_int(index, offset_of(index, idx));
+      if (k < -n || k >= n) return ORC_ERR_INDEX;
+      if (!pass) continue;
+      if (k < 0) k += n;
+      int64_t sidx[ORC_MAX_DIMS] = {0};
+      unravel(k, input->ndim, input->sizes, sidx);
+      std::memcpy(mptr(out, offset_of(out, idx)), cptr(input, offset_of(input, sidx)), es);
+    }
+  }
+  return ORC_OK;
+}
+
+// masked_select(x, mask): the elements of x (broadcast with the bool mask) where the mask is true, in logical
+// (row-major) order of the broadcast shape.  `out` is a 1-D buffer of x's dtype with room for them (its first
+// *count elements are written; a smaller buffer is a shape error and nothing is written).
+int orc_masked_select(const orc_tensor* out, const orc_tensor* x, const orc_tensor* mask, int64_t* count) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x)) || (rc = check_tensor(mask))) return rc;
+  if (mask->dtype != ORC_BOOL || out->dtype != x->dtype) return ORC_ERR_DTYPE;
+  if (out->ndim != 1) return ORC_ERR_SHAPE;
+  const orc_tensor* ops[2] = {x, mask};
+  int nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(ops, 2, &nd, sizes))) return rc;
+  int64_t n = 1;
+  for (int d = 0; d < nd; ++d) n *= sizes[d];
+  int64_t c = 0;
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    c += load_int(mask, bcast_offset(mask, nd, idx)) != 0;
+  }
+  if (count) *count = c;
+  if (out->sizes[0] < c) return ORC_ERR_SHAPE;
+  const int es = esize(x->dtype);
+  int64_t w = 0;
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    if (!load_int(mask, bcast_offset(mask, nd, idx))) continue;
+    std::memcpy(mptr(out, w * out->strides[0]), cptr(x, bcast_offset(x, nd, idx)), es);
+    ++w;
+  }
+  return ORC_OK;
+}
+
+// nonzero(x): the multi-indices of the elements that are not zero (a NaN is not zero; -0.0 is zero), in logical
+// (row-major) order, one row of x.ndim int64 coordinates each.  `out` is a 2-D int64 buffer [capacity, x.ndim];
+// its first *count rows are written (a smaller buffer is a shape error and nothing is written).
+int orc_nonzero(const orc_tensor* out, const orc_tensor* x, int64_t* count) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  if (out->dtype != ORC_I64) return ORC_ERR_DTYPE;
+  if (out->ndim != 2 || out->sizes[1] != x->ndim) return ORC_ERR_SHAPE;
+  const int64_t n = numel(x);
+  auto is_nz = [&](int64_t off) { return is_float(x->dtype) ? !(load_flt(x, off) == 0.0) : load_int(x, off) != 0; };
+  int64_t c = 0;
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, x->ndim, x->sizes, idx);
+    c += is_nz(offset_of(x, idx));
+  }
+  if (count) *count = c;
+  if (out->sizes[0] < c) return ORC_ERR_SHAPE;
+  int64_t w = 0;
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, x->ndim, x->sizes, idx);
+    if (!is_nz(offset_of(x, idx))) continue;
+    for (int d = 0; d < x->ndim; ++d) store_int(out, w * out->strides[0] + d * out->strides[1], idx[d]);
+    ++w;
+  }
+  return ORC_OK;
+}
+
 // Test hooks for the format codecs: encode a binary64 value into `dtype`
 // (F16 / BF16 / F32) with one rounding, and decode a bit pattern exactly.
 uint32_t orc_encode(double v, int dtype) {

@@ -68,6 +68,10 @@ def lib():
         _lib.orc_gather.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_index_select.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_scatter_add.argtypes = [P, ctypes.c_int64, P, P]
+        _lib.orc_index_add.argtypes = [P, ctypes.c_int64, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
+        _lib.orc_take.argtypes = [P, P, P]
+        _lib.orc_masked_select.argtypes = [P, P, P, I64P]
+        _lib.orc_nonzero.argtypes = [P, P, I64P]
         _lib.orc_infer_binary.argtypes = [ctypes.c_int, P, P, I32P, I32P, I64P]
         _lib.orc_infer_reduce.argtypes = [ctypes.c_int, P, I64P, ctypes.c_int32, ctypes.c_int, I32P, I32P, I64P]
         _lib.orc_unary_result_dtype.argtypes = [ctypes.c_int, ctypes.c_int]
@@ -262,6 +266,39 @@ def index_select(src, dim, index, out=None):
 def scatter_add_(self, dim, index, src):
     _check(lib().orc_scatter_add(desc(self), dim, desc(index), desc(src)))
     return self
+
+
+def index_add_(self, dim, index, source, alpha=1):
+    af, ai, isint = _scalar(alpha)
+    _check(lib().orc_index_add(desc(self), dim, desc(index), desc(source), af, ai, isint))
+    return self
+
+
+def take(input, index, out=None):
+    if out is None:
+        out = torch.empty(index.shape, dtype=input.dtype)
+    _check(lib().orc_take(desc(out), desc(input), desc(index)))
+    return out
+
+
+def masked_select(x, mask):
+    cap = 1
+    try:
+        for s in torch.broadcast_shapes(x.shape, mask.shape):
+            cap *= s
+    except RuntimeError:
+        pass                      # not broadcastable: the oracle call below reports it
+    out = torch.empty((cap,), dtype=x.dtype)
+    n = ctypes.c_int64()
+    _check(lib().orc_masked_select(desc(out), desc(x), desc(mask), ctypes.byref(n)))
+    return out[:n.value]
+
+
+def nonzero(x):
+    out = torch.empty((x.numel(), x.dim()), dtype=torch.int64)
+    n = ctypes.c_int64()
+    _check(lib().orc_nonzero(desc(out), desc(x), ctypes.byref(n)))
+    return out[:n.value]
 
 
 # --------------------------------------------------------------------------- codec hooks
