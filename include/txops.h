@@ -280,6 +280,44 @@ tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* i
 size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index,
                                       const tx_tensor* src, int deterministic);
 
+/* In place: self[..., index[i], ...] += alpha * source[..., i, ...] along dim.
+ * index is 1-D (or 0-dim) int32 / int64 with source.size(dim) entries in
+ * [0, self.size(dim)); source has self's shape except along dim and self's
+ * dtype (bool is TX_ERR_DTYPE).  alpha as in tx_add (a floating alpha with an
+ * integer dtype is TX_ERR_SCALAR); integers wrap.  Kernels, determinism and
+ * workspace exactly as tx_scatter_add_ with the index broadcast over the other
+ * dims: dim 0 with contiguous rows takes the sorted whole-row path. */
+tx_status tx_index_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source, double alpha_f,
+                        int64_t alpha_i, int alpha_is_int, int deterministic, void* ws, size_t ws_bytes, void* stream);
+size_t tx_index_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source,
+                                    int deterministic);
+
+/* out[p] = input, read as a 1-D tensor in logical (row-major) order whatever
+ * its strides, at index[p]; negative indices count from the end.  out has
+ * index's shape and input's dtype; index is int32 / int64.  Indices outside
+ * [-numel, numel) are not checked on the device (a non-empty index into an
+ * empty input is TX_ERR_INDEX). */
+tx_status tx_take(const tx_tensor* out, const tx_tensor* input, const tx_tensor* index, void* stream);
+
+/* Data-dependent output sizes.  The caller passes `out` as a buffer with room
+ * for `capacity` results and `count`, a one-element int64 device tensor; the
+ * call writes the number of selected elements to `count` and the first
+ * min(count, capacity) results to out, in logical (row-major) order (so
+ * count > capacity tells the caller the buffer was too small; numel of the
+ * input always suffices).  Both need a 4-byte aligned device workspace of
+ * tx_*_workspace_bytes() bytes and handle fewer than 2^31 elements.
+ *   masked_select: the elements of x, broadcast with the bool mask, where the
+ *     mask is true; out is 1-D with x's dtype.
+ *   nonzero: the coordinates of the elements of x that are not zero (-0.0 is
+ *     zero, a NaN is not); out is int64 [capacity, x.ndim]. */
+tx_status tx_masked_select(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x, const tx_tensor* mask,
+                           void* workspace, size_t workspace_bytes, void* stream);
+size_t tx_masked_select_workspace_bytes(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x,
+                                        const tx_tensor* mask);
+tx_status tx_nonzero(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x, void* workspace, size_t workspace_bytes,
+                     void* stream);
+size_t tx_nonzero_workspace_bytes(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_POW). */

@@ -1374,27 +1374,41 @@ int orc_index_add(const orc_tensor* self, int64_t dim, const orc_tensor* index, 
     if (k < 0 || k >= extent) return ORC_ERR_INDEX;      // checked first: nothing is written on error
   }
   const double alpha = alpha_is_int ? (double)alpha_i : alpha_f;
-  // one destination element at a time: its contributions in index order
-  const int64_t nself = numel(self);
-  for (int64_t lin = 0; lin < nself; ++lin) {
+  // walk source in logical order: for one destination element the contributions then arrive in index order
+  const int64_t nself = numel(self), nsrc = numel(source);
+  std::vector<double> acc;
+  std::vector<uint8_t> touched;
+  int64_t lstr[ORC_MAX_DIMS];                          // row-major strides of self's logical shape
+  if (flt) {
+    acc.assign((size_t)nself, 0.0);
+    touched.assign((size_t)nself, 0);
+    int64_t st = 1;
+    for (int d = nd - 1; d >= 0; --d) { lstr[d] = st; st *= self->sizes[d]; }
+  }
+  for (int64_t lin = 0; lin < nsrc; ++lin) {
     int64_t idx[ORC_MAX_DIMS] = {0};
-    unravel(lin, nd, self->sizes, idx);
-    const int64_t d_o = offset_of(self, idx);
-    const int64_t row = nd ? idx[dim] : 0;
-    double acc = 0.0;
-    uint64_t iacc = 0;
-    bool touched = false;
-    for (int64_t i = 0; i < ni; ++i) {
-      if (load_int(index, i * istride) != row) continue;
-      if (nd) idx[dim] = i;
-      const int64_t so = offset_of(source, idx);
-      if (flt) acc += alpha * load_flt(source, so);
-      else iacc += (uint64_t)alpha_i * (uint64_t)load_int(source, so);
-      touched = true;
+    unravel(lin, nd, source->sizes, idx);
+    const int64_t so = offset_of(source, idx);
+    const int64_t i = nd ? idx[dim] : 0;
+    if (nd) idx[dim] = load_int(index, i * istride);
+    if (flt) {
+      int64_t l = 0;
+      for (int d = 0; d < nd; ++d) l += idx[d] * lstr[d];
+      acc[(size_t)l] += alpha * load_flt(source, so);
+      touched[(size_t)l] = 1;
+    } else {
+      const int64_t d_o = offset_of(self, idx);
+      store_int(self, d_o, (int64_t)((uint64_t)load_int(self, d_o) + (uint64_t)alpha_i * (uint64_t)load_int(source, so)));
     }
-    if (!touched) continue;                              // untouched elements keep their bits
-    if (flt) store_flt(self, d_o, load_flt(self, d_o) + acc);
-    else store_int(self, d_o, (int64_t)((uint64_t)load_int(self, d_o) + iacc));
+  }
+  if (flt) {
+    for (int64_t l = 0; l < nself; ++l) {
+      if (!touched[(size_t)l]) continue;               // untouched elements keep their bits
+      int64_t idx[ORC_MAX_DIMS] = {0};
+      unravel(l, nd, self->sizes, idx);
+      const int64_t d_o = offset_of(self, idx);
+      store_flt(self, d_o, load_flt(self, d_o) + acc[(size_t)l]);
+    }
   }
   return ORC_OK;
 }

@@ -31,7 +31,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so
 
 EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
            "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
-           "tx_scatter_add_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
+           "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_take", "tx_masked_select",
+           "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
 
 
@@ -86,6 +87,14 @@ def lib():
         "tx_index_select": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
         "tx_scatter_add_": ([P, ctypes.c_int64, P, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_scatter_add_workspace_bytes": ([P, ctypes.c_int64, P, P, ctypes.c_int], ctypes.c_size_t),
+        "tx_index_add_": ([P, ctypes.c_int64, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, ctypes.c_int, V,
+                           ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_index_add_workspace_bytes": ([P, ctypes.c_int64, P, P, ctypes.c_int], ctypes.c_size_t),
+        "tx_take": ([P, P, P, V], ctypes.c_int32),
+        "tx_masked_select": ([P, P, P, P, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_masked_select_workspace_bytes": ([P, P, P, P], ctypes.c_size_t),
+        "tx_nonzero": ([P, P, P, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_nonzero_workspace_bytes": ([P, P, P], ctypes.c_size_t),
         "tx_infer_binary": ([ctypes.c_int, P, P, I32P, I32P, I64P], ctypes.c_int32),
         "tx_infer_where": ([P, P, I32P], ctypes.c_int32),
         "tx_infer_unary_dtype": ([ctypes.c_int, ctypes.c_int32], ctypes.c_int32),
@@ -182,6 +191,39 @@ def tx_infer_clamp_dtype(dtype, lo=None, hi=None):
                                     hi is not None, _scalar(0 if hi is None else hi)[2])
     _check(rc)
     return CODE_DTYPE[rc]
+
+
+def tx_index_add_workspace_bytes(self, dim, index, source, deterministic=True):
+    return lib().tx_index_add_workspace_bytes(desc(self), dim, desc(index), desc(source), int(deterministic))
+
+
+def tx_index_add_(self, dim, index, source, alpha=1, deterministic=True, ws=None, stream=None):
+    af, ai, isint = _scalar(alpha)
+    p, n = _ws(ws)
+    _check(lib().tx_index_add_(desc(self), dim, desc(index), desc(source), af, ai, isint, int(deterministic), p, n,
+                               _stream(stream)))
+
+
+def tx_take(out, input, index, stream=None):
+    _check(lib().tx_take(desc(out), desc(input), desc(index), _stream(stream)))
+
+
+def tx_masked_select_workspace_bytes(out, count, x, mask):
+    return lib().tx_masked_select_workspace_bytes(desc(out), desc(count), desc(x), desc(mask))
+
+
+def tx_masked_select(out, count, x, mask, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tx_masked_select(desc(out), desc(count), desc(x), desc(mask), p, n, _stream(stream)))
+
+
+def tx_nonzero_workspace_bytes(out, count, x):
+    return lib().tx_nonzero_workspace_bytes(desc(out), desc(count), desc(x))
+
+
+def tx_nonzero(out, count, x, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tx_nonzero(desc(out), desc(count), desc(x), p, n, _stream(stream)))
 
 
 REDUCTION = {"none": 0, "mean": 1, "sum": 2}

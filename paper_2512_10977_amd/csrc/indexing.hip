@@ -52,7 +52,16 @@ struct ElemArgs {
   int64_t istride[TX_MAX_DIMS];    // index strides (index_select: only [dim] is used)
   int64_t sstride[TX_MAX_DIMS];    // source strides
   int64_t dstride[TX_MAX_DIMS];    // destination strides
+  float alpha_f;                   // scatter / index_add: multiplier of the source (floating dtypes)
+  int64_t alpha_i;                 // the same for integer dtypes (wrapping); bool: zero or not
 };
+
+// alpha * v in the arithmetic of T (sums are linear, so the sorted paths scale a whole sum once)
+template <class T, class V> __device__ __forceinline__ V scaled(V v, float alpha_f, int64_t alpha_i) {
+  if constexpr (std::is_same<T, uint8_t>::value) return alpha_i ? v : V(0);
+  else if constexpr (std::is_integral<T>::value) return (V)((unsigned long long)v * (unsigned long long)alpha_i);
+  else return v * (V)alpha_f;
+}
 
 // Each lane handles kGatherU elements (a workgroup covers kGatherU consecutive runs of 256): all index loads
 // are issued first, then all data-dependent source loads, so several random accesses are in flight per lane.
@@ -180,7 +189,7 @@ __global__ __launch_bounds__(kBlock) void scatter_add_atomic_kernel(const ElemAr
   }
   const int64_t k = load_index(a.index, io, a.index_is64);
   d_o += k * a.dstride[a.dim];
-  atomic_accumulate<T>((T*)a.dst + d_o, ((const T*)a.src)[so]);
+  atomic_accumulate<T>((T*)a.dst + d_o, scaled<T, T>(((const T*)a.src)[so], a.alpha_f, a.alpha_i));
 }
 
 // ---------------------------------------------------------------------------
@@ -349,7 +358,7 @@ __global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, 
     acc += cvt<double>(((const T*)a.src)[so]);
   }
   T* dst = (T*)a.dst + k;
-  *dst = cvt<T>((float)(cvt<double>(*dst) + acc));
+  *dst = cvt<T>((float)(cvt<double>(*dst) + (double)a.alpha_f * acc));
 }
 
 constexpr int kChunk = 128;                 // sorted rows per wave
@@ -372,6 +381,8 @@ struct SegRowArgs {
   uint32_t* key_b;               // destination row of the chunk's start piece
   uint32_t* start_list;          // chunks that hold the start piece of a run that goes on
   unsigned int* nstart;          // length of start_list (cleared by row_keys_kernel)
+  float alpha_f;                 // multiplier of every sum (floating dtypes / integer dtypes)
+  int64_t alpha_i;
 };
 
 // Accumulator of a segmented row sum: fp32 for the floating dtypes, wrapping unsigned arithmetic for integers.
@@ -471,7 +482,7 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
           const Vec<Acc, VEC> sum = done_rows[w][i][lane];
           Vec<T, VEC> t;
 #pragma unroll
-          for (int q = 0; q < VEC; ++q) t.v[q] = seg_add<T, Acc>(row[i].v[q], sum.v[q]);
+          for (int q = 0; q < VEC; ++q) t.v[q] = seg_add<T, Acc>(row[i].v[q], scaled<T, Acc>(sum.v[q], a.alpha_f, a.alpha_i));
           if (active) vec_store<T, VEC, true>(self_col + (int64_t)key * a.self_row, t);
         }
       nbuf = 0;
@@ -597,7 +608,7 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
         for (int e = 0; e < VEC; ++e) {
           Acc t = b[e];
           for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
-          d[e] = seg_add<T, Acc>(d[e], t);
+          d[e] = seg_add<T, Acc>(d[e], scaled<T, Acc>(t, a.alpha_f, a.alpha_i));
         }
       }
       __syncthreads();
@@ -689,7 +700,15 @@ tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, c
   return TX_OK;
 }
 
-void fill_scatter_elem_args(ElemArgs* a, const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src) {
+struct Alpha {
+  float f;
+  int64_t i;
+};
+
+void fill_scatter_elem_args(ElemArgs* a, const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src,
+                            Alpha alpha = Alpha{1.0f, 1}) {
+  a->alpha_f = alpha.f;
+  a->alpha_i = alpha.i;
   fill_dims(&a->shape, index->ndim, index->sizes);
   a->dim = dim;
   a->index_is64 = index->dtype == TX_I64;
@@ -730,13 +749,13 @@ tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_bu
 // per source element by plain row sums, and hot destination rows no longer serialise on atomics.
 template <class T>
 tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int dim, const tx_tensor* index,
-                                const tx_tensor* src, char* ws, hipStream_t s) {
+                                const tx_tensor* src, char* ws, hipStream_t s, Alpha alpha) {
   constexpr int V = sizeof(T) == 2 ? 4 : 16 / sizeof(T);     // row kernels: at most 16 bytes of accumulators per lane
   constexpr int kVecBytes = V * (int)sizeof(T);
   uint32_t* keys0 = (uint32_t*)(ws + p.off_keys[0]);
   uint32_t* vals0 = (uint32_t*)(ws + p.off_vals[0]);
   ElemArgs ea;
-  fill_scatter_elem_args(&ea, self, dim, index, src);
+  fill_scatter_elem_args(&ea, self, dim, index, src, alpha);
   const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
   if (p.row_mode)
     hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
@@ -773,6 +792,8 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   a.key_b = (uint32_t*)(ws + p.off_key_b);
   a.start_list = (uint32_t*)(ws + p.off_start_list);
   a.nstart = (unsigned int*)(ws + p.off_counter);
+  a.alpha_f = alpha.f;
+  a.alpha_i = alpha.i;
   const bool al = p.width % V == 0 && (uintptr_t)src->data % kVecBytes == 0 && (uintptr_t)self->data % kVecBytes == 0 &&
                   (a.src_row * (int64_t)sizeof(T)) % kVecBytes == 0 && (a.self_row * (int64_t)sizeof(T)) % kVecBytes == 0;
   const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
@@ -805,6 +826,89 @@ tx_status scatter_checks(const tx_tensor* self, int64_t dim, const tx_tensor* in
   if (!no_internal_overlap(self)) return fail(TX_ERR_OVERLAP, "self has overlapping elements");
   if (partial_overlap(self, src) || partial_overlap(self, index) || (self->data == src->data && numel(src) && numel(self)))
     return fail(TX_ERR_OVERLAP, "self overlaps src or index");
+  return TX_OK;
+}
+
+// shared by scatter_add_ and index_add_ (whose index is presented as a broadcast view): workspace size and dispatch
+size_t scatter_ws_bytes(const tx_tensor* self, int d, const tx_tensor* index, const tx_tensor* src, int deterministic) {
+  if (numel(index) == 0) return 0;
+  const bool int_rows = (self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
+                        index->sizes[0] >= kIntRowModeMin;
+  if (!dtype_is_float(self->dtype) && !int_rows) return 0;
+  if (!deterministic && self->dtype == TX_F32) return 0;
+  ScatterPlan p;
+  if (scatter_plan(self, d, index, src, &p)) return 0;
+  return p.bytes;
+}
+
+tx_status scatter_core(const char* name, const tx_tensor* self, int d, const tx_tensor* index, const tx_tensor* src, Alpha alpha,
+                       int deterministic, void* ws, size_t ws_bytes, hipStream_t s) {
+  tx_status rc;
+  const int64_t n = numel(index);
+  if (n == 0) return TX_OK;
+  // fp16 / bf16 always take the sorted path: 16-bit atomics would round every partial sum to the half type
+  if (dtype_is_float(self->dtype) && (deterministic || self->dtype != TX_F32)) {
+    ScatterPlan p;
+    if ((rc = scatter_plan(self, d, index, src, &p))) return rc;
+    if (!ws || ws_bytes < p.bytes) return fail(TX_ERR_WORKSPACE, "%s needs %zu workspace bytes, got %zu", name, p.bytes, ws_bytes);
+    if ((uintptr_t)ws % 16) return fail(TX_ERR_WORKSPACE, "%s workspace must be 16-byte aligned", name);
+    switch (self->dtype) {
+      case TX_F32: return scatter_deterministic<float>(p, self, d, index, src, (char*)ws, s, alpha);
+      case TX_BF16: return scatter_deterministic<bf16>(p, self, d, index, src, (char*)ws, s, alpha);
+      default: return scatter_deterministic<f16>(p, self, d, index, src, (char*)ws, s, alpha);
+    }
+  }
+  // int32 / int64 with a broadcast row index: group rows by destination first and add whole rows.
+  // Needs the workspace; without it (or for small inputs) fall through to one atomic per element.
+  if ((self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
+      index->sizes[0] >= kIntRowModeMin && strcmp(forced_path(), "scatter-atomic") != 0) {
+    ScatterPlan p;
+    if (!scatter_plan(self, d, index, src, &p) && ws && ws_bytes >= p.bytes && (uintptr_t)ws % 16 == 0) {
+      if (self->dtype == TX_I32) return scatter_deterministic<int32_t>(p, self, d, index, src, (char*)ws, s, alpha);
+      return scatter_deterministic<int64_t>(p, self, d, index, src, (char*)ws, s, alpha);
+    }
+  }
+  if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "%s: more than 2^31 index elements", name);
+  ElemArgs a;
+  fill_scatter_elem_args(&a, self, d, index, src, alpha);
+  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  set_path("scatter-atomic");
+  switch (self->dtype) {
+    case TX_BOOL: hipLaunchKernelGGL((scatter_add_atomic_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a); break;
+    case TX_I32: hipLaunchKernelGGL((scatter_add_atomic_kernel<int32_t>), grid, dim3(kBlock), 0, s, a); break;
+    case TX_I64: hipLaunchKernelGGL((scatter_add_atomic_kernel<int64_t>), grid, dim3(kBlock), 0, s, a); break;
+    default: hipLaunchKernelGGL((scatter_add_atomic_kernel<float>), grid, dim3(kBlock), 0, s, a); break;
+  }
+  return check_launch("scatter_add atomic kernel");
+}
+
+// index_add_: checks, and the 1-D index presented as a view of source's shape (stride 0 off `dim`)
+tx_status index_add_checks(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source, int alpha_is_int,
+                           int* d, tx_tensor* view) {
+  tx_status rc;
+  if ((rc = check_tensor(self, "self")) || (rc = check_tensor(index, "index")) || (rc = check_tensor(source, "source")))
+    return rc;
+  if (!index_dtype_ok(index->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
+  if (self->dtype != source->dtype) return fail(TX_ERR_DTYPE, "index_add_: self and source dtypes differ");
+  if (self->dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "index_add_ does not take bool");
+  if (index->ndim > 1) return fail(TX_ERR_SHAPE, "index_add_: index must be 1-D or 0-dim");
+  if (source->ndim != self->ndim) return fail(TX_ERR_SHAPE, "index_add_: self and source must have the same rank");
+  if ((rc = wrap_dim(dim, self->ndim, d))) return rc;
+  if ((self->ndim ? source->sizes[*d] : 1) != numel(index))
+    return fail(TX_ERR_SHAPE, "index_add_: source.size(dim) must be the number of indices");
+  for (int i = 0; i < self->ndim; ++i)
+    if (i != *d && source->sizes[i] != self->sizes[i]) return fail(TX_ERR_SHAPE, "index_add_: source and self differ in dim %d", i);
+  if (!dtype_is_float(self->dtype) && !alpha_is_int) return fail(TX_ERR_SCALAR, "floating alpha with an integer result");
+  if (!no_internal_overlap(self)) return fail(TX_ERR_OVERLAP, "self has overlapping elements");
+  if (partial_overlap(self, source) || partial_overlap(self, index) || (self->data == source->data && numel(source) && numel(self)))
+    return fail(TX_ERR_OVERLAP, "self overlaps source or index");
+  view->data = index->data;
+  view->dtype = index->dtype;
+  view->ndim = source->ndim;
+  for (int i = 0; i < source->ndim; ++i) {
+    view->sizes[i] = source->sizes[i];
+    view->strides[i] = i == *d ? (index->ndim ? index->strides[0] : 0) : 0;
+  }
   return TX_OK;
 }
 
@@ -955,14 +1059,7 @@ size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const 
                                       int deterministic) {
   int d;
   if (scatter_checks(self, dim, index, src, &d)) return 0;
-  if (numel(index) == 0) return 0;
-  const bool int_rows = (self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
-                        index->sizes[0] >= kIntRowModeMin;
-  if (!dtype_is_float(self->dtype) && !int_rows) return 0;
-  if (!deterministic && self->dtype == TX_F32) return 0;
-  ScatterPlan p;
-  if (scatter_plan(self, d, index, src, &p)) return 0;
-  return p.bytes;
+  return scatter_ws_bytes(self, d, index, src, deterministic);
 }
 
 tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
@@ -971,44 +1068,26 @@ tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* i
   tx_status rc = scatter_checks(self, dim, index, src, &d);
   if (rc) return rc;
   set_path("");
-  const int64_t n = numel(index);
-  if (n == 0) return TX_OK;
-  hipStream_t s = as_stream(stream);
-  // fp16 / bf16 always take the sorted path: 16-bit atomics would round every partial sum to the half type
-  if (dtype_is_float(self->dtype) && (deterministic || self->dtype != TX_F32)) {
-    ScatterPlan p;
-    if ((rc = scatter_plan(self, d, index, src, &p))) return rc;
-    if (!ws || ws_bytes < p.bytes)
-      return fail(TX_ERR_WORKSPACE, "scatter_add_ needs %zu workspace bytes, got %zu", p.bytes, ws_bytes);
-    if ((uintptr_t)ws % 16) return fail(TX_ERR_WORKSPACE, "scatter_add_ workspace must be 16-byte aligned");
-    switch (self->dtype) {
-      case TX_F32: return scatter_deterministic<float>(p, self, d, index, src, (char*)ws, s);
-      case TX_BF16: return scatter_deterministic<bf16>(p, self, d, index, src, (char*)ws, s);
-      default: return scatter_deterministic<f16>(p, self, d, index, src, (char*)ws, s);
-    }
-  }
-  // int32 / int64 with a broadcast row index: group rows by destination first and add whole rows.
-  // Needs the workspace; without it (or for small inputs) fall through to one atomic per element.
-  if ((self->dtype == TX_I32 || self->dtype == TX_I64) && is_row_mode(self, d, index, src) &&
-      index->sizes[0] >= kIntRowModeMin && strcmp(forced_path(), "scatter-atomic") != 0) {
-    ScatterPlan p;
-    if (!scatter_plan(self, d, index, src, &p) && ws && ws_bytes >= p.bytes && (uintptr_t)ws % 16 == 0) {
-      if (self->dtype == TX_I32) return scatter_deterministic<int32_t>(p, self, d, index, src, (char*)ws, s);
-      return scatter_deterministic<int64_t>(p, self, d, index, src, (char*)ws, s);
-    }
-  }
-  if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "scatter_add_: more than 2^31 index elements");
-  ElemArgs a;
-  fill_scatter_elem_args(&a, self, d, index, src);
-  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
-  set_path("scatter-atomic");
-  switch (self->dtype) {
-    case TX_BOOL: hipLaunchKernelGGL((scatter_add_atomic_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a); break;
-    case TX_I32: hipLaunchKernelGGL((scatter_add_atomic_kernel<int32_t>), grid, dim3(kBlock), 0, s, a); break;
-    case TX_I64: hipLaunchKernelGGL((scatter_add_atomic_kernel<int64_t>), grid, dim3(kBlock), 0, s, a); break;
-    default: hipLaunchKernelGGL((scatter_add_atomic_kernel<float>), grid, dim3(kBlock), 0, s, a); break;
-  }
-  return check_launch("scatter_add atomic kernel");
+  return scatter_core("scatter_add_", self, d, index, src, Alpha{1.0f, 1}, deterministic, ws, ws_bytes, as_stream(stream));
+}
+
+size_t tx_index_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source,
+                                    int deterministic) {
+  int d;
+  tx_tensor view;
+  if (index_add_checks(self, dim, index, source, 1, &d, &view)) return 0;
+  return scatter_ws_bytes(self, d, &view, source, deterministic);
+}
+
+tx_status tx_index_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source, double alpha_f,
+                        int64_t alpha_i, int alpha_is_int, int deterministic, void* ws, size_t ws_bytes, void* stream) {
+  int d;
+  tx_tensor view;
+  tx_status rc = index_add_checks(self, dim, index, source, alpha_is_int, &d, &view);
+  if (rc) return rc;
+  set_path("");
+  const Alpha alpha{(float)(alpha_is_int ? (double)alpha_i : alpha_f), alpha_is_int ? alpha_i : 0};
+  return scatter_core("index_add_", self, d, &view, source, alpha, deterministic, ws, ws_bytes, as_stream(stream));
 }
 
 }  // extern "C"

@@ -1,0 +1,455 @@
+// take, masked_select and nonzero.
+//
+// take: one lane per output element; the flat index is wrapped and, for a
+//   non-contiguous input, decomposed into the input's coordinates.
+// masked_select / nonzero: stream compaction in three launches.  The logical
+//   index space is cut into tiles of 4096 elements (a 256-lane workgroup; each
+//   wave owns 1024 consecutive elements as 16 slabs of 64).
+//     count  : every workgroup counts its selected elements (ballot + popcount).
+//     offsets: one workgroup turns the counts into exclusive offsets in place
+//              and writes the total to the caller's count tensor.
+//     write  : every workgroup recomputes its flags; a lane's destination is
+//              tile offset + selected elements in earlier waves + earlier
+//              slabs + lower lanes of its slab, so the output keeps the
+//              logical (row-major) order.
+#include <cstring>
+
+#include "common.h"
+
+namespace tx {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / kWave;
+constexpr int kSlabs = 16;                           // slabs of 64 elements per wave
+constexpr int kTile = kBlock * kSlabs;               // 4096 elements per workgroup
+constexpr int kScanBlock = 1024;
+
+struct Dims {
+  int n;
+  FastDiv div[TX_MAX_DIMS];
+  int64_t numel;
+};
+
+void fill_dims(Dims* d, int nd, const int64_t* sizes) {
+  d->n = nd;
+  d->numel = 1;
+  for (int i = 0; i < nd; ++i) {
+    d->div[i] = FastDiv((uint32_t)std::min<int64_t>(std::max<int64_t>(sizes[i], 1), 0x7fffffff));
+    d->numel *= sizes[i];
+  }
+}
+
+__device__ __forceinline__ int64_t load_index(const char* p, int64_t off, int is64) {
+  return is64 ? ((const int64_t*)p)[off] : (int64_t)((const int32_t*)p)[off];
+}
+
+// ---------------------------------------------------------------------------
+// take
+// ---------------------------------------------------------------------------
+struct TakeArgs {
+  Dims shape;                        // index's (= out's) shape
+  Dims in_shape;                     // input's shape (used when the input is not contiguous)
+  int64_t istride[TX_MAX_DIMS], ostride[TX_MAX_DIMS], sstride[TX_MAX_DIMS];
+  const char* index;
+  const char* src;
+  char* dst;
+  int64_t in_numel;
+  int index_is64, contiguous;
+};
+
+constexpr int kTakeU = 4;
+template <class B>
+__global__ __launch_bounds__(kBlock) void take_kernel(const TakeArgs a) {
+  int64_t so[kTakeU], d_o[kTakeU];
+  bool live[kTakeU];
+#pragma unroll
+  for (int u = 0; u < kTakeU; ++u) {
+    const int64_t lin = ((int64_t)blockIdx.x * kTakeU + u) * kBlock + threadIdx.x;
+    live[u] = lin < a.shape.numel;
+    so[u] = d_o[u] = 0;
+    if (!live[u]) continue;
+    int64_t io = 0;
+    uint32_t rem = (uint32_t)lin;
+    for (int d = a.shape.n - 1; d >= 0; --d) {
+      uint32_t q, m;
+      a.shape.div[d].divmod(rem, q, m);
+      rem = q;
+      io += (int64_t)m * a.istride[d];
+      d_o[u] += (int64_t)m * a.ostride[d];
+    }
+    int64_t k = load_index(a.index, io, a.index_is64);
+    k += k < 0 ? a.in_numel : 0;
+    if (a.contiguous) {
+      so[u] = k;
+    } else {
+      uint32_t r2 = (uint32_t)k;
+      for (int d = a.in_shape.n - 1; d >= 0; --d) {
+        uint32_t q, m;
+        a.in_shape.div[d].divmod(r2, q, m);
+        r2 = q;
+        so[u] += (int64_t)m * a.sstride[d];
+      }
+    }
+  }
+  B v[kTakeU];
+#pragma unroll
+  for (int u = 0; u < kTakeU; ++u)
+    if (live[u]) v[u] = ((const B*)a.src)[so[u]];
+#pragma unroll
+  for (int u = 0; u < kTakeU; ++u)
+    if (live[u]) ((B*)a.dst)[d_o[u]] = v[u];
+}
+
+// ---------------------------------------------------------------------------
+// compaction
+// ---------------------------------------------------------------------------
+struct SelectArgs {
+  Dims shape;                        // logical (broadcast) shape that is walked in row-major order
+  int64_t fstride[TX_MAX_DIMS];      // strides of the tensor the flags come from (mask, or x for nonzero)
+  int64_t pstride[TX_MAX_DIMS];      // masked_select: strides of x
+  const char* flag;
+  const char* payload;
+  char* out;
+  int64_t ostride0, ostride1;        // out strides in elements
+  int64_t capacity;                  // rows of out
+  uint32_t* offsets;                 // per tile: count, then exclusive offset
+  int64_t* count;
+  int64_t ntiles;
+  unsigned long long zmask;          // nonzero: bits of an element that must not all be zero
+  int contiguous;                    // flags (and payload) can be addressed by the linear index
+};
+
+template <int ES> struct Raw;
+template <> struct Raw<1> { using type = uint8_t; };
+template <> struct Raw<2> { using type = uint16_t; };
+template <> struct Raw<4> { using type = uint32_t; };
+template <> struct Raw<8> { using type = unsigned long long; };
+
+// offset of logical element lin in the flag tensor (and in the payload tensor)
+__device__ __forceinline__ void select_offsets(const SelectArgs& a, int64_t lin, int64_t* fo, int64_t* po) {
+  if (a.contiguous) { *fo = lin; *po = lin; return; }
+  int64_t f = 0, p = 0;
+  uint32_t rem = (uint32_t)lin;
+  for (int d = a.shape.n - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.shape.div[d].divmod(rem, q, m);
+    rem = q;
+    f += (int64_t)m * a.fstride[d];
+    p += (int64_t)m * a.pstride[d];
+  }
+  *fo = f;
+  *po = p;
+}
+
+// flags of the wave's 16 slabs as ballots.  FES: bytes per flag element.
+template <int FES>
+__device__ __forceinline__ void slab_ballots(const SelectArgs& a, int64_t wave_base, int lane, unsigned long long (&bal)[kSlabs],
+                                             int64_t (&poff)[kSlabs]) {
+  using F = typename Raw<FES>::type;
+  F raw[kSlabs];
+#pragma unroll
+  for (int s = 0; s < kSlabs; ++s) {
+    const int64_t lin = wave_base + s * kWave + lane;
+    int64_t fo;
+    select_offsets(a, lin < a.shape.numel ? lin : a.shape.numel - 1, &fo, &poff[s]);    // clamped: unconditional load
+    raw[s] = ((const F*)a.flag)[fo];
+  }
+#pragma unroll
+  for (int s = 0; s < kSlabs; ++s) {
+    const int64_t lin = wave_base + s * kWave + lane;
+    const bool on = lin < a.shape.numel && ((unsigned long long)raw[s] & a.zmask) != 0;
+    bal[s] = __ballot(on);
+  }
+}
+
+template <int FES>
+__global__ __launch_bounds__(kBlock) void select_count_kernel(const SelectArgs a) {
+  __shared__ uint32_t wave_count[kWaves];
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t wave_base = (int64_t)blockIdx.x * kTile + (int64_t)w * (kSlabs * kWave);
+  unsigned long long bal[kSlabs];
+  int64_t poff[kSlabs];
+  slab_ballots<FES>(a, wave_base, lane, bal, poff);
+  uint32_t c = 0;
+#pragma unroll
+  for (int s = 0; s < kSlabs; ++s) c += (uint32_t)__popcll(bal[s]);
+  if (lane == 0) wave_count[w] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t t = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) t += wave_count[i];
+    a.offsets[blockIdx.x] = t;
+  }
+}
+
+// counts -> exclusive offsets in place; total -> *count.  One workgroup.
+__global__ __launch_bounds__(kScanBlock) void select_offsets_kernel(uint32_t* counts, int64_t n, int64_t* total) {
+  __shared__ uint32_t wave_tot[kScanBlock / kWave];
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < n; base += kScanBlock) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t v = i < n ? counts[i] : 0u;
+    uint32_t incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const uint32_t up = shfl_up(incl, d);
+      if (lane >= d) incl += up;
+    }
+    if (lane == kWave - 1) wave_tot[w] = incl;
+    __syncthreads();
+    uint32_t before = carry, all = carry;
+#pragma unroll
+    for (int k = 0; k < kScanBlock / kWave; ++k) {
+      if (k == w) before = all;
+      all += wave_tot[k];
+    }
+    if (i < n) counts[i] = before + incl - v;
+    carry = all;
+    __syncthreads();                        // wave_tot is rewritten by the next chunk
+  }
+  if (threadIdx.x == 0) *total = (int64_t)carry;
+}
+
+// NONZERO = false: copy the payload element (PES bytes); true: write the coordinates as int64
+template <int FES, int PES, bool NONZERO>
+__global__ __launch_bounds__(kBlock) void select_write_kernel(const SelectArgs a) {
+  __shared__ uint32_t wave_count[kWaves];
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t wave_base = (int64_t)blockIdx.x * kTile + (int64_t)w * (kSlabs * kWave);
+  unsigned long long bal[kSlabs];
+  int64_t poff[kSlabs];
+  slab_ballots<FES>(a, wave_base, lane, bal, poff);
+  uint32_t c = 0;
+#pragma unroll
+  for (int s = 0; s < kSlabs; ++s) c += (uint32_t)__popcll(bal[s]);
+  if (lane == 0) wave_count[w] = c;
+  __syncthreads();
+  int64_t pos = a.offsets[blockIdx.x];
+  for (int i = 0; i < w; ++i) pos += wave_count[i];
+  const unsigned long long below = (1ull << lane) - 1ull;
+  using P = typename Raw<PES>::type;
+#pragma unroll
+  for (int s = 0; s < kSlabs; ++s) {
+    if (bal[s] == 0) continue;                                       // wave-uniform
+    const bool on = (bal[s] >> lane) & 1ull;
+    const int64_t dst = pos + __popcll(bal[s] & below);
+    if (on && dst < a.capacity) {
+      if constexpr (NONZERO) {
+        uint32_t rem = (uint32_t)(wave_base + s * kWave + lane);
+        int64_t* row = (int64_t*)a.out + dst * a.ostride0;
+        for (int d = a.shape.n - 1; d >= 0; --d) {
+          uint32_t q, m;
+          a.shape.div[d].divmod(rem, q, m);
+          rem = q;
+          row[d * a.ostride1] = (int64_t)m;
+        }
+      } else {
+        ((P*)a.out)[dst * a.ostride0] = ((const P*)a.payload)[poff[s]];
+      }
+    }
+    pos += __popcll(bal[s]);
+  }
+}
+
+template <int FES, int PES, bool NONZERO>
+tx_status run_select(SelectArgs& a, void* ws, hipStream_t stream) {
+  a.offsets = (uint32_t*)ws;
+  if (a.shape.numel > 0) {
+    hipLaunchKernelGGL((select_count_kernel<FES>), dim3((unsigned)a.ntiles), dim3(kBlock), 0, stream, a);
+  }
+  hipLaunchKernelGGL(select_offsets_kernel, dim3(1), dim3(kScanBlock), 0, stream, a.offsets, a.ntiles, a.count);
+  if (a.shape.numel > 0) {
+    hipLaunchKernelGGL((select_write_kernel<FES, PES, NONZERO>), dim3((unsigned)a.ntiles), dim3(kBlock), 0, stream, a);
+  }
+  return check_launch("compaction kernels");
+}
+
+bool row_major(const tx_tensor* t) {
+  int64_t expect = 1;
+  for (int d = t->ndim - 1; d >= 0; --d) {
+    if (t->sizes[d] != 1 && t->strides[d] != expect) return false;
+    expect *= t->sizes[d];
+  }
+  return true;
+}
+
+tx_status count_checks(const tx_tensor* count) {
+  tx_status rc;
+  if ((rc = check_tensor(count, "count"))) return rc;
+  if (count->dtype != TX_I64) return fail(TX_ERR_DTYPE, "count must be int64");
+  if (numel(count) != 1) return fail(TX_ERR_SHAPE, "count must hold one element");
+  return TX_OK;
+}
+
+tx_status ws_checks(const char* name, void* ws, size_t ws_bytes, size_t need) {
+  if (!ws || ws_bytes < need) return fail(TX_ERR_WORKSPACE, "%s needs %zu workspace bytes, got %zu", name, need, ws_bytes);
+  if ((uintptr_t)ws % 4) return fail(TX_ERR_WORKSPACE, "%s workspace must be 4-byte aligned", name);
+  return TX_OK;
+}
+
+size_t select_ws_bytes(int64_t n) { return (size_t)((n + kTile - 1) / kTile + 1) * sizeof(uint32_t); }
+
+tx_status masked_select_checks(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x, const tx_tensor* mask, int* nd,
+                               int64_t* shape) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(x, "x")) || (rc = check_tensor(mask, "mask")) ||
+      (rc = count_checks(count)))
+    return rc;
+  if (mask->dtype != TX_BOOL) return fail(TX_ERR_DTYPE, "masked_select: mask must be bool");
+  if (out->dtype != x->dtype) return fail(TX_ERR_DTYPE, "masked_select: out must have x's dtype");
+  if (out->ndim != 1) return fail(TX_ERR_SHAPE, "masked_select: out is a 1-D buffer");
+  const tx_tensor* ins[2] = {x, mask};
+  if ((rc = broadcast_shapes(ins, 2, nd, shape))) return rc;
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  for (const tx_tensor* in : {x, mask, count})
+    if (numel(out) && numel(in) && (partial_overlap(out, in) || out->data == in->data))
+      return fail(TX_ERR_OVERLAP, "masked_select: out overlaps an input");
+  return TX_OK;
+}
+
+tx_status nonzero_checks(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(x, "x")) || (rc = count_checks(count))) return rc;
+  if (out->dtype != TX_I64) return fail(TX_ERR_DTYPE, "nonzero: out must be int64");
+  if (out->ndim != 2 || out->sizes[1] != x->ndim) return fail(TX_ERR_SHAPE, "nonzero: out must be [capacity, x.ndim]");
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  for (const tx_tensor* in : {x, count})
+    if (numel(out) && numel(in) && (partial_overlap(out, in) || out->data == in->data))
+      return fail(TX_ERR_OVERLAP, "nonzero: out overlaps an input");
+  return TX_OK;
+}
+
+}  // namespace
+}  // namespace tx
+
+using namespace tx;
+
+extern "C" {
+
+tx_status tx_take(const tx_tensor* out, const tx_tensor* input, const tx_tensor* index, void* stream) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(input, "input")) || (rc = check_tensor(index, "index"))) return rc;
+  if (index->dtype != TX_I32 && index->dtype != TX_I64) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
+  if (out->dtype != input->dtype) return fail(TX_ERR_DTYPE, "take: out must have input's dtype");
+  if (!same_sizes(out, index->ndim, index->sizes)) return fail(TX_ERR_SHAPE, "take: out must have index's shape");
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  if (numel(out) && ((numel(input) && (partial_overlap(out, input) || out->data == input->data)) || partial_overlap(out, index) ||
+                     out->data == index->data))
+    return fail(TX_ERR_OVERLAP, "take: out overlaps an input");
+  set_path("");
+  const int64_t n = numel(out);
+  if (n == 0) return TX_OK;
+  if (numel(input) == 0) return fail(TX_ERR_INDEX, "take: index into an empty tensor");
+  if (n >= (1ll << 31) || numel(input) >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "take: more than 2^31 elements");
+  TakeArgs a;
+  memset(&a, 0, sizeof(a));
+  fill_dims(&a.shape, index->ndim, index->sizes);
+  fill_dims(&a.in_shape, input->ndim, input->sizes);
+  for (int d = 0; d < index->ndim; ++d) {
+    a.istride[d] = index->strides[d];
+    a.ostride[d] = out->strides[d];
+  }
+  for (int d = 0; d < input->ndim; ++d) a.sstride[d] = input->strides[d];
+  a.index = (const char*)index->data;
+  a.src = (const char*)input->data;
+  a.dst = (char*)out->data;
+  a.in_numel = numel(input);
+  a.index_is64 = index->dtype == TX_I64;
+  a.contiguous = row_major(input);
+  const dim3 grid((unsigned)((n + kBlock * kTakeU - 1) / (kBlock * kTakeU)));
+  hipStream_t s = as_stream(stream);
+  set_path(a.contiguous ? "take" : "take-strided");
+  switch (dtype_size(input->dtype)) {
+    case 1: hipLaunchKernelGGL((take_kernel<uint8_t>), grid, dim3(kBlock), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((take_kernel<uint16_t>), grid, dim3(kBlock), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((take_kernel<uint32_t>), grid, dim3(kBlock), 0, s, a); break;
+    default: hipLaunchKernelGGL((take_kernel<uint64_t>), grid, dim3(kBlock), 0, s, a); break;
+  }
+  return check_launch("take kernel");
+}
+
+size_t tx_masked_select_workspace_bytes(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x, const tx_tensor* mask) {
+  int nd;
+  int64_t shape[TX_MAX_DIMS];
+  if (masked_select_checks(out, count, x, mask, &nd, shape)) return 0;
+  int64_t n = 1;
+  for (int d = 0; d < nd; ++d) n *= shape[d];
+  return select_ws_bytes(n);
+}
+
+tx_status tx_masked_select(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x, const tx_tensor* mask,
+                           void* workspace, size_t workspace_bytes, void* stream) {
+  int nd;
+  int64_t shape[TX_MAX_DIMS];
+  tx_status rc = masked_select_checks(out, count, x, mask, &nd, shape);
+  if (rc) return rc;
+  set_path("");
+  SelectArgs a;
+  memset(&a, 0, sizeof(a));
+  fill_dims(&a.shape, nd, shape);
+  if (a.shape.numel >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "masked_select: more than 2^31 elements");
+  if ((rc = ws_checks("masked_select", workspace, workspace_bytes, select_ws_bytes(a.shape.numel)))) return rc;
+  for (int d = 0; d < nd; ++d) {
+    const int dm = d - (nd - mask->ndim), dx = d - (nd - x->ndim);
+    a.fstride[d] = dm >= 0 && mask->sizes[dm] != 1 ? mask->strides[dm] : 0;
+    a.pstride[d] = dx >= 0 && x->sizes[dx] != 1 ? x->strides[dx] : 0;
+  }
+  a.flag = (const char*)mask->data;
+  a.payload = (const char*)x->data;
+  a.out = (char*)out->data;
+  a.ostride0 = out->strides[0];
+  a.capacity = out->sizes[0];
+  a.count = (int64_t*)count->data;
+  a.ntiles = (a.shape.numel + kTile - 1) / kTile;
+  a.zmask = 0xffull;
+  a.contiguous = same_sizes(x, nd, shape) && same_sizes(mask, nd, shape) && row_major(x) && row_major(mask);
+  hipStream_t s = as_stream(stream);
+  set_path(a.contiguous ? "select" : "select-strided");
+  switch (dtype_size(x->dtype)) {
+    case 1: return run_select<1, 1, false>(a, workspace, s);
+    case 2: return run_select<1, 2, false>(a, workspace, s);
+    case 4: return run_select<1, 4, false>(a, workspace, s);
+    default: return run_select<1, 8, false>(a, workspace, s);
+  }
+}
+
+size_t tx_nonzero_workspace_bytes(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x) {
+  if (nonzero_checks(out, count, x)) return 0;
+  return select_ws_bytes(numel(x));
+}
+
+tx_status tx_nonzero(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x, void* workspace, size_t workspace_bytes,
+                     void* stream) {
+  tx_status rc = nonzero_checks(out, count, x);
+  if (rc) return rc;
+  set_path("");
+  SelectArgs a;
+  memset(&a, 0, sizeof(a));
+  fill_dims(&a.shape, x->ndim, x->sizes);
+  if (a.shape.numel >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "nonzero: more than 2^31 elements");
+  if ((rc = ws_checks("nonzero", workspace, workspace_bytes, select_ws_bytes(a.shape.numel)))) return rc;
+  for (int d = 0; d < x->ndim; ++d) a.fstride[d] = x->strides[d];
+  a.flag = (const char*)x->data;
+  a.out = (char*)out->data;
+  a.ostride0 = out->strides[0];
+  a.ostride1 = out->strides[1];
+  a.capacity = out->sizes[0];
+  a.count = (int64_t*)count->data;
+  a.ntiles = (a.shape.numel + kTile - 1) / kTile;
+  // floats: every bit but the sign (so -0.0 is zero and a NaN is not); integers and bool: every bit
+  a.zmask = x->dtype == TX_F32 ? 0x7fffffffull : dtype_is_float(x->dtype) ? 0x7fffull : ~0ull;
+  a.contiguous = row_major(x);
+  hipStream_t s = as_stream(stream);
+  set_path(a.contiguous ? "select" : "select-strided");
+  switch (dtype_size(x->dtype)) {
+    case 1: return run_select<1, 8, true>(a, workspace, s);
+    case 2: return run_select<2, 8, true>(a, workspace, s);
+    case 4: return run_select<4, 8, true>(a, workspace, s);
+    default: return run_select<8, 8, true>(a, workspace, s);
+  }
+}
+
+}  // extern "C"

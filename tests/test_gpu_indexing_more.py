@@ -1,0 +1,231 @@
+"""GPU parity: index_add_, take, masked_select, nonzero (HIP library through the C ABI) vs. the CPU oracle.
+
+index_add_ on floating dtypes is held to rel 1e-5 (fp32) / 1e-2 (half) of max(|oracle|, scale) with scale the root
+of the sum of squares of everything that lands on an element; everything else is bit-exact.
+"""
+import itertools
+
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2512_10977_amd import binding as B
+from paper_2512_10977_amd import inputs as I
+from tests.parity import assert_exact, assert_rel, to_device_view
+
+pytestmark = pytest.mark.gpu
+F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
+ALL = [F32, BF16, F16, I32, I64, BOOL]
+
+
+def index_add_scale(self_cpu, dim, idx_cpu, src_cpu, alpha):
+    s2 = self_cpu.double() ** 2
+    s2.index_add_(dim, idx_cpu.long().reshape(-1), (src_cpu.double() * float(alpha)) ** 2)
+    return s2.sqrt()
+
+
+def check_index_add(self_cpu, dim, idx_cpu, src_cpu, alpha=1, deterministic=True, what=""):
+    want = O.index_add_(self_cpu.clone(), dim, idx_cpu, src_cpu, alpha)
+    dst = to_device_view(self_cpu).clone() if self_cpu.is_contiguous() else to_device_view(self_cpu)
+    idx, src = to_device_view(idx_cpu), to_device_view(src_cpu)
+    nbytes = B.tx_index_add_workspace_bytes(dst, dim, idx, src, deterministic)
+    ws = B.workspace(nbytes) if nbytes else None
+    B.tx_index_add_(dst, dim, idx, src, alpha, deterministic, ws)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    what = "index_add %s self%s n=%d dim=%d alpha=%r %s [%s]" % (self_cpu.dtype, tuple(self_cpu.shape), idx_cpu.numel(), dim,
+                                                               alpha, what, used)
+    if not self_cpu.dtype.is_floating_point:
+        assert_exact(dst, want, what)
+    else:
+        assert_rel(dst, want, 1e-5 if self_cpu.dtype == F32 else 1e-2, index_add_scale(self_cpu, dim, idx_cpu, src_cpu, alpha), what)
+    return used
+
+
+def test_index_add_sweep():
+    g = torch.Generator().manual_seed(400)
+    for dt in (F32, BF16, F16, I32, I64):
+        for shape, dim, n in [((50, 64), 0, 300), ((50, 64), 1, 40), ((6, 20, 48), 1, 77), ((6, 20, 48), -1, 9), ((33,), 0, 100),
+                              ((40, 7), 0, 5), ((5000, 32), 0, 9000)]:
+            s = I.typed(shape, dt, seed=401)
+            sshape = list(shape)
+            sshape[dim] = n
+            src = I.typed(tuple(sshape), dt, seed=402)
+            idx = torch.randint(0, shape[dim], (n,), generator=g)
+            for alpha in ((1, -3) if not dt.is_floating_point else (1, 0.375, -2)):
+                check_index_add(s, dim, idx, src, alpha)
+            check_index_add(s, dim, idx.to(I32), src, what="int32 index")
+        # views: strided self rows, strided source, strided index
+        s = I.typed((50, 128), dt, seed=403)
+        src = I.typed((60, 128), dt, seed=404)
+        idx = torch.randint(0, 25, (120,), generator=g)
+        check_index_add(s[::2], 0, idx[::2], src, what="strided self, index")
+        check_index_add(s[:, ::2], 0, idx[:60], src[:, ::2], what="strided columns")
+        check_index_add(torch.tensor(2, dtype=dt), 0, torch.tensor([0]), torch.tensor(3, dtype=dt), 2, what="0-dim")
+        check_index_add(s, 0, torch.zeros((0,), dtype=I64), src[:0], what="no indices")
+    # fp32 atomics (not reproducible, same tolerance)
+    s, src = I.typed((64, 256), F32, seed=405), I.typed((5000, 256), F32, seed=406)
+    assert check_index_add(s, 0, torch.randint(0, 64, (5000,), generator=g), src, 0.5, deterministic=False) == "scatter-atomic"
+
+
+def test_index_add_full_size_rows_and_errors():
+    rows = I.zipf_rows(1 << 20, 65536, 1.1, seed=4)
+    for dt, alpha in ((F32, 1), (F32, 0.5), (I32, -3), (BF16, 1)):
+        s = I.typed((65536, 256), dt, seed=407)
+        src = I.typed((1 << 20, 256), dt, seed=408)
+        assert check_index_add(s, 0, rows, src, alpha) == "scatter-sort-rows"
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    ix = lambda *v: torch.tensor(v, device="cuda")
+    for args, kind in (((d(4, 3), 0, ix(0, 1), d(3, 3)), "SHAPE"), ((d(4, 3), 0, ix(0, 1), d(2, 4)), "SHAPE"),
+                       ((d(4, 3), 2, ix(0, 1), d(2, 3)), "DIM"), ((d(4, 3), 0, ix(0.0, 1.0), d(2, 3)), "DTYPE"),
+                       ((d(4, 3, dt=BOOL), 0, ix(0, 1), d(2, 3, dt=BOOL)), "DTYPE"), ((d(4, 3), 0, ix(0, 1), d(2, 3, dt=BF16)), "DTYPE"),
+                       ((d(4, 3), 0, ix(0, 1).view(1, 2), d(2, 3)), "SHAPE"), ((d(4, 3, dt=I64), 0, ix(0, 1), d(2, 3, dt=I64), 0.5), "SCALAR")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_index_add_(*args)
+        assert e.value.kind == kind, (kind, e.value.kind)
+    with pytest.raises(B.TxError) as e:
+        B.tx_index_add_(d(40, 64), 0, ix(0, 1), d(2, 64), 1, True, None)
+    assert e.value.kind == "WORKSPACE"
+
+
+def check_take(x_cpu, idx_cpu, out_like=None, what=""):
+    want = O.take(x_cpu, idx_cpu)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda") if out_like is None else to_device_view(out_like)
+    B.tx_take(out, to_device_view(x_cpu), to_device_view(idx_cpu))
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    assert_exact(out, want, "take %s %s idx%s %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), tuple(idx_cpu.shape), what, used))
+    return used
+
+
+def test_take_sweep():
+    g = torch.Generator().manual_seed(410)
+    for dt in ALL:
+        x = I.typed((7, 13, 5), dt, seed=411) if dt != BOOL else I.booleans((7, 13, 5), 0.5, seed=411)
+        n = x.numel()
+        idx = torch.randint(-n, n, (9, 31), generator=g)
+        assert check_take(x, idx) == "take"
+        check_take(x, idx.to(I32), what="int32 index")
+        assert check_take(x.permute(2, 0, 1), idx, what="permuted") == "take-strided"
+        assert check_take(x[:, ::2, 1:4], torch.randint(-63, 63, (50,), generator=g), what="sliced") == "take-strided"
+        check_take(x, idx.t(), what="strided index")
+        check_take(x, idx, out_like=torch.empty((31, 9), dtype=dt).t(), what="strided out")
+        check_take(x, torch.zeros((0, 4), dtype=I64), what="empty index")
+        check_take(torch.tensor(3, dtype=I64).to(dt), torch.tensor([0, -1, 0]), what="0-dim input")
+        check_take(x, torch.tensor(-1), what="0-dim index")
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    for args, kind in (((d(3), d(5), d(3)), "DTYPE"), ((d(3, dt=I32), d(5), d(3, dt=I64)), "DTYPE"), ((d(4), d(5), d(3, dt=I64)), "SHAPE"),
+                       ((d(3), d(0), d(3, dt=I64)), "INDEX")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_take(*args)
+        assert e.value.kind == kind, (kind, e.value.kind)
+
+
+def test_take_full_size():
+    x = I.typed((8192, 8192), F32, seed=412)
+    idx = torch.randint(-x.numel(), x.numel(), (4096, 4096), generator=torch.Generator().manual_seed(413))
+    assert check_take(x, idx) == "take"
+    assert check_take(x.t(), idx[:1024], what="transposed input") == "take-strided"
+
+
+def run_select(fn_bytes, fn, out, what):
+    count = torch.full((1,), -7, dtype=I64, device="cuda")
+    ws = B.workspace(fn_bytes(out, count))
+    fn(out, count, ws)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    return int(count.item()), used
+
+
+def check_masked_select(x_cpu, m_cpu, capacity=None, what=""):
+    want = O.masked_select(x_cpu, m_cpu)
+    x, m = to_device_view(x_cpu), to_device_view(m_cpu)
+    total = 1
+    for s in torch.broadcast_shapes(x_cpu.shape, m_cpu.shape):
+        total *= s
+    cap = total if capacity is None else capacity
+    out = torch.full((cap + 3,), 0, dtype=x_cpu.dtype, device="cuda")[:cap]       # a guard zone after the buffer
+    guard = out.storage_offset()
+    n, used = run_select(lambda o, c: B.tx_masked_select_workspace_bytes(o, c, x, m), lambda o, c, ws: B.tx_masked_select(o, c, x, m, ws),
+                         out, what)
+    what = "masked_select %s x%s mask%s %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), tuple(m_cpu.shape), what, used)
+    assert n == want.numel(), (what, n, want.numel())
+    k = min(n, cap)
+    assert_exact(out[:k], want[:k], what)
+    return used
+
+
+def check_nonzero(x_cpu, capacity=None, what=""):
+    want = O.nonzero(x_cpu)
+    x = to_device_view(x_cpu)
+    cap = x_cpu.numel() if capacity is None else capacity
+    out = torch.full((cap, x_cpu.dim()), -1, dtype=I64, device="cuda")
+    n, used = run_select(lambda o, c: B.tx_nonzero_workspace_bytes(o, c, x), lambda o, c, ws: B.tx_nonzero(o, c, x, ws), out, what)
+    what = "nonzero %s %s %s [%s]" % (x_cpu.dtype, tuple(x_cpu.shape), what, used)
+    assert n == want.shape[0], (what, n, want.shape[0])
+    k = min(n, cap)
+    assert_exact(out[:k], want[:k], what)
+    if cap > k:
+        assert (out[k:] == -1).all(), what + ": rows past the count were written"
+    return used
+
+
+def test_masked_select_sweep():
+    for dt in ALL:
+        for shape in [(7, 13, 5), (4096,), (4097,), (3, 5000), (1,), ()]:
+            x = I.typed(shape, dt, seed=420) if dt != BOOL else I.booleans(shape, 0.5, seed=420)
+            for p in (0.0, 0.03, 0.5, 1.0):
+                m = I.bernoulli_mask(shape, p, seed=421)
+                assert check_masked_select(x, m, what="p=%g" % p) == "select"
+        x = I.typed((6, 50, 7), dt, seed=422) if dt != BOOL else I.booleans((6, 50, 7), 0.5, seed=422)
+        m = I.bernoulli_mask((6, 50, 7), 0.3, seed=423)
+        assert check_masked_select(x.permute(2, 0, 1), m.permute(2, 0, 1), what="permuted") == "select-strided"
+        check_masked_select(x, m[:, :, :1], what="mask broadcast")
+        check_masked_select(x[:, :1], m, what="x broadcast")
+        check_masked_select(x, I.bernoulli_mask((7,), 0.5, seed=424), what="row mask")
+        check_masked_select(x, m, capacity=10, what="small buffer")            # count still exact, 10 results written
+        check_masked_select(x[:0], m[:0], what="empty")
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    cnt, ws = d(1, dt=I64), B.workspace(4096)
+    for args, kind in (((d(5), cnt, d(5), d(5)), "DTYPE"), ((d(5, dt=I32), cnt, d(5), d(5, dt=BOOL)), "DTYPE"),
+                       ((d(5), d(1, dt=I32), d(5), d(5, dt=BOOL)), "DTYPE"), ((d(5), d(2, dt=I64), d(5), d(5, dt=BOOL)), "SHAPE"),
+                       ((d(5, 1), cnt, d(5), d(5, dt=BOOL)), "SHAPE"), ((d(5), cnt, d(5), d(4, dt=BOOL)), "SHAPE")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_masked_select(*args, ws)
+        assert e.value.kind == kind, (kind, e.value.kind)
+    with pytest.raises(B.TxError) as e:
+        B.tx_masked_select(d(5), cnt, d(5), d(5, dt=BOOL), None)
+    assert e.value.kind == "WORKSPACE"
+
+
+def test_nonzero_sweep():
+    for dt in ALL:
+        for shape in [(7, 13, 5), (4096,), (4097,), (3, 5000), (1,), (), (2, 3, 4, 5, 6)]:
+            for p in (0.0, 0.05, 0.7):
+                keep = I.bernoulli_mask(shape, p, seed=430)
+                x = (I.typed(shape, dt, seed=431) if dt != BOOL else torch.ones(shape, dtype=BOOL))
+                x = torch.where(keep, x, torch.zeros((), dtype=dt))
+                assert check_nonzero(x, what="p=%g" % p) == "select"
+        x = torch.where(I.bernoulli_mask((6, 50, 7), 0.3, seed=432), I.typed((6, 50, 7), dt, seed=433) if dt != BOOL
+                        else torch.ones((6, 50, 7), dtype=BOOL), torch.zeros((), dtype=dt))
+        assert check_nonzero(x.permute(2, 0, 1), what="permuted") == "select-strided"
+        check_nonzero(x[:, ::2], what="sliced")
+        check_nonzero(x, capacity=17, what="small buffer")
+        check_nonzero(x[:0], what="empty")
+    sp = torch.tensor([0.0, -0.0, 1.0, float("nan"), 0.0, float("-inf"), 1e-45])
+    for dt in (F32, BF16, F16):
+        check_nonzero(sp.to(dt), what="signed zero, nan")
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    cnt, ws = d(1, dt=I64), B.workspace(4096)
+    for args, kind in (((d(5, 1), cnt, d(5)), "DTYPE"), ((d(5, 2, dt=I64), cnt, d(5)), "SHAPE"), ((d(5, dt=I64), cnt, d(5)), "SHAPE")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_nonzero(*args, ws)
+        assert e.value.kind == kind, (kind, e.value.kind)
+
+
+def test_compaction_full_size():
+    x = I.typed((8192, 8192), F32, seed=440)
+    m = I.bernoulli_mask((8192, 8192), 0.25, seed=441)
+    assert check_masked_select(x, m) == "select"
+    xs = torch.where(I.bernoulli_mask((8192, 4096), 0.1, seed=442), x[:, :4096], torch.zeros(()))
+    assert check_nonzero(xs) == "select"
