@@ -258,6 +258,25 @@ def build_ops(torch, B):
     mask = torch.rand((NS, W), device=dev, generator=g) < 0.3
     omf = osel[:NS]
     add("masked_fill_f32", "a16", "ew_vec_kernel", NS * W * 9, NS * W, lambda: B.tx_masked_fill(omf, src, mask, -1.0))
+    # further indexing operators, timed outside the step
+    wsia = B.workspace(B.tx_index_add_workspace_bytes(dst_f, 0, rows, src, True))
+    extra("index_add_f32_rows_alpha", "f3", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
+          lambda: B.tx_index_add_(dst_f, 0, rows, src, 0.5, True, wsia))
+    flat = src.view(-1)
+    tidx = torch.randint(-flat.numel(), flat.numel(), (16384 * W,), device=dev, dtype=I64, generator=g)
+    otake = ogat.view(-1)
+    extra("take_f32", "f3", "take_kernel", tidx.numel() * 16, tidx.numel(), lambda: B.tx_take(otake, src, tidx))
+    cnt = torch.zeros((1,), device=dev, dtype=I64)
+    osel1 = osel.view(-1)[: NS * W]
+    nsel = int(mask.sum().item())
+    wsm = B.workspace(B.tx_masked_select_workspace_bytes(osel1, cnt, src, mask))
+    extra("masked_select_f32_p0.3", "f3", "select_write_kernel", NS * W * 5 + nsel * 4, NS * W,
+          lambda: B.tx_masked_select(osel1, cnt, src, mask, wsm))
+    sparse = torch.where(mask, src, torch.zeros((), device=dev))
+    onz = torch.empty((NS * W // 2, 2), device=dev, dtype=I64)
+    wsn = B.workspace(B.tx_nonzero_workspace_bytes(onz, cnt, sparse))
+    extra("nonzero_f32_p0.3", "f3", "select_write_kernel", NS * W * 4 + nsel * 16, NS * W,
+          lambda: B.tx_nonzero(onz, cnt, sparse, wsn))
     return ops
 
 

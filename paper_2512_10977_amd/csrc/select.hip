@@ -147,6 +147,33 @@ template <int FES>
 __device__ __forceinline__ void slab_ballots(const SelectArgs& a, int64_t wave_base, int lane, unsigned long long (&bal)[kSlabs],
                                              int64_t (&poff)[kSlabs]) {
   using F = typename Raw<FES>::type;
+  if constexpr (FES == 1) {
+    // one-byte flags addressed linearly: a lane fetches the 16 flags of elements [16 lane, 16 lane + 16) with one
+    // 16-byte load (64 one-byte loads per slab would move 64 bytes per instruction) and folds them to 16 bits;
+    // slab s is then the concatenation of the masks held by lanes 4s .. 4s + 3
+    if (a.contiguous && wave_base + kSlabs * kWave <= a.shape.numel && ((uintptr_t)(a.flag + wave_base) & 15) == 0) {
+      const u32x4 v = *(const u32x4*)(a.flag + wave_base + lane * 16);
+      uint32_t m16 = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint32_t t = v[q];
+        t |= t >> 4;
+        t |= t >> 2;
+        t |= t >> 1;                                    // bit 8k = byte k is not zero
+        m16 |= ((t & 1u) | ((t >> 7) & 2u) | ((t >> 14) & 4u) | ((t >> 21) & 8u)) << (4 * q);
+      }
+#pragma unroll
+      for (int s = 0; s < kSlabs; ++s) {
+        unsigned long long b = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          b |= (unsigned long long)(uint32_t)__builtin_amdgcn_readlane((int)m16, 4 * s + q) << (16 * q);
+        bal[s] = b;
+        poff[s] = wave_base + s * kWave + lane;
+      }
+      return;
+    }
+  }
   F raw[kSlabs];
 #pragma unroll
   for (int s = 0; s < kSlabs; ++s) {
@@ -184,15 +211,22 @@ __global__ __launch_bounds__(kBlock) void select_count_kernel(const SelectArgs a
   }
 }
 
-// counts -> exclusive offsets in place; total -> *count.  One workgroup.
+// counts -> exclusive offsets in place; total -> *count.  One workgroup; a lane scans 16 consecutive counts per
+// step, so 64 Ki tiles (2^28 elements) take four steps.
+constexpr int kScanPer = 16;
 __global__ __launch_bounds__(kScanBlock) void select_offsets_kernel(uint32_t* counts, int64_t n, int64_t* total) {
   __shared__ uint32_t wave_tot[kScanBlock / kWave];
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   uint32_t carry = 0;
-  for (int64_t base = 0; base < n; base += kScanBlock) {
-    const int64_t i = base + threadIdx.x;
-    const uint32_t v = i < n ? counts[i] : 0u;
-    uint32_t incl = v;
+  for (int64_t base = 0; base < n; base += (int64_t)kScanBlock * kScanPer) {
+    const int64_t i0 = base + (int64_t)threadIdx.x * kScanPer;
+    uint32_t v[kScanPer];
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) v[k] = i0 + k < n ? counts[i0 + k] : 0u;
+    uint32_t sum = 0;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) sum += v[k];
+    uint32_t incl = sum;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) {
       const uint32_t up = shfl_up(incl, d);
@@ -206,9 +240,14 @@ __global__ __launch_bounds__(kScanBlock) void select_offsets_kernel(uint32_t* co
       if (k == w) before = all;
       all += wave_tot[k];
     }
-    if (i < n) counts[i] = before + incl - v;
+    uint32_t run = before + incl - sum;
+#pragma unroll
+    for (int k = 0; k < kScanPer; ++k) {
+      if (i0 + k < n) counts[i0 + k] = run;
+      run += v[k];
+    }
     carry = all;
-    __syncthreads();                        // wave_tot is rewritten by the next chunk
+    __syncthreads();                        // wave_tot is rewritten by the next step
   }
   if (threadIdx.x == 0) *total = (int64_t)carry;
 }
@@ -231,6 +270,13 @@ __global__ __launch_bounds__(kBlock) void select_write_kernel(const SelectArgs a
   for (int i = 0; i < w; ++i) pos += wave_count[i];
   const unsigned long long below = (1ull << lane) - 1ull;
   using P = typename Raw<PES>::type;
+  // every payload load is issued before the first store, and unconditionally (poff of a lane past the end is
+  // that of the last element): a load under `if (selected)` would be waited for right there, one slab at a time
+  P val[kSlabs];
+  if constexpr (!NONZERO) {
+#pragma unroll
+    for (int s = 0; s < kSlabs; ++s) val[s] = ((const P*)a.payload)[poff[s]];
+  }
 #pragma unroll
   for (int s = 0; s < kSlabs; ++s) {
     if (bal[s] == 0) continue;                                       // wave-uniform
@@ -247,7 +293,7 @@ __global__ __launch_bounds__(kBlock) void select_write_kernel(const SelectArgs a
           row[d * a.ostride1] = (int64_t)m;
         }
       } else {
-        ((P*)a.out)[dst * a.ostride0] = ((const P*)a.payload)[poff[s]];
+        ((P*)a.out)[dst * a.ostride0] = val[s];
       }
     }
     pos += __popcll(bal[s]);
