@@ -218,7 +218,7 @@ size_t tx_binary_cross_entropy_workspace_bytes(const tx_tensor* out, const tx_te
  *         still go to the lowest index).
  *   ANY / ALL  any input dtype, bool result: some / every element is non-zero
  *         (NaN is non-zero); empty extent: ANY false, ALL true.
- *   LOGSUMEXP  float only; log of the sum of exp(x), computed as a running
+ *   LOGSUMEXP  bool / integer input is converted to fp32 (fp32 result); log of the sum of exp(x), computed as a running
  *         (maximum, scaled sum) pair; -inf for an empty or all -inf extent,
  *         +inf if +inf is present, NaN is sticky.
  * For SUM / MEAN / PROD / VAR / STD / LOGSUMEXP on fp16 / bf16 input, out may
@@ -283,8 +283,8 @@ size_t tx_scatter_add_workspace_bytes(const tx_tensor* self, int64_t dim, const 
 /* In place: self[..., index[i], ...] += alpha * source[..., i, ...] along dim.
  * index is 1-D (or 0-dim) int32 / int64 with source.size(dim) entries in
  * [0, self.size(dim)); source has self's shape except along dim and self's
- * dtype (bool is TX_ERR_DTYPE).  alpha as in tx_add (a floating alpha with an
- * integer dtype is TX_ERR_SCALAR); integers wrap.  Kernels, determinism and
+ * dtype.  alpha as in tx_add (a floating alpha with an integer dtype is
+ * TX_ERR_SCALAR); integers wrap; bool: self OR (alpha != 0 AND source).  Kernels, determinism and
  * workspace exactly as tx_scatter_add_ with the index broadcast over the other
  * dims: dim 0 with contiguous rows takes the sorted whole-row path. */
 tx_status tx_index_add_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source, double alpha_f,

@@ -769,6 +769,11 @@ int orc_clamp(const orc_tensor* out, const orc_tensor* x, int has_lo, double lo_
 // ===========================================================================
 // Normalise a dim list: wrap negatives, reject out-of-range and duplicates.
 // An empty list means all dims.  A 0-dim tensor accepts dim 0 / -1.
+// logsumexp operand: a floating element as it is, a bool / integer element converted to fp32 (nearest-even)
+static inline double lse_value(const orc_tensor* x, int64_t off) {
+  return is_float(x->dtype) ? load_flt(x, off) : (double)(float)load_int(x, off);
+}
+
 static int normalise_dims(int nd, const int64_t* dims, int ndims, bool* reduced) {
   for (int d = 0; d < ORC_MAX_DIMS; ++d) reduced[d] = false;
   if (ndims == 0 || dims == nullptr) {
@@ -792,7 +797,8 @@ int orc_reduce_result_dtype(int op, int in_dtype) {
   if (!valid_dtype(in_dtype)) return ORC_ERR_DTYPE;
   switch (op) {
     case ORC_SUM: case ORC_PROD: return is_float(in_dtype) ? in_dtype : ORC_I64;
-    case ORC_MEAN: case ORC_VAR: case ORC_STD: case ORC_LOGSUMEXP: return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_MEAN: case ORC_VAR: case ORC_STD: return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_LOGSUMEXP: return is_float(in_dtype) ? in_dtype : ORC_F32;    // bool / integer input is converted to fp32
     case ORC_AMAX: case ORC_AMIN: return in_dtype;
     case ORC_ARGMAX: case ORC_ARGMIN: return in_dtype == ORC_BOOL ? (int)ORC_ERR_DTYPE : (int)ORC_I64;
     case ORC_ANY: case ORC_ALL: return ORC_BOOL;
@@ -899,7 +905,7 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
       for (int64_t r = 0; r < nred; ++r) {
         unravel(r, nr, rsz, ridx);
         for (int i = 0; i < nr; ++i) xi[rdm[i]] = ridx[i];
-        double v = load_flt(x, offset_of(x, xi));
+        double v = lse_value(x, offset_of(x, xi));
         if (std::isnan(v)) lse_nan = true;
         else if (v > lse_max) lse_max = v;
       }
@@ -937,7 +943,7 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
           break;
         }
         case ORC_LOGSUMEXP:                            // second pass: sum of exp(x - max); skipped when max is infinite
-          if (std::isfinite(lse_max)) accd += std::exp(load_flt(x, xo) - lse_max);
+          if (std::isfinite(lse_max)) accd += std::exp(lse_value(x, xo) - lse_max);
           break;
         case ORC_AMIN: case ORC_ARGMIN:
           if (flt) {
@@ -1212,13 +1218,14 @@ int orc_gather(const orc_tensor* out, const orc_tensor* src, int64_t dim, const 
   if ((rc = check_tensor(out)) || (rc = check_tensor(src)) || (rc = check_tensor(index))) return rc;
   if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
   if (out->dtype != src->dtype) return ORC_ERR_DTYPE;
-  if (index->ndim != src->ndim) return ORC_ERR_SHAPE;
+  // ranks must agree, a 0-dim tensor counting as 1-D with one element
+  if (std::max<int>(index->ndim, 1) != std::max<int>(src->ndim, 1)) return ORC_ERR_SHAPE;
   const int nd = src->ndim;
   int lim = nd == 0 ? 1 : nd;
   if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
   if (dim < 0) dim += lim;
   for (int d = 0; d < nd; ++d)
-    if (d != dim && index->sizes[d] > src->sizes[d]) return ORC_ERR_SHAPE;
+    if (d != dim && index->ndim && index->sizes[d] > src->sizes[d]) return ORC_ERR_SHAPE;
   if (!same_shape(out, index->ndim, index->sizes)) return ORC_ERR_SHAPE;
   const int64_t n = numel(out);
   const int64_t extent = nd == 0 ? 1 : src->sizes[dim];
@@ -1227,12 +1234,12 @@ int orc_gather(const orc_tensor* out, const orc_tensor* src, int64_t dim, const 
 #pragma omp parallel for schedule(static) reduction(| : bad)
   for (int64_t lin = 0; lin < n; ++lin) {
     int64_t idx[ORC_MAX_DIMS] = {0};
-    unravel(lin, nd, out->sizes, idx);
+    unravel(lin, out->ndim, out->sizes, idx);
     int64_t oo = offset_of(out, idx);
     int64_t k = load_int(index, offset_of(index, idx));
     if (k < 0 || k >= extent) { bad |= 1; continue; }
     if (nd) idx[dim] = k;
-    std::memcpy(mptr(out, oo), cptr(src, offset_of(src, idx)), es);
+    std::memcpy(mptr(out, oo), cptr(src, offset_of(src, idx)), es);    // a 0-dim src has no coordinates: offset 0
   }
   return bad ? ORC_ERR_INDEX : ORC_OK;
 }
@@ -1347,15 +1354,15 @@ int orc_scatter_add(const orc_tensor* self, int64_t dim, const orc_tensor* index
 
 // index_add_ (in place on self): for every i, self[..., index[i], ...] += alpha * source[..., i, ...] along `dim`.
 // index is 1-D (or 0-dim) int32 / int64 with source.size(dim) entries in [0, self.size(dim)); source has self's
-// shape except along dim; both have the same dtype (bool is refused).  Integers: exact wrapping arithmetic, alpha
-// must be integral.  Floating dtypes: the products alpha * source are accumulated per destination element in
+// shape except along dim; both have the same dtype.  Integers: exact wrapping arithmetic, alpha must be integral;
+// bool: self OR (alpha != 0 AND source).  Floating dtypes: the products alpha * source are accumulated per destination element in
 // binary64 in index order, the initial value of self is added, one rounding.
 int orc_index_add(const orc_tensor* self, int64_t dim, const orc_tensor* index, const orc_tensor* source, double alpha_f,
                   int64_t alpha_i, int alpha_is_int) {
   int rc;
   if ((rc = check_tensor(self)) || (rc = check_tensor(index)) || (rc = check_tensor(source))) return rc;
   if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
-  if (self->dtype != source->dtype || self->dtype == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (self->dtype != source->dtype) return ORC_ERR_DTYPE;
   if (index->ndim > 1 || source->ndim != self->ndim) return ORC_ERR_SHAPE;
   const int nd = self->ndim;
   int lim = nd == 0 ? 1 : nd;
@@ -1398,7 +1405,8 @@ int orc_index_add(const orc_tensor* self, int64_t dim, const orc_tensor* index, 
       touched[(size_t)l] = 1;
     } else {
       const int64_t d_o = offset_of(self, idx);
-      store_int(self, d_o, (int64_t)((uint64_t)load_int(self, d_o) + (uint64_t)alpha_i * (uint64_t)load_int(source, so)));
+      if (self->dtype == ORC_BOOL) store_int(self, d_o, load_int(self, d_o) | ((alpha_i != 0) & load_int(source, so)));
+      else store_int(self, d_o, (int64_t)((uint64_t)load_int(self, d_o) + (uint64_t)alpha_i * (uint64_t)load_int(source, so)));
     }
   }
   if (flt) {

@@ -890,7 +890,6 @@ tx_status index_add_checks(const tx_tensor* self, int64_t dim, const tx_tensor* 
     return rc;
   if (!index_dtype_ok(index->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
   if (self->dtype != source->dtype) return fail(TX_ERR_DTYPE, "index_add_: self and source dtypes differ");
-  if (self->dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "index_add_ does not take bool");
   if (index->ndim > 1) return fail(TX_ERR_SHAPE, "index_add_: index must be 1-D or 0-dim");
   if (source->ndim != self->ndim) return fail(TX_ERR_SHAPE, "index_add_: self and source must have the same rank");
   if ((rc = wrap_dim(dim, self->ndim, d))) return rc;
@@ -898,7 +897,7 @@ tx_status index_add_checks(const tx_tensor* self, int64_t dim, const tx_tensor* 
     return fail(TX_ERR_SHAPE, "index_add_: source.size(dim) must be the number of indices");
   for (int i = 0; i < self->ndim; ++i)
     if (i != *d && source->sizes[i] != self->sizes[i]) return fail(TX_ERR_SHAPE, "index_add_: source and self differ in dim %d", i);
-  if (!dtype_is_float(self->dtype) && !alpha_is_int) return fail(TX_ERR_SCALAR, "floating alpha with an integer result");
+  if (!dtype_is_float(self->dtype) && !alpha_is_int) return fail(TX_ERR_SCALAR, "floating alpha with an integer / bool result");
   if (!no_internal_overlap(self)) return fail(TX_ERR_OVERLAP, "self has overlapping elements");
   if (partial_overlap(self, source) || partial_overlap(self, index) || (self->data == source->data && numel(source) && numel(self)))
     return fail(TX_ERR_OVERLAP, "self overlaps source or index");
@@ -924,10 +923,11 @@ tx_status tx_gather(const tx_tensor* out, const tx_tensor* src, int64_t dim, con
   if ((rc = check_tensor(out, "out")) || (rc = check_tensor(src, "src")) || (rc = check_tensor(index, "index"))) return rc;
   if (!index_dtype_ok(index->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
   if (out->dtype != src->dtype) return fail(TX_ERR_DTYPE, "gather: out must have src's dtype");
-  if (index->ndim != src->ndim) return fail(TX_ERR_SHAPE, "gather: index and src must have the same rank");
+  // ranks must agree, a 0-dim tensor counting as 1-D with one element
+  if (std::max(index->ndim, 1) != std::max(src->ndim, 1)) return fail(TX_ERR_SHAPE, "gather: index and src must have the same rank");
   int d;
   if ((rc = wrap_dim(dim, src->ndim, &d))) return rc;
-  for (int i = 0; i < src->ndim; ++i)
+  for (int i = 0; i < src->ndim && index->ndim; ++i)
     if (i != d && index->sizes[i] > src->sizes[i]) return fail(TX_ERR_SHAPE, "gather: index larger than src in dim %d", i);
   if (!same_sizes(out, index->ndim, index->sizes)) return fail(TX_ERR_SHAPE, "gather: out must have index's shape");
   if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
@@ -946,7 +946,7 @@ tx_status tx_gather(const tx_tensor* out, const tx_tensor* src, int64_t dim, con
   a.dst = (char*)out->data;
   for (int i = 0; i < index->ndim; ++i) {
     a.istride[i] = index->strides[i];
-    a.sstride[i] = src->strides[i];
+    a.sstride[i] = i < src->ndim ? src->strides[i] : 0;      // 0-dim src read through a 1-D index: one element
     a.dstride[i] = out->strides[i];
   }
   if (index->ndim == 0) a.sstride[0] = a.istride[0] = a.dstride[0] = 0;
@@ -1086,7 +1086,7 @@ tx_status tx_index_add_(const tx_tensor* self, int64_t dim, const tx_tensor* ind
   tx_status rc = index_add_checks(self, dim, index, source, alpha_is_int, &d, &view);
   if (rc) return rc;
   set_path("");
-  const Alpha alpha{(float)(alpha_is_int ? (double)alpha_i : alpha_f), alpha_is_int ? alpha_i : 0};
+  const Alpha alpha{(float)(alpha_is_int ? (double)alpha_i : alpha_f), alpha_is_int ? alpha_i : 0};   // bool: zero or not
   return scatter_core("index_add_", self, d, &view, source, alpha, deterministic, ws, ws_bytes, as_stream(stream));
 }
 

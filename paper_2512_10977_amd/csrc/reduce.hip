@@ -203,10 +203,11 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
   int rd;
   switch (op) {
     case TX_SUM: case TX_PROD: rd = flt ? x->dtype : TX_I64; break;
-    case TX_MEAN: case TX_VAR: case TX_STD: case TX_LOGSUMEXP:
-      if (!flt) return fail(TX_ERR_DTYPE, "mean / var / std / logsumexp take floating dtypes only");
+    case TX_MEAN: case TX_VAR: case TX_STD:
+      if (!flt) return fail(TX_ERR_DTYPE, "mean / var / std take floating dtypes only");
       rd = x->dtype;
       break;
+    case TX_LOGSUMEXP: rd = flt ? x->dtype : TX_F32; break;     // bool / integer input is converted to fp32
     case TX_AMAX: case TX_AMIN: rd = x->dtype; break;
     case TX_ARGMAX: case TX_ARGMIN:
       if (x->dtype == TX_BOOL) return fail(TX_ERR_DTYPE, "argmax / argmin do not take bool");

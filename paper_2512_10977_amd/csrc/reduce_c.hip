@@ -37,12 +37,8 @@ tx_status launch_anyall(const Plan& p, const tx_tensor* x, const tx_tensor* out,
 
 tx_status launch_logsumexp(const Plan& p, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb,
                            hipStream_t s) {
-  switch (x->dtype) {
-    case TX_F32: return launch<LsePolicy<float>>(p, x, out, c, ws, wsb, s);
-    case TX_BF16: return launch<LsePolicy<bf16>>(p, x, out, c, ws, wsb, s);
-    case TX_F16: return launch<LsePolicy<f16>>(p, x, out, c, ws, wsb, s);
-    default: return fail(TX_ERR_DTYPE, "logsumexp takes floating dtypes only");
-  }
+  TX_ALL_DTYPES(LsePolicy)
+  return launch<LsePolicy<uint8_t>>(p, x, out, c, ws, wsb, s);
 }
 
 }  // namespace red

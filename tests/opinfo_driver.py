@@ -1,0 +1,557 @@
+"""Drive an operator backend through PyTorch's OpInfo sample generators.
+
+The paper's acceptance criterion (Section 3.3) is that an operator passes every OpInfo sample for every dtype it
+supports, "passing" meaning agreement with the ATen CPU operator within a dtype-dependent tolerance (Section 3.2).
+This module reproduces that loop for the operators of this library: the sample generators and the reference
+operator are the ones that ship inside the installed torch package (used as a test DRIVER: nothing of the suite is
+copied here), the backend under test is either the HIP library (GPU tests) or the CPU oracle (CPU tests, which
+pins the oracle to the ATen CPU operators on the same samples).
+
+A sample is "unsupported" when it asks for something outside the library's C ABI (a dtype other than the six,
+a dtype= / out= keyword, tensor-valued clamp bounds, rounding modes, ...); those are counted and reported, never
+silently passed.
+"""
+import sys
+import types
+import unittest
+
+import torch
+
+F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
+DTYPES = (F32, BF16, F16, I32, I64, BOOL)
+# |got - want| <= atol + rtol * |want| against the ATen CPU result (itself computed in fp32 for the half types)
+TOL = {F32: (1e-5, 2e-5), BF16: (1.6e-2, 1e-2), F16: (2e-3, 2e-3)}
+
+
+class Unsupported(Exception):
+    pass
+
+
+def load_op_db():
+    """name -> list of OpInfo.  The internal test package needs `expecttest` (absent here: stubbed) and probes the
+    GPU's architecture name at import (patched for the import when there is no GPU)."""
+    if "expecttest" not in sys.modules:
+        try:
+            import expecttest  # noqa: F401
+        except ImportError:
+            stub = types.ModuleType("expecttest")
+            stub.TestCase = type("TestCase", (unittest.TestCase,), {})
+            sys.modules["expecttest"] = stub
+    saved = None
+    if not torch.cuda.is_available():
+        saved = torch.cuda.get_device_properties
+        props = types.SimpleNamespace(gcnArchName="gfx950", major=9, minor=5, multi_processor_count=256,
+                                      total_memory=1 << 38, name="none")
+        torch.cuda.get_device_properties = lambda *a, **k: props
+    try:
+        from torch.testing._internal.common_methods_invocations import op_db
+    finally:
+        if saved is not None:
+            torch.cuda.get_device_properties = saved
+    db = {}
+    for op in op_db:
+        db.setdefault(op.name, []).append(op)
+    return db
+
+
+# --------------------------------------------------------------------------- backends
+class OracleBackend:
+    """The CPU oracle, called on the samples as they are."""
+    name = "oracle"
+
+    def __init__(self):
+        from oracle import oracle as O
+        self.O = O
+        self.refused = (O.OracleError,)
+
+    def unary(self, op, x):
+        return self.O.unary(op, x)
+
+    def binary(self, op, a, b, alpha=1):
+        return self.O.binary(op, a, b, alpha=alpha)
+
+    def clamp(self, x, lo, hi):
+        return self.O.clamp(x, lo, hi)
+
+    def where(self, c, x, y):
+        return self.O.where(c, x, y)
+
+    def masked_fill(self, x, m, v):
+        return self.O.masked_fill(x, m, v)
+
+    def reduce(self, op, x, dims, keepdim, correction=1.0):
+        return self.O.reduce(op, x, dims, keepdim, correction)
+
+    def softmax(self, x, dim, log):
+        return self.O.softmax(x, dim, log)
+
+    def cumsum(self, x, dim):
+        return self.O.cumsum(x, dim)
+
+    def gather(self, x, dim, index):
+        return self.O.gather(x, dim, index)
+
+    def index_select(self, x, dim, index):
+        return self.O.index_select(x, dim, index)
+
+    def scatter_add(self, x, dim, index, src):
+        return self.O.scatter_add_(x.clone(), dim, index, src)
+
+    def index_add(self, x, dim, index, src, alpha):
+        return self.O.index_add_(x.clone(), dim, index, src, alpha)
+
+    def take(self, x, index):
+        return self.O.take(x, index)
+
+    def masked_select(self, x, m):
+        return self.O.masked_select(x, m)
+
+    def nonzero(self, x):
+        return self.O.nonzero(x)
+
+    def layer_norm(self, x, k, w, b, eps):
+        return self.O.layer_norm(x, k, w, b, eps)
+
+    def bce(self, x, t, w, reduction):
+        return self.O.binary_cross_entropy(x, t, w, reduction)
+
+
+class LibraryBackend:
+    """The HIP library: operands copied to the GPU with their strides, outputs allocated from the library's own
+    inference functions, every call through the C ABI binding."""
+    name = "library"
+
+    def __init__(self):
+        from paper_2512_10977_amd import binding as B
+        from tests.parity import to_device_view
+        self.B = B
+        self.dev = to_device_view
+        self.refused = (B.TxError,)
+
+    def _out(self, shape, dtype):
+        return torch.empty(tuple(shape), dtype=dtype, device="cuda")
+
+    def _ws(self, nbytes):
+        return self.B.workspace(nbytes) if nbytes else None
+
+    def unary(self, op, x):
+        out = self._out(x.shape, self.B.tx_infer_unary_dtype(op, x.dtype))
+        self.B.tx_unary(op, out, self.dev(x))
+        return out.cpu()
+
+    def binary(self, op, a, b, alpha=1):
+        da, db = self.dev(a), self.dev(b)
+        dt, shape = self.B.tx_infer_binary(op, da, db)
+        out = self._out(shape, dt)
+        if op == "add":
+            self.B.tx_add(out, da, db, alpha)
+        elif op == "sub":
+            self.B.tx_sub(out, da, db, alpha)
+        else:
+            self.B.tx_binary(op, out, da, db)
+        return out.cpu()
+
+    def clamp(self, x, lo, hi):
+        out = self._out(x.shape, self.B.tx_infer_clamp_dtype(x.dtype, lo, hi))
+        self.B.tx_clamp(out, self.dev(x), lo, hi)
+        return out.cpu()
+
+    def where(self, c, x, y):
+        dx, dy = self.dev(x), self.dev(y)
+        out = self._out(torch.broadcast_shapes(c.shape, x.shape, y.shape), self.B.tx_infer_where(dx, dy))
+        self.B.tx_where(out, self.dev(c), dx, dy)
+        return out.cpu()
+
+    def masked_fill(self, x, m, v):
+        out = self._out(torch.broadcast_shapes(x.shape, m.shape), x.dtype)
+        self.B.tx_masked_fill(out, self.dev(x), self.dev(m), v)
+        return out.cpu()
+
+    def reduce(self, op, x, dims, keepdim, correction=1.0):
+        dx = self.dev(x)
+        dt, shape = self.B.tx_infer_reduce(op, dx, dims, keepdim)
+        out = self._out(shape, dt)
+        ws = self._ws(self.B.tx_reduce_workspace_bytes(op, out, dx, dims, keepdim))
+        self.B.tx_reduce(op, out, dx, dims, keepdim, correction, ws)
+        return out.cpu()
+
+    def softmax(self, x, dim, log):
+        out = self._out(x.shape, x.dtype)
+        self.B.tx_softmax(out, self.dev(x), dim, log)
+        return out.cpu()
+
+    def cumsum(self, x, dim):
+        dx = self.dev(x)
+        out = self._out(x.shape, x.dtype if x.dtype.is_floating_point else I64)
+        self.B.tx_cumsum(out, dx, dim, self._ws(self.B.tx_cumsum_workspace_bytes(out, dx, dim)))
+        return out.cpu()
+
+    def gather(self, x, dim, index):
+        out = self._out(index.shape, x.dtype)
+        self.B.tx_gather(out, self.dev(x), dim, self.dev(index))
+        return out.cpu()
+
+    def index_select(self, x, dim, index):
+        shape = list(x.shape)
+        if x.dim():
+            shape[dim] = index.numel()
+        out = self._out(shape, x.dtype)
+        self.B.tx_index_select(out, self.dev(x), dim, self.dev(index))
+        return out.cpu()
+
+    def scatter_add(self, x, dim, index, src):
+        dst, di, ds = x.contiguous().cuda(), self.dev(index), self.dev(src)
+        self.B.tx_scatter_add_(dst, dim, di, ds, True, self._ws(self.B.tx_scatter_add_workspace_bytes(dst, dim, di, ds, True)))
+        return dst.cpu()
+
+    def index_add(self, x, dim, index, src, alpha):
+        dst, di, ds = x.contiguous().cuda(), self.dev(index), self.dev(src)
+        self.B.tx_index_add_(dst, dim, di, ds, alpha, True, self._ws(self.B.tx_index_add_workspace_bytes(dst, dim, di, ds, True)))
+        return dst.cpu()
+
+    def take(self, x, index):
+        out = self._out(index.shape, x.dtype)
+        self.B.tx_take(out, self.dev(x), self.dev(index))
+        return out.cpu()
+
+    def _select(self, out, nbytes, call):
+        count = torch.zeros((1,), dtype=I64, device="cuda")
+        call(out, count, self.B.workspace(nbytes(out, count)))
+        return out[: int(count.item())].cpu()
+
+    def masked_select(self, x, m):
+        dx, dm = self.dev(x), self.dev(m)
+        cap = 1
+        for s in torch.broadcast_shapes(x.shape, m.shape):
+            cap *= s
+        return self._select(self._out((cap,), x.dtype), lambda o, c: self.B.tx_masked_select_workspace_bytes(o, c, dx, dm),
+                            lambda o, c, ws: self.B.tx_masked_select(o, c, dx, dm, ws))
+
+    def nonzero(self, x):
+        dx = self.dev(x)
+        return self._select(self._out((x.numel(), x.dim()), I64), lambda o, c: self.B.tx_nonzero_workspace_bytes(o, c, dx),
+                            lambda o, c, ws: self.B.tx_nonzero(o, c, dx, ws))
+
+    def layer_norm(self, x, k, w, b, eps):
+        out = self._out(x.shape, x.dtype)
+        self.B.tx_layer_norm(out, self.dev(x), k, None if w is None else self.dev(w), None if b is None else self.dev(b), eps)
+        return out.cpu()
+
+    def bce(self, x, t, w, reduction):
+        dx, dt_, dw = self.dev(x), self.dev(t), None if w is None else self.dev(w)
+        out = self._out(x.shape if reduction == "none" else (), x.dtype)
+        ws = self._ws(self.B.tx_binary_cross_entropy_workspace_bytes(out, dx, dt_, dw, reduction))
+        self.B.tx_binary_cross_entropy(out, dx, dt_, dw, reduction, ws)
+        return out.cpu()
+
+
+# --------------------------------------------------------------------------- sample -> backend call
+def _tensor_ok(t):
+    if t.dtype not in DTYPES:
+        raise Unsupported("dtype %s" % t.dtype)
+    if any(s < 0 for s in t.stride()):
+        raise Unsupported("negative stride")
+    return t
+
+
+def _operand(v):
+    """A tensor operand, or a Python scalar as the 0-dim tensor ATen's promotion treats it like."""
+    if isinstance(v, torch.Tensor):
+        return _tensor_ok(v)
+    if isinstance(v, (bool, int, float)):
+        return torch.tensor(v)
+    raise Unsupported("operand %r" % type(v))
+
+
+def _no_kwargs(s, allowed=()):
+    extra = set(s.kwargs) - set(allowed)
+    if extra:
+        raise Unsupported("keyword %s" % sorted(extra))
+
+
+def _scalar(v):
+    if isinstance(v, torch.Tensor):
+        if v.dim() != 0:
+            raise Unsupported("tensor-valued scalar argument")
+        return v.item()
+    if v is None or isinstance(v, (bool, int, float)):
+        return v
+    raise Unsupported("scalar %r" % type(v))
+
+
+def unary(name):
+    def run(be, s):
+        _no_kwargs(s)
+        if s.args:
+            raise Unsupported("positional arguments")
+        return be.unary(name, _tensor_ok(s.input))
+    return run
+
+
+def gelu(be, s):
+    _no_kwargs(s, ("approximate",))
+    if s.kwargs.get("approximate", "none") != "none" or s.args:
+        raise Unsupported("tanh approximation")
+    return be.unary("gelu", _tensor_ok(s.input))
+
+
+def binary(name, alpha_ok=False):
+    def run(be, s):
+        _no_kwargs(s, ("alpha",) if alpha_ok else ())
+        if len(s.args) != 1:
+            raise Unsupported("arguments")
+        return be.binary(name, _operand(s.input), _operand(s.args[0]), _scalar(s.kwargs.get("alpha", 1)))
+    return run
+
+
+def clamp(be, s):
+    bounds = dict(zip(("min", "max"), s.args))
+    bounds.update(s.kwargs)
+    _no_kwargs(types.SimpleNamespace(kwargs=bounds), ("min", "max"))
+    lo, hi = bounds.get("min"), bounds.get("max")
+    x = _tensor_ok(s.input)
+    if any(isinstance(b, torch.Tensor) and b.dim() > 0 for b in (lo, hi)):
+        # tensor-valued bounds are outside the clamp entry point (scalar bounds); the same function is
+        # min(max(x, lo), hi) on the broadcasting binary entry point
+        r = x
+        if lo is not None:
+            r = be.binary("maximum", r, _operand(lo))
+        if hi is not None:
+            r = be.binary("minimum", r, _operand(hi))
+        return r
+    return be.clamp(x, _scalar(lo), _scalar(hi))
+
+
+def where(be, s):
+    _no_kwargs(s)
+    return be.where(_tensor_ok(s.args[0]), _operand(s.input), _operand(s.args[1]))
+
+
+def masked_fill(be, s):
+    _no_kwargs(s)
+    return be.masked_fill(_tensor_ok(s.input), _tensor_ok(s.args[0]), _scalar(s.args[1]))
+
+
+def reduction(name, variance=False, index=False):
+    def run(be, s):
+        kw = dict(s.kwargs)
+        args = list(s.args)
+        x = _tensor_ok(s.input)
+        correction = 1.0
+        if variance:
+            if args and isinstance(args[0], bool):                   # var(x, unbiased)
+                correction = 1.0 if args.pop(0) else 0.0
+            if "unbiased" in kw:
+                correction = 1.0 if kw.pop("unbiased") else 0.0
+            if "correction" in kw:
+                c = kw.pop("correction")
+                correction = 1.0 if c is None else float(c)
+        if args:
+            kw["dim"] = args.pop(0)
+        if args:
+            kw["keepdim"] = args.pop(0)
+            if variance and isinstance(kw["keepdim"], bool) and args:
+                raise Unsupported("arguments")
+        if variance and args:
+            raise Unsupported("arguments")
+        if set(kw) - {"dim", "keepdim"}:
+            raise Unsupported("keyword %s" % sorted(set(kw) - {"dim", "keepdim"}))
+        dim = kw.get("dim")
+        if isinstance(dim, (list, tuple)):
+            dim = list(dim)
+            if index and len(dim) != 1:
+                raise Unsupported("several dims")
+        return be.reduce(name, x, dim, bool(kw.get("keepdim", False)), correction)
+    return run
+
+
+def softmax(log):
+    def run(be, s):
+        _no_kwargs(s)
+        return be.softmax(_tensor_ok(s.input), s.args[0], log)
+    return run
+
+
+def cumsum(be, s):
+    _no_kwargs(s)
+    return be.cumsum(_tensor_ok(s.input), s.args[0])
+
+
+def gather(be, s):
+    _no_kwargs(s)
+    return be.gather(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]))
+
+
+def index_select(be, s):
+    _no_kwargs(s)
+    return be.index_select(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]))
+
+
+def scatter_add(be, s):
+    _no_kwargs(s)
+    return be.scatter_add(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]), _tensor_ok(s.args[2]))
+
+
+def index_add(be, s):
+    _no_kwargs(s, ("alpha",))
+    return be.index_add(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]), _tensor_ok(s.args[2]), _scalar(s.kwargs.get("alpha", 1)))
+
+
+def take(be, s):
+    _no_kwargs(s)
+    return be.take(_tensor_ok(s.input), _tensor_ok(s.args[0]))
+
+
+def masked_select(be, s):
+    _no_kwargs(s)
+    return be.masked_select(_tensor_ok(s.input), _tensor_ok(s.args[0]))
+
+
+def nonzero(be, s):
+    _no_kwargs(s, ("as_tuple",))
+    if s.kwargs.get("as_tuple", False) or s.args:
+        raise Unsupported("as_tuple")
+    return be.nonzero(_tensor_ok(s.input))
+
+
+def layer_norm(be, s):
+    _no_kwargs(s, ("eps", "weight", "bias"))
+    x = _tensor_ok(s.input)
+    shape = tuple(s.args[0])
+    w = s.args[1] if len(s.args) > 1 else s.kwargs.get("weight")
+    b = s.args[2] if len(s.args) > 2 else s.kwargs.get("bias")
+    if len(s.args) > 3:
+        raise Unsupported("arguments")
+    return be.layer_norm(x, len(shape), None if w is None else _tensor_ok(w), None if b is None else _tensor_ok(b),
+                         float(s.kwargs.get("eps", 1e-5)))
+
+
+def bce(be, s):
+    _no_kwargs(s, ("weight", "reduction"))
+    if len(s.args) != 1:
+        raise Unsupported("arguments")
+    w = s.kwargs.get("weight")
+    return be.bce(_tensor_ok(s.input), _tensor_ok(s.args[0]), None if w is None else _tensor_ok(w), s.kwargs.get("reduction", "mean"))
+
+
+# OpInfo name -> (variant names to take, adapter)
+ADAPTERS = {
+    "neg": unary("neg"), "abs": unary("abs"), "exp": unary("exp"), "log": unary("log"), "sqrt": unary("sqrt"),
+    "sigmoid": unary("sigmoid"), "tanh": unary("tanh"), "log1p": unary("log1p"), "expm1": unary("expm1"),
+    "logical_not": unary("logical_not"), "nn.functional.logsigmoid": unary("logsigmoid"), "nn.functional.gelu": gelu,
+    "add": binary("add", True), "sub": binary("sub", True), "mul": binary("mul"), "true_divide": binary("div"),
+    "maximum": binary("maximum"), "minimum": binary("minimum"), "eq": binary("eq"), "ne": binary("ne"), "lt": binary("lt"),
+    "le": binary("le"), "gt": binary("gt"), "ge": binary("ge"), "logical_and": binary("logical_and"),
+    "logical_or": binary("logical_or"), "logical_xor": binary("logical_xor"), "pow": binary("pow"),
+    "clamp": clamp, "where": where, "masked_fill": masked_fill,
+    "sum": reduction("sum"), "mean": reduction("mean"), "amax": reduction("amax"), "amin": reduction("amin"),
+    "argmax": reduction("argmax", index=True), "argmin": reduction("argmin", index=True), "prod": reduction("prod", index=True),
+    "var": reduction("var", variance=True), "std": reduction("std", variance=True), "any": reduction("any"),
+    "all": reduction("all"), "logsumexp": reduction("logsumexp"),
+    "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": cumsum,
+    "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
+    "masked_select": masked_select, "nonzero": nonzero,
+    "nn.functional.layer_norm": layer_norm, "nn.functional.binary_cross_entropy": bce,
+}
+
+
+def compare(got, want):
+    """None if got matches the ATen CPU result, else a short description."""
+    if not isinstance(want, torch.Tensor):
+        return "reference returned %r" % type(want)
+    if got.dtype != want.dtype:
+        return "dtype %s, ATen %s" % (got.dtype, want.dtype)
+    if tuple(got.shape) != tuple(want.shape):
+        return "shape %s, ATen %s" % (tuple(got.shape), tuple(want.shape))
+    if not want.dtype.is_floating_point:
+        bad = got != want
+        return None if not bad.any() else "%d of %d integer / bool elements differ" % (int(bad.sum()), bad.numel())
+    rtol, atol = TOL[want.dtype]
+    g, w = got.double(), want.double()
+    ok = torch.where(w.isfinite() & g.isfinite(), (g - w).abs() <= atol + rtol * w.abs(), (g == w) | (g.isnan() & w.isnan()))
+    if ok.all():
+        return None
+    i = (~ok).nonzero()[0].tolist()
+    return "%d of %d outside tolerance, first at %s: %r vs ATen %r" % (int((~ok).sum()), ok.numel(), i, got[tuple(i)].item(),
+                                                                     want[tuple(i)].item())
+
+
+def sweep(backend, names=None, db=None):
+    """Runs every OpInfo sample of every adapted operator and dtype.  Returns {op: {"samples", "supported", "passed",
+    "unsupported": {reason: n}, "failures": [...]}}."""
+    db = db or load_op_db()
+    report = {}
+    for name, adapter in ADAPTERS.items():
+        if names and name not in names:
+            continue
+        rec = report.setdefault(name, {"samples": 0, "supported": 0, "passed": 0, "unsupported": {}, "failures": []})
+        for op in db.get(name, []):
+            for dt in DTYPES:
+                if dt not in op.supported_dtypes("cpu"):
+                    continue
+                for s in op.sample_inputs("cpu", dt, requires_grad=False):
+                    rec["samples"] += 1
+                    label = "%s%s %s %s" % (name, "/" + op.variant_test_name if op.variant_test_name else "", dt, _describe(s))
+                    try:
+                        want = op.op(s.input, *s.args, **s.kwargs)
+                    except Exception as e:                              # the reference refuses this sample itself
+                        rec["unsupported"]["ATen raised"] = rec["unsupported"].get("ATen raised", 0) + 1
+                        continue
+                    try:
+                        got = adapter(backend, s)
+                    except Unsupported as e:
+                        key = str(e)
+                        rec["unsupported"][key] = rec["unsupported"].get(key, 0) + 1
+                        continue
+                    except backend.refused as e:
+                        rec["supported"] += 1
+                        rec["failures"].append("%s: %s refused: %s" % (label, backend.name, e))
+                        continue
+                    rec["supported"] += 1
+                    bad = compare(got, want)
+                    if bad is None:
+                        rec["passed"] += 1
+                    else:
+                        rec["failures"].append("%s: %s" % (label, bad))
+    return report
+
+
+def _describe(s):
+    def d(v):
+        if isinstance(v, torch.Tensor):
+            return "T%s%s" % (list(v.shape), "" if v.is_contiguous() else "nc")
+        if isinstance(v, (list, tuple)):
+            return "(" + ",".join(d(x) for x in v) + ")"
+        return repr(v)
+    return "%s %s %s" % (d(s.input), [d(a) for a in s.args], {k: d(v) for k, v in s.kwargs.items()})
+
+
+def summarise(report):
+    lines = ["%-36s %8s %10s %8s  %s" % ("operator", "samples", "supported", "passed", "unsupported (reason: count)")]
+    for name, r in sorted(report.items()):
+        lines.append("%-36s %8d %10d %8d  %s" % (name, r["samples"], r["supported"], r["passed"],
+                                               "; ".join("%s: %d" % kv for kv in sorted(r["unsupported"].items()))))
+    return "\n".join(lines)
+
+
+def check(report):
+    """Assertion helper for the tests: every supported sample passed, and every operator had supported samples."""
+    problems = []
+    for name, r in sorted(report.items()):
+        if r["supported"] == 0:
+            problems.append("%s: no supported sample out of %d" % (name, r["samples"]))
+        problems.extend(r["failures"])
+    assert not problems, "%d problems\n%s\n\n%s" % (len(problems), "\n".join(p[:400] for p in problems[:40]), summarise(report))
+
+
+if __name__ == "__main__":
+    import warnings
+    warnings.filterwarnings("ignore")
+    which = sys.argv[1] if len(sys.argv) > 1 else "oracle"
+    rep = sweep(LibraryBackend() if which == "library" else OracleBackend())
+    print(summarise(rep))
+    tot = [sum(r[k] for r in rep.values()) for k in ("samples", "supported", "passed")]
+    print("total: %d samples, %d supported, %d passed, %d operators" % (tot[0], tot[1], tot[2], len(rep)))
+    for r in rep.values():
+        for f in r["failures"]:
+            print("FAIL", f[:400])

@@ -79,12 +79,30 @@ def test_index_add_other_dims_views_and_aten():
     assert O.index_add_(z.clone(), 0, torch.tensor([0]), torch.tensor(3.0), alpha=2).item() == 8.0
 
 
+def test_index_add_bool_is_or_with_alpha():
+    s = torch.tensor([[True, False, False], [False, False, False]])
+    src = torch.tensor([[False, True, False], [True, True, False], [False, False, False]])
+    idx = torch.tensor([1, 1, 0])
+    assert O.index_add_(s.clone(), 0, idx, src).tolist() == [[True, False, False], [True, True, False]]
+    assert O.index_add_(s.clone(), 0, idx, src, alpha=False).tolist() == s.tolist()
+    assert torch.equal(O.index_add_(s.clone(), 0, idx, src, alpha=True), torch.index_add(s, 0, idx, src, alpha=True))
+
+
+def test_gather_zero_dim_counts_as_one_dim():
+    x = torch.tensor(7.5)
+    assert O.gather(x, 0, torch.tensor([0])).tolist() == [7.5]
+    assert O.gather(torch.tensor([1.0, 2.0]), 0, torch.tensor(1)).item() == 2.0
+    assert torch.equal(O.gather(x, 0, torch.tensor([0])), torch.gather(x, 0, torch.tensor([0])))
+    with pytest.raises(O.OracleError):
+        O.gather(x, 0, torch.tensor([[0]]))
+
+
 def test_index_add_errors():
     s, src, idx = torch.zeros(4, 3), torch.zeros(2, 3), torch.tensor([0, 3])
     for args, kind in (((s, 0, torch.tensor([0, 4]), src), "index"), ((s, 0, torch.tensor([-1, 0]), src), "index"),
                        ((s, 0, idx, torch.zeros(3, 3)), "shape"), ((s, 0, idx, torch.zeros(2, 4)), "shape"),
                        ((s, 2, idx, src), "dim"), ((s, 0, idx.float(), src), "dtype"), ((s, 0, idx, src.double().float().long()), "dtype"),
-                       ((s.bool(), 0, idx, src.bool()), "dtype"), ((s, 0, idx.view(1, 2), src), "shape"),
+                       ((s, 0, idx.view(1, 2), src), "shape"),
                        ((s.long(), 0, idx, src.long(), 0.5), "scalar")):
         with pytest.raises(O.OracleError) as e:
             O.index_add_(args[0].clone(), *args[1:])

@@ -369,8 +369,11 @@ def test_logsumexp_invariants_and_special_values():
     assert math.isnan(O.reduce("logsumexp", torch.tensor([1.0, nan, inf])).item())
     assert math.isnan(O.reduce("logsumexp", torch.tensor([inf, -inf, nan])).item())
     assert O.reduce("logsumexp", torch.zeros((2, 0)), 1).tolist() == [-inf, -inf]     # empty sum: log 0
-    with pytest.raises(O.OracleError):
-        O.reduce("logsumexp", torch.tensor([1, 2]))
+    # bool / integer input is converted to fp32 (as the ATen CPU operator does): log(e^1 + e^2), log(e^1 + e^0)
+    r = O.reduce("logsumexp", torch.tensor([1, 2]))
+    assert r.dtype == torch.float32 and r.item() == torch.tensor(math.log(math.e + math.e ** 2), dtype=torch.float64).float().item()
+    r = O.reduce("logsumexp", torch.tensor([True, False]))
+    assert r.dtype == torch.float32 and r.item() == torch.tensor(math.log(math.e + 1.0), dtype=torch.float64).float().item()
     y = I.normal((4, 6, 5), 2.0, seed=542)
     for dims in (0, (0, 2), None):
         ref = torch.logsumexp(y.double(), dims if dims is not None else (0, 1, 2)).float()
