@@ -23,9 +23,7 @@ MiB = 1 << 20
 # HBM bytes per launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE; the text summary under
 # profiles/ has the commands and the copy calibration: bytes = 2.0 x FETCH_SIZE KiB + 1.0 x WRITE_SIZE KiB).  An entry
 # is valid only for the kernel version it was measured on: remove it when that kernel changes.
-PMC_TRAFFIC_BYTES = {
-    "index_select_f32": (2 * 2122607 + 4194434) * 1024,
-}
+PMC_TRAFFIC_BYTES = {"index_select_f32": (2 * 2122814 + 4194435) * 1024}
 
 
 def build_ops(torch, B):
@@ -310,15 +308,19 @@ def cpu_baseline(torch):
     items.append((65536 * (1024 + 8) + 2 * 4096 * 1024, lambda: O.scatter_add_(dst, 0, rows.unsqueeze(1).expand(65536, 256), src)))
     m = I.bernoulli_mask((65536, 256), 0.3, seed=4)
     items.append((65536 * 256 * 9, lambda: O.masked_fill(src, m, -1.0)))
-    total_bytes = 0
+    # passes over the sample until about 10 s of CPU work are on the clock (the sample itself takes well under a second
+    # on 16 cores, too little to time)
+    total_bytes, passes = 0, 0
     t0 = time.perf_counter()
-    for nbytes, fn in items:
-        fn()
-        total_bytes += nbytes
+    while passes < 400 and time.perf_counter() - t0 < 10.0:
+        for nbytes, fn in items:
+            fn()
+            total_bytes += nbytes
+        passes += 1
     dt = time.perf_counter() - t0
     return {"value": total_bytes / dt / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
-            "seconds": round(dt, 3),
-            "sample": "one pass of the CPU oracle over 11 operators of the step at 1/8-1/64 of the workload sizes "
+            "seconds": round(dt, 3), "passes": passes,
+            "sample": "repeated passes (about 10 s) of the CPU oracle over 11 operators of the step at 1/8-1/64 of the workload sizes "
                       "(broadcast add full size; exp/add on [1024,8192]; sums on [8,4096,1024]; softmax [2048,4096]; "
                       "cumsum [256,65536]; index_select 262144 rows; scatter_add 65536 rows; masked_fill [65536,256])"}
 
