@@ -1352,6 +1352,211 @@ int orc_scatter_add(const orc_tensor* self, int64_t dim, const orc_tensor* index
   return ORC_OK;
 }
 
+// scatter_reduce_ (in place on self): every position p of index sends src[p] to self[p with coordinate dim =
+// index[p]], where the values that arrive are combined with the element's own value by `reduce`:
+//   0 sum, 1 prod, 2 mean, 3 amax, 4 amin.
+// include_self == 0: an element that receives at least one value starts from the values alone (its old content is
+// dropped); elements that receive nothing always keep their bits.  Shapes and dtypes as scatter_add_; bool is refused.
+//   sum / prod : integers wrap; floats accumulate in binary64 in position order, one rounding.
+//   mean       : (sum of the values [+ self]) / (their number [+ 1]); integers divide rounding toward -infinity;
+//                floats in binary64, one rounding.
+//   amax / amin: the largest / smallest; a NaN among the values (or in self when it is included) gives NaN.
+int orc_scatter_reduce(const orc_tensor* self, int64_t dim, const orc_tensor* index, const orc_tensor* src, int reduce,
+                       int include_self) {
+  int rc;
+  if ((rc = check_tensor(self)) || (rc = check_tensor(index)) || (rc = check_tensor(src))) return rc;
+  if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
+  if (self->dtype != src->dtype || self->dtype == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (reduce < 0 || reduce > 4) return ORC_ERR_SCALAR;
+  if (index->ndim != self->ndim || src->ndim != self->ndim) return ORC_ERR_SHAPE;
+  const int nd = self->ndim;
+  int lim = nd == 0 ? 1 : nd;
+  if (dim < -lim || dim >= lim) return ORC_ERR_DIM;
+  if (dim < 0) dim += lim;
+  for (int d = 0; d < nd; ++d) {
+    if (index->sizes[d] > src->sizes[d]) return ORC_ERR_SHAPE;
+    if (d != dim && index->sizes[d] > self->sizes[d]) return ORC_ERR_SHAPE;
+  }
+  const int64_t n = numel(index);
+  if (n == 0) return ORC_OK;
+  const int64_t extent = nd == 0 ? 1 : self->sizes[dim];
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, index->sizes, idx);
+    int64_t k = load_int(index, offset_of(index, idx));
+    if (k < 0 || k >= extent) return ORC_ERR_INDEX;
+  }
+  const bool flt = is_float(self->dtype);
+  const int64_t nself = numel(self);
+  int64_t lstr[ORC_MAX_DIMS];
+  { int64_t st = 1; for (int d = nd - 1; d >= 0; --d) { lstr[d] = st; st *= self->sizes[d]; } }
+  // per destination element (logical index): number of values, and their running combination
+  std::vector<int64_t> cnt((size_t)nself, 0);
+  std::vector<double> accd;
+  std::vector<int64_t> acci;
+  if (flt) accd.assign((size_t)nself, 0.0); else acci.assign((size_t)nself, 0);
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, nd, index->sizes, idx);
+    const int64_t k = load_int(index, offset_of(index, idx));
+    const int64_t so = offset_of(src, idx);
+    if (nd) idx[dim] = k;
+    int64_t l = 0;
+    for (int d = 0; d < nd; ++d) l += idx[d] * lstr[d];
+    const bool first = cnt[(size_t)l]++ == 0;
+    if (flt) {
+      const double v = load_flt(src, so);
+      double& a = accd[(size_t)l];
+      if (first) a = v;
+      else switch (reduce) {
+        case 0: case 2: a += v; break;
+        case 1: a *= v; break;
+        case 3: a = (std::isnan(a) || std::isnan(v)) ? kNaN : (v > a ? v : a); break;
+        case 4: a = (std::isnan(a) || std::isnan(v)) ? kNaN : (v < a ? v : a); break;
+      }
+    } else {
+      const int64_t v = load_int(src, so);
+      int64_t& a = acci[(size_t)l];
+      if (first) a = v;
+      else switch (reduce) {
+        case 0: case 2: a = (int64_t)((uint64_t)a + (uint64_t)v); break;
+        case 1: a = (int64_t)((uint64_t)a * (uint64_t)v); break;
+        case 3: a = v > a ? v : a; break;
+        case 4: a = v < a ? v : a; break;
+      }
+      if (self->dtype == ORC_I32) a = (int64_t)(int32_t)(uint32_t)(uint64_t)a;      // int32 arithmetic wraps at 32 bits
+    }
+  }
+  for (int64_t l = 0; l < nself; ++l) {
+    if (!cnt[(size_t)l]) continue;
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(l, nd, self->sizes, idx);
+    const int64_t d_o = offset_of(self, idx);
+    const int64_t c = cnt[(size_t)l] + (include_self ? 1 : 0);
+    if (flt) {
+      double a = accd[(size_t)l];
+      if (include_self) {
+        const double s0 = load_flt(self, d_o);
+        switch (reduce) {
+          case 0: case 2: a += s0; break;
+          case 1: a *= s0; break;
+          case 3: a = (std::isnan(a) || std::isnan(s0)) ? kNaN : (s0 > a ? s0 : a); break;
+          case 4: a = (std::isnan(a) || std::isnan(s0)) ? kNaN : (s0 < a ? s0 : a); break;
+        }
+      }
+      if (reduce == 2) a /= (double)c;
+      store_flt(self, d_o, a);
+    } else {
+      int64_t a = acci[(size_t)l];
+      if (include_self) {
+        const int64_t s0 = load_int(self, d_o);
+        switch (reduce) {
+          case 0: case 2: a = (int64_t)((uint64_t)a + (uint64_t)s0); break;
+          case 1: a = (int64_t)((uint64_t)a * (uint64_t)s0); break;
+          case 3: a = s0 > a ? s0 : a; break;
+          case 4: a = s0 < a ? s0 : a; break;
+        }
+        if (self->dtype == ORC_I32) a = (int64_t)(int32_t)(uint32_t)(uint64_t)a;
+      }
+      if (reduce == 2) {                                 // floor division
+        int64_t q = a / c;
+        if ((a % c != 0) && ((a < 0) != (c < 0))) --q;
+        a = q;
+      }
+      store_int(self, d_o, a);
+    }
+  }
+  return ORC_OK;
+}
+
+// index_put_ (in place on self): `nidx` index tensors address the first nidx dims of self.  They broadcast together
+// to a shape I; values has shape I + self.shape[nidx:] (or broadcasts to it).  For every position p of I and every
+// coordinate r of the remaining dims: self[idx_0[p], ..., idx_{k-1}[p], r] = values[p, r], or += when accumulate.
+// Negative indices count from the end.  accumulate: integers wrap (bool: OR); floats gather each destination's
+// values in position order in binary64, add the old content, round once.  Without accumulate, when several positions
+// name one destination the LAST in position order is kept here (the operator itself leaves the winner undefined).
+int orc_index_put(const orc_tensor* self, const orc_tensor* const* indices, int32_t nidx, const orc_tensor* values,
+                  int accumulate) {
+  int rc;
+  if ((rc = check_tensor(self)) || (rc = check_tensor(values))) return rc;
+  if (nidx < 1 || nidx > self->ndim) return ORC_ERR_DIM;
+  for (int j = 0; j < nidx; ++j) {
+    if (!indices || (rc = check_tensor(indices[j]))) return rc ? rc : ORC_ERR_NULL;
+    if (!index_dtype_ok(indices[j]->dtype)) return ORC_ERR_DTYPE;
+  }
+  if (values->dtype != self->dtype) return ORC_ERR_DTYPE;
+  int ind;
+  int64_t ishape[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(indices, nidx, &ind, ishape))) return rc;
+  const int rest = self->ndim - nidx;
+  if (ind + rest > ORC_MAX_DIMS) return ORC_ERR_NDIM;
+  // the full shape values must broadcast to: I + remaining dims of self
+  int64_t vshape[ORC_MAX_DIMS];
+  const int vnd = ind + rest;
+  for (int d = 0; d < ind; ++d) vshape[d] = ishape[d];
+  for (int d = 0; d < rest; ++d) vshape[ind + d] = self->sizes[nidx + d];
+  if (values->ndim > vnd) return ORC_ERR_SHAPE;
+  for (int d = 0; d < values->ndim; ++d) {
+    const int64_t vs = values->sizes[d], ts = vshape[vnd - values->ndim + d];
+    if (vs != ts && vs != 1) return ORC_ERR_SHAPE;
+  }
+  int64_t n = 1;
+  for (int d = 0; d < vnd; ++d) n *= vshape[d];
+  // validate (and wrap) every index first
+  int64_t npos = 1;
+  for (int d = 0; d < ind; ++d) npos *= ishape[d];
+  for (int64_t p = 0; p < npos; ++p) {
+    int64_t pidx[ORC_MAX_DIMS] = {0};
+    unravel(p, ind, ishape, pidx);
+    for (int j = 0; j < nidx; ++j) {
+      const int64_t k = load_int(indices[j], bcast_offset(indices[j], ind, pidx));
+      if (k < -self->sizes[j] || k >= self->sizes[j]) return ORC_ERR_INDEX;
+    }
+  }
+  const bool flt = is_float(self->dtype);
+  const int64_t nself = numel(self);
+  int64_t lstr[ORC_MAX_DIMS];
+  { int64_t st = 1; for (int d = self->ndim - 1; d >= 0; --d) { lstr[d] = st; st *= self->sizes[d]; } }
+  std::vector<double> acc;
+  std::vector<uint8_t> touched;
+  if (flt && accumulate) { acc.assign((size_t)nself, 0.0); touched.assign((size_t)nself, 0); }
+  const int es = esize(self->dtype);
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t vidx[ORC_MAX_DIMS] = {0};
+    unravel(lin, vnd, vshape, vidx);
+    int64_t sidx[ORC_MAX_DIMS] = {0};
+    for (int j = 0; j < nidx; ++j) {
+      int64_t k = load_int(indices[j], bcast_offset(indices[j], ind, vidx));
+      sidx[j] = k < 0 ? k + self->sizes[j] : k;
+    }
+    for (int d = 0; d < rest; ++d) sidx[nidx + d] = vidx[ind + d];
+    const int64_t d_o = offset_of(self, sidx);
+    const int64_t vo = bcast_offset(values, vnd, vidx);
+    if (!accumulate) {
+      std::memcpy(mptr(self, d_o), cptr(values, vo), es);
+    } else if (flt) {
+      int64_t l = 0;
+      for (int d = 0; d < self->ndim; ++d) l += sidx[d] * lstr[d];
+      acc[(size_t)l] += load_flt(values, vo);
+      touched[(size_t)l] = 1;
+    } else if (self->dtype == ORC_BOOL) {
+      store_int(self, d_o, load_int(self, d_o) | load_int(values, vo));
+    } else {
+      store_int(self, d_o, (int64_t)((uint64_t)load_int(self, d_o) + (uint64_t)load_int(values, vo)));
+    }
+  }
+  if (flt && accumulate) {
+    for (int64_t l = 0; l < nself; ++l) {
+      if (!touched[(size_t)l]) continue;
+      int64_t idx[ORC_MAX_DIMS] = {0};
+      unravel(l, self->ndim, self->sizes, idx);
+      const int64_t d_o = offset_of(self, idx);
+      store_flt(self, d_o, load_flt(self, d_o) + acc[(size_t)l]);
+    }
+  }
+  return ORC_OK;
+}
+
 // index_add_ (in place on self): for every i, self[..., index[i], ...] += alpha * source[..., i, ...] along `dim`.
 // index is 1-D (or 0-dim) int32 / int64 with source.size(dim) entries in [0, self.size(dim)); source has self's
 // shape except along dim; both have the same dtype.  Integers: exact wrapping arithmetic, alpha must be integral;

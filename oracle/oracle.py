@@ -70,6 +70,8 @@ def lib():
         _lib.orc_scatter_add.argtypes = [P, ctypes.c_int64, P, P]
         _lib.orc_index_add.argtypes = [P, ctypes.c_int64, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
         _lib.orc_take.argtypes = [P, P, P]
+        _lib.orc_scatter_reduce.argtypes = [P, ctypes.c_int64, P, P, ctypes.c_int, ctypes.c_int]
+        _lib.orc_index_put.argtypes = [P, ctypes.POINTER(P), ctypes.c_int32, P, ctypes.c_int]
         _lib.orc_masked_select.argtypes = [P, P, P, I64P]
         _lib.orc_nonzero.argtypes = [P, P, I64P]
         _lib.orc_infer_binary.argtypes = [ctypes.c_int, P, P, I32P, I32P, I64P]
@@ -271,6 +273,21 @@ def scatter_add_(self, dim, index, src):
 def index_add_(self, dim, index, source, alpha=1):
     af, ai, isint = _scalar(alpha)
     _check(lib().orc_index_add(desc(self), dim, desc(index), desc(source), af, ai, isint))
+    return self
+
+
+SCATTER_REDUCE = {"sum": 0, "prod": 1, "mean": 2, "amax": 3, "amin": 4}
+
+
+def scatter_reduce_(self, dim, index, src, reduce, include_self=True):
+    _check(lib().orc_scatter_reduce(desc(self), dim, desc(index), desc(src), SCATTER_REDUCE.get(reduce, 9), int(include_self)))
+    return self
+
+
+def index_put_(self, indices, values, accumulate=False):
+    ds = [desc(i) for i in indices]
+    arr = (ctypes.POINTER(OrcTensor) * max(1, len(ds)))(*[ctypes.pointer(d) for d in ds])
+    _check(lib().orc_index_put(desc(self), arr, len(ds), desc(values), int(accumulate)))
     return self
 
 
