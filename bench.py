@@ -260,6 +260,17 @@ def build_ops(torch, B):
     wsia = B.workspace(B.tx_index_add_workspace_bytes(dst_f, 0, rows, src, True))
     extra("index_add_f32_rows_alpha", "f3", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
           lambda: B.tx_index_add_(dst_f, 0, rows, src, 0.5, True, wsia))
+    NR = 131072                                      # element-wise paths: one sort entry per element, so a smaller source
+    eidx_r = eidx[:NR]
+    wssr = B.workspace(B.tx_scatter_reduce_workspace_bytes(dst_f, 0, eidx_r, src[:NR], "amax", True))
+    extra("scatter_reduce_amax_f32[131072,256]", "f3", "seg_reduce_kernel", NR * W * (4 + 8 + 8), NR * W,
+          lambda: B.tx_scatter_reduce_(dst_f, 0, eidx_r, src[:NR], "amax", True, wssr))
+    wsip = B.workspace(B.tx_index_put_workspace_bytes(dst_f, [rows[:NR]], src[:NR], True))
+    extra("index_put_accumulate_f32_rows[131072,256]", "f3", "seg_rows_kernel", NR * (W * 4 + 8) + 2 * ND * W * 4, NR * W,
+          lambda: B.tx_index_put_(dst_f, [rows[:NR]], src[:NR], True, wsip))
+    prm = torch.randperm(ND, device=dev, generator=g)
+    extra("index_put_assign_f32_rows[65536,256]", "f3", "index_put_kernel", ND * (W * 8 + 8), ND * W,
+          lambda: B.tx_index_put_(dst_f, [prm], src[:ND], False, None))
     flat = src.view(-1)
     tidx = torch.randint(-flat.numel(), flat.numel(), (16384 * W,), device=dev, dtype=I64, generator=g)
     otake = ogat.view(-1)

@@ -292,6 +292,39 @@ tx_status tx_index_add_(const tx_tensor* self, int64_t dim, const tx_tensor* ind
 size_t tx_index_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source,
                                     int deterministic);
 
+enum { TX_SCATTER_SUM = 0, TX_SCATTER_PROD = 1, TX_SCATTER_MEAN = 2, TX_SCATTER_AMAX = 3, TX_SCATTER_AMIN = 4 };
+
+/* In place: every position p of index sends src[p] to self[p with coordinate
+ * dim = index[p]]; the values that arrive at an element are combined by
+ * `reduce` (TX_SCATTER_*; another code is TX_ERR_SCALAR) with each other and,
+ * when include_self != 0, with the element's own value.  Elements that receive
+ * nothing keep their bits.  Shapes and dtypes as tx_scatter_add_; bool: SUM
+ * and AMAX are OR, PROD and AMIN are AND, MEAN is TX_ERR_DTYPE.  Integers wrap, MEAN divides rounding toward -infinity; floats
+ * are combined in binary64 in position order and rounded once; AMAX / AMIN give
+ * NaN when a NaN takes part.  Always the sorted path (reproducible run to run):
+ * needs a 16-byte aligned workspace of tx_scatter_reduce_workspace_bytes(). */
+tx_status tx_scatter_reduce_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src, int reduce,
+                             int include_self, void* ws, size_t ws_bytes, void* stream);
+size_t tx_scatter_reduce_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
+                                         int reduce, int include_self);
+
+/* In place: `nidx` index tensors (int32 / int64; 1 <= nidx <= self.ndim, else
+ * TX_ERR_DIM) address the first nidx dims of self; they broadcast together to a
+ * shape I, and values (self's dtype) broadcasts to I + self.shape[nidx:].  For
+ * every position p of I and coordinate r of the remaining dims,
+ * self[idx_0[p], ..., idx_{nidx-1}[p], r] = values[p, r], or += when
+ * accumulate != 0.  Negative indices count from the end; indices are not
+ * range-checked on the device.  `indices` is a host array of descriptor
+ * pointers.  accumulate = 0: when several positions name one element, which of
+ * them is kept is unspecified.  accumulate != 0: integers / bool use device
+ * atomics (exact); floats sort the destinations and sum each in position order
+ * (binary64, reproducible) and need a 16-byte aligned workspace of
+ * tx_index_put_workspace_bytes() (0 otherwise). */
+tx_status tx_index_put_(const tx_tensor* self, const tx_tensor* const* indices, int32_t nidx, const tx_tensor* values,
+                        int accumulate, void* ws, size_t ws_bytes, void* stream);
+size_t tx_index_put_workspace_bytes(const tx_tensor* self, const tx_tensor* const* indices, int32_t nidx,
+                                    const tx_tensor* values, int accumulate);
+
 /* out[p] = input, read as a 1-D tensor in logical (row-major) order whatever
  * its strides, at index[p]; negative indices count from the end.  out has
  * index's shape and input's dtype; index is int32 / int64.  Indices outside

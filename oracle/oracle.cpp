@@ -1356,7 +1356,8 @@ int orc_scatter_add(const orc_tensor* self, int64_t dim, const orc_tensor* index
 // index[p]], where the values that arrive are combined with the element's own value by `reduce`:
 //   0 sum, 1 prod, 2 mean, 3 amax, 4 amin.
 // include_self == 0: an element that receives at least one value starts from the values alone (its old content is
-// dropped); elements that receive nothing always keep their bits.  Shapes and dtypes as scatter_add_; bool is refused.
+// dropped); elements that receive nothing always keep their bits.  Shapes and dtypes as scatter_add_.  bool: sum and
+// amax are OR, prod and amin are AND, mean is refused.
 //   sum / prod : integers wrap; floats accumulate in binary64 in position order, one rounding.
 //   mean       : (sum of the values [+ self]) / (their number [+ 1]); integers divide rounding toward -infinity;
 //                floats in binary64, one rounding.
@@ -1366,8 +1367,9 @@ int orc_scatter_reduce(const orc_tensor* self, int64_t dim, const orc_tensor* in
   int rc;
   if ((rc = check_tensor(self)) || (rc = check_tensor(index)) || (rc = check_tensor(src))) return rc;
   if (!index_dtype_ok(index->dtype)) return ORC_ERR_DTYPE;
-  if (self->dtype != src->dtype || self->dtype == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (self->dtype != src->dtype) return ORC_ERR_DTYPE;
   if (reduce < 0 || reduce > 4) return ORC_ERR_SCALAR;
+  if (self->dtype == ORC_BOOL && reduce == 2) return ORC_ERR_DTYPE;   // no mean of bools
   if (index->ndim != self->ndim || src->ndim != self->ndim) return ORC_ERR_SHAPE;
   const int nd = self->ndim;
   int lim = nd == 0 ? 1 : nd;

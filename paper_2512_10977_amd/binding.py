@@ -31,7 +31,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so
 
 EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
            "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
-           "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_take", "tx_masked_select",
+           "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
+           "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_masked_select",
            "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
 
@@ -90,6 +91,10 @@ def lib():
         "tx_index_add_": ([P, ctypes.c_int64, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, ctypes.c_int, V,
                            ctypes.c_size_t, V], ctypes.c_int32),
         "tx_index_add_workspace_bytes": ([P, ctypes.c_int64, P, P, ctypes.c_int], ctypes.c_size_t),
+        "tx_scatter_reduce_": ([P, ctypes.c_int64, P, P, ctypes.c_int, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_scatter_reduce_workspace_bytes": ([P, ctypes.c_int64, P, P, ctypes.c_int, ctypes.c_int], ctypes.c_size_t),
+        "tx_index_put_": ([P, ctypes.POINTER(P), ctypes.c_int32, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_index_put_workspace_bytes": ([P, ctypes.POINTER(P), ctypes.c_int32, P, ctypes.c_int], ctypes.c_size_t),
         "tx_take": ([P, P, P, V], ctypes.c_int32),
         "tx_masked_select": ([P, P, P, P, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_masked_select_workspace_bytes": ([P, P, P, P], ctypes.c_size_t),
@@ -202,6 +207,37 @@ def tx_index_add_(self, dim, index, source, alpha=1, deterministic=True, ws=None
     p, n = _ws(ws)
     _check(lib().tx_index_add_(desc(self), dim, desc(index), desc(source), af, ai, isint, int(deterministic), p, n,
                                _stream(stream)))
+
+
+SCATTER_REDUCE = {"sum": 0, "prod": 1, "mean": 2, "amax": 3, "amin": 4}
+
+
+def tx_scatter_reduce_workspace_bytes(self, dim, index, src, reduce, include_self=True):
+    return lib().tx_scatter_reduce_workspace_bytes(desc(self), dim, desc(index), desc(src), SCATTER_REDUCE.get(reduce, 9),
+                                                   int(include_self))
+
+
+def tx_scatter_reduce_(self, dim, index, src, reduce, include_self=True, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tx_scatter_reduce_(desc(self), dim, desc(index), desc(src), SCATTER_REDUCE.get(reduce, 9), int(include_self),
+                                    p, n, _stream(stream)))
+
+
+def _desc_list(tensors):
+    ds = [desc(t) for t in tensors]            # kept alive by the returned tuple
+    arr = (ctypes.POINTER(TxTensor) * max(1, len(ds)))(*[ctypes.pointer(d) for d in ds])
+    return arr, ds
+
+
+def tx_index_put_workspace_bytes(self, indices, values, accumulate=False):
+    arr, keep = _desc_list(indices)
+    return lib().tx_index_put_workspace_bytes(desc(self), arr, len(keep), desc(values), int(accumulate))
+
+
+def tx_index_put_(self, indices, values, accumulate=False, ws=None, stream=None):
+    arr, keep = _desc_list(indices)
+    p, n = _ws(ws)
+    _check(lib().tx_index_put_(desc(self), arr, len(keep), desc(values), int(accumulate), p, n, _stream(stream)))
 
 
 def tx_take(out, input, index, stream=None):

@@ -54,6 +54,7 @@ struct ElemArgs {
   int64_t dstride[TX_MAX_DIMS];    // destination strides
   float alpha_f;                   // scatter / index_add: multiplier of the source (floating dtypes)
   int64_t alpha_i;                 // the same for integer dtypes (wrapping); bool: zero or not
+  int64_t wrap;                    // scatter: added to a negative index (0: indices are never negative)
 };
 
 // alpha * v in the arithmetic of T (sums are linear, so the sorted paths scale a whole sum once)
@@ -187,7 +188,8 @@ __global__ __launch_bounds__(kBlock) void scatter_add_atomic_kernel(const ElemAr
     so += (int64_t)m * a.sstride[d];
     if (d != a.dim) d_o += (int64_t)m * a.dstride[d];
   }
-  const int64_t k = load_index(a.index, io, a.index_is64);
+  int64_t k = load_index(a.index, io, a.index_is64);
+  k += k < 0 ? a.wrap : 0;
   d_o += k * a.dstride[a.dim];
   atomic_accumulate<T>((T*)a.dst + d_o, scaled<T, T>(((const T*)a.src)[so], a.alpha_f, a.alpha_i));
 }
@@ -212,17 +214,21 @@ __global__ __launch_bounds__(kBlock) void scatter_keys_kernel(const ElemArgs a, 
     io += (int64_t)m * a.istride[d];
     if (d != a.dim) d_o += (int64_t)m * a.dstride[d];
   }
-  d_o += load_index(a.index, io, a.index_is64) * a.dstride[a.dim];
+  int64_t k = load_index(a.index, io, a.index_is64);
+  k += k < 0 ? a.wrap : 0;
+  d_o += k * a.dstride[a.dim];
   keys[lin] = (uint32_t)d_o;
   vals[lin] = (uint32_t)lin;
 }
 // keys for the row mode: the row id of every source row
 __global__ __launch_bounds__(kBlock) void row_keys_kernel(const char* index, int is64, int64_t istride, int64_t n,
-                                                          uint32_t* keys, uint32_t* vals, unsigned int* counter) {
+                                                          uint32_t* keys, uint32_t* vals, unsigned int* counter, int64_t wrap) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (i == 0 && counter) *counter = 0u;      // start-list length for the row-mode combine pass
   if (i >= n) return;
-  keys[i] = (uint32_t)load_index(index, i * istride, is64);
+  int64_t k = load_index(index, i * istride, is64);
+  k += k < 0 ? wrap : 0;
+  keys[i] = (uint32_t)k;
   vals[i] = (uint32_t)i;
 }
 
@@ -359,6 +365,118 @@ __global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, 
   }
   T* dst = (T*)a.dst + k;
   *dst = cvt<T>((float)(cvt<double>(*dst) + (double)a.alpha_f * acc));
+}
+
+// scatter_reduce_, every mode: the first entry of each run of equal keys combines the run in position order
+// (binary64 for floats, wrapping 64-bit for integers), then with the element's own value when it is included.
+enum { kRedSum = 0, kRedProd = 1, kRedMean = 2, kRedAmax = 3, kRedAmin = 4 };
+template <class T>
+__global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
+                                                            const ElemArgs a, int mode, int include_self) {
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= n) return;
+  const uint32_t k = keys[j];
+  if (j > 0 && keys[j - 1] == k) return;
+  using A = typename std::conditional<std::is_integral<T>::value, int64_t, double>::type;
+  auto combine = [&](A x, A v) -> A {
+    if constexpr (std::is_integral<T>::value) {
+      switch (mode) {
+        case kRedProd: return (A)((uint64_t)x * (uint64_t)v);
+        case kRedAmax: return v > x ? v : x;
+        case kRedAmin: return v < x ? v : x;
+        default: return (A)((uint64_t)x + (uint64_t)v);
+      }
+    } else {
+      switch (mode) {
+        case kRedProd: return x * v;
+        case kRedAmax: return (x != x || v != v) ? (A)__builtin_nan("") : (v > x ? v : x);
+        case kRedAmin: return (x != x || v != v) ? (A)__builtin_nan("") : (v < x ? v : x);
+        default: return x + v;
+      }
+    }
+  };
+  A acc = A(0);
+  int64_t count = 0;
+  for (int64_t e = j; e < n && keys[e] == k; ++e, ++count) {
+    int64_t so = 0;
+    uint32_t rem = vals[e];
+    for (int d = a.shape.n - 1; d >= 0; --d) {
+      uint32_t q, m;
+      a.shape.div[d].divmod(rem, q, m);
+      rem = q;
+      so += (int64_t)m * a.sstride[d];
+    }
+    const A v = cvt<A>(((const T*)a.src)[so]);
+    acc = count ? combine(acc, v) : v;
+  }
+  T* dst = (T*)a.dst + k;
+  if (include_self) {
+    acc = combine(acc, cvt<A>(*dst));
+    ++count;
+  }
+  if constexpr (std::is_integral<T>::value) {
+    if constexpr (std::is_same<T, uint8_t>::value) acc = acc != 0;     // bool: a sum of ones is an OR
+    else acc = (A)(T)acc;                              // int32 arithmetic wraps at 32 bits (before a mean divides)
+    if (mode == kRedMean) {                            // rounding toward -infinity
+      A q = acc / count;
+      if (acc % count != 0 && acc < 0) --q;
+      acc = q;
+    }
+    *dst = (T)acc;
+  } else {
+    if (mode == kRedMean) acc /= (double)count;
+    *dst = cvt<T>((float)acc);                         // binary64 -> fp32 -> T: T is fp32 or narrower
+  }
+}
+
+// index_put_: one lane per element of the value shape I + rest.  MODE 0 assigns, 1 accumulates with an atomic
+// (integers, bool), 2 only records the destination element offset as a sort key.
+struct PutArgs {
+  Dims shape;                        // I (the broadcast index shape) followed by the dims of self that are not indexed
+  int nidx, ind;                     // index tensors; rank of I
+  const char* index[TX_MAX_DIMS];
+  int is64[TX_MAX_DIMS];
+  int64_t istride[TX_MAX_DIMS][TX_MAX_DIMS];   // [index tensor][dim of I], 0 where it broadcasts
+  int64_t extent[TX_MAX_DIMS];       // self.size(j) of the indexed dims (negative indices wrap)
+  int64_t dstride_idx[TX_MAX_DIMS];  // self.stride(j) of the indexed dims
+  int64_t dstride[TX_MAX_DIMS];      // per dim of `shape`: self's stride for the rest dims, 0 for the dims of I
+  int64_t vstride[TX_MAX_DIMS];      // values' strides over `shape` (0 where it broadcasts)
+  const char* src;
+  char* dst;
+  uint32_t* keys;
+  uint32_t* vals;
+};
+
+template <class T, int MODE>
+__global__ __launch_bounds__(kBlock) void index_put_kernel(const PutArgs a) {
+  const int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (lin >= a.shape.numel) return;
+  int64_t coord[TX_MAX_DIMS];
+  int64_t vo = 0, d_o = 0;
+  uint32_t rem = (uint32_t)lin;
+  for (int d = a.shape.n - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.shape.div[d].divmod(rem, q, m);
+    rem = q;
+    coord[d] = m;
+    vo += (int64_t)m * a.vstride[d];
+    d_o += (int64_t)m * a.dstride[d];
+  }
+  for (int j = 0; j < a.nidx; ++j) {
+    int64_t io = 0;
+    for (int d = 0; d < a.ind; ++d) io += coord[d] * a.istride[j][d];
+    int64_t k = load_index(a.index[j], io, a.is64[j]);
+    k += k < 0 ? a.extent[j] : 0;
+    d_o += k * a.dstride_idx[j];
+  }
+  if constexpr (MODE == 2) {
+    a.keys[lin] = (uint32_t)d_o;
+    a.vals[lin] = (uint32_t)lin;
+  } else if constexpr (MODE == 1) {
+    atomic_accumulate<T>((T*)a.dst + d_o, ((const T*)a.src)[vo]);
+  } else {
+    ((T*)a.dst)[d_o] = ((const T*)a.src)[vo];
+  }
 }
 
 constexpr int kChunk = 128;                 // sorted rows per wave
@@ -661,9 +779,10 @@ bool is_row_mode(const tx_tensor* self, int dim, const tx_tensor* index, const t
   return inner >= 16 && index->sizes[0] < (1ll << 31) && self->sizes[0] < (1ll << 32);
 }
 
-tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src, ScatterPlan* p) {
+tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src, ScatterPlan* p,
+                       bool allow_rows = true) {
   memset(p, 0, sizeof(*p));
-  p->row_mode = is_row_mode(self, dim, index, src);
+  p->row_mode = allow_rows && is_row_mode(self, dim, index, src);
   uint64_t max_key;
   if (p->row_mode) {
     p->n = index->sizes[0];
@@ -703,12 +822,14 @@ tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, c
 struct Alpha {
   float f;
   int64_t i;
+  int64_t wrap = 0;        // not a multiplier: the extent added to negative indices (index_put_), carried along
 };
 
 void fill_scatter_elem_args(ElemArgs* a, const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src,
                             Alpha alpha = Alpha{1.0f, 1}) {
   a->alpha_f = alpha.f;
   a->alpha_i = alpha.i;
+  a->wrap = alpha.wrap;
   fill_dims(&a->shape, index->ndim, index->sizes);
   a->dim = dim;
   a->index_is64 = index->dtype == TX_I64;
@@ -759,7 +880,7 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
   if (p.row_mode)
     hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
-                       index->strides[0], p.n, keys0, vals0, (unsigned int*)(ws + p.off_counter));
+                       index->strides[0], p.n, keys0, vals0, (unsigned int*)(ws + p.off_counter), alpha.wrap);
   else
     hipLaunchKernelGGL(scatter_keys_kernel, dim3(nb), dim3(kBlock), 0, s, ea, keys0, vals0);
   int cur;
@@ -882,6 +1003,117 @@ tx_status scatter_core(const char* name, const tx_tensor* self, int d, const tx_
   return check_launch("scatter_add atomic kernel");
 }
 
+// sort plan for n (key, position) pairs whose keys are element offsets inside `self`
+tx_status elem_sort_plan(const char* name, const tx_tensor* self, int64_t n, ScatterPlan* p) {
+  memset(p, 0, sizeof(*p));
+  p->n = n;
+  uintptr_t lo, hi;
+  byte_extent(self, &lo, &hi);
+  const uint64_t extent = (hi - lo) / dtype_size(self->dtype);
+  if (n >= (1ll << 32) || extent >= (1ull << 32))
+    return fail(TX_ERR_UNSUPPORTED, "%s: more than 2^32 positions or destination elements", name);
+  p->passes = (bits_for(extent ? extent - 1 : 0) + 7) / 8;
+  p->nblocks = (int)((n + kSortTile - 1) / kSortTile);
+  size_t o = 0;
+  for (int i = 0; i < 2; ++i) { p->off_keys[i] = o; o = align_up(o + (size_t)n * 4, 256); }
+  for (int i = 0; i < 2; ++i) { p->off_vals[i] = o; o = align_up(o + (size_t)n * 4, 256); }
+  p->off_hist = o; o = align_up(o + (size_t)256 * p->nblocks * 4, 256);
+  p->off_totals = o; o = align_up(o + 256 * 4, 256);
+  p->bytes = o;
+  return TX_OK;
+}
+
+tx_status sort_ws_checks(const char* name, const ScatterPlan& p, void* ws, size_t ws_bytes) {
+  if (!ws || ws_bytes < p.bytes) return fail(TX_ERR_WORKSPACE, "%s needs %zu workspace bytes, got %zu", name, p.bytes, ws_bytes);
+  if ((uintptr_t)ws % 16) return fail(TX_ERR_WORKSPACE, "%s workspace must be 16-byte aligned", name);
+  return TX_OK;
+}
+
+template <class T>
+tx_status scatter_reduce_typed(const ScatterPlan& p, const tx_tensor* self, int d, const tx_tensor* index, const tx_tensor* src,
+                               int mode, int include_self, char* ws, hipStream_t s) {
+  ElemArgs ea;
+  fill_scatter_elem_args(&ea, self, d, index, src);
+  const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
+  hipLaunchKernelGGL(scatter_keys_kernel, dim3(nb), dim3(kBlock), 0, s, ea, (uint32_t*)(ws + p.off_keys[0]),
+                     (uint32_t*)(ws + p.off_vals[0]));
+  int cur;
+  tx_status rc = run_sort(p, ws, s, &cur);
+  if (rc) return rc;
+  set_path("scatter-reduce-sort");
+  hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, (const uint32_t*)(ws + p.off_keys[cur]),
+                     (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea, mode, include_self);
+  return check_launch("scatter_reduce segmented kernel");
+}
+
+// index_put_: checks; fills the kernel arguments (shape I + rest, strides of every operand over it)
+tx_status index_put_checks(const tx_tensor* self, const tx_tensor* const* indices, int32_t nidx, const tx_tensor* values,
+                           PutArgs* a) {
+  tx_status rc;
+  if ((rc = check_tensor(self, "self")) || (rc = check_tensor(values, "values"))) return rc;
+  if (nidx < 1 || nidx > self->ndim) return fail(TX_ERR_DIM, "index_put_: %d index tensors for a %d-dim tensor", nidx, self->ndim);
+  if (!indices) return fail(TX_ERR_NULL, "index_put_: null index list");
+  for (int j = 0; j < nidx; ++j) {
+    if ((rc = check_tensor(indices[j], "index"))) return rc;
+    if (!index_dtype_ok(indices[j]->dtype)) return fail(TX_ERR_DTYPE, "index must be int32 or int64");
+  }
+  if (values->dtype != self->dtype) return fail(TX_ERR_DTYPE, "index_put_: values must have self's dtype");
+  int ind;
+  int64_t ishape[TX_MAX_DIMS];
+  if ((rc = broadcast_shapes(indices, nidx, &ind, ishape))) return rc;
+  const int rest = self->ndim - nidx;
+  if (ind + rest > TX_MAX_DIMS) return fail(TX_ERR_NDIM, "index_put_: index shape plus remaining dims exceed %d dims", TX_MAX_DIMS);
+  int64_t vshape[TX_MAX_DIMS];
+  const int vnd = ind + rest;
+  for (int d = 0; d < ind; ++d) vshape[d] = ishape[d];
+  for (int d = 0; d < rest; ++d) vshape[ind + d] = self->sizes[nidx + d];
+  if (values->ndim > vnd) return fail(TX_ERR_SHAPE, "index_put_: values has too many dims");
+  for (int d = 0; d < values->ndim; ++d) {
+    const int64_t vs = values->sizes[d], ts = vshape[vnd - values->ndim + d];
+    if (vs != ts && vs != 1) return fail(TX_ERR_SHAPE, "index_put_: values does not broadcast to the indexed shape");
+  }
+  if (!no_internal_overlap(self)) return fail(TX_ERR_OVERLAP, "self has overlapping elements");
+  if (partial_overlap(self, values) || (self->data == values->data && numel(values) && numel(self)))
+    return fail(TX_ERR_OVERLAP, "self overlaps values");
+  for (int j = 0; j < nidx; ++j)
+    if (partial_overlap(self, indices[j])) return fail(TX_ERR_OVERLAP, "self overlaps an index");
+  memset(a, 0, sizeof(*a));
+  fill_dims(&a->shape, vnd, vshape);
+  a->nidx = nidx;
+  a->ind = ind;
+  for (int j = 0; j < nidx; ++j) {
+    const tx_tensor* ix = indices[j];
+    a->index[j] = (const char*)ix->data;
+    a->is64[j] = ix->dtype == TX_I64;
+    for (int d = 0; d < ix->ndim; ++d) a->istride[j][ind - ix->ndim + d] = ix->sizes[d] != 1 ? ix->strides[d] : 0;
+    a->extent[j] = self->sizes[j];
+    a->dstride_idx[j] = self->strides[j];
+  }
+  for (int d = 0; d < rest; ++d) a->dstride[ind + d] = self->strides[nidx + d];
+  for (int d = 0; d < values->ndim; ++d) a->vstride[vnd - values->ndim + d] = values->sizes[d] != 1 ? values->strides[d] : 0;
+  a->src = (const char*)values->data;
+  a->dst = (char*)self->data;
+  return TX_OK;
+}
+
+// one 1-D index tensor over dim 0 and values of exactly the shape [n, self.shape[1:]]: accumulation is scatter_add_ with
+// the index broadcast over the trailing dims (whole-row sorted path); `view` is that broadcast index
+bool index_put_as_rows(const tx_tensor* self, const tx_tensor* const* indices, int32_t nidx, const tx_tensor* values,
+                       tx_tensor* view) {
+  if (nidx != 1 || indices[0]->ndim != 1 || values->ndim != self->ndim || self->dtype == TX_BOOL) return false;
+  if (values->sizes[0] != indices[0]->sizes[0]) return false;
+  for (int d = 1; d < self->ndim; ++d)
+    if (values->sizes[d] != self->sizes[d]) return false;
+  view->data = indices[0]->data;
+  view->dtype = indices[0]->dtype;
+  view->ndim = self->ndim;
+  for (int d = 0; d < self->ndim; ++d) {
+    view->sizes[d] = values->sizes[d];
+    view->strides[d] = d == 0 ? indices[0]->strides[0] : 0;
+  }
+  return true;
+}
+
 // index_add_: checks, and the 1-D index presented as a view of source's shape (stride 0 off `dim`)
 tx_status index_add_checks(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source, int alpha_is_int,
                            int* d, tx_tensor* view) {
@@ -938,6 +1170,7 @@ tx_status tx_gather(const tx_tensor* out, const tx_tensor* src, int64_t dim, con
   if (n == 0) return TX_OK;
   if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "gather: more than 2^31 output elements");
   ElemArgs a;
+  memset(&a, 0, sizeof(a));
   fill_dims(&a.shape, index->ndim, index->sizes);
   a.dim = src->ndim ? d : 0;
   a.index_is64 = index->dtype == TX_I64;
@@ -1069,6 +1302,116 @@ tx_status tx_scatter_add_(const tx_tensor* self, int64_t dim, const tx_tensor* i
   if (rc) return rc;
   set_path("");
   return scatter_core("scatter_add_", self, d, index, src, Alpha{1.0f, 1}, deterministic, ws, ws_bytes, as_stream(stream));
+}
+
+size_t tx_scatter_reduce_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
+                                         int reduce, int include_self) {
+  int d;
+  if (scatter_checks(self, dim, index, src, &d) || numel(index) == 0) return 0;
+  if (reduce == TX_SCATTER_SUM && include_self) return scatter_ws_bytes(self, d, index, src, 1);
+  ScatterPlan p;
+  if (elem_sort_plan("scatter_reduce_", self, numel(index), &p)) return 0;
+  return p.bytes;
+}
+
+tx_status tx_scatter_reduce_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src, int reduce,
+                             int include_self, void* ws, size_t ws_bytes, void* stream) {
+  int d;
+  tx_status rc = scatter_checks(self, dim, index, src, &d);
+  if (rc) return rc;
+  if (reduce < TX_SCATTER_SUM || reduce > TX_SCATTER_AMIN) return fail(TX_ERR_SCALAR, "scatter_reduce_: unknown reduction %d", reduce);
+  if (self->dtype == TX_BOOL && reduce == TX_SCATTER_MEAN) return fail(TX_ERR_DTYPE, "scatter_reduce_: no mean of bools");
+  set_path("");
+  const int64_t n = numel(index);
+  if (n == 0) return TX_OK;
+  hipStream_t s = as_stream(stream);
+  // a sum that keeps self is scatter_add_ (sorted, so that it is reproducible)
+  if (reduce == TX_SCATTER_SUM && include_self)
+    return scatter_core("scatter_reduce_", self, d, index, src, Alpha{1.0f, 1}, 1, ws, ws_bytes, s);
+  ScatterPlan p;
+  if ((rc = elem_sort_plan("scatter_reduce_", self, n, &p)) || (rc = sort_ws_checks("scatter_reduce_", p, ws, ws_bytes))) return rc;
+  switch (self->dtype) {
+    case TX_F32: return scatter_reduce_typed<float>(p, self, d, index, src, reduce, include_self, (char*)ws, s);
+    case TX_BF16: return scatter_reduce_typed<bf16>(p, self, d, index, src, reduce, include_self, (char*)ws, s);
+    case TX_F16: return scatter_reduce_typed<f16>(p, self, d, index, src, reduce, include_self, (char*)ws, s);
+    case TX_I32: return scatter_reduce_typed<int32_t>(p, self, d, index, src, reduce, include_self, (char*)ws, s);
+    case TX_BOOL: return scatter_reduce_typed<uint8_t>(p, self, d, index, src, reduce, include_self, (char*)ws, s);
+    default: return scatter_reduce_typed<int64_t>(p, self, d, index, src, reduce, include_self, (char*)ws, s);
+  }
+}
+
+size_t tx_index_put_workspace_bytes(const tx_tensor* self, const tx_tensor* const* indices, int32_t nidx,
+                                    const tx_tensor* values, int accumulate) {
+  PutArgs a;
+  if (index_put_checks(self, indices, nidx, values, &a)) return 0;
+  tx_tensor view;
+  if (accumulate && index_put_as_rows(self, indices, nidx, values, &view)) return scatter_ws_bytes(self, 0, &view, values, 1);
+  if (!accumulate || !dtype_is_float(self->dtype) || a.shape.numel == 0) return 0;
+  ScatterPlan p;
+  if (elem_sort_plan("index_put_", self, a.shape.numel, &p)) return 0;
+  return p.bytes;
+}
+
+tx_status tx_index_put_(const tx_tensor* self, const tx_tensor* const* indices, int32_t nidx, const tx_tensor* values,
+                        int accumulate, void* ws, size_t ws_bytes, void* stream) {
+  PutArgs a;
+  tx_status rc = index_put_checks(self, indices, nidx, values, &a);
+  if (rc) return rc;
+  set_path("");
+  const int64_t n = a.shape.numel;
+  if (n == 0) return TX_OK;
+  if (n >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "index_put_: more than 2^31 value elements");
+  hipStream_t s = as_stream(stream);
+  tx_tensor view;
+  if (accumulate && index_put_as_rows(self, indices, nidx, values, &view))
+    return scatter_core("index_put_", self, 0, &view, values, Alpha{1.0f, 1, self->sizes[0]}, 1, ws, ws_bytes, s);
+  const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  if (!accumulate) {
+    set_path("index-put");
+    switch (dtype_size(self->dtype)) {
+      case 1: hipLaunchKernelGGL((index_put_kernel<uint8_t, 0>), grid, dim3(kBlock), 0, s, a); break;
+      case 2: hipLaunchKernelGGL((index_put_kernel<uint16_t, 0>), grid, dim3(kBlock), 0, s, a); break;
+      case 4: hipLaunchKernelGGL((index_put_kernel<uint32_t, 0>), grid, dim3(kBlock), 0, s, a); break;
+      default: hipLaunchKernelGGL((index_put_kernel<uint64_t, 0>), grid, dim3(kBlock), 0, s, a); break;
+    }
+    return check_launch("index_put kernel");
+  }
+  if (!dtype_is_float(self->dtype)) {
+    set_path("index-put-atomic");
+    switch (self->dtype) {
+      case TX_BOOL: hipLaunchKernelGGL((index_put_kernel<uint8_t, 1>), grid, dim3(kBlock), 0, s, a); break;
+      case TX_I32: hipLaunchKernelGGL((index_put_kernel<int32_t, 1>), grid, dim3(kBlock), 0, s, a); break;
+      default: hipLaunchKernelGGL((index_put_kernel<int64_t, 1>), grid, dim3(kBlock), 0, s, a); break;
+    }
+    return check_launch("index_put atomic kernel");
+  }
+  // floats: destination offsets as sort keys, then each run summed in position order (binary64) by its first entry
+  ScatterPlan p;
+  if ((rc = elem_sort_plan("index_put_", self, n, &p)) || (rc = sort_ws_checks("index_put_", p, ws, ws_bytes))) return rc;
+  char* w = (char*)ws;
+  a.keys = (uint32_t*)(w + p.off_keys[0]);
+  a.vals = (uint32_t*)(w + p.off_vals[0]);
+  hipLaunchKernelGGL((index_put_kernel<uint8_t, 2>), grid, dim3(kBlock), 0, s, a);
+  int cur;
+  if ((rc = run_sort(p, w, s, &cur))) return rc;
+  // the segmented sum maps a position back to its value through the value shape and strides
+  ElemArgs ea;
+  memset(&ea, 0, sizeof(ea));
+  ea.shape = a.shape;
+  for (int d = 0; d < a.shape.n; ++d) ea.sstride[d] = a.vstride[d];
+  ea.src = a.src;
+  ea.dst = a.dst;
+  ea.alpha_f = 1.0f;
+  ea.alpha_i = 1;
+  set_path("index-put-sort");
+  const uint32_t* keys = (const uint32_t*)(w + p.off_keys[cur]);
+  const uint32_t* vals = (const uint32_t*)(w + p.off_vals[cur]);
+  switch (self->dtype) {
+    case TX_F32: hipLaunchKernelGGL((seg_elem_kernel<float>), grid, dim3(kBlock), 0, s, keys, vals, n, ea); break;
+    case TX_BF16: hipLaunchKernelGGL((seg_elem_kernel<bf16>), grid, dim3(kBlock), 0, s, keys, vals, n, ea); break;
+    default: hipLaunchKernelGGL((seg_elem_kernel<f16>), grid, dim3(kBlock), 0, s, keys, vals, n, ea); break;
+  }
+  return check_launch("index_put segmented sum");
 }
 
 size_t tx_index_add_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* source,

@@ -100,6 +100,12 @@ class OracleBackend:
     def index_add(self, x, dim, index, src, alpha):
         return self.O.index_add_(x.clone(), dim, index, src, alpha)
 
+    def scatter_reduce(self, x, dim, index, src, reduce, include_self):
+        return self.O.scatter_reduce_(x.clone(), dim, index, src, reduce, include_self)
+
+    def index_put(self, x, indices, values, accumulate):
+        return self.O.index_put_(x.clone(), indices, values, accumulate)
+
     def take(self, x, index):
         return self.O.take(x, index)
 
@@ -207,6 +213,17 @@ class LibraryBackend:
     def index_add(self, x, dim, index, src, alpha):
         dst, di, ds = x.contiguous().cuda(), self.dev(index), self.dev(src)
         self.B.tx_index_add_(dst, dim, di, ds, alpha, True, self._ws(self.B.tx_index_add_workspace_bytes(dst, dim, di, ds, True)))
+        return dst.cpu()
+
+    def scatter_reduce(self, x, dim, index, src, reduce, include_self):
+        dst, di, ds = x.contiguous().cuda(), self.dev(index), self.dev(src)
+        ws = self._ws(self.B.tx_scatter_reduce_workspace_bytes(dst, dim, di, ds, reduce, include_self))
+        self.B.tx_scatter_reduce_(dst, dim, di, ds, reduce, include_self, ws)
+        return dst.cpu()
+
+    def index_put(self, x, indices, values, accumulate):
+        dst, di, dv = x.contiguous().cuda(), [self.dev(i) for i in indices], self.dev(values)
+        self.B.tx_index_put_(dst, di, dv, accumulate, self._ws(self.B.tx_index_put_workspace_bytes(dst, di, dv, accumulate)))
         return dst.cpu()
 
     def take(self, x, index):
@@ -397,6 +414,25 @@ def index_add(be, s):
     return be.index_add(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]), _tensor_ok(s.args[2]), _scalar(s.kwargs.get("alpha", 1)))
 
 
+def scatter_reduce(be, s):
+    _no_kwargs(s, ("include_self",))
+    return be.scatter_reduce(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]), _tensor_ok(s.args[2]), s.args[3],
+                             bool(s.kwargs.get("include_self", True)))
+
+
+def index_put(be, s):
+    _no_kwargs(s, ("accumulate",))
+    indices = [_tensor_ok(i) for i in s.args[0]]
+    if any(i.dtype == BOOL for i in indices):
+        raise Unsupported("bool mask as index")
+    accumulate = bool(s.kwargs.get("accumulate", False))
+    if not accumulate:
+        flat = torch.stack([i.reshape(-1) % n for i, n in zip(torch.broadcast_tensors(*indices), s.input.shape)], 1)
+        if len(torch.unique(flat, dim=0)) != len(flat):
+            raise Unsupported("assignment with repeated destinations (no unique result)")
+    return be.index_put(_tensor_ok(s.input), indices, _tensor_ok(s.args[1]), accumulate)
+
+
 def take(be, s):
     _no_kwargs(s)
     return be.take(_tensor_ok(s.input), _tensor_ok(s.args[0]))
@@ -450,7 +486,7 @@ ADAPTERS = {
     "all": reduction("all"), "logsumexp": reduction("logsumexp"),
     "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": cumsum,
     "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
-    "masked_select": masked_select, "nonzero": nonzero,
+    "masked_select": masked_select, "nonzero": nonzero, "scatter_reduce": scatter_reduce, "index_put": index_put,
     "nn.functional.layer_norm": layer_norm, "nn.functional.binary_cross_entropy": bce,
 }
 

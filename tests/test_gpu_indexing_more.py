@@ -235,3 +235,141 @@ def test_compaction_full_size():
     assert check_masked_select(x, m) == "select"
     xs = torch.where(I.bernoulli_mask((8192, 4096), 0.1, seed=442), x[:, :4096], torch.zeros(()))
     assert check_nonzero(xs) == "select"
+
+
+# --------------------------------------------------------------------------- scatter_reduce_, index_put_
+def check_scatter_reduce(self_cpu, dim, idx_cpu, src_cpu, reduce, include_self, what=""):
+    want = O.scatter_reduce_(self_cpu.clone(), dim, idx_cpu, src_cpu, reduce, include_self)
+    dst = to_device_view(self_cpu).clone() if self_cpu.is_contiguous() else to_device_view(self_cpu)
+    idx, src = to_device_view(idx_cpu), to_device_view(src_cpu)
+    ws = B.workspace(B.tx_scatter_reduce_workspace_bytes(dst, dim, idx, src, reduce, include_self))
+    B.tx_scatter_reduce_(dst, dim, idx, src, reduce, include_self, ws)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    what = "scatter_reduce %s %s self%s idx%s dim=%d include_self=%s %s [%s]" % (reduce, self_cpu.dtype, tuple(self_cpu.shape),
+                                                                              tuple(idx_cpu.shape), dim, include_self, what, used)
+    if not self_cpu.dtype.is_floating_point:
+        assert_exact(dst, want, what)
+    else:
+        # what lands on an element, in magnitude: sums and means are judged against it, products and extrema have no cancellation
+        s2 = self_cpu.double() ** 2
+        window = tuple(slice(0, n) for n in idx_cpu.shape)
+        s2.scatter_add_(dim, idx_cpu.long().contiguous(), (src_cpu.double() ** 2)[window].contiguous())
+        scale = s2.sqrt() if reduce in ("sum", "mean") else torch.zeros_like(s2)
+        assert_rel(dst, want, 1e-5 if self_cpu.dtype == F32 else 1e-2, scale, what)
+    return used
+
+
+@pytest.mark.parametrize("reduce", ["sum", "prod", "mean", "amax", "amin"])
+def test_scatter_reduce_sweep(reduce):
+    g = torch.Generator().manual_seed(450)
+    for dt, inc in itertools.product((F32, BF16, F16, I32, I64), (True, False)):
+        for shape, dim, ishape in [((50, 64), 0, (300, 64)), ((50, 64), 1, (50, 20)), ((6, 20, 48), 1, (6, 77, 48)), ((33,), 0, (200,)),
+                                   ((40, 7), 0, (5, 3))]:
+            small = reduce == "prod"
+            s = (I.typed(shape, dt, seed=451) if not small else (torch.randint(-2, 3, shape, generator=g).to(dt)))
+            sshape = tuple(max(a, b) for a, b in zip(ishape, shape)) if dim is None else ishape
+            src = (I.typed(sshape, dt, seed=452) if not small else torch.randint(-2, 3, sshape, generator=g).to(dt))
+            if reduce == "prod" and dt.is_floating_point:
+                s, src = s * 0.5 + 1, src * 0.25 + 1                      # products of many terms stay finite
+            idx = torch.randint(0, shape[dim], ishape, generator=g)
+            used = check_scatter_reduce(s, dim, idx, src, reduce, inc)
+            assert used == ("scatter-reduce-sort" if not (reduce == "sum" and inc) else used)
+        # NaN / inf in the values, strided views, int32 index
+        if dt.is_floating_point:
+            s, src = I.typed((30, 16), dt, seed=453, specials=0.05), I.typed((90, 16), dt, seed=454, specials=0.05)
+            idx = torch.randint(0, 30, (90, 16), generator=g)
+            if reduce in ("amax", "amin"):
+                check_scatter_reduce(s, 0, idx, src, reduce, inc, what="specials")
+        s, src = I.typed((30, 32), dt, seed=455), I.typed((90, 32), dt, seed=456)
+        if reduce == "prod":
+            s, src = (s.abs().clamp(max=1) if dt.is_floating_point else s.clamp(-1, 1)), (src.abs().clamp(max=1) if dt.is_floating_point else src.clamp(-1, 1))
+        idx = torch.randint(0, 15, (90, 16), generator=g)
+        check_scatter_reduce(s[::2, ::2], 0, idx.to(I32), src[:, ::2], reduce, inc, what="views")
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    ws = B.workspace(1 << 16)
+    if reduce == "mean":
+        with pytest.raises(B.TxError) as e:
+            B.tx_scatter_reduce_(d(4, 3, dt=BOOL), 0, d(2, 3, dt=I64), d(2, 3, dt=BOOL), reduce, True, ws)
+        assert e.value.kind == "DTYPE"
+    else:
+        for inc in (True, False):
+            check_scatter_reduce(I.booleans((30, 16), 0.4, seed=457), 0, torch.randint(0, 30, (90, 16), generator=g),
+                                 I.booleans((90, 16), 0.6, seed=458), reduce, inc, what="bool")
+    with pytest.raises(B.TxError) as e:
+        B.tx_scatter_reduce_(d(4, 3), 0, d(2, 3, dt=I64), d(2, 3), "median", True, ws)
+    assert e.value.kind == "SCALAR"
+    with pytest.raises(B.TxError) as e:
+        B.tx_scatter_reduce_(d(4, 3), 0, d(2, 3, dt=I64), d(2, 3), reduce, False, None)
+    assert e.value.kind == "WORKSPACE"
+
+
+def check_index_put(self_cpu, indices_cpu, values_cpu, accumulate, unique=True, what=""):
+    want = O.index_put_(self_cpu.clone(), indices_cpu, values_cpu, accumulate)
+    dst = to_device_view(self_cpu).clone() if self_cpu.is_contiguous() else to_device_view(self_cpu)
+    ind, val = [to_device_view(i) for i in indices_cpu], to_device_view(values_cpu)
+    nbytes = B.tx_index_put_workspace_bytes(dst, ind, val, accumulate)
+    B.tx_index_put_(dst, ind, val, accumulate, B.workspace(nbytes) if nbytes else None)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    what = "index_put %s self%s values%s accumulate=%s %s [%s]" % (self_cpu.dtype, tuple(self_cpu.shape), tuple(values_cpu.shape),
+                                                                accumulate, what, used)
+    if accumulate and self_cpu.dtype.is_floating_point:
+        s2 = self_cpu.double() ** 2
+        s2.index_put_(tuple(i.long() for i in indices_cpu), values_cpu.double() ** 2, accumulate=True)
+        assert_rel(dst, want, 1e-5 if self_cpu.dtype == F32 else 1e-2, s2.sqrt(), what)
+    else:
+        assert unique or accumulate, "assignment with duplicates has no unique answer"
+        assert_exact(dst, want, what)
+    return used
+
+
+def test_index_put_sweep():
+    g = torch.Generator().manual_seed(460)
+    for dt in ALL:
+        mk = (lambda shape, seed: I.typed(shape, dt, seed=seed)) if dt != BOOL else (lambda shape, seed: I.booleans(shape, 0.3, seed=seed))
+        s = mk((12, 9, 16), 461)
+        # accumulate, duplicates allowed: one, two and three index tensors, negative indices, broadcast values
+        i0, i1, i2 = torch.randint(-12, 12, (40,), generator=g), torch.randint(-9, 9, (40,), generator=g), torch.randint(-16, 16, (40,), generator=g)
+        used = check_index_put(s, [i0], mk((40, 9, 16), 462), True)              # whole rows: the scatter_add_ row path
+        assert used == ("scatter-sort-rows" if dt.is_floating_point else "index-put-atomic" if dt == BOOL else "scatter-atomic")
+        used = check_index_put(s, [i0, i1], mk((40, 16), 463), True)
+        assert used == ("index-put-sort" if dt.is_floating_point else "index-put-atomic")
+        check_index_put(s, [i0, i1.to(I32), i2], mk((40,), 464), True)
+        check_index_put(s, [i0, i1], mk((16,), 465), True, what="values broadcast over positions")
+        check_index_put(s, [i0, i1], mk((), 466), True, what="0-dim values")
+        check_index_put(s, [i0.view(40, 1)[:5], i1.view(1, 40)[:, :7]], mk((5, 7, 16), 467), True, what="broadcast indices")
+        check_index_put(s.permute(1, 0, 2), [i1, i0], mk((40, 16), 468), True, what="permuted self")
+        check_index_put(s, [i0[::2], i1[::2]], mk((40, 16), 469)[::2], True, what="strided index and values")
+        # assignment: distinct destinations
+        perm = torch.randperm(12 * 9, generator=g)[:50]
+        u0, u1 = perm // 9, perm % 9 - 9                                       # second index given as negatives
+        assert check_index_put(s, [u0, u1], mk((50, 16), 470), False) == "index-put"
+        check_index_put(s, [torch.randperm(12, generator=g)[:7]], mk((7, 9, 16), 471), False, what="rows")
+        check_index_put(s, [u0, u1], mk((1, 16), 472), False, what="broadcast values")
+        check_index_put(s, [u0[:0], u1[:0]], mk((0, 16), 473), True, what="no positions")
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    ix = lambda *v: torch.tensor(v, device="cuda")
+    for args, kind in (((d(4, 3), [ix(0, 1)], d(2, 4)), "SHAPE"), ((d(4, 3), [ix(0, 1), ix(0, 1, 2)], d(2)), "SHAPE"),
+                       ((d(4, 3), [ix(0.0, 1.0)], d(2, 3)), "DTYPE"), ((d(4, 3), [ix(0, 1)], d(2, 3, dt=BF16)), "DTYPE"),
+                       ((d(4, 3), [], d(2, 3)), "DIM"), ((d(4, 3), [ix(0), ix(0), ix(0)], d(1)), "DIM")):
+        with pytest.raises(B.TxError) as e:
+            B.tx_index_put_(args[0], args[1], args[2], True, B.workspace(1 << 16))
+        assert e.value.kind == kind, (kind, e.value.kind)
+    with pytest.raises(B.TxError) as e:
+        B.tx_index_put_(d(4, 3), [ix(0, 1)], d(2, 3), True, None)
+    assert e.value.kind == "WORKSPACE"
+
+
+def test_scatter_reduce_and_index_put_larger():
+    g = torch.Generator().manual_seed(480)
+    s, src = I.typed((4096, 256), F32, seed=481), I.typed((65536, 256), F32, seed=482)
+    rows = I.zipf_rows(65536, 4096, 1.1, seed=4)
+    idx = rows.unsqueeze(1).expand(65536, 256)
+    for reduce, inc in (("amax", True), ("mean", False), ("sum", False)):
+        check_scatter_reduce(s, 0, idx, src, reduce, inc, what="zipf rows")
+    check_index_put(s, [rows], src, True, what="zipf rows")
+    si = I.typed((4096, 256), I64, seed=483)
+    check_index_put(si, [rows, torch.randint(0, 256, (65536,), generator=g)], I.typed((65536,), I64, seed=484), True)
+    perm = torch.randperm(4096, generator=g)
+    assert check_index_put(s, [perm], I.typed((4096, 256), F32, seed=485), False) == "index-put"

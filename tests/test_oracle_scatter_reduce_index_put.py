@@ -96,7 +96,14 @@ def test_scatter_reduce_special_cases_and_aten():
     for dt in (BF16, F16):
         want = s.to(dt).double().scatter_reduce_(1, idx, src.to(dt).double(), "amax", include_self=True).to(dt)
         assert torch.equal(O.scatter_reduce_(s.to(dt), 1, idx, src.to(dt), "amax"), want)
-    for args, kind in (((s, 1, idx, src, "median"), "scalar"), ((s.bool(), 1, idx, src.bool(), "sum"), "dtype"),
+    sb, srcb = s > 0.3, src > 0.3                                             # bool: OR / AND
+    for reduce in ("sum", "prod", "amax", "amin"):
+        for inc in (True, False):
+            assert torch.equal(O.scatter_reduce_(sb.clone(), 1, idx, srcb, reduce, inc),
+                               sb.clone().scatter_reduce_(1, idx, srcb, reduce, include_self=inc)), (reduce, inc)
+    assert O.scatter_reduce_(torch.tensor([False, True]), 0, torch.tensor([0, 0, 1]), torch.tensor([True, True, False]), "sum").tolist() == [True, True]
+    assert O.scatter_reduce_(torch.tensor([True, True]), 0, torch.tensor([0, 0, 1]), torch.tensor([True, False, True]), "prod").tolist() == [False, True]
+    for args, kind in (((s, 1, idx, src, "median"), "scalar"), ((s.bool(), 1, idx, src.bool(), "mean"), "dtype"),
                        ((s, 1, idx + 6, src, "sum"), "index"), ((s, 3, idx, src, "sum"), "dim"),
                        ((s, 1, idx, src[:, :8], "sum"), "shape"), ((s, 1, idx.float(), src, "sum"), "dtype")):
         with pytest.raises(O.OracleError) as e:
