@@ -374,7 +374,12 @@ const char* tx_last_path(void);
  * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".
  * Reduction with lanes along the kept dim: "cols-nv1", "cols-nv2", "cols-nv4"
  * (vectors per thread).  Integer scatter_add_: "scatter-atomic" (one atomic
- * per element even when a workspace is given).  Requests that a path cannot
+ * per element even when a workspace is given).  softmax / cumsum along a
+ * non-innermost dim: "softmax-strided", "scan-strided" (one lane per slice
+ * instead of the column kernels).  layer_norm: "layer-norm-block" (one
+ * workgroup per row), "layer-norm-generic" (three passes, any strides).
+ * binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
+ * first; the workspace query then reports that form's size).  Requests that a path cannot
  * serve fall back to the automatic choice.  Process-wide; meant for A/B
  * profiling. */
 void tx_force_path(const char* name);
