@@ -10,8 +10,6 @@ namespace {
 // ---------------------------------------------------------------------------
 // pow
 // ---------------------------------------------------------------------------
-// fp32 power through binary64 (well within 2 ulp after the final rounding; the special values follow C Annex F)
-__device__ __forceinline__ float pow_f32(float a, float b) { return (float)pow((double)a, (double)b); }
 
 // wrapping integer power by squaring; a negative exponent is the truncated reciprocal
 __device__ __forceinline__ int64_t pow_int(int64_t b, int64_t e) {

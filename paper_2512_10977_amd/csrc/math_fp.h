@@ -45,6 +45,47 @@ __device__ __forceinline__ double exp_d(double y) {  // y clamped by the caller
   return __builtin_fma(p, pow2_d(n), pow2_d(n));
 }
 
+// log(a) for finite, positive, normal a: a = 2^e m with m in [sqrt(1/2), sqrt 2), log m = 2 atanh(z),
+// z = (m - 1) / (m + 1), |z| <= 0.1716: z (1 + w/3 + ... + w^7/15), w = z^2 (first dropped term below 4e-14 relative)
+__device__ __forceinline__ double log_d(double a) {
+  const double kLn2Hi = 6.93147180369123816490e-01, kLn2Lo = 1.90821492927058770002e-10;
+  const long long bits = __double_as_longlong(a);
+  int e = (int)((bits >> 52) & 0x7ff) - 1023;
+  double m = __longlong_as_double((bits & 0x000fffffffffffffLL) | 0x3ff0000000000000LL);
+  if (m > 1.4142135623730951) { m *= 0.5; ++e; }
+  const double z = (m - 1.0) * rcp_d(m + 1.0);
+  const double w = z * z;
+  double p = 1.0 / 15.0;
+  p = __builtin_fma(p, w, 1.0 / 13.0);
+  p = __builtin_fma(p, w, 1.0 / 11.0);
+  p = __builtin_fma(p, w, 1.0 / 9.0);
+  p = __builtin_fma(p, w, 1.0 / 7.0);
+  p = __builtin_fma(p, w, 1.0 / 5.0);
+  p = __builtin_fma(p, w, 1.0 / 3.0);
+  p = __builtin_fma(p, w, 1.0);
+  const double ef = (double)e;
+  return __builtin_fma(ef, kLn2Hi, __builtin_fma(ef, kLn2Lo, 2.0 * z * p));
+}
+
+// fp32 power.  Finite non-zero base and finite exponent: exp(b log|a|) in binary64 (the error of b log|a| stays
+// below 1e-11 wherever the result is finite, far inside one fp32 ulp), the sign from the exponent's parity for a
+// negative base, NaN for a negative base with a non-integer exponent.  Zeros, infinities and NaNs: the device
+// library's binary64 pow, which carries the C Annex F table.
+__device__ __forceinline__ float pow_f32(float af, float bf) {
+  const float aa = __builtin_fabsf(af), inf = __builtin_inff();
+  if (!(aa > 0.0f && aa < inf && __builtin_fabsf(bf) < inf)) return (float)pow((double)af, (double)bf);
+  if (bf == 0.0f) return 1.0f;
+  bool odd = false;
+  if (af < 0.0f) {
+    if (bf != __builtin_truncf(bf)) return __uint_as_float(0x7fc00000u);
+    odd = __builtin_fabsf(bf) < 16777216.0f && ((long long)bf & 1);      // every float from 2^24 on is an even integer
+  }
+  double y = (double)bf * log_d((double)aa);
+  y = y > 90.0 ? 90.0 : (y < -110.0 ? -110.0 : y);                       // beyond fp32's range either way
+  const float r = (float)exp_d(y);
+  return odd ? -r : r;
+}
+
 __device__ __forceinline__ float sigmoid_f32(float xf) {
   if (xf != xf) return xf;
   double x = (double)xf;
