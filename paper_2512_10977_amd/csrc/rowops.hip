@@ -348,7 +348,11 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
   __syncthreads();
   const int64_t ticket = my_ticket;
   if (ticket >= a.total_tiles) return;
-  const int64_t row = ticket / a.tiles_per_row, t = ticket - row * a.tiles_per_row;
+  // tickets walk the rows round-robin (tile t of every row, then tile t + 1, ...): a tile's predecessors in its row
+  // still have smaller tickets, and the workgroups resident at one time are spread over all rows instead of sitting
+  // in one or two of them, which shortens every look-back chain
+  const int64_t t = ticket / a.rows, row = ticket - t * a.rows;
+  const int64_t slot = row * a.tiles_per_row + t;      // status word of this tile (row-major)
   const T* x = (const T*)a.x + row * a.xrow + t * kTileElems;
   O* out = (O*)a.out + row * a.orow + t * kTileElems;
   const int64_t left = a.len - t * kTileElems;      // valid elements in this tile (may exceed the tile)
@@ -376,9 +380,9 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
     const Acc tile_total = shfl_idx(incl, kTotals - 1);
     Acc prefix = Acc(0);
     if (t == 0) {
-      if (lane == 0) TileState<Acc>::publish(status, ticket, kPrefix, tile_total);
+      if (lane == 0) TileState<Acc>::publish(status, slot, kPrefix, tile_total);
     } else {
-      if (lane == 0) TileState<Acc>::publish(status, ticket, kAggregate, tile_total);
+      if (lane == 0) TileState<Acc>::publish(status, slot, kAggregate, tile_total);
       int64_t look = t - 1;                    // nearest predecessor not yet folded in (row-local index)
       bool done = false;
       while (!done) {
@@ -388,7 +392,7 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
         if (mine >= 0) {
           int spins = 0;
           do {
-            flag = TileState<Acc>::read(status, ticket - t + mine, &val);
+            flag = TileState<Acc>::read(status, slot - t + mine, &val);
             if (flag != kEmpty) break;
             __builtin_amdgcn_s_sleep(2);
           } while (++spins < kSpinLimit);
@@ -403,7 +407,7 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
         if (stop >= 0) done = true;
         else look -= kWave;
       }
-      if (lane == 0) TileState<Acc>::publish(status, ticket, kPrefix, prefix + tile_total);
+      if (lane == 0) TileState<Acc>::publish(status, slot, kPrefix, prefix + tile_total);
     }
     if (lane == 0) tile_prefix = prefix;
   }
