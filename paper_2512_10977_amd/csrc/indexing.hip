@@ -21,21 +21,14 @@
 #include <cstring>
 
 #include "common.h"
+#include "index_util.h"
 
 namespace tx {
 namespace {
 
 constexpr int kBlock = 256;
 
-struct Dims {
-  int n;
-  FastDiv div[TX_MAX_DIMS];
-  int64_t numel;
-};
 
-__device__ __forceinline__ int64_t load_index(const char* p, int64_t off, int is64) {
-  return is64 ? ((const int64_t*)p)[off] : (int64_t)((const int32_t*)p)[off];
-}
 
 // ---------------------------------------------------------------------------
 // gather / generic index_select / atomic scatter_add share one addressing
@@ -737,14 +730,6 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
 // ---------------------------------------------------------------------------
 // host helpers
 // ---------------------------------------------------------------------------
-void fill_dims(Dims* d, int nd, const int64_t* sizes) {
-  d->n = nd;
-  d->numel = 1;
-  for (int i = 0; i < nd; ++i) {
-    d->div[i] = FastDiv((uint32_t)std::min<int64_t>(sizes[i], 0x7fffffff));
-    d->numel *= sizes[i];
-  }
-}
 bool index_dtype_ok(int dt) { return dt == TX_I32 || dt == TX_I64; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int bits_for(uint64_t max_value) {
