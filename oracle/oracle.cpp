@@ -71,9 +71,12 @@ enum {
 
 // op codes
 enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, ORC_GELU, ORC_LOG1P, ORC_EXPM1,
-       ORC_LOGSIGMOID, ORC_LOGICAL_NOT };
+       ORC_LOGSIGMOID, ORC_LOGICAL_NOT, ORC_SIN, ORC_COS, ORC_EXP2, ORC_LOG2, ORC_LOG10, ORC_RSQRT, ORC_RECIPROCAL,
+       ORC_SILU, ORC_SQUARE, ORC_SIGN, ORC_FLOOR, ORC_CEIL, ORC_TRUNC, ORC_ROUND, ORC_ISNAN, ORC_ISINF, ORC_ISFINITE,
+       ORC_BITWISE_NOT };
 enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM, ORC_NE, ORC_LT, ORC_LE, ORC_GT, ORC_GE,
-       ORC_LOGICAL_AND, ORC_LOGICAL_OR, ORC_LOGICAL_XOR, ORC_POW };
+       ORC_LOGICAL_AND, ORC_LOGICAL_OR, ORC_LOGICAL_XOR, ORC_POW, ORC_BITWISE_AND, ORC_BITWISE_OR, ORC_BITWISE_XOR,
+       ORC_ATAN2 };
 enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
        ORC_LOGSUMEXP };
 
@@ -388,8 +391,20 @@ int orc_unary_result_dtype(int op, int in_dtype) {
       return is_float(in_dtype) ? in_dtype : ORC_F32;   // integral input computes in fp32
     case ORC_GELU: case ORC_LOGSIGMOID:
       return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
-    case ORC_LOGICAL_NOT:
+    case ORC_LOGICAL_NOT: case ORC_ISNAN: case ORC_ISINF: case ORC_ISFINITE:
       return ORC_BOOL;
+    case ORC_SIN: case ORC_COS: case ORC_EXP2: case ORC_LOG2: case ORC_LOG10: case ORC_RSQRT: case ORC_RECIPROCAL:
+      return is_float(in_dtype) ? in_dtype : ORC_F32;
+    case ORC_SILU:
+      return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_SQUARE:
+      return in_dtype == ORC_BOOL ? ORC_I64 : in_dtype;    // a bool squares as the integer 0 / 1
+    case ORC_SIGN:
+      return in_dtype;
+    case ORC_FLOOR: case ORC_CEIL: case ORC_TRUNC: case ORC_ROUND:
+      return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
+    case ORC_BITWISE_NOT:
+      return is_float(in_dtype) ? ORC_ERR_DTYPE : in_dtype;
   }
   return ORC_ERR_DTYPE;
 }
@@ -403,10 +418,12 @@ int orc_infer_binary(int op, const orc_tensor* a, const orc_tensor* b, int32_t* 
   const orc_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
-  if (op < ORC_ADD || op > ORC_POW) return ORC_ERR_DTYPE;
+  if (op < ORC_ADD || op > ORC_ATAN2) return ORC_ERR_DTYPE;
   if (op == ORC_DIV && !is_float(common)) res = ORC_F32;   // true division
   if (op == ORC_EQ || (op >= ORC_NE && op <= ORC_LOGICAL_XOR)) res = ORC_BOOL;   // comparison and logical families
   if (op == ORC_POW && common == ORC_BOOL) return ORC_ERR_DTYPE;                 // no bool power
+  if (op >= ORC_BITWISE_AND && op <= ORC_BITWISE_XOR && is_float(common)) return ORC_ERR_DTYPE;
+  if (op == ORC_ATAN2 && !is_float(common)) res = ORC_F32;
   if (op == ORC_SUB && (a->dtype == ORC_BOOL || b->dtype == ORC_BOOL)) return ORC_ERR_DTYPE;   // no bool subtraction
   int nd;
   int64_t s[ORC_MAX_DIMS];
@@ -430,6 +447,13 @@ int orc_where_result_dtype(const orc_tensor* x, const orc_tensor* y) {
 // out[i] = f(a[i]).  `out` must have a's shape; its dtype is the inferred one or any dtype that one can be cast to
 // (see can_cast): the result is rounded to the inferred dtype first, then converted.
 //   logical_not   : x == 0 for any dtype, bool result.
+//   sin cos exp2 log2 log10 rsqrt reciprocal : like exp (binary64 evaluation, bool / integer input computes in fp32);
+//                   rsqrt = 1 / sqrt(x).  silu = x / (1 + exp(-x)), floating dtypes only.
+//   square        : x * x (integers wrap; a bool gives the int64 0 / 1).  sign: -1, 0, 1 in the input's dtype, 0 for
+//                   a NaN and for -0.0 (the value of (0 < x) - (x < 0)); a bool is returned as it is.
+//   floor ceil trunc round : floats (round: halves to even, the sign of zero is kept); integers are returned as they
+//                   are; bool is a dtype error.  isnan / isinf / isfinite: bool result, integers are finite.
+//   bitwise_not   : ~x for integers, logical not for bool, floats are a dtype error.
 //   neg, abs      : exact; integers wrap (abs(INT_MIN) == INT_MIN); floats
 //                   flip / clear the sign bit (NaN and zeros included).
 //   exp log sqrt sigmoid tanh : binary64 evaluation of the input converted to
@@ -481,9 +505,38 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
       }
       continue;
     }
+    if (op == ORC_ISNAN || op == ORC_ISINF || op == ORC_ISFINITE) {       // integers and bools are always finite
+      const double v = is_float(a->dtype) ? load_flt(a, ao) : 0.0;
+      put_int(out, oo, ORC_BOOL, op == ORC_ISNAN ? std::isnan(v) : op == ORC_ISINF ? std::isinf(v) : std::isfinite(v));
+      continue;
+    }
+    if (!is_float(a->dtype) && (op == ORC_SQUARE || op == ORC_SIGN || op == ORC_FLOOR || op == ORC_CEIL || op == ORC_TRUNC ||
+                                op == ORC_ROUND || op == ORC_BITWISE_NOT)) {
+      const int64_t v = load_int(a, ao);
+      int64_t r = v;                                  // floor / ceil / trunc / round of an integer: itself
+      if (op == ORC_SQUARE) r = (int64_t)((uint64_t)v * (uint64_t)v);
+      else if (op == ORC_SIGN) r = (v > 0) - (v < 0);
+      else if (op == ORC_BITWISE_NOT) r = a->dtype == ORC_BOOL ? !v : ~v;
+      put_int(out, oo, rd, r);
+      continue;
+    }
     double x = (double)load_as(a, ao, rd).f;          // converted to result dtype first
     double y = 0.0;
     switch (op) {
+      case ORC_SIN: y = std::sin(x); break;
+      case ORC_COS: y = std::cos(x); break;
+      case ORC_EXP2: y = std::exp2(x); break;
+      case ORC_LOG2: y = std::log2(x); break;
+      case ORC_LOG10: y = std::log10(x); break;
+      case ORC_RSQRT: y = 1.0 / std::sqrt(x); break;
+      case ORC_RECIPROCAL: y = 1.0 / x; break;
+      case ORC_SILU: y = x / (1.0 + std::exp(-x)); break;                // x * sigmoid(x)
+      case ORC_SQUARE: y = x * x; break;                                   // exact in binary64, one rounding on store
+      case ORC_SIGN: y = (double)((0.0 < x) - (x < 0.0)); break;          // 0 for a NaN and for either zero
+      case ORC_FLOOR: y = std::floor(x); break;
+      case ORC_CEIL: y = std::ceil(x); break;
+      case ORC_TRUNC: y = std::trunc(x); break;
+      case ORC_ROUND: y = std::nearbyint(x); break;                        // halves to even (default rounding mode)
       case ORC_EXP: y = std::exp(x); break;
       case ORC_LOG: y = std::log(x); break;
       case ORC_SQRT: y = std::sqrt(x); break;
@@ -529,6 +582,12 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
 //             copies of a; for b < 0 the truncated reciprocal: 1 for a == 1,
 //             +-1 for a == -1 by b's parity, 0 otherwise (0^negative included).
 //             Two bool operands are a dtype error.
+//   bitwise_and / or / xor : on the two's-complement integers of the common
+//             dtype (bool: the logical operation); a floating common dtype is
+//             a dtype error.
+//   atan2   : the angle of the point (b, a), binary64 evaluation of the
+//             converted operands, one rounding; bool / integer operands are
+//             converted to fp32.
 // `out` may have any dtype the result dtype can be cast to (can_cast): the
 // value is formed in the result dtype, then converted.
 int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_tensor* b, double alpha_f,
@@ -542,7 +601,7 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
   if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
   const orc_tensor* ops[2] = {a, b};
   int cd = result_type(ops, 2);                       // dtype the op is applied in
-  if (op == ORC_DIV && !is_float(cd)) cd = ORC_F32;
+  if ((op == ORC_DIV || op == ORC_ATAN2) && !is_float(cd)) cd = ORC_F32;
   if ((op == ORC_ADD || op == ORC_SUB) && !is_float(cd) && !alpha_is_int) return ORC_ERR_SCALAR;
   const double alpha_d = alpha_is_int ? (double)alpha_i : alpha_f;
   const float alpha32 = (float)alpha_d;
@@ -597,6 +656,7 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_LOGICAL_OR: put_int(out, oo, rd, (x.f != 0.0f) || (y.f != 0.0f)); break;
         case ORC_LOGICAL_XOR: put_int(out, oo, rd, (x.f != 0.0f) != (y.f != 0.0f)); break;
         case ORC_POW: put_flt(out, oo, rd, std::pow((double)x.f, (double)y.f)); break;       // C Annex F special cases
+        case ORC_ATAN2: put_flt(out, oo, rd, std::atan2((double)x.f, (double)y.f)); break;
       }
     } else if (cd == ORC_BOOL) {
       switch (op) {
@@ -612,7 +672,9 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_GE: put_int(out, oo, rd, x.i >= y.i); break;
         case ORC_LOGICAL_AND: put_int(out, oo, rd, x.i & y.i); break;
         case ORC_LOGICAL_OR: put_int(out, oo, rd, x.i | y.i); break;
-        case ORC_LOGICAL_XOR: put_int(out, oo, rd, x.i ^ y.i); break;
+        case ORC_LOGICAL_XOR: case ORC_BITWISE_XOR: put_int(out, oo, rd, x.i ^ y.i); break;
+        case ORC_BITWISE_AND: put_int(out, oo, rd, x.i & y.i); break;
+        case ORC_BITWISE_OR: put_int(out, oo, rd, x.i | y.i); break;
       }
     } else {
       uint64_t ux = (uint64_t)x.i, uy = (uint64_t)y.i;
@@ -632,6 +694,9 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_LOGICAL_OR: put_int(out, oo, rd, (x.i != 0) || (y.i != 0)); break;
         case ORC_LOGICAL_XOR: put_int(out, oo, rd, (x.i != 0) != (y.i != 0)); break;
         case ORC_POW: put_int(out, oo, rd, int_pow(x.i, y.i)); break;
+        case ORC_BITWISE_AND: put_int(out, oo, rd, x.i & y.i); break;
+        case ORC_BITWISE_OR: put_int(out, oo, rd, x.i | y.i); break;
+        case ORC_BITWISE_XOR: put_int(out, oo, rd, x.i ^ y.i); break;
       }
     }
   }

@@ -475,6 +475,12 @@ ADAPTERS = {
     "neg": unary("neg"), "abs": unary("abs"), "exp": unary("exp"), "log": unary("log"), "sqrt": unary("sqrt"),
     "sigmoid": unary("sigmoid"), "tanh": unary("tanh"), "log1p": unary("log1p"), "expm1": unary("expm1"),
     "logical_not": unary("logical_not"), "nn.functional.logsigmoid": unary("logsigmoid"), "nn.functional.gelu": gelu,
+    "sin": unary("sin"), "cos": unary("cos"), "exp2": unary("exp2"), "log2": unary("log2"), "log10": unary("log10"),
+    "rsqrt": unary("rsqrt"), "reciprocal": unary("reciprocal"), "nn.functional.silu": unary("silu"), "square": unary("square"),
+    "sign": unary("sign"), "floor": unary("floor"), "ceil": unary("ceil"), "trunc": unary("trunc"), "round": unary("round"),
+    "isnan": unary("isnan"), "isinf": unary("isinf"), "isfinite": unary("isfinite"), "bitwise_not": unary("bitwise_not"),
+    "bitwise_and": binary("bitwise_and"), "bitwise_or": binary("bitwise_or"), "bitwise_xor": binary("bitwise_xor"),
+    "atan2": binary("atan2"),
     "add": binary("add", True), "sub": binary("sub", True), "mul": binary("mul"), "true_divide": binary("div"),
     "maximum": binary("maximum"), "minimum": binary("minimum"), "eq": binary("eq"), "ne": binary("ne"), "lt": binary("lt"),
     "le": binary("le"), "gt": binary("gt"), "ge": binary("ge"), "logical_and": binary("logical_and"),
