@@ -98,6 +98,10 @@ def build_ops(torch, B):
     extra("expm1_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("expm1", of, xf))
     extra("logsigmoid_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("logsigmoid", of, xf))
     extra("logsigmoid_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("logsigmoid", ob, xb))
+    for third in ("sin", "exp2", "rsqrt", "silu", "round"):
+        extra(third + "_f32", "f1", "ew_vec_kernel", n2 * 8, n2, (lambda o: (lambda: B.tx_unary(o, of, xf)))(third))
+    extra("isfinite_f32", "f1", "ew_vec_kernel", n2 * 5, n2, lambda: B.tx_unary("isfinite", obool, xf))
+    extra("atan2_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("atan2", of, xf, yf))
     extra("pow_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("pow", of, xf, yf))
     extra("clamp_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_clamp(of, xf, -0.5, 0.75))
     extra("clamp_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_clamp(ob, xb, -0.5, 0.75))

@@ -88,9 +88,10 @@ enum {
 
 /* operator codes */
 enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF, TX_LOG1P, TX_EXPM1, TX_LOGSIGMOID,
-       TX_LOGICAL_NOT };
+       TX_LOGICAL_NOT, TX_SIN, TX_COS, TX_EXP2, TX_LOG2, TX_LOG10, TX_RSQRT, TX_RECIPROCAL, TX_SILU, TX_SQUARE, TX_SIGN,
+       TX_FLOOR, TX_CEIL, TX_TRUNC, TX_ROUND, TX_ISNAN, TX_ISINF, TX_ISFINITE, TX_BITWISE_NOT };
 enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE,
-       TX_LOGICAL_AND, TX_LOGICAL_OR, TX_LOGICAL_XOR, TX_POW };
+       TX_LOGICAL_AND, TX_LOGICAL_OR, TX_LOGICAL_XOR, TX_POW, TX_BITWISE_AND, TX_BITWISE_OR, TX_BITWISE_XOR, TX_ATAN2 };
 enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARGMIN, TX_STD, TX_ANY, TX_ALL,
        TX_LOGSUMEXP };
 
@@ -108,7 +109,16 @@ enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARG
  *   GELU_ERF : x * Phi(x); float dtypes only.
  *   LOGSIGMOID : log(1 / (1 + exp(-x))) (Appendix D's worked example), float
  *              dtypes only, evaluated as min(x, 0) - log1p(exp(-|x|)).
- *   LOGICAL_NOT : x == 0 for any dtype (a NaN is not zero), bool result. */
+ *   LOGICAL_NOT : x == 0 for any dtype (a NaN is not zero), bool result.
+ *   SIN COS EXP2 LOG2 LOG10 RSQRT RECIPROCAL : like EXP (RSQRT = 1 / sqrt(x)).
+ *   SILU : x / (1 + exp(-x)); float dtypes only.
+ *   SQUARE : x * x; integers wrap; a bool gives the int64 0 / 1.
+ *   SIGN : -1, 0 or 1 in a's dtype; 0 for a NaN and for either zero; a bool is
+ *              returned unchanged.
+ *   FLOOR CEIL TRUNC ROUND : floats (ROUND: halves to even; the sign of zero is
+ *              kept); integers are returned unchanged; bool is TX_ERR_DTYPE.
+ *   ISNAN ISINF ISFINITE : any dtype, bool result (integers are finite).
+ *   BITWISE_NOT : ~x for integers, logical not for bool; floats are TX_ERR_DTYPE. */
 tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream);
 
 /* out = a + alpha * b with broadcasting and type promotion.  alpha is given
@@ -126,8 +136,9 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
                  int alpha_is_int, void* stream);
 
 /* out = a (op) b with broadcasting and type promotion, op in MUL DIV MAXIMUM
- * MINIMUM EQ NE LT LE GT GE LOGICAL_AND LOGICAL_OR LOGICAL_XOR POW (TX_ADD and
- * TX_SUB are accepted too, with alpha = 1).
+ * MINIMUM EQ NE LT LE GT GE LOGICAL_AND LOGICAL_OR LOGICAL_XOR POW BITWISE_AND
+ * BITWISE_OR BITWISE_XOR ATAN2 (TX_ADD and TX_SUB are accepted too, with
+ * alpha = 1).
  *   MUL: bool AND, integers wrap.  DIV: true division, bool / integer pairs are
  *   computed and returned in fp32.  MAXIMUM / MINIMUM: NaN if either operand is
  *   NaN; on ties the first operand; bool OR / AND.
@@ -140,7 +151,11 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
  *   non-integer exponent = NaN), fp32 results within 2 ulp.  Integer common
  *   dtype: wrapping product; a negative exponent gives the truncated
  *   reciprocal (1 for base 1, +-1 for base -1 by parity, else 0).  Two bool
- *   operands are TX_ERR_DTYPE. */
+ *   operands are TX_ERR_DTYPE.
+ *   BITWISE_AND / OR / XOR: on the integers of the common dtype (bool: the
+ *   logical operation); a floating common dtype is TX_ERR_DTYPE.
+ *   ATAN2: the angle of the point (b, a); bool / integer pairs are computed and
+ *   returned in fp32; fp32 results within 2 ulp. */
 tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream);
 
 /* out = min(max(x, lo), hi) with scalar bounds; has_lo / has_hi say which are
@@ -353,7 +368,7 @@ size_t tx_nonzero_workspace_bytes(const tx_tensor* out, const tx_tensor* count, 
 
 /* ------------------------------------------------------------------ host-only helpers */
 
-/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_POW). */
+/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_ATAN2). */
 tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_t* dtype, int32_t* ndim,
                           int64_t* sizes);
 /* Result dtype of where(cond, x, y). */

@@ -32,6 +32,10 @@ tx_status ew_compare_cast(const Iter& it, int code, int common, hipStream_t s);
 // unary op whose out dtype differs from the result dtype rd, and logical_not
 tx_status ew_unary_cast(const Iter& it, int op, int in_dtype, int rd, hipStream_t s);
 
+// third translation unit (elementwise_c.hip): unary operators from TX_SIN on, bitwise binary operators and atan2
+tx_status ew_unary_third(const Iter& it, int op, int in_dtype, int rd, hipStream_t s);
+tx_status ew_binary_third(const Iter& it, int op, int da, int db, int common, hipStream_t s);
+
 namespace {
 
 constexpr int kBlock = 256;

@@ -185,8 +185,23 @@ int32_t tx_infer_unary_dtype(int op, int32_t in) {
     case TX_GELU_ERF: case TX_LOGSIGMOID:
       if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "gelu / logsigmoid take floating dtypes only");
       return in;
-    case TX_LOGICAL_NOT:
+    case TX_LOGICAL_NOT: case TX_ISNAN: case TX_ISINF: case TX_ISFINITE:
       return TX_BOOL;
+    case TX_SIN: case TX_COS: case TX_EXP2: case TX_LOG2: case TX_LOG10: case TX_RSQRT: case TX_RECIPROCAL:
+      return dtype_is_float(in) ? in : TX_F32;
+    case TX_SILU:
+      if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "silu takes floating dtypes only");
+      return in;
+    case TX_SQUARE:
+      return in == TX_BOOL ? TX_I64 : in;
+    case TX_SIGN:
+      return in;
+    case TX_FLOOR: case TX_CEIL: case TX_TRUNC: case TX_ROUND:
+      if (in == TX_BOOL) return fail(TX_ERR_DTYPE, "floor / ceil / trunc / round do not take bool");
+      return in;
+    case TX_BITWISE_NOT:
+      if (dtype_is_float(in)) return fail(TX_ERR_DTYPE, "bitwise_not takes integer and bool dtypes only");
+      return in;
   }
   return fail(TX_ERR_DTYPE, "unknown unary op %d", op);
 }
@@ -197,13 +212,16 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (a->ndim < 0 || a->ndim > TX_MAX_DIMS || b->ndim < 0 || b->ndim > TX_MAX_DIMS)
     return fail(TX_ERR_NDIM, "infer_binary: bad ndim");
   if (!dtype_valid(a->dtype) || !dtype_valid(b->dtype)) return fail(TX_ERR_DTYPE, "infer_binary: bad dtype code");
-  if (op < TX_ADD || op > TX_POW) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
+  if (op < TX_ADD || op > TX_ATAN2) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
   const tx_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
   if (op == TX_DIV && !dtype_is_float(common)) res = TX_F32;
   if (op == TX_EQ || (op >= TX_NE && op <= TX_LOGICAL_XOR)) res = TX_BOOL;
   if (op == TX_POW && common == TX_BOOL) return fail(TX_ERR_DTYPE, "pow does not take two bool operands");
+  if (op >= TX_BITWISE_AND && op <= TX_BITWISE_XOR && dtype_is_float(common))
+    return fail(TX_ERR_DTYPE, "bitwise operators take integer and bool dtypes only");
+  if (op == TX_ATAN2 && !dtype_is_float(common)) res = TX_F32;
   if (op == TX_SUB && (a->dtype == TX_BOOL || b->dtype == TX_BOOL))
     return fail(TX_ERR_DTYPE, "sub does not take bool operands");
   int nd;

@@ -93,6 +93,15 @@ __device__ __forceinline__ float sigmoid_f32(float xf) {
   return (float)rcp_d(1.0 + exp_d(-x));
 }
 
+// x / (1 + exp(-x)) in binary64: for large negative x the fp32 sigmoid is subnormal and would lose the product's bits
+__device__ __forceinline__ float silu_f32(float xf) {
+  if (xf != xf) return xf;
+  if (xf == -__builtin_inff()) return __uint_as_float(0x7fc00000u);      // -inf / inf
+  const double x = (double)xf;
+  const double m = -x > 708.0 ? 708.0 : (-x < -708.0 ? -708.0 : -x);
+  return (float)(x * rcp_d(1.0 + exp_d(m)));
+}
+
 __device__ __forceinline__ float tanh_f32(float xf) {
   if (xf != xf) return xf;
   double y = 2.0 * (double)xf;

@@ -20,9 +20,13 @@ pytestmark = pytest.mark.gpu
 
 F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
 ALL = [F32, BF16, F16, I32, I64, BOOL]
-UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu", "log1p", "expm1", "logsigmoid", "logical_not"]
+UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu", "log1p", "expm1", "logsigmoid", "logical_not",
+         "sin", "cos", "exp2", "log2", "log10", "rsqrt", "reciprocal", "silu", "square", "sign", "floor", "ceil", "trunc", "round",
+         "isnan", "isinf", "isfinite", "bitwise_not"]
+EXACT_UNARY = ("neg", "abs", "logical_not", "square", "sign", "floor", "ceil", "trunc", "round", "isnan", "isinf", "isfinite",
+               "bitwise_not")
 BINARY = ["add", "mul", "div", "maximum", "eq", "sub", "minimum", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or",
-          "logical_xor", "pow"]
+          "logical_xor", "pow", "bitwise_and", "bitwise_or", "bitwise_xor", "atan2"]
 COMPARE = ("eq", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or", "logical_xor")
 CAST_OK = lambda src, dst: not (src.is_floating_point and not dst.is_floating_point) and not (src != BOOL and dst == BOOL)
 MIXED = [(I32, I64), (I64, F32), (BF16, F32), (F16, BF16), (BOOL, I32), (I64, F16)]
@@ -51,7 +55,7 @@ def check_unary(op, a_cpu, layout="contig", path=None, what=""):
         B.tx_force_path(None)
     sync()
     what = "%s %s %s %s %s [%s]" % (op, a_cpu.dtype, tuple(a_cpu.shape), what, layout, used)
-    if op in ("neg", "abs", "logical_not"):
+    if op in EXACT_UNARY:
         assert_exact_fp(out, want, what)
     elif want.dtype == F32:
         assert_ulp(out, want, 2, what)
@@ -92,7 +96,7 @@ def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what="")
     what = "%s %s,%s %s %s %s [%s]" % (op, a_cpu.dtype, b_cpu.dtype, tuple(want.shape), what, layout, used)
     if op in COMPARE:
         assert_exact(out, want, what)
-    elif op in ("div", "pow") and want.dtype.is_floating_point:
+    elif op in ("div", "pow", "atan2") and want.dtype.is_floating_point:
         if want.dtype == F32:
             assert_ulp(out, want, 2, what)
         else:
@@ -357,6 +361,22 @@ def test_unary_full_size(op, dt):
     assert check_unary(op, a) == "vec"
 
 
+@pytest.mark.parametrize("op", ["sin", "log2", "rsqrt", "silu", "round", "isfinite", "square"])
+def test_third_batch_unary_full_size(op):
+    x = I.typed(FULL, F32, seed=9, specials=0.01)
+    assert check_unary(op, x) == "vec"
+    if op in ("sin", "silu"):
+        wide = torch.linspace(-100.0, 100.0, 1 << 20).view(1024, 1024) * (1000.0 if op == "sin" else 1.0)
+        check_unary(op, wide, what="wide range")
+
+
+def test_third_batch_binary_full_size():
+    a, b = I.typed(FULL, F32, seed=10, specials=0.01), I.typed(FULL, F32, seed=11, specials=0.01)
+    assert check_binary("atan2", a, b) == "vec"
+    ai, bi = I.typed(FULL, I32, seed=12), I.typed(FULL, I32, seed=13)
+    assert check_binary("bitwise_xor", ai, bi) == "vec"
+
+
 @pytest.mark.parametrize("op", ["log1p", "expm1", "logsigmoid"])
 def test_new_unary_full_size_and_wide_range(op):
     a = I.typed(FULL, F32, seed=176, specials=0.01)
@@ -505,7 +525,7 @@ def test_unary_out_casting():
                 B.tx_unary(op, torch.empty(a.shape, dtype=dst, device="cuda"), da_)
             assert e.value.kind == "DTYPE"
             continue
-        cls = "exact" if op in ("neg", "abs", "logical_not") else "half" if (rd != F32 or dst != F32) else "f32"
+        cls = "exact" if op in EXACT_UNARY else "half" if (rd != F32 or dst != F32) else "f32"
         check_cast(lambda: O.unary(op, a, out_dtype=dst), lambda o: B.tx_unary(op, o, da_), cls,
                    "%s %s -> %s" % (op, src, dst))
 
