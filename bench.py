@@ -188,6 +188,8 @@ def build_ops(torch, B):
     extra("softmax_f32_dim0[4096,32768]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(oT, sT, 0, False))
     s3, o3d = sf.view(64, 4096, 512), osf.view(64, 4096, 512)
     extra("log_softmax_f32_dim1[64,4096,512]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(o3d, s3, 1, True))
+    sC, oC = sf.view(512, 128, 2048), osf.view(512, 128, 2048)       # softmax over 128 channels
+    extra("softmax_f32_dim1[512,128,2048]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(oC, sC, 1, False))
     wsc = B.workspace(max(B.tx_cumsum_workspace_bytes(oT, lx.view(4096, 32768), 0),
                           B.tx_cumsum_workspace_bytes(osf.view(65536, 2048), lx.view(65536, 2048), 0)))
     extra("cumsum_f32_dim0[4096,32768]", "f3", "colscan_apply_kernel", ns * 8, ns,
