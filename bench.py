@@ -266,10 +266,13 @@ def build_ops(torch, B):
     wsia = B.workspace(B.tx_index_add_workspace_bytes(dst_f, 0, rows, src, True))
     extra("index_add_f32_rows_alpha", "f3", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
           lambda: B.tx_index_add_(dst_f, 0, rows, src, 0.5, True, wsia))
+    wsrr = B.workspace(B.tx_scatter_reduce_workspace_bytes(dst_f, 0, eidx, src, "amax", True))
+    extra("scatter_reduce_amax_f32_rows", "f3", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
+          lambda: B.tx_scatter_reduce_(dst_f, 0, eidx, src, "amax", True, wsrr))
     NR = 131072                                      # element-wise paths: one sort entry per element, so a smaller source
-    eidx_r = eidx[:NR]
+    eidx_r = eidx[:NR].contiguous()                  # a materialised index: element keys
     wssr = B.workspace(B.tx_scatter_reduce_workspace_bytes(dst_f, 0, eidx_r, src[:NR], "amax", True))
-    extra("scatter_reduce_amax_f32[131072,256]", "f3", "seg_reduce_kernel", NR * W * (4 + 8 + 8), NR * W,
+    extra("scatter_reduce_amax_f32_elem_index[131072,256]", "f3", "seg_reduce_kernel", NR * W * (4 + 8 + 8), NR * W,
           lambda: B.tx_scatter_reduce_(dst_f, 0, eidx_r, src[:NR], "amax", True, wssr))
     wsip = B.workspace(B.tx_index_put_workspace_bytes(dst_f, [rows[:NR]], src[:NR], True))
     extra("index_put_accumulate_f32_rows[131072,256]", "f3", "seg_rows_kernel", NR * (W * 4 + 8) + 2 * ND * W * 4, NR * W,

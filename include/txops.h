@@ -316,8 +316,11 @@ enum { TX_SCATTER_SUM = 0, TX_SCATTER_PROD = 1, TX_SCATTER_MEAN = 2, TX_SCATTER_
  * nothing keep their bits.  Shapes and dtypes as tx_scatter_add_; bool: SUM
  * and AMAX are OR, PROD and AMIN are AND, MEAN is TX_ERR_DTYPE.  Integers wrap, MEAN divides rounding toward -infinity; floats
  * are combined in binary64 in position order and rounded once; AMAX / AMIN give
- * NaN when a NaN takes part.  Always the sorted path (reproducible run to run):
- * needs a 16-byte aligned workspace of tx_scatter_reduce_workspace_bytes(). */
+ * NaN when a NaN takes part.  Always a sorted path (reproducible run to run):
+ * needs a 16-byte aligned workspace of tx_scatter_reduce_workspace_bytes().
+ * SUM, AMAX and AMIN over dim 0 with a row id broadcast over contiguous rows
+ * take the whole-row kernels of tx_scatter_add_ (sums of floats then in fp32,
+ * in sorted source-row order). */
 tx_status tx_scatter_reduce_(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src, int reduce,
                              int include_self, void* ws, size_t ws_bytes, void* stream);
 size_t tx_scatter_reduce_workspace_bytes(const tx_tensor* self, int64_t dim, const tx_tensor* index, const tx_tensor* src,
@@ -389,7 +392,9 @@ const char* tx_last_path(void);
  * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".
  * Reduction with lanes along the kept dim: "cols-nv1", "cols-nv2", "cols-nv4"
  * (vectors per thread).  Integer scatter_add_: "scatter-atomic" (one atomic
- * per element even when a workspace is given).  softmax / cumsum along a
+ * per element even when a workspace is given).  scatter_reduce_:
+ * "scatter-reduce-sort" (element keys even for a broadcast row index).
+ * softmax / cumsum along a
  * non-innermost dim: "softmax-strided", "scan-strided" (one lane per slice
  * instead of the column kernels).  layer_norm: "layer-norm-block" (one
  * workgroup per row), "layer-norm-generic" (three passes, any strides).

@@ -19,6 +19,7 @@
 //                  on the data alone.
 #include <algorithm>
 #include <cstring>
+#include <limits>
 
 #include "common.h"
 #include "index_util.h"
@@ -494,6 +495,7 @@ struct SegRowArgs {
   unsigned int* nstart;          // length of start_list (cleared by row_keys_kernel)
   float alpha_f;                 // multiplier of every sum (floating dtypes / integer dtypes)
   int64_t alpha_i;
+  int include_self;              // OP >= 0 kernels only: whether self takes part
 };
 
 // Accumulator of a segmented row sum: fp32 for the floating dtypes, wrapping unsigned arithmetic for integers.
@@ -503,6 +505,33 @@ template <> struct SegAcc<int64_t> { using type = unsigned long long; };
 template <class T, class Acc> __device__ __forceinline__ T seg_add(T old, Acc sum) {
   if constexpr (std::is_integral<T>::value) return (T)((Acc)old + sum);
   else return cvt<T>(cvt<float>(old) + sum);
+}
+
+// OP >= 0 variants of the row kernels (scatter_reduce_ with a broadcast row index; OP = -1 is scatter_add_ with its
+// multiplier): the same walk with the combining operator one of sum, amax and amin (all exact or order-insensitive enough for an fp32
+// accumulator; prod and mean are not), and self taking part or not.  Integer accumulators hold the value's bits.
+template <class T, class Acc, int OP> __device__ __forceinline__ Acc seg_identity() {
+  if constexpr (OP != kRedAmax && OP != kRedAmin) return Acc(0);
+  else if constexpr (std::is_integral<T>::value)
+    return (Acc)(OP == kRedAmax ? std::numeric_limits<T>::lowest() : std::numeric_limits<T>::max());
+  else return OP == kRedAmax ? -__builtin_inff() : __builtin_inff();
+}
+template <class T, class Acc, int OP> __device__ __forceinline__ Acc seg_op(Acc a, Acc v) {
+  if constexpr (OP != kRedAmax && OP != kRedAmin) {
+    return a + v;
+  } else if constexpr (std::is_integral<T>::value) {
+    const T x = (T)a, y = (T)v;
+    return (Acc)(OP == kRedAmax ? (y > x ? y : x) : (y < x ? y : x));
+  } else {
+    // v replaces a when it is beyond it or NaN; a NaN a stays
+    const Acc r = OP == kRedAmax ? (!(v <= a) ? v : a) : (!(v >= a) ? v : a);
+    return a != a ? a : r;
+  }
+}
+template <class T, class Acc, int OP> __device__ __forceinline__ T seg_finish(int include_self, T old, Acc acc) {
+  if (include_self) acc = seg_op<T, Acc, OP>(acc, cvt<Acc>(old));
+  if constexpr (std::is_integral<T>::value) return (T)acc;
+  else return cvt<T>(acc);
 }
 
 // Segmented row sums over sorted (destination row, source row) pairs.  One wave owns a chunk of 128
@@ -522,9 +551,11 @@ template <class T, class Acc> __device__ __forceinline__ T seg_add(T old, Acc su
 // chunk boundaries are parked in part_a / part_b and added by seg_combine_kernel in chunk order.
 constexpr int kSegSlots = 8;
 
-template <class T, int VEC>
+template <class T, int VEC, int OP>
 __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
   using Acc = typename SegAcc<T>::type;
+  constexpr bool GENERAL = OP >= 0;
+  const Acc ident = seg_identity<T, Acc, OP>();
   constexpr int kBatch = 8;
   static_assert(kSegSlots >= kBatch, "a drained buffer must take every run that can end in one batch");
   static_assert(sizeof(Acc) * VEC <= 16, "one slot is at most 1 KiB per wave");
@@ -557,7 +588,7 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
     T* self_col = (T*)a.self + (active ? col : 0);
     Vec<Acc, VEC> acc;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) acc.v[e] = Acc(0);
+    for (int e = 0; e < VEC; ++e) acc.v[e] = ident;
     uint32_t cur = first_key;
     bool first_piece = true;
     int nbuf = 0;                              // finished runs waiting in done_rows[w]
@@ -593,7 +624,10 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
           const Vec<Acc, VEC> sum = done_rows[w][i][lane];
           Vec<T, VEC> t;
 #pragma unroll
-          for (int q = 0; q < VEC; ++q) t.v[q] = seg_add<T, Acc>(row[i].v[q], scaled<T, Acc>(sum.v[q], a.alpha_f, a.alpha_i));
+          for (int q = 0; q < VEC; ++q) {
+            if constexpr (GENERAL) t.v[q] = seg_finish<T, Acc, OP>(a.include_self, row[i].v[q], sum.v[q]);
+            else t.v[q] = seg_add<T, Acc>(row[i].v[q], scaled<T, Acc>(sum.v[q], a.alpha_f, a.alpha_i));
+          }
           if (active) vec_store<T, VEC, true>(self_col + (int64_t)key * a.self_row, t);
         }
       nbuf = 0;
@@ -620,12 +654,15 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
               nbuf = __builtin_amdgcn_readfirstlane(nbuf + 1);
             }
 #pragma unroll
-            for (int q = 0; q < VEC; ++q) acc.v[q] = Acc(0);
+            for (int q = 0; q < VEC; ++q) acc.v[q] = ident;
             cur = k[b];
             first_piece = false;
           }
 #pragma unroll
-          for (int q = 0; q < VEC; ++q) acc.v[q] += cvt<Acc>(row[b].v[q]);
+          for (int q = 0; q < VEC; ++q) {
+            if constexpr (GENERAL) acc.v[q] = seg_op<T, Acc, OP>(acc.v[q], cvt<Acc>(row[b].v[q]));
+            else acc.v[q] += cvt<Acc>(row[b].v[q]);
+          }
         }
       }
       // runs that will end in the next batch (its keys are already here): make room if they might not fit
@@ -667,9 +704,11 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
 // workgroups walk the start list; each run is handled by one workgroup whose waves take contiguous
 // sub-ranges of the pieces and are then added in wave order, so the order of additions depends only on
 // the data.
-template <class T, int VEC>
+template <class T, int VEC, int OP>
 __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(const SegRowArgs a) {
   using Acc = typename SegAcc<T>::type;
+  constexpr bool GENERAL = OP >= 0;
+  const Acc ident = seg_identity<T, Acc, OP>();
   __shared__ long long end_chunk;
   __shared__ Acc sub[kCombineWaves][kWave * VEC];
   const Acc* const part_a = (const Acc*)a.part_a;
@@ -700,13 +739,16 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
       const bool active = col < a.width;
       Acc acc[VEC];
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[e] = Acc(0);
+      for (int e = 0; e < VEC; ++e) acc[e] = ident;
       if (active) {
 #pragma unroll 16
         for (int64_t p = p0; p < p1; ++p) {
           const Acc* src = part_a + p * a.width + col;
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) acc[e] += src[e];
+          for (int e = 0; e < VEC; ++e) {
+            if constexpr (GENERAL) acc[e] = seg_op<T, Acc, OP>(acc[e], src[e]);
+            else acc[e] += src[e];
+          }
         }
       }
 #pragma unroll
@@ -718,8 +760,13 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           Acc t = b[e];
-          for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
-          d[e] = seg_add<T, Acc>(d[e], scaled<T, Acc>(t, a.alpha_f, a.alpha_i));
+          if constexpr (GENERAL) {
+            for (int ww = 0; ww < kCombineWaves; ++ww) t = seg_op<T, Acc, OP>(t, sub[ww][lane * VEC + e]);
+            d[e] = seg_finish<T, Acc, OP>(a.include_self, d[e], t);
+          } else {
+            for (int ww = 0; ww < kCombineWaves; ++ww) t += sub[ww][lane * VEC + e];
+            d[e] = seg_add<T, Acc>(d[e], scaled<T, Acc>(t, a.alpha_f, a.alpha_i));
+          }
         }
       }
       __syncthreads();
@@ -855,7 +902,8 @@ tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_bu
 // per source element by plain row sums, and hot destination rows no longer serialise on atomics.
 template <class T>
 tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int dim, const tx_tensor* index,
-                                const tx_tensor* src, char* ws, hipStream_t s, Alpha alpha) {
+                                const tx_tensor* src, char* ws, hipStream_t s, Alpha alpha, int general_op = -1,
+                                int include_self = 1) {
   constexpr int V = sizeof(T) == 2 ? 4 : 16 / sizeof(T);     // row kernels: at most 16 bytes of accumulators per lane
   constexpr int kVecBytes = V * (int)sizeof(T);
   uint32_t* keys0 = (uint32_t*)(ws + p.off_keys[0]);
@@ -900,18 +948,26 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   a.nstart = (unsigned int*)(ws + p.off_counter);
   a.alpha_f = alpha.f;
   a.alpha_i = alpha.i;
+  a.include_self = include_self;
   const bool al = p.width % V == 0 && (uintptr_t)src->data % kVecBytes == 0 && (uintptr_t)self->data % kVecBytes == 0 &&
                   (a.src_row * (int64_t)sizeof(T)) % kVecBytes == 0 && (a.self_row * (int64_t)sizeof(T)) % kVecBytes == 0;
   const unsigned gb = (unsigned)((p.nchunks + kWaves - 1) / kWaves);
   set_path(al ? "scatter-sort-rows" : "scatter-sort-rows-scalar");
   const unsigned cg = (unsigned)std::min<int64_t>(kCombineBlocks, p.nchunks);
-  if (al) {
-    hipLaunchKernelGGL((seg_rows_kernel<T, V>), dim3(gb), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL((seg_combine_kernel<T, V>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
-  } else {
-    hipLaunchKernelGGL((seg_rows_kernel<T, 1>), dim3(gb), dim3(kBlock), 0, s, a);
-    hipLaunchKernelGGL((seg_combine_kernel<T, 1>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
-  }
+  auto launch = [&](auto vec, auto op) {
+    constexpr int VV = decltype(vec)::value, OP = decltype(op)::value;
+    hipLaunchKernelGGL((seg_rows_kernel<T, VV, OP>), dim3(gb), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((seg_combine_kernel<T, VV, OP>), dim3(cg), dim3(kCombineWaves * kWave), 0, s, a);
+  };
+  auto with_op = [&](auto op) {
+    if (al) launch(std::integral_constant<int, V>{}, op);
+    else launch(std::integral_constant<int, 1>{}, op);
+  };
+  if (general_op >= 0) set_path(al ? "scatter-reduce-rows" : "scatter-reduce-rows-scalar");
+  if (general_op == kRedSum) with_op(std::integral_constant<int, kRedSum>{});
+  else if (general_op == kRedAmax) with_op(std::integral_constant<int, kRedAmax>{});
+  else if (general_op == kRedAmin) with_op(std::integral_constant<int, kRedAmin>{});
+  else with_op(std::integral_constant<int, -1>{});
   return check_launch("segmented row sum");
 }
 
@@ -1029,6 +1085,14 @@ tx_status scatter_reduce_typed(const ScatterPlan& p, const tx_tensor* self, int 
   hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, (const uint32_t*)(ws + p.off_keys[cur]),
                      (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea, mode, include_self);
   return check_launch("scatter_reduce segmented kernel");
+}
+
+// scatter_reduce_ through the whole-row kernels: sum, amax, amin (an fp32 accumulator is exact for the extrema and
+// inside the tolerance for sums; products and means are left to the element path), row layout, not bool
+bool scatter_reduce_rows_ok(const tx_tensor* self, int d, const tx_tensor* index, const tx_tensor* src, int reduce) {
+  if (reduce != TX_SCATTER_SUM && reduce != TX_SCATTER_AMAX && reduce != TX_SCATTER_AMIN) return false;
+  if (self->dtype == TX_BOOL || !strcmp(forced_path(), "scatter-reduce-sort")) return false;
+  return is_row_mode(self, d, index, src);
 }
 
 // index_put_: checks; fills the kernel arguments (shape I + rest, strides of every operand over it)
@@ -1295,6 +1359,7 @@ size_t tx_scatter_reduce_workspace_bytes(const tx_tensor* self, int64_t dim, con
   if (scatter_checks(self, dim, index, src, &d) || numel(index) == 0) return 0;
   if (reduce == TX_SCATTER_SUM && include_self) return scatter_ws_bytes(self, d, index, src, 1);
   ScatterPlan p;
+  if (scatter_reduce_rows_ok(self, d, index, src, reduce)) return scatter_plan(self, d, index, src, &p) ? 0 : p.bytes;
   if (elem_sort_plan("scatter_reduce_", self, numel(index), &p)) return 0;
   return p.bytes;
 }
@@ -1314,6 +1379,18 @@ tx_status tx_scatter_reduce_(const tx_tensor* self, int64_t dim, const tx_tensor
   if (reduce == TX_SCATTER_SUM && include_self)
     return scatter_core("scatter_reduce_", self, d, index, src, Alpha{1.0f, 1}, 1, ws, ws_bytes, s);
   ScatterPlan p;
+  if (scatter_reduce_rows_ok(self, d, index, src, reduce)) {
+    // a row id broadcast over the trailing dims: whole rows, sorted by destination, as scatter_add_ does
+    if ((rc = scatter_plan(self, d, index, src, &p)) || (rc = sort_ws_checks("scatter_reduce_", p, ws, ws_bytes))) return rc;
+    const Alpha one{1.0f, 1};
+    switch (self->dtype) {
+      case TX_F32: return scatter_deterministic<float>(p, self, d, index, src, (char*)ws, s, one, reduce, include_self);
+      case TX_BF16: return scatter_deterministic<bf16>(p, self, d, index, src, (char*)ws, s, one, reduce, include_self);
+      case TX_F16: return scatter_deterministic<f16>(p, self, d, index, src, (char*)ws, s, one, reduce, include_self);
+      case TX_I32: return scatter_deterministic<int32_t>(p, self, d, index, src, (char*)ws, s, one, reduce, include_self);
+      default: return scatter_deterministic<int64_t>(p, self, d, index, src, (char*)ws, s, one, reduce, include_self);
+    }
+  }
   if ((rc = elem_sort_plan("scatter_reduce_", self, n, &p)) || (rc = sort_ws_checks("scatter_reduce_", p, ws, ws_bytes))) return rc;
   switch (self->dtype) {
     case TX_F32: return scatter_reduce_typed<float>(p, self, d, index, src, reduce, include_self, (char*)ws, s);

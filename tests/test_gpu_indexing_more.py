@@ -376,6 +376,37 @@ def test_index_put_sweep():
     assert e.value.kind == "WORKSPACE"
 
 
+def test_scatter_reduce_whole_rows():
+    # a row id broadcast over the trailing dims: sum, amax and amin take the sorted whole-row kernels
+    g = torch.Generator().manual_seed(470)
+    cases = [(37, 1000, 256, "uniform"), (37, 1000, 99, "uniform"), (9, 1500, 64, "hot"), (300, 130, 24, "uniform"),
+             (5, 700, 16, "one")]
+    for dt, (nrow, n, width, kind) in itertools.product((F32, BF16, F16, I32, I64), cases):
+        s, src = I.typed((nrow, width), dt, seed=471), I.typed((n, width), dt, seed=472)
+        if kind == "uniform":
+            rows = torch.randint(0, nrow, (n,), generator=g)
+        elif kind == "hot":                           # one destination takes most rows: runs that pass through whole chunks
+            rows = torch.where(torch.rand(n, generator=g) < 0.9, torch.tensor(4), torch.randint(0, nrow, (n,), generator=g))
+        else:
+            rows = torch.full((n,), 2)
+        idx = rows.unsqueeze(1).expand(n, width)
+        for reduce, inc in (("sum", False), ("amax", True), ("amax", False), ("amin", True), ("amin", False)):
+            used = check_scatter_reduce(s, 0, idx, src, reduce, inc, what=kind)
+            assert used == ("scatter-reduce-rows" if width % 4 == 0 else "scatter-reduce-rows-scalar"), used
+        assert check_scatter_reduce(s, 0, idx, src, "mean", True, what=kind) == "scatter-reduce-sort"
+    # NaN in src, int32 index, a strided destination whose rows stay contiguous, and the same input forced onto the element path
+    s, src = I.typed((64, 128), F32, seed=473), I.typed((900, 128), F32, seed=474, specials=0.02)
+    rows = torch.randint(0, 32, (900,), generator=g)
+    idx = rows.to(I32).unsqueeze(1).expand(900, 128)
+    for reduce, inc in (("amax", True), ("amin", False), ("sum", False)):
+        assert check_scatter_reduce(s[::2], 0, idx, src, reduce, inc, what="views").startswith("scatter-reduce-rows")
+        B.tx_force_path("scatter-reduce-sort")
+        try:
+            assert check_scatter_reduce(s[::2], 0, idx, src, reduce, inc, what="forced") == "scatter-reduce-sort"
+        finally:
+            B.tx_force_path(None)
+
+
 def test_scatter_reduce_and_index_put_larger():
     g = torch.Generator().manual_seed(480)
     s, src = I.typed((4096, 256), F32, seed=481), I.typed((65536, 256), F32, seed=482)
