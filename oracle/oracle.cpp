@@ -73,10 +73,12 @@ enum {
 enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, ORC_GELU, ORC_LOG1P, ORC_EXPM1,
        ORC_LOGSIGMOID, ORC_LOGICAL_NOT, ORC_SIN, ORC_COS, ORC_EXP2, ORC_LOG2, ORC_LOG10, ORC_RSQRT, ORC_RECIPROCAL,
        ORC_SILU, ORC_SQUARE, ORC_SIGN, ORC_FLOOR, ORC_CEIL, ORC_TRUNC, ORC_ROUND, ORC_ISNAN, ORC_ISINF, ORC_ISFINITE,
-       ORC_BITWISE_NOT };
+       ORC_BITWISE_NOT, ORC_TAN, ORC_ASIN, ORC_ACOS, ORC_ATAN, ORC_SINH, ORC_COSH, ORC_ASINH, ORC_ACOSH, ORC_ATANH, ORC_ERF,
+       ORC_ERFC, ORC_RELU, ORC_FRAC, ORC_SIGNBIT, ORC_HARDSWISH, ORC_HARDSIGMOID, ORC_MISH };
 enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM, ORC_NE, ORC_LT, ORC_LE, ORC_GT, ORC_GE,
        ORC_LOGICAL_AND, ORC_LOGICAL_OR, ORC_LOGICAL_XOR, ORC_POW, ORC_BITWISE_AND, ORC_BITWISE_OR, ORC_BITWISE_XOR,
-       ORC_ATAN2 };
+       ORC_ATAN2, ORC_FMOD, ORC_REMAINDER, ORC_HYPOT, ORC_COPYSIGN, ORC_LOGADDEXP, ORC_LOGADDEXP2, ORC_XLOGY, ORC_HEAVISIDE,
+       ORC_FMAX, ORC_FMIN, ORC_NEXTAFTER, ORC_GCD, ORC_LCM, ORC_SHIFT_LEFT, ORC_SHIFT_RIGHT };
 enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
        ORC_LOGSUMEXP };
 
@@ -369,6 +371,41 @@ int64_t int_pow(int64_t b, int64_t e) {
   return (int64_t)r;
 }
 
+// greatest common divisor of the magnitudes (Euclid); gcd(0, 0) = 0
+uint64_t gcd_mag(int64_t a, int64_t b) {
+  uint64_t x = a < 0 ? 0 - (uint64_t)a : (uint64_t)a, y = b < 0 ? 0 - (uint64_t)b : (uint64_t)b;
+  while (y) {
+    uint64_t t = x % y;
+    x = y;
+    y = t;
+  }
+  return x;
+}
+
+// the value of format `dt` next to a in the direction of b: b when they are equal, the smallest subnormal when a
+// is a zero, otherwise one step on a's encoding (sign-magnitude, so magnitude + 1 moves away from zero and the
+// largest finite value steps to infinity); NaN when either is NaN
+double next_toward(double a, double b, int dt) {
+  if (std::isnan(a) || std::isnan(b)) return std::numeric_limits<double>::quiet_NaN();
+  if (a == b) return b;
+  const bool away = (a < b) == (a > 0.0);           // the step grows the magnitude
+  if (dt == ORC_F32) {
+    uint32_t u;
+    float f = (float)a;
+    if (a == 0.0) { u = (b < 0.0 ? 0x80000000u : 0u) | 1u; }
+    else { std::memcpy(&u, &f, 4); u = away ? u + 1 : u - 1; }
+    std::memcpy(&f, &u, 4);
+    return (double)f;
+  }
+  uint16_t h;
+  if (a == 0.0) h = (uint16_t)((b < 0.0 ? 0x8000u : 0u) | 1u);
+  else {
+    h = dt == ORC_F16 ? double_to_f16(a) : double_to_bf16(a);
+    h = (uint16_t)(away ? h + 1 : h - 1);
+  }
+  return dt == ORC_F16 ? f16_to_double(h) : bf16_to_double(h);
+}
+
 const double kNaN = std::numeric_limits<double>::quiet_NaN();
 const double kInf = std::numeric_limits<double>::infinity();
 
@@ -405,6 +442,15 @@ int orc_unary_result_dtype(int op, int in_dtype) {
       return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
     case ORC_BITWISE_NOT:
       return is_float(in_dtype) ? ORC_ERR_DTYPE : in_dtype;
+    case ORC_TAN: case ORC_ASIN: case ORC_ACOS: case ORC_ATAN: case ORC_SINH: case ORC_COSH: case ORC_ASINH: case ORC_ACOSH:
+    case ORC_ATANH: case ORC_ERF: case ORC_ERFC:
+      return is_float(in_dtype) ? in_dtype : ORC_F32;
+    case ORC_RELU:
+      return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
+    case ORC_FRAC: case ORC_HARDSWISH: case ORC_HARDSIGMOID: case ORC_MISH:
+      return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_SIGNBIT:
+      return ORC_BOOL;
   }
   return ORC_ERR_DTYPE;
 }
@@ -418,12 +464,17 @@ int orc_infer_binary(int op, const orc_tensor* a, const orc_tensor* b, int32_t* 
   const orc_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
-  if (op < ORC_ADD || op > ORC_ATAN2) return ORC_ERR_DTYPE;
+  if (op < ORC_ADD || op > ORC_SHIFT_RIGHT) return ORC_ERR_DTYPE;
   if (op == ORC_DIV && !is_float(common)) res = ORC_F32;   // true division
   if (op == ORC_EQ || (op >= ORC_NE && op <= ORC_LOGICAL_XOR)) res = ORC_BOOL;   // comparison and logical families
   if (op == ORC_POW && common == ORC_BOOL) return ORC_ERR_DTYPE;                 // no bool power
   if (op >= ORC_BITWISE_AND && op <= ORC_BITWISE_XOR && is_float(common)) return ORC_ERR_DTYPE;
   if (op == ORC_ATAN2 && !is_float(common)) res = ORC_F32;
+  if ((op == ORC_FMOD || op == ORC_REMAINDER) && common == ORC_BOOL) return ORC_ERR_DTYPE;
+  if ((op == ORC_HYPOT || op == ORC_LOGADDEXP || op == ORC_LOGADDEXP2 || op == ORC_NEXTAFTER) && !is_float(common)) return ORC_ERR_DTYPE;
+  if ((op == ORC_COPYSIGN || op == ORC_XLOGY) && !is_float(common)) res = ORC_F32;
+  if (op == ORC_HEAVISIDE && a->dtype != b->dtype) return ORC_ERR_DTYPE;        // no promotion between the two
+  if (op >= ORC_GCD && op <= ORC_SHIFT_RIGHT && (is_float(common) || common == ORC_BOOL)) return ORC_ERR_DTYPE;
   if (op == ORC_SUB && (a->dtype == ORC_BOOL || b->dtype == ORC_BOOL)) return ORC_ERR_DTYPE;   // no bool subtraction
   int nd;
   int64_t s[ORC_MAX_DIMS];
@@ -454,6 +505,11 @@ int orc_where_result_dtype(const orc_tensor* x, const orc_tensor* y) {
 //   floor ceil trunc round : floats (round: halves to even, the sign of zero is kept); integers are returned as they
 //                   are; bool is a dtype error.  isnan / isinf / isfinite: bool result, integers are finite.
 //   bitwise_not   : ~x for integers, logical not for bool, floats are a dtype error.
+//   tan asin acos atan sinh cosh asinh acosh atanh erf erfc : like exp.
+//   relu          : x < 0 ? 0 : x (a NaN and -0.0 stay); integers too; bool is a dtype error.
+//   frac          : x - trunc(x) (so frac(+-inf) is NaN); hardsigmoid: min(max(x + 3, 0), 6) / 6; hardswish: x times
+//                   that; mish: x * tanh(log1p(exp(x))).  Floating dtypes only; a NaN gives NaN.
+//   signbit       : the sign bit of a float (-0.0 and negative NaNs included), x < 0 for an integer, false for a bool.
 //   neg, abs      : exact; integers wrap (abs(INT_MIN) == INT_MIN); floats
 //                   flip / clear the sign bit (NaN and zeros included).
 //   exp log sqrt sigmoid tanh : binary64 evaluation of the input converted to
@@ -505,6 +561,24 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
       }
       continue;
     }
+    if (op == ORC_SIGNBIT) {
+      bool neg;
+      if (is_float(a->dtype)) {
+        const int es = esize(a->dtype);
+        uint32_t bits = 0;
+        std::memcpy(&bits, cptr(a, ao), es);
+        neg = (bits >> (8 * es - 1)) & 1u;
+      } else {
+        neg = a->dtype != ORC_BOOL && load_int(a, ao) < 0;
+      }
+      put_int(out, oo, ORC_BOOL, neg);
+      continue;
+    }
+    if (op == ORC_RELU && !is_float(a->dtype)) {
+      const int64_t v = load_int(a, ao);
+      put_int(out, oo, rd, v < 0 ? 0 : v);
+      continue;
+    }
     if (op == ORC_ISNAN || op == ORC_ISINF || op == ORC_ISFINITE) {       // integers and bools are always finite
       const double v = is_float(a->dtype) ? load_flt(a, ao) : 0.0;
       put_int(out, oo, ORC_BOOL, op == ORC_ISNAN ? std::isnan(v) : op == ORC_ISINF ? std::isinf(v) : std::isfinite(v));
@@ -547,6 +621,27 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
       case ORC_EXPM1: y = std::expm1(x); break;
       // log(1 / (1 + exp(-x))) written so that neither tail overflows or cancels: min(x, 0) - log1p(exp(-|x|))
       case ORC_LOGSIGMOID: y = (x < 0.0 ? x : 0.0) - std::log1p(std::exp(-std::fabs(x))); break;
+      case ORC_TAN: y = std::tan(x); break;
+      case ORC_ASIN: y = std::asin(x); break;
+      case ORC_ACOS: y = std::acos(x); break;
+      case ORC_ATAN: y = std::atan(x); break;
+      case ORC_SINH: y = std::sinh(x); break;
+      case ORC_COSH: y = std::cosh(x); break;
+      case ORC_ASINH: y = std::asinh(x); break;
+      case ORC_ACOSH: y = std::acosh(x); break;
+      case ORC_ATANH: y = std::atanh(x); break;
+      case ORC_ERF: y = std::erf(x); break;
+      case ORC_ERFC: y = std::erfc(x); break;
+      case ORC_RELU: y = x < 0.0 ? 0.0 : x; break;
+      case ORC_FRAC: y = x - std::trunc(x); break;
+      case ORC_HARDSIGMOID: case ORC_HARDSWISH: {
+        double t = x + 3.0;
+        t = t < 0.0 ? 0.0 : t;                      // a NaN fails both comparisons and stays
+        t = t > 6.0 ? 6.0 : t;
+        y = op == ORC_HARDSWISH ? x * t / 6.0 : t / 6.0;
+        break;
+      }
+      case ORC_MISH: y = x * std::tanh(std::log1p(std::exp(x))); break;
     }
     put_flt(out, oo, rd, y);
   }
@@ -588,6 +683,24 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
 //   atan2   : the angle of the point (b, a), binary64 evaluation of the
 //             converted operands, one rounding; bool / integer operands are
 //             converted to fp32.
+//   fmod    : the remainder with the dividend's sign (C fmod / integer %);
+//             remainder: the one with the divisor's sign (fmod, plus the
+//             divisor when the signs differ and the value is not zero).
+//             bool is a dtype error; an integer zero divisor is ORC_ERR_SCALAR.
+//   hypot   : sqrt(a^2 + b^2) without intermediate overflow, +inf when either
+//             is infinite; logaddexp: log(e^a + e^b) as max + log1p(exp(-|a-b|)),
+//             equal infinities give themselves; logaddexp2: the base-2 form;
+//             nextafter: the neighbour of a toward b in the common format.
+//             Floating common dtype only.
+//   copysign: |a| with b's sign bit; xlogy: NaN if b is NaN, else 0 if a == 0,
+//             else a * log(b).  bool / integer operands are converted to fp32.
+//   heaviside: 0 for a < 0 and for a NaN a, 1 for a > 0, b for a == 0; both
+//             operands must have the same dtype.
+//   fmax / fmin : the larger / smaller; a NaN only when both are NaN.
+//   gcd / lcm : of the magnitudes, wrapped to the dtype (gcd(0,0) = lcm(0,x) =
+//             0); shift_left / shift_right: a << b and the arithmetic a >> b; a
+//             shift count below 0 or at least the width gives 0, or -1 for a
+//             negative a shifted right.  int32 / int64 only.
 // `out` may have any dtype the result dtype can be cast to (can_cast): the
 // value is formed in the result dtype, then converted.
 int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_tensor* b, double alpha_f,
@@ -601,12 +714,19 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
   if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
   const orc_tensor* ops[2] = {a, b};
   int cd = result_type(ops, 2);                       // dtype the op is applied in
-  if ((op == ORC_DIV || op == ORC_ATAN2) && !is_float(cd)) cd = ORC_F32;
+  if ((op == ORC_DIV || op == ORC_ATAN2 || op == ORC_COPYSIGN || op == ORC_XLOGY) && !is_float(cd)) cd = ORC_F32;
   if ((op == ORC_ADD || op == ORC_SUB) && !is_float(cd) && !alpha_is_int) return ORC_ERR_SCALAR;
   const double alpha_d = alpha_is_int ? (double)alpha_i : alpha_f;
   const float alpha32 = (float)alpha_d;
   const bool alpha_one = alpha_is_int ? (alpha_i == 1) : (alpha_f == 1.0);
   const int64_t n = numel(out);
+  if ((op == ORC_FMOD || op == ORC_REMAINDER) && !is_float(cd))             // an integer zero divisor anywhere: nothing is written
+    for (int64_t lin = 0; lin < n; ++lin) {
+      int64_t idx[ORC_MAX_DIMS];
+      unravel(lin, nd, sizes, idx);
+      if (load_as(b, bcast_offset(b, nd, idx), cd).i == 0) return ORC_ERR_SCALAR;
+    }
+  const int width = cd == ORC_I32 ? 32 : 64;
 #pragma omp parallel for schedule(static)
   for (int64_t lin = 0; lin < n; ++lin) {
     int64_t idx[ORC_MAX_DIMS];
@@ -615,6 +735,35 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
     Val x = load_as(a, bcast_offset(a, nd, idx), cd);
     Val y = load_as(b, bcast_offset(b, nd, idx), cd);
     if (is_float(cd)) {
+      const double xd = (double)x.f, yd = (double)y.f;
+      switch (op) {
+        case ORC_FMOD: put_flt(out, oo, rd, std::fmod(xd, yd)); break;
+        case ORC_REMAINDER: {
+          double r = std::fmod(xd, yd);
+          if (r != 0.0 && ((r < 0.0) != (yd < 0.0))) r += yd;
+          put_flt(out, oo, rd, r);
+          break;
+        }
+        case ORC_HYPOT: put_flt(out, oo, rd, std::hypot(xd, yd)); break;
+        case ORC_COPYSIGN: put_flt(out, oo, rd, std::copysign(xd, yd)); break;
+        case ORC_LOGADDEXP: case ORC_LOGADDEXP2: {
+          double r;
+          if (std::isnan(xd) || std::isnan(yd)) r = kNaN;
+          else if (std::isinf(xd) && xd == yd) r = xd;
+          else {
+            const double m = xd > yd ? xd : yd, d = -std::fabs(xd - yd);
+            r = op == ORC_LOGADDEXP ? m + std::log1p(std::exp(d)) : m + std::log1p(std::exp2(d)) / std::log(2.0);
+          }
+          put_flt(out, oo, rd, r);
+          break;
+        }
+        case ORC_XLOGY: put_flt(out, oo, rd, std::isnan(yd) ? kNaN : xd == 0.0 ? 0.0 : xd * std::log(yd)); break;
+        case ORC_HEAVISIDE: put_flt(out, oo, rd, xd == 0.0 ? yd : (xd > 0.0 ? 1.0 : 0.0)); break;
+        case ORC_FMAX: put_flt(out, oo, rd, std::isnan(xd) ? yd : std::isnan(yd) ? xd : (yd > xd ? yd : xd)); break;
+        case ORC_FMIN: put_flt(out, oo, rd, std::isnan(xd) ? yd : std::isnan(yd) ? xd : (yd < xd ? yd : xd)); break;
+        case ORC_NEXTAFTER: put_flt(out, oo, rd, next_toward(xd, yd, cd)); break;
+        default: break;
+      }
       switch (op) {
         case ORC_ADD: {
           float r = alpha_one ? (x.f + y.f) : std::fmaf(alpha32, y.f, x.f);
@@ -675,6 +824,9 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_LOGICAL_XOR: case ORC_BITWISE_XOR: put_int(out, oo, rd, x.i ^ y.i); break;
         case ORC_BITWISE_AND: put_int(out, oo, rd, x.i & y.i); break;
         case ORC_BITWISE_OR: put_int(out, oo, rd, x.i | y.i); break;
+        case ORC_HEAVISIDE: put_int(out, oo, rd, x.i ? 1 : y.i); break;
+        case ORC_FMAX: put_int(out, oo, rd, x.i | y.i); break;
+        case ORC_FMIN: put_int(out, oo, rd, x.i & y.i); break;
       }
     } else {
       uint64_t ux = (uint64_t)x.i, uy = (uint64_t)y.i;
@@ -697,6 +849,28 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
         case ORC_BITWISE_AND: put_int(out, oo, rd, x.i & y.i); break;
         case ORC_BITWISE_OR: put_int(out, oo, rd, x.i | y.i); break;
         case ORC_BITWISE_XOR: put_int(out, oo, rd, x.i ^ y.i); break;
+        case ORC_FMOD: case ORC_REMAINDER: {
+          int64_t r = y.i == -1 ? 0 : x.i % y.i;     // by -1 everything divides (and INT_MIN % -1 is not a C expression)
+          if (op == ORC_REMAINDER && r != 0 && ((r < 0) != (y.i < 0))) r += y.i;
+          put_int(out, oo, rd, r);
+          break;
+        }
+        case ORC_HEAVISIDE: put_int(out, oo, rd, x.i == 0 ? y.i : (x.i > 0 ? 1 : 0)); break;
+        case ORC_FMAX: put_int(out, oo, rd, y.i > x.i ? y.i : x.i); break;
+        case ORC_FMIN: put_int(out, oo, rd, y.i < x.i ? y.i : x.i); break;
+        case ORC_GCD: put_int(out, oo, rd, (int64_t)gcd_mag(x.i, y.i)); break;
+        case ORC_LCM: {
+          const uint64_t g = gcd_mag(x.i, y.i);
+          const uint64_t ua = x.i < 0 ? 0 - ux : ux, ub = y.i < 0 ? 0 - uy : uy;
+          put_int(out, oo, rd, g == 0 ? 0 : (int64_t)(ua / g * ub));
+          break;
+        }
+        case ORC_SHIFT_LEFT:
+          put_int(out, oo, rd, (y.i < 0 || y.i >= width) ? 0 : (int64_t)(ux << y.i));
+          break;
+        case ORC_SHIFT_RIGHT:                          // arithmetic: the sign fills
+          put_int(out, oo, rd, (y.i < 0 || y.i >= width) ? (x.i < 0 ? -1 : 0) : (x.i >> y.i));
+          break;
       }
     }
   }
