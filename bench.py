@@ -103,6 +103,11 @@ def build_ops(torch, B):
     extra("isfinite_f32", "f1", "ew_vec_kernel", n2 * 5, n2, lambda: B.tx_unary("isfinite", obool, xf))
     extra("atan2_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("atan2", of, xf, yf))
     extra("pow_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("pow", of, xf, yf))
+    for fourth in ("relu", "hardswish", "erf", "tan", "mish"):
+        extra(fourth + "_f32", "f1", "ew_vec_kernel", n2 * 8, n2, (lambda o: (lambda: B.tx_unary(o, of, xf)))(fourth))
+    extra("relu_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("relu", ob, xb))
+    for fourth in ("fmax", "remainder", "hypot", "logaddexp"):
+        extra(fourth + "_f32", "f1", "ew_vec_kernel", n2 * 12, n2, (lambda o: (lambda: B.tx_binary(o, of, xf, yf)))(fourth))
     extra("clamp_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_clamp(of, xf, -0.5, 0.75))
     extra("clamp_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_clamp(ob, xb, -0.5, 0.75))
     extra("logical_and_f32", "f1", "ew_vec_kernel", n2 * 9, n2, lambda: B.tx_binary("logical_and", obool, xf, yf))

@@ -89,9 +89,13 @@ enum {
 /* operator codes */
 enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU_ERF, TX_LOG1P, TX_EXPM1, TX_LOGSIGMOID,
        TX_LOGICAL_NOT, TX_SIN, TX_COS, TX_EXP2, TX_LOG2, TX_LOG10, TX_RSQRT, TX_RECIPROCAL, TX_SILU, TX_SQUARE, TX_SIGN,
-       TX_FLOOR, TX_CEIL, TX_TRUNC, TX_ROUND, TX_ISNAN, TX_ISINF, TX_ISFINITE, TX_BITWISE_NOT };
+       TX_FLOOR, TX_CEIL, TX_TRUNC, TX_ROUND, TX_ISNAN, TX_ISINF, TX_ISFINITE, TX_BITWISE_NOT, TX_TAN, TX_ASIN, TX_ACOS,
+       TX_ATAN, TX_SINH, TX_COSH, TX_ASINH, TX_ACOSH, TX_ATANH, TX_ERF, TX_ERFC, TX_RELU, TX_FRAC, TX_SIGNBIT,
+       TX_HARDSWISH, TX_HARDSIGMOID, TX_MISH };
 enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE,
-       TX_LOGICAL_AND, TX_LOGICAL_OR, TX_LOGICAL_XOR, TX_POW, TX_BITWISE_AND, TX_BITWISE_OR, TX_BITWISE_XOR, TX_ATAN2 };
+       TX_LOGICAL_AND, TX_LOGICAL_OR, TX_LOGICAL_XOR, TX_POW, TX_BITWISE_AND, TX_BITWISE_OR, TX_BITWISE_XOR, TX_ATAN2,
+       TX_FMOD, TX_REMAINDER, TX_HYPOT, TX_COPYSIGN, TX_LOGADDEXP, TX_LOGADDEXP2, TX_XLOGY, TX_HEAVISIDE, TX_FMAX,
+       TX_FMIN, TX_NEXTAFTER, TX_GCD, TX_LCM, TX_SHIFT_LEFT, TX_SHIFT_RIGHT };
 enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARGMIN, TX_STD, TX_ANY, TX_ALL,
        TX_LOGSUMEXP };
 
@@ -118,7 +122,15 @@ enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARG
  *   FLOOR CEIL TRUNC ROUND : floats (ROUND: halves to even; the sign of zero is
  *              kept); integers are returned unchanged; bool is TX_ERR_DTYPE.
  *   ISNAN ISINF ISFINITE : any dtype, bool result (integers are finite).
- *   BITWISE_NOT : ~x for integers, logical not for bool; floats are TX_ERR_DTYPE. */
+ *   BITWISE_NOT : ~x for integers, logical not for bool; floats are TX_ERR_DTYPE.
+ *   TAN ASIN ACOS ATAN SINH COSH ASINH ACOSH ATANH ERF ERFC : like EXP.
+ *   RELU : x < 0 ? 0 : x (a NaN and -0.0 stay); integers too; bool is
+ *              TX_ERR_DTYPE.
+ *   FRAC : x - trunc(x).  HARDSIGMOID : min(max(x + 3, 0), 6) / 6.  HARDSWISH :
+ *              x times that.  MISH : x * tanh(log1p(exp(x))).  Float dtypes
+ *              only; fp32 results within 2 ulp.
+ *   SIGNBIT : the sign bit of a float (-0.0 and negative NaNs included), x < 0
+ *              for an integer, false for a bool; bool result. */
 tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream);
 
 /* out = a + alpha * b with broadcasting and type promotion.  alpha is given
@@ -137,8 +149,9 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
 
 /* out = a (op) b with broadcasting and type promotion, op in MUL DIV MAXIMUM
  * MINIMUM EQ NE LT LE GT GE LOGICAL_AND LOGICAL_OR LOGICAL_XOR POW BITWISE_AND
- * BITWISE_OR BITWISE_XOR ATAN2 (TX_ADD and TX_SUB are accepted too, with
- * alpha = 1).
+ * BITWISE_OR BITWISE_XOR ATAN2 FMOD REMAINDER HYPOT COPYSIGN LOGADDEXP
+ * LOGADDEXP2 XLOGY HEAVISIDE FMAX FMIN NEXTAFTER GCD LCM SHIFT_LEFT
+ * SHIFT_RIGHT (TX_ADD and TX_SUB are accepted too, with alpha = 1).
  *   MUL: bool AND, integers wrap.  DIV: true division, bool / integer pairs are
  *   computed and returned in fp32.  MAXIMUM / MINIMUM: NaN if either operand is
  *   NaN; on ties the first operand; bool OR / AND.
@@ -155,7 +168,25 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
  *   BITWISE_AND / OR / XOR: on the integers of the common dtype (bool: the
  *   logical operation); a floating common dtype is TX_ERR_DTYPE.
  *   ATAN2: the angle of the point (b, a); bool / integer pairs are computed and
- *   returned in fp32; fp32 results within 2 ulp. */
+ *   returned in fp32; fp32 results within 2 ulp.
+ *   FMOD: the remainder with the dividend's sign; REMAINDER: with the
+ *   divisor's (fmod, plus the divisor when the signs differ and the value is
+ *   not zero).  Exact for floats up to REMAINDER's one addition.  Two bools are
+ *   TX_ERR_DTYPE.  An integer zero divisor is outside the contract: the
+ *   device cannot report it and writes 0 there.
+ *   HYPOT: sqrt(a^2 + b^2) without overflow, +inf when either is infinite.
+ *   LOGADDEXP / LOGADDEXP2: log(e^a + e^b) and its base-2 form, equal
+ *   infinities give themselves.  NEXTAFTER: the neighbour of a toward b in the
+ *   common format.  These four need a floating common dtype.
+ *   COPYSIGN: |a| with b's sign bit.  XLOGY: NaN if b is NaN, else 0 if
+ *   a == 0, else a * log(b).  bool / integer pairs compute and return fp32.
+ *   HEAVISIDE: 0 for a < 0 and for a NaN a, 1 for a > 0, b for a == 0; the
+ *   two dtypes must be equal (TX_ERR_DTYPE otherwise).
+ *   FMAX / FMIN: the larger / smaller; NaN only when both are NaN.
+ *   GCD / LCM: of the magnitudes, wrapped to the dtype (gcd(0, 0) = lcm(0, x) =
+ *   0).  SHIFT_LEFT / SHIFT_RIGHT: a << b and the arithmetic a >> b; a count
+ *   below 0 or at least the width gives 0, or -1 for a negative a shifted
+ *   right.  int32 / int64 only (a bool beside an integer promotes). */
 tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream);
 
 /* out = min(max(x, lo), hi) with scalar bounds; has_lo / has_hi say which are
@@ -371,7 +402,7 @@ size_t tx_nonzero_workspace_bytes(const tx_tensor* out, const tx_tensor* count, 
 
 /* ------------------------------------------------------------------ host-only helpers */
 
-/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_ATAN2). */
+/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_SHIFT_RIGHT). */
 tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_t* dtype, int32_t* ndim,
                           int64_t* sizes);
 /* Result dtype of where(cond, x, y). */

@@ -20,10 +20,14 @@ CODE_DTYPE = {v: k for k, v in DTYPE_CODE.items()}
 UNARY = {"neg": 0, "abs": 1, "exp": 2, "log": 3, "sqrt": 4, "sigmoid": 5, "tanh": 6, "gelu": 7, "log1p": 8, "expm1": 9,
          "logsigmoid": 10, "logical_not": 11, "sin": 12, "cos": 13, "exp2": 14, "log2": 15, "log10": 16, "rsqrt": 17,
          "reciprocal": 18, "silu": 19, "square": 20, "sign": 21, "floor": 22, "ceil": 23, "trunc": 24, "round": 25, "isnan": 26,
-         "isinf": 27, "isfinite": 28, "bitwise_not": 29}
+         "isinf": 27, "isfinite": 28, "bitwise_not": 29, "tan": 30, "asin": 31, "acos": 32, "atan": 33, "sinh": 34, "cosh": 35,
+         "asinh": 36, "acosh": 37, "atanh": 38, "erf": 39, "erfc": 40, "relu": 41, "frac": 42, "signbit": 43, "hardswish": 44,
+         "hardsigmoid": 45, "mish": 46}
 BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimum": 6, "ne": 7, "lt": 8, "le": 9, "gt": 10,
           "ge": 11, "logical_and": 12, "logical_or": 13, "logical_xor": 14, "pow": 15, "bitwise_and": 16, "bitwise_or": 17,
-          "bitwise_xor": 18, "atan2": 19}
+          "bitwise_xor": 18, "atan2": 19, "fmod": 20, "remainder": 21, "hypot": 22, "copysign": 23, "logaddexp": 24,
+          "logaddexp2": 25, "xlogy": 26, "heaviside": 27, "fmax": 28, "fmin": 29, "nextafter": 30, "gcd": 31, "lcm": 32,
+          "bitwise_left_shift": 33, "bitwise_right_shift": 34}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
           "all": 10, "logsumexp": 11}
 

@@ -243,7 +243,7 @@ tx_status binary_impl(int op, const tx_tensor* out, const tx_tensor* a, const tx
   if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the broadcast shape");
   const tx_tensor* ins[2] = {a, b};
   int common = result_type(ins, 2);
-  if ((op == TX_DIV || op == TX_ATAN2) && !dtype_is_float(common)) common = TX_F32;
+  if ((op == TX_DIV || op == TX_ATAN2 || op == TX_COPYSIGN || op == TX_XLOGY) && !dtype_is_float(common)) common = TX_F32;
   if ((op == TX_ADD || op == TX_SUB) && !dtype_is_float(common) && !alpha_is_int)
     return fail(TX_ERR_SCALAR, "floating alpha with an integer / bool result");
   if ((rc = check_out_overlap(out, ins, 2))) return rc;
@@ -271,6 +271,7 @@ tx_status binary_impl(int op, const tx_tensor* out, const tx_tensor* a, const tx
     case TX_BITWISE_AND: case TX_BITWISE_OR: case TX_BITWISE_XOR: case TX_ATAN2:
       return ew_binary_third(it, op, a->dtype, b->dtype, common, s);
   }
+  if (op >= TX_FMOD) return ew_binary_fourth(it, op, a->dtype, b->dtype, common, s);
   return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
 }
 
@@ -297,6 +298,7 @@ tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* strea
   Iter it;
   iter_build(&it, a->ndim, a->sizes, ops, 2);
   hipStream_t s = as_stream(stream);
+  if (op >= TX_TAN) return ew_unary_fourth(it, op, a->dtype, rd, s);
   if (op >= TX_SIN) return ew_unary_third(it, op, a->dtype, rd, s);
   if (out->dtype != rd || op == TX_LOGICAL_NOT) return ew_unary_cast(it, op, a->dtype, rd, s);
   if (op == TX_NEG || op == TX_ABS) {

@@ -36,6 +36,10 @@ tx_status ew_unary_cast(const Iter& it, int op, int in_dtype, int rd, hipStream_
 tx_status ew_unary_third(const Iter& it, int op, int in_dtype, int rd, hipStream_t s);
 tx_status ew_binary_third(const Iter& it, int op, int da, int db, int common, hipStream_t s);
 
+// fourth translation unit (elementwise_d.hip): unary operators from TX_TAN on, binary operators from TX_FMOD on
+tx_status ew_unary_fourth(const Iter& it, int op, int in_dtype, int rd, hipStream_t s);
+tx_status ew_binary_fourth(const Iter& it, int op, int da, int db, int common, hipStream_t s);
+
 namespace {
 
 constexpr int kBlock = 256;

@@ -202,6 +202,17 @@ int32_t tx_infer_unary_dtype(int op, int32_t in) {
     case TX_BITWISE_NOT:
       if (dtype_is_float(in)) return fail(TX_ERR_DTYPE, "bitwise_not takes integer and bool dtypes only");
       return in;
+    case TX_TAN: case TX_ASIN: case TX_ACOS: case TX_ATAN: case TX_SINH: case TX_COSH: case TX_ASINH: case TX_ACOSH:
+    case TX_ATANH: case TX_ERF: case TX_ERFC:
+      return dtype_is_float(in) ? in : TX_F32;
+    case TX_RELU:
+      if (in == TX_BOOL) return fail(TX_ERR_DTYPE, "relu does not take bool");
+      return in;
+    case TX_FRAC: case TX_HARDSWISH: case TX_HARDSIGMOID: case TX_MISH:
+      if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "frac / hardswish / hardsigmoid / mish take floating dtypes only");
+      return in;
+    case TX_SIGNBIT:
+      return TX_BOOL;
   }
   return fail(TX_ERR_DTYPE, "unknown unary op %d", op);
 }
@@ -212,7 +223,7 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (a->ndim < 0 || a->ndim > TX_MAX_DIMS || b->ndim < 0 || b->ndim > TX_MAX_DIMS)
     return fail(TX_ERR_NDIM, "infer_binary: bad ndim");
   if (!dtype_valid(a->dtype) || !dtype_valid(b->dtype)) return fail(TX_ERR_DTYPE, "infer_binary: bad dtype code");
-  if (op < TX_ADD || op > TX_ATAN2) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
+  if (op < TX_ADD || op > TX_SHIFT_RIGHT) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
   const tx_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
@@ -222,6 +233,13 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (op >= TX_BITWISE_AND && op <= TX_BITWISE_XOR && dtype_is_float(common))
     return fail(TX_ERR_DTYPE, "bitwise operators take integer and bool dtypes only");
   if (op == TX_ATAN2 && !dtype_is_float(common)) res = TX_F32;
+  if ((op == TX_FMOD || op == TX_REMAINDER) && common == TX_BOOL) return fail(TX_ERR_DTYPE, "fmod / remainder do not take two bool operands");
+  if ((op == TX_HYPOT || op == TX_LOGADDEXP || op == TX_LOGADDEXP2 || op == TX_NEXTAFTER) && !dtype_is_float(common))
+    return fail(TX_ERR_DTYPE, "hypot / logaddexp / logaddexp2 / nextafter need a floating operand");
+  if ((op == TX_COPYSIGN || op == TX_XLOGY) && !dtype_is_float(common)) res = TX_F32;
+  if (op == TX_HEAVISIDE && a->dtype != b->dtype) return fail(TX_ERR_DTYPE, "heaviside takes two operands of one dtype");
+  if (op >= TX_GCD && op <= TX_SHIFT_RIGHT && (dtype_is_float(common) || common == TX_BOOL))
+    return fail(TX_ERR_DTYPE, "gcd / lcm / shifts take int32 / int64 (a bool with an integer promotes)");
   if (op == TX_SUB && (a->dtype == TX_BOOL || b->dtype == TX_BOOL))
     return fail(TX_ERR_DTYPE, "sub does not take bool operands");
   int nd;

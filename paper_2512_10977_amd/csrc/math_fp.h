@@ -67,6 +67,46 @@ __device__ __forceinline__ double log_d(double a) {
   return __builtin_fma(ef, kLn2Hi, __builtin_fma(ef, kLn2Lo, 2.0 * z * p));
 }
 
+// log1p(t) for 0 <= t <= 1 (t is the exponential of a non-positive number): 2 atanh(t / (2 + t)) while that
+// argument is small enough for the same series (it keeps full relative accuracy down to t = 0), log(1 + t) above
+__device__ __forceinline__ double log1p_unit_d(double t) {
+  if (t > 0.25) return log_d(1.0 + t);
+  const double z = t * rcp_d(2.0 + t);
+  const double w = z * z;
+  double p = 1.0 / 15.0;
+  p = __builtin_fma(p, w, 1.0 / 13.0);
+  p = __builtin_fma(p, w, 1.0 / 11.0);
+  p = __builtin_fma(p, w, 1.0 / 9.0);
+  p = __builtin_fma(p, w, 1.0 / 7.0);
+  p = __builtin_fma(p, w, 1.0 / 5.0);
+  p = __builtin_fma(p, w, 1.0 / 3.0);
+  p = __builtin_fma(p, w, 1.0);
+  return 2.0 * z * p;
+}
+
+// log(e^a + e^b) (base2: log2(2^a + 2^b)) = max + log1p(exp(-|a - b|)); fp32 operands, binary64 evaluation
+__device__ __forceinline__ float logaddexp_f32(float a, float b, bool base2) {
+  if (a != a || b != b) return __uint_as_float(0x7fc00000u);
+  if (a == b && __builtin_fabsf(a) == __builtin_inff()) return a;
+  const double kLn2 = 6.93147180559945309417e-01, kLog2e = 1.4426950408889634074;
+  const double m = (double)(a > b ? a : b);
+  double d = -__builtin_fabs((double)a - (double)b);
+  if (base2) d *= kLn2;
+  d = d < -700.0 ? -700.0 : d;                       // exp(-700) is far below half an ulp of 1
+  const double l = log1p_unit_d(exp_d(d));
+  return (float)(m + (base2 ? l * kLog2e : l));
+}
+
+// mish(x) = x tanh(log(1 + e^x)) = x n / (n + 2) with n = e^x (e^x + 2): one exponential, no cancellation
+__device__ __forceinline__ float mish_f32(float xf) {
+  if (xf > 20.0f) return xf;                          // 1 - tanh(...) = 2 / (n + 2) < 2^-25
+  if (xf == -__builtin_inff()) return __uint_as_float(0x7fc00000u);   // -inf * 0
+  const double x = (double)xf;
+  const double w = exp_d(x < -700.0 ? -700.0 : x);
+  const double n = w * (w + 2.0);
+  return (float)(x * n * rcp_d(n + 2.0));
+}
+
 // fp32 power.  Finite non-zero base and finite exponent: exp(b log|a|) in binary64 (the error of b log|a| stays
 // below 1e-11 wherever the result is finite, far inside one fp32 ulp), the sign from the exponent's parity for a
 // negative base, NaN for a negative base with a non-integer exponent.  Zeros, infinities and NaNs: the device

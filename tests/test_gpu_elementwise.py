@@ -22,11 +22,15 @@ F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, t
 ALL = [F32, BF16, F16, I32, I64, BOOL]
 UNARY = ["neg", "abs", "exp", "log", "sqrt", "sigmoid", "tanh", "gelu", "log1p", "expm1", "logsigmoid", "logical_not",
          "sin", "cos", "exp2", "log2", "log10", "rsqrt", "reciprocal", "silu", "square", "sign", "floor", "ceil", "trunc", "round",
-         "isnan", "isinf", "isfinite", "bitwise_not"]
+         "isnan", "isinf", "isfinite", "bitwise_not", "tan", "asin", "acos", "atan", "sinh", "cosh", "asinh", "acosh", "atanh",
+         "erf", "erfc", "relu", "frac", "signbit", "hardswish", "hardsigmoid", "mish"]
 EXACT_UNARY = ("neg", "abs", "logical_not", "square", "sign", "floor", "ceil", "trunc", "round", "isnan", "isinf", "isfinite",
-               "bitwise_not")
+               "bitwise_not", "relu", "frac", "signbit")
 BINARY = ["add", "mul", "div", "maximum", "eq", "sub", "minimum", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or",
-          "logical_xor", "pow", "bitwise_and", "bitwise_or", "bitwise_xor", "atan2"]
+          "logical_xor", "pow", "bitwise_and", "bitwise_or", "bitwise_xor", "atan2", "fmod", "remainder", "hypot", "copysign",
+          "logaddexp", "logaddexp2", "xlogy", "heaviside", "fmax", "fmin", "nextafter", "gcd", "lcm", "bitwise_left_shift",
+          "bitwise_right_shift"]
+ULP_BINARY = ("div", "pow", "atan2", "remainder", "hypot", "logaddexp", "logaddexp2", "xlogy")
 COMPARE = ("eq", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or", "logical_xor")
 CAST_OK = lambda src, dst: not (src.is_floating_point and not dst.is_floating_point) and not (src != BOOL and dst == BOOL)
 MIXED = [(I32, I64), (I64, F32), (BF16, F32), (F16, BF16), (BOOL, I32), (I64, F16)]
@@ -68,7 +72,19 @@ def check_unary(op, a_cpu, layout="contig", path=None, what=""):
 FLT_TINY = 1.2e-38
 
 
+def nonzero_divisor(t):
+    """An integer zero divisor is outside fmod's / remainder's contract (the oracle refuses it, the device cannot): make
+    every element of the divisor's storage odd, or True, in place, so that views keep their layout."""
+    base = t._base if t._base is not None else t
+    if base.dtype == BOOL:
+        base.fill_(True)
+    else:
+        base.bitwise_or_(1)
+
+
 def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what=""):
+    if op in ("fmod", "remainder") and not a_cpu.dtype.is_floating_point and not b_cpu.dtype.is_floating_point:
+        nonzero_divisor(b_cpu)
     try:
         want = O.binary(op, a_cpu, b_cpu, alpha=alpha)
     except O.OracleError as err:                  # the library must refuse what the oracle refuses, with the same class
@@ -96,7 +112,7 @@ def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what="")
     what = "%s %s,%s %s %s %s [%s]" % (op, a_cpu.dtype, b_cpu.dtype, tuple(want.shape), what, layout, used)
     if op in COMPARE:
         assert_exact(out, want, what)
-    elif op in ("div", "pow", "atan2") and want.dtype.is_floating_point:
+    elif op in ULP_BINARY and want.dtype.is_floating_point:
         if want.dtype == F32:
             assert_ulp(out, want, 2, what)
         else:
@@ -377,6 +393,42 @@ def test_third_batch_binary_full_size():
     assert check_binary("bitwise_xor", ai, bi) == "vec"
 
 
+@pytest.mark.parametrize("op", ["tan", "asinh", "erf", "erfc", "mish", "relu", "hardswish", "signbit"])
+def test_fourth_batch_unary_full_size(op):
+    x = I.typed(FULL, F32, seed=14, specials=0.01)
+    assert check_unary(op, x) == "vec"
+    if op in ("erfc", "mish", "tan"):
+        wide = torch.linspace(-12.0, 12.0, 1 << 20).view(1024, 1024) * (8.0 if op == "mish" else 1.0)
+        check_unary(op, wide, what="wide range")
+    if op == "relu":
+        assert check_unary(op, I.typed(FULL, BF16, seed=15, specials=0.01)) == "vec"
+        assert check_unary(op, I.typed((4096, 4096), I64, seed=16)) == "vec"
+
+
+@pytest.mark.parametrize("op", ["fmod", "remainder", "hypot", "logaddexp", "xlogy", "nextafter", "fmax"])
+def test_fourth_batch_binary_full_size(op):
+    a, b = I.typed(FULL, F32, seed=17, specials=0.01), I.typed(FULL, F32, seed=18, specials=0.01)
+    assert check_binary(op, a, b) == "vec"
+    if op in ("fmod", "remainder"):
+        # quotients up to 2^60: the remainder stays exact
+        big = a[:1024] * 1e15
+        check_binary(op, big, b[:1024], what="large quotients")
+        ai, bi = I.typed((4096, 4096), I32, seed=19), I.typed((4096, 4096), I32, seed=20)
+        assert check_binary(op, ai, bi) == "vec"
+
+
+def test_fourth_batch_integer_ops_full_size():
+    g = torch.Generator().manual_seed(21)
+    for dt, bits in ((I32, 32), (I64, 64)):
+        a = torch.randint(-2 ** (bits - 2), 2 ** (bits - 2), (2048, 4096), generator=g, dtype=I64).to(dt)
+        b = torch.randint(-2 ** (bits - 2), 2 ** (bits - 2), (2048, 4096), generator=g, dtype=I64).to(dt)
+        for op in ("gcd", "lcm"):
+            assert check_binary(op, a, b) == "vec"
+        sh = torch.randint(-4, bits + 4, (2048, 4096), generator=g, dtype=I64).to(dt)
+        for op in ("bitwise_left_shift", "bitwise_right_shift"):
+            assert check_binary(op, a, sh) == "vec"
+
+
 @pytest.mark.parametrize("op", ["log1p", "expm1", "logsigmoid"])
 def test_new_unary_full_size_and_wide_range(op):
     a = I.typed(FULL, F32, seed=176, specials=0.01)
@@ -487,7 +539,7 @@ def check_cast(fn_oracle, fn_lib, want_dtype_class, what):
                    overflow_max=HALF_MAX.get(want.dtype))
 
 
-@pytest.mark.parametrize("op", ["add", "sub", "mul", "div", "maximum", "minimum", "lt", "logical_or", "pow"])
+@pytest.mark.parametrize("op", ["add", "sub", "mul", "div", "maximum", "minimum", "lt", "logical_or", "pow", "fmax", "xlogy", "copysign"])
 def test_binary_out_casting(op):
     pairs = [(F32, F32), (BF16, BF16), (F16, BF16), (I32, I32), (I32, I64), (I64, F32), (BOOL, BOOL), (BOOL, I32)]
     for (da, db), dst, kind in itertools.product(pairs, ALL, ["contig", "transposed"]):
@@ -508,7 +560,7 @@ def test_binary_out_casting(op):
             with pytest.raises(O.OracleError):
                 O.binary(op, a, b, out_dtype=dst)
             continue
-        cls = "exact" if op not in ("div", "pow") or not rd.is_floating_point else "half" if rd != F32 or dst != F32 else "f32"
+        cls = "exact" if op not in ULP_BINARY or not rd.is_floating_point else "half" if rd != F32 or dst != F32 else "f32"
         check_cast(lambda: O.binary(op, a, b, out_dtype=dst), call, cls, "%s %s,%s -> %s %s" % (op, da, db, dst, kind))
 
 
