@@ -1405,6 +1405,59 @@ int orc_bce(const orc_tensor* out, const orc_tensor* x, const orc_tensor* t, con
 }
 
 // ===========================================================================
+// regression losses: mse_loss, l1_loss, smooth_l1_loss, huber_loss (Table 1 "Deep Learning"; the same
+// elementwise-term-then-reduce shape as the binary_cross_entropy listing of Appendix B.1)
+// ===========================================================================
+// With d = x - t on the broadcast of the two shapes:
+//   kind 0 mse       : d^2
+//   kind 1 l1        : |d|
+//   kind 2 smooth_l1 : |d| < beta ? d^2 / (2 beta) : |d| - beta / 2   (param = beta >= 0; beta = 0 is l1)
+//   kind 3 huber     : |d| <= delta ? d^2 / 2 : delta (|d| - delta / 2)   (param = delta > 0)
+// A parameter outside its range is ORC_ERR_SCALAR.  x and t have one floating dtype, which is out's too.
+// reduction: 0 none (out has the broadcast shape), 1 mean, 2 sum (out is 0-dim; the mean of no elements is NaN,
+// the sum 0).  binary64 throughout (the sum is one running binary64 accumulator), one rounding to out's dtype.
+int orc_loss(int kind, const orc_tensor* out, const orc_tensor* x, const orc_tensor* t, int reduction, double param) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x)) || (rc = check_tensor(t))) return rc;
+  if (kind < 0 || kind > 3) return ORC_ERR_SCALAR;
+  if (!is_float(x->dtype) || t->dtype != x->dtype || out->dtype != x->dtype) return ORC_ERR_DTYPE;
+  if (reduction < 0 || reduction > 2) return ORC_ERR_SCALAR;
+  if ((kind == 2 && !(param >= 0.0)) || (kind == 3 && !(param > 0.0))) return ORC_ERR_SCALAR;
+  const orc_tensor* ops[2] = {x, t};
+  int nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(ops, 2, &nd, sizes))) return rc;
+  if (reduction == 0 ? !same_shape(out, nd, sizes) : out->ndim != 0) return ORC_ERR_SHAPE;
+  int64_t n = 1;
+  for (int d = 0; d < nd; ++d) n *= sizes[d];
+  auto loss_at = [&](int64_t lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    const double d = load_flt(x, bcast_offset(x, nd, idx)) - load_flt(t, bcast_offset(t, nd, idx));
+    const double ad = std::fabs(d);
+    switch (kind) {
+      case 0: return d * d;
+      case 1: return ad;
+      case 2: return ad < param ? d * d / (2.0 * param) : ad - param / 2.0;     // NaN fails the comparison and comes out of the second form
+      default: return ad <= param ? d * d / 2.0 : (std::isnan(ad) ? ad : param * (ad - param / 2.0));
+    }
+  };
+  if (reduction == 0) {
+#pragma omp parallel for schedule(static)
+    for (int64_t lin = 0; lin < n; ++lin) {
+      int64_t idx[ORC_MAX_DIMS];
+      unravel(lin, nd, sizes, idx);
+      store_flt(out, offset_of(out, idx), loss_at(lin));
+    }
+    return ORC_OK;
+  }
+  double sum = 0.0;
+  for (int64_t lin = 0; lin < n; ++lin) sum += loss_at(lin);
+  store_flt(out, 0, reduction == 1 ? sum / (double)n : sum);
+  return ORC_OK;
+}
+
+// ===========================================================================
 // cumsum along one dim (inclusive)
 // ===========================================================================
 // bool / int32 / int64 input -> int64 output, exact wrapping sums.  Floating

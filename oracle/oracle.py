@@ -72,6 +72,7 @@ def lib():
         _lib.orc_cumsum.argtypes = [P, P, ctypes.c_int64]
         _lib.orc_layer_norm.argtypes = [P, P, ctypes.c_int32, P, P, ctypes.c_double]
         _lib.orc_bce.argtypes = [P, P, P, P, ctypes.c_int]
+        _lib.orc_loss.argtypes = [ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double]
         _lib.orc_gather.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_index_select.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_scatter_add.argtypes = [P, ctypes.c_int64, P, P]
@@ -239,6 +240,16 @@ def binary_cross_entropy(x, target, weight=None, reduction="mean", out=None):
     if out is None:
         out = torch.empty(x.shape if reduction == "none" else (), dtype=x.dtype)
     _check(lib().orc_bce(desc(out), desc(x), desc(target), _opt(weight), REDUCTION.get(reduction, 9)))
+    return out
+
+
+LOSS = {"mse": 0, "l1": 1, "smooth_l1": 2, "huber": 3}
+
+
+def loss(kind, x, target, reduction="mean", param=1.0, out=None):
+    if out is None:
+        out = torch.empty(torch.broadcast_shapes(x.shape, target.shape) if reduction == "none" else (), dtype=x.dtype)
+    _check(lib().orc_loss(LOSS.get(kind, 9), desc(out), desc(x), desc(target), REDUCTION.get(reduction, 9), ctypes.c_double(param)))
     return out
 
 
