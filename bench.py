@@ -187,6 +187,12 @@ def build_ops(torch, B):
     extra("bce_sum_bf16", "f2", "bce_partial_kernel", n2 * 4, n2,
           lambda: B.tx_binary_cross_entropy(oscalar_b, pxb, ptb, None, "sum", wsb))
     extra("bce_none_f32", "f2", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary_cross_entropy(of, px, pt, None, "none"))
+    wsl = B.workspace(B.tx_loss_workspace_bytes("mse", oscalar, xf, yf, "mean", 1.0))
+    extra("mse_loss_mean_f32", "f2", "bce_partial_kernel", n2 * 8, n2, lambda: B.tx_loss("mse", oscalar, xf, yf, "mean", 1.0, wsl))
+    extra("huber_loss_mean_f32", "f2", "bce_partial_kernel", n2 * 8, n2, lambda: B.tx_loss("huber", oscalar, xf, yf, "mean", 1.0, wsl))
+    extra("smooth_l1_loss_sum_bf16", "f2", "bce_partial_kernel", n2 * 4, n2,
+          lambda: B.tx_loss("smooth_l1", oscalar_b, pxb, ptb, "sum", 0.5, wsl))
+    extra("l1_loss_none_f32", "f2", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_loss("l1", of, xf, yf, "none"))
 
     # softmax / cumsum along a dim that is not the innermost one (column kernels), timed outside the step
     sT, oT = sf.view(4096, 32768), osf.view(4096, 32768)

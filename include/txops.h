@@ -244,6 +244,25 @@ tx_status tx_binary_cross_entropy(const tx_tensor* out, const tx_tensor* input, 
 size_t tx_binary_cross_entropy_workspace_bytes(const tx_tensor* out, const tx_tensor* input, const tx_tensor* target,
                                                const tx_tensor* weight, int reduction);
 
+enum { TX_LOSS_MSE = 0, TX_LOSS_L1 = 1, TX_LOSS_SMOOTH_L1 = 2, TX_LOSS_HUBER = 3 };
+
+/* Regression losses (Table 1 "Deep Learning"; the same term-then-reduce shape as
+ * the binary_cross_entropy listing of Appendix B.1).  With d = input - target on
+ * the broadcast of the two shapes:
+ *   MSE d^2;  L1 |d|;
+ *   SMOOTH_L1 |d| < beta ? d^2 / (2 beta) : |d| - beta / 2  (param = beta >= 0);
+ *   HUBER |d| <= delta ? d^2 / 2 : delta (|d| - delta / 2)  (param = delta > 0);
+ * a parameter outside its range, an unknown kind or reduction is TX_ERR_SCALAR.
+ * input, target and out have one floating dtype.  reduction NONE: out has the
+ * broadcast shape and may alias an operand exactly.  MEAN / SUM: out is 0-dim;
+ * terms are formed in fp32 and added in fp32 per thread, binary64 across threads
+ * and workgroups; the mean of no elements is NaN, the sum 0.  They need a 16-byte
+ * aligned device workspace of tx_loss_workspace_bytes() bytes (0 for NONE). */
+tx_status tx_loss(int kind, const tx_tensor* out, const tx_tensor* input, const tx_tensor* target, int reduction, double param,
+                  void* workspace, size_t workspace_bytes, void* stream);
+size_t tx_loss_workspace_bytes(int kind, const tx_tensor* out, const tx_tensor* input, const tx_tensor* target, int reduction,
+                               double param);
+
 /* ------------------------------------------------------------------ reductions
  * (Table 1 "Reduction"; the row mean / variance kernels of the layer_norm
  * listing in Appendix B are the paper's form of the inner-dim case.)
@@ -430,7 +449,8 @@ const char* tx_last_path(void);
  * instead of the column kernels).  layer_norm: "layer-norm-block" (one
  * workgroup per row), "layer-norm-generic" (three passes, any strides).
  * binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
- * first; the workspace query then reports that form's size).  Requests that a path cannot
+ * first; the workspace query then reports that form's size); tx_loss:
+ * "loss-two-pass" likewise.  Requests that a path cannot
  * serve fall back to the automatic choice.  Process-wide; meant for A/B
  * profiling. */
 void tx_force_path(const char* name);

@@ -37,7 +37,7 @@ STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so")
 
 EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
-           "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
+           "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
            "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_masked_select",
            "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
@@ -89,6 +89,8 @@ def lib():
         "tx_layer_norm": ([P, P, ctypes.c_int32, P, P, ctypes.c_double, V], ctypes.c_int32),
         "tx_binary_cross_entropy": ([P, P, P, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_binary_cross_entropy_workspace_bytes": ([P, P, P, P, ctypes.c_int], ctypes.c_size_t),
+        "tx_loss": ([ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_loss_workspace_bytes": ([ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double], ctypes.c_size_t),
         "tx_cumsum": ([P, P, ctypes.c_int64, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_cumsum_workspace_bytes": ([P, P, ctypes.c_int64], ctypes.c_size_t),
         "tx_gather": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
@@ -289,6 +291,20 @@ def tx_binary_cross_entropy(out, input, target, weight=None, reduction="mean", w
     p, n = _ws(ws)
     _check(lib().tx_binary_cross_entropy(desc(out), desc(input), desc(target), _opt(weight), REDUCTION.get(reduction, 9),
                                          p, n, _stream(stream)))
+
+
+LOSS = {"mse": 0, "l1": 1, "smooth_l1": 2, "huber": 3}
+
+
+def tx_loss_workspace_bytes(kind, out, input, target, reduction="mean", param=1.0):
+    return lib().tx_loss_workspace_bytes(LOSS.get(kind, 9), desc(out), desc(input), desc(target), REDUCTION.get(reduction, 9),
+                                         float(param))
+
+
+def tx_loss(kind, out, input, target, reduction="mean", param=1.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(lib().tx_loss(LOSS.get(kind, 9), desc(out), desc(input), desc(target), REDUCTION.get(reduction, 9), float(param),
+                         p, n, _stream(stream)))
 
 
 def tx_where(out, cond, x, y, stream=None):

@@ -11,7 +11,8 @@ int bce_fused_mode(const tx_tensor* x, const tx_tensor* t, const tx_tensor* w);
 // number of binary64 partials the fused kernel writes for n elements of esize bytes
 size_t bce_partial_count(int64_t n, int esize);
 // sum (mean != 0: mean) of the losses into the 0-dim `out`.  mode 3: `x` holds n precomputed losses, contiguous
+// kind 0: binary_cross_entropy terms; 1 mse, 2 l1, 3 smooth_l1 (param = beta), 4 huber (param = delta): no weight
 tx_status bce_reduce(const tx_tensor* out, int dtype, const void* x, const void* t, const tx_tensor* w, int mode, int64_t n,
-                     int64_t last, int mean, double* partial, hipStream_t stream);
+                     int64_t last, int mean, double* partial, hipStream_t stream, int kind = 0, double param = 1.0);
 
 }  // namespace tx

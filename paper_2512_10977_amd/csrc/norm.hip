@@ -269,10 +269,23 @@ struct BceArgs {
   int w_mode;               // 0 none, 1 same layout, 2 last-dim vector, 3: x already holds the losses
   int w_f32;
   FastDiv last;             // mode 2: extent of the last dim
+  float param, half_param, half_over_param;   // KIND 3 / 4: beta or delta, half of it, 0.5 / it
 };
 
+// one term of the loss family.  KIND 0: binary_cross_entropy; 1: (x - t)^2; 2: |x - t|;
+// 3: smooth_l1, |d| < beta ? d^2 / (2 beta) : |d| - beta / 2; 4: huber, |d| <= delta ? d^2 / 2 : delta (|d| - delta / 2).
+// A NaN difference fails the comparison and comes out of the second form.
+template <int KIND> __device__ __forceinline__ float loss_term(float x, float t, const BceArgs& a) {
+  if constexpr (KIND == 0) return bce_term_fast(x, t);
+  const float d = x - t, ad = __builtin_fabsf(d);
+  if constexpr (KIND == 1) return d * d;
+  if constexpr (KIND == 2) return ad;
+  if constexpr (KIND == 3) return ad < a.param ? d * d * a.half_over_param : ad - a.half_param;
+  return ad <= a.param ? 0.5f * d * d : a.param * (ad - a.half_param);
+}
+
 // MODE: the weight mode as a compile-time constant, or -1 = read a.w_mode at run time (the scalar kernel)
-template <class T, int VEC, int MODE>
+template <class T, int VEC, int MODE, int KIND = 0>
 __global__ __launch_bounds__(kBlock) void bce_partial_kernel(const BceArgs a) {
   __shared__ double lds[kBlock / kWave];
   const int mode = MODE < 0 ? a.w_mode : MODE;
@@ -309,7 +322,7 @@ __global__ __launch_bounds__(kBlock) void bce_partial_kernel(const BceArgs a) {
         }
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-          float l = mode == 3 ? cvt<float>(xv[u].v[e]) : bce_term_fast(cvt<float>(xv[u].v[e]), cvt<float>(tv[u].v[e]));
+          float l = mode == 3 ? cvt<float>(xv[u].v[e]) : loss_term<KIND>(cvt<float>(xv[u].v[e]), cvt<float>(tv[u].v[e]), a);
           if (mode == 1 || mode == 2) l *= wv[e];
           acc += l;
         }
@@ -389,7 +402,7 @@ size_t bce_partial_count(int64_t n, int esize) {
 // sum / mean of the losses.  mode 3: `x` holds precomputed losses (contiguous, n elements)
 template <class T>
 tx_status bce_reduce_typed(const tx_tensor* out, const void* x, const void* t, const tx_tensor* w, int mode, int64_t n,
-                           int64_t last, int mean, double* partial, hipStream_t stream) {
+                           int64_t last, int mean, double* partial, hipStream_t stream, int kind, double param) {
   constexpr int V = 16 / sizeof(T);
   size_t blocks = 0;
   if (n > 0) {
@@ -403,10 +416,28 @@ tx_status bce_reduce_typed(const tx_tensor* out, const void* x, const void* t, c
     a.w_mode = mode;
     a.w_f32 = w && w->dtype == TX_F32 && sizeof(T) == 2;
     a.last = FastDiv((uint32_t)std::max<int64_t>(1, std::min<int64_t>(last, 0x7fffffff)));
+    a.param = (float)param;
+    a.half_param = (float)(0.5 * param);
+    a.half_over_param = (float)(0.5 / param);          // beta = 0: infinite and never selected
     blocks = bce_partial_count(n, sizeof(T));
     bool al = (uintptr_t)x % 16 == 0 && (mode == 3 || (uintptr_t)t % 16 == 0) && n % V == 0;
     if (mode == 1 || mode == 2) al = al && (uintptr_t)w->data % 16 == 0 && (mode == 1 || last % V == 0);
-    if (al) {
+    if (kind != 0 && mode != 3) {                      // the regression losses: no weight
+      const dim3 grid((unsigned)(al ? blocks : std::min<int64_t>((n + kBlock * kBceUnroll - 1) / (kBlock * kBceUnroll), kBceMaxBlocks)));
+      if (!al) blocks = grid.x;
+      set_path(al ? "loss-fused" : "loss-fused-scalar");
+      auto go = [&](auto k) {
+        constexpr int K = decltype(k)::value;
+        if (al) hipLaunchKernelGGL((bce_partial_kernel<T, V, 0, K>), grid, dim3(kBlock), 0, stream, a);
+        else hipLaunchKernelGGL((bce_partial_kernel<T, 1, -1, K>), grid, dim3(kBlock), 0, stream, a);
+      };
+      switch (kind) {
+        case 1: go(std::integral_constant<int, 1>{}); break;
+        case 2: go(std::integral_constant<int, 2>{}); break;
+        case 3: go(std::integral_constant<int, 3>{}); break;
+        default: go(std::integral_constant<int, 4>{}); break;
+      }
+    } else if (al) {
       const dim3 grid((unsigned)blocks);
       set_path("bce-fused");
       switch (mode) {
@@ -430,11 +461,11 @@ tx_status bce_reduce_typed(const tx_tensor* out, const void* x, const void* t, c
 }
 
 tx_status bce_reduce(const tx_tensor* out, int dtype, const void* x, const void* t, const tx_tensor* w, int mode, int64_t n,
-                     int64_t last, int mean, double* partial, hipStream_t stream) {
+                     int64_t last, int mean, double* partial, hipStream_t stream, int kind, double param) {
   switch (dtype) {
-    case TX_F32: return bce_reduce_typed<float>(out, x, t, w, mode, n, last, mean, partial, stream);
-    case TX_BF16: return bce_reduce_typed<bf16>(out, x, t, w, mode, n, last, mean, partial, stream);
-    default: return bce_reduce_typed<f16>(out, x, t, w, mode, n, last, mean, partial, stream);
+    case TX_F32: return bce_reduce_typed<float>(out, x, t, w, mode, n, last, mean, partial, stream, kind, param);
+    case TX_BF16: return bce_reduce_typed<bf16>(out, x, t, w, mode, n, last, mean, partial, stream, kind, param);
+    default: return bce_reduce_typed<f16>(out, x, t, w, mode, n, last, mean, partial, stream, kind, param);
   }
 }
 

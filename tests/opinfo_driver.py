@@ -121,6 +121,9 @@ class OracleBackend:
     def bce(self, x, t, w, reduction):
         return self.O.binary_cross_entropy(x, t, w, reduction)
 
+    def loss(self, kind, x, t, reduction, param):
+        return self.O.loss(kind, x, t, reduction, param)
+
 
 class LibraryBackend:
     """The HIP library: operands copied to the GPU with their strides, outputs allocated from the library's own
@@ -259,6 +262,13 @@ class LibraryBackend:
         out = self._out(x.shape if reduction == "none" else (), x.dtype)
         ws = self._ws(self.B.tx_binary_cross_entropy_workspace_bytes(out, dx, dt_, dw, reduction))
         self.B.tx_binary_cross_entropy(out, dx, dt_, dw, reduction, ws)
+        return out.cpu()
+
+    def loss(self, kind, x, t, reduction, param):
+        dx, dt_ = self.dev(x), self.dev(t)
+        out = self._out(torch.broadcast_shapes(x.shape, t.shape) if reduction == "none" else (), x.dtype)
+        ws = self._ws(self.B.tx_loss_workspace_bytes(kind, out, dx, dt_, reduction, param))
+        self.B.tx_loss(kind, out, dx, dt_, reduction, param, ws)
         return out.cpu()
 
 
@@ -470,6 +480,18 @@ def bce(be, s):
     return be.bce(_tensor_ok(s.input), _tensor_ok(s.args[0]), None if w is None else _tensor_ok(w), s.kwargs.get("reduction", "mean"))
 
 
+def regression_loss(kind, param_name=None):
+    def run(be, s):
+        _no_kwargs(s, ("reduction",) + ((param_name,) if param_name else ()))
+        if len(s.args) != 1:
+            raise Unsupported("arguments")
+        x, t = _tensor_ok(s.input), _tensor_ok(s.args[0])
+        if x.dtype != t.dtype:
+            raise Unsupported("input and target of different dtypes")
+        return be.loss(kind, x, t, s.kwargs.get("reduction", "mean"), float(s.kwargs.get(param_name, 1.0)) if param_name else 1.0)
+    return run
+
+
 # OpInfo name -> (variant names to take, adapter)
 ADAPTERS = {
     "neg": unary("neg"), "abs": unary("abs"), "exp": unary("exp"), "log": unary("log"), "sqrt": unary("sqrt"),
@@ -504,6 +526,8 @@ ADAPTERS = {
     "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
     "masked_select": masked_select, "nonzero": nonzero, "scatter_reduce": scatter_reduce, "index_put": index_put,
     "nn.functional.layer_norm": layer_norm, "nn.functional.binary_cross_entropy": bce,
+    "nn.functional.mse_loss": regression_loss("mse"), "nn.functional.l1_loss": regression_loss("l1"),
+    "nn.functional.smooth_l1_loss": regression_loss("smooth_l1", "beta"), "nn.functional.huber_loss": regression_loss("huber", "delta"),
 }
 
 

@@ -221,3 +221,85 @@ def test_bce_full_size(dt, red):
     w = torch.rand(8192, generator=torch.Generator().manual_seed(351)).to(dt)
     assert check_bce(x, t, None, red) == ("vec" if red == "none" else "bce-fused")
     assert check_bce(x, t, w, red, what="last-dim weight") == ("vec" if red == "none" else "bce-fused")
+
+
+# --------------------------------------------------------------------------- regression losses
+LOSSES = [("mse", 1.0), ("l1", 1.0), ("smooth_l1", 0.75), ("smooth_l1", 0.0), ("huber", 1.5)]
+
+
+def check_loss(kind, param, x_cpu, t_cpu, reduction="mean", path=None, what=""):
+    want = O.loss(kind, x_cpu, t_cpu, reduction, param)
+    x, t = to_device_view(x_cpu), to_device_view(t_cpu)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_force_path(path)
+    try:
+        ws = B.workspace(B.tx_loss_workspace_bytes(kind, out, x, t, reduction, param))
+        B.tx_loss(kind, out, x, t, reduction, param, ws)
+        used = B.tx_last_path()
+    finally:
+        B.tx_force_path(None)
+    torch.cuda.synchronize()
+    assert_rel(out, want, rel_of(x_cpu.dtype), scale=FLT_TINY, overflow_max=HALF_MAX.get(x_cpu.dtype),
+               what="%s(%g) %s %s %s %s [%s]" % (kind, param, x_cpu.dtype, tuple(x_cpu.shape), reduction, what, used))
+    return used
+
+
+@pytest.mark.parametrize("dt", [F32, BF16, F16])
+def test_loss_sweep(dt):
+    for (kind, p), shape, red in itertools.product(LOSSES, [(64, 48), (7, 13, 5), (1,), (), (33, 1000), (5, 4099)], ["none", "mean", "sum"]):
+        x, t = I.typed(shape, dt, seed=360, std=2.0), I.typed(shape, dt, seed=361, std=2.0)
+        used = check_loss(kind, p, x, t, red)
+        if red != "none":
+            assert used.startswith("loss-fused"), used
+            check_loss(kind, p, x, t, red, path="loss-two-pass", what="forced two-pass")
+    x, t = I.typed((64, 48), dt, seed=362, std=2.0), I.typed((64, 48), dt, seed=363, std=2.0)
+    for (kind, p), red in itertools.product(LOSSES, ["none", "mean", "sum"]):
+        used = check_loss(kind, p, x.t(), t.t(), red, what="both transposed")
+        assert red == "none" or used.startswith("loss-fused")
+        used = check_loss(kind, p, x.t(), t.t().contiguous(), red, what="one transposed")
+        assert red == "none" or used == "loss-two-pass"
+        check_loss(kind, p, x[:, ::2], t[:, ::2], red, what="step-2")
+        used = check_loss(kind, p, x, t[0], red, what="broadcast target")
+        assert red == "none" or used == "loss-two-pass"
+        check_loss(kind, p, x[:, :1], t[:1], red, what="both broadcast")
+        check_loss(kind, p, x, t[0, 0], red, what="0-dim target")
+
+
+def test_loss_special_values_empty_and_errors():
+    x = torch.tensor([float("nan"), float("inf"), 1.0, float("inf"), -float("inf"), 2.0, 2.0], dtype=F32)
+    t = torch.tensor([0.0, 0.0, float("nan"), float("inf"), float("inf"), 0.5, 2.0], dtype=F32)
+    for (kind, p), red in itertools.product(LOSSES, ["none", "mean", "sum"]):
+        check_loss(kind, p, x, t, red)
+        check_loss(kind, p, x[5:], t[5:], red, what="edge of the two branches")
+        e0 = torch.empty((0, 3), dtype=F32)
+        check_loss(kind, p, e0, e0, red)
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    ws = B.workspace(1 << 16)
+    for args, kind in [(("mse", d(3, dt=torch.int64), d(3, dt=torch.int64), d(3, dt=torch.int64), "none"), "DTYPE"),
+                       (("mse", d(3), d(3), d(3, dt=BF16), "none"), "DTYPE"), (("l1", d(3), d(3), d(4), "none"), "SHAPE"),
+                       (("l1", d(3), d(3), d(3), "mean"), "SHAPE"), (("mse", d(), d(3), d(3), "median"), "SCALAR"),
+                       (("hinge", d(), d(3), d(3), "mean"), "SCALAR")]:
+        with pytest.raises(B.TxError) as e:
+            B.tx_loss(args[0], args[1], args[2], args[3], args[4], 1.0, ws)
+        assert e.value.kind == kind, args
+    for kind, bad in (("smooth_l1", -0.5), ("huber", 0.0), ("huber", float("nan"))):
+        with pytest.raises(B.TxError) as e:
+            B.tx_loss(kind, d(), d(3), d(3), "mean", bad, ws)
+        assert e.value.kind == "SCALAR"
+    with pytest.raises(B.TxError) as e:
+        B.tx_loss("mse", d(), d(3, 4), d(3, 4), "mean", 1.0, None)
+    assert e.value.kind == "WORKSPACE"
+    # in place over the input
+    xi = I.typed((40, 30), F32, seed=364)
+    ti = I.typed((40, 30), F32, seed=365)
+    want = O.loss("huber", xi, ti, "none", 1.0)
+    dx = xi.cuda()
+    B.tx_loss("huber", dx, dx, ti.cuda(), "none", 1.0)
+    assert_rel(dx, want, 1e-5, scale=FLT_TINY, what="huber in place")
+
+
+@pytest.mark.parametrize("kind,p,dt,red", [("mse", 1.0, F32, "mean"), ("huber", 1.0, F32, "sum"), ("smooth_l1", 0.5, BF16, "mean"),
+                                           ("l1", 1.0, F32, "none"), ("mse", 1.0, BF16, "none")])
+def test_loss_full_size(kind, p, dt, red):
+    x, t = I.typed((8192, 8192), dt, seed=370, std=2.0), I.typed((8192, 8192), dt, seed=371, std=2.0)
+    assert check_loss(kind, p, x, t, red) == ("vec" if red == "none" else "loss-fused")
