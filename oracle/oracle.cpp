@@ -80,7 +80,7 @@ enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM,
        ORC_ATAN2, ORC_FMOD, ORC_REMAINDER, ORC_HYPOT, ORC_COPYSIGN, ORC_LOGADDEXP, ORC_LOGADDEXP2, ORC_XLOGY, ORC_HEAVISIDE,
        ORC_FMAX, ORC_FMIN, ORC_NEXTAFTER, ORC_GCD, ORC_LCM, ORC_SHIFT_LEFT, ORC_SHIFT_RIGHT };
 enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
-       ORC_LOGSUMEXP };
+       ORC_LOGSUMEXP, ORC_NANSUM, ORC_NANMEAN, ORC_COUNT_NONZERO, ORC_NORM };
 
 }  // extern "C"
 
@@ -1041,6 +1041,9 @@ int orc_reduce_result_dtype(int op, int in_dtype) {
     case ORC_AMAX: case ORC_AMIN: return in_dtype;
     case ORC_ARGMAX: case ORC_ARGMIN: return in_dtype == ORC_BOOL ? (int)ORC_ERR_DTYPE : (int)ORC_I64;
     case ORC_ANY: case ORC_ALL: return ORC_BOOL;
+    case ORC_NANSUM: return is_float(in_dtype) ? in_dtype : ORC_I64;
+    case ORC_NANMEAN: case ORC_NORM: return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_COUNT_NONZERO: return ORC_I64;
   }
   return ORC_ERR_DTYPE;
 }
@@ -1085,6 +1088,17 @@ int orc_infer_reduce(int op, const orc_tensor* x, const int64_t* dims, int32_t n
 //           any input dtype, bool result; empty extent: any = false, all = true.
 //   logsumexp : max + log(sum exp(x - max)) in binary64; an infinite maximum is
 //           the result (-inf for an empty or all -inf slice), NaN is sticky.
+//   nansum / nanmean : sum and mean of the elements that are not NaN (the mean
+//           divides by their count: NaN when there is none); nansum of an
+//           integer tensor is its sum; nanmean takes floats only.
+//   count_nonzero : the number of elements that are not zero (a NaN is not
+//           zero, -0.0 is); any dtype, int64 result.
+//   norm  : the vector p-norm with p = `correction`; floats only.  p = 0: the
+//           count of non-zero elements; p = +inf / -inf: the largest / smallest
+//           |x| (NaN if any NaN; empty extent: error); otherwise
+//           (sum |x|^p)^(1/p) in binary64 - p = 1 and p = 2 written as |x| and
+//           x*x with a square root - so nothing overflows that the result does
+//           not; a negative p over an empty extent is an error as well.
 // A floating `out` dtype wider than x's (fp32 out for a half x) is allowed for
 // sum / mean / prod / var: the single rounding then goes to that dtype.
 int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
@@ -1113,6 +1127,9 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
   if (nout == 0) return ORC_OK;
   if ((op == ORC_AMAX || op == ORC_ARGMAX || op == ORC_AMIN || op == ORC_ARGMIN) && nred == 0)
     return ORC_ERR_EMPTY_REDUCTION;
+  const double ord = correction;                       // norm: the exponent p
+  if (op == ORC_NORM && std::isnan(ord)) return ORC_ERR_SCALAR;
+  if (op == ORC_NORM && nred == 0 && (std::isinf(ord) || ord < 0.0)) return ORC_ERR_EMPTY_REDUCTION;
   const bool flt = is_float(x->dtype);
   const bool single_dim = (nr == 1);
 
@@ -1140,6 +1157,8 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
     bool any_true = false, all_true = true;            // any / all: an element counts as true when it is not zero (NaN is)
     double lse_max = -std::numeric_limits<double>::infinity();
     bool lse_nan = false;
+    int64_t count = 0;                                 // nanmean: elements that are not NaN; count_nonzero, norm 0: not zero
+    bool norm_nan = false;
     if (op == ORC_LOGSUMEXP) {                         // first pass: the maximum (NaN is sticky)
       for (int64_t r = 0; r < nred; ++r) {
         unravel(r, nr, rsz, ridx);
@@ -1173,6 +1192,29 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
         case ORC_VAR: case ORC_STD: {
           double dlt = load_flt(x, xo) - mean;
           accd += dlt * dlt;
+          break;
+        }
+        case ORC_NANSUM: case ORC_NANMEAN:
+          if (flt) {
+            const double v = load_flt(x, xo);
+            if (!std::isnan(v)) { accd += v; ++count; }
+          } else {
+            acci += (uint64_t)load_int(x, xo);
+          }
+          break;
+        case ORC_COUNT_NONZERO:
+          count += flt ? (load_flt(x, xo) != 0.0) : (load_int(x, xo) != 0);
+          break;
+        case ORC_NORM: {
+          const double v = std::fabs(load_flt(x, xo));
+          if (ord == 0.0) count += (v != 0.0);                           // NaN != 0 is true
+          else if (std::isinf(ord)) {
+            if (std::isnan(v)) norm_nan = true;
+            else if (!have || (ord > 0.0 ? v > bestd : v < bestd)) { bestd = v; have = true; }
+          }
+          else if (ord == 1.0) accd += v;
+          else if (ord == 2.0) accd += v * v;
+          else accd += std::pow(v, ord);
           break;
         }
         case ORC_ANY: case ORC_ALL: {
@@ -1225,6 +1267,18 @@ int orc_reduce(int op, const orc_tensor* out, const orc_tensor* x, const int64_t
         store_flt(out, oo, nred ? std::sqrt(accd / div) : kNaN);
         break;
       }
+      case ORC_NANSUM:
+        if (flt) store_flt(out, oo, accd); else store_int(out, oo, (int64_t)acci);
+        break;
+      case ORC_NANMEAN: store_flt(out, oo, count ? accd / (double)count : kNaN); break;
+      case ORC_COUNT_NONZERO: store_int(out, oo, count); break;
+      case ORC_NORM:
+        if (ord == 0.0) store_flt(out, oo, (double)count);
+        else if (std::isinf(ord)) store_flt(out, oo, norm_nan ? kNaN : bestd);
+        else if (ord == 1.0) store_flt(out, oo, accd);
+        else if (ord == 2.0) store_flt(out, oo, std::sqrt(accd));
+        else store_flt(out, oo, std::pow(accd, 1.0 / ord));
+        break;
       case ORC_ANY: store_int(out, oo, any_true); break;
       case ORC_ALL: store_int(out, oo, all_true); break;
       case ORC_LOGSUMEXP:

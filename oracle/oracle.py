@@ -29,7 +29,7 @@ BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimu
           "logaddexp2": 25, "xlogy": 26, "heaviside": 27, "fmax": 28, "fmin": 29, "nextafter": 30, "gcd": 31, "lcm": 32,
           "bitwise_left_shift": 33, "bitwise_right_shift": 34}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
-          "all": 10, "logsumexp": 11}
+          "all": 10, "logsumexp": 11, "nansum": 12, "nanmean": 13, "count_nonzero": 14, "norm": 15}
 
 ERRORS = {-1: "null", -2: "ndim", -3: "dtype", -4: "shape", -5: "dim", -7: "empty_reduction",
           -8: "scalar", -10: "index"}
