@@ -122,11 +122,11 @@ def build_ops(torch, B):
     rb = rf.to(BF16)
     ri = randint(R, -(2 ** 20), 2 ** 20)
 
-    def reducer(op, x, dims, out_shape, out_dtype):
+    def reducer(op, x, dims, out_shape, out_dtype, param=1.0):
         out = torch.empty(out_shape, device=dev, dtype=out_dtype)
         nb = B.tx_reduce_workspace_bytes(op, out, x, dims)
         ws = B.workspace(nb) if nb else None
-        return lambda: B.tx_reduce(op, out, x, dims, False, 1.0, ws)
+        return lambda: B.tx_reduce(op, out, x, dims, False, param, ws)
 
     add("sum_f32_dim-1", "a6", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("sum", rf, -1, (64, 4096), F32))
     add("argmax_f32_dim-1", "a6", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 8, nr, reducer("argmax", rf, -1, (64, 4096), I64))
@@ -148,6 +148,14 @@ def build_ops(torch, B):
           reducer("logsumexp", rb, 0, (4096, 1024), BF16))
     extra("all_i64_all_dims", "f1", "reduce_rows_kernel", nr * 8 + 1, nr, reducer("all", ri, None, (), torch.bool))
     extra("any_f32_dims(0,2)", "f1", "reduce_rows_kernel", nr * 4 + 4096, nr, reducer("any", rf, (0, 2), (4096,), torch.bool))
+    extra("nanmean_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("nanmean", rf, -1, (64, 4096), F32))
+    extra("nansum_bf16_dim0", "f1", "reduce_cols_kernel", nr * 2 + 4096 * 1024 * 2, nr, reducer("nansum", rb, 0, (4096, 1024), BF16))
+    extra("count_nonzero_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 8, nr,
+          reducer("count_nonzero", rf, -1, (64, 4096), I64))
+    extra("norm2_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("norm", rf, -1, (64, 4096), F32, 2.0))
+    extra("norm2_f32_dim0", "f1", "reduce_cols_kernel", nr * 4 + 4096 * 1024 * 4, nr, reducer("norm", rf, 0, (4096, 1024), F32, 2.0))
+    extra("norm_inf_bf16_all", "f1", "reduce_rows_kernel", nr * 2 + 2, nr, reducer("norm", rb, None, (), BF16, float("inf")))
+    extra("norm3_f32_dim-1", "f1", "reduce_rows_kernel", nr * 4 + 64 * 4096 * 4, nr, reducer("norm", rf, -1, (64, 4096), F32, 3.0))
 
     # ---- workload 4: softmax [32768,4096], cumsum [4096,65536]
     S = (32768, 4096)

@@ -97,7 +97,7 @@ enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE,
        TX_FMOD, TX_REMAINDER, TX_HYPOT, TX_COPYSIGN, TX_LOGADDEXP, TX_LOGADDEXP2, TX_XLOGY, TX_HEAVISIDE, TX_FMAX,
        TX_FMIN, TX_NEXTAFTER, TX_GCD, TX_LCM, TX_SHIFT_LEFT, TX_SHIFT_RIGHT };
 enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARGMIN, TX_STD, TX_ANY, TX_ALL,
-       TX_LOGSUMEXP };
+       TX_LOGSUMEXP, TX_NANSUM, TX_NANMEAN, TX_COUNT_NONZERO, TX_NORM };
 
 /* ------------------------------------------------------------------ elementwise
  * (Table 1 "Elementwise"; the flat masked kernels of Appendix B are the paper's
@@ -286,8 +286,18 @@ size_t tx_loss_workspace_bytes(int kind, const tx_tensor* out, const tx_tensor* 
  *   LOGSUMEXP  bool / integer input is converted to fp32 (fp32 result); log of the sum of exp(x), computed as a running
  *         (maximum, scaled sum) pair; -inf for an empty or all -inf extent,
  *         +inf if +inf is present, NaN is sticky.
- * For SUM / MEAN / PROD / VAR / STD / LOGSUMEXP on fp16 / bf16 input, out may
- * be fp32.
+ *   NANSUM / NANMEAN  the sum / mean of the elements that are not NaN (the mean
+ *         divides by their count: NaN when there is none); NANSUM of a bool /
+ *         integer x is SUM; NANMEAN takes floats only.
+ *   COUNT_NONZERO  any dtype, int64 result; a NaN is not zero, -0.0 is.
+ *   NORM  the vector p-norm, p passed in `correction`; floats only.  p = 0: the
+ *         count of non-zero elements; p = +inf / -inf: the largest / smallest
+ *         |x|, NaN if any NaN (an empty extent is TX_ERR_EMPTY_REDUCTION, as it
+ *         is for a negative p); p = 2 accumulates squares in binary64, so only
+ *         a result beyond the dtype's range overflows; any other p is
+ *         (sum |x|^p)^(1/p) in binary64.  A NaN p is TX_ERR_SCALAR.
+ * For SUM / MEAN / PROD / VAR / STD / LOGSUMEXP / NANSUM / NANMEAN / NORM on
+ * fp16 / bf16 input, out may be fp32.
  * ws / ws_bytes: device scratch of at least tx_reduce_workspace_bytes() for the
  * same arguments (0 when the reduction is not split across workgroups; the
  * data pointers of out / x are not dereferenced by the query). */

@@ -29,7 +29,7 @@ BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimu
           "logaddexp2": 25, "xlogy": 26, "heaviside": 27, "fmax": 28, "fmin": 29, "nextafter": 30, "gcd": 31, "lcm": 32,
           "bitwise_left_shift": 33, "bitwise_right_shift": 34}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
-          "all": 10, "logsumexp": 11}
+          "all": 10, "logsumexp": 11, "nansum": 12, "nanmean": 13, "count_nonzero": 14, "norm": 15}
 
 STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", -6: "OVERLAP",
           -7: "EMPTY_REDUCTION", -8: "SCALAR", -9: "WORKSPACE", -10: "INDEX", -11: "LAUNCH", -12: "UNSUPPORTED"}

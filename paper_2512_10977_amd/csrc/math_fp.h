@@ -84,6 +84,18 @@ __device__ __forceinline__ double log1p_unit_d(double t) {
   return 2.0 * z * p;
 }
 
+// v^p for v >= 0 that came from an fp32 value (so it is zero, a normal binary64 number, +inf or NaN) and p != 0
+__device__ __forceinline__ double pow_abs_d(double v, double p) {
+  if (v != v) return v;
+  const double inf = __builtin_inf();
+  if (v == 0.0) return p > 0.0 ? 0.0 : inf;
+  if (v == inf) return p > 0.0 ? inf : 0.0;
+  const double y = p * log_d(v);
+  if (y > 709.0) return inf;
+  if (y < -708.0) return 0.0;                          // below 1e-307: nothing an fp32 result can see
+  return exp_d(y);
+}
+
 // log(e^a + e^b) (base2: log2(2^a + 2^b)) = max + log1p(exp(-|a - b|)); fp32 operands, binary64 evaluation
 __device__ __forceinline__ float logaddexp_f32(float a, float b, bool base2) {
   if (a != a || b != b) return __uint_as_float(0x7fc00000u);

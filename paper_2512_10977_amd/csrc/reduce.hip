@@ -138,6 +138,9 @@ size_t acc_size(int op, int dtype) {
     case TX_AMIN: return flt ? 4 : 8;
     case TX_ANY: case TX_ALL: return 8;
     case TX_LOGSUMEXP: return 8;
+    case TX_NANSUM: return flt ? 16 : 8;
+    case TX_NANMEAN: return 16;
+    case TX_COUNT_NONZERO: case TX_NORM: return 8;
   }
   return 16;
 }
@@ -214,6 +217,12 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
       rd = TX_I64;
       break;
     case TX_ANY: case TX_ALL: rd = TX_BOOL; break;
+    case TX_NANSUM: rd = flt ? x->dtype : TX_I64; break;
+    case TX_NANMEAN: case TX_NORM:
+      if (!flt) return fail(TX_ERR_DTYPE, "nanmean / norm take floating dtypes only");
+      rd = x->dtype;
+      break;
+    case TX_COUNT_NONZERO: rd = TX_I64; break;
     default: return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
   }
   if ((op == TX_PROD || op == TX_ARGMAX || op == TX_ARGMIN) && ndims > 1 && dims)
@@ -259,8 +268,17 @@ tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int6
   if (p.nout == 0) return TX_OK;
   if ((op == TX_AMAX || op == TX_ARGMAX || op == TX_AMIN || op == TX_ARGMIN) && p.nred == 0)
     return fail(TX_ERR_EMPTY_REDUCTION, "amax / amin / argmax / argmin over an empty extent");
+  if (op == TX_NORM) {                                   // correction carries the exponent p
+    if (correction != correction) return fail(TX_ERR_SCALAR, "norm: the exponent is NaN");
+    if (p.nred == 0 && (correction < 0.0 || correction == __builtin_inf()))
+      return fail(TX_ERR_EMPTY_REDUCTION, "norm with an infinite or negative exponent over an empty extent");
+  }
   hipStream_t s = as_stream(stream);
   switch (op) {
+    case TX_NANSUM: return launch_nansum(false, p, x, out, correction, ws, ws_bytes, s);
+    case TX_NANMEAN: return launch_nansum(true, p, x, out, correction, ws, ws_bytes, s);
+    case TX_COUNT_NONZERO: return launch_count(p, x, out, correction, ws, ws_bytes, s);
+    case TX_NORM: return launch_norm(p, x, out, correction, ws, ws_bytes, s);
     case TX_SUM: return launch_sum(false, p, x, out, correction, ws, ws_bytes, s);
     case TX_MEAN: return launch_sum(true, p, x, out, correction, ws, ws_bytes, s);
     case TX_VAR: return launch_var(p, x, out, correction, ws, ws_bytes, s);

@@ -21,6 +21,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "math_fp.h"
 
 namespace tx {
 namespace red {
@@ -253,6 +254,77 @@ template <class T> struct VarPolicy {
   }
 };
 
+// nansum (MEAN = false) / nanmean: the elements that are not NaN, and how many they are
+struct NanAcc { float s; int64_t n; };
+template <class T, bool MEAN> struct NanSumPolicy {
+  using In = T;
+  static constexpr bool flt = true;
+  using Acc = NanAcc;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() { return Acc{0.0f, 0}; }
+  __device__ static void step(Acc& a, T x, int64_t, double) {
+    const float v = cvt<float>(x);
+    const bool ok = v == v;
+    a.s += ok ? v : 0.0f;
+    a.n += ok;
+  }
+  __device__ static void merge(Acc& a, const Acc& b) { a.s += b.s; a.n += b.n; }
+  __device__ static Acc shfl(const Acc& a, int m) { return Acc{shfl_xor(a.s, m), shfl_xor(a.n, m)}; }
+  __device__ static void finish(const Acc& a, int64_t, double, double, double* f, int64_t*) {
+    *f = MEAN ? (double)a.s / (double)a.n : (double)a.s;          // 0 / 0 = NaN: nothing but NaNs, or nothing at all
+  }
+};
+
+// count_nonzero: a NaN is not zero, -0.0 is
+template <class T> struct CountPolicy {
+  using In = T;
+  static constexpr bool flt = false;                 // int64 out
+  using Acc = int64_t;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() { return 0; }
+  __device__ static void step(Acc& a, T x, int64_t, double) {
+    if constexpr (IsFloatT<T>::value) a += cvt<float>(x) != 0.0f;
+    else a += x != 0;
+  }
+  __device__ static void merge(Acc& a, const Acc& b) { a += b; }
+  __device__ static Acc shfl(const Acc& a, int m) { return shfl_xor(a, m); }
+  __device__ static void finish(const Acc& a, int64_t, double, double, double*, int64_t* i) { *i = a; }
+};
+
+// vector p-norm.  ORD 0: the count of non-zero elements; 1: sum |x| (fp32, like sum); 2: sqrt of the sum of squares
+// (binary64, so the squares of large fp32 values do not overflow); 3 / 4: the largest / smallest |x|, NaN if any;
+// 5: (sum |x|^p)^(1/p) in binary64 with p arriving as the op's parameter.
+template <class T, int ORD> struct NormPolicy {
+  using In = T;
+  static constexpr bool flt = true;
+  using Acc = typename std::conditional<ORD == 0, int64_t, typename std::conditional<ORD == 2 || ORD == 5, double, float>::type>::type;
+  static constexpr bool needs_shift = false;
+  __device__ static Acc init() {
+    if constexpr (ORD == 3) return 0.0f;                               // |x| >= 0
+    else if constexpr (ORD == 4) return __uint_as_float(0x7f800000u);
+    else return Acc(0);
+  }
+  __device__ static void merge(Acc& a, const Acc& b) {
+    if constexpr (ORD == 3) a = (a != a) ? a : ((b != b) ? b : (b > a ? b : a));
+    else if constexpr (ORD == 4) a = (a != a) ? a : ((b != b) ? b : (b < a ? b : a));
+    else a += b;
+  }
+  __device__ static void step(Acc& a, T x, int64_t, double p) {
+    const float v = __builtin_fabsf(cvt<float>(x));
+    if constexpr (ORD == 0) a += v != 0.0f;
+    else if constexpr (ORD == 1) a += v;
+    else if constexpr (ORD == 2) a = __builtin_fma((double)v, (double)v, a);
+    else if constexpr (ORD == 5) a += pow_abs_d((double)v, p);
+    else merge(a, v);
+  }
+  __device__ static Acc shfl(const Acc& a, int m) { return shfl_xor(a, m); }
+  __device__ static void finish(const Acc& a, int64_t, double p, double, double* f, int64_t*) {
+    if constexpr (ORD == 2) *f = __builtin_sqrt(a);
+    else if constexpr (ORD == 5) *f = pow(a, 1.0 / p);
+    else *f = (double)a;
+  }
+};
+
 // store a finished value in the run-time output dtype
 template <bool FLT> __device__ __forceinline__ void store_result(char* out, int64_t off, int dt, double f, int64_t i) {
   if constexpr (FLT) {
@@ -344,9 +416,11 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const Args a) {
   if (end > a.nred) end = a.nred;
   const T* x = (const T*)a.x + xo;
   const ReducedOffset<ONE_DIM> roff(a);
-  double K = 0.0;
-  if constexpr (P::needs_shift)
+  double K = a.correction;                             // policies without a shift receive the op's parameter here
+  if constexpr (P::needs_shift) {
+    K = 0.0;
     if (live && a.nred > 0) K = cvt<double>(x[roff(0)]);
+  }
   Acc acc = P::init();
   if (live) {
     // four loads are issued before the first value is used: a loop that loads, waits and accumulates one
@@ -425,7 +499,7 @@ __global__ __launch_bounds__(kBlock) void reduce_cols_kernel(const Args a) {
 #pragma unroll
   for (int j = 0; j < NV; ++j)
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) { acc[j][e] = P::init(); K[j][e] = 0.0; }
+    for (int e = 0; e < VEC; ++e) { acc[j][e] = P::init(); K[j][e] = P::needs_shift ? 0.0 : a.correction; }
   if constexpr (P::needs_shift) {
     if (a.nred > 0) {
       const int64_t off = roff(0);
@@ -587,6 +661,9 @@ tx_status launch_amin(const Plan&, const tx_tensor* x, const tx_tensor* out, dou
 tx_status launch_argmin(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
 tx_status launch_anyall(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
 tx_status launch_logsumexp(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_nansum(bool mean, const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_count(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
+tx_status launch_norm(const Plan&, const tx_tensor* x, const tx_tensor* out, double c, void* ws, size_t wsb, hipStream_t s);
 size_t acc_size(int op, int dtype);
 
 }  // namespace red

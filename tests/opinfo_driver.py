@@ -480,6 +480,22 @@ def bce(be, s):
     return be.bce(_tensor_ok(s.input), _tensor_ok(s.args[0]), None if w is None else _tensor_ok(w), s.kwargs.get("reduction", "mean"))
 
 
+def vector_norm(be, s):
+    kw = dict(s.kwargs)
+    args = list(s.args)
+    order = args.pop(0) if args else kw.pop("ord", 2)
+    if args:
+        kw["dim"] = args.pop(0)
+    if args:
+        kw["keepdim"] = args.pop(0)
+    if args or set(kw) - {"dim", "keepdim"}:
+        raise Unsupported("keyword %s" % sorted(set(kw) - {"dim", "keepdim"}))
+    dim = kw.get("dim")
+    if isinstance(dim, (list, tuple)):
+        dim = list(dim)
+    return be.reduce("norm", _tensor_ok(s.input), dim, bool(kw.get("keepdim", False)), float(order))
+
+
 def regression_loss(kind, param_name=None):
     def run(be, s):
         _no_kwargs(s, ("reduction",) + ((param_name,) if param_name else ()))
@@ -522,6 +538,8 @@ ADAPTERS = {
     "argmax": reduction("argmax", index=True), "argmin": reduction("argmin", index=True), "prod": reduction("prod", index=True),
     "var": reduction("var", variance=True), "std": reduction("std", variance=True), "any": reduction("any"),
     "all": reduction("all"), "logsumexp": reduction("logsumexp"),
+    "nansum": reduction("nansum"), "nanmean": reduction("nanmean"), "count_nonzero": reduction("count_nonzero"),
+    "linalg.vector_norm": vector_norm,
     "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": cumsum,
     "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
     "masked_select": masked_select, "nonzero": nonzero, "scatter_reduce": scatter_reduce, "index_put": index_put,

@@ -17,13 +17,14 @@ from tests.parity import assert_exact, assert_exact_fp, assert_rel, to_device_vi
 pytestmark = pytest.mark.gpu
 
 F32, BF16, F16, I32, I64, BOOL = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64, torch.bool
-OPS = ["sum", "mean", "amax", "argmax", "prod", "var", "amin", "argmin", "std", "any", "all", "logsumexp"]
+OPS = ["sum", "mean", "amax", "argmax", "prod", "var", "amin", "argmin", "std", "any", "all", "logsumexp", "nansum", "nanmean",
+       "count_nonzero", "norm"]
 FLT_MIN = 1.1754943508222875e-38
 
 
 def natural_scale(op, x, dims, keepdim):
     """Magnitude of what a result was made of (binary64): sqrt(sum x^2) for sum, that / n for mean."""
-    if op in ("sum", "mean"):
+    if op in ("sum", "mean", "nansum", "nanmean") and x.dtype.is_floating_point:
         xd = x.double()
         xd = torch.where(xd.isfinite(), xd, torch.zeros_like(xd))
         d = list(range(x.dim())) if dims is None else dims
@@ -35,7 +36,7 @@ def natural_scale(op, x, dims, keepdim):
             n = 1
             for k in ([d] if isinstance(d, int) else d):
                 n *= x.shape[k]
-        return s / max(n, 1) if op == "mean" else s
+        return s / max(n, 1) if op in ("mean", "nanmean") else s
     if op == "prod":
         return FLT_MIN
     if op == "logsumexp":
@@ -159,7 +160,7 @@ def test_reduce_multi_tile_ragged(op):
         paths.add(check_reduce(op, I.typed((600, 9001), dt, seed=215, std=1.0), 1))   # long rows, enough of them: block per row
     paths.discard(None)
     assert {"rows-wave", "rows-block", "rows-split", "cols"} <= paths, paths
-    if op in ("sum", "mean", "prod", "var", "std", "logsumexp"):
+    if op in ("sum", "mean", "prod", "var", "std", "logsumexp", "nansum", "nanmean", "norm"):
         check_reduce(op, I.typed((64, 300), BF16, seed=213, std=1.0), 1, out_dtype=F32, what="fp32 out")
 
 
@@ -222,3 +223,44 @@ def test_std_and_logsumexp_details():
     check_reduce("logsumexp", sp, 1)
     check_reduce("logsumexp", sp, 0)
     check_reduce("logsumexp", sp.repeat(1, 500), 1)          # across lanes and waves
+
+
+@pytest.mark.parametrize("p", [0.0, 2.0, float("inf"), -float("inf"), 3.0, 0.5, -1.0])
+def test_norm_orders(p):
+    paths = set()
+    for dt in (F32, BF16, F16):
+        x = I.typed((37, 50, 259), dt, seed=220, std=1.0)
+        for dims in (0, -1, (0, 2), None, 1):
+            paths.add(check_reduce("norm", x, dims, correction=p))
+        paths.add(check_reduce("norm", I.typed((3, 70001), dt, seed=221, std=1.0), 1, correction=p))
+        paths.add(check_reduce("norm", I.typed((5000, 96), dt, seed=222, std=1.0), 0, correction=p))
+        check_reduce("norm", I.typed((6, 9), dt, seed=223, specials=0.08), 1, correction=p, what="specials")
+        check_reduce("norm", torch.zeros((3, 0), dtype=dt), 1, correction=p)         # empty extent: 0, or an error for inf / negative p
+        check_reduce("norm", torch.zeros((0, 3), dtype=dt), 1, correction=p)
+    assert {"rows-wave", "rows-split", "cols"} <= paths, paths
+    # squares beyond fp32's range inside, a result within it
+    big = torch.tensor([[1e20, -1e20, 3e19], [1e-30, 1e-30, 0.0]], dtype=F32)
+    check_reduce("norm", big, 1, correction=p, what="large and tiny")
+    check_reduce("norm", torch.tensor([1, 2]), None, correction=p)                    # integers: refused
+    check_reduce("norm", torch.ones(3), None, correction=float("nan"))               # NaN exponent: refused
+
+
+def test_nan_reductions_and_count_full_size(full_inputs):
+    x = full_inputs[F32].clone()
+    x.view(-1)[::7] = float("nan")
+    for dims in (0, -1, None):
+        check_reduce("nansum", x, dims)
+        check_reduce("nanmean", x, dims)
+    x[:, 3, :] = float("nan")                                                        # whole slices of NaN: nansum 0, nanmean NaN
+    check_reduce("nanmean", x, 0)
+    check_reduce("nansum", x, -1)
+    z = full_inputs[F32].clone()
+    z.view(-1)[::3] = 0.0
+    z.view(-1)[1::5] = -0.0
+    for dims in (0, -1, None):
+        check_reduce("count_nonzero", z, dims)
+        check_reduce("norm", full_inputs[F32], dims, correction=2.0)
+    check_reduce("count_nonzero", full_inputs[BF16], -1)
+    check_reduce("count_nonzero", full_inputs[I64] % 3, 0)
+    check_reduce("norm", full_inputs[BF16], -1, correction=2.0)
+    check_reduce("norm", full_inputs[F32], 0, correction=float("inf"))
