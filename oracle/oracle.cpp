@@ -1517,10 +1517,19 @@ int orc_loss(int kind, const orc_tensor* out, const orc_tensor* x, const orc_ten
 // bool / int32 / int64 input -> int64 output, exact wrapping sums.  Floating
 // input: running binary64 accumulator, each prefix rounded independently to
 // the output dtype (x's dtype, or fp32 for a half x).
-int orc_cumsum(const orc_tensor* out, const orc_tensor* x, int64_t dim) {
+// cumprod and logcumsumexp along one dim (inclusive), with cumsum's shape and dim rules.
+//   op 1 cumprod      : dtypes as cumsum (bool / integer input -> int64, wrapping products); floating input: running
+//                       binary64 product, each prefix rounded independently.
+//   op 2 logcumsumexp : floating input only; out[i] = log(sum_{j <= i} exp(x[j])), carried as the running maximum m and
+//                       the sum s of exp(x[j] - m) in binary64 (out[i] = m + log s); an infinite maximum is the result
+//                       itself (-inf while nothing but -inf has been seen), a NaN makes every later prefix NaN.
+//   op 0 is cumsum.
+int orc_scan(int op, const orc_tensor* out, const orc_tensor* x, int64_t dim) {
+  if (op < 0 || op > 2) return ORC_ERR_SCALAR;
   int rc;
   if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
   const bool flt = is_float(x->dtype);
+  if (op == 2 && !flt) return ORC_ERR_DTYPE;
   if (flt) { if (out->dtype != x->dtype && out->dtype != ORC_F32) return ORC_ERR_DTYPE; }
   else if (out->dtype != ORC_I64) return ORC_ERR_DTYPE;
   if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
@@ -1542,15 +1551,38 @@ int orc_cumsum(const orc_tensor* out, const orc_tensor* x, int64_t dim) {
     unravel(s, nod, osz, sidx);
     for (int i = 0; i < nod; ++i) xi[od[i]] = sidx[i];
     const int64_t xb = offset_of(x, xi), ob = offset_of(out, xi);
-    double accd = 0.0;
-    uint64_t acci = 0;
+    double accd = op == 1 ? 1.0 : 0.0;
+    uint64_t acci = op == 1 ? 1u : 0u;
+    double m = -kInf, sum = 0.0;                       // logcumsumexp: running maximum and scaled sum
+    bool nan = false;
     for (int64_t j = 0; j < L; ++j) {
-      if (flt) { accd += load_flt(x, xb + j * xs); store_flt(out, ob + j * os, accd); }
-      else { acci += (uint64_t)load_int(x, xb + j * xs); store_int(out, ob + j * os, (int64_t)acci); }
+      if (op == 2) {
+        const double v = load_flt(x, xb + j * xs);
+        if (std::isnan(v)) nan = true;
+        if (!nan) {
+          if (v > m) {                                 // rescale the sum to the new maximum (exp(-inf - finite) = 0 for the first element)
+            sum = std::isinf(v) ? 0.0 : sum * std::exp(m - v) + 1.0;
+            m = v;
+          } else if (!std::isinf(v)) {                 // v <= m, finite: m is finite too
+            sum += std::exp(v - m);
+          }
+        }
+        store_flt(out, ob + j * os, nan ? kNaN : (std::isinf(m) ? m : m + std::log(sum)));
+      } else if (flt) {
+        const double v = load_flt(x, xb + j * xs);
+        accd = op == 1 ? accd * v : accd + v;
+        store_flt(out, ob + j * os, accd);
+      } else {
+        const uint64_t v = (uint64_t)load_int(x, xb + j * xs);
+        acci = op == 1 ? acci * v : acci + v;
+        store_int(out, ob + j * os, (int64_t)acci);
+      }
     }
   }
   return ORC_OK;
 }
+
+int orc_cumsum(const orc_tensor* out, const orc_tensor* x, int64_t dim) { return orc_scan(0, out, x, dim); }
 
 // ===========================================================================
 // Indexing

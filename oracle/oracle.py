@@ -72,6 +72,7 @@ def lib():
         _lib.orc_cumsum.argtypes = [P, P, ctypes.c_int64]
         _lib.orc_layer_norm.argtypes = [P, P, ctypes.c_int32, P, P, ctypes.c_double]
         _lib.orc_bce.argtypes = [P, P, P, P, ctypes.c_int]
+        _lib.orc_scan.argtypes = [ctypes.c_int, P, P, ctypes.c_int64]
         _lib.orc_loss.argtypes = [ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double]
         _lib.orc_gather.argtypes = [P, P, ctypes.c_int64, P]
         _lib.orc_index_select.argtypes = [P, P, ctypes.c_int64, P]
@@ -258,6 +259,17 @@ def cumsum(x, dim=-1, out=None, out_dtype=None):
         dt = x.dtype if x.dtype.is_floating_point else torch.int64
         out = torch.empty(x.shape, dtype=out_dtype or dt)
     _check(lib().orc_cumsum(desc(out), desc(x), dim))
+    return out
+
+
+SCAN = {"cumsum": 0, "cumprod": 1, "logcumsumexp": 2}
+
+
+def scan(op, x, dim=-1, out=None, out_dtype=None):
+    if out is None:
+        dt = x.dtype if x.dtype.is_floating_point else torch.int64
+        out = torch.empty(x.shape, dtype=out_dtype or dt)
+    _check(lib().orc_scan(SCAN.get(op, 9), desc(out), desc(x), dim))
     return out
 
 

@@ -93,6 +93,14 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* lds) 
   return r;
 }
 
+// one lane per slice: the slices, and the extent and strides of the dim operated on
+struct StridedArgs {
+  const char* x;
+  char* out;
+  Slices sl;
+  int64_t len, xs, os;
+  int is_log;
+};
 
 }  // namespace
 }  // namespace tx
