@@ -232,6 +232,9 @@ def build_ops(torch, B):
         finally:
             B.tx_force_path(None)
     extra("cumsum_f32_row_carry", "a11", "cumsum_carry_kernel", nc * 8, nc, carry_f32)
+    wsp = B.workspace(B.tx_scan_workspace_bytes("cumprod", ocf, cf, -1))
+    extra("cumprod_f32", "f3", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_scan("cumprod", ocf, cf, -1, wsp))
+    extra("logcumsumexp_f32", "f3", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_scan("logcumsumexp", ocf, cf, -1, wsp))
     # few long rows: every row has to be spread over the whole chip
     cl = randn((8, 1 << 24))
     ocl = torch.empty_like(cl)

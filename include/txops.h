@@ -319,6 +319,22 @@ tx_status tx_softmax(const tx_tensor* out, const tx_tensor* x, int64_t dim, int 
 tx_status tx_cumsum(const tx_tensor* out, const tx_tensor* x, int64_t dim, void* ws, size_t ws_bytes, void* stream);
 size_t tx_cumsum_workspace_bytes(const tx_tensor* out, const tx_tensor* x, int64_t dim);
 
+enum { TX_SCAN_SUM = 0, TX_SCAN_PROD = 1, TX_SCAN_LOGSUMEXP = 2 };
+
+/* Inclusive scan along `dim` with another combining operation; shapes, dim,
+ * aliasing and workspace rules as tx_cumsum (TX_SCAN_SUM is tx_cumsum).
+ *   PROD       cumprod: dtypes as cumsum (bool / integer x -> int64, wrapping);
+ *              floats multiply in binary64 and each prefix is rounded once.
+ *   LOGSUMEXP  logcumsumexp: floats only; out[i] = log(sum_{j<=i} exp(x[j])),
+ *              carried as (largest exponent m, sum of exp(x - m)) pairs in fp32
+ *              with one logarithm per output; -inf
+ *              while only -inf has been seen, +inf from the first +inf on, NaN
+ *              from the first NaN on.
+ * Another code is TX_ERR_SCALAR.  A contiguous `dim` takes the single-pass
+ * look-back / row-carry kernels; other layouts one lane per slice. */
+tx_status tx_scan(int op, const tx_tensor* out, const tx_tensor* x, int64_t dim, void* ws, size_t ws_bytes, void* stream);
+size_t tx_scan_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* x, int64_t dim);
+
 /* ------------------------------------------------------------------ indexing
  * (Table 1 "Indexing & Selection".)  Index tensors are int64 or int32 and are
  * NOT range-checked on the device: an index outside [0, extent) is undefined

@@ -37,7 +37,7 @@ STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so")
 
 EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
-           "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
+           "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_scan", "tx_scan_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
            "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_masked_select",
            "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
@@ -92,6 +92,8 @@ def lib():
         "tx_loss": ([ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_loss_workspace_bytes": ([ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double], ctypes.c_size_t),
         "tx_cumsum": ([P, P, ctypes.c_int64, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_scan": ([ctypes.c_int, P, P, ctypes.c_int64, V, ctypes.c_size_t, V], ctypes.c_int32),
+        "tx_scan_workspace_bytes": ([ctypes.c_int, P, P, ctypes.c_int64], ctypes.c_size_t),
         "tx_cumsum_workspace_bytes": ([P, P, ctypes.c_int64], ctypes.c_size_t),
         "tx_gather": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
         "tx_index_select": ([P, P, ctypes.c_int64, P, V], ctypes.c_int32),
@@ -339,6 +341,18 @@ def tx_cumsum(out, x, dim=-1, ws=None, stream=None):
 
 def tx_cumsum_workspace_bytes(out, x, dim=-1):
     return lib().tx_cumsum_workspace_bytes(desc(out), desc(x), dim)
+
+
+SCAN = {"cumsum": 0, "cumprod": 1, "logcumsumexp": 2}
+
+
+def tx_scan(op, out, x, dim=-1, ws=None, stream=None):
+    wp, wb = _ws(ws)
+    _check(lib().tx_scan(SCAN.get(op, 9), desc(out), desc(x), dim, wp, wb, _stream(stream)))
+
+
+def tx_scan_workspace_bytes(op, out, x, dim=-1):
+    return lib().tx_scan_workspace_bytes(SCAN.get(op, 9), desc(out), desc(x), dim)
 
 
 def tx_gather(out, src, dim, index, stream=None):

@@ -115,6 +115,9 @@ template <> struct Cvt<f16, float> {
 template <> struct Cvt<bf16, int64_t> {
   __device__ __forceinline__ static bf16 run(int64_t v) { return float_to_bf16((float)v); }
 };
+template <> struct Cvt<bf16, double> {
+  __device__ __forceinline__ static bf16 run(double v) { return float_to_bf16((float)v); }
+};
 template <> struct Cvt<uint8_t, float> {
   __device__ __forceinline__ static uint8_t run(float v) { return v != 0.0f; }
 };

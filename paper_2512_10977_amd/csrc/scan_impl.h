@@ -10,6 +10,30 @@
 #include "rows.h"
 
 namespace tx {
+
+// logcumsumexp accumulator: log(sum) = m + log(s), m the largest exponent met and s the sum of exp(x - m).
+// An element x is (x, 1), or (0, NaN) for a NaN; nothing is (-inf, 0).
+struct LsePair { float m, s; };
+template <> struct Cvt<LsePair, float> {
+  __device__ __forceinline__ static LsePair run(float v) { return v != v ? LsePair{0.0f, v} : LsePair{v, 1.0f}; }
+};
+template <> struct Cvt<LsePair, bf16> {
+  __device__ __forceinline__ static LsePair run(bf16 v) { return Cvt<LsePair, float>::run(bf16_to_float(v)); }
+};
+template <> struct Cvt<LsePair, f16> {
+  __device__ __forceinline__ static LsePair run(f16 v) { return Cvt<LsePair, float>::run((float)v); }
+};
+template <> struct Cvt<float, LsePair> {
+  // s >= 1 unless nothing or only -inf was met (s = 0, m = -inf: -inf + -inf) or a NaN was (s = NaN)
+  __device__ __forceinline__ static float run(LsePair a) { return a.m + __logf(a.s); }
+};
+template <> struct Cvt<bf16, LsePair> {
+  __device__ __forceinline__ static bf16 run(LsePair a) { return float_to_bf16(Cvt<float, LsePair>::run(a)); }
+};
+template <> struct Cvt<f16, LsePair> {
+  __device__ __forceinline__ static f16 run(LsePair a) { return (f16)Cvt<float, LsePair>::run(a); }
+};
+
 namespace {
 
 // ---------------------------------------------------------------------------
@@ -26,13 +50,14 @@ struct ScanMul {
     else return a * b;
   }
 };
-struct ScanLse {                                 // fp32 accumulators only
-  template <class A> __device__ __forceinline__ static A id() { return -__builtin_inff(); }
+struct ScanLse {                                 // on LsePair accumulators
+  template <class A> __device__ __forceinline__ static A id() { return LsePair{-__builtin_inff(), 0.0f}; }
+  // both sums are rescaled to the larger exponent.  The exponent difference is taken as 0 when the two are equal, so
+  // equal infinities do not produce inf - inf; exp(-inf) = 0 removes the side that has met nothing (or only -inf)
   template <class A> __device__ __forceinline__ static A op(A a, A b) {
-    if (a != a || b != b) return __uint_as_float(0x7fc00000u);
-    if (a == b) return a + 0.693147180559945309f;          // covers equal infinities, whose difference is NaN
-    const float m = a > b ? a : b;
-    return m + log1pf(expf(-__builtin_fabsf(a - b)));
+    const float M = a.m > b.m ? a.m : b.m;
+    const float da = a.m == M ? 0.0f : a.m - M, db = b.m == M ? 0.0f : b.m - M;
+    return LsePair{M, a.s * __expf(da) + b.s * __expf(db)};
   }
 };
 
@@ -85,6 +110,18 @@ template <> struct TileState<int64_t> {
   }
 };
 
+template <> struct TileState<LsePair> {
+  static constexpr int words = 4;
+  __device__ static void publish(unsigned long long* st, int64_t tile, uint32_t flag, LsePair v) {
+    TileState<int64_t>::publish(st, tile, flag, __builtin_bit_cast(int64_t, v));
+  }
+  __device__ static uint32_t read(unsigned long long* st, int64_t tile, LsePair* v) {
+    int64_t bits;
+    const uint32_t f = TileState<int64_t>::read(st, tile, &bits);
+    *v = __builtin_bit_cast(LsePair, bits);
+    return f;
+  }
+};
 // binary64 accumulators (cumprod of floats) travel as their bit pattern
 template <> struct TileState<double> {
   static constexpr int words = 4;

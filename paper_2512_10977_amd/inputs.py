@@ -159,6 +159,16 @@ def cumsum_input(shape=(4096, 65536), dtype=torch.float32, seed=3):
     return normal(shape, 1.0, seed, dtype)
 
 
+def cumprod_input(shape, dtype=torch.float32, seed=3):
+    """Factors whose running product stays finite over long rows: 1 + 0.001 N(0,1) with one sign in ten flipped for the
+    floating dtypes, odd integers in [-9, 9] (products wrap but never collapse to zero) for the integer ones."""
+    if dtype in INT_DTYPES:
+        return (integers(shape, -4, 4, seed, torch.int64) * 2 + 1).to(dtype)
+    x = 1.0 + 0.001 * normal(shape, 1.0, seed, torch.float32)
+    flip = torch.rand(shape, generator=_gen(seed + 1)) < 0.1
+    return torch.where(flip, -x, x).to(dtype)
+
+
 def uniform_indices(n, hi, seed=4, dtype=torch.int64):
     return torch.randint(0, hi, n if isinstance(n, tuple) else (n,), generator=_gen(seed), dtype=torch.int64).to(dtype)
 

@@ -88,6 +88,9 @@ class OracleBackend:
     def cumsum(self, x, dim):
         return self.O.cumsum(x, dim)
 
+    def scan(self, op, x, dim):
+        return self.O.scan(op, x, dim)
+
     def gather(self, x, dim, index):
         return self.O.gather(x, dim, index)
 
@@ -193,6 +196,12 @@ class LibraryBackend:
         dx = self.dev(x)
         out = self._out(x.shape, x.dtype if x.dtype.is_floating_point else I64)
         self.B.tx_cumsum(out, dx, dim, self._ws(self.B.tx_cumsum_workspace_bytes(out, dx, dim)))
+        return out.cpu()
+
+    def scan(self, op, x, dim):
+        dx = self.dev(x)
+        out = self._out(x.shape, x.dtype if x.dtype.is_floating_point else I64)
+        self.B.tx_scan(op, out, dx, dim, self._ws(self.B.tx_scan_workspace_bytes(op, out, dx, dim)))
         return out.cpu()
 
     def gather(self, x, dim, index):
@@ -404,6 +413,15 @@ def cumsum(be, s):
     return be.cumsum(_tensor_ok(s.input), s.args[0])
 
 
+def scan(op):
+    def run(be, s):
+        _no_kwargs(s)
+        if len(s.args) != 1:
+            raise Unsupported("arguments")
+        return be.scan(op, _tensor_ok(s.input), s.args[0])
+    return run
+
+
 def gather(be, s):
     _no_kwargs(s)
     return be.gather(_tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]))
@@ -540,7 +558,8 @@ ADAPTERS = {
     "all": reduction("all"), "logsumexp": reduction("logsumexp"),
     "nansum": reduction("nansum"), "nanmean": reduction("nanmean"), "count_nonzero": reduction("count_nonzero"),
     "linalg.vector_norm": vector_norm,
-    "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": cumsum,
+    "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": cumsum, "cumprod": scan("cumprod"),
+    "logcumsumexp": scan("logcumsumexp"),
     "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
     "masked_select": masked_select, "nonzero": nonzero, "scatter_reduce": scatter_reduce, "index_put": index_put,
     "nn.functional.layer_norm": layer_norm, "nn.functional.binary_cross_entropy": bce,

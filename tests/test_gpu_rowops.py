@@ -249,3 +249,98 @@ def test_column_forms_full_size(shape, dim):
     x = I.softmax_logits(shape, F32, seed=350)
     assert check_softmax(x, dim, False) == "softmax-cols"
     assert check_cumsum(x, dim) == "scan-cols"
+
+
+# --------------------------------------------------------------------------- cumprod, logcumsumexp
+def scan_input(op, shape, dt, seed):
+    if op == "cumprod":
+        return I.cumprod_input(shape, dt, seed=seed) if dt != BOOL else I.booleans(shape, 0.97, seed=seed)
+    return I.typed(shape, dt, seed=seed, std=3.0)
+
+
+def check_scan(op, x_cpu, dim=-1, out_dtype=None, what=""):
+    want = O.scan(op, x_cpu, dim, out_dtype=out_dtype)
+    x = to_device_view(x_cpu)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    nbytes = B.tx_scan_workspace_bytes(op, out, x, dim)
+    ws = B.workspace(nbytes) if nbytes else None
+    B.tx_scan(op, out, x, dim, ws)
+    used = B.tx_last_path()
+    torch.cuda.synchronize()
+    what = "%s %s %s dim=%d %s [%s]" % (op, x_cpu.dtype, tuple(x_cpu.shape), dim, what, used)
+    if not want.dtype.is_floating_point:
+        assert_exact(out, want, what)
+    elif op == "cumprod":                       # binary64 products, one rounding: no cancellation to allow for
+        assert_rel(out, want, 1e-6 if want.dtype == F32 else 1e-2, FLT_MIN, what)
+    else:                                       # a logarithm: absolute error of a few fp32 roundings of values of order |max|
+        assert_rel(out, want, 1e-5 if want.dtype == F32 else 1e-2, 1.0, what)
+    if ws is not None and used.startswith("scan-lookback"):
+        assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
+    return used
+
+
+@pytest.mark.parametrize("op", ["cumprod", "logcumsumexp"])
+def test_scan_shapes_and_paths(op):
+    paths = set()
+    dtypes = (F32, BF16, F16, I32, I64, BOOL) if op == "cumprod" else (F32, BF16, F16)
+    for dt in dtypes:
+        for shape in [(7, 13, 5), (33, 64), (9, 1000), (5, 4096), (3, 5000), (2, 70001), (1, 17), (40, 1), (2, 300000)]:
+            paths.add(check_scan(op, scan_input(op, shape, dt, 330), -1))
+        x = scan_input(op, (6, 50, 7), dt, 331)
+        for dim in (0, 1, 2, -2):
+            paths.add(check_scan(op, x, dim))
+        paths.add(check_scan(op, scan_input(op, (257, 30), dt, 332).t(), -1, what="transposed"))
+        paths.add(check_scan(op, scan_input(op, (30, 4096), dt, 333)[:, ::2], -1, what="step2_inner"))
+        paths.add(check_scan(op, scan_input(op, (60, 2048), dt, 334)[::2], -1, what="step2_outer"))
+    assert {"scan-carry", "scan-lookback", "scan-strided"} <= paths and any(p.endswith("-scalar") for p in paths), paths
+    check_scan(op, scan_input(op, (16, 9000), BF16, 335), -1, out_dtype=F32, what="fp32 out")
+    for dt in (F32, I64) if op == "cumprod" else (F32,):
+        x = scan_input(op, (1500, 6000), dt, 336)            # many short rows: row-carry
+        assert check_scan(op, x, -1).startswith("scan-carry")
+        B.tx_force_path("scan-lookback")
+        try:
+            assert check_scan(op, x, -1).startswith("scan-lookback")
+        finally:
+            B.tx_force_path(None)
+        assert check_scan(op, scan_input(op, (5, (1 << 22) + 776), dt, 337), -1) == "scan-lookback-wide"
+        assert check_scan(op, scan_input(op, (3, 3000001), dt, 338), -1) == "scan-lookback-wide-scalar"
+
+
+def test_scan_special_values_edges_and_errors():
+    inf, nan = float("inf"), float("nan")
+    check_scan("cumprod", torch.tensor([2.0, inf, 0.5, 0.0, 3.0]), 0)
+    check_scan("cumprod", torch.tensor([2.0, nan, 0.5]), 0)
+    check_scan("cumprod", torch.tensor([2 ** 31, 2 ** 31, 2, 3]), 0)                      # wraps to 0, stays 0
+    check_scan("logcumsumexp", torch.tensor([-inf, -inf, 1.0, -inf, 2.0]), 0)
+    check_scan("logcumsumexp", torch.tensor([0.0, inf, 1.0, -inf, inf]), 0)
+    check_scan("logcumsumexp", torch.tensor([1.0, nan, 2.0, inf]), 0)
+    check_scan("logcumsumexp", torch.tensor([1000.0, 999.0, -1000.0, 1001.0]), 0)
+    x = I.typed((9, 5000), F32, seed=339, specials=0.001)                                  # a few NaN / inf inside long rows
+    check_scan("logcumsumexp", x, -1, what="specials")
+    for op in ("cumprod", "logcumsumexp"):
+        check_scan(op, torch.tensor(4.0), 0)
+        check_scan(op, torch.zeros((0, 4)), 1)
+        check_scan(op, torch.zeros((4, 0)), 1)
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    for args, kind in [(("logcumsumexp", d(4, dt=I64), d(4, dt=I64), 0), "DTYPE"), (("cumprod", d(4, dt=I32), d(4, dt=I32), 0), "DTYPE"),
+                       (("cumprod", d(4, 4), d(4, 4), 2), "DIM"), (("cummax", d(4), d(4), 0), "SCALAR"),
+                       (("cumprod", d(4, 5), d(4, 4), 1), "SHAPE")]:
+        with pytest.raises(B.TxError) as e:
+            B.tx_scan(*args)
+        assert e.value.kind == kind, args
+    with pytest.raises(B.TxError) as e:
+        B.tx_scan("cumprod", d(4, 4), d(4, 4), 1, ws=None)
+    assert e.value.kind == "WORKSPACE"
+    # the sum through the same entry point is cumsum
+    xs = I.cumsum_input((5, 3000), F32, seed=340)
+    dx, o1, o2 = xs.cuda(), d(5, 3000), d(5, 3000)
+    ws = B.workspace(B.tx_scan_workspace_bytes("cumsum", o1, dx, -1))
+    B.tx_scan("cumsum", o1, dx, -1, ws)
+    B.tx_cumsum(o2, dx, -1, ws)
+    assert torch.equal(o1, o2)
+
+
+@pytest.mark.parametrize("op,dt", [("cumprod", F32), ("logcumsumexp", F32), ("cumprod", I64), ("logcumsumexp", BF16)])
+def test_scan_full_size(op, dt):
+    x = scan_input(op, (4096, 65536), dt, 341)
+    assert check_scan(op, x, -1) == "scan-lookback-wide"
