@@ -79,6 +79,9 @@ enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM,
        ORC_LOGICAL_AND, ORC_LOGICAL_OR, ORC_LOGICAL_XOR, ORC_POW, ORC_BITWISE_AND, ORC_BITWISE_OR, ORC_BITWISE_XOR,
        ORC_ATAN2, ORC_FMOD, ORC_REMAINDER, ORC_HYPOT, ORC_COPYSIGN, ORC_LOGADDEXP, ORC_LOGADDEXP2, ORC_XLOGY, ORC_HEAVISIDE,
        ORC_FMAX, ORC_FMIN, ORC_NEXTAFTER, ORC_GCD, ORC_LCM, ORC_SHIFT_LEFT, ORC_SHIFT_RIGHT };
+enum { ORC_LEAKY_RELU = 0, ORC_ELU, ORC_CELU, ORC_SELU, ORC_SOFTPLUS, ORC_THRESHOLD, ORC_HARDSHRINK, ORC_SOFTSHRINK, ORC_LOGIT,
+       ORC_NAN_TO_NUM };
+enum { ORC_ADDCMUL = 0, ORC_ADDCDIV, ORC_LERP };
 enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
        ORC_LOGSUMEXP, ORC_NANSUM, ORC_NANMEAN, ORC_COUNT_NONZERO, ORC_NORM };
 
@@ -873,6 +876,150 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
           break;
       }
     }
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// Elementwise: unary operators with scalar parameters (Table 1 "Deep Learning" activations and friends)
+// ===========================================================================
+// out[i] = f(a[i]; p0, p1, p2); out has a's shape and the result dtype.  The parameters are binary64 values and the
+// function is evaluated in binary64 on the input converted to the result dtype, one rounding.
+//   leaky_relu(p0 = slope)  : x > 0 ? x : x * slope
+//   elu(p0 = alpha)         : x > 0 ? x : alpha * expm1(x)
+//   celu(p0 = alpha != 0)   : x > 0 ? x : alpha * expm1(x / alpha)       (alpha = 0 is ORC_ERR_SCALAR)
+//   selu                    : scale * (x > 0 ? x : alpha * expm1(x)), scale = 1.0507009873554805, alpha = 1.6732632423543772
+//   softplus(p0 = beta, p1 = threshold) : x * beta > threshold ? x : log1p(exp(x * beta)) / beta
+//   hardshrink(p0 = lambda) : -lambda <= x <= lambda ? 0 : x                (a NaN stays)
+//   softshrink(p0 = lambda >= 0) : x > lambda ? x - lambda : x < -lambda ? x + lambda : x * 0   (keeps -0.0 and NaN;
+//                             a negative lambda is ORC_ERR_SCALAR)
+//     - these seven take floating dtypes only -
+//   threshold(p0 = threshold, p1 = value) : x <= threshold ? value : x; floats and int32 / int64 (the two parameters are
+//                             truncated to the integer dtype first); a NaN x stays
+//   logit(p0 = eps, p1 != 0: eps given) : log(z / (1 - z)), z = x clamped to [eps, 1 - eps] when eps is given (x < eps ?
+//                             eps : x > 1 - eps ? 1 - eps : x); bool / integer input computes in fp32
+//   nan_to_num(p0 = nan, p1 = posinf, p2 = neginf) : replaces NaN, +inf, -inf by the parameters rounded to the dtype;
+//                             integers and bools are returned as they are
+int orc_unary_param_result_dtype(int op, int in_dtype) {
+  if (!valid_dtype(in_dtype)) return ORC_ERR_DTYPE;
+  switch (op) {
+    case ORC_LEAKY_RELU: case ORC_ELU: case ORC_CELU: case ORC_SELU: case ORC_SOFTPLUS: case ORC_HARDSHRINK: case ORC_SOFTSHRINK:
+      return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
+    case ORC_THRESHOLD: return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
+    case ORC_LOGIT: return is_float(in_dtype) ? in_dtype : ORC_F32;
+    case ORC_NAN_TO_NUM: return in_dtype;
+  }
+  return ORC_ERR_SCALAR;
+}
+
+int orc_unary_param(int op, const orc_tensor* out, const orc_tensor* a, double p0, double p1, double p2) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(a))) return rc;
+  const int rd = orc_unary_param_result_dtype(op, a->dtype);
+  if (rd < 0) return rd;
+  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  if (!same_shape(out, a->ndim, a->sizes)) return ORC_ERR_SHAPE;
+  if (op == ORC_CELU && p0 == 0.0) return ORC_ERR_SCALAR;
+  if (op == ORC_SOFTSHRINK && !(p0 >= 0.0)) return ORC_ERR_SCALAR;
+  const int64_t n = numel(out);
+  const int nd = a->ndim;
+  const double selu_scale = 1.0507009873554804934193349852946, selu_alpha = 1.6732632423543772848170429916717;
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, out->sizes, idx);
+    const int64_t oo = offset_of(out, idx), ao = offset_of(a, idx);
+    if (!is_float(rd)) {                                // threshold / nan_to_num of an integer or bool tensor
+      const int64_t v = load_int(a, ao);
+      if (op == ORC_THRESHOLD) {
+        const int64_t th = rd == ORC_I32 ? (int64_t)(int32_t)p0 : (int64_t)p0, val = rd == ORC_I32 ? (int64_t)(int32_t)p1 : (int64_t)p1;
+        put_int(out, oo, rd, v <= th ? val : v);
+      } else {
+        put_int(out, oo, rd, v);
+      }
+      continue;
+    }
+    const double x = (double)load_as(a, ao, rd).f;
+    double y = 0.0;
+    switch (op) {
+      case ORC_LEAKY_RELU: y = x > 0.0 ? x : x * p0; break;
+      case ORC_ELU: y = x > 0.0 ? x : p0 * std::expm1(x); break;
+      case ORC_CELU: y = x > 0.0 ? x : p0 * std::expm1(x / p0); break;
+      case ORC_SELU: y = selu_scale * (x > 0.0 ? x : selu_alpha * std::expm1(x)); break;
+      case ORC_SOFTPLUS: y = x * p0 > p1 ? x : std::log1p(std::exp(x * p0)) / p0; break;
+      case ORC_THRESHOLD: y = x <= p0 ? (double)round_to_float_dtype(p1, rd) : x; break;
+      case ORC_HARDSHRINK: y = (x >= -p0 && x <= p0) ? 0.0 : x; break;
+      case ORC_SOFTSHRINK: y = x > p0 ? x - p0 : (x < -p0 ? x + p0 : x * 0.0); break;
+      case ORC_LOGIT: {
+        double z = x;
+        if (p1 != 0.0) z = z < p0 ? p0 : (z > 1.0 - p0 ? 1.0 - p0 : z);
+        y = std::log(z / (1.0 - z));
+        break;
+      }
+      case ORC_NAN_TO_NUM: y = std::isnan(x) ? p0 : (std::isinf(x) ? (x > 0.0 ? p1 : p2) : x); break;
+    }
+    put_flt(out, oo, rd, y);
+  }
+  return ORC_OK;
+}
+
+// ===========================================================================
+// Elementwise: ternary (addcmul, addcdiv, lerp) with broadcasting and type promotion
+// ===========================================================================
+//   addcmul : a + value * b * c.  Integer result: wrapping, value truncated to an integer.  bool is a dtype error.
+//   addcdiv : a + value * b / c; the promoted dtype must be floating.
+//   lerp    : a + w (b - a) for w < 1/2, b - (b - a)(1 - w) otherwise (exact at both ends); w is the tensor c, or the
+//             scalar `value` when c is null; every tensor has one floating dtype.
+// Operands are converted to the promoted dtype, the expression is evaluated in binary64 and rounded once.
+int orc_ternary_result_dtype(int op, const orc_tensor* a, const orc_tensor* b, const orc_tensor* c) {
+  if (op < ORC_ADDCMUL || op > ORC_LERP) return ORC_ERR_SCALAR;
+  if (!a || !b || (op != ORC_LERP && !c)) return ORC_ERR_NULL;
+  if (op == ORC_LERP) {
+    if (!is_float(a->dtype) || b->dtype != a->dtype || (c && c->dtype != a->dtype)) return ORC_ERR_DTYPE;
+    return a->dtype;
+  }
+  const orc_tensor* ops[3] = {a, b, c};
+  const int rd = result_type(ops, 3);
+  if (rd == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (op == ORC_ADDCDIV && !is_float(rd)) return ORC_ERR_DTYPE;
+  return rd;
+}
+
+int orc_ternary(int op, const orc_tensor* out, const orc_tensor* a, const orc_tensor* b, const orc_tensor* c, double value_f,
+                int64_t value_i, int value_is_int) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(a)) || (rc = check_tensor(b))) return rc;
+  if (c && (rc = check_tensor(c))) return rc;
+  const int rd = orc_ternary_result_dtype(op, a, b, c);
+  if (rd < 0) return rd;
+  if (out->dtype != rd) return ORC_ERR_DTYPE;
+  const orc_tensor* ops[3] = {a, b, c};
+  int nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(ops, c ? 3 : 2, &nd, sizes))) return rc;
+  if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;
+  const double value = value_is_int ? (double)value_i : value_f;
+  const int64_t ivalue = value_is_int ? value_i : (int64_t)value_f;      // integer result: truncated
+  int64_t n = 1;
+  for (int d = 0; d < nd; ++d) n *= sizes[d];
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    const int64_t oo = offset_of(out, idx);
+    const Val x = load_as(a, bcast_offset(a, nd, idx), rd), y = load_as(b, bcast_offset(b, nd, idx), rd);
+    Val z{0, 0.0f};
+    if (c) z = load_as(c, bcast_offset(c, nd, idx), rd);
+    if (!is_float(rd)) {
+      put_int(out, oo, rd, (int64_t)((uint64_t)x.i + (uint64_t)ivalue * (uint64_t)y.i * (uint64_t)z.i));
+      continue;
+    }
+    const double xd = x.f, yd = y.f, zd = c ? (double)z.f : value;
+    double r;
+    if (op == ORC_ADDCMUL) r = xd + value * yd * zd;
+    else if (op == ORC_ADDCDIV) r = xd + value * yd / zd;
+    else r = zd < 0.5 ? xd + zd * (yd - xd) : yd - (yd - xd) * (1.0 - zd);
+    put_flt(out, oo, rd, r);
   }
   return ORC_OK;
 }

@@ -72,6 +72,9 @@ def lib():
         _lib.orc_cumsum.argtypes = [P, P, ctypes.c_int64]
         _lib.orc_layer_norm.argtypes = [P, P, ctypes.c_int32, P, P, ctypes.c_double]
         _lib.orc_bce.argtypes = [P, P, P, P, ctypes.c_int]
+        _lib.orc_unary_param.argtypes = [ctypes.c_int, P, P, ctypes.c_double, ctypes.c_double, ctypes.c_double]
+        _lib.orc_ternary_result_dtype.argtypes = [ctypes.c_int, P, P, P]
+        _lib.orc_ternary.argtypes = [ctypes.c_int, P, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
         _lib.orc_scan.argtypes = [ctypes.c_int, P, P, ctypes.c_int64]
         _lib.orc_loss.argtypes = [ctypes.c_int, P, P, P, ctypes.c_int, ctypes.c_double]
         _lib.orc_gather.argtypes = [P, P, ctypes.c_int64, P]
@@ -167,6 +170,35 @@ def binary(op, a, b, alpha=1, out=None, out_dtype=None):
         out = torch.empty(shape, dtype=out_dtype or dt)
     af, ai, isint = _scalar(alpha)
     _check(lib().orc_binary(BINARY[op], desc(out), desc(a), desc(b), af, ai, isint))
+    return out
+
+
+UNARY_PARAM = {"leaky_relu": 0, "elu": 1, "celu": 2, "selu": 3, "softplus": 4, "threshold": 5, "hardshrink": 6, "softshrink": 7,
+               "logit": 8, "nan_to_num": 9}
+TERNARY = {"addcmul": 0, "addcdiv": 1, "lerp": 2}
+
+
+def unary_param(op, a, p0=0.0, p1=0.0, p2=0.0, out=None):
+    if out is None:
+        rc = lib().orc_unary_param_result_dtype(UNARY_PARAM.get(op, 99), DTYPE_CODE[a.dtype])
+        _check(min(rc, 0))
+        out = torch.empty(a.shape, dtype=CODE_DTYPE[rc])
+    _check(lib().orc_unary_param(UNARY_PARAM.get(op, 99), desc(out), desc(a), float(p0), float(p1), float(p2)))
+    return out
+
+
+def ternary(op, a, b, c=None, value=1, out=None):
+    if out is None:
+        rc = lib().orc_ternary_result_dtype(TERNARY.get(op, 99), desc(a), desc(b), _opt(c))
+        _check(min(rc, 0))
+        ts = [a, b] + ([c] if c is not None else [])
+        try:
+            shape = torch.broadcast_shapes(*[t.shape for t in ts])
+        except RuntimeError:                          # not broadcastable: the oracle reports it
+            shape = a.shape
+        out = torch.empty(shape, dtype=CODE_DTYPE[rc])
+    vf, vi, isint = _scalar(value)
+    _check(lib().orc_ternary(TERNARY.get(op, 99), desc(out), desc(a), desc(b), _opt(c), vf, vi, isint))
     return out
 
 
