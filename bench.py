@@ -106,6 +106,11 @@ def build_ops(torch, B):
     for fourth in ("relu", "hardswish", "erf", "tan", "mish"):
         extra(fourth + "_f32", "f1", "ew_vec_kernel", n2 * 8, n2, (lambda o: (lambda: B.tx_unary(o, of, xf)))(fourth))
     extra("relu_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("relu", ob, xb))
+    for name, params in (("leaky_relu", (0.01,)), ("elu", (1.0,)), ("softplus", (1.0, 20.0)), ("hardshrink", (0.5,))):
+        extra(name + "_f32", "f1", "ew_vec_kernel", n2 * 8, n2, (lambda o, p: (lambda: B.tx_unary_param(o, of, xf, *p)))(name, params))
+    extra("elu_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary_param("elu", ob, xb, 1.0))
+    extra("addcmul_f32", "f1", "ew_vec_kernel", n2 * 16, n2, lambda: B.tx_ternary("addcmul", of, xf, yf, tall[:N], 0.5))
+    extra("lerp_f32_scalar_weight", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_ternary("lerp", of, xf, yf, None, 0.3))
     for fourth in ("fmax", "remainder", "hypot", "logaddexp"):
         extra(fourth + "_f32", "f1", "ew_vec_kernel", n2 * 12, n2, (lambda o: (lambda: B.tx_binary(o, of, xf, yf)))(fourth))
     extra("clamp_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_clamp(of, xf, -0.5, 0.75))

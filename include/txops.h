@@ -133,6 +133,48 @@ enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARG
  *              for an integer, false for a bool; bool result. */
 tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* stream);
 
+/* Unary operators with scalar parameters (Table 1 "Deep Learning" activations and
+ * their relatives): out[i] = f(a[i]; p0, p1, p2), out has a's shape and the
+ * result dtype.  The parameters are binary64 values; fp32 results are within
+ * 2 ulp of the binary64 evaluation.
+ *   LEAKY_RELU(p0 = slope)   x > 0 ? x : x * slope
+ *   ELU(p0 = alpha)          x > 0 ? x : alpha * expm1(x)
+ *   CELU(p0 = alpha)         x > 0 ? x : alpha * expm1(x / alpha); alpha = 0 is
+ *                            TX_ERR_SCALAR
+ *   SELU                     scale * ELU(alpha) with the two published constants
+ *   SOFTPLUS(p0 = beta, p1 = threshold)  x * beta > threshold ? x :
+ *                            log1p(exp(x * beta)) / beta
+ *   HARDSHRINK(p0 = lambda)  -lambda <= x <= lambda ? 0 : x
+ *   SOFTSHRINK(p0 = lambda)  x > lambda ? x - lambda : x < -lambda ? x + lambda :
+ *                            x * 0; a negative lambda is TX_ERR_SCALAR
+ *       - floating dtypes only for these seven -
+ *   THRESHOLD(p0 = threshold, p1 = value)  x <= threshold ? value : x; floats,
+ *                            int32, int64 (parameters truncated to the integer
+ *                            dtype); a NaN x stays
+ *   LOGIT(p0 = eps, p1 != 0: eps given)  log(z / (1 - z)), z = x clamped to
+ *                            [eps, 1 - eps] when eps is given; bool / integer a
+ *                            computes and returns fp32
+ *   NAN_TO_NUM(p0, p1, p2)   NaN, +inf, -inf replaced by the parameters rounded
+ *                            to the dtype; bool / integer a is copied */
+enum { TX_LEAKY_RELU = 0, TX_ELU, TX_CELU, TX_SELU, TX_SOFTPLUS, TX_THRESHOLD, TX_HARDSHRINK, TX_SOFTSHRINK, TX_LOGIT,
+       TX_NAN_TO_NUM };
+tx_status tx_unary_param(int op, const tx_tensor* out, const tx_tensor* a, double p0, double p1, double p2, void* stream);
+int32_t tx_infer_unary_param_dtype(int op, int32_t in_dtype);
+
+/* Ternary operators with broadcasting and type promotion.
+ *   ADDCMUL  a + value * b * c; integer result: wrapping, value truncated; three
+ *            bools are TX_ERR_DTYPE.
+ *   ADDCDIV  a + value * b / c; the promoted dtype must be floating.
+ *   LERP     a + w (b - a) for w < 1/2, b - (b - a)(1 - w) otherwise; w is the
+ *            tensor c, or the scalar value when c is NULL; one floating dtype
+ *            for every tensor.
+ * value is given both ways (value_is_int selects value_i).  fp32 results are the
+ * binary64 evaluation rounded once. */
+enum { TX_ADDCMUL = 0, TX_ADDCDIV = 1, TX_LERP = 2 };
+tx_status tx_ternary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, const tx_tensor* c, double value_f,
+                     int64_t value_i, int value_is_int, void* stream);
+int32_t tx_infer_ternary_dtype(int op, const tx_tensor* a, const tx_tensor* b, const tx_tensor* c);
+
 /* out = a + alpha * b with broadcasting and type promotion.  alpha is given
  * both ways: alpha_is_int selects alpha_i, else alpha_f.  bool: a OR (alpha!=0
  * AND b).  Integer result: wrapping arithmetic, alpha must be integral

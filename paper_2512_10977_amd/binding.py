@@ -40,7 +40,7 @@ EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_cl
            "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_scan", "tx_scan_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
            "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_masked_select",
-           "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype",
+           "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype", "tx_unary_param", "tx_infer_unary_param_dtype", "tx_ternary", "tx_infer_ternary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
 
 
@@ -114,6 +114,10 @@ def lib():
         "tx_infer_binary": ([ctypes.c_int, P, P, I32P, I32P, I64P], ctypes.c_int32),
         "tx_infer_where": ([P, P, I32P], ctypes.c_int32),
         "tx_infer_unary_dtype": ([ctypes.c_int, ctypes.c_int32], ctypes.c_int32),
+        "tx_unary_param": ([ctypes.c_int, P, P, ctypes.c_double, ctypes.c_double, ctypes.c_double, V], ctypes.c_int32),
+        "tx_infer_unary_param_dtype": ([ctypes.c_int, ctypes.c_int32], ctypes.c_int32),
+        "tx_ternary": ([ctypes.c_int, P, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
+        "tx_infer_ternary_dtype": ([ctypes.c_int, P, P, P], ctypes.c_int32),
         "tx_infer_reduce": ([ctypes.c_int, P, I64P, ctypes.c_int32, ctypes.c_int, I32P, I32P, I64P], ctypes.c_int32),
         "tx_last_path": ([], ctypes.c_char_p),
         "tx_force_path": ([ctypes.c_char_p], None),
@@ -390,6 +394,32 @@ def tx_infer_unary_dtype(op, dtype):
     rc = lib().tx_infer_unary_dtype(UNARY[op], DTYPE_CODE[dtype])
     _check(rc)
     return CODE_DTYPE[rc]
+
+
+UNARY_PARAM = {"leaky_relu": 0, "elu": 1, "celu": 2, "selu": 3, "softplus": 4, "threshold": 5, "hardshrink": 6, "softshrink": 7,
+               "logit": 8, "nan_to_num": 9}
+TERNARY = {"addcmul": 0, "addcdiv": 1, "lerp": 2}
+
+
+def tx_infer_unary_param_dtype(op, dtype):
+    rc = lib().tx_infer_unary_param_dtype(UNARY_PARAM.get(op, 99), DTYPE_CODE[dtype])
+    _check(rc)
+    return CODE_DTYPE[rc]
+
+
+def tx_unary_param(op, out, a, p0=0.0, p1=0.0, p2=0.0, stream=None):
+    _check(lib().tx_unary_param(UNARY_PARAM.get(op, 99), desc(out), desc(a), float(p0), float(p1), float(p2), _stream(stream)))
+
+
+def tx_infer_ternary_dtype(op, a, b, c=None):
+    rc = lib().tx_infer_ternary_dtype(TERNARY.get(op, 99), desc(a), desc(b), _opt(c))
+    _check(rc)
+    return CODE_DTYPE[rc]
+
+
+def tx_ternary(op, out, a, b, c=None, value=1, stream=None):
+    vf, vi, isint = _scalar(value)
+    _check(lib().tx_ternary(TERNARY.get(op, 99), desc(out), desc(a), desc(b), _opt(c), vf, vi, isint, _stream(stream)))
 
 
 def tx_infer_reduce(op, x, dims=None, keepdim=False):

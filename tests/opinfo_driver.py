@@ -91,6 +91,12 @@ class OracleBackend:
     def scan(self, op, x, dim):
         return self.O.scan(op, x, dim)
 
+    def unary_param(self, op, x, *params):
+        return self.O.unary_param(op, x, *params)
+
+    def ternary(self, op, a, b, c, value):
+        return self.O.ternary(op, a, b, c, value)
+
     def gather(self, x, dim, index):
         return self.O.gather(x, dim, index)
 
@@ -196,6 +202,18 @@ class LibraryBackend:
         dx = self.dev(x)
         out = self._out(x.shape, x.dtype if x.dtype.is_floating_point else I64)
         self.B.tx_cumsum(out, dx, dim, self._ws(self.B.tx_cumsum_workspace_bytes(out, dx, dim)))
+        return out.cpu()
+
+    def unary_param(self, op, x, *params):
+        out = self._out(x.shape, self.B.tx_infer_unary_param_dtype(op, x.dtype))
+        self.B.tx_unary_param(op, out, self.dev(x), *params)
+        return out.cpu()
+
+    def ternary(self, op, a, b, c, value):
+        da, db, dc = self.dev(a), self.dev(b), None if c is None else self.dev(c)
+        shape = torch.broadcast_shapes(*[t.shape for t in (a, b, c) if t is not None])
+        out = self._out(shape, self.B.tx_infer_ternary_dtype(op, da, db, dc))
+        self.B.tx_ternary(op, out, da, db, dc, value)
         return out.cpu()
 
     def scan(self, op, x, dim):
@@ -498,6 +516,71 @@ def bce(be, s):
     return be.bce(_tensor_ok(s.input), _tensor_ok(s.args[0]), None if w is None else _tensor_ok(w), s.kwargs.get("reduction", "mean"))
 
 
+def activation(op, names, defaults):
+    """A unary operator with scalar parameters: positional arguments fill `names` in order, then keywords."""
+    def run(be, s):
+        _no_kwargs(s, tuple(names) + ("inplace",))
+        if len(s.args) > len(names) or s.kwargs.get("inplace"):
+            raise Unsupported("arguments")
+        vals = dict(zip(names, defaults))
+        vals.update(dict(zip(names, s.args)))
+        vals.update({k: v for k, v in s.kwargs.items() if k != "inplace"})
+        if any(isinstance(v, torch.Tensor) for v in vals.values()):
+            raise Unsupported("tensor-valued parameter")
+        return be.unary_param(op, _tensor_ok(s.input), *[_scalar(vals[n]) for n in names])
+    return run
+
+
+def logit(be, s):
+    _no_kwargs(s, ("eps",))
+    eps = s.args[0] if s.args else s.kwargs.get("eps")
+    x = _tensor_ok(s.input)
+    return be.unary_param("logit", x) if eps is None else be.unary_param("logit", x, float(eps), 1)
+
+
+def nan_to_num(be, s):
+    _no_kwargs(s, ("nan", "posinf", "neginf"))
+    x = _tensor_ok(s.input)
+    vals = dict(zip(("nan", "posinf", "neginf"), s.args))
+    vals.update(s.kwargs)
+    fi = torch.finfo(x.dtype) if x.dtype.is_floating_point else None
+    nan = vals.get("nan")
+    pos, neg = vals.get("posinf"), vals.get("neginf")
+    return be.unary_param("nan_to_num", x, 0.0 if nan is None else float(nan), (fi.max if fi else 0.0) if pos is None else float(pos),
+                          (fi.min if fi else 0.0) if neg is None else float(neg))
+
+
+def hardtanh(lo, hi):
+    def run(be, s):
+        _no_kwargs(s, ("min_val", "max_val", "inplace"))
+        vals = {"min_val": lo, "max_val": hi}
+        vals.update(dict(zip(("min_val", "max_val"), s.args)))
+        vals.update({k: v for k, v in s.kwargs.items() if k != "inplace"})
+        x = _tensor_ok(s.input)
+        bounds = [_scalar(vals["min_val"]), _scalar(vals["max_val"])]
+        if not x.dtype.is_floating_point:                  # the operator keeps an integer dtype: its bounds are truncated to it
+            bounds = [int(b) for b in bounds]
+        return be.clamp(x, *bounds)
+    return run
+
+
+def ternary(op):
+    def run(be, s):
+        _no_kwargs(s, ("value",))
+        if len(s.args) != 2:
+            raise Unsupported("arguments")
+        return be.ternary(op, _tensor_ok(s.input), _tensor_ok(s.args[0]), _tensor_ok(s.args[1]), _scalar(s.kwargs.get("value", 1)))
+    return run
+
+
+def lerp(be, s):
+    _no_kwargs(s)
+    a, b, w = _tensor_ok(s.input), _tensor_ok(s.args[0]), s.args[1]
+    if isinstance(w, torch.Tensor):
+        return be.ternary("lerp", a, b, _tensor_ok(w), 1)
+    return be.ternary("lerp", a, b, None, _scalar(w))
+
+
 def vector_norm(be, s):
     kw = dict(s.kwargs)
     args = list(s.args)
@@ -563,6 +646,14 @@ ADAPTERS = {
     "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
     "masked_select": masked_select, "nonzero": nonzero, "scatter_reduce": scatter_reduce, "index_put": index_put,
     "nn.functional.layer_norm": layer_norm, "nn.functional.binary_cross_entropy": bce,
+    "nn.functional.leaky_relu": activation("leaky_relu", ("negative_slope",), (0.01,)),
+    "nn.functional.elu": activation("elu", ("alpha",), (1.0,)), "nn.functional.celu": activation("celu", ("alpha",), (1.0,)),
+    "nn.functional.selu": activation("selu", (), ()), "nn.functional.softplus": activation("softplus", ("beta", "threshold"), (1.0, 20.0)),
+    "nn.functional.threshold": activation("threshold", ("threshold", "value"), (None, None)),
+    "nn.functional.hardshrink": activation("hardshrink", ("lambd",), (0.5,)),
+    "nn.functional.softshrink": activation("softshrink", ("lambd",), (0.5,)), "logit": logit, "nan_to_num": nan_to_num,
+    "nn.functional.hardtanh": hardtanh(-1.0, 1.0), "nn.functional.relu6": hardtanh(0.0, 6.0),
+    "addcmul": ternary("addcmul"), "addcdiv": ternary("addcdiv"), "lerp": lerp,
     "nn.functional.mse_loss": regression_loss("mse"), "nn.functional.l1_loss": regression_loss("l1"),
     "nn.functional.smooth_l1_loss": regression_loss("smooth_l1", "beta"), "nn.functional.huber_loss": regression_loss("huber", "delta"),
 }

@@ -612,3 +612,131 @@ def test_binary_out_casting_full_size():
     assert B.tx_last_path() == "vec"
     sync()
     assert_exact_fp(out, O.binary("add", a, b, out_dtype=F32), "bf16 + bf16 -> f32 out")
+
+
+# --------------------------------------------------------------------------- unary operators with parameters, ternary operators
+PARAM_OPS = [("leaky_relu", (0.01,)), ("leaky_relu", (-2.0,)), ("elu", (1.5,)), ("elu", (0.0,)), ("celu", (2.5,)), ("celu", (-1.0,)),
+             ("selu", ()), ("softplus", (1.0, 20.0)), ("softplus", (2.0, 5.0)), ("softplus", (-1.0, 20.0)), ("threshold", (0.3, 9.0)),
+             ("threshold", (1, 7)), ("hardshrink", (0.5,)), ("hardshrink", (-1.0,)), ("softshrink", (0.5,)), ("softshrink", (0.0,)),
+             ("logit", ()), ("logit", (0.125, 1)), ("logit", (0.75, 1)), ("nan_to_num", (0.0, 3e38, -3e38)), ("nan_to_num", (1.0, 2.0, -3.0))]
+EXACT_PARAM = ("threshold", "hardshrink", "nan_to_num")
+
+
+def check_unary_param(op, params, a_cpu, what=""):
+    try:
+        want = O.unary_param(op, a_cpu, *params)
+    except O.OracleError as e:
+        a = to_device_view(a_cpu)
+        with pytest.raises(B.TxError) as g:
+            B.tx_unary_param(op, torch.empty(a.shape, dtype=a.dtype, device="cuda"), a, *params)
+        assert g.value.kind.lower() == e.kind, (op, a_cpu.dtype, g.value.kind, e.kind)
+        return None
+    a = to_device_view(a_cpu)
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_unary_param(op, out, a, *params)
+    used = B.tx_last_path()
+    sync()
+    what = "%s%s %s %s %s [%s]" % (op, params, a_cpu.dtype, tuple(a_cpu.shape), what, used)
+    if op in EXACT_PARAM or not want.dtype.is_floating_point:
+        assert_exact_fp(out, want, what) if want.dtype.is_floating_point else assert_exact(out, want, what)
+    elif want.dtype == F32:
+        assert_ulp(out, want, 2, what)
+    else:
+        assert_rel(out, want, 1e-2, scale=6.2e-5 if want.dtype == F16 else FLT_TINY, what=what, overflow_max=HALF_MAX[want.dtype])
+    return used
+
+
+@pytest.mark.parametrize("op,params", PARAM_OPS)
+def test_unary_param_sweep(op, params):
+    unit = op == "logit"
+    for dt, kind in itertools.product(ALL, I.VIEW_KINDS):
+        a = I.make_view((7, 13, 5), dt, kind, seed=190, specials=0.02, std=0.4 if unit else 3.0)
+        if unit and dt.is_floating_point:
+            a = (a * 0.5 + 0.5)                                     # mostly inside (0, 1), some outside, the special values kept
+        check_unary_param(op, params, a, what=kind)
+    for dt in ALL:
+        check_unary_param(op, params, I.typed((0,), dt, seed=1))
+        check_unary_param(op, params, I.typed((), dt, seed=2))
+    x = I.typed((2048, 4096), F32, seed=191, specials=0.01, std=0.4 if unit else 3.0)
+    assert check_unary_param(op, params, x * 0.5 + 0.5 if unit else x) == "vec"
+    wide = torch.linspace(-100.0, 100.0, 1 << 20).view(1024, 1024)
+    check_unary_param(op, params, wide * 0.006 + 0.5 if unit else wide, what="wide range")
+    check_unary_param(op, params, I.typed((1024, 4096), BF16, seed=192, specials=0.01))
+
+
+def test_unary_param_errors():
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    for args, kind in [(("celu", d(3), d(3), 0.0), "SCALAR"), (("softshrink", d(3), d(3), -1.0), "SCALAR"), (("prelu", d(3), d(3)), "SCALAR"),
+                       (("elu", d(3, dt=I32), d(3, dt=I32), 1.0), "DTYPE"), (("threshold", d(3, dt=BOOL), d(3, dt=BOOL), 1, 2), "DTYPE"),
+                       (("elu", d(3, dt=BF16), d(3), 1.0), "DTYPE"), (("elu", d(4), d(3), 1.0), "SHAPE"), (("logit", d(3, dt=I64), d(3, dt=I64)), "DTYPE")]:
+        with pytest.raises(B.TxError) as e:
+            B.tx_unary_param(*args)
+        assert e.value.kind == kind, args
+    x = I.typed((40, 30), F32, seed=193)
+    dx = x.cuda()
+    B.tx_unary_param("elu", dx, dx, 1.5)                             # in place
+    assert_ulp(dx, O.unary_param("elu", x, 1.5), 2, "elu in place")
+
+
+def check_ternary(op, a_cpu, b_cpu, c_cpu, value=1, what=""):
+    try:
+        want = O.ternary(op, a_cpu, b_cpu, c_cpu, value)
+    except O.OracleError as e:
+        with pytest.raises(B.TxError) as g:
+            B.tx_ternary(op, torch.empty(a_cpu.shape, dtype=a_cpu.dtype, device="cuda"), to_device_view(a_cpu), to_device_view(b_cpu),
+                         None if c_cpu is None else to_device_view(c_cpu), value)
+        assert g.value.kind.lower() == e.kind, (op, g.value.kind, e.kind)
+        return None
+    a, b = to_device_view(a_cpu), to_device_view(b_cpu)
+    c = None if c_cpu is None else to_device_view(c_cpu)
+    assert B.tx_infer_ternary_dtype(op, a, b, c) == want.dtype
+    out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
+    B.tx_ternary(op, out, a, b, c, value)
+    used = B.tx_last_path()
+    sync()
+    what = "%s %s,%s,%s %s value=%s %s [%s]" % (op, a_cpu.dtype, b_cpu.dtype, None if c_cpu is None else c_cpu.dtype, tuple(want.shape), value, what, used)
+    if not want.dtype.is_floating_point:
+        assert_exact(out, want, what)
+    elif want.dtype == F32:
+        assert_ulp(out, want, 2, what)
+    else:
+        # half results: the terms are rounded separately; what the sum was made of sets the scale
+        ad, bd = a_cpu.double(), b_cpu.double()
+        cd = c_cpu.double() if c_cpu is not None else torch.tensor(float(value), dtype=torch.float64)
+        scale = ad.abs() + (bd.abs() if op == "lerp" else (float(value) * bd * cd).abs() if op == "addcmul" else (float(value) * bd / cd).abs())
+        scale = torch.where(scale.isfinite(), scale, torch.zeros_like(scale)).expand(want.shape)
+        assert_rel(out, want, 1e-2, scale=scale, what=what, overflow_max=HALF_MAX[want.dtype])
+    return used
+
+
+@pytest.mark.parametrize("op", ["addcmul", "addcdiv", "lerp"])
+def test_ternary_sweep(op):
+    for dt, kind in itertools.product(ALL, ["contig", "transposed", "step2_inner", "expand_col"]):
+        a = I.make_view((7, 13, 5), dt, kind, seed=194, specials=0.01)
+        b = I.make_view((7, 13, 5), dt, "contig", seed=195, specials=0.01)
+        c = I.make_view((7, 13, 5), dt, "contig", seed=196, specials=0.01)
+        if op == "lerp" and dt.is_floating_point:
+            c = (c * 0.2 + 0.5).to(dt)
+        for value in (1, -3, 0.375):
+            check_ternary(op, a, b, c, value, what=kind)
+        check_ternary(op, b, c, a, 2, what="rot-" + kind)
+    for da, db, dc in [(F32, I64, BF16), (I32, I64, I32), (BF16, F16, BF16), (BOOL, I32, I32), (F16, F16, F32), (I64, BOOL, F32)]:
+        a, b, c = I.typed((33, 20), da, seed=197), I.typed((33, 20), db, seed=198), I.typed((33, 20), dc, seed=199)
+        check_ternary(op, a, b, c, 2, what="mixed")
+    a, b, c = I.typed((6, 1, 9), F32, seed=200), I.typed((5, 1), F32, seed=201), I.typed((9,), F32, seed=202) + 4
+    check_ternary(op, a, b, c, -1.25, what="broadcast")
+    check_ternary(op, I.typed((), F32, seed=203), b, c, 0.5, what="0-dim a")
+    check_ternary(op, I.typed((0, 4), F32, seed=204), I.typed((0, 4), F32, seed=205), I.typed((4,), F32, seed=206) + 3, 1, what="empty")
+    if op == "lerp":
+        for w in (0.0, 1.0, 0.3, 0.5, -0.7, 1.9):
+            for dt in (F32, BF16, F16):
+                check_ternary(op, I.typed((64, 300), dt, seed=207), I.typed((64, 300), dt, seed=208), None, w, what="scalar weight")
+    x, y, z = I.typed((4096, 4096), F32, seed=209, specials=0.01), I.typed((4096, 4096), F32, seed=210, specials=0.01), I.typed((4096, 4096), F32, seed=211)
+    assert check_ternary(op, x, y, (z * 0.2 + 0.5) if op == "lerp" else z, 0.5, what="full") == "vec"
+    d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
+    with pytest.raises(B.TxError) as e:
+        B.tx_ternary(op, d(3), d(3), d(4), d(3))
+    assert e.value.kind == "SHAPE"
+    with pytest.raises(B.TxError) as e:
+        B.tx_ternary("fma", d(3), d(3), d(3), d(3))
+    assert e.value.kind == "SCALAR"
