@@ -1024,6 +1024,106 @@ int orc_ternary(int op, const orc_tensor* out, const orc_tensor* a, const orc_te
   return ORC_OK;
 }
 
+// ===========================================================================
+// Shape manipulation with data movement (Table 1 "Shape Manipulation"): copy with conversion, flip, roll, tril / triu
+// ===========================================================================
+// One element converted to out's dtype and stored.  Between floating dtypes: the value, rounded once.  Integer or
+// bool to floating: through binary32, nearest-even.  Floating to integer: truncated toward zero (values outside the
+// target range, and NaN, are outside the contract).  Anything to bool: value != 0.  int64 to int32 wraps.  The same
+// dtype on both sides copies the bits.
+static void convert_element(const orc_tensor* out, int64_t oo, const orc_tensor* x, int64_t xo) {
+  if (out->dtype == x->dtype) {
+    std::memcpy(mptr(out, oo), cptr(x, xo), esize(x->dtype));
+  } else if (is_float(x->dtype)) {
+    const double v = load_flt(x, xo);
+    if (is_float(out->dtype)) store_flt(out, oo, v);
+    else if (out->dtype == ORC_BOOL) store_int(out, oo, v != 0.0);
+    else store_int(out, oo, (int64_t)v);
+  } else {
+    const int64_t v = load_int(x, xo);
+    if (is_float(out->dtype)) store_flt(out, oo, (double)(float)v);
+    else store_int(out, oo, v);
+  }
+}
+
+// out = x broadcast to out's shape, converted to out's dtype (clone, contiguous, to, expand made real, copy_)
+int orc_copy(const orc_tensor* out, const orc_tensor* x) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  const orc_tensor* ops[2] = {out, x};
+  int nd;
+  int64_t sizes[ORC_MAX_DIMS];
+  if ((rc = broadcast_shapes(ops, 2, &nd, sizes))) return rc;
+  if (!same_shape(out, nd, sizes)) return ORC_ERR_SHAPE;          // x may be broadcast, out may not
+  const int64_t n = numel(out);
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < n; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, sizes, idx);
+    convert_element(out, offset_of(out, idx), x, bcast_offset(x, nd, idx));
+  }
+  return ORC_OK;
+}
+
+// out[i] = x[j]: along every dim listed in `dims`, j = size - 1 - i (flip, how = 0), or j = (i - shift) mod size
+// (roll, how = 1: the element at j moves to j + shift); other coordinates are equal.  Same shape and dtype; a dim
+// listed twice is ORC_ERR_DIM for flip, and shifts add up for roll.
+int orc_flip_roll(int how, const orc_tensor* out, const orc_tensor* x, const int64_t* dims, const int64_t* shifts, int32_t n) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  if (out->dtype != x->dtype) return ORC_ERR_DTYPE;
+  if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  const int nd = x->ndim;
+  bool flip[ORC_MAX_DIMS] = {false};
+  int64_t shift[ORC_MAX_DIMS] = {0};
+  for (int i = 0; i < n; ++i) {
+    int64_t d = dims[i];
+    const int lim = nd == 0 ? 1 : nd;
+    if (d < -lim || d >= lim) return ORC_ERR_DIM;
+    if (d < 0) d += lim;
+    if (nd == 0) continue;                              // a 0-dim tensor has nothing to move
+    if (how == 0) {
+      if (flip[d]) return ORC_ERR_DIM;
+      flip[d] = true;
+    } else if (x->sizes[d] > 0) {
+      shift[d] = ((shift[d] + shifts[i]) % x->sizes[d] + x->sizes[d]) % x->sizes[d];
+    }
+  }
+  const int64_t total = numel(out);
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < total; ++lin) {
+    int64_t idx[ORC_MAX_DIMS], src[ORC_MAX_DIMS];
+    unravel(lin, nd, out->sizes, idx);
+    for (int d = 0; d < nd; ++d)
+      src[d] = flip[d] ? x->sizes[d] - 1 - idx[d] : ((idx[d] - shift[d]) % x->sizes[d] + x->sizes[d]) % x->sizes[d];
+    std::memcpy(mptr(out, offset_of(out, idx)), cptr(x, offset_of(x, src)), esize(x->dtype));
+  }
+  return ORC_OK;
+}
+
+// tril (upper = 0): out[..., i, j] = x[..., i, j] where j - i <= diagonal, else 0; triu (upper != 0): where
+// j - i >= diagonal.  At least two dims; same shape and dtype.
+int orc_tri(const orc_tensor* out, const orc_tensor* x, int64_t diagonal, int upper) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(x))) return rc;
+  if (out->dtype != x->dtype) return ORC_ERR_DTYPE;
+  if (x->ndim < 2) return ORC_ERR_NDIM;
+  if (!same_shape(out, x->ndim, x->sizes)) return ORC_ERR_SHAPE;
+  const int nd = x->ndim;
+  const int64_t total = numel(out);
+#pragma omp parallel for schedule(static)
+  for (int64_t lin = 0; lin < total; ++lin) {
+    int64_t idx[ORC_MAX_DIMS];
+    unravel(lin, nd, out->sizes, idx);
+    const int64_t off = idx[nd - 1] - idx[nd - 2];
+    const bool keep = upper ? off >= diagonal : off <= diagonal;
+    char* dst = mptr(out, offset_of(out, idx));
+    if (keep) std::memcpy(dst, cptr(x, offset_of(x, idx)), esize(x->dtype));
+    else std::memset(dst, 0, esize(x->dtype));
+  }
+  return ORC_OK;
+}
+
 // where(cond, x, y): cond must be bool; result dtype = promotion of x and y;
 // all three broadcast together.  The selected element is converted to the
 // result dtype; when no conversion is needed its bits are copied unchanged.

@@ -72,6 +72,9 @@ def lib():
         _lib.orc_cumsum.argtypes = [P, P, ctypes.c_int64]
         _lib.orc_layer_norm.argtypes = [P, P, ctypes.c_int32, P, P, ctypes.c_double]
         _lib.orc_bce.argtypes = [P, P, P, P, ctypes.c_int]
+        _lib.orc_copy.argtypes = [P, P]
+        _lib.orc_flip_roll.argtypes = [ctypes.c_int, P, P, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), ctypes.c_int32]
+        _lib.orc_tri.argtypes = [P, P, ctypes.c_int64, ctypes.c_int]
         _lib.orc_unary_param.argtypes = [ctypes.c_int, P, P, ctypes.c_double, ctypes.c_double, ctypes.c_double]
         _lib.orc_ternary_result_dtype.argtypes = [ctypes.c_int, P, P, P]
         _lib.orc_ternary.argtypes = [ctypes.c_int, P, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
@@ -199,6 +202,48 @@ def ternary(op, a, b, c=None, value=1, out=None):
         out = torch.empty(shape, dtype=CODE_DTYPE[rc])
     vf, vi, isint = _scalar(value)
     _check(lib().orc_ternary(TERNARY.get(op, 99), desc(out), desc(a), desc(b), _opt(c), vf, vi, isint))
+    return out
+
+
+def copy(x, out=None, dtype=None, shape=None):
+    """x broadcast to `shape` (default: its own) and converted to `dtype` (default: its own), or into `out`."""
+    if out is None:
+        out = torch.empty(x.shape if shape is None else shape, dtype=dtype or x.dtype)
+    _check(lib().orc_copy(desc(out), desc(x)))
+    return out
+
+
+def _i64(values):
+    values = list(values)
+    return (ctypes.c_int64 * max(1, len(values)))(*values), len(values)
+
+
+def flip(x, dims, out=None):
+    out = torch.empty(x.shape, dtype=x.dtype) if out is None else out
+    d, n = _i64(dims)
+    _check(lib().orc_flip_roll(0, desc(out), desc(x), d, d, n))
+    return out
+
+
+def roll(x, shifts, dims, out=None):
+    out = torch.empty(x.shape, dtype=x.dtype) if out is None else out
+    d, n = _i64(dims)
+    sh, m = _i64(shifts)
+    if n != m:
+        raise OracleError(-4)
+    _check(lib().orc_flip_roll(1, desc(out), desc(x), d, sh, n))
+    return out
+
+
+def tril(x, diagonal=0, out=None):
+    out = torch.empty(x.shape, dtype=x.dtype) if out is None else out
+    _check(lib().orc_tri(desc(out), desc(x), diagonal, 0))
+    return out
+
+
+def triu(x, diagonal=0, out=None):
+    out = torch.empty(x.shape, dtype=x.dtype) if out is None else out
+    _check(lib().orc_tri(desc(out), desc(x), diagonal, 1))
     return out
 
 
