@@ -90,6 +90,14 @@ def build_ops(torch, B):
     add("add_f32_transposed", "a5", "ew_tile_kernel", n2 * 12, n2, lambda: B.tx_add(of, xf.t(), yf, 1))
     add("mul_bf16_transposed", "a5", "ew_tile_kernel", n2 * 6, n2, lambda: B.tx_binary("mul", ob, xb.t(), xb))
 
+    # data-moving shape operators, timed outside the step
+    extra("copy_f32_contiguous", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_copy(of, xf))
+    extra("copy_f32_to_bf16", "f1", "ew_vec_kernel", n2 * 6, n2, lambda: B.tx_copy(ob, xf))
+    extra("copy_f32_transposed", "f1", "ew_tile_kernel", n2 * 8, n2, lambda: B.tx_copy(of, xf.t()))
+    extra("flip_f32_dim0", "f1", "remap_copy_kernel", n2 * 8, n2, lambda: B.tx_flip(of, xf, [0]))
+    extra("flip_f32_dim1", "f1", "remap_copy_kernel", n2 * 8, n2, lambda: B.tx_flip(of, xf, [1]))
+    extra("roll_f32_dim0", "f1", "remap_copy_kernel", n2 * 8, n2, lambda: B.tx_roll(of, xf, [1234], [0]))
+    extra("tril_f32", "f1", "remap_copy_kernel", n2 * 8, n2, lambda: B.tx_tri(of, xf, 0, False))
     # second batch of elementwise operators (same iterator paths), timed outside the step
     extra("sub_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_sub(of, xf, yf, 1))
     extra("minimum_f32", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_binary("minimum", of, xf, yf))

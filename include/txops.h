@@ -487,6 +487,31 @@ tx_status tx_nonzero(const tx_tensor* out, const tx_tensor* count, const tx_tens
                      void* stream);
 size_t tx_nonzero_workspace_bytes(const tx_tensor* out, const tx_tensor* count, const tx_tensor* x);
 
+/* ------------------------------------------------------------------ shape manipulation
+ * (Table 1 "Shape Manipulation": views are the caller's business - a
+ * descriptor with other sizes and strides - these are the members that move
+ * data.)
+ *
+ * tx_copy: out = x broadcast to out's shape and converted to out's dtype (clone,
+ *   contiguous, to, an expand made real, copy_; cat and stack are copies into
+ *   slices of out).  Floating to floating: one rounding.  bool / integer to
+ *   floating: through fp32, nearest-even.  Floating to integer: truncated
+ *   toward zero (NaN and values outside the target range are outside the
+ *   contract).  Anything to bool: value != 0.  int64 to int32 wraps.  Equal
+ *   dtypes copy the bits.  out may alias x exactly.
+ * tx_flip: out[i] = x[j] with j = size - 1 - i along every listed dim (a dim
+ *   listed twice is TX_ERR_DIM).
+ * tx_roll: the element at j moves to (j + shift) mod size along every listed
+ *   dim; n shifts for n dims; a dim listed twice adds its shifts.
+ * tx_tri: upper == 0 tril: out[..., i, j] = x[..., i, j] where j - i <=
+ *   diagonal, else 0; upper != 0 triu: where j - i >= diagonal.  At least two
+ *   dims (TX_ERR_NDIM).
+ * flip / roll / tri: out has x's shape and dtype and may not alias x. */
+tx_status tx_copy(const tx_tensor* out, const tx_tensor* x, void* stream);
+tx_status tx_flip(const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims, void* stream);
+tx_status tx_roll(const tx_tensor* out, const tx_tensor* x, const int64_t* shifts, const int64_t* dims, int32_t n, void* stream);
+tx_status tx_tri(const tx_tensor* out, const tx_tensor* x, int64_t diagonal, int upper, void* stream);
+
 /* ------------------------------------------------------------------ host-only helpers */
 
 /* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_SHIFT_RIGHT). */

@@ -40,7 +40,7 @@ EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_cl
            "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_scan", "tx_scan_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
            "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_masked_select",
-           "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_infer_where", "tx_infer_unary_dtype", "tx_unary_param", "tx_infer_unary_param_dtype", "tx_ternary", "tx_infer_ternary_dtype",
+           "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_copy", "tx_flip", "tx_roll", "tx_tri", "tx_infer_where", "tx_infer_unary_dtype", "tx_unary_param", "tx_infer_unary_param_dtype", "tx_ternary", "tx_infer_ternary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
 
 
@@ -114,6 +114,10 @@ def lib():
         "tx_infer_binary": ([ctypes.c_int, P, P, I32P, I32P, I64P], ctypes.c_int32),
         "tx_infer_where": ([P, P, I32P], ctypes.c_int32),
         "tx_infer_unary_dtype": ([ctypes.c_int, ctypes.c_int32], ctypes.c_int32),
+        "tx_copy": ([P, P, V], ctypes.c_int32),
+        "tx_flip": ([P, P, ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, V], ctypes.c_int32),
+        "tx_roll": ([P, P, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), ctypes.c_int32, V], ctypes.c_int32),
+        "tx_tri": ([P, P, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_unary_param": ([ctypes.c_int, P, P, ctypes.c_double, ctypes.c_double, ctypes.c_double, V], ctypes.c_int32),
         "tx_infer_unary_param_dtype": ([ctypes.c_int, ctypes.c_int32], ctypes.c_int32),
         "tx_ternary": ([ctypes.c_int, P, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
@@ -420,6 +424,32 @@ def tx_infer_ternary_dtype(op, a, b, c=None):
 def tx_ternary(op, out, a, b, c=None, value=1, stream=None):
     vf, vi, isint = _scalar(value)
     _check(lib().tx_ternary(TERNARY.get(op, 99), desc(out), desc(a), desc(b), _opt(c), vf, vi, isint, _stream(stream)))
+
+
+def _i64_list(values):
+    values = list(values)
+    return (ctypes.c_int64 * max(1, len(values)))(*values), len(values)
+
+
+def tx_copy(out, x, stream=None):
+    _check(lib().tx_copy(desc(out), desc(x), _stream(stream)))
+
+
+def tx_flip(out, x, dims, stream=None):
+    d, n = _i64_list(dims)
+    _check(lib().tx_flip(desc(out), desc(x), d, n, _stream(stream)))
+
+
+def tx_roll(out, x, shifts, dims, stream=None):
+    d, n = _i64_list(dims)
+    sh, m = _i64_list(shifts)
+    if n != m:
+        raise ValueError("roll: one shift per dim")
+    _check(lib().tx_roll(desc(out), desc(x), sh, d, n, _stream(stream)))
+
+
+def tx_tri(out, x, diagonal=0, upper=False, stream=None):
+    _check(lib().tx_tri(desc(out), desc(x), diagonal, int(bool(upper)), _stream(stream)))
 
 
 def tx_infer_reduce(op, x, dims=None, keepdim=False):

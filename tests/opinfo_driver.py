@@ -94,6 +94,18 @@ class OracleBackend:
     def unary_param(self, op, x, *params):
         return self.O.unary_param(op, x, *params)
 
+    def copy(self, x, dtype=None, out=None):
+        return self.O.copy(x, dtype=dtype, out=out)
+
+    def remap(self, op, x, *args):
+        return getattr(self.O, op)(x, *args)
+
+    def empty(self, shape, dtype):
+        return torch.empty(shape, dtype=dtype)
+
+    def host(self, t):
+        return t
+
     def ternary(self, op, a, b, c, value):
         return self.O.ternary(op, a, b, c, value)
 
@@ -203,6 +215,28 @@ class LibraryBackend:
         out = self._out(x.shape, x.dtype if x.dtype.is_floating_point else I64)
         self.B.tx_cumsum(out, dx, dim, self._ws(self.B.tx_cumsum_workspace_bytes(out, dx, dim)))
         return out.cpu()
+
+    def copy(self, x, dtype=None, out=None):
+        if out is None:
+            out = self._out(x.shape, dtype or x.dtype)
+        self.B.tx_copy(out, self.dev(x) if x.device.type == "cpu" else x)
+        return out.cpu() if out.device.type != "cpu" and not getattr(out, "_keep", False) else out
+
+    def remap(self, op, x, *args):
+        out = self._out(x.shape, x.dtype)
+        if op == "flip":
+            self.B.tx_flip(out, self.dev(x), *args)
+        elif op == "roll":
+            self.B.tx_roll(out, self.dev(x), *args)
+        else:
+            self.B.tx_tri(out, self.dev(x), args[0], op == "triu")
+        return out.cpu()
+
+    def empty(self, shape, dtype):
+        return self._out(shape, dtype)
+
+    def host(self, t):
+        return t.cpu()
 
     def unary_param(self, op, x, *params):
         out = self._out(x.shape, self.B.tx_infer_unary_param_dtype(op, x.dtype))
@@ -581,6 +615,84 @@ def lerp(be, s):
     return be.ternary("lerp", a, b, None, _scalar(w))
 
 
+def clone(be, s):
+    _no_kwargs(s)
+    if s.args:
+        raise Unsupported("arguments")
+    return be.copy(_tensor_ok(s.input))
+
+
+def flip(dims=None):
+    def run(be, s):
+        _no_kwargs(s, ("dims",))
+        d = dims if dims is not None else (s.args[0] if s.args else s.kwargs["dims"])
+        return be.remap("flip", _tensor_ok(s.input), list(d))
+    return run
+
+
+def roll(be, s):
+    kw = dict(zip(("shifts", "dims"), s.args))
+    kw.update(s.kwargs)
+    _no_kwargs(types.SimpleNamespace(kwargs=kw), ("shifts", "dims"))
+    if kw.get("dims") is None:
+        raise Unsupported("roll of the flattened tensor")
+    sh, d = kw["shifts"], kw["dims"]
+    return be.remap("roll", _tensor_ok(s.input), [sh] if isinstance(sh, int) else list(sh), [d] if isinstance(d, int) else list(d))
+
+
+def tri(op):
+    def run(be, s):
+        _no_kwargs(s, ("diagonal",))
+        k = s.args[0] if s.args else s.kwargs.get("diagonal", 0)
+        return be.remap(op, _tensor_ok(s.input), int(k))
+    return run
+
+
+def concatenate(stack):
+    """cat / stack: the result is allocated and every input is copied into its slice of it (the slices are views,
+    descriptors with other offsets and strides), converting to the promoted dtype on the way."""
+    def run(be, s):
+        _no_kwargs(s, ("dim",))
+        tensors = [_tensor_ok(t) for t in s.input]
+        dim = s.args[0] if s.args else s.kwargs.get("dim", 0)
+        if stack:
+            tensors = [t.unsqueeze(dim if dim >= 0 else dim + t.dim() + 1) for t in tensors]
+        if not stack and any(t.dim() == 1 and t.numel() == 0 for t in tensors) and any(t.dim() > 1 for t in tensors):
+            raise Unsupported("legacy empty operand")
+        nd = tensors[0].dim()
+        dim = dim if dim >= 0 else dim + nd
+        shape = list(tensors[0].shape)
+        shape[dim] = sum(t.shape[dim] for t in tensors)
+        dtype = tensors[0].dtype
+        for t in tensors[1:]:
+            dtype = torch.promote_types(dtype, t.dtype)
+        if dtype not in DTYPES:
+            raise Unsupported("dtype %s" % dtype)
+        out = be.empty(shape, dtype)
+        at = 0
+        for t in tensors:
+            piece = out.narrow(dim, at, t.shape[dim])
+            piece._keep = True
+            if t.numel():
+                be.copy(t, out=piece)
+            at += t.shape[dim]
+        return be.host(out)
+    return run
+
+
+def view_then_copy(be, s, op):
+    """A view operator: the view is a descriptor (sizes, strides, offset) that the caller builds - here ATen builds
+    it on the host - and the library's part is materialising it with tx_copy."""
+    v = op.op(_tensor_ok(s.input), *s.args, **s.kwargs)
+    if not isinstance(v, torch.Tensor):
+        raise Unsupported("not a single tensor")
+    return be.copy(_tensor_ok(v))
+
+
+VIEW_OPS = ("expand", "expand_as", "broadcast_to", "permute", "transpose", "t", "movedim", "narrow", "select", "squeeze", "unsqueeze",
+            "flatten", "reshape", "view", "diagonal", "unfold", "as_strided", "T", "mT")
+
+
 def vector_norm(be, s):
     kw = dict(s.kwargs)
     args = list(s.args)
@@ -654,9 +766,14 @@ ADAPTERS = {
     "nn.functional.softshrink": activation("softshrink", ("lambd",), (0.5,)), "logit": logit, "nan_to_num": nan_to_num,
     "nn.functional.hardtanh": hardtanh(-1.0, 1.0), "nn.functional.relu6": hardtanh(0.0, 6.0),
     "addcmul": ternary("addcmul"), "addcdiv": ternary("addcdiv"), "lerp": lerp,
+    "clone": clone, "contiguous": clone, "flip": flip(), "fliplr": flip([1]), "flipud": flip([0]), "roll": roll,
+    "tril": tri("tril"), "triu": tri("triu"), "cat": concatenate(False), "stack": concatenate(True),
     "nn.functional.mse_loss": regression_loss("mse"), "nn.functional.l1_loss": regression_loss("l1"),
     "nn.functional.smooth_l1_loss": regression_loss("smooth_l1", "beta"), "nn.functional.huber_loss": regression_loss("huber", "delta"),
 }
+
+
+ADAPTERS.update({name: view_then_copy for name in VIEW_OPS})
 
 
 def compare(got, want):
@@ -720,7 +837,7 @@ def sweep(backend, names=None, db=None):
                         rec["unsupported"]["ATen raised"] = rec["unsupported"].get("ATen raised", 0) + 1
                         continue
                     try:
-                        got = adapter(backend, s)
+                        got = view_then_copy(backend, s, op) if adapter is view_then_copy else adapter(backend, s)
                     except Unsupported as e:
                         key = str(e)
                         rec["unsupported"][key] = rec["unsupported"].get(key, 0) + 1
