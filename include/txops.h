@@ -155,9 +155,15 @@ tx_status tx_unary(int op, const tx_tensor* out, const tx_tensor* a, void* strea
  *                            [eps, 1 - eps] when eps is given; bool / integer a
  *                            computes and returns fp32
  *   NAN_TO_NUM(p0, p1, p2)   NaN, +inf, -inf replaced by the parameters rounded
- *                            to the dtype; bool / integer a is copied */
+ *                            to the dtype; bool / integer a is copied
+ *   ROUND_DECIMALS(p0 = d)   d > 0: rint(x * 10^d) / 10^d; d < 0: rint(x / 10^-d)
+ *                            * 10^-d; every step in fp32 (that arithmetic is the
+ *                            operator's definition); d must be an integer with
+ *                            |d| <= 38 (TX_ERR_SCALAR); floating dtypes only
+ *   GELU_TANH                x (1 + tanh u) / 2, u = sqrt(2/pi)(x + 0.044715 x^3),
+ *                            evaluated as x / (1 + exp(-2u)); floating dtypes only */
 enum { TX_LEAKY_RELU = 0, TX_ELU, TX_CELU, TX_SELU, TX_SOFTPLUS, TX_THRESHOLD, TX_HARDSHRINK, TX_SOFTSHRINK, TX_LOGIT,
-       TX_NAN_TO_NUM };
+       TX_NAN_TO_NUM, TX_ROUND_DECIMALS, TX_GELU_TANH };
 tx_status tx_unary_param(int op, const tx_tensor* out, const tx_tensor* a, double p0, double p1, double p2, void* stream);
 int32_t tx_infer_unary_param_dtype(int op, int32_t in_dtype);
 

@@ -80,7 +80,7 @@ enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM,
        ORC_ATAN2, ORC_FMOD, ORC_REMAINDER, ORC_HYPOT, ORC_COPYSIGN, ORC_LOGADDEXP, ORC_LOGADDEXP2, ORC_XLOGY, ORC_HEAVISIDE,
        ORC_FMAX, ORC_FMIN, ORC_NEXTAFTER, ORC_GCD, ORC_LCM, ORC_SHIFT_LEFT, ORC_SHIFT_RIGHT };
 enum { ORC_LEAKY_RELU = 0, ORC_ELU, ORC_CELU, ORC_SELU, ORC_SOFTPLUS, ORC_THRESHOLD, ORC_HARDSHRINK, ORC_SOFTSHRINK, ORC_LOGIT,
-       ORC_NAN_TO_NUM };
+       ORC_NAN_TO_NUM, ORC_ROUND_DECIMALS, ORC_GELU_TANH };
 enum { ORC_ADDCMUL = 0, ORC_ADDCDIV, ORC_LERP };
 enum { ORC_SUM = 0, ORC_MEAN, ORC_AMAX, ORC_ARGMAX, ORC_PROD, ORC_VAR, ORC_AMIN, ORC_ARGMIN, ORC_STD, ORC_ANY, ORC_ALL,
        ORC_LOGSUMEXP, ORC_NANSUM, ORC_NANMEAN, ORC_COUNT_NONZERO, ORC_NORM };
@@ -900,10 +900,17 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
 //                             eps : x > 1 - eps ? 1 - eps : x); bool / integer input computes in fp32
 //   nan_to_num(p0 = nan, p1 = posinf, p2 = neginf) : replaces NaN, +inf, -inf by the parameters rounded to the dtype;
 //                             integers and bools are returned as they are
+//   round_decimals(p0 = d, an integer) : d > 0: rint(x * 10^d) / 10^d; d < 0: rint(x / 10^-d) * 10^-d; d = 0: rint(x);
+//                             halves to even.  The operator is defined by this arithmetic in binary32 (10^|d| rounded
+//                             to binary32, each product and quotient rounded to binary32), so it is evaluated that
+//                             way here; floating dtypes only
+//   gelu_tanh               : x / (1 + exp(-2u)), u = sqrt(2/pi) (x + 0.044715 x^3), which is the tanh form
+//                             x (1 + tanh u) / 2 written without the cancellation at negative u; floating dtypes only
 int orc_unary_param_result_dtype(int op, int in_dtype) {
   if (!valid_dtype(in_dtype)) return ORC_ERR_DTYPE;
   switch (op) {
     case ORC_LEAKY_RELU: case ORC_ELU: case ORC_CELU: case ORC_SELU: case ORC_SOFTPLUS: case ORC_HARDSHRINK: case ORC_SOFTSHRINK:
+    case ORC_ROUND_DECIMALS: case ORC_GELU_TANH:
       return is_float(in_dtype) ? in_dtype : ORC_ERR_DTYPE;
     case ORC_THRESHOLD: return in_dtype == ORC_BOOL ? ORC_ERR_DTYPE : in_dtype;
     case ORC_LOGIT: return is_float(in_dtype) ? in_dtype : ORC_F32;
@@ -921,6 +928,8 @@ int orc_unary_param(int op, const orc_tensor* out, const orc_tensor* a, double p
   if (!same_shape(out, a->ndim, a->sizes)) return ORC_ERR_SHAPE;
   if (op == ORC_CELU && p0 == 0.0) return ORC_ERR_SCALAR;
   if (op == ORC_SOFTSHRINK && !(p0 >= 0.0)) return ORC_ERR_SCALAR;
+  if (op == ORC_ROUND_DECIMALS && (p0 != std::trunc(p0) || std::fabs(p0) > 38.0)) return ORC_ERR_SCALAR;
+  const float ten_pow = (float)std::pow(10.0, std::fabs(p0));       // round_decimals: 10^|d| in binary32
   const int64_t n = numel(out);
   const int nd = a->ndim;
   const double selu_scale = 1.0507009873554804934193349852946, selu_alpha = 1.6732632423543772848170429916717;
@@ -957,6 +966,18 @@ int orc_unary_param(int op, const orc_tensor* out, const orc_tensor* a, double p
         break;
       }
       case ORC_NAN_TO_NUM: y = std::isnan(x) ? p0 : (std::isinf(x) ? (x > 0.0 ? p1 : p2) : x); break;
+      case ORC_ROUND_DECIMALS: {
+        const float xf = (float)x;
+        if (p0 == 0.0) y = std::nearbyint(xf);
+        else if (p0 > 0.0) { const float t = xf * ten_pow; y = std::nearbyint(t) / ten_pow; y = (double)(float)y; }
+        else { const float t = xf / ten_pow; y = (double)(float)(std::nearbyint(t) * ten_pow); }
+        break;
+      }
+      case ORC_GELU_TANH: {
+        const double u = 0.79788456080286535588 * (x + 0.044715 * x * x * x);
+        y = x / (1.0 + std::exp(-2.0 * u));
+        break;
+      }
     }
     put_flt(out, oo, rd, y);
   }

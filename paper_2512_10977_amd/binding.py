@@ -401,7 +401,7 @@ def tx_infer_unary_dtype(op, dtype):
 
 
 UNARY_PARAM = {"leaky_relu": 0, "elu": 1, "celu": 2, "selu": 3, "softplus": 4, "threshold": 5, "hardshrink": 6, "softshrink": 7,
-               "logit": 8, "nan_to_num": 9}
+               "logit": 8, "nan_to_num": 9, "round_decimals": 10, "gelu_tanh": 11}
 TERNARY = {"addcmul": 0, "addcdiv": 1, "lerp": 2}
 
 

@@ -57,6 +57,19 @@ __device__ __forceinline__ float param_op_f32(const Params& a, float xf) {
       else y = log_d(z / (1.0 - z));
       break;
     }
+    case TX_ROUND_DECIMALS: {                                         // fp32 arithmetic by definition; p1 holds 10^|d| in fp32
+      const float tp = (float)a.p1;
+      if (a.p0 == 0.0) return __builtin_rintf(xf);
+      return a.p0 > 0.0 ? __builtin_rintf(xf * tp) / tp : __builtin_rintf(xf / tp) * tp;
+    }
+    case TX_GELU_TANH: {
+      if (x != x) return xf;
+      const double u = 0.79788456080286535588 * (x + 0.044715 * x * x * x);
+      const double t = -2.0 * u;
+      if (t > 700.0) return (float)(x * 0.0);                        // x / (1 + e^700): -0.0, or NaN for -inf
+      y = x * rcp_d(1.0 + exp_d(t < -700.0 ? -700.0 : t));
+      break;
+    }
     default: y = x != x ? a.p0 : (__builtin_fabs(x) == __builtin_inf() ? (x > 0.0 ? a.p1 : a.p2) : x); break;   // TX_NAN_TO_NUM
   }
   return (float)y;
@@ -89,6 +102,14 @@ __device__ __forceinline__ float param_op_half(const Params& a, float x) {
       float z = x;
       if (a.p1 != 0.0) z = z < p0 ? p0 : (z > 1.0f - p0 ? 1.0f - p0 : z);
       return logf(z / (1.0f - z));
+    }
+    case TX_ROUND_DECIMALS:
+      if (a.p0 == 0.0) return __builtin_rintf(x);
+      return a.p0 > 0.0 ? __builtin_rintf(x * p1) / p1 : __builtin_rintf(x / p1) * p1;
+    case TX_GELU_TANH: {
+      const float t = -1.5957691216f * (x + 0.044715f * x * x * x);            // -2u
+      if (t > 80.0f) return param_op_f32(a, x);                             // e^t nears fp32's range: the binary64 form keeps the tail
+      return x / (1.0f + __expf(t));
     }
     default: return x != x ? p0 : (__builtin_fabsf(x) == __builtin_inff() ? (x > 0.0f ? p1 : p2) : x);
   }
@@ -210,6 +231,7 @@ int32_t tx_infer_unary_param_dtype(int op, int32_t in) {
   if (!dtype_valid(in)) return fail(TX_ERR_DTYPE, "unary_param: dtype code %d", in);
   switch (op) {
     case TX_LEAKY_RELU: case TX_ELU: case TX_CELU: case TX_SELU: case TX_SOFTPLUS: case TX_HARDSHRINK: case TX_SOFTSHRINK:
+    case TX_ROUND_DECIMALS: case TX_GELU_TANH:
       if (!dtype_is_float(in)) return fail(TX_ERR_DTYPE, "this activation takes floating dtypes only");
       return in;
     case TX_THRESHOLD:
@@ -230,6 +252,8 @@ tx_status tx_unary_param(int op, const tx_tensor* out, const tx_tensor* a, doubl
   if (!same_sizes(out, a->ndim, a->sizes)) return fail(TX_ERR_SHAPE, "out does not have a's shape");
   if (op == TX_CELU && p0 == 0.0) return fail(TX_ERR_SCALAR, "celu: alpha must not be zero");
   if (op == TX_SOFTSHRINK && !(p0 >= 0.0)) return fail(TX_ERR_SCALAR, "softshrink: lambda must not be negative");
+  if (op == TX_ROUND_DECIMALS && (p0 != std::trunc(p0) || std::fabs(p0) > 38.0))
+    return fail(TX_ERR_SCALAR, "round: decimals must be an integer of magnitude at most 38");
   const tx_tensor* ins[1] = {a};
   if ((rc = check_out_overlap(out, ins, 1))) return rc;
   set_path("");
@@ -244,6 +268,7 @@ tx_status tx_unary_param(int op, const tx_tensor* out, const tx_tensor* a, doubl
   }
   Params pa{op, p0, p1, p2};
   if (op == TX_THRESHOLD) pa.p1 = (double)host_round_half(p1, rd);
+  if (op == TX_ROUND_DECIMALS) pa.p1 = (double)(float)std::pow(10.0, std::fabs(p0));
   if (op == TX_NAN_TO_NUM) { pa.p0 = (double)host_round_half(p0, rd); pa.p1 = (double)host_round_half(p1, rd); pa.p2 = (double)host_round_half(p2, rd); }
   if (a->dtype == rd) {
     if (rd == TX_F32) return launch_ew(it, ParamOpF32{pa}, s);

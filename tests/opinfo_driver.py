@@ -378,8 +378,10 @@ def unary(name):
 
 def gelu(be, s):
     _no_kwargs(s, ("approximate",))
-    if s.kwargs.get("approximate", "none") != "none" or s.args:
-        raise Unsupported("tanh approximation")
+    if s.args:
+        raise Unsupported("arguments")
+    if s.kwargs.get("approximate", "none") == "tanh":
+        return be.unary_param("gelu_tanh", _tensor_ok(s.input))
     return be.unary("gelu", _tensor_ok(s.input))
 
 
@@ -420,6 +422,12 @@ def masked_fill(be, s):
     return be.masked_fill(_tensor_ok(s.input), _tensor_ok(s.args[0]), _scalar(s.args[1]))
 
 
+def _convert_first(be, x, dtype):
+    if dtype not in DTYPES:
+        raise Unsupported("dtype %s" % dtype)
+    return x if dtype == x.dtype else be.copy(x, dtype=dtype)
+
+
 def reduction(name, variance=False, index=False):
     def run(be, s):
         kw = dict(s.kwargs)
@@ -442,6 +450,9 @@ def reduction(name, variance=False, index=False):
                 raise Unsupported("arguments")
         if variance and args:
             raise Unsupported("arguments")
+        want_dtype = kw.pop("dtype", None)
+        if want_dtype is not None:                                   # dtype=: the input is converted first
+            x = _convert_first(be, x, want_dtype)
         if set(kw) - {"dim", "keepdim"}:
             raise Unsupported("keyword %s" % sorted(set(kw) - {"dim", "keepdim"}))
         dim = kw.get("dim")
@@ -449,7 +460,9 @@ def reduction(name, variance=False, index=False):
             dim = list(dim)
             if index and len(dim) != 1:
                 raise Unsupported("several dims")
-        return be.reduce(name, x, dim, bool(kw.get("keepdim", False)), correction)
+        r = be.reduce(name, x, dim, bool(kw.get("keepdim", False)), correction)
+        # an integer dtype= narrower than the int64 accumulator: wrapping arithmetic commutes with the narrowing
+        return r if want_dtype is None or r.dtype == want_dtype else be.copy(r, dtype=want_dtype)
     return run
 
 
@@ -467,10 +480,15 @@ def cumsum(be, s):
 
 def scan(op):
     def run(be, s):
-        _no_kwargs(s)
+        _no_kwargs(s, ("dtype",))
         if len(s.args) != 1:
             raise Unsupported("arguments")
-        return be.scan(op, _tensor_ok(s.input), s.args[0])
+        x = _tensor_ok(s.input)
+        want_dtype = s.kwargs.get("dtype")
+        if want_dtype is not None:
+            x = _convert_first(be, x, want_dtype)
+        r = be.scan(op, x, s.args[0])
+        return r if want_dtype is None or r.dtype == want_dtype else be.copy(r, dtype=want_dtype)
     return run
 
 
@@ -615,6 +633,16 @@ def lerp(be, s):
     return be.ternary("lerp", a, b, None, _scalar(w))
 
 
+def round_(be, s):
+    _no_kwargs(s, ("decimals",))
+    if s.args:
+        raise Unsupported("arguments")
+    x = _tensor_ok(s.input)
+    if "decimals" in s.kwargs:
+        return be.unary_param("round_decimals", x, int(s.kwargs["decimals"]))
+    return be.unary("round", x)
+
+
 def clone(be, s):
     _no_kwargs(s)
     if s.args:
@@ -728,7 +756,7 @@ ADAPTERS = {
     "logical_not": unary("logical_not"), "nn.functional.logsigmoid": unary("logsigmoid"), "nn.functional.gelu": gelu,
     "sin": unary("sin"), "cos": unary("cos"), "exp2": unary("exp2"), "log2": unary("log2"), "log10": unary("log10"),
     "rsqrt": unary("rsqrt"), "reciprocal": unary("reciprocal"), "nn.functional.silu": unary("silu"), "square": unary("square"),
-    "sign": unary("sign"), "floor": unary("floor"), "ceil": unary("ceil"), "trunc": unary("trunc"), "round": unary("round"),
+    "sign": unary("sign"), "floor": unary("floor"), "ceil": unary("ceil"), "trunc": unary("trunc"), "round": round_,
     "isnan": unary("isnan"), "isinf": unary("isinf"), "isfinite": unary("isfinite"), "bitwise_not": unary("bitwise_not"),
     "bitwise_and": binary("bitwise_and"), "bitwise_or": binary("bitwise_or"), "bitwise_xor": binary("bitwise_xor"),
     "atan2": binary("atan2"),
@@ -753,7 +781,7 @@ ADAPTERS = {
     "all": reduction("all"), "logsumexp": reduction("logsumexp"),
     "nansum": reduction("nansum"), "nanmean": reduction("nanmean"), "count_nonzero": reduction("count_nonzero"),
     "linalg.vector_norm": vector_norm,
-    "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": cumsum, "cumprod": scan("cumprod"),
+    "softmax": softmax(False), "log_softmax": softmax(True), "cumsum": scan("cumsum"), "cumprod": scan("cumprod"),
     "logcumsumexp": scan("logcumsumexp"),
     "gather": gather, "index_select": index_select, "scatter_add": scatter_add, "index_add": index_add, "take": take,
     "masked_select": masked_select, "nonzero": nonzero, "scatter_reduce": scatter_reduce, "index_put": index_put,

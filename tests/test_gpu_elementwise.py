@@ -619,7 +619,7 @@ PARAM_OPS = [("leaky_relu", (0.01,)), ("leaky_relu", (-2.0,)), ("elu", (1.5,)), 
              ("selu", ()), ("softplus", (1.0, 20.0)), ("softplus", (2.0, 5.0)), ("softplus", (-1.0, 20.0)), ("threshold", (0.3, 9.0)),
              ("threshold", (1, 7)), ("hardshrink", (0.5,)), ("hardshrink", (-1.0,)), ("softshrink", (0.5,)), ("softshrink", (0.0,)),
              ("logit", ()), ("logit", (0.125, 1)), ("logit", (0.75, 1)), ("nan_to_num", (0.0, 3e38, -3e38)), ("nan_to_num", (1.0, 2.0, -3.0))]
-EXACT_PARAM = ("threshold", "hardshrink", "nan_to_num")
+EXACT_PARAM = ("threshold", "hardshrink", "nan_to_num", "round_decimals")
 
 
 def check_unary_param(op, params, a_cpu, what=""):
@@ -740,3 +740,14 @@ def test_ternary_sweep(op):
     with pytest.raises(B.TxError) as e:
         B.tx_ternary("fma", d(3), d(3), d(3), d(3))
     assert e.value.kind == "SCALAR"
+
+
+@pytest.mark.parametrize("op,params", [("round_decimals", (2,)), ("round_decimals", (-2,)), ("round_decimals", (0,)), ("gelu_tanh", ())])
+def test_round_decimals_and_gelu_tanh(op, params):
+    for dt, kind in itertools.product(ALL, I.VIEW_KINDS):
+        check_unary_param(op, params, I.make_view((7, 13, 5), dt, kind, seed=420, specials=0.02, std=300.0 if op == "round_decimals" else 3.0), what=kind)
+    x = I.typed((2048, 4096), F32, seed=421, specials=0.01, std=300.0 if op == "round_decimals" else 3.0)
+    assert check_unary_param(op, params, x) == "vec"
+    wide = torch.linspace(-30.0, 30.0, 1 << 20).view(1024, 1024)
+    check_unary_param(op, params, wide, what="wide range")
+    check_unary_param(op, params, I.typed((1024, 4096), BF16, seed=422, specials=0.01))

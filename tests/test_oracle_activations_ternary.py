@@ -175,3 +175,40 @@ def test_ternary_exact_and_against_aten():
     assert e.value.kind == "shape"
     sp = O.ternary("lerp", torch.tensor([1.0, 1.0, NAN]), torch.tensor([3.0, INF, 1.0]), torch.tensor([1.0, 0.0, 0.5])).tolist()
     assert sp[0] == 3.0 and math.isnan(sp[1]) and math.isnan(sp[2])                               # 0 * inf
+
+
+def test_round_decimals_and_gelu_tanh():
+    mpmath.mp.dps = 40
+    rng = random.Random(85)
+    # round(x, decimals): binary32 arithmetic is the definition; ATen's CPU operator follows the same steps
+    x = torch.tensor([f32(rng.uniform(-3000, 3000)) for _ in range(400)] + [1.2345, -2.5, 1250.0, 0.5, 15.0, 25.0, 0.125, -0.0, NAN, INF], dtype=F32)
+    for d in (0, 1, 2, 3, -1, -2, -3):
+        got = O.unary_param("round_decimals", x, d)
+        want = torch.round(x, decimals=d)
+        assert torch.equal(got.nan_to_num(7.0), want.nan_to_num(7.0)), d
+        assert torch.equal(O.unary_param("round_decimals", x.to(BF16), d).float().nan_to_num(7.0), torch.round(x.to(BF16), decimals=d).float().nan_to_num(7.0)), d
+    t = O.unary_param("round_decimals", torch.tensor([1.2345, -2.5, 1250.0, 0.125, 15.0, 25.0]), 2).tolist()
+    assert t == [f32(1.23), -2.5, 1250.0, f32(0.12), 15.0, 25.0]                                  # 12.5 -> 12: halves to even
+    assert O.unary_param("round_decimals", torch.tensor([15.0, 25.0, 35.0, -15.0]), -1).tolist() == [20.0, 20.0, 40.0, -20.0]
+    assert torch.equal(O.unary_param("round_decimals", x[:400], 0), O.unary("round", x[:400]))
+    for bad in (0.5, 39.0, NAN):
+        with pytest.raises(O.OracleError) as e:
+            O.unary_param("round_decimals", torch.ones(3), bad)
+        assert e.value.kind == "scalar"
+    with pytest.raises(O.OracleError) as e:
+        O.unary_param("round_decimals", torch.tensor([1, 2]), 1)
+    assert e.value.kind == "dtype"
+    # tanh gelu: x (1 + tanh u) / 2 at 40 digits; relative accuracy also deep in the negative tail
+    xs = [f32(rng.uniform(-9, 9)) for _ in range(300)] + [f32(-12.0), f32(-6.5), f32(1e-6), f32(-1e-6), f32(30.0)]
+    got = O.unary_param("gelu_tanh", torch.tensor(xs, dtype=F32)).tolist()
+    c = mpmath.sqrt(2 / mpmath.pi)
+    for v, g in zip(xs, got):
+        u = c * (mpmath.mpf(v) + mpmath.mpf("0.044715") * mpmath.mpf(v) ** 3)
+        close_half_ulp(g, mpmath.mpf(v) * (1 + mpmath.tanh(u)) / 2, (v, g))
+    sp = O.unary_param("gelu_tanh", torch.tensor([0.0, -0.0, INF, -INF, NAN, -100.0])).tolist()
+    assert sp[0] == 0.0 and sp[2] == INF and math.isnan(sp[3]) and math.isnan(sp[4]) and sp[5] == 0.0 and math.copysign(1, sp[5]) == -1
+    g = torch.Generator().manual_seed(86)
+    for dt in (F32, BF16, F16):
+        t = (torch.randn(500, generator=g) * 3).to(dt)
+        tol = 2e-6 if dt == F32 else 1e-2
+        assert torch.allclose(O.unary_param("gelu_tanh", t).double(), NF.gelu(t, approximate="tanh").double(), rtol=tol, atol=tol)
