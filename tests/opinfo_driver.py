@@ -536,6 +536,76 @@ def take(be, s):
     return be.take(_tensor_ok(s.input), _tensor_ok(s.args[0]))
 
 
+# Indexing operators that are another entry point seen through a view (a descriptor with permuted, sliced or flattened
+# sizes and strides): the view is built on the host, the data movement is the library's.
+def _front(t, dim):
+    return t.movedim(dim, 0) if t.dim() else t
+
+
+def index_copy(be, s):
+    _no_kwargs(s)
+    x, dim, index, src = _tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]), _tensor_ok(s.args[2])
+    if index.numel() != len(torch.unique(index)):
+        raise Unsupported("assignment with repeated destinations (no unique result)")
+    if x.dim() == 0:
+        return be.index_put(x.reshape(1), [index.reshape(-1)], src.reshape(-1), False).reshape(())
+    r = be.index_put(_front(x, dim), [index.reshape(-1)], _front(src, dim), False)
+    return r.movedim(0, dim)
+
+
+def index_fill(be, s):
+    _no_kwargs(s)
+    x, dim, index, value = _tensor_ok(s.input), s.args[0], _tensor_ok(s.args[1]), s.args[2]
+    v = value.to(x.dtype) if isinstance(value, torch.Tensor) else torch.tensor(value, dtype=x.dtype)
+    if v.dim():
+        raise Unsupported("tensor-valued fill")
+    if x.dim() == 0:
+        return be.index_put(x.reshape(1), [index.reshape(-1)], v, False).reshape(())
+    return be.index_put(_front(x, dim), [index.reshape(-1)], v, False).movedim(0, dim)
+
+
+def take_along_dim(be, s):
+    _no_kwargs(s, ("dim",))
+    x, idx = _tensor_ok(s.input), _tensor_ok(s.args[0])
+    dim = s.args[1] if len(s.args) > 1 else s.kwargs.get("dim")
+    n = x.numel() if dim is None else x.shape[dim]
+    if idx.numel() and int(idx.min()) < 0:                            # negative indices count from the end: remainder by the extent
+        idx = be.binary("remainder", idx, torch.tensor(n, dtype=idx.dtype), 1)
+    if dim is None:
+        return be.gather(x.reshape(-1), 0, idx.reshape(-1))
+    d = dim if dim >= 0 else dim + x.dim()
+    xs, is_ = list(x.shape), list(idx.shape)
+    xs[d], is_[d] = 1, 1
+    common = list(torch.broadcast_shapes(xs, is_))
+    xs, is_ = list(common), list(common)
+    xs[d], is_[d] = x.shape[d], idx.shape[d]
+    return be.gather(x.expand(xs), d, idx.expand(is_))
+
+
+def put(be, s):
+    _no_kwargs(s, ("accumulate",))
+    x, index, src = _tensor_ok(s.input), _tensor_ok(s.args[0]), _tensor_ok(s.args[1])
+    accumulate = bool(s.args[2]) if len(s.args) > 2 else bool(s.kwargs.get("accumulate", False))
+    if not accumulate and index.numel() != len(torch.unique(index % max(x.numel(), 1))):
+        raise Unsupported("assignment with repeated destinations (no unique result)")
+    return be.index_put(x.reshape(-1), [index.reshape(-1)], src.reshape(-1), accumulate).reshape(x.shape)
+
+
+def scatter_into_view(view_of):
+    """select_scatter / slice_scatter / diagonal_scatter: a copy of the input with `src` copied over one view of it."""
+    def run(be, s):
+        x, src = _tensor_ok(s.input), _tensor_ok(s.args[0])
+        out = be.empty(x.shape, x.dtype)
+        out._keep = True
+        be.copy(x, out=out)
+        piece = view_of(out, *s.args[1:], **s.kwargs)
+        piece._keep = True
+        if piece.numel():
+            be.copy(src, out=piece)
+        return be.host(out)
+    return run
+
+
 def masked_select(be, s):
     _no_kwargs(s)
     return be.masked_select(_tensor_ok(s.input), _tensor_ok(s.args[0]))
@@ -794,6 +864,10 @@ ADAPTERS = {
     "nn.functional.softshrink": activation("softshrink", ("lambd",), (0.5,)), "logit": logit, "nan_to_num": nan_to_num,
     "nn.functional.hardtanh": hardtanh(-1.0, 1.0), "nn.functional.relu6": hardtanh(0.0, 6.0),
     "addcmul": ternary("addcmul"), "addcdiv": ternary("addcdiv"), "lerp": lerp,
+    "index_copy": index_copy, "index_fill": index_fill, "take_along_dim": take_along_dim, "put": put,
+    "select_scatter": scatter_into_view(lambda o, dim, index: o.select(dim, index)),
+    "slice_scatter": scatter_into_view(lambda o, dim=0, start=None, end=None, step=1: o[(slice(None),) * (dim % max(o.dim(), 1)) + (slice(start, end, step),)]),
+    "diagonal_scatter": scatter_into_view(lambda o, offset=0, dim1=0, dim2=1: o.diagonal(offset, dim1, dim2)),
     "clone": clone, "contiguous": clone, "flip": flip(), "fliplr": flip([1]), "flipud": flip([0]), "roll": roll,
     "tril": tri("tril"), "triu": tri("triu"), "cat": concatenate(False), "stack": concatenate(True),
     "nn.functional.mse_loss": regression_loss("mse"), "nn.functional.l1_loss": regression_loss("l1"),
