@@ -135,3 +135,55 @@ def test_workspace_queries_are_host_only():
     idx = torch.zeros((100, 1), dtype=torch.int64).expand(100, 64)
     assert B.tx_scatter_add_workspace_bytes(torch.zeros((8, 64)), 0, idx, torch.zeros((100, 64)), True) > 0
     assert B.tx_scatter_add_workspace_bytes(torch.zeros((8, 64)), 0, idx, torch.zeros((100, 64)), False) == 0
+
+
+def test_later_entry_points_infer_and_validate_on_the_host():
+    z = lambda *s, dt=torch.float32: torch.zeros(s, dtype=dt)
+    null_stream = B.ctypes.c_void_p(0)
+    for op, dt in itertools.product(B.UNARY_PARAM, DT):
+        try:
+            want = O.unary_param(op, torch.zeros(2, dtype=dt), 1.0, 1.0, 1.0).dtype
+        except O.OracleError as err:
+            with pytest.raises(B.TxError) as e:
+                B.tx_infer_unary_param_dtype(op, dt)
+            assert e.value.kind.lower() == err.kind, (op, dt)
+            continue
+        assert B.tx_infer_unary_param_dtype(op, dt) == want, (op, dt)
+    for op in B.TERNARY:
+        for da, db, dc in itertools.product(DT, DT, DT):
+            a, b, c = z(3, dt=da), z(3, dt=db), z(3, dt=dc) + 1
+            try:
+                want = O.ternary(op, a, b, c).dtype
+            except O.OracleError as err:
+                with pytest.raises(B.TxError) as e:
+                    B.tx_infer_ternary_dtype(op, a, b, c)
+                assert e.value.kind.lower() == err.kind, (op, da, db, dc)
+                continue
+            assert B.tx_infer_ternary_dtype(op, a, b, c) == want, (op, da, db, dc)
+    for call, kind in [(lambda: B.tx_unary_param("celu", z(3), z(3), 0.0, stream=null_stream), "SCALAR"),
+                       (lambda: B.tx_unary_param("round_decimals", z(3), z(3), 0.5, stream=null_stream), "SCALAR"),
+                       (lambda: B.tx_ternary("lerp", z(3), z(3), z(3, dt=torch.bfloat16), None, 0.5, stream=null_stream), "DTYPE"),
+                       (lambda: B.tx_ternary("addcmul", z(3), z(3), z(4), z(3), stream=null_stream), "SHAPE"),
+                       (lambda: B.tx_scan("logcumsumexp", z(4, dt=torch.int64), z(4, dt=torch.int64), 0, stream=null_stream), "DTYPE"),
+                       (lambda: B.tx_scan("cummax", z(4), z(4), 0, stream=null_stream), "SCALAR"),
+                       (lambda: B.tx_copy(z(3), z(4, 3), stream=null_stream), "SHAPE"),
+                       (lambda: B.tx_flip(z(2, 3), z(2, 3), [0, 0], stream=null_stream), "DIM"),
+                       (lambda: B.tx_roll(z(2, 3), z(2, 3), [1], [2], stream=null_stream), "DIM"),
+                       (lambda: B.tx_tri(z(5), z(5), 0, False, stream=null_stream), "NDIM"),
+                       (lambda: B.tx_loss("huber", z(), z(3), z(3), "mean", 0.0, None, stream=null_stream), "SCALAR"),
+                       (lambda: B.tx_loss("mse", z(), z(3), z(3), "mean", 1.0, None, stream=null_stream), "WORKSPACE"),
+                       (lambda: B.tx_reduce("norm", z(), z(0), None, False, float("inf"), stream=null_stream), "EMPTY_REDUCTION"),
+                       (lambda: B.tx_reduce("nanmean", z(dt=torch.int64), z(3, dt=torch.int64), None, stream=null_stream), "DTYPE")]:
+        with pytest.raises(B.TxError) as e:
+            call()
+        assert e.value.kind == kind, kind
+    buf = z(12)
+    with pytest.raises(B.TxError) as e:
+        B.tx_copy(buf[1:9], buf[0:8], stream=null_stream)                     # a shifted alias
+    assert e.value.kind == "OVERLAP"
+    B.tx_copy(z(0, 3), z(3), stream=null_stream)                              # nothing to do: no device needed
+    B.tx_flip(z(0, 3), z(0, 3), [0], stream=null_stream)
+    assert B.tx_scan_workspace_bytes("cumprod", z(4, 65536), z(4, 65536), -1) == 256 + 4 * 16 * 32     # binary64 accumulators: 4 words per tile
+    assert B.tx_scan_workspace_bytes("cumsum", z(4, 65536), z(4, 65536), -1) == B.tx_cumsum_workspace_bytes(z(4, 65536), z(4, 65536), -1)
+    assert B.tx_loss_workspace_bytes("mse", z(), z(64, 64), z(64, 64), "none", 1.0) == 0
+    assert B.tx_loss_workspace_bytes("mse", z(), z(64, 64), z(64), "sum", 1.0) > B.tx_loss_workspace_bytes("mse", z(), z(64, 64), z(64, 64), "sum", 1.0)
