@@ -325,6 +325,13 @@ def build_ops(torch, B):
     wsm = B.workspace(B.tx_masked_select_workspace_bytes(osel1, cnt, src, mask))
     extra("masked_select_f32_p0.3", "f3", "select_write_kernel", NS * W * 5 + nsel * 4, NS * W,
           lambda: B.tx_masked_select(osel1, cnt, src, mask, wsm))
+    def fused():
+        B.tx_force_path("select-fused")
+        try:
+            B.tx_masked_select(osel1, cnt, src, mask, wsm)
+        finally:
+            B.tx_force_path(None)
+    extra("masked_select_f32_p0.3_single_pass_look_back", "f3", "select_fused_quad_kernel", NS * W * 5 + nsel * 4, NS * W, fused)
     sparse = torch.where(mask, src, torch.zeros((), device=dev))
     onz = torch.empty((NS * W // 2, 2), device=dev, dtype=I64)
     wsn = B.workspace(B.tx_nonzero_workspace_bytes(onz, cnt, sparse))

@@ -479,7 +479,7 @@ tx_status tx_take(const tx_tensor* out, const tx_tensor* input, const tx_tensor*
  * call writes the number of selected elements to `count` and the first
  * min(count, capacity) results to out, in logical (row-major) order (so
  * count > capacity tells the caller the buffer was too small; numel of the
- * input always suffices).  Both need a 4-byte aligned device workspace of
+ * input always suffices).  Both need a 16-byte aligned device workspace of
  * tx_*_workspace_bytes() bytes and handle fewer than 2^31 elements.
  *   masked_select: the elements of x, broadcast with the bool mask, where the
  *     mask is true; out is 1-D with x's dtype.
@@ -547,7 +547,8 @@ const char* tx_last_path(void);
  * non-innermost dim: "softmax-strided", "scan-strided" (one lane per slice
  * instead of the column kernels).  layer_norm: "layer-norm-block" (one
  * workgroup per row), "layer-norm-generic" (three passes, any strides).
- * binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
+ * masked_select: "select-fused" (one pass with decoupled look-back instead of
+ * the count, offsets and write passes).  binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
  * first; the workspace query then reports that form's size); tx_loss:
  * "loss-two-pass" likewise.  Requests that a path cannot
  * serve fall back to the automatic choice.  Process-wide; meant for A/B

@@ -140,6 +140,8 @@ def run_select(fn_bytes, fn, out, what):
     fn(out, count, ws)
     used = B.tx_last_path()
     torch.cuda.synchronize()
+    if used == "select-fused":
+        assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
     return int(count.item()), used
 
 
@@ -235,19 +237,34 @@ def test_compaction_both_contiguous_forms_agree_with_oracle():
         m = I.bernoulli_mask((300, 1024), 0.3, seed=446)
         xs = torch.where(m, x, torch.zeros((), dtype=dt))
         assert check_masked_select(x, m) == "select" and check_nonzero(xs) == "select"
+        B.tx_force_path("select-fused")
+        try:
+            assert check_masked_select(x, m) == "select-fused"
+        finally:
+            B.tx_force_path(None)
         B.tx_force_path("select-slab")
         try:
             assert check_masked_select(x, m) == "select-slab" and check_nonzero(xs) == "select-slab"
         finally:
             B.tx_force_path(None)
         # unaligned bases fall back to the element-per-lane form
-        assert check_masked_select(x.view(-1)[1:-3], m.view(-1)[1:-3], what="offset base") in ("select", "select-slab")
+        assert check_masked_select(x.view(-1)[1:-3], m.view(-1)[1:-3], what="offset base") in ("select", "select-fused", "select-slab")
 
 
 def test_compaction_full_size():
     x = I.typed((8192, 8192), F32, seed=440)
     m = I.bernoulli_mask((8192, 8192), 0.25, seed=441)
     assert check_masked_select(x, m) == "select"
+    B.tx_force_path("select-fused")                                     # the single-pass alternative on the same inputs
+    try:
+        assert check_masked_select(x, m) == "select-fused"
+        for p in (0.0, 1.0):                                            # nothing / everything selected, many tiles
+            assert check_masked_select(x[:2048], I.bernoulli_mask((2048, 8192), p, seed=443)) == "select-fused"
+        xb = I.typed((4096, 8192), BF16, seed=444)
+        assert check_masked_select(xb, I.bernoulli_mask((4096, 8192), 0.6, seed=445)) == "select-fused"
+        assert check_masked_select(x[:1025, :8188].contiguous(), m[:1025, :8188].contiguous(), what="ragged last tile") == "select-fused"
+    finally:
+        B.tx_force_path(None)
     xs = torch.where(I.bernoulli_mask((8192, 4096), 0.1, seed=442), x[:, :4096], torch.zeros(()))
     assert check_nonzero(xs) == "select"
 
