@@ -364,15 +364,23 @@ __global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, 
 // scatter_reduce_, every mode: the first entry of each run of equal keys combines the run in position order
 // (binary64 for floats, wrapping 64-bit for integers), then with the element's own value when it is included.
 enum { kRedSum = 0, kRedProd = 1, kRedMean = 2, kRedAmax = 3, kRedAmin = 4 };
-template <class T>
-__global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
-                                                            const ElemArgs a, int mode, int include_self) {
-  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (j >= n) return;
-  const uint32_t k = keys[j];
-  if (j > 0 && keys[j - 1] == k) return;
+enum { kNone = 0, kEnd = 1, kThrough = 2 };       // what the piece at the start of a chunk or block does
+
+// scatter_reduce_ on the element-key sort.  The sorted (destination element, position) pairs are cut into blocks of
+// kBlock entries, one per workgroup; a run of equal keys is cut where it crosses a block boundary, and the lane at the
+// start of each piece combines the piece in order (binary64 / wrapping int64).  A run that lies inside one block is
+// finished there.  The pieces of a run that crosses blocks are parked - the piece that ends a block in part_b, the
+// piece that begins a block in part_a with a mark saying whether the run stops in that block or passes through it -
+// and seg_reduce_finish_kernel adds them up in block order, one lane per crossing run.  No lane walks more than a
+// block's worth of entries, however many entries share a destination, and the order of combination depends only on
+// the data.
+template <class A> struct RedPart {
+  A acc;
+  int64_t count;
+};
+template <class T> struct RedOps {
   using A = typename std::conditional<std::is_integral<T>::value, int64_t, double>::type;
-  auto combine = [&](A x, A v) -> A {
+  __device__ __forceinline__ static A combine(int mode, A x, A v) {
     if constexpr (std::is_integral<T>::value) {
       switch (mode) {
         case kRedProd: return (A)((uint64_t)x * (uint64_t)v);
@@ -388,10 +396,48 @@ __global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys
         default: return x + v;
       }
     }
-  };
+  }
+  // folds in the destination's own value if asked, divides for the mean, stores
+  __device__ __forceinline__ static void finish(int mode, int include_self, T* dst, A acc, int64_t count) {
+    if (include_self) {
+      acc = combine(mode, acc, cvt<A>(*dst));
+      ++count;
+    }
+    if constexpr (std::is_integral<T>::value) {
+      if constexpr (std::is_same<T, uint8_t>::value) acc = acc != 0;     // bool: a sum of ones is an OR
+      else acc = (A)(T)acc;                              // int32 arithmetic wraps at 32 bits (before a mean divides)
+      if (mode == kRedMean) {                            // rounding toward -infinity
+        A q = acc / count;
+        if (acc % count != 0 && acc < 0) --q;
+        acc = q;
+      }
+      *dst = (T)acc;
+    } else {
+      if (mode == kRedMean) acc /= (double)count;
+      *dst = cvt<T>((float)acc);                         // binary64 -> fp32 -> T: T is fp32 or narrower
+    }
+  }
+};
+struct RedPieces {                                       // per block of kBlock sorted entries
+  char* part_a;                                          // RedPart: the piece that begins the block and continues a run
+  char* part_b;                                          // RedPart: the piece that ends the block and goes on
+  uint8_t* flag_a;                                       // kNone / kEnd / kThrough for part_a
+};
+
+template <class T>
+__global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
+                                                            const ElemArgs a, int mode, int include_self, RedPieces pc) {
+  using A = typename RedOps<T>::A;
+  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (j >= n) return;
+  const uint32_t k = keys[j];
+  const bool starts_run = j == 0 || keys[j - 1] != k;
+  if (threadIdx.x == 0 && starts_run) pc.flag_a[blockIdx.x] = kNone;
+  if (!starts_run && threadIdx.x != 0) return;           // a piece begins where a run begins, and at the block's first entry
+  const int64_t block_end = std::min<int64_t>(((int64_t)blockIdx.x + 1) * kBlock, n);
   A acc = A(0);
-  int64_t count = 0;
-  for (int64_t e = j; e < n && keys[e] == k; ++e, ++count) {
+  int64_t count = 0, e = j;
+  for (; e < block_end && keys[e] == k; ++e, ++count) {
     int64_t so = 0;
     uint32_t rem = vals[e];
     for (int d = a.shape.n - 1; d >= 0; --d) {
@@ -401,26 +447,37 @@ __global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys
       so += (int64_t)m * a.sstride[d];
     }
     const A v = cvt<A>(((const T*)a.src)[so]);
-    acc = count ? combine(acc, v) : v;
+    acc = count ? RedOps<T>::combine(mode, acc, v) : v;
   }
-  T* dst = (T*)a.dst + k;
-  if (include_self) {
-    acc = combine(acc, cvt<A>(*dst));
-    ++count;
-  }
-  if constexpr (std::is_integral<T>::value) {
-    if constexpr (std::is_same<T, uint8_t>::value) acc = acc != 0;     // bool: a sum of ones is an OR
-    else acc = (A)(T)acc;                              // int32 arithmetic wraps at 32 bits (before a mean divides)
-    if (mode == kRedMean) {                            // rounding toward -infinity
-      A q = acc / count;
-      if (acc % count != 0 && acc < 0) --q;
-      acc = q;
-    }
-    *dst = (T)acc;
+  const bool ends_run = e == n || keys[e] != k;          // e == block_end < n with the same key: the run goes on
+  if (starts_run && ends_run) {
+    RedOps<T>::finish(mode, include_self, (T*)a.dst + k, acc, count);
+  } else if (!starts_run) {
+    ((RedPart<A>*)pc.part_a)[blockIdx.x] = RedPart<A>{acc, count};
+    pc.flag_a[blockIdx.x] = ends_run ? kEnd : kThrough;
   } else {
-    if (mode == kRedMean) acc /= (double)count;
-    *dst = cvt<T>((float)acc);                         // binary64 -> fp32 -> T: T is fp32 or narrower
+    ((RedPart<A>*)pc.part_b)[blockIdx.x] = RedPart<A>{acc, count};
   }
+}
+
+// one lane per block whose last piece starts a run that crosses into the next block
+template <class T>
+__global__ __launch_bounds__(kBlock) void seg_reduce_finish_kernel(const uint32_t* keys, int64_t n, int64_t nblocks, const ElemArgs a,
+                                                                   int mode, int include_self, RedPieces pc) {
+  using A = typename RedOps<T>::A;
+  const int64_t b = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (b >= nblocks) return;
+  const int64_t last = std::min<int64_t>((b + 1) * kBlock, n) - 1;
+  if (last + 1 >= n || keys[last + 1] != keys[last]) return;           // nothing crosses
+  if (pc.flag_a[b] == kThrough) return;                                // the crossing run started before this block
+  RedPart<A> r = ((const RedPart<A>*)pc.part_b)[b];
+  for (int64_t bb = b + 1; bb < nblocks; ++bb) {
+    const RedPart<A> piece = ((const RedPart<A>*)pc.part_a)[bb];
+    r.acc = RedOps<T>::combine(mode, r.acc, piece.acc);
+    r.count += piece.count;
+    if (pc.flag_a[bb] != kThrough) break;
+  }
+  RedOps<T>::finish(mode, include_self, (T*)a.dst + keys[last], r.acc, r.count);
 }
 
 // index_put_: one lane per element of the value shape I + rest.  MODE 0 assigns, 1 accumulates with an atomic
@@ -477,7 +534,6 @@ constexpr int kChunk = 128;                 // sorted rows per wave
 constexpr int64_t kIntRowModeMin = 4096;    // integer row mode pays for its sort from about this many rows
 constexpr int kCombineWaves = 4;
 constexpr int kCombineBlocks = 2048;
-enum { kNone = 0, kEnd = 1, kThrough = 2 };
 
 struct SegRowArgs {
   const uint32_t* keys;
@@ -1060,6 +1116,11 @@ tx_status elem_sort_plan(const char* name, const tx_tensor* self, int64_t n, Sca
   for (int i = 0; i < 2; ++i) { p->off_vals[i] = o; o = align_up(o + (size_t)n * 4, 256); }
   p->off_hist = o; o = align_up(o + (size_t)256 * p->nblocks * 4, 256);
   p->off_totals = o; o = align_up(o + 256 * 4, 256);
+  // the pieces of runs that cross blocks of kBlock sorted entries (scatter_reduce_): two 16-byte records and a mark per block
+  const size_t rblocks = (size_t)((n + kBlock - 1) / kBlock);
+  p->off_part_a = o; o = align_up(o + rblocks * 16, 256);
+  p->off_part_b = o; o = align_up(o + rblocks * 16, 256);
+  p->off_flag_a = o; o = align_up(o + rblocks, 256);
   p->bytes = o;
   return TX_OK;
 }
@@ -1082,9 +1143,13 @@ tx_status scatter_reduce_typed(const ScatterPlan& p, const tx_tensor* self, int 
   tx_status rc = run_sort(p, ws, s, &cur);
   if (rc) return rc;
   set_path("scatter-reduce-sort");
-  hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, (const uint32_t*)(ws + p.off_keys[cur]),
-                     (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea, mode, include_self);
-  return check_launch("scatter_reduce segmented kernel");
+  const RedPieces pc{ws + p.off_part_a, ws + p.off_part_b, (uint8_t*)(ws + p.off_flag_a)};
+  const uint32_t* keys = (const uint32_t*)(ws + p.off_keys[cur]);
+  hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea,
+                     mode, include_self, pc);
+  hipLaunchKernelGGL((seg_reduce_finish_kernel<T>), dim3((nb + kBlock - 1) / kBlock), dim3(kBlock), 0, s, keys, p.n, (int64_t)nb, ea,
+                     mode, include_self, pc);
+  return check_launch("scatter_reduce segmented kernels");
 }
 
 // scatter_reduce_ through the whole-row kernels: sum, amax, amin (an fp32 accumulator is exact for the extrema and
