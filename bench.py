@@ -301,6 +301,9 @@ def build_ops(torch, B):
     wsia = B.workspace(B.tx_index_add_workspace_bytes(dst_f, 0, rows, src, True))
     extra("index_add_f32_rows_alpha", "f3", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
           lambda: B.tx_index_add_(dst_f, 0, rows, src, 0.5, True, wsia))
+    wsfe = B.workspace(B.tx_scatter_add_workspace_bytes(dst_f, 0, midx, src[:NE], True))
+    extra("scatter_add_f32_sorted_elem_index[131072,256]", "a15", "seg_reduce_kernel", NE * W * (4 + 8 + 8), NE * W,
+          lambda: B.tx_scatter_add_(dst_f, 0, midx, src[:NE], True, wsfe))
     wsrr = B.workspace(B.tx_scatter_reduce_workspace_bytes(dst_f, 0, eidx, src, "amax", True))
     extra("scatter_reduce_amax_f32_rows", "f3", "seg_rows_kernel", NS * (W * 4 + 8) + 2 * ND * W * 4, NS * W,
           lambda: B.tx_scatter_reduce_(dst_f, 0, eidx, src, "amax", True, wsrr))

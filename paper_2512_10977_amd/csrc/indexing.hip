@@ -334,46 +334,21 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(const uint32_t* ke
 }
 
 // ---------------------------------------------------------------------------
-// deterministic segmented sums
+// deterministic segmented reductions
 // ---------------------------------------------------------------------------
-// element mode: the first entry of each run of equal keys sums the run in order (binary64 accumulator)
-template <class T>
-__global__ __launch_bounds__(kBlock) void seg_elem_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
-                                                          const ElemArgs a) {
-  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (j >= n) return;
-  const uint32_t k = keys[j];
-  if (j > 0 && keys[j - 1] == k) return;
-  double acc = 0.0;
-  for (int64_t e = j; e < n && keys[e] == k; ++e) {
-    // source offset of index position vals[e]
-    int64_t so = 0;
-    uint32_t rem = vals[e];
-    for (int d = a.shape.n - 1; d >= 0; --d) {
-      uint32_t q, m;
-      a.shape.div[d].divmod(rem, q, m);
-      rem = q;
-      so += (int64_t)m * a.sstride[d];
-    }
-    acc += cvt<double>(((const T*)a.src)[so]);
-  }
-  T* dst = (T*)a.dst + k;
-  *dst = cvt<T>((float)(cvt<double>(*dst) + (double)a.alpha_f * acc));
-}
-
-// scatter_reduce_, every mode: the first entry of each run of equal keys combines the run in position order
-// (binary64 for floats, wrapping 64-bit for integers), then with the element's own value when it is included.
+// Element mode (scatter_reduce_ in every mode; the float sums of scatter_add_ / index_put_ with an index that is not
+// a broadcast row id): runs of equal keys are combined in position order (binary64 for floats, wrapping 64-bit for
+// integers), then with the element's own value when it is included.
 enum { kRedSum = 0, kRedProd = 1, kRedMean = 2, kRedAmax = 3, kRedAmin = 4 };
 enum { kNone = 0, kEnd = 1, kThrough = 2 };       // what the piece at the start of a chunk or block does
 
 // scatter_reduce_ on the element-key sort.  The sorted (destination element, position) pairs are cut into blocks of
-// kBlock entries, one per workgroup; a run of equal keys is cut where it crosses a block boundary, and the lane at the
-// start of each piece combines the piece in order (binary64 / wrapping int64).  A run that lies inside one block is
-// finished there.  The pieces of a run that crosses blocks are parked - the piece that ends a block in part_b, the
+// kBlock entries, one per workgroup; a run of equal keys is cut where it crosses a block boundary, and each piece is
+// combined in binary64 / wrapping int64.  A run that lies inside one block is finished there.  The pieces of a run that crosses blocks are parked - the piece that ends a block in part_b, the
 // piece that begins a block in part_a with a mark saying whether the run stops in that block or passes through it -
-// and seg_reduce_finish_kernel adds them up in block order, one lane per crossing run.  No lane walks more than a
-// block's worth of entries, however many entries share a destination, and the order of combination depends only on
-// the data.
+// and seg_reduce_finish_kernel adds them up in block order, one lane per crossing run.  Inside a block the pieces
+// come from a segmented scan (every lane gathers its own value; shuffles inside a wave, then the waves' last pieces), so the association of
+// a floating-point sum is a tree within a block and left to right across blocks; it depends only on the data.
 template <class A> struct RedPart {
   A acc;
   int64_t count;
@@ -398,7 +373,9 @@ template <class T> struct RedOps {
     }
   }
   // folds in the destination's own value if asked, divides for the mean, stores
-  __device__ __forceinline__ static void finish(int mode, int include_self, T* dst, A acc, int64_t count) {
+  __device__ __forceinline__ static void finish(int mode, int include_self, T* dst, A acc, int64_t count, float alpha = 1.0f) {
+    if constexpr (!std::is_integral<T>::value)
+      if (mode == kRedSum) acc *= (double)alpha;        // scatter_add_ / index_add_ scale the sum of what arrives
     if (include_self) {
       acc = combine(mode, acc, cvt<A>(*dst));
       ++count;
@@ -428,35 +405,72 @@ template <class T>
 __global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
                                                             const ElemArgs a, int mode, int include_self, RedPieces pc) {
   using A = typename RedOps<T>::A;
-  const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (j >= n) return;
-  const uint32_t k = keys[j];
-  const bool starts_run = j == 0 || keys[j - 1] != k;
-  if (threadIdx.x == 0 && starts_run) pc.flag_a[blockIdx.x] = kNone;
-  if (!starts_run && threadIdx.x != 0) return;           // a piece begins where a run begins, and at the block's first entry
-  const int64_t block_end = std::min<int64_t>(((int64_t)blockIdx.x + 1) * kBlock, n);
-  A acc = A(0);
-  int64_t count = 0, e = j;
-  for (; e < block_end && keys[e] == k; ++e, ++count) {
-    int64_t so = 0;
-    uint32_t rem = vals[e];
-    for (int d = a.shape.n - 1; d >= 0; --d) {
-      uint32_t q, m;
-      a.shape.div[d].divmod(rem, q, m);
-      rem = q;
-      so += (int64_t)m * a.sstride[d];
-    }
-    const A v = cvt<A>(((const T*)a.src)[so]);
-    acc = count ? RedOps<T>::combine(mode, acc, v) : v;
+  __shared__ A sh_acc[kBlock / 64];
+  __shared__ int sh_cnt[kBlock / 64];
+  __shared__ uint32_t sh_key[kBlock / 64];
+  const int t = threadIdx.x;
+  const int64_t j = (int64_t)blockIdx.x * kBlock + t;
+  const bool valid = j < n;
+  const int64_t jc = valid ? j : n - 1;                  // lanes past the end read the last entry and store nothing
+  const uint32_t k = keys[jc];
+  int64_t so = 0;
+  uint32_t rem = vals[jc];
+  for (int d = a.shape.n - 1; d >= 0; --d) {
+    uint32_t q, m;
+    a.shape.div[d].divmod(rem, q, m);
+    rem = q;
+    so += (int64_t)m * a.sstride[d];
   }
-  const bool ends_run = e == n || keys[e] != k;          // e == block_end < n with the same key: the run goes on
+  A acc = cvt<A>(((const T*)a.src)[so]);
+  int cnt = 1;
+  // Segmented inclusive scan over the block's entries.  Keys are sorted, so the entry d places back belongs to the
+  // same run exactly when its key is equal; the earlier operand always goes on the left.
+  const int lane = t & 63;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t ko = shfl_up(k, d);
+    const A ao = shfl_up(acc, d);
+    const int co = shfl_up(cnt, d);
+    if (lane >= d && ko == k) {
+      acc = RedOps<T>::combine(mode, ao, acc);
+      cnt += co;
+    }
+  }
+  // across waves: the last lane of a wave holds the piece that ends it; a lane whose run reaches back to the start of
+  // its wave takes in the pieces of the waves before, nearest first, for as long as they carry the same key whole
+  const int w = t >> 6;
+  if (lane == 63) {
+    sh_acc[w] = acc;
+    sh_cnt[w] = cnt;
+    sh_key[w] = k;
+  }
+  __syncthreads();
+  if (cnt == lane + 1) {
+    A carry = A(0);
+    int ccnt = 0;
+    for (int p = w - 1; p >= 0 && sh_key[p] == k; --p) {
+      carry = ccnt ? RedOps<T>::combine(mode, sh_acc[p], carry) : sh_acc[p];
+      ccnt += sh_cnt[p];
+      if (sh_cnt[p] != 64) break;
+    }
+    if (ccnt) {
+      acc = RedOps<T>::combine(mode, carry, acc);
+      cnt += ccnt;
+    }
+  }
+  if (!valid) return;
+  const bool ends_run = j + 1 == n || keys[j + 1] != k;
+  if (t == 0 && (j == 0 || keys[j - 1] != k)) pc.flag_a[blockIdx.x] = kNone;
+  if (!ends_run && t != kBlock - 1) return;              // a piece ends where a run ends, and at the block's last entry
+  const int first = t - cnt + 1;                         // where this piece begins in the block
+  const bool starts_run = first > 0 || j - t == 0 || keys[j - t - 1] != k;
   if (starts_run && ends_run) {
-    RedOps<T>::finish(mode, include_self, (T*)a.dst + k, acc, count);
+    RedOps<T>::finish(mode, include_self, (T*)a.dst + k, acc, (int64_t)cnt, a.alpha_f);
   } else if (!starts_run) {
-    ((RedPart<A>*)pc.part_a)[blockIdx.x] = RedPart<A>{acc, count};
+    ((RedPart<A>*)pc.part_a)[blockIdx.x] = RedPart<A>{acc, (int64_t)cnt};
     pc.flag_a[blockIdx.x] = ends_run ? kEnd : kThrough;
   } else {
-    ((RedPart<A>*)pc.part_b)[blockIdx.x] = RedPart<A>{acc, count};
+    ((RedPart<A>*)pc.part_b)[blockIdx.x] = RedPart<A>{acc, (int64_t)cnt};
   }
 }
 
@@ -477,7 +491,7 @@ __global__ __launch_bounds__(kBlock) void seg_reduce_finish_kernel(const uint32_
     r.count += piece.count;
     if (pc.flag_a[bb] != kThrough) break;
   }
-  RedOps<T>::finish(mode, include_self, (T*)a.dst + keys[last], r.acc, r.count);
+  RedOps<T>::finish(mode, include_self, (T*)a.dst + keys[last], r.acc, r.count, a.alpha_f);
 }
 
 // index_put_: one lane per element of the value shape I + rest.  MODE 0 assigns, 1 accumulates with an atomic
@@ -833,6 +847,17 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
 // ---------------------------------------------------------------------------
 // host helpers
 // ---------------------------------------------------------------------------
+// the two kernels above on n sorted entries; the three arrays hold one record per block of kBlock entries
+template <class T>
+void launch_seg_reduce(const uint32_t* keys, const uint32_t* vals, int64_t n, const ElemArgs& ea, int mode, int include_self,
+                       char* part_a, char* part_b, char* flag_a, hipStream_t s) {
+  const unsigned nb = (unsigned)((n + kBlock - 1) / kBlock);
+  const RedPieces pc{part_a, part_b, (uint8_t*)flag_a};
+  hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, vals, n, ea, mode, include_self, pc);
+  hipLaunchKernelGGL((seg_reduce_finish_kernel<T>), dim3((nb + kBlock - 1) / kBlock), dim3(kBlock), 0, s, keys, n, (int64_t)nb, ea, mode,
+                     include_self, pc);
+}
+inline size_t seg_reduce_blocks(int64_t n) { return (size_t)((n + kBlock - 1) / kBlock); }
 bool index_dtype_ok(int dt) { return dt == TX_I32 || dt == TX_I64; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 int bits_for(uint64_t max_value) {
@@ -902,6 +927,11 @@ tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, c
     p->off_key_b = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
     p->off_start_list = o; o = align_up(o + (size_t)p->nchunks * 4, 256);
     p->off_counter = o; o += 256;
+  } else {                                              // element mode: the pieces of runs that cross blocks of sorted entries
+    const size_t rblocks = seg_reduce_blocks(p->n);
+    p->off_part_a = o; o = align_up(o + rblocks * 16, 256);
+    p->off_part_b = o; o = align_up(o + rblocks * 16, 256);
+    p->off_flag_a = o; o = align_up(o + rblocks, 256);
   }
   p->bytes = o;
   return TX_OK;
@@ -982,7 +1012,7 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
       return fail(TX_ERR_UNSUPPORTED, "sorted integer scatter_add needs a broadcast row index");
     } else {
       set_path("scatter-sort-elem");
-      hipLaunchKernelGGL((seg_elem_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, vals, p.n, ea);
+      launch_seg_reduce<T>(keys, vals, p.n, ea, kRedSum, 1, ws + p.off_part_a, ws + p.off_part_b, ws + p.off_flag_a, s);
       return check_launch("segmented sum");
     }
   }
@@ -1117,7 +1147,7 @@ tx_status elem_sort_plan(const char* name, const tx_tensor* self, int64_t n, Sca
   p->off_hist = o; o = align_up(o + (size_t)256 * p->nblocks * 4, 256);
   p->off_totals = o; o = align_up(o + 256 * 4, 256);
   // the pieces of runs that cross blocks of kBlock sorted entries (scatter_reduce_): two 16-byte records and a mark per block
-  const size_t rblocks = (size_t)((n + kBlock - 1) / kBlock);
+  const size_t rblocks = seg_reduce_blocks(n);
   p->off_part_a = o; o = align_up(o + rblocks * 16, 256);
   p->off_part_b = o; o = align_up(o + rblocks * 16, 256);
   p->off_flag_a = o; o = align_up(o + rblocks, 256);
@@ -1143,12 +1173,8 @@ tx_status scatter_reduce_typed(const ScatterPlan& p, const tx_tensor* self, int 
   tx_status rc = run_sort(p, ws, s, &cur);
   if (rc) return rc;
   set_path("scatter-reduce-sort");
-  const RedPieces pc{ws + p.off_part_a, ws + p.off_part_b, (uint8_t*)(ws + p.off_flag_a)};
-  const uint32_t* keys = (const uint32_t*)(ws + p.off_keys[cur]);
-  hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea,
-                     mode, include_self, pc);
-  hipLaunchKernelGGL((seg_reduce_finish_kernel<T>), dim3((nb + kBlock - 1) / kBlock), dim3(kBlock), 0, s, keys, p.n, (int64_t)nb, ea,
-                     mode, include_self, pc);
+  launch_seg_reduce<T>((const uint32_t*)(ws + p.off_keys[cur]), (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea, mode, include_self,
+                       ws + p.off_part_a, ws + p.off_part_b, ws + p.off_flag_a, s);
   return check_launch("scatter_reduce segmented kernels");
 }
 
@@ -1533,10 +1559,13 @@ tx_status tx_index_put_(const tx_tensor* self, const tx_tensor* const* indices, 
   set_path("index-put-sort");
   const uint32_t* keys = (const uint32_t*)(w + p.off_keys[cur]);
   const uint32_t* vals = (const uint32_t*)(w + p.off_vals[cur]);
+  char* pa = w + p.off_part_a;
+  char* pb = w + p.off_part_b;
+  char* fa = w + p.off_flag_a;
   switch (self->dtype) {
-    case TX_F32: hipLaunchKernelGGL((seg_elem_kernel<float>), grid, dim3(kBlock), 0, s, keys, vals, n, ea); break;
-    case TX_BF16: hipLaunchKernelGGL((seg_elem_kernel<bf16>), grid, dim3(kBlock), 0, s, keys, vals, n, ea); break;
-    default: hipLaunchKernelGGL((seg_elem_kernel<f16>), grid, dim3(kBlock), 0, s, keys, vals, n, ea); break;
+    case TX_F32: launch_seg_reduce<float>(keys, vals, n, ea, kRedSum, 1, pa, pb, fa, s); break;
+    case TX_BF16: launch_seg_reduce<bf16>(keys, vals, n, ea, kRedSum, 1, pa, pb, fa, s); break;
+    default: launch_seg_reduce<f16>(keys, vals, n, ea, kRedSum, 1, pa, pb, fa, s); break;
   }
   return check_launch("index_put segmented sum");
 }
