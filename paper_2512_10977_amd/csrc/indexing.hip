@@ -195,11 +195,14 @@ constexpr int kSortItems = 8;
 constexpr int kSortTile = kBlock * kSortItems;          // 2048 entries per workgroup
 constexpr int kWaves = kBlock / kWave;
 
-// keys for the element mode: destination element offset of every index position
+// keys for the element mode: destination element offset of every index position.  The value that travels with a key
+// is the position (EB = 0) or, for sources of EB = 1, 2 or 4 bytes, the source element itself, zero-extended: the
+// sort is stable, so values of equal keys stay in position order and the reduction needs no gather afterwards.
+template <int EB>
 __global__ __launch_bounds__(kBlock) void scatter_keys_kernel(const ElemArgs a, uint32_t* keys, uint32_t* vals) {
   const int64_t lin = (int64_t)blockIdx.x * kBlock + threadIdx.x;
   if (lin >= a.shape.numel) return;
-  int64_t io = 0, d_o = 0;
+  int64_t io = 0, d_o = 0, so = 0;
   uint32_t rem = (uint32_t)lin;
   for (int d = a.shape.n - 1; d >= 0; --d) {
     uint32_t q, m;
@@ -207,12 +210,22 @@ __global__ __launch_bounds__(kBlock) void scatter_keys_kernel(const ElemArgs a, 
     rem = q;
     io += (int64_t)m * a.istride[d];
     if (d != a.dim) d_o += (int64_t)m * a.dstride[d];
+    if constexpr (EB != 0) so += (int64_t)m * a.sstride[d];
   }
   int64_t k = load_index(a.index, io, a.index_is64);
   k += k < 0 ? a.wrap : 0;
   d_o += k * a.dstride[a.dim];
   keys[lin] = (uint32_t)d_o;
-  vals[lin] = (uint32_t)lin;
+  if constexpr (EB == 4) vals[lin] = ((const uint32_t*)a.src)[so];
+  else if constexpr (EB == 2) vals[lin] = ((const uint16_t*)a.src)[so];
+  else if constexpr (EB == 1) vals[lin] = ((const uint8_t*)a.src)[so];
+  else vals[lin] = (uint32_t)lin;
+}
+template <class T> constexpr int key_value_bytes() { return sizeof(T) <= 4 ? (int)sizeof(T) : 0; }
+template <class T> __device__ __forceinline__ T value_from_bits(uint32_t b) {
+  if constexpr (sizeof(T) == 4) return __builtin_bit_cast(T, b);
+  else if constexpr (sizeof(T) == 2) return __builtin_bit_cast(T, (uint16_t)b);
+  else return __builtin_bit_cast(T, (uint8_t)b);
 }
 // keys for the row mode: the row id of every source row
 __global__ __launch_bounds__(kBlock) void row_keys_kernel(const char* index, int is64, int64_t istride, int64_t n,
@@ -276,6 +289,8 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(const uint32_t* ke
   __shared__ unsigned int digit_base[256];
   __shared__ unsigned int cnt[kWaves][256];
   __shared__ unsigned int wsum[kWaves];
+  __shared__ unsigned int tile_start[256];
+  __shared__ uint32_t tile_key[kSortTile], tile_val[kSortTile];
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   {  // exclusive scan of the 256 digit totals
     const unsigned int v = totals[threadIdx.x];
@@ -320,15 +335,48 @@ __global__ __launch_bounds__(kBlock) void sort_scatter_kernel(const uint32_t* ke
     off[s] = old + rank;
   }
   __syncthreads();
+  // Order the tile in LDS first, so that neighbouring lanes then store to neighbouring addresses of a digit's range.
+  {  // one lane per digit: where the digit starts in the ordered tile, and what to add to get its place in the output
+    unsigned int v = 0;
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) v += cnt[ww][threadIdx.x];
+    unsigned int incl = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      unsigned int o = __shfl_up(incl, d, kWave);
+      if (lane >= d) incl += o;
+    }
+    if (lane == kWave - 1) wsum[w] = incl;
+    __syncthreads();
+    unsigned int before = 0;
+    for (int ww = 0; ww < w; ++ww) before += wsum[ww];
+    const unsigned int start = before + incl - v;
+    tile_start[threadIdx.x] = start;
+    digit_base[threadIdx.x] += hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] - start;
+  }
+  __syncthreads();
 #pragma unroll
   for (int s = 0; s < kSortItems; ++s) {
     const int64_t i = base + s * kWave + lane;
     if (i < n) {
       const uint32_t dg = (key[s] >> shift) & 255u;
-      unsigned int pos = digit_base[dg] + hist[(int64_t)dg * nblocks + blockIdx.x] + off[s];
+      unsigned int pos = tile_start[dg] + off[s];
       for (int ww = 0; ww < w; ++ww) pos += cnt[ww][dg];
-      keys_out[pos] = key[s];
-      vals_out[pos] = val[s];
+      tile_key[pos] = key[s];
+      tile_val[pos] = val[s];
+    }
+  }
+  __syncthreads();
+  const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
+  const int nvalid = (int)std::min<int64_t>(kSortTile, n - tile_base);
+#pragma unroll
+  for (int s = 0; s < kSortItems; ++s) {
+    const int i = s * kBlock + threadIdx.x;
+    if (i < nvalid) {
+      const uint32_t kk = tile_key[i];
+      const unsigned int pos = digit_base[(kk >> shift) & 255u] + i;
+      keys_out[pos] = kk;
+      vals_out[pos] = tile_val[i];
     }
   }
 }
@@ -401,7 +449,7 @@ struct RedPieces {                                       // per block of kBlock 
   uint8_t* flag_a;                                       // kNone / kEnd / kThrough for part_a
 };
 
-template <class T>
+template <class T, bool BITS>                            // BITS: vals holds the source elements, not their positions
 __global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys, const uint32_t* vals, int64_t n,
                                                             const ElemArgs a, int mode, int include_self, RedPieces pc) {
   using A = typename RedOps<T>::A;
@@ -413,15 +461,20 @@ __global__ __launch_bounds__(kBlock) void seg_reduce_kernel(const uint32_t* keys
   const bool valid = j < n;
   const int64_t jc = valid ? j : n - 1;                  // lanes past the end read the last entry and store nothing
   const uint32_t k = keys[jc];
-  int64_t so = 0;
-  uint32_t rem = vals[jc];
-  for (int d = a.shape.n - 1; d >= 0; --d) {
-    uint32_t q, m;
-    a.shape.div[d].divmod(rem, q, m);
-    rem = q;
-    so += (int64_t)m * a.sstride[d];
+  A acc;
+  if constexpr (BITS && sizeof(T) <= 4) {
+    acc = cvt<A>(value_from_bits<T>(vals[jc]));
+  } else {
+    int64_t so = 0;
+    uint32_t rem = vals[jc];
+    for (int d = a.shape.n - 1; d >= 0; --d) {
+      uint32_t q, m;
+      a.shape.div[d].divmod(rem, q, m);
+      rem = q;
+      so += (int64_t)m * a.sstride[d];
+    }
+    acc = cvt<A>(((const T*)a.src)[so]);
   }
-  A acc = cvt<A>(((const T*)a.src)[so]);
   int cnt = 1;
   // Segmented inclusive scan over the block's entries.  Keys are sorted, so the entry d places back belongs to the
   // same run exactly when its key is equal; the earlier operand always goes on the left.
@@ -848,12 +901,12 @@ __global__ __launch_bounds__(kCombineWaves * kWave) void seg_combine_kernel(cons
 // host helpers
 // ---------------------------------------------------------------------------
 // the two kernels above on n sorted entries; the three arrays hold one record per block of kBlock entries
-template <class T>
+template <class T, bool BITS = false>
 void launch_seg_reduce(const uint32_t* keys, const uint32_t* vals, int64_t n, const ElemArgs& ea, int mode, int include_self,
                        char* part_a, char* part_b, char* flag_a, hipStream_t s) {
   const unsigned nb = (unsigned)((n + kBlock - 1) / kBlock);
   const RedPieces pc{part_a, part_b, (uint8_t*)flag_a};
-  hipLaunchKernelGGL((seg_reduce_kernel<T>), dim3(nb), dim3(kBlock), 0, s, keys, vals, n, ea, mode, include_self, pc);
+  hipLaunchKernelGGL((seg_reduce_kernel<T, BITS>), dim3(nb), dim3(kBlock), 0, s, keys, vals, n, ea, mode, include_self, pc);
   hipLaunchKernelGGL((seg_reduce_finish_kernel<T>), dim3((nb + kBlock - 1) / kBlock), dim3(kBlock), 0, s, keys, n, (int64_t)nb, ea, mode,
                      include_self, pc);
 }
@@ -1001,7 +1054,7 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
     hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
                        index->strides[0], p.n, keys0, vals0, (unsigned int*)(ws + p.off_counter), alpha.wrap);
   else
-    hipLaunchKernelGGL(scatter_keys_kernel, dim3(nb), dim3(kBlock), 0, s, ea, keys0, vals0);
+    hipLaunchKernelGGL(scatter_keys_kernel<key_value_bytes<T>()>, dim3(nb), dim3(kBlock), 0, s, ea, keys0, vals0);
   int cur;
   tx_status rc = run_sort(p, ws, s, &cur);
   if (rc) return rc;
@@ -1012,7 +1065,7 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
       return fail(TX_ERR_UNSUPPORTED, "sorted integer scatter_add needs a broadcast row index");
     } else {
       set_path("scatter-sort-elem");
-      launch_seg_reduce<T>(keys, vals, p.n, ea, kRedSum, 1, ws + p.off_part_a, ws + p.off_part_b, ws + p.off_flag_a, s);
+      launch_seg_reduce<T, key_value_bytes<T>() != 0>(keys, vals, p.n, ea, kRedSum, 1, ws + p.off_part_a, ws + p.off_part_b, ws + p.off_flag_a, s);
       return check_launch("segmented sum");
     }
   }
@@ -1167,13 +1220,14 @@ tx_status scatter_reduce_typed(const ScatterPlan& p, const tx_tensor* self, int 
   ElemArgs ea;
   fill_scatter_elem_args(&ea, self, d, index, src);
   const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
-  hipLaunchKernelGGL(scatter_keys_kernel, dim3(nb), dim3(kBlock), 0, s, ea, (uint32_t*)(ws + p.off_keys[0]),
+  hipLaunchKernelGGL(scatter_keys_kernel<key_value_bytes<T>()>, dim3(nb), dim3(kBlock), 0, s, ea, (uint32_t*)(ws + p.off_keys[0]),
                      (uint32_t*)(ws + p.off_vals[0]));
   int cur;
   tx_status rc = run_sort(p, ws, s, &cur);
   if (rc) return rc;
   set_path("scatter-reduce-sort");
-  launch_seg_reduce<T>((const uint32_t*)(ws + p.off_keys[cur]), (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea, mode, include_self,
+  launch_seg_reduce<T, key_value_bytes<T>() != 0>((const uint32_t*)(ws + p.off_keys[cur]), (const uint32_t*)(ws + p.off_vals[cur]), p.n, ea, mode,
+                                                  include_self,
                        ws + p.off_part_a, ws + p.off_part_b, ws + p.off_flag_a, s);
   return check_launch("scatter_reduce segmented kernels");
 }
