@@ -878,8 +878,364 @@ ADAPTERS = {
 ADAPTERS.update({name: view_then_copy for name in VIEW_OPS})
 
 
+# --------------------------------------------------------------------------- operators that are other entry points
+# Operators ATen itself defines through other operators (reflected arithmetic, one-sided clamps, unit conversions,
+# conversions, copies of views, stacking, splitting, ...): each adapter spells the operator out over the library's
+# entry points, and the result is compared with ATen's own operator.
+def reflected(name):
+    def run(be, s):
+        _no_kwargs(s)
+        if len(s.args) != 1:
+            raise Unsupported("arguments")
+        return be.binary(name, _operand(s.args[0]), _operand(s.input))
+    return run
+
+
+def rsub(be, s):
+    _no_kwargs(s, ("alpha",))
+    return be.binary("sub", _operand(s.args[0]), _operand(s.input), _scalar(s.kwargs.get("alpha", 1)))
+
+
+def one_sided_clamp(op):
+    def run(be, s):
+        _no_kwargs(s)
+        bound, x = s.args[0], _tensor_ok(s.input)
+        if (isinstance(bound, torch.Tensor) and bound.dim() > 0) or x.dtype == torch.bool:
+            return be.binary(op, x, _operand(bound))             # (the clamp entry point takes no bool tensor)
+        return be.clamp(x, *((_scalar(bound), None) if op == "maximum" else (None, _scalar(bound))))
+    return run
+
+
+def times_constant(c):
+    def run(be, s):
+        _no_kwargs(s)
+        return be.binary("mul", _tensor_ok(s.input), torch.tensor(c))
+    return run
+
+
+def equals_constant(c):
+    def run(be, s):
+        _no_kwargs(s)
+        x = _tensor_ok(s.input)
+        if x.dtype == torch.bool:
+            raise Unsupported("bool input")
+        return be.binary("eq", x, torch.tensor(c))
+    return run
+
+
+def fill_like(value_at, default=None):
+    """fill / full_like / zeros_like / ones_like: masked_fill under a mask that is true everywhere."""
+    def run(be, s):
+        kw = dict(s.kwargs)
+        want_dtype = kw.pop("dtype", None)
+        args = list(s.args)
+        if value_at is not None and "value" in kw:
+            args.insert(value_at, kw.pop("value"))
+        for k in ("memory_format", "layout", "pin_memory", "requires_grad"):
+            kw.pop(k, None)
+        if kw:
+            raise Unsupported("keyword %s" % sorted(kw))
+        x = _tensor_ok(s.input)
+        v = _scalar(args[value_at]) if value_at is not None else default
+        if want_dtype is not None and want_dtype != x.dtype:
+            if want_dtype not in DTYPES:
+                raise Unsupported("dtype %s" % want_dtype)
+            x = be.copy(x, dtype=want_dtype)
+        return be.masked_fill(x, torch.ones((), dtype=torch.bool), v)
+    return run
+
+
+def softmin(be, s):
+    _no_kwargs(s, ("dtype",))
+    x = _tensor_ok(s.input)
+    if s.kwargs.get("dtype") is not None:
+        x = _convert_first(be, x, s.kwargs["dtype"])
+    return be.softmax(be.unary("neg", x), s.args[0], False)
+
+
+def softsign(be, s):
+    _no_kwargs(s)
+    x = _tensor_ok(s.input)
+    return be.binary("div", x, be.binary("add", be.unary("abs", x), torch.tensor(1)))
+
+
+def tanhshrink(be, s):
+    _no_kwargs(s)
+    x = _tensor_ok(s.input)
+    return be.binary("sub", x, be.unary("tanh", x))
+
+
+def copy_of_view(view):
+    def run(be, s):
+        x = _tensor_ok(s.input)
+        v = x if view == "alias" else getattr(torch.Tensor, view)(x, *s.args, **s.kwargs)
+        return be.copy(_tensor_ok(v))
+    return run
+
+
+def convert_to(dtype):
+    def run(be, s):
+        _no_kwargs(s, ("memory_format",))
+        return be.copy(_tensor_ok(s.input), dtype=dtype)
+    return run
+
+
+def several(*adapters_and_filters):
+    """An operator with several results: one adapter per result, each seeing the same sample."""
+    def run(be, s):
+        return tuple(a(be, s) for a in adapters_and_filters)
+    return run
+
+
+def _with_kwargs(s, **changes):
+    kw = dict(s.kwargs)
+    for k, v in changes.items():
+        if v is _DROP:
+            kw.pop(k, None)
+        else:
+            kw[k] = v
+    return types.SimpleNamespace(input=s.input, args=s.args, kwargs=kw)
+
+
+_DROP = object()
+
+
+def aminmax(be, s):
+    _no_kwargs(s, ("dim", "keepdim"))
+    if s.args:
+        raise Unsupported("arguments")
+    x = _tensor_ok(s.input)
+    dim, keep = s.kwargs.get("dim"), bool(s.kwargs.get("keepdim", False))
+    return be.reduce("amin", x, dim, keep), be.reduce("amax", x, dim, keep)
+
+
+def extremum(value_op, index_op, binary_op):
+    """max / min: with another tensor the elementwise operator; with a dim the pair (values, indices); alone the
+    extremum of everything."""
+    def run(be, s):
+        x = _tensor_ok(s.input)
+        if s.args and isinstance(s.args[0], torch.Tensor):
+            _no_kwargs(s)
+            return be.binary(binary_op, x, _operand(s.args[0]))
+        args, kw = list(s.args), dict(s.kwargs)
+        if args:
+            kw["dim"] = args.pop(0)
+        if args:
+            kw["keepdim"] = args.pop(0)
+        if args or set(kw) - {"dim", "keepdim"}:
+            raise Unsupported("arguments")
+        if "dim" not in kw:
+            return be.reduce(value_op, x, None, False)
+        if x.dtype == torch.bool:
+            raise Unsupported("bool input with a dim")            # no argmax / argmin of bool in ATen or here
+        keep = bool(kw.get("keepdim", False))
+        return be.reduce(value_op, x, kw["dim"], keep), be.reduce(index_op, x, kw["dim"], keep)
+    return run
+
+
+def moments(name):
+    """std_mean / var_mean: the pair (spread, mean) from two reductions."""
+    spread = reduction(name, variance=True)
+    mean = reduction("mean")
+
+    def run(be, s):
+        args = [a for a in s.args]
+        kw = dict(s.kwargs)
+        if args and isinstance(args[0], bool):                       # (x, unbiased)
+            mean_s = types.SimpleNamespace(input=s.input, args=(), kwargs={})
+        else:
+            mkw = {k: v for k, v in kw.items() if k in ("dim", "keepdim")}
+            mean_s = types.SimpleNamespace(input=s.input, args=tuple(args[:2]), kwargs=mkw)
+            if len(args) > 2:
+                raise Unsupported("arguments")
+        return spread(be, s), mean(be, mean_s)
+    return run
+
+
+def repeat(tile):
+    """repeat / tile: a copy of the view that reads every source element r times over (stride 0 along the new
+    dims), reshaped on the host."""
+    def run(be, s):
+        _no_kwargs(s)
+        x = _tensor_ok(s.input)
+        reps = list(s.args[0]) if len(s.args) == 1 and isinstance(s.args[0], (list, tuple, torch.Size)) else list(s.args)
+        if tile and len(reps) < x.dim():
+            reps = [1] * (x.dim() - len(reps)) + reps
+        if len(reps) < x.dim():
+            raise Unsupported("fewer repeats than dims")
+        shape = [1] * (len(reps) - x.dim()) + list(x.shape)
+        v = x.reshape(shape)
+        inter, final = [], []
+        for r, n in zip(reps, shape):
+            inter += [r, n]
+            final.append(r * n)
+        idx = tuple(i for n in range(len(shape)) for i in (None, slice(None)))
+        v = v[idx].expand(inter)
+        return be.copy(_tensor_ok(v)).reshape(final)
+    return run
+
+
+def rot90(be, s):
+    kw = dict(zip(("k", "dims"), s.args))
+    kw.update(s.kwargs)
+    k, dims = kw.get("k", 1) % 4, list(kw.get("dims", (0, 1)))
+    x = _tensor_ok(s.input)
+    if k == 0:
+        return be.copy(x)
+    if k == 2:
+        return be.remap("flip", x, dims)
+    return be.remap("flip", x, [dims[1] if k == 1 else dims[0]]).transpose(dims[0], dims[1])
+
+
+def outer(be, s):
+    _no_kwargs(s)
+    return be.binary("mul", _tensor_ok(s.input).unsqueeze(1), _tensor_ok(s.args[0]).unsqueeze(0))
+
+
+def trace(be, s):
+    _no_kwargs(s)
+    return be.reduce("sum", _tensor_ok(s.input).diagonal(), None, False)
+
+
+def dist(be, s):
+    _no_kwargs(s)
+    p = float(s.args[1]) if len(s.args) > 1 else 2.0
+    d = be.binary("sub", _tensor_ok(s.input), _tensor_ok(s.args[0]))
+    return be.reduce("norm", d, None, False, p)
+
+
+def normalize(be, s):
+    kw = dict(zip(("p", "dim", "eps"), s.args))
+    kw.update(s.kwargs)
+    _no_kwargs(types.SimpleNamespace(kwargs=kw), ("p", "dim", "eps"))
+    x = _tensor_ok(s.input)
+    n = be.reduce("norm", x, [kw.get("dim", 1)], True, float(kw.get("p", 2.0)))
+    return be.binary("div", x, be.clamp(n, float(kw.get("eps", 1e-12)), None))
+
+
+def ldexp(be, s):
+    _no_kwargs(s)
+    x, e = _operand(s.input), _operand(s.args[0])
+    p = be.binary("pow", torch.tensor(2.0), e)
+    # ATen's 2.0 is a scalar, which never widens a floating tensor: a 0-dim exponent keeps its own dtype
+    want = e.dtype if e.dtype.is_floating_point else F32
+    return be.binary("mul", x, p if p.dtype == want else be.copy(p, dtype=want))
+
+
+def glu(be, s):
+    _no_kwargs(s, ("dim",))
+    dim = s.args[0] if s.args else s.kwargs.get("dim", -1)
+    x = _tensor_ok(s.input)
+    half = x.shape[dim] // 2
+    return be.binary("mul", x.narrow(dim, 0, half), be.unary("sigmoid", x.narrow(dim, half, half)))
+
+
+def prelu(be, s):
+    _no_kwargs(s, ("weight",))
+    x, w = _tensor_ok(s.input), _tensor_ok(s.args[0] if s.args else s.kwargs["weight"])
+    if w.numel() != 1 and x.dim() >= 2:
+        w = w.reshape([1, -1] + [1] * (x.dim() - 2))
+    elif x.dim() == 0:
+        w = w.reshape(())
+    return be.where(be.binary("gt", x, torch.tensor(0)), x, be.binary("mul", w, x))
+
+
+def rms_norm(be, s):
+    kw = dict(zip(("normalized_shape", "weight", "eps"), s.args))
+    kw.update(s.kwargs)
+    _no_kwargs(types.SimpleNamespace(kwargs=kw), ("normalized_shape", "weight", "eps"))
+    x = _tensor_ok(s.input)
+    dims = list(range(x.dim() - len(kw["normalized_shape"]), x.dim()))
+    eps = kw.get("eps")
+    eps = torch.finfo(x.dtype).eps if eps is None else float(eps)
+    xf = x if x.dtype == F32 else be.copy(x, dtype=F32)          # ATen normalises in fp32 and rounds once
+    ms = be.reduce("mean", be.unary("square", xf), dims, True)
+    r = be.binary("mul", xf, be.unary("rsqrt", be.binary("add", ms, torch.tensor(eps))))
+    r = r if x.dtype == F32 else be.copy(r, dtype=x.dtype)
+    return r if kw.get("weight") is None else be.binary("mul", r, _tensor_ok(kw["weight"]))
+
+
+def diff(be, s):
+    kw = dict(zip(("n", "dim", "prepend", "append"), s.args))
+    kw.update(s.kwargs)
+    _no_kwargs(types.SimpleNamespace(kwargs=kw), ("n", "dim", "prepend", "append"))
+    x, dim = _tensor_ok(s.input), kw.get("dim", -1)
+    if kw.get("n", 1) == 0:                                      # ATen hands the input back, whatever else was passed
+        return be.copy(x)
+    parts = [_tensor_ok(t) for t in (kw.get("prepend"), x, kw.get("append")) if t is not None]
+    if len(parts) > 1:
+        x = concatenate(False)(be, types.SimpleNamespace(input=parts, args=(dim,), kwargs={}))
+    for _ in range(kw.get("n", 1)):
+        length = x.shape[dim]
+        if length == 0:
+            break
+        x = be.binary("logical_xor" if x.dtype == torch.bool else "sub", x.narrow(dim, 1, length - 1), x.narrow(dim, 0, length - 1))
+    return x if x is not s.input else be.copy(x)
+
+
+def stacked(prepare, dim_of):
+    """hstack / vstack / dstack / column_stack: cat after the host has reshaped the operands."""
+    cat = concatenate(False)
+
+    def run(be, s):
+        _no_kwargs(s)
+        tensors = [prepare(t) for t in s.input]
+        return cat(be, types.SimpleNamespace(input=tensors, args=(dim_of(tensors),), kwargs={}))
+    return run
+
+
+def copies_of_views(be, s, op):
+    """An operator whose results are views of its inputs: each is materialised with tx_copy."""
+    v = op.op(s.input, *s.args, **s.kwargs)
+    if isinstance(v, torch.Tensor):
+        return be.copy(_tensor_ok(v))
+    return tuple(be.copy(_tensor_ok(t)) for t in v)
+
+
+MULTI_VIEW_OPS = ("split", "split_with_sizes", "chunk", "unbind", "tensor_split", "hsplit", "vsplit", "dsplit", "unsafe_chunk",
+                  "unsafe_split", "split_with_sizes_copy", "unbind_copy", "atleast_1d", "atleast_2d", "atleast_3d",
+                  "broadcast_tensors", "meshgrid")
+IDENTITY_VIEW_OPS = ("ravel", "view_as", "reshape_as", "unflatten", "H", "mH", "real", "conj", "conj_physical", "resolve_conj",
+                     "resolve_neg", "positive", "squeeze_copy")
+
+ADAPTERS.update({
+    "__radd__": reflected("add"), "__rmul__": reflected("mul"), "__rsub__": reflected("sub"), "__rdiv__": reflected("div"),
+    "__rmod__": reflected("remainder"), "__rpow__": reflected("pow"), "__rand__": reflected("bitwise_and"),
+    "__ror__": reflected("bitwise_or"), "__rxor__": reflected("bitwise_xor"), "rsub": rsub,
+    "clamp_min": one_sided_clamp("maximum"), "clamp_max": one_sided_clamp("minimum"),
+    "deg2rad": times_constant(3.14159265358979323846 / 180.0), "rad2deg": times_constant(180.0 / 3.14159265358979323846),
+    "isposinf": equals_constant(float("inf")), "isneginf": equals_constant(float("-inf")), "sgn": unary("sign"),
+    "fill": fill_like(0), "full_like": fill_like(0), "zeros_like": fill_like(None, 0), "ones_like": fill_like(None, 1),
+    "nn.functional.softmin": softmin, "nn.functional.softsign": softsign, "nn.functional.tanhshrink": tanhshrink,
+    "expand_copy": copy_of_view("expand"), "permute_copy": copy_of_view("permute"), "t_copy": copy_of_view("t"),
+    "transpose_copy": copy_of_view("transpose"), "view_copy": copy_of_view("view"), "unsqueeze_copy": copy_of_view("unsqueeze"),
+    "diagonal_copy": copy_of_view("diagonal"), "narrow_copy": copy_of_view("narrow"), "as_strided_copy": copy_of_view("as_strided"),
+    "alias_copy": copy_of_view("alias"), "unfold_copy": copy_of_view("unfold"),
+    "float": convert_to(F32), "half": convert_to(F16), "bfloat16": convert_to(BF16), "int": convert_to(I32), "long": convert_to(I64),
+    "bool": convert_to(torch.bool),
+    "aminmax": aminmax, "max": extremum("amax", "argmax", "maximum"), "min": extremum("amin", "argmin", "minimum"),
+    "std_mean": moments("std"), "var_mean": moments("var"),
+    "repeat": repeat(False), "tile": repeat(True), "rot90": rot90, "outer": outer, "trace": trace, "dist": dist,
+    "nn.functional.normalize": normalize, "ldexp": ldexp, "nn.functional.glu": glu, "nn.functional.prelu": prelu,
+    "nn.functional.rms_norm": rms_norm, "diff": diff,
+    "hstack": stacked(torch.atleast_1d, lambda ts: 0 if ts[0].dim() == 1 else 1),
+    "vstack": stacked(torch.atleast_2d, lambda ts: 0), "dstack": stacked(torch.atleast_3d, lambda ts: 2),
+    "column_stack": stacked(lambda t: t.reshape(t.numel(), 1) if t.dim() <= 1 else t, lambda ts: 1),
+})
+ADAPTERS.update({name: view_then_copy for name in IDENTITY_VIEW_OPS})
+ADAPTERS.update({name: copies_of_views for name in MULTI_VIEW_OPS})
+
+
 def compare(got, want):
     """None if got matches the ATen CPU result, else a short description."""
+    if isinstance(want, (tuple, list)):
+        if not isinstance(got, (tuple, list)) or len(got) != len(want):
+            return "%r results, ATen %d" % (len(got) if isinstance(got, (tuple, list)) else type(got), len(want))
+        for i, (g, w) in enumerate(zip(got, want)):
+            bad = compare(g, w)
+            if bad is not None:
+                return "result %d: %s" % (i, bad)
+        return None
     if not isinstance(want, torch.Tensor):
         return "reference returned %r" % type(want)
     if got.dtype != want.dtype:
@@ -939,7 +1295,7 @@ def sweep(backend, names=None, db=None):
                         rec["unsupported"]["ATen raised"] = rec["unsupported"].get("ATen raised", 0) + 1
                         continue
                     try:
-                        got = view_then_copy(backend, s, op) if adapter is view_then_copy else adapter(backend, s)
+                        got = adapter(backend, s, op) if adapter in (view_then_copy, copies_of_views) else adapter(backend, s)
                     except Unsupported as e:
                         key = str(e)
                         rec["unsupported"][key] = rec["unsupported"].get(key, 0) + 1
