@@ -78,7 +78,7 @@ enum { ORC_NEG = 0, ORC_ABS, ORC_EXP, ORC_LOG, ORC_SQRT, ORC_SIGMOID, ORC_TANH, 
 enum { ORC_ADD = 0, ORC_MUL, ORC_DIV, ORC_MAXIMUM, ORC_EQ, ORC_SUB, ORC_MINIMUM, ORC_NE, ORC_LT, ORC_LE, ORC_GT, ORC_GE,
        ORC_LOGICAL_AND, ORC_LOGICAL_OR, ORC_LOGICAL_XOR, ORC_POW, ORC_BITWISE_AND, ORC_BITWISE_OR, ORC_BITWISE_XOR,
        ORC_ATAN2, ORC_FMOD, ORC_REMAINDER, ORC_HYPOT, ORC_COPYSIGN, ORC_LOGADDEXP, ORC_LOGADDEXP2, ORC_XLOGY, ORC_HEAVISIDE,
-       ORC_FMAX, ORC_FMIN, ORC_NEXTAFTER, ORC_GCD, ORC_LCM, ORC_SHIFT_LEFT, ORC_SHIFT_RIGHT };
+       ORC_FMAX, ORC_FMIN, ORC_NEXTAFTER, ORC_GCD, ORC_LCM, ORC_SHIFT_LEFT, ORC_SHIFT_RIGHT, ORC_FLOOR_DIVIDE, ORC_TRUNC_DIVIDE };
 enum { ORC_LEAKY_RELU = 0, ORC_ELU, ORC_CELU, ORC_SELU, ORC_SOFTPLUS, ORC_THRESHOLD, ORC_HARDSHRINK, ORC_SOFTSHRINK, ORC_LOGIT,
        ORC_NAN_TO_NUM, ORC_ROUND_DECIMALS, ORC_GELU_TANH };
 enum { ORC_ADDCMUL = 0, ORC_ADDCDIV, ORC_LERP };
@@ -375,6 +375,19 @@ int64_t int_pow(int64_t b, int64_t e) {
 }
 
 // greatest common divisor of the magnitudes (Euclid); gcd(0, 0) = 0
+// Floor of a / b in binary32: (a - fmod(a, b)) / b is an integer up to rounding; one is subtracted when the remainder
+// and the divisor differ in sign, the result is snapped to the integer next to it, a zero takes the quotient's sign,
+// and a zero divisor gives the IEEE quotient (an infinity or NaN).
+static float floor_quotient(float a, float b) {
+  if (b == 0.0f) return a / b;
+  const float mod = std::fmod(a, b);
+  float div = (a - mod) / b;
+  if (mod != 0.0f && ((b < 0.0f) != (mod < 0.0f))) div -= 1.0f;
+  if (div == 0.0f) return std::copysign(0.0f, a / b);
+  float fl = std::floor(div);
+  if (div - fl > 0.5f) fl += 1.0f;
+  return fl;
+}
 uint64_t gcd_mag(int64_t a, int64_t b) {
   uint64_t x = a < 0 ? 0 - (uint64_t)a : (uint64_t)a, y = b < 0 ? 0 - (uint64_t)b : (uint64_t)b;
   while (y) {
@@ -467,13 +480,13 @@ int orc_infer_binary(int op, const orc_tensor* a, const orc_tensor* b, int32_t* 
   const orc_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
-  if (op < ORC_ADD || op > ORC_SHIFT_RIGHT) return ORC_ERR_DTYPE;
+  if (op < ORC_ADD || op > ORC_TRUNC_DIVIDE) return ORC_ERR_DTYPE;
   if (op == ORC_DIV && !is_float(common)) res = ORC_F32;   // true division
   if (op == ORC_EQ || (op >= ORC_NE && op <= ORC_LOGICAL_XOR)) res = ORC_BOOL;   // comparison and logical families
   if (op == ORC_POW && common == ORC_BOOL) return ORC_ERR_DTYPE;                 // no bool power
   if (op >= ORC_BITWISE_AND && op <= ORC_BITWISE_XOR && is_float(common)) return ORC_ERR_DTYPE;
   if (op == ORC_ATAN2 && !is_float(common)) res = ORC_F32;
-  if ((op == ORC_FMOD || op == ORC_REMAINDER) && common == ORC_BOOL) return ORC_ERR_DTYPE;
+  if ((op == ORC_FMOD || op == ORC_REMAINDER || op == ORC_FLOOR_DIVIDE || op == ORC_TRUNC_DIVIDE) && common == ORC_BOOL) return ORC_ERR_DTYPE;
   if ((op == ORC_HYPOT || op == ORC_LOGADDEXP || op == ORC_LOGADDEXP2 || op == ORC_NEXTAFTER) && !is_float(common)) return ORC_ERR_DTYPE;
   if ((op == ORC_COPYSIGN || op == ORC_XLOGY) && !is_float(common)) res = ORC_F32;
   if (op == ORC_HEAVISIDE && a->dtype != b->dtype) return ORC_ERR_DTYPE;        // no promotion between the two
@@ -690,6 +703,13 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
 //             remainder: the one with the divisor's sign (fmod, plus the
 //             divisor when the signs differ and the value is not zero).
 //             bool is a dtype error; an integer zero divisor is ORC_ERR_SCALAR.
+//   floor_divide / trunc_divide (ATen's div with rounding_mode "floor" / "trunc"): the quotient rounded toward
+//             -infinity / toward zero, in the common dtype (integers stay integers; int32 wraps; bool is a dtype
+//             error; an integer zero divisor is ORC_ERR_SCALAR).  Floating operands follow ATen in binary32
+//             (bf16 / fp16 operands converted first, one rounding at the end): trunc is the truncated binary32
+//             quotient; floor is floor_quotient() above, the algorithm ATen shares with Python's float floor
+//             division, which starts from the exact fmod so that a quotient just below an integer is not
+//             rounded up to it by the division.
 //   hypot   : sqrt(a^2 + b^2) without intermediate overflow, +inf when either
 //             is infinite; logaddexp: log(e^a + e^b) as max + log1p(exp(-|a-b|)),
 //             equal infinities give themselves; logaddexp2: the base-2 form;
@@ -723,7 +743,7 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
   const float alpha32 = (float)alpha_d;
   const bool alpha_one = alpha_is_int ? (alpha_i == 1) : (alpha_f == 1.0);
   const int64_t n = numel(out);
-  if ((op == ORC_FMOD || op == ORC_REMAINDER) && !is_float(cd))             // an integer zero divisor anywhere: nothing is written
+  if ((op == ORC_FMOD || op == ORC_REMAINDER || op == ORC_FLOOR_DIVIDE || op == ORC_TRUNC_DIVIDE) && !is_float(cd))   // an integer zero divisor anywhere: nothing is written
     for (int64_t lin = 0; lin < n; ++lin) {
       int64_t idx[ORC_MAX_DIMS];
       unravel(lin, nd, sizes, idx);
@@ -747,6 +767,8 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
           put_flt(out, oo, rd, r);
           break;
         }
+        case ORC_TRUNC_DIVIDE: put_flt(out, oo, rd, (double)std::trunc(x.f / y.f)); break;   // the binary32 quotient, truncated
+        case ORC_FLOOR_DIVIDE: put_flt(out, oo, rd, (double)floor_quotient(x.f, y.f)); break;
         case ORC_HYPOT: put_flt(out, oo, rd, std::hypot(xd, yd)); break;
         case ORC_COPYSIGN: put_flt(out, oo, rd, std::copysign(xd, yd)); break;
         case ORC_LOGADDEXP: case ORC_LOGADDEXP2: {
@@ -856,6 +878,16 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
           int64_t r = y.i == -1 ? 0 : x.i % y.i;     // by -1 everything divides (and INT_MIN % -1 is not a C expression)
           if (op == ORC_REMAINDER && r != 0 && ((r < 0) != (y.i < 0))) r += y.i;
           put_int(out, oo, rd, r);
+          break;
+        }
+        case ORC_FLOOR_DIVIDE: case ORC_TRUNC_DIVIDE: {
+          int64_t q;
+          if (y.i == -1) q = (int64_t)(0 - (uint64_t)x.i);    // the most negative value wraps onto itself
+          else {
+            q = x.i / y.i;
+            if (op == ORC_FLOOR_DIVIDE && x.i % y.i != 0 && ((x.i < 0) != (y.i < 0))) --q;
+          }
+          put_int(out, oo, rd, q);
           break;
         }
         case ORC_HEAVISIDE: put_int(out, oo, rd, x.i == 0 ? y.i : (x.i > 0 ? 1 : 0)); break;
