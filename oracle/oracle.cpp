@@ -706,8 +706,9 @@ int orc_unary(int op, const orc_tensor* out, const orc_tensor* a) {
 //   floor_divide / trunc_divide (ATen's div with rounding_mode "floor" / "trunc"): the quotient rounded toward
 //             -infinity / toward zero, in the common dtype (integers stay integers; int32 wraps; bool is a dtype
 //             error; an integer zero divisor is ORC_ERR_SCALAR).  Floating operands follow ATen in binary32
-//             (bf16 / fp16 operands converted first, one rounding at the end): trunc is the truncated binary32
-//             quotient; floor is floor_quotient() above, the algorithm ATen shares with Python's float floor
+//             (bf16 / fp16 operands converted first): trunc truncates the quotient after it has been rounded to the
+//             common format, as ATen does on every device (5.99 / 1 in bf16 is 6, not 5); floor is
+//             floor_quotient() above, rounded to the common format once at the end, the algorithm ATen shares with Python's float floor
 //             division, which starts from the exact fmod so that a quotient just below an integer is not
 //             rounded up to it by the division.
 //   hypot   : sqrt(a^2 + b^2) without intermediate overflow, +inf when either
@@ -767,7 +768,9 @@ int orc_binary(int op, const orc_tensor* out, const orc_tensor* a, const orc_ten
           put_flt(out, oo, rd, r);
           break;
         }
-        case ORC_TRUNC_DIVIDE: put_flt(out, oo, rd, (double)std::trunc(x.f / y.f)); break;   // the binary32 quotient, truncated
+        case ORC_TRUNC_DIVIDE:                   // the quotient as the common format holds it, then truncated
+          put_flt(out, oo, rd, (double)std::trunc(round_to_float_dtype((double)(x.f / y.f), cd)));
+          break;
         case ORC_FLOOR_DIVIDE: put_flt(out, oo, rd, (double)floor_quotient(x.f, y.f)); break;
         case ORC_HYPOT: put_flt(out, oo, rd, std::hypot(xd, yd)); break;
         case ORC_COPYSIGN: put_flt(out, oo, rd, std::copysign(xd, yd)); break;

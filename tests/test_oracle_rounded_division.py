@@ -115,9 +115,10 @@ def test_against_aten_cpu_with_broadcasting_and_promotion(dt):
         want = torch.div(a, b, rounding_mode=mode)
         got = O.binary(op, a, b)
         assert got.dtype == want.dtype and got.shape == want.shape
-        if dt in (BF16, F16):
-            # ATen's CPU kernel rounds every step to the half format, the oracle evaluates in binary32 and rounds once:
-            # the integers can differ by one unit of the result's precision
+        if dt in (BF16, F16) and mode == "floor":
+            # ATen's kernel rounds every step of the floor algorithm to the half format, the oracle evaluates it in
+            # binary32 and rounds once (2.15625 // -0.02685546875 is -81, the stepwise bf16 evaluation says -82):
+            # quotients can differ by one, or in the last place
             assert ((got.float() - want.float()).abs() <= want.float().abs() * 2 ** -7 + 1).all()
             assert ((got.float() - want.float()).abs() == 0).float().mean() > 0.9
         else:
