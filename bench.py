@@ -119,7 +119,7 @@ def build_ops(torch, B):
     extra("elu_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary_param("elu", ob, xb, 1.0))
     extra("addcmul_f32", "f1", "ew_vec_kernel", n2 * 16, n2, lambda: B.tx_ternary("addcmul", of, xf, yf, tall[:N], 0.5))
     extra("lerp_f32_scalar_weight", "f1", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_ternary("lerp", of, xf, yf, None, 0.3))
-    for fourth in ("fmax", "remainder", "hypot", "logaddexp"):
+    for fourth in ("fmax", "remainder", "floor_divide", "hypot", "logaddexp"):
         extra(fourth + "_f32", "f1", "ew_vec_kernel", n2 * 12, n2, (lambda o: (lambda: B.tx_binary(o, of, xf, yf)))(fourth))
     extra("clamp_f32", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_clamp(of, xf, -0.5, 0.75))
     extra("clamp_bf16", "f1", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_clamp(ob, xb, -0.5, 0.75))

@@ -95,7 +95,7 @@ enum { TX_NEG = 0, TX_ABS, TX_EXP, TX_LOG, TX_SQRT, TX_SIGMOID, TX_TANH, TX_GELU
 enum { TX_ADD = 0, TX_MUL, TX_DIV, TX_MAXIMUM, TX_EQ, TX_SUB, TX_MINIMUM, TX_NE, TX_LT, TX_LE, TX_GT, TX_GE,
        TX_LOGICAL_AND, TX_LOGICAL_OR, TX_LOGICAL_XOR, TX_POW, TX_BITWISE_AND, TX_BITWISE_OR, TX_BITWISE_XOR, TX_ATAN2,
        TX_FMOD, TX_REMAINDER, TX_HYPOT, TX_COPYSIGN, TX_LOGADDEXP, TX_LOGADDEXP2, TX_XLOGY, TX_HEAVISIDE, TX_FMAX,
-       TX_FMIN, TX_NEXTAFTER, TX_GCD, TX_LCM, TX_SHIFT_LEFT, TX_SHIFT_RIGHT };
+       TX_FMIN, TX_NEXTAFTER, TX_GCD, TX_LCM, TX_SHIFT_LEFT, TX_SHIFT_RIGHT, TX_FLOOR_DIVIDE, TX_TRUNC_DIVIDE };
 enum { TX_SUM = 0, TX_MEAN, TX_AMAX, TX_ARGMAX, TX_PROD, TX_VAR, TX_AMIN, TX_ARGMIN, TX_STD, TX_ANY, TX_ALL,
        TX_LOGSUMEXP, TX_NANSUM, TX_NANMEAN, TX_COUNT_NONZERO, TX_NORM };
 
@@ -199,7 +199,8 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
  * MINIMUM EQ NE LT LE GT GE LOGICAL_AND LOGICAL_OR LOGICAL_XOR POW BITWISE_AND
  * BITWISE_OR BITWISE_XOR ATAN2 FMOD REMAINDER HYPOT COPYSIGN LOGADDEXP
  * LOGADDEXP2 XLOGY HEAVISIDE FMAX FMIN NEXTAFTER GCD LCM SHIFT_LEFT
- * SHIFT_RIGHT (TX_ADD and TX_SUB are accepted too, with alpha = 1).
+ * SHIFT_RIGHT FLOOR_DIVIDE TRUNC_DIVIDE (TX_ADD and TX_SUB are accepted too,
+ * with alpha = 1).
  *   MUL: bool AND, integers wrap.  DIV: true division, bool / integer pairs are
  *   computed and returned in fp32.  MAXIMUM / MINIMUM: NaN if either operand is
  *   NaN; on ties the first operand; bool OR / AND.
@@ -234,7 +235,17 @@ tx_status tx_sub(const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, d
  *   GCD / LCM: of the magnitudes, wrapped to the dtype (gcd(0, 0) = lcm(0, x) =
  *   0).  SHIFT_LEFT / SHIFT_RIGHT: a << b and the arithmetic a >> b; a count
  *   below 0 or at least the width gives 0, or -1 for a negative a shifted
- *   right.  int32 / int64 only (a bool beside an integer promotes). */
+ *   right.  int32 / int64 only (a bool beside an integer promotes).
+ *   FLOOR_DIVIDE / TRUNC_DIVIDE (Table 1, elementwise; ATen's div with a
+ *   rounding mode): the quotient rounded toward -infinity / toward zero, in
+ *   the common dtype (integers stay integers and wrap; two bools are
+ *   TX_ERR_DTYPE; an integer zero divisor is outside the contract, 0 is
+ *   written).  Floating operands are divided in binary32.  TRUNC truncates
+ *   the quotient after rounding it to the common dtype (in bf16, 5.99 / 1 is
+ *   6); FLOOR is rounded to the common dtype once at the end and starts from
+ *   the exact fmod, (a - fmod(a, b)) / b, so a
+ *   quotient just below an integer is not rounded up to it; zero results
+ *   carry the quotient's sign and x / 0 is the IEEE quotient. */
 tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_tensor* b, void* stream);
 
 /* out = min(max(x, lo), hi) with scalar bounds; has_lo / has_hi say which are
@@ -520,7 +531,7 @@ tx_status tx_tri(const tx_tensor* out, const tx_tensor* x, int64_t diagonal, int
 
 /* ------------------------------------------------------------------ host-only helpers */
 
-/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_SHIFT_RIGHT). */
+/* Result dtype and broadcast shape of a binary op (TX_ADD .. TX_TRUNC_DIVIDE). */
 tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_t* dtype, int32_t* ndim,
                           int64_t* sizes);
 /* Result dtype of where(cond, x, y). */

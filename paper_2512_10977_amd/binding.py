@@ -27,7 +27,7 @@ BINARY = {"add": 0, "mul": 1, "div": 2, "maximum": 3, "eq": 4, "sub": 5, "minimu
           "ge": 11, "logical_and": 12, "logical_or": 13, "logical_xor": 14, "pow": 15, "bitwise_and": 16, "bitwise_or": 17,
           "bitwise_xor": 18, "atan2": 19, "fmod": 20, "remainder": 21, "hypot": 22, "copysign": 23, "logaddexp": 24,
           "logaddexp2": 25, "xlogy": 26, "heaviside": 27, "fmax": 28, "fmin": 29, "nextafter": 30, "gcd": 31, "lcm": 32,
-          "bitwise_left_shift": 33, "bitwise_right_shift": 34}
+          "bitwise_left_shift": 33, "bitwise_right_shift": 34, "floor_divide": 35, "trunc_divide": 36}
 REDUCE = {"sum": 0, "mean": 1, "amax": 2, "argmax": 3, "prod": 4, "var": 5, "amin": 6, "argmin": 7, "std": 8, "any": 9,
           "all": 10, "logsumexp": 11, "nansum": 12, "nanmean": 13, "count_nonzero": 14, "norm": 15}
 

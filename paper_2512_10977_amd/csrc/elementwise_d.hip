@@ -117,7 +117,7 @@ struct SignbitInt {
 // ---------------------------------------------------------------------------
 // binary, floating common dtype
 // ---------------------------------------------------------------------------
-// fmod remainder hypot logaddexp logaddexp2 xlogy.  fmodf is exact and its result needs no more bits than the
+// fmod remainder floor_divide trunc_divide hypot logaddexp logaddexp2 xlogy.  fmodf is exact and its result needs no more bits than the
 // operands have, so remainder's one addition is the only rounding; the others go through binary64 for fp32.
 __device__ __forceinline__ float bin_heavy(int op, float a, float b, bool half) {
   switch (op) {
@@ -126,6 +126,18 @@ __device__ __forceinline__ float bin_heavy(int op, float a, float b, bool half) 
       float r = fmodf(a, b);
       if (r != 0.0f && ((r < 0.0f) != (b < 0.0f))) r += b;
       return r;
+    }
+    case TX_TRUNC_DIVIDE: return __builtin_truncf(a / b);         // (half formats: the caller rounds the quotient first)
+    case TX_FLOOR_DIVIDE: {
+      // (a - fmod(a, b)) / b is an integer up to rounding: a quotient just below an integer is not rounded up to it
+      if (b == 0.0f) return a / b;
+      const float mod = fmodf(a, b);
+      float div = (a - mod) / b;
+      if (mod != 0.0f && ((b < 0.0f) != (mod < 0.0f))) div -= 1.0f;
+      if (div == 0.0f) return __builtin_copysignf(0.0f, a / b);
+      float fl = __builtin_floorf(div);
+      if (div - fl > 0.5f) fl += 1.0f;
+      return fl;
     }
     case TX_HYPOT: {
       if (__builtin_fabsf(a) == __builtin_inff() || __builtin_fabsf(b) == __builtin_inff()) return __builtin_inff();
@@ -197,7 +209,10 @@ struct BinHeavyDyn {
   static constexpr int NIN = 2;
   int op, common;
   __device__ __forceinline__ float operator()(float a, float b) const {
-    return quantize(bin_heavy(op, quantize(a, common), quantize(b, common), common != TX_F32), common);
+    a = quantize(a, common);
+    b = quantize(b, common);
+    if (op == TX_TRUNC_DIVIDE) return __builtin_truncf(quantize(a / b, common));   // truncates the quotient the format holds
+    return quantize(bin_heavy(op, a, b, common != TX_F32), common);
   }
 };
 struct BinCheapDyn {
@@ -210,7 +225,7 @@ struct BinCheapDyn {
 };
 
 // ---------------------------------------------------------------------------
-// binary, integer / bool common dtype: fmod remainder heaviside fmax fmin gcd lcm shifts
+// binary, integer / bool common dtype: fmod remainder floor_divide trunc_divide heaviside fmax fmin gcd lcm shifts
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t gcd_mag(uint64_t x, uint64_t y) {
   while (y) {
@@ -236,6 +251,16 @@ struct BinIntOps {
         if (b == 0 || b == -1) r = 0;
         else r = w32 ? (int64_t)((int32_t)a % (int32_t)b) : a % b;
         if (op == TX_REMAINDER && r != 0 && ((r < 0) != (b < 0))) r += b;
+        break;
+      }
+      case TX_FLOOR_DIVIDE: case TX_TRUNC_DIVIDE: {
+        // a zero divisor is outside the contract (result 0); by -1 the quotient is the wrapping negation
+        if (b == 0) r = 0;
+        else if (b == -1) r = (int64_t)(0 - (uint64_t)a);
+        else {
+          r = w32 ? (int64_t)((int32_t)a / (int32_t)b) : a / b;
+          if (op == TX_FLOOR_DIVIDE && r * b != a && ((a < 0) != (b < 0))) --r;
+        }
         break;
       }
       case TX_HEAVISIDE: r = a == 0 ? b : (a > 0 ? 1 : 0); break;

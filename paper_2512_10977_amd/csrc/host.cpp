@@ -223,7 +223,7 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (a->ndim < 0 || a->ndim > TX_MAX_DIMS || b->ndim < 0 || b->ndim > TX_MAX_DIMS)
     return fail(TX_ERR_NDIM, "infer_binary: bad ndim");
   if (!dtype_valid(a->dtype) || !dtype_valid(b->dtype)) return fail(TX_ERR_DTYPE, "infer_binary: bad dtype code");
-  if (op < TX_ADD || op > TX_SHIFT_RIGHT) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
+  if (op < TX_ADD || op > TX_TRUNC_DIVIDE) return fail(TX_ERR_DTYPE, "unknown binary op %d", op);
   const tx_tensor* ops[2] = {a, b};
   int common = result_type(ops, 2);
   int res = common;
@@ -233,7 +233,8 @@ tx_status tx_infer_binary(int op, const tx_tensor* a, const tx_tensor* b, int32_
   if (op >= TX_BITWISE_AND && op <= TX_BITWISE_XOR && dtype_is_float(common))
     return fail(TX_ERR_DTYPE, "bitwise operators take integer and bool dtypes only");
   if (op == TX_ATAN2 && !dtype_is_float(common)) res = TX_F32;
-  if ((op == TX_FMOD || op == TX_REMAINDER) && common == TX_BOOL) return fail(TX_ERR_DTYPE, "fmod / remainder do not take two bool operands");
+  if ((op == TX_FMOD || op == TX_REMAINDER || op == TX_FLOOR_DIVIDE || op == TX_TRUNC_DIVIDE) && common == TX_BOOL)
+    return fail(TX_ERR_DTYPE, "fmod / remainder / floor_divide / trunc_divide do not take two bool operands");
   if ((op == TX_HYPOT || op == TX_LOGADDEXP || op == TX_LOGADDEXP2 || op == TX_NEXTAFTER) && !dtype_is_float(common))
     return fail(TX_ERR_DTYPE, "hypot / logaddexp / logaddexp2 / nextafter need a floating operand");
   if ((op == TX_COPYSIGN || op == TX_XLOGY) && !dtype_is_float(common)) res = TX_F32;

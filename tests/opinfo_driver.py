@@ -394,6 +394,14 @@ def binary(name, alpha_ok=False):
     return run
 
 
+def div(be, s):
+    _no_kwargs(s, ("rounding_mode",))
+    if len(s.args) != 1:
+        raise Unsupported("arguments")
+    op = {None: "div", "floor": "floor_divide", "trunc": "trunc_divide"}[s.kwargs.get("rounding_mode")]
+    return be.binary(op, _operand(s.input), _operand(s.args[0]))
+
+
 def clamp(be, s):
     bounds = dict(zip(("min", "max"), s.args))
     bounds.update(s.kwargs)
@@ -838,6 +846,7 @@ ADAPTERS = {
     "fmod": binary("fmod"), "remainder": binary("remainder"), "hypot": binary("hypot"), "copysign": binary("copysign"),
     "logaddexp": binary("logaddexp"), "logaddexp2": binary("logaddexp2"), "xlogy": binary("xlogy"),
     "heaviside": binary("heaviside"), "fmax": binary("fmax"), "fmin": binary("fmin"), "nextafter": binary("nextafter"),
+    "floor_divide": binary("floor_divide"), "div": div,
     "gcd": binary("gcd"), "lcm": binary("lcm"), "bitwise_left_shift": binary("bitwise_left_shift"),
     "bitwise_right_shift": binary("bitwise_right_shift"),
     "add": binary("add", True), "sub": binary("sub", True), "mul": binary("mul"), "true_divide": binary("div"),

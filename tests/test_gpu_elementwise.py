@@ -29,7 +29,8 @@ EXACT_UNARY = ("neg", "abs", "logical_not", "square", "sign", "floor", "ceil", "
 BINARY = ["add", "mul", "div", "maximum", "eq", "sub", "minimum", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or",
           "logical_xor", "pow", "bitwise_and", "bitwise_or", "bitwise_xor", "atan2", "fmod", "remainder", "hypot", "copysign",
           "logaddexp", "logaddexp2", "xlogy", "heaviside", "fmax", "fmin", "nextafter", "gcd", "lcm", "bitwise_left_shift",
-          "bitwise_right_shift"]
+          "bitwise_right_shift", "floor_divide", "trunc_divide"]
+DIVIDING = ("fmod", "remainder", "floor_divide", "trunc_divide")
 ULP_BINARY = ("div", "pow", "atan2", "remainder", "hypot", "logaddexp", "logaddexp2", "xlogy")
 COMPARE = ("eq", "ne", "lt", "le", "gt", "ge", "logical_and", "logical_or", "logical_xor")
 CAST_OK = lambda src, dst: not (src.is_floating_point and not dst.is_floating_point) and not (src != BOOL and dst == BOOL)
@@ -83,7 +84,7 @@ def nonzero_divisor(t):
 
 
 def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what=""):
-    if op in ("fmod", "remainder") and not a_cpu.dtype.is_floating_point and not b_cpu.dtype.is_floating_point:
+    if op in DIVIDING and not a_cpu.dtype.is_floating_point and not b_cpu.dtype.is_floating_point:
         nonzero_divisor(b_cpu)
     try:
         want = O.binary(op, a_cpu, b_cpu, alpha=alpha)
@@ -405,11 +406,11 @@ def test_fourth_batch_unary_full_size(op):
         assert check_unary(op, I.typed((4096, 4096), I64, seed=16)) == "vec"
 
 
-@pytest.mark.parametrize("op", ["fmod", "remainder", "hypot", "logaddexp", "xlogy", "nextafter", "fmax"])
+@pytest.mark.parametrize("op", ["fmod", "remainder", "hypot", "logaddexp", "xlogy", "nextafter", "fmax", "floor_divide", "trunc_divide"])
 def test_fourth_batch_binary_full_size(op):
     a, b = I.typed(FULL, F32, seed=17, specials=0.01), I.typed(FULL, F32, seed=18, specials=0.01)
     assert check_binary(op, a, b) == "vec"
-    if op in ("fmod", "remainder"):
+    if op in DIVIDING:
         # quotients up to 2^60: the remainder stays exact
         big = a[:1024] * 1e15
         check_binary(op, big, b[:1024], what="large quotients")
