@@ -2335,6 +2335,48 @@ int orc_take(const orc_tensor* out, const orc_tensor* input, const orc_tensor* i
   return ORC_OK;
 }
 
+// searchsorted(sorted_sequence, values, right) / bucketize: for every value the index at which it would be inserted
+// into its sequence so that the order is kept - the first position whose element is >= v (left) or > v (right).
+// A 1-D sequence serves every value; otherwise the sequence has the values' rank and leading dims and each row of
+// values is searched in the matching row.  The index is found by bisection of [0, n) with the midpoint
+// start + (end - start) / 2, moving right while !(element >= v) (left) or !(element > v) (right): on a sorted
+// sequence without NaN this is the count of elements below v (at most v); a NaN value lands at n, and on other
+// inputs the result is whatever these steps give.  Both dtypes must be equal and not bool; out is int64 or int32.
+int orc_searchsorted(const orc_tensor* out, const orc_tensor* seq, const orc_tensor* values, int right) {
+  int rc;
+  if ((rc = check_tensor(out)) || (rc = check_tensor(seq)) || (rc = check_tensor(values))) return rc;
+  if (seq->dtype != values->dtype || seq->dtype == ORC_BOOL) return ORC_ERR_DTYPE;
+  if (out->dtype != ORC_I64 && out->dtype != ORC_I32) return ORC_ERR_DTYPE;
+  if (seq->ndim < 1) return ORC_ERR_NDIM;
+  if (seq->ndim != 1) {
+    if (seq->ndim != values->ndim) return ORC_ERR_SHAPE;
+    for (int d = 0; d + 1 < seq->ndim; ++d)
+      if (seq->sizes[d] != values->sizes[d]) return ORC_ERR_SHAPE;
+  }
+  if (!same_shape(out, values->ndim, values->sizes)) return ORC_ERR_SHAPE;
+  const int64_t m = numel(values), n = seq->sizes[seq->ndim - 1];
+  const bool flt = is_float(seq->dtype);
+  for (int64_t lin = 0; lin < m; ++lin) {
+    int64_t idx[ORC_MAX_DIMS] = {0};
+    unravel(lin, values->ndim, values->sizes, idx);
+    const Val v = load_as(values, offset_of(values, idx), values->dtype);
+    int64_t sidx[ORC_MAX_DIMS] = {0};
+    if (seq->ndim != 1)
+      for (int d = 0; d + 1 < seq->ndim; ++d) sidx[d] = idx[d];
+    int64_t start = 0, end = n;
+    while (start < end) {
+      const int64_t mid = start + (end - start) / 2;
+      sidx[seq->ndim - 1] = mid;
+      const Val e = load_as(seq, offset_of(seq, sidx), seq->dtype);
+      const bool stop = flt ? (right ? e.f > v.f : e.f >= v.f) : (right ? e.i > v.i : e.i >= v.i);
+      if (!stop) start = mid + 1;
+      else end = mid;
+    }
+    store_int(out, offset_of(out, idx), start);
+  }
+  return ORC_OK;
+}
+
 // masked_select(x, mask): the elements of x (broadcast with the bool mask) where the mask is true, in logical
 // (row-major) order of the broadcast shape.  `out` is a 1-D buffer of x's dtype with room for them (its first
 // *count elements are written; a smaller buffer is a shape error and nothing is written).

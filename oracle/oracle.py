@@ -85,6 +85,7 @@ def lib():
         _lib.orc_scatter_add.argtypes = [P, ctypes.c_int64, P, P]
         _lib.orc_index_add.argtypes = [P, ctypes.c_int64, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int]
         _lib.orc_take.argtypes = [P, P, P]
+        _lib.orc_searchsorted.argtypes = [P, P, P, ctypes.c_int]
         _lib.orc_scatter_reduce.argtypes = [P, ctypes.c_int64, P, P, ctypes.c_int, ctypes.c_int]
         _lib.orc_index_put.argtypes = [P, ctypes.POINTER(P), ctypes.c_int32, P, ctypes.c_int]
         _lib.orc_masked_select.argtypes = [P, P, P, I64P]
@@ -396,6 +397,12 @@ def index_put_(self, indices, values, accumulate=False):
     arr = (ctypes.POINTER(OrcTensor) * max(1, len(ds)))(*[ctypes.pointer(d) for d in ds])
     _check(lib().orc_index_put(desc(self), arr, len(ds), desc(values), int(accumulate)))
     return self
+
+
+def searchsorted(sorted_sequence, values, right=False, out_int32=False):
+    out = torch.empty(values.shape, dtype=torch.int32 if out_int32 else torch.int64)
+    _check(lib().orc_searchsorted(desc(out), desc(sorted_sequence), desc(values), int(bool(right))))
+    return out
 
 
 def take(input, index, out=None):
