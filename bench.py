@@ -322,6 +322,11 @@ def build_ops(torch, B):
     tidx = torch.randint(-flat.numel(), flat.numel(), (16384 * W,), device=dev, dtype=I64, generator=g)
     otake = ogat.view(-1)
     extra("take_f32", "f3", "take_kernel", tidx.numel() * 16, tidx.numel(), lambda: B.tx_take(otake, src, tidx))
+    bounds = torch.randn((65536,), device=dev, generator=g).sort().values
+    bvals = torch.randn((4096, 4096), device=dev, generator=g)
+    obkt = torch.empty((4096, 4096), device=dev, dtype=I64)
+    extra("bucketize_f32[4096,4096]_in_65536", "f3", "searchsorted_kernel", bvals.numel() * 12 + 65536 * 4, bvals.numel(),
+          lambda: B.tx_searchsorted(obkt, bounds, bvals, False))
     cnt = torch.zeros((1,), device=dev, dtype=I64)
     osel1 = osel.view(-1)[: NS * W]
     nsel = int(mask.sum().item())

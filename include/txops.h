@@ -485,6 +485,22 @@ size_t tx_index_put_workspace_bytes(const tx_tensor* self, const tx_tensor* cons
  * empty input is TX_ERR_INDEX). */
 tx_status tx_take(const tx_tensor* out, const tx_tensor* input, const tx_tensor* index, void* stream);
 
+/* searchsorted / bucketize (Table 1, indexing operators): out[p] = the index
+ * at which values[p] would be inserted into its sorted sequence so that the
+ * order is kept - the first position whose element is >= the value (right =
+ * 0) or > the value (right != 0).  A 1-D sorted_sequence serves every value
+ * (bucketize's boundaries); otherwise it has the values' rank and leading
+ * dims and the rows are searched one by one.  The index comes from bisection
+ * of [0, n) with the midpoint start + (end - start) / 2, moving right while
+ * !(element >= value) (or !(element > value)): on a sorted sequence without
+ * NaN that is the count of elements below (at most) the value; a NaN value
+ * lands at n; on unsorted input the result is what these steps give.  All
+ * three are device tensors, any strides; the two inputs share one dtype that
+ * is not bool (TX_ERR_DTYPE), out is int64 or int32 with the values' shape
+ * (TX_ERR_SHAPE) and overlaps neither input (TX_ERR_OVERLAP).  No sorter
+ * argument; at most 2^31 values and sequence elements (TX_ERR_UNSUPPORTED). */
+tx_status tx_searchsorted(const tx_tensor* out, const tx_tensor* sorted_sequence, const tx_tensor* values, int right, void* stream);
+
 /* Data-dependent output sizes.  The caller passes `out` as a buffer with room
  * for `capacity` results and `count`, a one-element int64 device tensor; the
  * call writes the number of selected elements to `count` and the first

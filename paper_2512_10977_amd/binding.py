@@ -39,7 +39,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so
 EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
            "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_scan", "tx_scan_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
-           "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_masked_select",
+           "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_searchsorted", "tx_masked_select",
            "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_copy", "tx_flip", "tx_roll", "tx_tri", "tx_infer_where", "tx_infer_unary_dtype", "tx_unary_param", "tx_infer_unary_param_dtype", "tx_ternary", "tx_infer_ternary_dtype",
            "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
 
@@ -107,6 +107,7 @@ def lib():
         "tx_index_put_": ([P, ctypes.POINTER(P), ctypes.c_int32, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_index_put_workspace_bytes": ([P, ctypes.POINTER(P), ctypes.c_int32, P, ctypes.c_int], ctypes.c_size_t),
         "tx_take": ([P, P, P, V], ctypes.c_int32),
+        "tx_searchsorted": ([P, P, P, ctypes.c_int, V], ctypes.c_int32),
         "tx_masked_select": ([P, P, P, P, V, ctypes.c_size_t, V], ctypes.c_int32),
         "tx_masked_select_workspace_bytes": ([P, P, P, P], ctypes.c_size_t),
         "tx_nonzero": ([P, P, P, V, ctypes.c_size_t, V], ctypes.c_int32),
@@ -261,6 +262,10 @@ def tx_index_put_(self, indices, values, accumulate=False, ws=None, stream=None)
 
 def tx_take(out, input, index, stream=None):
     _check(lib().tx_take(desc(out), desc(input), desc(index), _stream(stream)))
+
+
+def tx_searchsorted(out, sorted_sequence, values, right=False, stream=None):
+    _check(lib().tx_searchsorted(desc(out), desc(sorted_sequence), desc(values), int(bool(right)), _stream(stream)))
 
 
 def tx_masked_select_workspace_bytes(out, count, x, mask):

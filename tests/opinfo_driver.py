@@ -130,6 +130,9 @@ class OracleBackend:
     def take(self, x, index):
         return self.O.take(x, index)
 
+    def searchsorted(self, seq, values, right, out_int32):
+        return self.O.searchsorted(seq, values, right, out_int32)
+
     def masked_select(self, x, m):
         return self.O.masked_select(x, m)
 
@@ -295,6 +298,11 @@ class LibraryBackend:
         self.B.tx_take(out, self.dev(x), self.dev(index))
         return out.cpu()
 
+    def searchsorted(self, seq, values, right, out_int32):
+        out = self._out(values.shape, I32 if out_int32 else I64)
+        self.B.tx_searchsorted(out, self.dev(seq), self.dev(values), right)
+        return out.cpu()
+
     def _select(self, out, nbytes, call):
         count = torch.zeros((1,), dtype=I64, device="cuda")
         call(out, count, self.B.workspace(nbytes(out, count)))
@@ -400,6 +408,19 @@ def div(be, s):
         raise Unsupported("arguments")
     op = {None: "div", "floor": "floor_divide", "trunc": "trunc_divide"}[s.kwargs.get("rounding_mode")]
     return be.binary(op, _operand(s.input), _operand(s.args[0]))
+
+
+def searchsorted(bucketize):
+    def run(be, s):
+        _no_kwargs(s, ("right", "out_int32", "side", "sorter"))
+        if s.kwargs.get("sorter") is not None:
+            raise Unsupported("sorter")
+        seq, values = (s.args[0], s.input) if bucketize else (s.input, s.args[0])
+        if not isinstance(values, torch.Tensor):
+            raise Unsupported("scalar value")
+        right = bool(s.kwargs.get("right", False)) or s.kwargs.get("side") == "right"
+        return be.searchsorted(_tensor_ok(seq), _tensor_ok(values), right, bool(s.kwargs.get("out_int32", False)))
+    return run
 
 
 def clamp(be, s):
@@ -846,7 +867,7 @@ ADAPTERS = {
     "fmod": binary("fmod"), "remainder": binary("remainder"), "hypot": binary("hypot"), "copysign": binary("copysign"),
     "logaddexp": binary("logaddexp"), "logaddexp2": binary("logaddexp2"), "xlogy": binary("xlogy"),
     "heaviside": binary("heaviside"), "fmax": binary("fmax"), "fmin": binary("fmin"), "nextafter": binary("nextafter"),
-    "floor_divide": binary("floor_divide"), "div": div,
+    "floor_divide": binary("floor_divide"), "div": div, "searchsorted": searchsorted(False), "bucketize": searchsorted(True),
     "gcd": binary("gcd"), "lcm": binary("lcm"), "bitwise_left_shift": binary("bitwise_left_shift"),
     "bitwise_right_shift": binary("bitwise_right_shift"),
     "add": binary("add", True), "sub": binary("sub", True), "mul": binary("mul"), "true_divide": binary("div"),
