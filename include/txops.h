@@ -577,7 +577,8 @@ const char* tx_last_path(void);
  * masked_select: "select-fused" (one pass with decoupled look-back instead of
  * the count, offsets and write passes).  binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
  * first; the workspace query then reports that form's size); tx_loss:
- * "loss-two-pass" likewise.  Requests that a path cannot
+ * "loss-two-pass" likewise.  searchsorted: "searchsorted" (every probe from
+ * memory, also where the first levels would be walked in LDS).  Requests that a path cannot
  * serve fall back to the automatic choice.  Process-wide; meant for A/B
  * profiling. */
 void tx_force_path(const char* name);

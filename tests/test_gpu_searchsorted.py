@@ -10,12 +10,17 @@ pytestmark = pytest.mark.gpu
 F32, BF16, F16, I32, I64 = torch.float32, torch.bfloat16, torch.float16, torch.int32, torch.int64
 
 
-def check(seq, vals, right=False, out_int32=False, out_view=None, what=""):
+def check(seq, vals, right=False, out_int32=False, out_view=None, what="", forced=None):
     want = O.searchsorted(seq, vals, right=right, out_int32=out_int32)
     out = torch.empty(vals.shape, dtype=I32 if out_int32 else I64, device="cuda") if out_view is None else out_view
-    B.tx_searchsorted(out, to_device_view(seq), to_device_view(vals), right)
+    B.tx_force_path(forced)
+    try:
+        B.tx_searchsorted(out, to_device_view(seq), to_device_view(vals), right)
+    finally:
+        B.tx_force_path(None)
     torch.cuda.synchronize()
-    assert B.tx_last_path() == ("searchsorted" if vals.numel() else "")
+    tree = seq.dim() == 1 and seq.numel() >= 2048 and vals.numel() >= 65536 and forced is None
+    assert B.tx_last_path() == (("searchsorted-tree" if tree else "searchsorted") if vals.numel() else "")
     assert torch.equal(out.cpu(), want), (what, seq.dtype, tuple(seq.shape), tuple(vals.shape), right)
 
 
@@ -84,3 +89,19 @@ def test_full_size_bucketize():
     vals = torch.randn((4096, 4096), generator=g)
     check(bounds, vals, False)
     check(bounds, vals, True, out_int32=True)
+    check(bounds, vals[:512], False, forced="searchsorted")
+
+
+@pytest.mark.parametrize("dt", [F32, BF16, F16, I32, I64])
+def test_lds_tree_takes_the_same_steps(dt):
+    """Lengths around the threshold and far from powers of two, ties, strided views, a ragged last tile, and unsorted
+    input, where only identical bisection steps give identical answers."""
+    g = torch.Generator().manual_seed(14)
+    for n in (2047, 2048, 2049, 3000, 4095, 65537):
+        seq = (torch.randn((n,), generator=g) * 30).to(dt).sort().values
+        vals = (torch.randn((65536 + 777,), generator=g) * 35).to(dt)
+        check(seq, vals, False)
+        check(seq, vals, True)
+    wide = (torch.randn((20000,), generator=g) * 30).to(dt)
+    check(wide, (torch.randn((300, 250), generator=g) * 35).to(dt).t(), False, what="unsorted, transposed values")
+    check(wide.sort().values[::2], (torch.randn((70000,), generator=g) * 35).to(dt), True, what="strided boundaries")
