@@ -23,7 +23,8 @@ MiB = 1 << 20
 # HBM bytes per launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE; the text summary under
 # profiles/ has the commands and the copy calibration: bytes = 2.0 x FETCH_SIZE KiB + 1.0 x WRITE_SIZE KiB).  An entry
 # is valid only for the kernel version it was measured on: remove it when that kernel changes.
-PMC_TRAFFIC_BYTES = {"index_select_f32": (2 * 2122786 + 4194457) * 1024}
+PMC_TRAFFIC_BYTES = {"index_select_f32": (2 * 2122786 + 4194457) * 1024,
+                     "gather_f32": (2 * 277623 + 16384) * 1024}
 
 
 def build_ops(torch, B):
@@ -348,51 +349,169 @@ def build_ops(torch, B):
     return ops
 
 
-def cpu_baseline(torch):
-    """The oracle on a bounded sample of the same step (same op classes, 1/8 .. 1/64 of each workload)."""
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(torch, budget_s=2.0):
+    """The oracle on a bounded slice of each of the five workloads, timed twice: with every host thread OpenMP
+    hands out, and with one thread.  Returns (summary for the headline line, per-workload table for the side file).
+    A workload's rate is its algorithmic bytes over its time; slices are cut along the outermost independent dim."""
     from oracle import oracle as O
     from paper_2512_10977_amd import inputs as I
-    F32, I64 = torch.float32, torch.int64
-    items = []
+    F32 = torch.float32
     a, b = I.broadcast_add_inputs(4096, 4096, 0)
-    items.append((4096 * 4096 * 4, lambda: O.binary("add", a, b)))
     x = I.typed((1024, 8192), F32, seed=1)
     y = I.typed((1024, 8192), F32, seed=2)
-    n = x.numel()
-    items.append((n * 8, lambda: O.unary("exp", x)))
-    items.append((n * 12, lambda: O.binary("add", x, y)))
     y2 = y.reshape(8192, 1024)
-    items.append((n * 12, lambda: O.binary("add", x.t(), y2)))          # transposed input, contiguous output
+    n = x.numel()
     r = I.reduction_input((8, 4096, 1024), F32, seed=2)
-    items.append((r.numel() * 4, lambda: O.reduce("sum", r, -1)))
-    items.append((r.numel() * 4, lambda: O.reduce("sum", r, 0)))
     s = I.softmax_logits((2048, 4096), F32, seed=3)
-    items.append((s.numel() * 8, lambda: O.softmax(s)))
     c = I.cumsum_input((256, 65536), F32, seed=3)
-    items.append((c.numel() * 8, lambda: O.cumsum(c)))
     src = r.view(-1, 256)[:65536]
     idx = I.uniform_indices(262144, 65536, seed=4)
-    items.append((262144 * (8 + 2048), lambda: O.index_select(src, 0, idx)))
     rows = I.zipf_rows(65536, 4096, 1.1, seed=4)
     dst = torch.zeros((4096, 256))
-    items.append((65536 * (1024 + 8) + 2 * 4096 * 1024, lambda: O.scatter_add_(dst, 0, rows.unsqueeze(1).expand(65536, 256), src)))
     m = I.bernoulli_mask((65536, 256), 0.3, seed=4)
-    items.append((65536 * 256 * 9, lambda: O.masked_fill(src, m, -1.0)))
-    # passes over the sample until about 10 s of CPU work are on the clock (the sample itself takes well under a second
-    # on 16 cores, too little to time)
-    total_bytes, passes = 0, 0
-    t0 = time.perf_counter()
-    while passes < 400 and time.perf_counter() - t0 < 10.0:
-        for nbytes, fn in items:
-            fn()
-            total_bytes += nbytes
-        passes += 1
-    dt = time.perf_counter() - t0
-    return {"value": total_bytes / dt / 1e9, "unit": "GB/s", "cores": O.num_threads(), "kind": "oracle",
-            "seconds": round(dt, 3), "passes": passes,
-            "sample": "repeated passes (about 10 s) of the CPU oracle over 11 operators of the step at 1/8-1/64 of the workload sizes "
-                      "(broadcast add full size; exp/add on [1024,8192]; sums on [8,4096,1024]; softmax [2048,4096]; "
-                      "cumsum [256,65536]; index_select 262144 rows; scatter_add 65536 rows; masked_fill [65536,256])"}
+    workloads = [
+        ("1 broadcast add", "full size [4096,1]+[1,4096]", [(4096 * 4096 * 4 + 2 * 4096 * 4, lambda: O.binary("add", a, b))]),
+        ("2 elementwise sweep", "1/8: exp, add, add with a transposed input on [1024,8192] f32",
+         [(n * 8, lambda: O.unary("exp", x)), (n * 12, lambda: O.binary("add", x, y)),
+          (n * 12, lambda: O.binary("add", x.t(), y2))]),
+        ("3 reductions", "1/8: sum over dim -1 and over dim 0 of [8,4096,1024] f32",
+         [(r.numel() * 4, lambda: O.reduce("sum", r, -1)), (r.numel() * 4, lambda: O.reduce("sum", r, 0))]),
+        ("4 softmax + cumsum", "1/16: softmax [2048,4096], cumsum [256,65536] f32",
+         [(s.numel() * 8, lambda: O.softmax(s)), (c.numel() * 8, lambda: O.cumsum(c))]),
+        ("5 indexing", "1/16: index_select 262144 rows, scatter_add 65536 Zipf rows into 4096, masked_fill [65536,256]",
+         [(262144 * (8 + 2048), lambda: O.index_select(src, 0, idx)),
+          (65536 * (1024 + 8) + 2 * 4096 * 1024, lambda: O.scatter_add_(dst, 0, rows.unsqueeze(1).expand(65536, 256), src)),
+          (65536 * 256 * 9, lambda: O.masked_fill(src, m, -1.0))]),
+    ]
+    all_threads = O.num_threads()
+    table = []
+    tot = {all_threads: [0, 0.0], 1: [0, 0.0]}
+    try:
+        for name, what, items in workloads:
+            row = {"workload": name, "sample": what}
+            for threads in (all_threads, 1):
+                O.set_num_threads(threads)
+                nbytes, passes = 0, 0
+                t0 = time.perf_counter()
+                while passes == 0 or (time.perf_counter() - t0 < budget_s and passes < 200):
+                    for item_bytes, fn in items:
+                        fn()
+                        nbytes += item_bytes
+                    passes += 1
+                dt = time.perf_counter() - t0
+                row["GB/s_%s" % ("1_thread" if threads == 1 else "all_threads")] = round(nbytes / dt / 1e9, 3)
+                row["s_per_pass_%s" % ("1_thread" if threads == 1 else "all_threads")] = round(dt / passes, 4)
+                tot[threads][0] += nbytes
+                tot[threads][1] += dt
+            table.append(row)
+    finally:
+        O.set_num_threads(all_threads)
+    summary = {"value": round(tot[all_threads][0] / tot[all_threads][1] / 1e9, 3), "unit": "GB/s", "cores": all_threads,
+               "kind": "oracle", "value_1_thread": round(tot[1][0] / tot[1][1] / 1e9, 3),
+               "seconds": round(tot[all_threads][1] + tot[1][1], 1), "nproc": os.cpu_count(), "cpu": cpu_model(),
+               "sample": "oracle over 1/8-1/16 slices of workloads 2-5 and all of workload 1, about %g s each at %d "
+                         "threads and at 1 thread; per-workload table in the side file" % (budget_s, all_threads)}
+    return summary, table
+
+
+# Kernel behind each dispatch path the step takes (paths are what the library reports for its last launch).
+PATH_KERNEL = {"vec": "ew_vec_kernel", "tile": "ew_tile_vec_kernel", "generic": "ew_generic_kernel",
+               "rows-wave": "reduce_rows_kernel", "rows-block": "reduce_rows_kernel", "rows-split": "reduce_rows_kernel",
+               "cols": "reduce_cols_kernel", "cols-split": "reduce_cols_kernel", "softmax-wave": "softmax_wave_kernel",
+               "scan-lookback-wide": "cumsum_lookback_kernel", "scan-lookback": "cumsum_lookback_kernel",
+               "scan-carry": "cumsum_carry_kernel", "index-select-rows": "index_select_rows_kernel",
+               "gather": "gather_kernel", "scatter-sort-rows": "seg_rows_kernel", "scatter-atomic": "scatter_add_atomic_kernel"}
+
+
+def op_row(op, ms):
+    gbps = op["bytes"] / (ms * 1e-3) / 1e9
+    return {"op": op["name"], "row": op["row"], "path": op.get("path", ""), "kernel": op["kernel"], "us": round(ms * 1e3, 2),
+            "GB/s": round(gbps, 1), "frac_of_peak": round(gbps / PEAK_GBPS, 4),
+            "Gelem/s": round(op["elems"] / (ms * 1e-3) / 1e9, 2), "bytes": op["bytes"]}
+
+
+def headline(result):
+    """The one JSON line the harness reads: short enough to survive a truncated log tail (the per-operator tables
+    go to the side file).  Raises if it grows past 1500 characters."""
+    keep = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+            "vs_baseline", "dtype", "data", "config", "frac_of_peak", "elements_per_s", "roofline", "cpu_baseline", "side_file")
+    line = json.dumps({k: result[k] for k in keep if k in result}, separators=(",", ":"))
+    if len(line) > 1500 or "\n" in line:
+        raise ValueError("headline JSON line is %d characters; the limit is 1500" % len(line))
+    return line
+
+
+def time_launches(torch, fn, count, warm):
+    """Average time in ms of `count` back-to-back launches (events on the launch stream), after `warm` warm-ups."""
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(count):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / count
+
+
+def measurement_detail(torch, B):
+    """Numbers beside the step: workload 1 with rotating and with one output buffer and as a single launch;
+    1 GiB probes (copy, pure read, pure write) that show what this GPU sustains on the simplest kernels."""
+    dev = "cuda"
+    F32 = torch.float32
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+    a1 = torch.randn((4096, 1), device=dev, generator=g)
+    b1 = torch.randn((1, 4096), device=dev, generator=g)
+    outs = [torch.empty((4096, 4096), device=dev) for _ in range(9)]
+    state = {"i": 0}
+    nb1 = 4096 * 4096 * 4 + 2 * 4096 * 4
+
+    def rotating():
+        state["i"] = (state["i"] + 1) % len(outs)
+        B.tx_add(outs[state["i"]], a1, b1, 1)
+
+    def rate(nbytes, ms):
+        return {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "frac_of_peak": round(nbytes / (ms * 1e-3) / 1e9 / PEAK_GBPS, 4)}
+
+    detail = {"timing": "HIP events around 27 back-to-back launches after 9 warm-ups, divided by 27; "
+                        "single launch = events around one launch after a device synchronisation, median of 9"}
+    w1 = {"rotating_9_outputs": rate(nb1, time_launches(torch, rotating, 27, 9)),
+          "one_output_buffer": rate(nb1, time_launches(torch, lambda: B.tx_add(outs[0], a1, b1, 1), 27, 9))}
+    singles = []
+    for _ in range(9):
+        torch.cuda.synchronize()
+        singles.append(time_launches(torch, rotating, 1, 0))
+    w1["single_launch"] = rate(nb1, sorted(singles)[4])
+    detail["workload_1_add[4096,1]+[1,4096]"] = w1
+    n = 1 << 28
+    x = torch.empty(n, device=dev, dtype=F32).normal_(generator=g)
+    y = torch.empty_like(x)
+    probes = {"tx_copy_f32_1GiB (1 read + 1 write)": rate(2 * n * 4, time_launches(torch, lambda: B.tx_copy(y, x), 10, 3)),
+              "device_memcpy_1GiB (1 read + 1 write)": rate(2 * n * 4, time_launches(torch, lambda: y.copy_(x), 10, 3))}
+    out0 = torch.empty((), device=dev)
+    ws = B.workspace(B.tx_reduce_workspace_bytes("sum", out0, x, None))
+    probes["tx_reduce_sum_all_f32_1GiB (pure read)"] = rate(n * 4, time_launches(
+        torch, lambda: B.tx_reduce("sum", out0, x, None, False, 1.0, ws), 10, 3))
+    ar = torch.randn((16384, 1), device=dev, generator=g)
+    br = torch.randn((1, 16384), device=dev, generator=g)
+    y2 = y.view(16384, 16384)
+    probes["tx_add_[16384,1]+[1,16384]_1GiB (pure write)"] = rate(n * 4, time_launches(
+        torch, lambda: B.tx_add(y2, ar, br, 1), 10, 3))
+    detail["probes_1GiB"] = probes
+    return detail
 
 
 def main():
@@ -401,10 +520,13 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the operators timed outside the step")
     ap.add_argument("--only", default="", help="comma-separated substrings: run only the operators whose name matches "
                                                "(for profiling single kernels; the JSON line then covers that subset)")
     ap.add_argument("--calibrate", action="store_true",
                     help="add a plain 1 GiB device-to-device copy to the step (known traffic, to scale profiler counters)")
+    ap.add_argument("--side-file", default=os.path.join("gpurun_out", "bench_per_op.json"),
+                    help="where the per-operator tables go (relative to the repository root)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: every operator here runs on a single GPU; --gpus %d is not supported "
@@ -418,7 +540,7 @@ def main():
     if args.only:
         pats = [p for p in args.only.split(",") if p]
         ops = [o for o in ops if any(p in o["name"] for p in pats)]
-    extras = [o for o in ops if o["extra"]]
+    extras = [] if args.no_extras else [o for o in ops if o["extra"]]
     ops = [o for o in ops if not o["extra"]]
     if args.calibrate:
         ca = torch.empty(1 << 28, device="cuda", dtype=torch.float32).normal_()
@@ -426,9 +548,17 @@ def main():
         ops.append(dict(name="calibration_copy_1GiB", row="-", kernel="device copy", bytes=2 << 30, elems=1 << 28,
                         fn=lambda: cb.copy_(ca), extra=False))
     torch.cuda.synchronize()
-    for _ in range(args.warmup):
+
+    def label(op):                                  # the path the dispatcher took, and the kernel behind it
+        if op["kernel"] != "device copy":
+            op["path"] = B.tx_last_path()
+            op["kernel"] = PATH_KERNEL.get(op["path"], op["kernel"])
+
+    for w in range(max(1, args.warmup)):
         for op in ops:
             op["fn"]()
+            if w == 0:
+                label(op)
     torch.cuda.synchronize()
     events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
               for _ in range(args.steps)]
@@ -444,49 +574,51 @@ def main():
     outside = []
     for op in extras:                        # alternatives the dispatcher did not choose: one warm-up, two timed launches
         op["fn"]()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        op["fn"]()
-        op["fn"]()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / 2
-        gbps = op["bytes"] / (ms * 1e-3) / 1e9
-        outside.append({"op": op["name"], "row": op["row"], "kernel": op["kernel"], "us": round(ms * 1e3, 2),
-                        "GB/s": round(gbps, 1), "frac_of_peak": round(gbps / PEAK_GBPS, 4),
-                        "Gelem/s": round(op["elems"] / (ms * 1e-3) / 1e9, 2), "bytes": op["bytes"]})
+        label(op)
+        outside.append(op_row(op, time_launches(torch, op["fn"], 2, 0)))
     step_bytes = sum(op["bytes"] for op in ops)
     step_elems = sum(op["elems"] for op in ops)
-    per_op = []
-    for j, op in enumerate(ops):
-        ms = sum(events[k][j][0].elapsed_time(events[k][j][1]) for k in range(args.steps)) / args.steps
-        gbps = op["bytes"] / (ms * 1e-3) / 1e9
-        per_op.append({"op": op["name"], "row": op["row"], "kernel": op["kernel"], "us": round(ms * 1e3, 2),
-                       "GB/s": round(gbps, 1), "frac_of_peak": round(gbps / PEAK_GBPS, 4),
-                       "Gelem/s": round(op["elems"] / (ms * 1e-3) / 1e9, 2), "bytes": op["bytes"]})
+    per_op = [op_row(op, sum(events[k][j][0].elapsed_time(events[k][j][1]) for k in range(args.steps)) / args.steps)
+              for j, op in enumerate(ops)]
+    for r in per_op:                         # stored counter readings: traffic and the rate in bytes actually moved
+        if r["op"] in PMC_TRAFFIC_BYTES:
+            t = PMC_TRAFFIC_BYTES[r["op"]]
+            r["hbm_traffic_bytes_counters"] = t
+            r["frac_of_peak_in_traffic_bytes"] = round(t / (r["us"] * 1e-6) / 1e9 / PEAK_GBPS, 4)
     dom = max(per_op, key=lambda r: r["us"])
     ms_step = wall / args.steps * 1e3
     value = step_bytes / (wall / args.steps) / 1e9
+    side = os.path.join(ROOT, args.side_file)
     result = {
         "metric": "achieved HBM GB/s (algorithmic bytes / time) over one pass of all operator classes on one GPU",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "all five operator workloads at full size: broadcast add [4096,1]+[1,4096]; elementwise "
-                               "sweep [8192,8192]; reductions x[64,4096,1024]; softmax [32768,4096] + cumsum "
-                               "[4096,65536]; indexing on src[1048576,256]", "ops_per_step": len(ops)},
+        "config": {"workload": "all five workloads at full size: add [4096,1]+[1,4096]; elementwise [8192,8192]; "
+                               "reductions [64,4096,1024]; softmax [32768,4096]; cumsum [4096,65536]; "
+                               "indexing on src[1048576,256]", "ops_per_step": len(ops)},
         "frac_of_peak": round(value / PEAK_GBPS, 4),
         "elements_per_s": round(step_elems / (wall / args.steps), 1),
         "roofline": {"bound": "hbm", "kernel": dom["kernel"], "op": dom["op"], "achieved": dom["GB/s"],
                      "peak": PEAK_GBPS, "unit": "GB/s", "frac": dom["frac_of_peak"],
                      "traffic": PMC_TRAFFIC_BYTES.get(dom["op"]), "algorithmic_bytes": dom["bytes"],
                      "avg_us": dom["us"]},
+        "side_file": args.side_file,
         "per_op": per_op,
         "per_op_outside_step": outside,
     }
+    if not args.only:
+        result["measurement_detail"] = measurement_detail(torch, B)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(torch)
-    print(json.dumps(result))
+        result["cpu_baseline"], result["cpu_baseline_per_workload"] = cpu_baseline(torch)
+    try:                                       # the tables: a file, never the line the harness parses
+        os.makedirs(os.path.dirname(side), exist_ok=True)
+        with open(side, "w") as f:
+            json.dump(result, f, indent=1)
+    except OSError as e:
+        print("could not write %s: %s" % (side, e), file=sys.stderr)
+    sys.stdout.flush()
+    print(headline(result), flush=True)
 
 
 if __name__ == "__main__":

@@ -579,8 +579,9 @@ const char* tx_last_path(void);
  * first; the workspace query then reports that form's size); tx_loss:
  * "loss-two-pass" likewise.  searchsorted: "searchsorted" (every probe from
  * memory, also where the first levels would be walked in LDS).  Requests that a path cannot
- * serve fall back to the automatic choice.  Process-wide; meant for A/B
- * profiling. */
+ * serve fall back to the automatic choice.  Per calling thread, like
+ * tx_last_error and tx_last_path (a thread's forced path affects only the
+ * calls that thread makes); meant for A/B profiling. */
 void tx_force_path(const char* name);
 
 const char* tx_strerror(tx_status status);

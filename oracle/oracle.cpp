@@ -2467,4 +2467,14 @@ int orc_num_threads(void) {
 #endif
 }
 
+// Sets the number of OpenMP threads later parallel regions use (for timing the
+// same code on one core and on all of them; results do not depend on it).
+void orc_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
 }  // extern "C"

@@ -132,6 +132,11 @@ def num_threads():
     return lib().orc_num_threads()
 
 
+def set_num_threads(n):
+    """Thread count of later calls (timing control only: one accumulation is never split across threads)."""
+    lib().orc_set_num_threads(int(n))
+
+
 # --------------------------------------------------------------------------- inference
 def infer_binary(op, a, b):
     dt, nd = ctypes.c_int32(), ctypes.c_int32()

@@ -13,7 +13,7 @@ namespace tx {
 namespace {
 thread_local char g_err[512] = "";
 thread_local const char* g_path = "";
-std::string g_forced;
+thread_local std::string g_forced;
 }  // namespace
 
 const char* dtype_name(int dt) {
