@@ -365,6 +365,28 @@ tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int6
 size_t tx_reduce_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
                                  int keepdim);
 
+/* tx_reduce for callers that cannot allocate device memory or must not have
+ * it allocated on their behalf (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, same kernels and
+ * same results as tx_reduce, but the partial results of a reduction that is
+ * split across workgroups go to a buffer built into the library instead of a
+ * caller workspace.  The call allocates and frees nothing.
+ *   - The buffer is TX_REDUCE_STATIC_SCRATCH_BYTES (4 MiB) of device memory per
+ *     GPU, part of the loaded library, held until the process ends.  A
+ *     reduction whose tx_reduce_workspace_bytes() exceeds it is refused with
+ *     TX_ERR_WORKSPACE before any launch (every all-dims reduction needs at
+ *     most 32 KiB).
+ *   - The buffer belongs to the device that is current when the call is made;
+ *     out, x and stream must belong to that device.
+ *   - Every call on one GPU shares that GPU's buffer: two calls may overlap
+ *     only if they are ordered on one stream; calls on different streams (or
+ *     from different threads) that overlap in time race on the partials.
+ *     Nothing in the buffer has to start at zero (the first pass writes every
+ *     partial the second one reads), so no clearing is done or needed. */
+#define TX_REDUCE_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+tx_status tx_reduce_static(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
+                           int keepdim, double correction, void* stream);
+
 /* softmax (is_log == 0) or log_softmax (is_log != 0) of x along `dim`.
  * Float dtypes only; out has x's shape and dtype, or fp32 for a half x.
  * m = max; softmax = exp(x-m)/sum exp(x-m); log_softmax = (x-m) - log sum.

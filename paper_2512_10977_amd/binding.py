@@ -36,7 +36,7 @@ STATUS = {0: "OK", -1: "NULL", -2: "NDIM", -3: "DTYPE", -4: "SHAPE", -5: "DIM", 
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtxops.so")
 
-EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes",
+EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_clamp_dtype", "tx_where", "tx_masked_fill", "tx_reduce", "tx_reduce_workspace_bytes", "tx_reduce_static",
            "tx_softmax", "tx_layer_norm", "tx_binary_cross_entropy", "tx_binary_cross_entropy_workspace_bytes", "tx_loss", "tx_loss_workspace_bytes", "tx_cumsum", "tx_cumsum_workspace_bytes", "tx_scan", "tx_scan_workspace_bytes", "tx_gather", "tx_index_select", "tx_scatter_add_",
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
            "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_searchsorted", "tx_masked_select",
@@ -85,6 +85,7 @@ def lib():
         "tx_reduce": ([ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int, ctypes.c_double, V, ctypes.c_size_t, V],
                       ctypes.c_int32),
         "tx_reduce_workspace_bytes": ([ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int], ctypes.c_size_t),
+        "tx_reduce_static": ([ctypes.c_int, P, P, I64P, ctypes.c_int32, ctypes.c_int, ctypes.c_double, V], ctypes.c_int32),
         "tx_softmax": ([P, P, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_layer_norm": ([P, P, ctypes.c_int32, P, P, ctypes.c_double, V], ctypes.c_int32),
         "tx_binary_cross_entropy": ([P, P, P, P, ctypes.c_int, V, ctypes.c_size_t, V], ctypes.c_int32),
@@ -336,6 +337,11 @@ def tx_reduce(op, out, x, dims=None, keepdim=False, correction=1.0, ws=None, str
     wp, wb = _ws(ws)
     _check(lib().tx_reduce(REDUCE[op], desc(out), desc(x), arr, n, int(keepdim), float(correction), wp, wb,
                            _stream(stream)))
+
+
+def tx_reduce_static(op, out, x, dims=None, keepdim=False, correction=1.0, stream=None):
+    arr, n = _dims(dims)
+    _check(lib().tx_reduce_static(REDUCE[op], desc(out), desc(x), arr, n, int(keepdim), float(correction), _stream(stream)))
 
 
 def tx_reduce_workspace_bytes(op, out, x, dims=None, keepdim=False):

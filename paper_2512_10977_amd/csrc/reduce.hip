@@ -1,5 +1,7 @@
 // tx_reduce: validation, planning and dispatch; instantiates the sum / mean /
 // var policies (reduce_b.hip holds prod / amax / argmax).
+#include <mutex>
+
 #include "reduce_impl.h"
 
 namespace tx {
@@ -195,6 +197,88 @@ tx_status build_plan(int op, const tx_tensor* x, const tx_tensor* out, const int
 using namespace tx;
 using namespace tx::red;
 
+static tx_status reduce_checks(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
+                               int keepdim) {
+  tx_status rc;
+  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(x, "x"))) return rc;
+  int32_t rd, nd;
+  int64_t shape[TX_MAX_DIMS];
+  if ((rc = tx_infer_reduce(op, x, dims, ndims, keepdim, &rd, &nd, shape))) return rc;
+  const bool widen = dtype_is_float(rd) && out->dtype == TX_F32 && op != TX_AMAX && op != TX_AMIN;
+  if (out->dtype != rd && !widen)
+    return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
+  if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the reduced shape");
+  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
+  if (partial_overlap(out, x) || (out->data == x->data && numel(out) && numel(x)))
+    return fail(TX_ERR_OVERLAP, "out overlaps the input");
+  return TX_OK;
+}
+
+namespace {
+
+// Scratch of the entry point that allocates nothing: one array per GPU, held until the process ends.  The name is a
+// host-side stand-in; the device address comes from hipGetSymbolAddress, once per device, and only that address is
+// handed to kernels.
+constexpr size_t kStaticScratchBytes = TX_REDUCE_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+tx_status static_scratch(void** ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(TX_ERR_LAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(TX_ERR_LAUNCH, "device ordinal %d is outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(TX_ERR_LAUNCH, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return TX_OK;
+}
+
+tx_status reduce_dispatch(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
+                          double correction, void* ws, size_t ws_bytes, void* stream) {
+  tx_status rc = reduce_checks(op, out, x, dims, ndims, keepdim);
+  if (rc) return rc;
+  set_path("");
+  Plan p;
+  if ((rc = build_plan(op, x, out, dims, ndims, keepdim, &p))) return rc;
+  if (p.nout == 0) return TX_OK;
+  if ((op == TX_AMAX || op == TX_ARGMAX || op == TX_AMIN || op == TX_ARGMIN) && p.nred == 0)
+    return fail(TX_ERR_EMPTY_REDUCTION, "amax / amin / argmax / argmin over an empty extent");
+  if (op == TX_NORM) {                                   // correction carries the exponent p
+    if (correction != correction) return fail(TX_ERR_SCALAR, "norm: the exponent is NaN");
+    if (p.nred == 0 && (correction < 0.0 || correction == __builtin_inf()))
+      return fail(TX_ERR_EMPTY_REDUCTION, "norm with an infinite or negative exponent over an empty extent");
+  }
+  hipStream_t s = as_stream(stream);
+  switch (op) {
+    case TX_NANSUM: return launch_nansum(false, p, x, out, correction, ws, ws_bytes, s);
+    case TX_NANMEAN: return launch_nansum(true, p, x, out, correction, ws, ws_bytes, s);
+    case TX_COUNT_NONZERO: return launch_count(p, x, out, correction, ws, ws_bytes, s);
+    case TX_NORM: return launch_norm(p, x, out, correction, ws, ws_bytes, s);
+    case TX_SUM: return launch_sum(false, p, x, out, correction, ws, ws_bytes, s);
+    case TX_MEAN: return launch_sum(true, p, x, out, correction, ws, ws_bytes, s);
+    case TX_VAR: return launch_var(p, x, out, correction, ws, ws_bytes, s);
+    case TX_PROD: return launch_prod(p, x, out, correction, ws, ws_bytes, s);
+    case TX_AMAX: return launch_amax(p, x, out, correction, ws, ws_bytes, s);
+    case TX_ARGMAX: return launch_argmax(p, x, out, correction, ws, ws_bytes, s);
+    case TX_STD: return launch_var(p, x, out, correction, ws, ws_bytes, s);          // Plan::aux asks for the square root
+    case TX_AMIN: return launch_amin(p, x, out, correction, ws, ws_bytes, s);
+    case TX_ARGMIN: return launch_argmin(p, x, out, correction, ws, ws_bytes, s);
+    case TX_ANY: case TX_ALL: return launch_anyall(p, x, out, correction, ws, ws_bytes, s);
+    case TX_LOGSUMEXP: return launch_logsumexp(p, x, out, correction, ws, ws_bytes, s);
+  }
+  return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
+}
+
+}  // namespace
+
 extern "C" {
 
 tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim, int32_t* dtype,
@@ -240,58 +324,24 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
   return TX_OK;
 }
 
-static tx_status reduce_checks(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
-                               int keepdim) {
-  tx_status rc;
-  if ((rc = check_tensor(out, "out")) || (rc = check_tensor(x, "x"))) return rc;
-  int32_t rd, nd;
-  int64_t shape[TX_MAX_DIMS];
-  if ((rc = tx_infer_reduce(op, x, dims, ndims, keepdim, &rd, &nd, shape))) return rc;
-  const bool widen = dtype_is_float(rd) && out->dtype == TX_F32 && op != TX_AMAX && op != TX_AMIN;
-  if (out->dtype != rd && !widen)
-    return fail(TX_ERR_DTYPE, "out dtype %s, expected %s", dtype_name(out->dtype), dtype_name(rd));
-  if (!same_sizes(out, nd, shape)) return fail(TX_ERR_SHAPE, "out does not have the reduced shape");
-  if (!no_internal_overlap(out)) return fail(TX_ERR_OVERLAP, "out has overlapping elements");
-  if (partial_overlap(out, x) || (out->data == x->data && numel(out) && numel(x)))
-    return fail(TX_ERR_OVERLAP, "out overlaps the input");
-  return TX_OK;
-}
-
 tx_status tx_reduce(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims, int keepdim,
                     double correction, void* ws, size_t ws_bytes, void* stream) {
+  return reduce_dispatch(op, out, x, dims, ndims, keepdim, correction, ws, ws_bytes, stream);
+}
+
+tx_status tx_reduce_static(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
+                           int keepdim, double correction, void* stream) {
   tx_status rc = reduce_checks(op, out, x, dims, ndims, keepdim);
   if (rc) return rc;
-  set_path("");
   Plan p;
-  // a dummy out for planning is not needed: out is validated above
   if ((rc = build_plan(op, x, out, dims, ndims, keepdim, &p))) return rc;
-  if (p.nout == 0) return TX_OK;
-  if ((op == TX_AMAX || op == TX_ARGMAX || op == TX_AMIN || op == TX_ARGMIN) && p.nred == 0)
-    return fail(TX_ERR_EMPTY_REDUCTION, "amax / amin / argmax / argmin over an empty extent");
-  if (op == TX_NORM) {                                   // correction carries the exponent p
-    if (correction != correction) return fail(TX_ERR_SCALAR, "norm: the exponent is NaN");
-    if (p.nred == 0 && (correction < 0.0 || correction == __builtin_inf()))
-      return fail(TX_ERR_EMPTY_REDUCTION, "norm with an infinite or negative exponent over an empty extent");
-  }
-  hipStream_t s = as_stream(stream);
-  switch (op) {
-    case TX_NANSUM: return launch_nansum(false, p, x, out, correction, ws, ws_bytes, s);
-    case TX_NANMEAN: return launch_nansum(true, p, x, out, correction, ws, ws_bytes, s);
-    case TX_COUNT_NONZERO: return launch_count(p, x, out, correction, ws, ws_bytes, s);
-    case TX_NORM: return launch_norm(p, x, out, correction, ws, ws_bytes, s);
-    case TX_SUM: return launch_sum(false, p, x, out, correction, ws, ws_bytes, s);
-    case TX_MEAN: return launch_sum(true, p, x, out, correction, ws, ws_bytes, s);
-    case TX_VAR: return launch_var(p, x, out, correction, ws, ws_bytes, s);
-    case TX_PROD: return launch_prod(p, x, out, correction, ws, ws_bytes, s);
-    case TX_AMAX: return launch_amax(p, x, out, correction, ws, ws_bytes, s);
-    case TX_ARGMAX: return launch_argmax(p, x, out, correction, ws, ws_bytes, s);
-    case TX_STD: return launch_var(p, x, out, correction, ws, ws_bytes, s);          // Plan::aux asks for the square root
-    case TX_AMIN: return launch_amin(p, x, out, correction, ws, ws_bytes, s);
-    case TX_ARGMIN: return launch_argmin(p, x, out, correction, ws, ws_bytes, s);
-    case TX_ANY: case TX_ALL: return launch_anyall(p, x, out, correction, ws, ws_bytes, s);
-    case TX_LOGSUMEXP: return launch_logsumexp(p, x, out, correction, ws, ws_bytes, s);
-  }
-  return fail(TX_ERR_DTYPE, "unknown reduce op %d", op);
+  const size_t need = plan_ws_bytes(p, acc_size(op, x->dtype));
+  if (need > kStaticScratchBytes)
+    return fail(TX_ERR_WORKSPACE, "tx_reduce_static: this reduction needs %zu bytes of scratch, the built-in buffer holds %zu; "
+                                  "use tx_reduce with a caller workspace", need, kStaticScratchBytes);
+  void* ws = nullptr;
+  if (need > 0 && (rc = static_scratch(&ws))) return rc;
+  return reduce_dispatch(op, out, x, dims, ndims, keepdim, correction, ws, kStaticScratchBytes, stream);
 }
 
 size_t tx_reduce_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
