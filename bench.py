@@ -78,6 +78,8 @@ def build_ops(torch, B):
     add("add_f32", "a3", "ew_vec_kernel", n2 * 12, n2, lambda: B.tx_add(of, xf, yf, 1))
     add("gelu_bf16", "a3", "ew_vec_kernel", n2 * 4, n2, lambda: B.tx_unary("gelu", ob, xb))
     add("gelu_f32", "a3", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("gelu", of, xf))
+    add("sigmoid_f32", "a3", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("sigmoid", of, xf))
+    add("tanh_f32", "a3", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_unary("tanh", of, xf))
     add("add_i64", "a3", "ew_vec_kernel", n2 * 24, n2, lambda: B.tx_add(oi, xi, yi, 1))
     add("eq_f32", "a3", "ew_vec_kernel", n2 * 9, n2, lambda: B.tx_binary("eq", obool, xf, yf))
     add("where_f32", "a3", "ew_vec_kernel", n2 * 13, n2, lambda: B.tx_where(of, cond, xf, yf))
@@ -578,8 +580,12 @@ def main():
         outside.append(op_row(op, time_launches(torch, op["fn"], 2, 0)))
     step_bytes = sum(op["bytes"] for op in ops)
     step_elems = sum(op["elems"] for op in ops)
-    per_op = [op_row(op, sum(events[k][j][0].elapsed_time(events[k][j][1]) for k in range(args.steps)) / args.steps)
-              for j, op in enumerate(ops)]
+    per_op = []
+    for j, op in enumerate(ops):
+        times = sorted(events[k][j][0].elapsed_time(events[k][j][1]) for k in range(args.steps))
+        row = op_row(op, sum(times) / args.steps)
+        row["us_min"], row["us_median"] = round(times[0] * 1e3, 2), round(times[len(times) // 2] * 1e3, 2)
+        per_op.append(row)
     for r in per_op:                         # stored counter readings: traffic and the rate in bytes actually moved
         if r["op"] in PMC_TRAFFIC_BYTES:
             t = PMC_TRAFFIC_BYTES[r["op"]]

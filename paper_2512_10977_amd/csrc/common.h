@@ -213,8 +213,7 @@ struct FastDiv {
     while ((1ull << s) < d) ++s;                       // s = ceil(log2 d)
     m = (uint32_t)(((1ull << 32) * ((1ull << s) - d)) / d + 1);
   }
-  __host__ __device__ __forceinline__ uint32_t div(uint32_t n) const {
-    if (d == 1) return n;
+  __host__ __device__ __forceinline__ uint32_t div(uint32_t n) const {   // d == 1: m = 0, s = 0 gives n without a branch
 #if defined(__HIP_DEVICE_COMPILE__)
     uint32_t t = __umulhi(n, m);
 #else

@@ -244,27 +244,102 @@ __device__ __forceinline__ void vec_fetch(const VecArgs<NOPS>& a, int o, int64_t
   }
 }
 
+// The same fetch for a tile that lies wholly inside the row, in two steps so that the loads of all operands are in
+// flight together: vec_issue starts the load (an operand with inner stride 0 loads its one element into x[0]),
+// vec_spread copies that element to the other slots.  Done in one step, the copies make the wave wait for the
+// stride-0 load before the next operand's load is even issued: two memory round trips in a row for a[r] + b[c].
+template <class In, int E, bool STREAM, int NOPS>
+__device__ __forceinline__ void vec_issue(const VecArgs<NOPS>& a, int o, int64_t base, int64_t i,
+                                          typename ValueOf<In>::type (&x)[E]) {
+  if constexpr (!std::is_void<In>::value) {
+    using EL = Elem<In>;
+    if (a.inner_stride[o] == 0) x[0] = EL::load(a.data[o], base, a.dtype[o]);
+    else EL::template load_vec<E, STREAM>(a.data[o], base + i, a.dtype[o], x);
+  }
+}
+template <class In, int E, int NOPS>
+__device__ __forceinline__ void vec_spread(const VecArgs<NOPS>& a, int o, typename ValueOf<In>::type (&x)[E]) {
+  if constexpr (!std::is_void<In>::value) {
+    if (a.inner_stride[o] == 0) {
+#pragma unroll
+      for (int e = 1; e < E; ++e) x[e] = x[0];
+    }
+  }
+}
+
 // STREAM: every input that is read along the inner dim is read exactly once (no broadcast dim anywhere), so
 // its loads are marked non-temporal.
 template <class F, int E, int U, bool STREAM>
 __global__ __launch_bounds__(kBlock) void ew_vec_kernel(const F f, const VecArgs<F::NIN + 1> a) {
   constexpr int NOPS = F::NIN + 1;
+  // Everything up to the first vector load is scalar work on kernel arguments.  It is written so that the argument
+  // reads have fixed offsets and no read waits for a branch on an earlier one (a chain of dependent scalar loads is a
+  // few hundred nanoseconds in which the workgroup has no memory request in flight, and a workgroup only moves a few
+  // KiB): up to two outer dims are decomposed by unrolled code (the host pads the unused ones with size 1, stride 0),
+  // more by the loop.
+  // Naming every argument the common path needs as the input of one empty asm statement makes the compiler fetch them
+  // together, ahead of the first branch (it would otherwise fetch each where it is first used, one round trip each).
+  asm volatile("" ::"s"(a.tiles_per_row.m), "s"(a.tiles_per_row.s), "s"(a.tiles_per_row.d), "s"(a.nouter), "s"(a.n0),
+               "s"(a.osize[0].m), "s"(a.osize[0].s), "s"(a.osize[0].d), "s"(a.osize[1].m), "s"(a.osize[1].s),
+               "s"(a.osize[1].d), "s"(a.data[0]), "s"(a.data[1]), "s"(a.ostride[0][0]), "s"(a.ostride[0][1]),
+               "s"(a.ostride[1][0]), "s"(a.ostride[1][1]), "s"(a.inner_stride[1]));
+  if constexpr (NOPS >= 3)
+    asm volatile("" ::"s"(a.data[2]), "s"(a.ostride[2][0]), "s"(a.ostride[2][1]), "s"(a.inner_stride[2]));
+  if constexpr (NOPS >= 4)
+    asm volatile("" ::"s"(a.data[3]), "s"(a.ostride[3][0]), "s"(a.ostride[3][1]), "s"(a.inner_stride[3]));
   uint32_t outer, tile;
   a.tiles_per_row.divmod(blockIdx.x, outer, tile);
   int64_t base[NOPS];
 #pragma unroll
   for (int o = 0; o < NOPS; ++o) base[o] = 0;
-  for (int d = a.nouter - 1; d >= 0; --d) {
-    uint32_t q, r;
-    a.osize[d].divmod(outer, q, r);
-    outer = q;
+  if (a.nouter <= 2) {
 #pragma unroll
-    for (int o = 0; o < NOPS; ++o) base[o] += (int64_t)r * a.ostride[o][d];
+    for (int d = 1; d >= 0; --d) {
+      uint32_t q, r;
+      a.osize[d].divmod(outer, q, r);
+      outer = q;
+#pragma unroll
+      for (int o = 0; o < NOPS; ++o) base[o] += (int64_t)r * a.ostride[o][d];
+    }
+  } else {
+    for (int d = a.nouter - 1; d >= 0; --d) {
+      uint32_t q, r;
+      a.osize[d].divmod(outer, q, r);
+      outer = q;
+#pragma unroll
+      for (int o = 0; o < NOPS; ++o) base[o] += (int64_t)r * a.ostride[o][d];
+    }
   }
-  const int64_t i0 = (int64_t)tile * (kBlock * E * U) + (int64_t)threadIdx.x * E;
+  const int64_t t0 = (int64_t)tile * (kBlock * E * U);
+  const int64_t i0 = t0 + (int64_t)threadIdx.x * E;
   typename ValueOf<typename F::In0>::type x0[U][E];
   typename ValueOf<typename F::In1>::type x1[U][E];
   typename ValueOf<typename F::In2>::type x2[U][E];
+  using EO = Elem<typename F::Out>;
+  if (t0 + kBlock * E * U <= a.n0) {                      // the whole tile lies inside the row (wave-uniform): no masks
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = i0 + (int64_t)u * kBlock * E;
+      vec_issue<typename F::In0, E, STREAM>(a, 1, base[1], i, x0[u]);
+      if constexpr (F::NIN >= 2) vec_issue<typename F::In1, E, STREAM>(a, 2, base[2], i, x1[u]);
+      if constexpr (F::NIN >= 3) vec_issue<typename F::In2, E, STREAM>(a, 3, base[3], i, x2[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      vec_spread<typename F::In0, E>(a, 1, x0[u]);
+      if constexpr (F::NIN >= 2) vec_spread<typename F::In1, E>(a, 2, x1[u]);
+      if constexpr (F::NIN >= 3) vec_spread<typename F::In2, E>(a, 3, x2[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t i = i0 + (int64_t)u * kBlock * E;
+      typename EO::value_t y[E];
+#pragma unroll
+      for (int e = 0; e < E; ++e) y[e] = apply(f, x0[u][e], x1[u][e], x2[u][e]);
+      EO::template store_vec<E>(a.data[0], base[0] + i, a.dtype[0], y);
+    }
+    return;
+  }
   int valid[U];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -277,7 +352,6 @@ __global__ __launch_bounds__(kBlock) void ew_vec_kernel(const F f, const VecArgs
       if constexpr (F::NIN >= 3) vec_fetch<typename F::In2, E, STREAM>(a, 3, base[3], i, valid[u], x2[u]);
     }
   }
-  using EO = Elem<typename F::Out>;
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     if (valid[u] == 0) continue;
@@ -645,10 +719,16 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     a.nouter = in;
     int64_t outer = 1;
     for (int d = 0; d < in; ++d) { a.osize[d] = FastDiv((uint32_t)it.size[d]); outer *= it.size[d]; }
+    for (int d = in; d < TX_MAX_DIMS - 1; ++d) {         // unused outer dims: size 1, stride 0 (the kernel's unrolled part reads two)
+      a.osize[d] = FastDiv(1);
+      for (int o = 0; o < NOPS; ++o) a.ostride[o][d] = 0;
+    }
     a.n0 = it.size[in];
-    // write-dominated case (every input is a broadcast that stays in cache): a wave's lifetime is one load
-    // round trip whatever it stores, so let it store four vectors instead of one
-    bool wide = !Shape<F>::dynamic;
+    // write-dominated case (every input is a broadcast that stays in cache): four vectors per lane.  A workgroup's
+    // lifetime is then dominated by its scalar set-up and one load round trip whatever it stores, and with one vector
+    // per lane the [4096,1] + [1,4096] add needs 16384 such lifetimes (14.8 us per launch against 12.3 us with four,
+    // graph replay so that the host's launch cost is out of the measurement; "vec-narrow" selects one vector)
+    bool wide = !Shape<F>::dynamic && strcmp(forced, "vec-narrow") != 0;
     for (int o = 1; o < NOPS; ++o) wide = wide && !a.stream[o];
     constexpr int UW = 4;
     const int u_rt = wide ? UW : U;

@@ -7,15 +7,25 @@
 
 namespace tx {
 
-// 1/x to ~1e-15 relative: hardware reciprocal estimate + one Newton step
+// a * b + k with the constant k read from a scalar register pair.  Left to itself the compiler turns a Horner step
+// with a constant addend into the two-operand multiply-add, whose addend register is overwritten, so it first
+// copies the constant into a fresh vector register pair: two moves per coefficient, which was 47 of the 105 vector
+// instructions per element of the fp32 gelu.  The three-operand form reads the constant where it is.
+__device__ __forceinline__ double fma_k(double a, double b, double k) {
+  double r;
+  asm("v_fma_f64 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "s"(k));
+  return r;
+}
+
+// 1/x to ~1e-14 relative: hardware reciprocal estimate (about 24 bits) + one Newton step
 __device__ __forceinline__ double rcp_d(double x) {
   double r = __builtin_amdgcn_rcp(x);
   return __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
 }
 
-// exp(y) = 2^n * (1 + p(r)), r = y - n ln2, |r| <= ln2/2; *p_out receives p(r)
-// (= expm1(r)), *n_out receives n.  Degree-10 Taylor polynomial: remainder
-// below 3e-13 relative.  y must be finite and within [-708, 708].
+// exp(y) = 2^n * (1 + p), r = y - n ln2, |r| <= ln2/2; *p_out receives p = expm1(r), *n_out receives n.
+// Degree-10 Taylor polynomial (remainder below 3e-13 relative) and a two-part ln 2: for the callers that subtract
+// afterwards (logaddexp near a + b = 0, pow through y log a).  y must be finite and within [-708, 708].
 __device__ __forceinline__ void exp_parts_d(double y, double* p_out, int* n_out) {
   const double kLog2e = 1.4426950408889634074, kLn2Hi = 6.93147180369123816490e-01,
                kLn2Lo = 1.90821492927058770002e-10;
@@ -23,15 +33,15 @@ __device__ __forceinline__ void exp_parts_d(double y, double* p_out, int* n_out)
   double r = __builtin_fma(-nf, kLn2Hi, y);
   r = __builtin_fma(-nf, kLn2Lo, r);
   double p = 1.0 / 3628800.0;
-  p = __builtin_fma(p, r, 1.0 / 362880.0);
-  p = __builtin_fma(p, r, 1.0 / 40320.0);
-  p = __builtin_fma(p, r, 1.0 / 5040.0);
-  p = __builtin_fma(p, r, 1.0 / 720.0);
-  p = __builtin_fma(p, r, 1.0 / 120.0);
-  p = __builtin_fma(p, r, 1.0 / 24.0);
-  p = __builtin_fma(p, r, 1.0 / 6.0);
-  p = __builtin_fma(p, r, 0.5);
-  p = __builtin_fma(p, r, 1.0);
+  p = fma_k(p, r, 1.0 / 362880.0);
+  p = fma_k(p, r, 1.0 / 40320.0);
+  p = fma_k(p, r, 1.0 / 5040.0);
+  p = fma_k(p, r, 1.0 / 720.0);
+  p = fma_k(p, r, 1.0 / 120.0);
+  p = fma_k(p, r, 1.0 / 24.0);
+  p = fma_k(p, r, 1.0 / 6.0);
+  p = fma_k(p, r, 0.5);
+  p = fma_k(p, r, 1.0);
   *p_out = p * r;
   *n_out = (int)nf;
 }
@@ -45,6 +55,40 @@ __device__ __forceinline__ double exp_d(double y) {  // y clamped by the caller
   return __builtin_fma(p, pow2_d(n), pow2_d(n));
 }
 
+// The same for results that are rounded to fp32 with nothing subtracted in between (sigmoid, tanh, gelu):
+// p = r + r^2 Q(r) with Q of degree QDEG, fitted at Chebyshev nodes to the exponential's relative error (degree 4:
+// below 3.7e-9; degree 5: below 6.1e-11, for tanh, whose small arguments see Q's own error; half an fp32 ulp is
+// 3e-8), and one constant for ln 2 (n stays below 2400, so its rounding error, 5.5e-17 n, is far below the
+// polynomial's).  y must be finite and within [-1600, 708].
+template <int QDEG> __device__ __forceinline__ void exp_short_parts_d(double y, double* p_out, int* n_out) {
+  const double kLog2e = 1.4426950408889634074, kLn2 = 6.93147180559945309417e-01;
+  const double nf = __builtin_rint(y * kLog2e);
+  const double r = __builtin_fma(-nf, kLn2, y);
+  double q;
+  if constexpr (QDEG == 4) {
+    q = 1.37513947303978708e-03;
+    q = fma_k(q, r, 8.36892165717010965e-03);
+    q = fma_k(q, r, 4.16695338312040170e-02);
+    q = fma_k(q, r, 1.66665184160031177e-01);
+    q = fma_k(q, r, 4.99999885906078634e-01);
+  } else {
+    q = 1.98264486625870186e-04;
+    q = fma_k(q, r, 1.39461602826869186e-03);
+    q = fma_k(q, r, 8.33343047100944950e-03);
+    q = fma_k(q, r, 4.16662683527592170e-02);
+    q = fma_k(q, r, 1.66666661600924665e-01);
+    q = fma_k(q, r, 5.00000007869999985e-01);
+  }
+  *p_out = __builtin_fma(r * r, q, r);
+  *n_out = (int)nf;
+}
+__device__ __forceinline__ double exp6_d(double y) {   // a result below the normal range goes to 0 gradually
+  double p;
+  int n;
+  exp_short_parts_d<4>(y, &p, &n);
+  return __builtin_ldexp(1.0 + p, n);
+}
+
 // log(a) for finite, positive, normal a: a = 2^e m with m in [sqrt(1/2), sqrt 2), log m = 2 atanh(z),
 // z = (m - 1) / (m + 1), |z| <= 0.1716: z (1 + w/3 + ... + w^7/15), w = z^2 (first dropped term below 4e-14 relative)
 __device__ __forceinline__ double log_d(double a) {
@@ -56,13 +100,13 @@ __device__ __forceinline__ double log_d(double a) {
   const double z = (m - 1.0) * rcp_d(m + 1.0);
   const double w = z * z;
   double p = 1.0 / 15.0;
-  p = __builtin_fma(p, w, 1.0 / 13.0);
-  p = __builtin_fma(p, w, 1.0 / 11.0);
-  p = __builtin_fma(p, w, 1.0 / 9.0);
-  p = __builtin_fma(p, w, 1.0 / 7.0);
-  p = __builtin_fma(p, w, 1.0 / 5.0);
-  p = __builtin_fma(p, w, 1.0 / 3.0);
-  p = __builtin_fma(p, w, 1.0);
+  p = fma_k(p, w, 1.0 / 13.0);
+  p = fma_k(p, w, 1.0 / 11.0);
+  p = fma_k(p, w, 1.0 / 9.0);
+  p = fma_k(p, w, 1.0 / 7.0);
+  p = fma_k(p, w, 1.0 / 5.0);
+  p = fma_k(p, w, 1.0 / 3.0);
+  p = fma_k(p, w, 1.0);
   const double ef = (double)e;
   return __builtin_fma(ef, kLn2Hi, __builtin_fma(ef, kLn2Lo, 2.0 * z * p));
 }
@@ -74,13 +118,13 @@ __device__ __forceinline__ double log1p_unit_d(double t) {
   const double z = t * rcp_d(2.0 + t);
   const double w = z * z;
   double p = 1.0 / 15.0;
-  p = __builtin_fma(p, w, 1.0 / 13.0);
-  p = __builtin_fma(p, w, 1.0 / 11.0);
-  p = __builtin_fma(p, w, 1.0 / 9.0);
-  p = __builtin_fma(p, w, 1.0 / 7.0);
-  p = __builtin_fma(p, w, 1.0 / 5.0);
-  p = __builtin_fma(p, w, 1.0 / 3.0);
-  p = __builtin_fma(p, w, 1.0);
+  p = fma_k(p, w, 1.0 / 13.0);
+  p = fma_k(p, w, 1.0 / 11.0);
+  p = fma_k(p, w, 1.0 / 9.0);
+  p = fma_k(p, w, 1.0 / 7.0);
+  p = fma_k(p, w, 1.0 / 5.0);
+  p = fma_k(p, w, 1.0 / 3.0);
+  p = fma_k(p, w, 1.0);
   return 2.0 * z * p;
 }
 
@@ -138,11 +182,12 @@ __device__ __forceinline__ float pow_f32(float af, float bf) {
   return odd ? -r : r;
 }
 
+// 1 / (1 + exp(-x)): the exponent is clamped to where the fp32 result has long been 1 or 0.  The clamp is one
+// median-of-three, which drops a NaN, so a NaN input is put back at the end.
 __device__ __forceinline__ float sigmoid_f32(float xf) {
-  if (xf != xf) return xf;
-  double x = (double)xf;
-  x = x > 708.0 ? 708.0 : (x < -708.0 ? -708.0 : x);
-  return (float)rcp_d(1.0 + exp_d(-x));
+  const double y = (double)__builtin_amdgcn_fmed3f(-xf, -40.0f, 110.0f);
+  const float r = (float)rcp_d(1.0 + exp6_d(y));
+  return xf != xf ? xf : r;
 }
 
 // x / (1 + exp(-x)) in binary64: for large negative x the fp32 sigmoid is subnormal and would lose the product's bits
@@ -154,52 +199,47 @@ __device__ __forceinline__ float silu_f32(float xf) {
   return (float)(x * rcp_d(1.0 + exp_d(m)));
 }
 
+// tanh|x| = em / (em + 2), em = expm1(2|x|) = 2^n (1 + p) - 1 from the exponential's own reduction: with n = 0 the
+// multiply-add returns p itself, so small arguments keep their relative accuracy without a branch.  The sign is copied
+// at the end (keeps -0); |x| is clamped at 20, far beyond where the fp32 result is 1 (a NaN passes the clamp).
 __device__ __forceinline__ float tanh_f32(float xf) {
-  if (xf != xf) return xf;
-  double y = 2.0 * (double)xf;
-  y = y > 60.0 ? 60.0 : (y < -60.0 ? -60.0 : y);      // tanh saturates to +-1 in fp32 well before
+  float ax = __builtin_fabsf(xf);
+  ax = ax > 20.0f ? 20.0f : ax;
   double p;
   int n;
-  exp_parts_d(y, &p, &n);
-  // em = expm1(y): exact polynomial form when n == 0, else 2^n (1+p) - 1 (no cancellation there)
-  double s = pow2_d(n);
-  double em = n == 0 ? p : __builtin_fma(p, s, s - 1.0);
-  double t = em * rcp_d(em + 2.0);
-  float r = (float)t;
-  return xf == 0.0f ? xf : r;                          // keeps -0
+  exp_short_parts_d<5>(2.0 * (double)ax, &p, &n);
+  const double s = pow2_d(n);
+  const double em = __builtin_fma(p, s, s - 1.0);
+  return __builtin_copysignf((float)(em * rcp_d(em + 2.0)), xf);
 }
 
-// gelu(x) = x * Phi(x), Phi(x) = erfc(-x / sqrt 2) / 2.  erfc(z) for z >= 0 is
-// exp(-z^2) * P(t) / (z + 1.5) with t = (z - 1.5) / (z + 1.5); the coefficients
-// come from fit_erfcx.py (max relative error 2.1e-11).
+// gelu(x) = x Phi(x), Phi(x) = erfc(-x / sqrt 2) / 2.  With z = |x| / sqrt 2, h = Phi(-|x|) = erfc(z) / 2 is
+// exp(-z^2) P(t) / (z + 3), t = (z - 3) / (z + 3) = 1 - 6 / (z + 3); P has degree 9 (relative error of h below 3.2e-9
+// for z <= 10.5, where the fp32 result has already underflowed to zero; fitted at Chebyshev nodes against 40-digit
+// values, the factor 1/2 folded in).  Then gelu(x) = g + max(x, 0) with g = gelu(-|x|) = -|x| h: for x >= 0 that is
+// x - x h = x (1 - h), and there is one rounding to fp32 at the end.  z is clamped at 40, where exp(-z^2) is exactly
+// 0: -inf * 0 gives the NaN that the IEEE evaluation of x Phi(x) gives at -inf; +inf is put back at the end; a NaN
+// input stays NaN through -|x| h whatever the clamp made of z.
 __device__ __forceinline__ float gelu_erf_f32(float xf) {
-  if (xf != xf) return xf;
-  double x = (double)xf;
-  double z = __builtin_fabs(x) * 0.70710678118654752440;
-  double zc = z > 26.0 ? 26.0 : z;                     // erfc(26) ~ 1e-296; beyond, Phi is 0 or 1 in fp32 anyway
-  double r = rcp_d(zc + 1.5);
-  double t = (zc - 1.5) * r;
-  double p = -4.48026131500465495e-06;
-  p = __builtin_fma(p, t, -7.46861071228703220e-06);
-  p = __builtin_fma(p, t, 1.83404688284764924e-05);
-  p = __builtin_fma(p, t, 5.22830653440947734e-05);
-  p = __builtin_fma(p, t, 9.80220151046439906e-06);
-  p = __builtin_fma(p, t, -1.35548154522782059e-04);
-  p = __builtin_fma(p, t, -2.62789064962181502e-04);
-  p = __builtin_fma(p, t, -4.25510922534018304e-05);
-  p = __builtin_fma(p, t, 8.86380580260421398e-04);
-  p = __builtin_fma(p, t, 1.77098141754734092e-03);
-  p = __builtin_fma(p, t, -8.10762765167988568e-04);
-  p = __builtin_fma(p, t, -9.46125727689550895e-03);
-  p = __builtin_fma(p, t, -8.11975334549758232e-03);
-  p = __builtin_fma(p, t, 4.77683625279125348e-02);
-  p = __builtin_fma(p, t, 7.56218045754478568e-02);
-  p = __builtin_fma(p, t, -5.07850010103267802e-01);
-  p = __builtin_fma(p, t, 9.64756249373572294e-01);
-  double half_erfc = z > 26.0 ? 0.0 : 0.5 * exp_d(-zc * zc) * p * r;    // Phi(-|x|)
-  double phi = x < 0.0 ? half_erfc : 1.0 - half_erfc;
-  // x = +-inf: +inf * 1 = +inf, -inf * 0 = NaN, as IEEE evaluation of x * Phi(x) gives
-  return (float)(x * phi);
+  const double x = (double)xf;
+  const double z = __builtin_fmin(__builtin_fabs(x) * 0.70710678118654752440, 40.0);
+  const double r = rcp_d(z + 3.0);
+  const double t = __builtin_fma(-6.0, r, 1.0);
+  double p = -1.63577015667414641e-04;
+  p = fma_k(p, t, -2.42564109869417211e-04);
+  p = fma_k(p, t, 1.54107519290801079e-03);
+  p = fma_k(p, t, -6.12201360389873044e-04);
+  p = fma_k(p, t, -1.34201827593240803e-02);
+  p = fma_k(p, t, 5.97642377890957935e-02);
+  p = fma_k(p, t, -1.55232970811848420e-01);
+  p = fma_k(p, t, 2.95114175237900955e-01);
+  p = fma_k(p, t, -4.41697244752364715e-01);
+  p = fma_k(p, t, 5.37003453557546528e-01);
+  const double m = __builtin_fmax(x, 0.0);                             // a NaN x: 0, and the product below is NaN
+  const double a = __builtin_fabs(x) * exp6_d(-z * z);                  // h = Phi(-|x|) = exp(-z^2) (p r); g = -|x| h
+  // gelu(x) has the sign of x everywhere, also where it rounds to zero; copying the sign settles -0 + +0
+  const float res = __builtin_copysignf((float)__builtin_fma(-a, p * r, m), xf);
+  return xf == __builtin_inff() ? xf : res;
 }
 
 // log(sigmoid(x)) = min(x, 0) - log1p(e), e = exp(-|x|) in (0, 1], composed in binary64 like the functions above.
@@ -263,7 +303,7 @@ __device__ __forceinline__ float bce_term_fast(float x, float t) {
 }
 
 // gelu for fp16 / bf16 results (8-11 significant bits): the same erfc form in plain fp32 with a degree-5
-// fit (relative error 5.5e-5, same fit_erfcx.py recipe) and the hardware exp2 / reciprocal.
+// fit at Chebyshev nodes (relative error 5.5e-5) and the hardware exp2 / reciprocal.
 __device__ __forceinline__ float gelu_erf_half(float x) {
   const float z = __builtin_fabsf(x) * 0.70710678118654752440f;
   const float zc = __builtin_fminf(z, 13.0f);          // exp(-169) is 0 in fp32
