@@ -81,7 +81,7 @@ enum {
   TX_ERR_EMPTY_REDUCTION = -7, /* amax / amin / argmax / argmin over an empty reduced extent */
   TX_ERR_SCALAR = -8,          /* non-integral alpha with an integer / bool result */
   TX_ERR_WORKSPACE = -9,       /* workspace missing or smaller than tx_*_workspace_bytes() */
-  TX_ERR_INDEX = -10,          /* reserved: index validation (indices are not checked on the device) */
+  TX_ERR_INDEX = -10,          /* an index value out of range: only with index validation on (tx_set_index_validation) */
   TX_ERR_LAUNCH = -11,         /* HIP reported an error at launch; see tx_last_error() */
   TX_ERR_UNSUPPORTED = -12     /* valid request that this build has no kernel for */
 };
@@ -181,7 +181,10 @@ tx_status tx_ternary(int op, const tx_tensor* out, const tx_tensor* a, const tx_
                      int64_t value_i, int value_is_int, void* stream);
 int32_t tx_infer_ternary_dtype(int op, const tx_tensor* a, const tx_tensor* b, const tx_tensor* c);
 
-/* out = a + alpha * b with broadcasting and type promotion.  alpha is given
+/* add (Table 1 "Elementwise", the paper's largest category; the operator every
+ * flat masked kernel of Appendix B is a variation of; accepted when its output
+ * equals the ATen CPU operator's, Section 3.2).
+ * out = a + alpha * b with broadcasting and type promotion.  alpha is given
  * both ways: alpha_is_int selects alpha_i, else alpha_f.  bool: a OR (alpha!=0
  * AND b).  Integer result: wrapping arithmetic, alpha must be integral
  * (TX_ERR_SCALAR otherwise).  Float result: alpha == 1 is one IEEE add;
@@ -257,12 +260,17 @@ tx_status tx_binary(int op, const tx_tensor* out, const tx_tensor* a, const tx_t
 tx_status tx_clamp(const tx_tensor* out, const tx_tensor* x, int has_lo, double lo_f, int64_t lo_i, int lo_is_int,
                    int has_hi, double hi_f, int64_t hi_i, int hi_is_int, void* stream);
 
-/* out = cond ? x : y.  cond must be bool; result dtype = promotion of x and y;
+/* where (Table 1 "Elementwise": a three-operand operator whose operands have
+ * three different roles; Section 3.2's criterion applied to the ATen operator
+ * `where(cond, x, y)`).
+ * out = cond ? x : y.  cond must be bool; result dtype = promotion of x and y;
  * the three operands broadcast together.  With no conversion the selected
  * element's bits are copied unchanged (NaN payloads survive). */
 tx_status tx_where(const tx_tensor* out, const tx_tensor* cond, const tx_tensor* x, const tx_tensor* y, void* stream);
 
-/* out = mask ? value : self.  mask is bool and broadcasts with self; out has
+/* masked_fill (Table 1 "Indexing & Selection": selection by a boolean mask, the
+ * case with a scalar payload; same acceptance criterion, Section 3.2).
+ * out = mask ? value : self.  mask is bool and broadcasts with self; out has
  * the broadcast shape and self's dtype.  value is cast to self's dtype
  * (floating value into an integer dtype truncates toward zero). */
 tx_status tx_masked_fill(const tx_tensor* out, const tx_tensor* self, const tx_tensor* mask, double value_f,
@@ -387,16 +395,23 @@ size_t tx_reduce_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* 
 tx_status tx_reduce_static(int op, const tx_tensor* out, const tx_tensor* x, const int64_t* dims, int32_t ndims,
                            int keepdim, double correction, void* stream);
 
-/* softmax (is_log == 0) or log_softmax (is_log != 0) of x along `dim`.
+/* softmax / log_softmax (Table 1 "Deep Learning", the category with the paper's
+ * lowest coverage; a row maximum, a row sum and an elementwise pass, the same
+ * row skeleton as the layer_norm listing of Appendix B).
+ * softmax (is_log == 0) or log_softmax (is_log != 0) of x along `dim`.
  * Float dtypes only; out has x's shape and dtype, or fp32 for a half x.
  * m = max; softmax = exp(x-m)/sum exp(x-m); log_softmax = (x-m) - log sum.
  * A slice that is all -inf, or holds +inf or NaN, is all NaN. */
 tx_status tx_softmax(const tx_tensor* out, const tx_tensor* x, int64_t dim, int is_log, void* stream);
 
-/* Inclusive prefix sum of x along `dim`.  bool / int32 / int64 x -> int64 out
+/* cumsum (Table 1 "Reduction": the scan member of the category; Section 3.3
+ * lists it among the operators whose loop-carried dependence the generated
+ * kernels handle with a sequential loop per row).
+ * Inclusive prefix sum of x along `dim`.  bool / int32 / int64 x -> int64 out
  * (exact, wrapping); float x keeps its dtype (or fp32 out for a half x),
  * accumulated in fp32.  ws / ws_bytes: device scratch of at least
- * tx_cumsum_workspace_bytes() (tile status words for the single-pass scan). */
+ * tx_cumsum_workspace_bytes() (tile status words for the single-pass scan; see
+ * tx_lookback_status for the one failure that scan can report afterwards). */
 tx_status tx_cumsum(const tx_tensor* out, const tx_tensor* x, int64_t dim, void* ws, size_t ws_bytes, void* stream);
 size_t tx_cumsum_workspace_bytes(const tx_tensor* out, const tx_tensor* x, int64_t dim);
 
@@ -417,10 +432,27 @@ tx_status tx_scan(int op, const tx_tensor* out, const tx_tensor* x, int64_t dim,
 size_t tx_scan_workspace_bytes(int op, const tx_tensor* out, const tx_tensor* x, int64_t dim);
 
 /* ------------------------------------------------------------------ indexing
- * (Table 1 "Indexing & Selection".)  Index tensors are int64 or int32 and are
- * NOT range-checked on the device: an index outside [0, extent) is undefined
- * behaviour.  There is no negative-index wrap-around.
+ * (Table 1 "Indexing & Selection".)  Index tensors are int64 or int32.  By
+ * default they are NOT range-checked: an index outside [0, extent) is
+ * undefined behaviour (an out-of-bounds access on the device), as on ATen's
+ * device backends.  There is no negative-index wrap-around except where a
+ * function says so (tx_index_put_, tx_take).
+ *
+ * Index validation is an opt-in mode.  With it on, tx_gather, tx_index_select,
+ * tx_scatter_add_, tx_scatter_reduce_, tx_index_add_, tx_index_put_ and tx_take
+ * first run one extra pass over the index tensor(s) on `stream`, synchronise
+ * the stream, and return TX_ERR_INDEX - before any data kernel is launched,
+ * nothing written - if a value lies outside the valid range ([0, extent), or
+ * [-extent, extent) where negative indices wrap); tx_last_error() names the
+ * value and its position.  The extra pass and the synchronisation make it a
+ * debugging mode: keep it off where time matters and inside graph capture.
+ * The switch is per calling thread; its initial state is off, or on when the
+ * environment variable TX_VALIDATE_INDICES is set to anything but "0".  The
+ * pass keeps its one flag word in the library image (no allocation); calls
+ * with validation on are serialised on that word.
  */
+void tx_set_index_validation(int on);
+int tx_get_index_validation(void);
 
 /* out[i...] = src[i... with coordinate `dim` replaced by index[i...]].
  * index.ndim == src.ndim; index.size(d) <= src.size(d) for d != dim; out has
@@ -585,6 +617,22 @@ tx_status tx_infer_reduce(int op, const tx_tensor* x, const int64_t* dims, int32
 /* Name of the kernel path the last call on this thread dispatched to
  * ("" if it launched nothing).  For tests and profiling. */
 const char* tx_last_path(void);
+
+/* The single-pass scans (tx_cumsum / tx_scan on paths "scan-lookback*") and the
+ * single-pass compaction ("select-fused") make each tile wait for its
+ * predecessors' status words.  The wait is bounded (2^24 polls); if it ever
+ * gives up, the tile continues with an empty prefix, the kernel still ends, and
+ * the error flag in the workspace header is set: the call has long returned
+ * TX_OK by then, and its output is wrong.  This query is how a caller finds
+ * out: it copies the 16-byte header of `ws` (the workspace that call was given)
+ * back on `stream`, synchronises the stream, and returns TX_OK, or
+ * TX_ERR_LAUNCH if the flag is set.  A workspace whose last user was not a
+ * look-back path carries no header tag and reports TX_OK.  Host-side cost: one
+ * small copy and a synchronisation - for tests and for callers that must know,
+ * not for the timed path.  What to do on TX_ERR_LAUNCH: run the call again (a
+ * predecessor that never publishes means the GPU lost a workgroup, not that
+ * the input was bad); the path "scan-carry" needs no waiting at all. */
+tx_status tx_lookback_status(const void* ws, void* stream);
 /* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
  * "vec", "tile", "generic".  cumsum along a contiguous dim: "scan-lookback"
  * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".

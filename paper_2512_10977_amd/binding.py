@@ -41,7 +41,8 @@ EXPORTS = ["tx_unary", "tx_add", "tx_sub", "tx_binary", "tx_clamp", "tx_infer_cl
            "tx_scatter_add_workspace_bytes", "tx_index_add_", "tx_index_add_workspace_bytes", "tx_scatter_reduce_", "tx_scatter_reduce_workspace_bytes",
            "tx_index_put_", "tx_index_put_workspace_bytes", "tx_take", "tx_searchsorted", "tx_masked_select",
            "tx_masked_select_workspace_bytes", "tx_nonzero", "tx_nonzero_workspace_bytes", "tx_infer_binary", "tx_copy", "tx_flip", "tx_roll", "tx_tri", "tx_infer_where", "tx_infer_unary_dtype", "tx_unary_param", "tx_infer_unary_param_dtype", "tx_ternary", "tx_infer_ternary_dtype",
-           "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error"]
+           "tx_infer_reduce", "tx_last_path", "tx_force_path", "tx_strerror", "tx_last_error",
+           "tx_set_index_validation", "tx_get_index_validation", "tx_lookback_status"]
 
 
 class TxError(RuntimeError):
@@ -125,6 +126,9 @@ def lib():
         "tx_ternary": ([ctypes.c_int, P, P, P, P, ctypes.c_double, ctypes.c_int64, ctypes.c_int, V], ctypes.c_int32),
         "tx_infer_ternary_dtype": ([ctypes.c_int, P, P, P], ctypes.c_int32),
         "tx_infer_reduce": ([ctypes.c_int, P, I64P, ctypes.c_int32, ctypes.c_int, I32P, I32P, I64P], ctypes.c_int32),
+        "tx_set_index_validation": ([ctypes.c_int], None),
+        "tx_get_index_validation": ([], ctypes.c_int),
+        "tx_lookback_status": ([V, V], ctypes.c_int32),
         "tx_last_path": ([], ctypes.c_char_p),
         "tx_force_path": ([ctypes.c_char_p], None),
         "tx_strerror": ([ctypes.c_int32], ctypes.c_char_p),
@@ -473,6 +477,19 @@ def tx_infer_reduce(op, x, dims=None, keepdim=False):
 
 def tx_last_path():
     return lib().tx_last_path().decode()
+
+
+def tx_set_index_validation(on):
+    lib().tx_set_index_validation(int(bool(on)))
+
+
+def tx_get_index_validation():
+    return bool(lib().tx_get_index_validation())
+
+
+def tx_lookback_status(ws, stream=None):
+    """Raises TxError(LAUNCH) if a look-back wait gave up in the last call that used `ws`; synchronises the stream."""
+    _check(lib().tx_lookback_status(ctypes.c_void_p(ws.data_ptr()), _stream(stream)))
 
 
 def tx_force_path(name):

@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libtxops.so")
 
-SOURCES = ["host.cpp", "iter.cpp", "elementwise.hip", "elementwise_b.hip", "elementwise_c.hip", "elementwise_d.hip", "elementwise_e.hip", "reduce.hip", "reduce_b.hip", "reduce_c.hip", "reduce_d.hip", "rowops.hip", "scanops.hip", "colops.hip", "norm.hip", "loss.hip", "indexing.hip", "select.hip", "searchops.hip", "shapeops.hip"]
+SOURCES = ["host.cpp", "iter.cpp", "elementwise.hip", "elementwise_b.hip", "elementwise_c.hip", "elementwise_d.hip", "elementwise_e.hip", "reduce.hip", "reduce_b.hip", "reduce_c.hip", "reduce_d.hip", "rowops.hip", "scanops.hip", "colops.hip", "norm.hip", "loss.hip", "indexing.hip", "select.hip", "searchops.hip", "shapeops.hip", "validate.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall",
          "-Wno-unused-function", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -41,6 +41,13 @@ tx_status fail(tx_status code, const char* fmt, ...);   // records the thread-lo
 void set_path(const char* name);                         // records the dispatched kernel path
 const char* forced_path();                               // "" when automatic
 tx_status check_launch(const char* what);                // hipGetLastError -> TX_ERR_LAUNCH
+// Header of a look-back workspace (single-pass scans, single-pass compaction): word 0 = ticket counter (low half) and
+// error flag (high half, set when a bounded wait gave up), word 1 = this tag, written by the clearing kernel.
+constexpr unsigned long long kLookbackMagic = 0x74784c6f6f6b6261ull;
+// Index validation (validate.hip): whether the calling thread asked for it, and the pass itself - range-checks every
+// value of `index` against [lo, hi) on the stream, synchronises it, and returns TX_OK or TX_ERR_INDEX.
+bool index_validation_on();
+tx_status validate_index(const tx_tensor* index, int64_t lo, int64_t hi, const char* what, hipStream_t stream);
 
 tx_status check_tensor(const tx_tensor* t, const char* name);
 inline int64_t numel(const tx_tensor* t) {

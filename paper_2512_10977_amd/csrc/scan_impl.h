@@ -136,9 +136,11 @@ template <> struct TileState<double> {
   }
 };
 
+// zeroes the header and every status word, and tags the header (second word) as a look-back workspace so that
+// tx_lookback_status can tell what it is reading
 __global__ void scan_clear_kernel(unsigned long long* ws, int64_t words) {
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < words) ws[i] = 0ull;
+  if (i < words) ws[i] = i == 1 ? kLookbackMagic : 0ull;
 }
 
 struct ScanArgs {
@@ -147,6 +149,7 @@ struct ScanArgs {
   char* ws;
   int64_t rows, len, xrow, orow;
   int64_t tiles_per_row, total_tiles;
+  int spin_limit;                               // polls of one predecessor's status word before the wait gives up
 };
 
 template <class OP, class Acc> __device__ __forceinline__ Acc wave_inclusive(Acc v) {
@@ -273,12 +276,12 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
         Acc val = kId;
         uint32_t flag = kPrefix;               // positions before the row start count as an empty prefix
         if (mine >= 0) {
-          int spins = 0;
-          do {
+          flag = kEmpty;
+          for (int spins = 0; spins < a.spin_limit; ++spins) {      // a limit of 0 (host-forced, for tests) gives up at once
             flag = TileState<Acc>::read(status, slot - t + mine, &val);
             if (flag != kEmpty) break;
             __builtin_amdgcn_s_sleep(2);
-          } while (++spins < kSpinLimit);
+          }
           if (flag == kEmpty) { hdr->error = 1; flag = kPrefix; val = kId; }
         }
         const unsigned long long has_prefix = __ballot(flag == kPrefix);
@@ -464,6 +467,7 @@ tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void*
       a.tiles_per_row = (p.len + tile - 1) / tile;
       a.total_tiles = a.tiles_per_row * p.rows;
     }
+    a.spin_limit = strcmp(forced_path(), "scan-lookback-giveup") ? kSpinLimit : 0;
     const int64_t words = (int64_t)((256 + (size_t)a.total_tiles * TileState<Acc>::words * 8) / 8);   // <= p.ws_bytes / 8
     hipLaunchKernelGGL(scan_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
                        (unsigned long long*)ws, words);

@@ -429,9 +429,9 @@ struct SelectHeader {                                               // first 256
   unsigned int ticket, error;
 };
 
-__global__ void select_clear_kernel(unsigned long long* ws, int64_t words) {
+__global__ void select_clear_kernel(unsigned long long* ws, int64_t words) {      // second word: the look-back tag
   const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i < words) ws[i] = 0ull;
+  if (i < words) ws[i] = i == 1 ? kLookbackMagic : 0ull;
 }
 
 template <int FES, int PES>
@@ -649,6 +649,7 @@ tx_status tx_take(const tx_tensor* out, const tx_tensor* input, const tx_tensor*
   if (n == 0) return TX_OK;
   if (numel(input) == 0) return fail(TX_ERR_INDEX, "take: index into an empty tensor");
   if (n >= (1ll << 31) || numel(input) >= (1ll << 31)) return fail(TX_ERR_UNSUPPORTED, "take: more than 2^31 elements");
+  if (index_validation_on() && (rc = validate_index(index, -numel(input), numel(input), "take", as_stream(stream)))) return rc;
   TakeArgs a;
   memset(&a, 0, sizeof(a));
   fill_dims(&a.shape, index->ndim, index->sizes);

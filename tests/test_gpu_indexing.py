@@ -233,6 +233,9 @@ def test_scatter_add_full_size(big_src):
     # materialised index, one Zipf draw per element (general path)
     full = I.zipf_rows(131072 * 256, 65536, 1.1, seed=9).reshape(131072, 256)
     check_scatter_add(dst_i, 0, full, src_i[:131072], what="int32 materialised")
+    # the same index with fp32 values: element keys, sorted, every run summed in position order; held to the
+    # tolerance and to bitwise run-to-run equality (check_scatter_add runs it twice)
+    assert check_scatter_add(dst, 0, full, big_src[:131072], what="fp32 materialised") == "scatter-sort-elem"
 
 
 def test_masked_fill_full_size(big_src):

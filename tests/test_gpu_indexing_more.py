@@ -141,7 +141,7 @@ def run_select(fn_bytes, fn, out, what):
     used = B.tx_last_path()
     torch.cuda.synchronize()
     if used == "select-fused":
-        assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
+        B.tx_lookback_status(ws)                       # raises if a bounded look-back wait gave up
     return int(count.item()), used
 
 

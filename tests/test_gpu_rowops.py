@@ -48,7 +48,7 @@ def check_cumsum(x_cpu, dim=-1, out_dtype=None, what=""):
         scale = (xd * xd).cumsum(dim if x_cpu.dim() else 0).sqrt() if x_cpu.dim() else xd.abs()
         assert_rel(out, want, 1e-5 if want.dtype == F32 else 1e-2, scale, what)
     if ws is not None and used.startswith("scan-lookback"):
-        assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
+        B.tx_lookback_status(ws)                       # raises if a bounded look-back wait gave up
     return used
 
 
@@ -267,6 +267,8 @@ def check_scan(op, x_cpu, dim=-1, out_dtype=None, what=""):
     B.tx_scan(op, out, x, dim, ws)
     used = B.tx_last_path()
     torch.cuda.synchronize()
+    if ws is not None and used.startswith("scan-lookback"):
+        B.tx_lookback_status(ws)                       # raises if a bounded look-back wait gave up
     what = "%s %s %s dim=%d %s [%s]" % (op, x_cpu.dtype, tuple(x_cpu.shape), dim, what, used)
     if not want.dtype.is_floating_point:
         assert_exact(out, want, what)
@@ -275,7 +277,7 @@ def check_scan(op, x_cpu, dim=-1, out_dtype=None, what=""):
     else:                                       # a logarithm: absolute error of a few fp32 roundings of values of order |max|
         assert_rel(out, want, 1e-5 if want.dtype == F32 else 1e-2, 1.0, what)
     if ws is not None and used.startswith("scan-lookback"):
-        assert ws[4:8].view(torch.int32).item() == 0, "look-back wait gave up"
+        B.tx_lookback_status(ws)                       # raises if a bounded look-back wait gave up
     return used
 
 

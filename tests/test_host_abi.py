@@ -187,3 +187,50 @@ def test_later_entry_points_infer_and_validate_on_the_host():
     assert B.tx_scan_workspace_bytes("cumsum", z(4, 65536), z(4, 65536), -1) == B.tx_cumsum_workspace_bytes(z(4, 65536), z(4, 65536), -1)
     assert B.tx_loss_workspace_bytes("mse", z(), z(64, 64), z(64, 64), "none", 1.0) == 0
     assert B.tx_loss_workspace_bytes("mse", z(), z(64, 64), z(64), "sum", 1.0) > B.tx_loss_workspace_bytes("mse", z(), z(64, 64), z(64, 64), "sum", 1.0)
+
+
+def test_index_validation_switch_follows_the_environment():
+    """The switch's initial state comes from TX_VALIDATE_INDICES (host logic only: no device call is made)."""
+    import subprocess
+    import sys
+    code = ("import sys; sys.path.insert(0, %r); from paper_2512_10977_amd import binding as B; "
+            "a = B.tx_get_index_validation(); B.tx_set_index_validation(not a); print(int(a), int(B.tx_get_index_validation()))" % ROOT)
+    for value, want in ((None, "0 1"), ("1", "1 0"), ("0", "0 1"), ("yes", "1 0"), ("", "0 1")):
+        env = dict(os.environ)
+        env.pop("TX_VALIDATE_INDICES", None)
+        if value is not None:
+            env["TX_VALIDATE_INDICES"] = value
+        out = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, check=True).stdout
+        assert out.strip() == want, (value, out)
+
+
+def test_sorted_scatter_refuses_two_to_the_31_entries():
+    """The sort-based paths decode positions with 32-bit magic-number divisions (dividends below 2^31): a larger index is
+    refused on the host, by the workspace query (0 bytes) and by the call (before any launch; the descriptors here
+    point at no real memory of that size)."""
+    big = 1 << 31
+    keep = []
+
+    def fake(shape, strides, dtype):
+        keep.append(torch.zeros(16, dtype=dtype))           # a buffer of its own, so that no operand overlaps another
+        d = B.desc(keep[-1])
+        d.ndim = len(shape)
+        for i, (n, s) in enumerate(zip(shape, strides)):
+            d.sizes[i], d.strides[i] = n, s
+        return d
+
+    lib = B.lib()
+    self_d = fake((4, 2), (2, 1), torch.float32)
+    idx_d = fake((big, 2), (0, 0), torch.int64)              # 2^32 element keys
+    src_d = fake((big, 2), (0, 0), torch.float32)
+    assert lib.tx_scatter_add_workspace_bytes(self_d, 0, idx_d, src_d, 1) == 0
+    ws = torch.zeros(1024, dtype=torch.uint8)
+    rc = lib.tx_scatter_add_(self_d, 0, idx_d, src_d, 1, ws.data_ptr(), 1024, None)
+    assert B.STATUS[rc] == "UNSUPPORTED", (rc, lib.tx_last_error())
+    assert b"2^31" in lib.tx_last_error()
+    rc = lib.tx_scatter_reduce_(self_d, 0, idx_d, src_d, B.SCATTER_REDUCE["amax"], 1, ws.data_ptr(), 1024, None)
+    assert B.STATUS[rc] == "UNSUPPORTED", (rc, lib.tx_last_error())
+    rows_d = fake((big, 2), (1, 0), torch.int64)             # row mode: 2^31 source rows
+    assert lib.tx_scatter_add_workspace_bytes(self_d, 0, rows_d, src_d, 1) == 0
+    rc = lib.tx_scatter_add_(self_d, 0, rows_d, src_d, 1, ws.data_ptr(), 1024, None)
+    assert B.STATUS[rc] == "UNSUPPORTED", (rc, lib.tx_last_error())
