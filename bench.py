@@ -93,6 +93,21 @@ def build_ops(torch, B):
     add("add_f32_transposed", "a5", "ew_tile_kernel", n2 * 12, n2, lambda: B.tx_add(of, xf.t(), yf, 1))
     add("mul_bf16_transposed", "a5", "ew_tile_kernel", n2 * 6, n2, lambda: B.tx_binary("mul", ob, xb.t(), xb))
 
+    def forced(path, fn):                 # the same call with a dispatch path forced (alternatives, for A/B measurements)
+        def run():
+            B.tx_force_path(path)
+            try:
+                fn()
+            finally:
+                B.tx_force_path(None)
+        return run
+
+    # alternatives of kernels in the step, timed outside it: what each design choice is measured against
+    extra("add_f32_transposed_via_generic_path", "a5", "ew_generic_kernel", n2 * 12, n2,
+          forced("generic", lambda: B.tx_add(of, xf.t(), yf, 1)))
+    extra("add_f32_plain_cached_loads", "a3", "ew_vec_kernel", n2 * 12, n2, forced("vec-cached", lambda: B.tx_add(of, xf, yf, 1)))
+    extra("add_bcast_f32_one_vector_per_lane x8", "a3", "ew_vec_kernel", REP1 * (4096 * 4096 * 4 + 2 * 4096 * 4), REP1 * 4096 * 4096,
+          forced("vec-narrow", f_bcast))
     # data-moving shape operators, timed outside the step
     extra("copy_f32_contiguous", "f1", "ew_vec_kernel", n2 * 8, n2, lambda: B.tx_copy(of, xf))
     extra("copy_f32_to_bf16", "f1", "ew_vec_kernel", n2 * 6, n2, lambda: B.tx_copy(ob, xf))
@@ -182,6 +197,10 @@ def build_ops(torch, B):
     osf, osb = torch.empty(S, device=dev), torch.empty(S, device=dev, dtype=BF16)
     add("softmax_f32", "a10", "softmax_wave_kernel", ns * 8, ns, lambda: B.tx_softmax(osf, sf, -1, False))
     add("log_softmax_bf16", "a10", "softmax_wave_kernel", ns * 4, ns, lambda: B.tx_softmax(osb, sb, -1, True))
+    extra("softmax_f32_wave_per_row", "a10", "softmax_wave_kernel", ns * 8, ns,
+          forced("softmax-wave", lambda: B.tx_softmax(osf, sf, -1, False)))
+    extra("log_softmax_bf16_wave_per_row", "a10", "softmax_wave_kernel", ns * 4, ns,
+          forced("softmax-wave", lambda: B.tx_softmax(osb, sb, -1, True)))
     # fused row-normalisation and loss operators (Appendix B.3, B.1), timed outside the step; the softmax
     # tensors double as inputs (layer_norm) and the sweep tensors as probabilities (binary_cross_entropy)
     lw, lb = randn((S[1],)), randn((S[1],))
@@ -348,6 +367,17 @@ def build_ops(torch, B):
     wsn = B.workspace(B.tx_nonzero_workspace_bytes(onz, cnt, sparse))
     extra("nonzero_f32_p0.3", "f3", "select_write_kernel", NS * W * 4 + nsel * 16, NS * W,
           lambda: B.tx_nonzero(onz, cnt, sparse, wsn))
+    # 1 GiB probes: the simplest kernels of the library on known traffic (what a copy, a pure read and a pure write sustain)
+    pn = 1 << 28
+    px1 = rf.view(-1)[:pn]
+    py1 = osel.view(-1)[:pn]
+    extra("probe_copy_f32_1GiB", "-", "ew_vec_kernel", 2 * pn * 4, pn, lambda: B.tx_copy(py1, px1))
+    pout0 = torch.empty((), device=dev)
+    pws = B.workspace(B.tx_reduce_workspace_bytes("sum", pout0, px1, None))
+    extra("probe_read_sum_f32_1GiB", "-", "reduce_rows_kernel", pn * 4, pn, lambda: B.tx_reduce("sum", pout0, px1, None, False, 1.0, pws))
+    par, pbr = randn((16384, 1)), randn((1, 16384))
+    py2 = py1.view(16384, 16384)
+    extra("probe_write_bcast_add_f32_1GiB", "-", "ew_vec_kernel", pn * 4, pn, lambda: B.tx_add(py2, par, pbr, 1))
     return ops
 
 
@@ -432,7 +462,7 @@ PATH_KERNEL = {"vec": "ew_vec_kernel", "tile": "ew_tile_vec_kernel", "generic": 
                "rows-wave": "reduce_rows_kernel", "rows-block": "reduce_rows_kernel", "rows-split": "reduce_rows_kernel",
                "cols": "reduce_cols_kernel", "cols-split": "reduce_cols_kernel", "softmax-wave": "softmax_wave_kernel",
                "scan-lookback-wide": "cumsum_lookback_kernel", "scan-lookback": "cumsum_lookback_kernel",
-               "scan-carry": "cumsum_carry_kernel", "index-select-rows": "index_select_rows_kernel",
+               "scan-carry": "cumsum_carry_kernel", "softmax-row": "softmax_row_kernel", "index-select-rows": "index_select_rows_kernel",
                "gather": "gather_kernel", "scatter-sort-rows": "seg_rows_kernel", "scatter-atomic": "scatter_add_atomic_kernel"}
 
 
@@ -574,10 +604,10 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     outside = []
-    for op in extras:                        # alternatives the dispatcher did not choose: one warm-up, two timed launches
+    for op in extras:                        # alternatives the dispatcher did not choose: one warm-up, four timed launches
         op["fn"]()
         label(op)
-        outside.append(op_row(op, time_launches(torch, op["fn"], 2, 0)))
+        outside.append(op_row(op, time_launches(torch, op["fn"], 4, 0)))
     step_bytes = sum(op["bytes"] for op in ops)
     step_elems = sum(op["elems"] for op in ops)
     per_op = []

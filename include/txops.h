@@ -633,14 +633,21 @@ const char* tx_last_path(void);
  * predecessor that never publishes means the GPU lost a workgroup, not that
  * the input was bad); the path "scan-carry" needs no waiting at all. */
 tx_status tx_lookback_status(const void* ws, void* stream);
+
 /* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
- * "vec", "tile", "generic".  cumsum along a contiguous dim: "scan-lookback"
- * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry".
+ * "vec", "tile", "generic"; on the vec path "vec-cached" (plain instead of
+ * non-temporal loads) and "vec-narrow" (one vector per lane where every input
+ * is a broadcast).  cumsum along a contiguous dim: "scan-lookback"
+ * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry",
+ * and "scan-lookback-giveup" (the look-back kernel with a poll limit of zero:
+ * every wait gives up at once, for testing tx_lookback_status).
  * Reduction with lanes along the kept dim: "cols-nv1", "cols-nv2", "cols-nv4"
  * (vectors per thread).  Integer scatter_add_: "scatter-atomic" (one atomic
  * per element even when a workspace is given).  scatter_reduce_:
  * "scatter-reduce-sort" (element keys even for a broadcast row index).
- * softmax / cumsum along a
+ * softmax along a contiguous last dim: "softmax-wave" (a wave per row, for rows
+ * of up to 1024 16-byte vectors) and "softmax-row" (a 256-lane workgroup per
+ * row, 65 to 4096 vectors) where the other would be chosen.  softmax / cumsum along a
  * non-innermost dim: "softmax-strided", "scan-strided" (one lane per slice
  * instead of the column kernels).  layer_norm: "layer-norm-block" (one
  * workgroup per row), "layer-norm-generic" (three passes, any strides).

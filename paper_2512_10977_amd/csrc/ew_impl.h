@@ -739,7 +739,7 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     set_path("vec");
     const dim3 grid((unsigned)(outer * tiles));
     // all inputs streamed (a stride-0 inner operand is one scalar load and does not count)
-    bool all_stream = true;
+    bool all_stream = strcmp(forced, "vec-cached") != 0;    // "vec-cached": plain loads, to measure what the hint is worth
     for (int o = 1; o < NOPS; ++o) all_stream = all_stream && (a.stream[o] || a.inner_stride[o] == 0);
     if constexpr (Shape<F>::dynamic) {
       if (e_rt == 2 && all_stream) hipLaunchKernelGGL((ew_vec_kernel<F, 2, U, true>), grid, dim3(kBlock), 0, stream, f, a);

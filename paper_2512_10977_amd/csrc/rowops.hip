@@ -101,6 +101,72 @@ __global__ __launch_bounds__(kBlock) void softmax_wave_kernel(const SoftmaxArgs 
   }
 }
 
+// one 256-lane workgroup per row, CH vectors per lane (the row is at most 256 CH vectors long): a quarter of the
+// registers of the wave-per-row form for the same row, so twice the resident waves, at the price of two
+// workgroup-wide reductions through LDS.  The waves write their partial results to separate slots for the maximum
+// and for the sum, so that one barrier each suffices.
+template <class T, class O, int VEC, int CH>
+__global__ __launch_bounds__(kBlock) void softmax_row_kernel(const SoftmaxArgs a) {
+  constexpr int NW = kBlock / kWave;
+  __shared__ float part_max[NW], part_sum[NW];
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t row = blockIdx.x;
+  const T* x = (const T*)a.x + row * a.xrow;
+  O* out = (O*)a.out + row * a.orow;
+  Vec<T, VEC> t[CH];
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {                                // all loads first, unconditional; len is a multiple of VEC here
+    const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+    t[k] = vec_load<T, VEC, true>(x + (c < a.len ? c : 0));
+  }
+  float v[CH][VEC];
+  float m = kNegInf;
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {
+    const bool in = ((int64_t)k * kBlock + threadIdx.x) * VEC < a.len;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      v[k][e] = in ? cvt<float>(t[k].v[e]) : kNegInf;
+      m = fmaxf(m, v[k][e]);
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) part_max[w] = m;
+  __syncthreads();
+  m = part_max[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) m = fmaxf(m, part_max[k]);
+  float s = 0.0f;
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {
+    const bool in = ((int64_t)k * kBlock + threadIdx.x) * VEC < a.len;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      v[k][e] -= m;
+      const float ex = in ? expf(v[k][e]) : 0.0f;
+      s += ex;
+      if (!a.is_log) v[k][e] = ex;
+    }
+  }
+  s = wave_sum(s);
+  if (lane == 0) part_sum[w] = s;
+  __syncthreads();
+  s = part_sum[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) s += part_sum[k];
+  const float inv = 1.0f / s, ls = logf(s);
+#pragma unroll
+  for (int k = 0; k < CH; ++k) {
+    const int64_t c = ((int64_t)k * kBlock + threadIdx.x) * VEC;
+    if (c < a.len) {
+      Vec<O, VEC> r;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) r.v[e] = from_float<O>(a.is_log ? v[k][e] - ls : v[k][e] * inv);
+      vec_store<O, VEC, true>(out + c, r);
+    }
+  }
+}
+
 // one workgroup per row, three passes
 template <class T, class O>
 __global__ __launch_bounds__(kBlock) void softmax_block_kernel(const SoftmaxArgs a) {
@@ -163,7 +229,24 @@ tx_status softmax_launch(const tx_tensor* out, const tx_tensor* x, int dim, int 
     const bool al = len % V == 0 && (uintptr_t)x->data % 16 == 0 && (uintptr_t)out->data % (V * sizeof(O) >= 16 ? 16 : V * sizeof(O)) == 0 &&
                     (a.xrow * (int64_t)sizeof(T)) % 16 == 0 && (a.orow * (int64_t)sizeof(O)) % 16 == 0;
     const dim3 grid((unsigned)((a.rows + 3) / 4));
-    if (al && len <= 64 * V) {
+    // A row of more than 256 vectors goes to a 256-lane workgroup (2, 4, 8 or 16 vectors per lane).  The wave-per-row
+    // form needs 112 registers for 16 vectors per lane, which leaves 4 waves per SIMD (counters: 3.1 resident on
+    // average) and took 188 us on [32768,4096] fp32 against 168 us for the workgroup form; up to 256 vectors the
+    // wave form wins (no barriers: 169 us against 186 us on [131072,1024] fp32).  "softmax-wave" / "softmax-row"
+    // force either form where it applies; rows beyond 4096 vectors take three passes.
+    const char* forced = forced_path();
+    const bool row_ok = al && len > 64 * V && len <= 4096 * V && a.rows < (1ll << 31);
+    const bool wave_ok = al && len <= 1024 * V;
+    const bool row_form = row_ok && (!strcmp(forced, "softmax-row") || !wave_ok || (len > 256 * V && strcmp(forced, "softmax-wave")));
+    if (row_form) {
+      set_path("softmax-row");
+      const dim3 rgrid((unsigned)a.rows);
+      if (len <= 256 * V) hipLaunchKernelGGL((softmax_row_kernel<T, O, V, 1>), rgrid, dim3(kBlock), 0, stream, a);
+      else if (len <= 512 * V) hipLaunchKernelGGL((softmax_row_kernel<T, O, V, 2>), rgrid, dim3(kBlock), 0, stream, a);
+      else if (len <= 1024 * V) hipLaunchKernelGGL((softmax_row_kernel<T, O, V, 4>), rgrid, dim3(kBlock), 0, stream, a);
+      else if (len <= 2048 * V) hipLaunchKernelGGL((softmax_row_kernel<T, O, V, 8>), rgrid, dim3(kBlock), 0, stream, a);
+      else hipLaunchKernelGGL((softmax_row_kernel<T, O, V, 16>), rgrid, dim3(kBlock), 0, stream, a);
+    } else if (al && len <= 64 * V) {
       set_path("softmax-wave");
       hipLaunchKernelGGL((softmax_wave_kernel<T, O, V, 1>), grid, dim3(kBlock), 0, stream, a);
     } else if (al && len <= 256 * V) {

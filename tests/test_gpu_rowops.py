@@ -66,8 +66,22 @@ def test_softmax_shapes_and_paths(log):
         paths.add(check_softmax(I.make_view((30, 257), dt, "transposed", seed=302), -1, log, what="transposed"))
         paths.add(check_softmax(I.make_view((30, 256), dt, "step2_outer", seed=303), -1, log, what="step2_outer"))
         paths.add(check_softmax(I.make_view((30, 256), dt, "step2_inner", seed=304), -1, log, what="step2_inner"))
-    assert {"softmax-wave", "softmax-wave-scalar", "softmax-block", "softmax-strided"} <= paths, paths
+    assert {"softmax-wave", "softmax-row", "softmax-wave-scalar", "softmax-block", "softmax-strided"} <= paths, paths
     check_softmax(I.softmax_logits((64, 512), BF16, seed=305), -1, log, out_dtype=F32, what="fp32 out")
+    # both register-resident forms on every row length they share, ragged multiples of the vector width included,
+    # and the workgroup form up to its longest rows (16 vectors per lane)
+    for dt, shape in [(F32, (37, 260)), (F32, (9, 1028)), (F32, (5, 2048)), (F32, (3, 4096)), (BF16, (7, 520)), (BF16, (5, 8192)),
+                      (F16, (6, 4104))]:
+        x = I.softmax_logits(shape, dt, seed=306)
+        for path in ("softmax-wave", "softmax-row"):
+            B.tx_force_path(path)
+            try:
+                assert check_softmax(x, -1, log, what="forced " + path) == path
+            finally:
+                B.tx_force_path(None)
+    for dt, shape in [(F32, (3, 4100)), (F32, (2, 16384)), (F32, (2, 12292)), (BF16, (2, 32768)), (BF16, (3, 9000))]:
+        assert check_softmax(I.softmax_logits(shape, dt, seed=307), -1, log, what="long rows") == "softmax-row"
+    assert check_softmax(I.softmax_logits((2, 16388), F32, seed=308), -1, log, what="beyond registers") == "softmax-block"
 
 
 def test_softmax_special_rows_and_edges():
@@ -94,7 +108,7 @@ def test_softmax_special_rows_and_edges():
 @pytest.mark.parametrize("log", [False, True])
 def test_softmax_full_size(dt, log):
     x = I.softmax_logits((32768, 4096), dt, seed=3)
-    assert check_softmax(x, -1, log) == "softmax-wave"
+    assert check_softmax(x, -1, log) == "softmax-row"
 
 
 # --------------------------------------------------------------------------- cumsum
