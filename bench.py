@@ -553,6 +553,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the operators timed outside the step")
+    ap.add_argument("--no-detail", action="store_true", help="skip the extra measurements of workload 1 and the 1 GiB probes")
     ap.add_argument("--only", default="", help="comma-separated substrings: run only the operators whose name matches "
                                                "(for profiling single kernels; the JSON line then covers that subset)")
     ap.add_argument("--calibrate", action="store_true",
@@ -643,7 +644,7 @@ def main():
         "per_op": per_op,
         "per_op_outside_step": outside,
     }
-    if not args.only:
+    if not args.only and not args.no_detail:
         result["measurement_detail"] = measurement_detail(torch, B)
     if not args.no_cpu_baseline:
         result["cpu_baseline"], result["cpu_baseline_per_workload"] = cpu_baseline(torch)
