@@ -227,16 +227,29 @@ template <class T> __device__ __forceinline__ T value_from_bits(uint32_t b) {
   else if constexpr (sizeof(T) == 2) return __builtin_bit_cast(T, (uint16_t)b);
   else return __builtin_bit_cast(T, (uint8_t)b);
 }
-// keys for the row mode: the row id of every source row
-__global__ __launch_bounds__(kBlock) void row_keys_kernel(const char* index, int is64, int64_t istride, int64_t n,
-                                                          uint32_t* keys, uint32_t* vals, unsigned int* counter, int64_t wrap) {
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i == 0 && counter) *counter = 0u;      // start-list length for the row-mode combine pass
-  if (i >= n) return;
-  int64_t k = load_index(index, i * istride, is64);
-  k += k < 0 ? wrap : 0;
-  keys[i] = (uint32_t)k;
-  vals[i] = (uint32_t)i;
+// The first pass of the row mode in one kernel: the row id of every source row becomes its key (and its position the
+// value), and the tile's histogram of the lowest digit is counted from the keys while they are in registers.
+__global__ __launch_bounds__(kBlock) void row_keys_hist_kernel(const char* index, int is64, int64_t istride, int64_t n,
+                                                               uint32_t* keys, uint32_t* vals, unsigned int* counter,
+                                                               int64_t wrap, uint32_t* hist, int nblocks) {
+  __shared__ unsigned int h[256];
+  h[threadIdx.x] = 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && counter) *counter = 0u;      // start-list length for the row-mode combine pass
+  __syncthreads();
+  const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll
+  for (int k = 0; k < kSortItems; ++k) {
+    const int64_t i = base + k * kBlock + threadIdx.x;
+    if (i < n) {
+      int64_t key = load_index(index, i * istride, is64);
+      key += key < 0 ? wrap : 0;
+      keys[i] = (uint32_t)key;
+      vals[i] = (uint32_t)i;
+      atomicAdd(&h[(uint32_t)key & 255u], 1u);
+    }
+  }
+  __syncthreads();
+  hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
 }
 
 __global__ __launch_bounds__(kBlock) void sort_hist_kernel(const uint32_t* keys, int64_t n, int shift, uint32_t* hist,
@@ -599,7 +612,7 @@ __global__ __launch_bounds__(kBlock) void index_put_kernel(const PutArgs a) {
 
 constexpr int kChunk = 128;                 // sorted rows per wave
 constexpr int64_t kIntRowModeMin = 4096;    // integer row mode pays for its sort from about this many rows
-constexpr int kCombineWaves = 4;              // 16 measured slower (56 us against 23 us): most runs have one or two pieces and a 1024-lane workgroup per run idles
+constexpr int kCombineWaves = 4;              // 8 measured 30 us and 16 measured 56 us against 23 us: most runs have one or two pieces, and a wider workgroup per run mostly idles
 constexpr int kCombineBlocks = 2048;
 
 struct SegRowArgs {
@@ -615,7 +628,7 @@ struct SegRowArgs {
   uint8_t* flag_a;               // kNone / kEnd / kThrough
   uint32_t* key_b;               // destination row of the chunk's start piece
   uint32_t* start_list;          // chunks that hold the start piece of a run that goes on
-  unsigned int* nstart;          // length of start_list (cleared by row_keys_kernel)
+  unsigned int* nstart;          // length of start_list (cleared by row_keys_hist_kernel)
   float alpha_f;                 // multiplier of every sum (floating dtypes / integer dtypes)
   int64_t alpha_i;
   int include_self;              // OP >= 0 kernels only: whether self takes part
@@ -717,7 +730,10 @@ __global__ __launch_bounds__(kBlock) void seg_rows_kernel(const SegRowArgs a) {
     int nbuf = 0;                              // finished runs waiting in done_rows[w]
     int kbuf = 0;                              // their destination rows: lane i holds the key of slot i
 
-    auto park = [&](Acc* part) {               // a piece of a run that crosses a chunk boundary
+    // a piece of a run that crosses a chunk boundary.  (Adding integer pieces to their row with atomics instead, and
+    // dropping the combine pass for integers, measured slower: 336 us against 312 us - the 1100 chunks of the hottest
+    // row then queue on the same 256 addresses.)
+    auto park = [&](Acc* part) {
       if (active) vec_store<Acc, VEC, false>(part + chunk * a.width + col, acc);      // read again soon by seg_combine_kernel
     };
 
@@ -1019,7 +1035,8 @@ void fill_scatter_elem_args(ElemArgs* a, const tx_tensor* self, int dim, const t
   }
 }
 
-tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_buffer) {
+// first_hist_done: the caller's key kernel has already counted the first pass's histogram (row_keys_hist_kernel)
+tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_buffer, bool first_hist_done = false) {
   uint32_t* keys[2] = {(uint32_t*)(ws + p.off_keys[0]), (uint32_t*)(ws + p.off_keys[1])};
   uint32_t* vals[2] = {(uint32_t*)(ws + p.off_vals[0]), (uint32_t*)(ws + p.off_vals[1])};
   uint32_t* hist = (uint32_t*)(ws + p.off_hist);
@@ -1027,7 +1044,8 @@ tx_status run_sort(const ScatterPlan& p, char* ws, hipStream_t s, int* result_bu
   int cur = 0;
   for (int pass = 0; pass < p.passes; ++pass) {
     const int shift = 8 * pass;
-    hipLaunchKernelGGL(sort_hist_kernel, dim3(p.nblocks), dim3(kBlock), 0, s, keys[cur], p.n, shift, hist, p.nblocks);
+    if (pass > 0 || !first_hist_done)
+      hipLaunchKernelGGL(sort_hist_kernel, dim3(p.nblocks), dim3(kBlock), 0, s, keys[cur], p.n, shift, hist, p.nblocks);
     hipLaunchKernelGGL(sort_rowscan_kernel, dim3(256), dim3(kBlock), 0, s, hist, p.nblocks, totals);
     hipLaunchKernelGGL(sort_scatter_kernel, dim3(p.nblocks), dim3(kBlock), 0, s, keys[cur], vals[cur], keys[1 - cur],
                        vals[1 - cur], p.n, shift, hist, totals, p.nblocks);
@@ -1052,12 +1070,13 @@ tx_status scatter_deterministic(const ScatterPlan& p, const tx_tensor* self, int
   fill_scatter_elem_args(&ea, self, dim, index, src, alpha);
   const unsigned nb = (unsigned)((p.n + kBlock - 1) / kBlock);
   if (p.row_mode)
-    hipLaunchKernelGGL(row_keys_kernel, dim3(nb), dim3(kBlock), 0, s, (const char*)index->data, index->dtype == TX_I64,
-                       index->strides[0], p.n, keys0, vals0, (unsigned int*)(ws + p.off_counter), alpha.wrap);
+    hipLaunchKernelGGL(row_keys_hist_kernel, dim3(p.nblocks), dim3(kBlock), 0, s, (const char*)index->data,
+                       index->dtype == TX_I64, index->strides[0], p.n, keys0, vals0, (unsigned int*)(ws + p.off_counter),
+                       alpha.wrap, (uint32_t*)(ws + p.off_hist), p.nblocks);
   else
     hipLaunchKernelGGL(scatter_keys_kernel<key_value_bytes<T>()>, dim3(nb), dim3(kBlock), 0, s, ea, keys0, vals0);
   int cur;
-  tx_status rc = run_sort(p, ws, s, &cur);
+  tx_status rc = run_sort(p, ws, s, &cur, p.row_mode && p.passes > 0);
   if (rc) return rc;
   const uint32_t* keys = (const uint32_t*)(ws + p.off_keys[cur]);
   const uint32_t* vals = (const uint32_t*)(ws + p.off_vals[cur]);
