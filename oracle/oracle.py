@@ -53,7 +53,7 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB
+        path = os.environ.get("ORACLE_LIB") or _build.LIB      # ORACLE_LIB: another build of oracle.cpp (the sanitizer test's)
         if not os.path.exists(path):
             _build.build()
         _lib = ctypes.CDLL(path)
