@@ -636,8 +636,9 @@ tx_status tx_lookback_status(const void* ws, void* stream);
 
 /* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
  * "vec", "tile", "generic"; on the vec path "vec-cached" (plain instead of
- * non-temporal loads) and "vec-narrow" (one vector per lane where every input
- * is a broadcast).  cumsum along a contiguous dim: "scan-lookback"
+ * non-temporal loads), and where every input is a broadcast "vec-wide" /
+ * "vec-narrow" (the general vec kernel with four / one vectors per lane instead
+ * of the lean broadcast kernel "vec-bcast").  cumsum along a contiguous dim: "scan-lookback"
  * (tile size automatic), "scan-lookback-narrow" (16 KiB tiles), "scan-carry",
  * and "scan-lookback-giveup" (the look-back kernel with a poll limit of zero:
  * every wait gives up at once, for testing tx_lookback_status).

@@ -128,7 +128,52 @@ def check_binary(op, a_cpu, b_cpu, alpha=1, layout="contig", path=None, what="")
 def test_broadcast_add_4096_bit_exact():
     a, b = I.broadcast_add_inputs(4096, 4096, seed=0)
     used = check_binary("add", a, b)
-    assert used == "vec"
+    assert used == "vec-bcast"
+    for path in ("vec-wide", "vec-narrow", "generic"):           # the other kernels that can serve it: same bits
+        assert check_binary("add", a, b, path=path) in ("vec", "generic")
+
+
+def test_broadcast_add_replayed_from_a_graph():
+    """The benchmark replays workload 1 from a HIP graph: captured launches must give the eager result on every replay,
+    with eager work and synchronisations between the replays."""
+    a, b = I.broadcast_add_inputs(4096, 4096, seed=0)
+    want = O.binary("add", a, b)
+    da, db = a.cuda(), b.cuda()
+    outs = [torch.zeros((4096, 4096), device="cuda") for _ in range(3)]
+    B.tx_add(outs[0], da, db, 1)                      # eager first (also loads the kernel before capture)
+    sync()
+    assert_exact_fp(outs[0], want, "eager")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for o in outs:
+            B.tx_add(o, da, db, 1)
+    for rep in range(3):
+        for o in outs:
+            o.fill_(float(rep))                       # eager work between replays; wipes the previous results
+        sync()
+        g.replay()
+        sync()
+        for o in outs:
+            assert_exact_fp(o, want, "replay %d" % rep)
+
+
+def test_write_dominated_broadcasts_take_the_lean_kernel():
+    """out[r][c] = f(a[r], b[c]): every input constant along one of the two dims, whole 4 KiB pieces per row."""
+    for dt, cols in ((F32, 2048), (BF16, 4096), (I64, 1024), (I32, 1024), (BOOL, 8192)):
+        col = I.typed((37, 1), dt, seed=150) if dt != BOOL else I.booleans((37, 1), 0.5, seed=150)
+        row = I.typed((1, cols), dt, seed=151) if dt != BOOL else I.booleans((1, cols), 0.5, seed=151)
+        for op in ("add", "mul", "maximum", "eq", "lt"):
+            assert check_binary(op, col, row, what="col op row") == "vec-bcast"
+            assert check_binary(op, row, col, what="row op col") == "vec-bcast"
+        assert check_binary("mul", row.expand(37, cols), torch.ones((), dtype=dt), what="row op scalar") == "vec-bcast"
+        if dt.is_floating_point:
+            assert check_binary("add", col, row, alpha=0.25, what="alpha") == "vec-bcast"
+    # a ragged row (not whole pieces) and three dims stay on the general vec kernel
+    assert check_binary("add", I.typed((37, 1), F32, seed=152), I.typed((1, 2052), F32, seed=153)) == "vec"
+    assert check_binary("add", I.typed((5, 3, 1), F32, seed=154), I.typed((1, 1, 1024), F32, seed=155)) == "vec-bcast"   # collapses to 2-D
+    assert check_binary("add", I.typed((5, 1, 1024), F32, seed=156), I.typed((1, 3, 1), F32, seed=157)) == "vec"
+    c = I.booleans((64, 1), 0.5, seed=158)
+    assert check_where(c, I.typed((1, 1024), F32, seed=159), torch.tensor(2.5)) == "vec-bcast"
 
 
 def test_broadcast_add_small_and_alpha():
@@ -271,10 +316,12 @@ def check_where(c, x, y, what=""):
     want = O.where(c, x, y)
     out = torch.empty(want.shape, dtype=want.dtype, device="cuda")
     B.tx_where(out, to_device_view(c), to_device_view(x), to_device_view(y))
+    used = B.tx_last_path()
     sync()
     assert_exact_fp(out, want, "where %s %s %s %s" % (x.dtype, y.dtype, tuple(want.shape), what))
     if x.dtype == y.dtype:
         assert_exact(out, want, "where bits " + what)
+    return used
 
 
 def test_where_sweep():
