@@ -10,6 +10,7 @@ namespace {
 template <class Op, class T> struct MathStatic {
   using Out = T; using In0 = T; using In1 = void; using In2 = void;
   static constexpr int NIN = 1;
+  static constexpr int VPL = 2;
   __device__ __forceinline__ T operator()(T x) const {
     if constexpr (sizeof(T) == 2) return cvt<T>(Op::run_half(cvt<float>(x)));
     else return cvt<T>(Op::run(cvt<float>(x)));

@@ -181,6 +181,9 @@ template <class T> constexpr bool is_dynamic() {
   else return Elem<T>::dynamic;
 }
 
+template <class F> constexpr int vec_per_lane(decltype(F::VPL)*) { return F::VPL; }
+template <class F> constexpr int vec_per_lane(...) { return 1; }
+
 template <class F> struct Shape {
   static constexpr bool dynamic = is_dynamic<typename F::Out>() || is_dynamic<typename F::In0>() ||
                                   is_dynamic<typename F::In1>() || is_dynamic<typename F::In2>();
@@ -197,8 +200,10 @@ template <class F> struct Shape {
   static constexpr int E = dynamic ? 4 : (max_size >= 16 ? 1 : 16 / max_size);
   // vectors per lane: one.  On this chip a streaming kernel is fastest with many small waves (a plain copy
   // moves 6.5 TB/s with one 16-byte vector per lane and 5.8 TB/s with four)
+  // A functor with enough arithmetic per element to show beside the memory time (a transcendental) may ask for more,
+  // by declaring VPL: its workgroup then has the next vector's load in flight while it computes the first.
   static constexpr int per_vec = E * max_size;
-  static constexpr int U = 1;
+  static constexpr int U = vec_per_lane<F>(0);
 };
 
 template <class T> struct TypeTag { using type = T; };

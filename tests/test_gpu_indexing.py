@@ -168,6 +168,19 @@ def test_scatter_add_float_deterministic(dt):
     assert used == ("scatter-atomic" if dt == F32 else "scatter-sort-elem")
 
 
+@pytest.mark.parametrize("dt", [F32, I32])
+def test_scatter_add_rows_chunk_sizes(dt):
+    # the sorted row path cuts its input into chunks of 64, 128 or 256 rows by input size: sizes on both sides of the
+    # two thresholds, with hot destinations (runs over many chunks), cold ones (runs inside a chunk) and a ragged tail
+    for n, rows, w in [(524288 - 3, 3000, 16), (524288 + 77, 3000, 16), (1048576 + 129, 40000, 16)]:
+        r = I.zipf_rows(n, rows, 1.1, seed=470)
+        if dt == F32:
+            src, dst = I.normal((n, w), 1.0, seed=471), I.normal((rows, w), 1.0, seed=472)
+        else:
+            src, dst = I.integers((n, w), -1000, 1000, seed=471, dtype=dt), I.integers((rows, w), -1000, 1000, seed=472, dtype=dt)
+        assert check_scatter_add(dst, 0, r.unsqueeze(1).expand(n, w), src, what="n=%d" % n) == "scatter-sort-rows"
+
+
 def test_indexing_error_codes():
     d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
     with pytest.raises(B.TxError) as e:
