@@ -10,7 +10,9 @@ namespace {
 template <class Op, class T> struct MathStatic {
   using Out = T; using In0 = T; using In1 = void; using In2 = void;
   static constexpr int NIN = 1;
-  static constexpr int VPL = 2;
+  // two vectors per lane for the operators composed in binary64 (their arithmetic then overlaps the second vector's
+  // load: gelu 108 -> 101 us, tanh 92 -> 83 us on [8192,8192] fp32), one for the cheap ones (exp: 79 against 82 us)
+  static constexpr int VPL = vec_per_lane<Op>(0);
   __device__ __forceinline__ T operator()(T x) const {
     if constexpr (sizeof(T) == 2) return cvt<T>(Op::run_half(cvt<float>(x)));
     else return cvt<T>(Op::run(cvt<float>(x)));

@@ -934,14 +934,17 @@ struct OpSqrt {
   __device__ static float run_half(float x) { return sqrtf(x); }
 };
 struct OpSigmoid {
+  static constexpr int VPL = 2;
   __device__ static float run(float x) { return sigmoid_f32(x); }
   __device__ static float run_half(float x) { return 1.0f / (1.0f + expf(-x)); }
 };
 struct OpTanh {
+  static constexpr int VPL = 2;
   __device__ static float run(float x) { return tanh_f32(x); }
   __device__ static float run_half(float x) { return tanhf(x); }
 };
 struct OpGelu {
+  static constexpr int VPL = 2;
   __device__ static float run(float x) { return gelu_erf_f32(x); }
   // x * erfc(-x / sqrt 2) / 2: erfc keeps its relative accuracy in the negative tail
   __device__ static float run_half(float x) { return gelu_erf_half(x); }
@@ -957,6 +960,7 @@ struct OpExpm1 {
 };
 // log(sigmoid(x)) = min(x, 0) - log1p(exp(-|x|)): neither tail overflows or cancels
 struct OpLogSigmoid {
+  static constexpr int VPL = 2;
   __device__ static float run(float x) { return logsigmoid_f32(x); }
   __device__ static float run_half(float x) { return logsigmoid_half(x); }
 };
