@@ -635,7 +635,8 @@ const char* tx_last_path(void);
 tx_status tx_lookback_status(const void* ws, void* stream);
 
 /* Force a kernel path by name ("" or NULL = automatic).  Elementwise iterator:
- * "vec", "tile", "generic"; on the vec path "vec-cached" (plain instead of
+ * "vec", "tile" (reported as "tile" when 16-byte vectors serve, else as
+ * "tile-scalar"), "generic"; on the vec path "vec-cached" (plain instead of
  * non-temporal loads), and where every input is a broadcast "vec-wide" /
  * "vec-narrow" (the general vec kernel with four / one vectors per lane instead
  * of the lean broadcast kernel "vec-bcast").  cumsum along a contiguous dim: "scan-lookback"

@@ -621,6 +621,16 @@ __device__ __forceinline__ void tilev_straight_load(const TileArgs<NOPS>& a, int
   using E = typename ValueOf<In>::type;
   const int cv = threadIdx.x % TV::LANES, rl = threadIdx.x / TV::LANES;
   const int64_t c = std::min<int64_t>(c0 + cv * TV::V, a.cols - TV::V);      // cols is a multiple of V on this path
+  if (a.stride_c[o] == 0) {                    // constant along the output's fast dim (a column vector, a scalar): one element per row
+#pragma unroll
+    for (int k = 0; k < TV::PASSES; ++k) {
+      const int64_t r = std::min<int64_t>(r0 + rl + TV::ROWS_PER_PASS * k, a.rows - 1);
+      const E v = ((const E*)a.data[o])[boff + r * a.stride_r[o]];
+#pragma unroll
+      for (int j = 0; j < TV::V; ++j) g[k].v[j] = v;
+    }
+    return;
+  }
 #pragma unroll
   for (int k = 0; k < TV::PASSES; ++k) {
     const int64_t r = std::min<int64_t>(r0 + rl + TV::ROWS_PER_PASS * k, a.rows - 1);
@@ -845,6 +855,7 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
       using TV = TileVec<F>;
       bool ok = a.rows % TV::V == 0 && a.cols % TV::V == 0;
       for (int o = 0; ok && o < NOPS; ++o) {
+        if (o > 0 && a.stride_c[o] == 0 && !a.transposed[o]) continue;      // read as single elements: any alignment
         ok = aligned_to(a.data[o], 16) && (a.stride_b[o] * TV::S) % 16 == 0;
         if (a.transposed[o]) ok = ok && (a.stride_c[o] * TV::S) % 16 == 0;
         else if (a.stride_c[o] == 1) ok = ok && (a.stride_r[o] * TV::S) % 16 == 0;
@@ -880,7 +891,7 @@ template <class F> tx_status launch_ew(const Iter& it, const F& f, hipStream_t s
     const int64_t nb = it.ndim == 3 ? it.size[0] : 1;
     a.tiles_c = FastDiv((uint32_t)tc);
     a.tiles_r = FastDiv((uint32_t)tr);
-    set_path("tile");
+    set_path("tile-scalar");
     hipLaunchKernelGGL((ew_tile_kernel<F>), dim3((unsigned)(tr * tc * nb)), dim3(kBlock), 0, stream, f, a);
     return check_launch("elementwise tile kernel");
   }

@@ -307,8 +307,18 @@ def test_path_selection():
         assert check_binary("add", v, w, what="vector tile") == "tile"
         assert check_binary("maximum", w, v, what="vector tile, transposed second") == "tile"
         assert check_binary("mul", v, v, what="vector tile, both transposed", layout="contig") == "tile"
+    # a transposed operand beside one that is constant along the output's fast dim (column vector, scalar, 0-dim):
+    # still the vector tile kernel, whatever the constant operand's alignment
+    t2 = I.make_view((520, 264), F32, "transposed", seed=160)
+    col = I.typed((521, 1), F32, seed=161)[1:]                                      # 4-byte aligned only
+    assert check_binary("add", t2, col.expand(520, 264), what="tile + column vector") == "tile"
+    assert check_binary("mul", col.expand(520, 264), t2, what="column vector + tile") == "tile"
+    assert check_binary("add", t2, I.typed((3,), F32, seed=162)[1:2].expand(520, 264), what="tile + one element") == "tile"
+    assert check_binary("add", t2, I.typed((), F32, seed=163), what="tile + 0-dim") == "tile"
+    assert check_binary("add", I.make_view((7, 13), F32, "transposed", seed=164), I.typed((7, 13), F32, seed=165),
+                        path="tile", what="not 16-byte granular") == "tile-scalar"
     b3 = I.make_view((6, 200, 300), BF16, "contig", seed=136).transpose(1, 2)       # batched transpose
-    assert check_binary("mul", b3, I.make_view((6, 300, 200), BF16, "contig", seed=137)) == "tile"
+    assert check_binary("mul", b3, I.make_view((6, 300, 200), BF16, "contig", seed=137)) == "tile-scalar"     # 300 is not a multiple of 8
 
 
 # --------------------------------------------------------------------------- where / masked_fill
@@ -572,7 +582,7 @@ def test_clamp_full_size(dt):
     x = I.typed(FULL, dt, seed=6, specials=0.01)
     assert check_clamp(x, -1 if dt == I64 else -0.5, 2 if dt == I64 else 0.75) == "vec"
     if dt == F32:
-        assert check_clamp(I.make_view(FULL, dt, "transposed", seed=7), -0.5, None) in ("tile-vec", "tile")
+        assert check_clamp(I.make_view(FULL, dt, "transposed", seed=7), -0.5, None) in ("tile", "tile-scalar")
 
 
 def check_cast(fn_oracle, fn_lib, want_dtype_class, what):
