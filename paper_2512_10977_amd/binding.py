@@ -143,7 +143,10 @@ def lib():
 
 
 def desc(t):
-    """tx_tensor descriptor of a torch tensor (any device; data is passed as a raw pointer)."""
+    """tx_tensor descriptor of a torch tensor (any device; data is passed as a raw pointer).  A descriptor built
+    earlier passes through, so a caller that launches the same operands many times marshals them once."""
+    if isinstance(t, TxTensor):
+        return t
     d = TxTensor()
     d.data = t.data_ptr() if t.numel() else None
     d.dtype = DTYPE_CODE[t.dtype]
