@@ -633,7 +633,8 @@ def main():
             t = PMC_TRAFFIC_BYTES[r["op"]]
             r["hbm_traffic_bytes_counters"] = t
             r["frac_of_peak_in_traffic_bytes"] = round(t / (r["us"] * 1e-6) / 1e9 / PEAK_GBPS, 4)
-    dom = max(per_op, key=lambda r: r["us"])
+    # (--only may leave the step empty: the line then describes the selected operators timed outside it)
+    dom = max(per_op or outside or [op_row({"name": "none", "row": "", "kernel": "", "bytes": 0, "elems": 0}, 1e-3)], key=lambda r: r["us"])
     ms_step = wall / args.steps * 1e3
     value = step_bytes / (wall / args.steps) / 1e9
     side = os.path.join(ROOT, args.side_file)

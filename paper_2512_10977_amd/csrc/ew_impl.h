@@ -962,7 +962,8 @@ struct OpGelu {
 };
 
 struct OpLog1p {
-  __device__ static float run(float x) { return log1pf(x); }
+  static constexpr int VPL = 2;
+  __device__ static float run(float x) { return log1p_f32(x); }
   __device__ static float run_half(float x) { return log1pf(x); }
 };
 struct OpExpm1 {

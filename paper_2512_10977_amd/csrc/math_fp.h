@@ -140,6 +140,20 @@ __device__ __forceinline__ double pow_abs_d(double v, double p) {
   return exp_d(y);
 }
 
+// log1p(x) for an fp32 x, in binary64: 1 + x is exact there from |x| = 2^-29 up to 2^53 (an fp32 x has 24 bits), so
+// log_d(1 + x) keeps full relative accuracy - for 1 + x in [sqrt 1/2, sqrt 2) its exponent term is zero and its
+// series runs in x / (2 + x).  Below 2^-12 the first three terms of the series in x itself are exact to 2^-38.
+// x < -1: NaN; x = -1: -inf; +inf stays; a NaN x fails the first comparison and comes out NaN.
+__device__ __forceinline__ float log1p_f32(float xf) {
+  const double x = (double)xf;
+  const bool inside = xf > -1.0f && xf < __builtin_inff();
+  const double l = log_d(inside ? 1.0 + x : 1.0);           // log_d wants a positive normal argument
+  const double s = x * __builtin_fma(x, __builtin_fma(x, 1.0 / 3.0, -0.5), 1.0);
+  float r = (float)(__builtin_fabsf(xf) < 0x1p-12f ? s : l);
+  if (!(xf > -1.0f)) r = xf == -1.0f ? -__builtin_inff() : __uint_as_float(0x7fc00000u);
+  return xf == __builtin_inff() ? xf : r;
+}
+
 // log(e^a + e^b) (base2: log2(2^a + 2^b)) = max + log1p(exp(-|a - b|)); fp32 operands, binary64 evaluation
 __device__ __forceinline__ float logaddexp_f32(float a, float b, bool base2) {
   if (a != a || b != b) return __uint_as_float(0x7fc00000u);
@@ -243,27 +257,27 @@ __device__ __forceinline__ float gelu_erf_f32(float xf) {
 }
 
 // log(sigmoid(x)) = min(x, 0) - log1p(e), e = exp(-|x|) in (0, 1], composed in binary64 like the functions above.
-// log1p(e) = 2 atanh(z) with z = e / (2 + e) <= 1/3: z (1 + w/3 + w^2/5 + ... + w^10/21), w = z^2 <= 1/9; the first
-// dropped term is below 1e-12 relative.
+// e comes from the short exponential (3.7e-9 relative: where log1p(e) is all of the result, for large x, it is e
+// itself to first order, and elsewhere it is the smaller term).  log1p(e) = 2 atanh(z) with z = e / (2 + e) <= 1/3:
+// z (1 + w/3 + w^2/5 + ... + w^8/17), w = z^2 <= 1/9; the dropped terms sum to 1.6e-9 relative at most.
+// |x| is clamped at 104, where e is below half the smallest fp32 subnormal.
 __device__ __forceinline__ float logsigmoid_f32(float xf) {
   if (xf != xf) return xf;
   const double x = (double)xf;
   double m = -__builtin_fabs(x);
-  m = m < -708.0 ? -708.0 : m;                         // exp(-708) ~ 3e-308: far below one ulp of |x| there
-  const double e = exp_d(m);
+  m = m < -104.0 ? -104.0 : m;
+  const double e = exp6_d(m);
   const double z = e * rcp_d(2.0 + e);
   const double w = z * z;
-  double p = 1.0 / 21.0;
-  p = __builtin_fma(p, w, 1.0 / 19.0);
-  p = __builtin_fma(p, w, 1.0 / 17.0);
-  p = __builtin_fma(p, w, 1.0 / 15.0);
-  p = __builtin_fma(p, w, 1.0 / 13.0);
-  p = __builtin_fma(p, w, 1.0 / 11.0);
-  p = __builtin_fma(p, w, 1.0 / 9.0);
-  p = __builtin_fma(p, w, 1.0 / 7.0);
-  p = __builtin_fma(p, w, 1.0 / 5.0);
-  p = __builtin_fma(p, w, 1.0 / 3.0);
-  p = __builtin_fma(p, w, 1.0);
+  double p = 1.0 / 17.0;
+  p = fma_k(p, w, 1.0 / 15.0);
+  p = fma_k(p, w, 1.0 / 13.0);
+  p = fma_k(p, w, 1.0 / 11.0);
+  p = fma_k(p, w, 1.0 / 9.0);
+  p = fma_k(p, w, 1.0 / 7.0);
+  p = fma_k(p, w, 1.0 / 5.0);
+  p = fma_k(p, w, 1.0 / 3.0);
+  p = fma_k(p, w, 1.0);
   const double l1p = 2.0 * z * p;
   return (float)((x < 0.0 ? x : 0.0) - l1p);
 }
