@@ -178,7 +178,8 @@ __device__ __forceinline__ float mish_f32(float xf) {
 }
 
 // fp32 power.  Finite non-zero base and finite exponent: exp(b log|a|) in binary64 (the error of b log|a| stays
-// below 1e-11 wherever the result is finite, far inside one fp32 ulp), the sign from the exponent's parity for a
+// below 1e-11 wherever the result is finite and the short exponential adds 3.7e-9: a sixteenth of an fp32 ulp), the
+// sign from the exponent's parity for a
 // negative base, NaN for a negative base with a non-integer exponent.  Zeros, infinities and NaNs: the device
 // library's binary64 pow, which carries the C Annex F table.
 __device__ __forceinline__ float pow_f32(float af, float bf) {
@@ -192,7 +193,7 @@ __device__ __forceinline__ float pow_f32(float af, float bf) {
   }
   double y = (double)bf * log_d((double)aa);
   y = y > 90.0 ? 90.0 : (y < -110.0 ? -110.0 : y);                       // beyond fp32's range either way
-  const float r = (float)exp_d(y);
+  const float r = (float)exp6_d(y);                                      // nothing is subtracted afterwards: the short form serves
   return odd ? -r : r;
 }
 
@@ -210,7 +211,7 @@ __device__ __forceinline__ float silu_f32(float xf) {
   if (xf == -__builtin_inff()) return __uint_as_float(0x7fc00000u);      // -inf / inf
   const double x = (double)xf;
   const double m = -x > 708.0 ? 708.0 : (-x < -708.0 ? -708.0 : -x);
-  return (float)(x * rcp_d(1.0 + exp_d(m)));
+  return (float)(x * rcp_d(1.0 + exp6_d(m)));
 }
 
 // tanh|x| = em / (em + 2), em = expm1(2|x|) = 2^n (1 + p) - 1 from the exponential's own reduction: with n = 0 the
