@@ -318,19 +318,21 @@ __device__ __forceinline__ float bce_term_fast(float x, float t) {
 }
 
 // gelu for fp16 / bf16 results (8-11 significant bits): the same erfc form in plain fp32 with a degree-5
-// fit at Chebyshev nodes (relative error 5.5e-5) and the hardware exp2 / reciprocal.
+// fit at Chebyshev nodes (relative error 5.5e-5) and the hardware exp2 / reciprocal.  Everything runs in
+// w = z sqrt(log2 e), so that exp(-z^2) is the hardware's 2^(-w^2) with no further multiplication:
+// t = (z - 1.5) / (z + 1.5) = 1 - 2 K r with K = 1.5 sqrt(log2 e) and r = 1 / (w + K), and the fit's coefficients
+// carry the factors 1/2 and sqrt(log2 e) that turn r into 1 / (z + 1.5) and erfc into erfc / 2.
 __device__ __forceinline__ float gelu_erf_half(float x) {
-  const float z = __builtin_fabsf(x) * 0.70710678118654752440f;
-  const float zc = __builtin_fminf(z, 13.0f);          // exp(-169) is 0 in fp32
-  const float r = __builtin_amdgcn_rcpf(zc + 1.5f);
-  const float t = (zc - 1.5f) * r;
-  float p = -6.683117244e-03f;
-  p = __builtin_fmaf(p, t, -8.231409825e-03f);
-  p = __builtin_fmaf(p, t, 4.644610733e-02f);
-  p = __builtin_fmaf(p, t, 7.555128634e-02f);
-  p = __builtin_fmaf(p, t, -5.076892972e-01f);
-  p = __builtin_fmaf(p, t, 9.647628665e-01f);
-  const float half_erfc = 0.5f * __expf(-zc * zc) * p * r;
+  const float w = __builtin_fminf(__builtin_fabsf(x) * 0.8493218002880191f, 15.614591f);      // 2^(-15.6^2) is 0 in fp32
+  const float r = __builtin_amdgcn_rcpf(w + 1.8016836131796747f);
+  const float t = __builtin_fmaf(-3.6033672263593495f, r, 1.0f);
+  float p = -4.013620941e-03f;
+  p = __builtin_fmaf(p, t, -4.943465398e-03f);
+  p = __builtin_fmaf(p, t, 2.789373016e-02f);
+  p = __builtin_fmaf(p, t, 4.537317152e-02f);
+  p = __builtin_fmaf(p, t, -3.048984958e-01f);
+  p = __builtin_fmaf(p, t, 5.793991491e-01f);
+  const float half_erfc = __builtin_amdgcn_exp2f(-w * w) * p * r;
   const float phi = x < 0.0f ? half_erfc : 1.0f - half_erfc;
   return x * phi;
 }
