@@ -232,29 +232,43 @@ __device__ __forceinline__ float tanh_f32(float xf) {
 // exp(-z^2) P(t) / (z + 3), t = (z - 3) / (z + 3) = 1 - 6 / (z + 3); P has degree 9 (relative error of h below 3.2e-9
 // for z <= 10.5, where the fp32 result has already underflowed to zero; fitted at Chebyshev nodes against 40-digit
 // values, the factor 1/2 folded in).  Then gelu(x) = g + max(x, 0) with g = gelu(-|x|) = -|x| h: for x >= 0 that is
-// x - x h = x (1 - h), and there is one rounding to fp32 at the end.  z is clamped at 40, where exp(-z^2) is exactly
-// 0: -inf * 0 gives the NaN that the IEEE evaluation of x Phi(x) gives at -inf; +inf is put back at the end; a NaN
-// input stays NaN through -|x| h whatever the clamp made of z.
+// x - x h = x (1 - h), and there is one rounding to fp32 at the end.  z is clamped at 25.5 (the fp32 result is 0
+// from z = 10.5 on); the infinities are put in at the end (+inf, and the NaN that the IEEE evaluation of x Phi(x)
+// gives at -inf); a NaN input stays NaN through -|x| h whatever the clamp made of z.
+// All of it runs in w = z sqrt(log2 e), so that exp(-z^2) = 2^(-w^2) needs no multiplication by log2 e: with
+// K = 3 sqrt(log2 e) and r = 1 / (w + K), t = 1 - 2 K r, 1 / (z + 3) = sqrt(log2 e) r (the factor sits in P's
+// coefficients, beside the 1/2), and 2^(-w^2) = 2^n (1 + f S(f)) with n = round(-w^2), f = -w^2 - n in
+// [-1/2, 1/2] and S of degree 5 fitted at Chebyshev nodes to the relative error of 2^f (2.2e-9).
 __device__ __forceinline__ float gelu_erf_f32(float xf) {
   const double x = (double)xf;
-  const double z = __builtin_fmin(__builtin_fabs(x) * 0.70710678118654752440, 40.0);
-  const double r = rcp_d(z + 3.0);
-  const double t = __builtin_fma(-6.0, r, 1.0);
-  double p = -1.63577015667414641e-04;
-  p = fma_k(p, t, -2.42564109869417211e-04);
-  p = fma_k(p, t, 1.54107519290801079e-03);
-  p = fma_k(p, t, -6.12201360389873044e-04);
-  p = fma_k(p, t, -1.34201827593240803e-02);
-  p = fma_k(p, t, 5.97642377890957935e-02);
-  p = fma_k(p, t, -1.55232970811848420e-01);
-  p = fma_k(p, t, 2.95114175237900955e-01);
-  p = fma_k(p, t, -4.41697244752364715e-01);
-  p = fma_k(p, t, 5.37003453557546528e-01);
+  const double w = __builtin_fmin(__builtin_fabs(x) * 8.49321800288019069e-01, 3.06286214240544723e+01);   // z <= 25.5
+  const double r = rcp_d(w + 3.60336722635934947e+00);
+  const double t = __builtin_fma(-7.20673445271869895e+00, r, 1.0);
+  double p = -1.96476019080543929e-04;
+  p = fma_k(p, t, -2.91349187931495444e-04);
+  p = fma_k(p, t, 1.85101994782671270e-03);
+  p = fma_k(p, t, -7.35328772653825731e-04);
+  p = fma_k(p, t, -1.61192822422337248e-02);
+  p = fma_k(p, t, 7.17841652525249146e-02);
+  p = fma_k(p, t, -1.86453799824604027e-01);
+  p = fma_k(p, t, 3.54468249028774052e-01);
+  p = fma_k(p, t, -5.30532458571298382e-01);
+  p = fma_k(p, t, 6.45006881663682696e-01);
+  const double y = -w * w;
+  const double nf = __builtin_rint(y);
+  const double f = y - nf;
+  double q = 1.53707048334774087e-04;
+  q = fma_k(q, f, 1.33998482906884158e-03);
+  q = fma_k(q, f, 9.61837325129530525e-03);
+  q = fma_k(q, f, 5.55032903515319184e-02);
+  q = fma_k(q, f, 2.40226484622816677e-01);
+  q = fma_k(q, f, 6.93147205577100745e-01);
+  const double e = __builtin_ldexp(__builtin_fma(q, f, 1.0), (int)nf);      // exp(-z^2); a result below the normal range goes to 0 gradually
   const double m = __builtin_fmax(x, 0.0);                             // a NaN x: 0, and the product below is NaN
-  const double a = __builtin_fabs(x) * exp6_d(-z * z);                  // h = Phi(-|x|) = exp(-z^2) (p r); g = -|x| h
+  const double a = __builtin_fabs(x) * e;                              // h = Phi(-|x|) = exp(-z^2) (p r); g = -|x| h
   // gelu(x) has the sign of x everywhere, also where it rounds to zero; copying the sign settles -0 + +0
   const float res = __builtin_copysignf((float)__builtin_fma(-a, p * r, m), xf);
-  return xf == __builtin_inff() ? xf : res;
+  return xf == __builtin_inff() ? xf : (xf == -__builtin_inff() ? __uint_as_float(0x7fc00000u) : res);
 }
 
 // log(sigmoid(x)) = min(x, 0) - log1p(e), e = exp(-|x|) in (0, 1], composed in binary64 like the functions above.
