@@ -17,6 +17,11 @@ template <class Op, class T> struct MathStatic {
     if constexpr (sizeof(T) == 2) return cvt<T>(Op::run_half(cvt<float>(x)));
     else return cvt<T>(Op::run(cvt<float>(x)));
   }
+  // the fp32 operators that define run_n evaluate a whole vector at once
+  template <int E, class O = Op, class = decltype(&O::template run_n<E>), class U = T, class = std::enable_if_t<sizeof(U) == 4>>
+  __device__ __forceinline__ void apply_n(const T (&x)[E], T (&y)[E]) const {
+    Op::template run_n<E>(x, y);
+  }
 };
 // float math op on a bool / integer tensor: convert to fp32, fp32 result
 template <class Op> struct MathDyn {

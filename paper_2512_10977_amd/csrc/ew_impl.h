@@ -208,6 +208,12 @@ template <class F> struct Shape {
 
 template <class T> struct TypeTag { using type = T; };
 
+// A unary functor may evaluate the E elements of a vector in one call (apply_n): what its formula keeps in vector
+// registers - the leading coefficient of a polynomial, which the instruction set cannot take from a scalar register
+// beside a second constant - is then set up once per vector and not once per element.
+template <class F, int E, class = void> struct HasApplyN : std::false_type {};
+template <class F, int E> struct HasApplyN<F, E, std::void_t<decltype(&F::template apply_n<E>)>> : std::true_type {};
+
 template <class F, class A, class B, class C>
 __device__ __forceinline__ typename ValueOf<typename F::Out>::type apply(const F& f, A a, B b, C c) {
   if constexpr (F::NIN == 1) return f(a);
@@ -341,8 +347,12 @@ __global__ __launch_bounds__(kBlock) void ew_vec_kernel(const F f, const VecArgs
     for (int u = 0; u < U; ++u) {
       const int64_t i = i0 + (int64_t)u * kBlock * E;
       typename EO::value_t y[E];
+      if constexpr (HasApplyN<F, E>::value) {
+        f.template apply_n<E>(x0[u], y);
+      } else {
 #pragma unroll
-      for (int e = 0; e < E; ++e) y[e] = apply(f, x0[u][e], x1[u][e], x2[u][e]);
+        for (int e = 0; e < E; ++e) y[e] = apply(f, x0[u][e], x1[u][e], x2[u][e]);
+      }
       EO::template store_vec<E>(a.data[0], base[0] + i, a.dtype[0], y);
     }
     return;
@@ -957,6 +967,11 @@ struct OpTanh {
 struct OpGelu {
   static constexpr int VPL = 2;
   __device__ static float run(float x) { return gelu_erf_f32(x); }
+  template <int N> __device__ static void run_n(const float (&x)[N], float (&y)[N]) {
+    const GeluLead k = gelu_lead();
+#pragma unroll
+    for (int i = 0; i < N; ++i) y[i] = gelu_erf_f32(x[i], k);
+  }
   // x * erfc(-x / sqrt 2) / 2: erfc keeps its relative accuracy in the negative tail
   __device__ static float run_half(float x) { return gelu_erf_half(x); }
 };

@@ -18,6 +18,19 @@ __device__ __forceinline__ double fma_k(double a, double b, double k) {
 }
 
 // 1/x to ~1e-14 relative: hardware reciprocal estimate (about 24 bits) + one Newton step
+// a b + 1 and a k + 1 with the 1 as the instruction's inline constant (left to itself the compiler loads it into a
+// register pair and uses the two-operand form)
+__device__ __forceinline__ double fma_1(double a, double b) {
+  double r;
+  asm("v_fma_f64 %0, %1, %2, 1.0" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ double fma_k1(double a, double k) {
+  double r;
+  asm("v_fma_f64 %0, %1, %2, 1.0" : "=v"(r) : "v"(a), "s"(k));
+  return r;
+}
+
 __device__ __forceinline__ double rcp_d(double x) {
   double r = __builtin_amdgcn_rcp(x);
   return __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
@@ -232,19 +245,28 @@ __device__ __forceinline__ float tanh_f32(float xf) {
 // exp(-z^2) P(t) / (z + 3), t = (z - 3) / (z + 3) = 1 - 6 / (z + 3); P has degree 9 (relative error of h below 3.2e-9
 // for z <= 10.5, where the fp32 result has already underflowed to zero; fitted at Chebyshev nodes against 40-digit
 // values, the factor 1/2 folded in).  Then gelu(x) = g + max(x, 0) with g = gelu(-|x|) = -|x| h: for x >= 0 that is
-// x - x h = x (1 - h), and there is one rounding to fp32 at the end.  z is clamped at 25.5 (the fp32 result is 0
-// from z = 10.5 on); the infinities are put in at the end (+inf, and the NaN that the IEEE evaluation of x Phi(x)
-// gives at -inf); a NaN input stays NaN through -|x| h whatever the clamp made of z.
+// x - x h = x (1 - h), and there is one rounding to fp32 at the end.  The infinities are put in at the end (+inf,
+// and the NaN that the IEEE evaluation of x Phi(x) gives at -inf); a NaN input stays NaN through -|x| h.
 // All of it runs in w = z sqrt(log2 e), so that exp(-z^2) = 2^(-w^2) needs no multiplication by log2 e: with
 // K = 3 sqrt(log2 e) and r = 1 / (w + K), t = 1 - 2 K r, 1 / (z + 3) = sqrt(log2 e) r (the factor sits in P's
 // coefficients, beside the 1/2), and 2^(-w^2) = 2^n (1 + f S(f)) with n = round(-w^2), f = -w^2 - n in
 // [-1/2, 1/2] and S of degree 5 fitted at Chebyshev nodes to the relative error of 2^f (2.2e-9).
-__device__ __forceinline__ float gelu_erf_f32(float xf) {
+// The leading coefficients of the two polynomials, held in vector registers: a caller that evaluates several elements
+// fetches them once (gelu_lead) - the empty asm keeps the compiler from re-creating them with two moves per use.
+struct GeluLead {
+  double p9, q5;
+};
+__device__ __forceinline__ GeluLead gelu_lead() {
+  GeluLead k{-1.96476019080543929e-04, 1.53707048334774087e-04};
+  asm("" : "+v"(k.p9), "+v"(k.q5));
+  return k;
+}
+__device__ __forceinline__ float gelu_erf_f32(float xf, const GeluLead k = GeluLead{-1.96476019080543929e-04, 1.53707048334774087e-04}) {
   const double x = (double)xf;
-  const double w = __builtin_fmin(__builtin_fabs(x) * 8.49321800288019069e-01, 3.06286214240544723e+01);   // z <= 25.5
+  const double w = __builtin_fabs(x) * 8.49321800288019069e-01;
   const double r = rcp_d(w + 3.60336722635934947e+00);
-  const double t = __builtin_fma(-7.20673445271869895e+00, r, 1.0);
-  double p = -1.96476019080543929e-04;
+  const double t = fma_k1(r, -7.20673445271869895e+00);
+  double p = k.p9;
   p = fma_k(p, t, -2.91349187931495444e-04);
   p = fma_k(p, t, 1.85101994782671270e-03);
   p = fma_k(p, t, -7.35328772653825731e-04);
@@ -257,14 +279,19 @@ __device__ __forceinline__ float gelu_erf_f32(float xf) {
   const double y = -w * w;
   const double nf = __builtin_rint(y);
   const double f = y - nf;
-  double q = 1.53707048334774087e-04;
+  double q = k.q5;
   q = fma_k(q, f, 1.33998482906884158e-03);
   q = fma_k(q, f, 9.61837325129530525e-03);
   q = fma_k(q, f, 5.55032903515319184e-02);
   q = fma_k(q, f, 2.40226484622816677e-01);
   q = fma_k(q, f, 6.93147205577100745e-01);
-  const double e = __builtin_ldexp(__builtin_fma(q, f, 1.0), (int)nf);      // exp(-z^2); a result below the normal range goes to 0 gradually
-  const double m = __builtin_fmax(x, 0.0);                             // a NaN x: 0, and the product below is NaN
+  // exp(-z^2); a result below the normal range goes to 0 gradually, and a huge w needs no clamp: -w^2 is then an
+  // integer, f = 0, the conversion of n saturates and ldexp returns 0
+  const double e = __builtin_ldexp(fma_1(q, f), (int)nf);
+  // max(x, 0); a NaN x gives 0, and the product below is NaN.  (One instruction: the builtin first canonicalises x
+  // with a max of its own, which a value that comes from a conversion does not need.)
+  double m;
+  asm("v_max_f64 %0, %1, 0" : "=v"(m) : "v"(x));
   const double a = __builtin_fabs(x) * e;                              // h = Phi(-|x|) = exp(-z^2) (p r); g = -|x| h
   // gelu(x) has the sign of x everywhere, also where it rounds to zero; copying the sign settles -0 + +0
   const float res = __builtin_copysignf((float)__builtin_fma(-a, p * r, m), xf);
