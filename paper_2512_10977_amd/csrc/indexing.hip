@@ -1003,7 +1003,8 @@ bool is_row_mode(const tx_tensor* self, int dim, const tx_tensor* index, const t
     if (self->sizes[d] > 1 && (self->strides[d] != inner || src->strides[d] != inner)) return false;
     inner *= self->sizes[d];
   }
-  return inner >= 16 && index->sizes[0] < (1ll << 31) && self->sizes[0] < (1ll << 32);
+  // (a lane's byte offset inside a row is kept in 32 bits)
+  return inner >= 16 && inner * dtype_size(self->dtype) < (1ll << 32) && index->sizes[0] < (1ll << 31) && self->sizes[0] < (1ll << 32);
 }
 
 tx_status scatter_plan(const tx_tensor* self, int dim, const tx_tensor* index, const tx_tensor* src, ScatterPlan* p,
