@@ -212,9 +212,10 @@ def test_sorted_scatter_refuses_two_to_the_31_entries():
     keep = []
 
     def fake(shape, strides, dtype):
-        keep.append(torch.zeros(16, dtype=dtype))           # a buffer of its own, so that no operand overlaps another
+        keep.append(torch.zeros(16, dtype=dtype))
         d = B.desc(keep[-1])
-        d.ndim = len(shape)
+        d.data = len(keep) << 40                            # addresses 1 TiB apart, so that no operand overlaps another whatever
+        d.ndim = len(shape)                                 # extent its descriptor claims (never dereferenced: every call is refused)
         for i, (n, s) in enumerate(zip(shape, strides)):
             d.sizes[i], d.strides[i] = n, s
         return d
@@ -233,4 +234,13 @@ def test_sorted_scatter_refuses_two_to_the_31_entries():
     rows_d = fake((big, 2), (1, 0), torch.int64)             # row mode: 2^31 source rows
     assert lib.tx_scatter_add_workspace_bytes(self_d, 0, rows_d, src_d, 1) == 0
     rc = lib.tx_scatter_add_(self_d, 0, rows_d, src_d, 1, ws.data_ptr(), 1024, None)
+    assert B.STATUS[rc] == "UNSUPPORTED", (rc, lib.tx_last_error())
+    # rows of 4 GiB or more do not take the row path (a lane's byte offset inside a row is kept in 32 bits): the call
+    # falls to element keys, whose own limit (2^32 destination elements) then refuses it
+    wide = 1 << 30
+    self_w = fake((4, wide), (wide, 1), torch.float32)
+    idx_w = fake((8, wide), (1, 0), torch.int64)
+    src_w = fake((8, wide), (wide, 1), torch.float32)
+    assert lib.tx_scatter_add_workspace_bytes(self_w, 0, idx_w, src_w, 1) == 0
+    rc = lib.tx_scatter_add_(self_w, 0, idx_w, src_w, 1, ws.data_ptr(), 1024, None)
     assert B.STATUS[rc] == "UNSUPPORTED", (rc, lib.tx_last_error())
