@@ -604,15 +604,16 @@ def main():
             if w == 0:
                 label(op)
     torch.cuda.synchronize()
-    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
-              for _ in range(args.steps)]
+    # one event after every operator (and one at the head of each step): an operator's time is the distance between
+    # the event before it and the event after it, so consecutive operators share a marker instead of each being
+    # bracketed by a pair of its own (a marker is a barrier on the stream, about 2 us during which nothing runs)
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(ops) + 1)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
+        events[k][0].record()
         for j, op in enumerate(ops):
-            e0, e1 = events[k][j]
-            e0.record()
             op["fn"]()
-            e1.record()
+            events[k][j + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     outside = []
@@ -624,7 +625,7 @@ def main():
     step_elems = sum(op["elems"] for op in ops)
     per_op = []
     for j, op in enumerate(ops):
-        times = sorted(events[k][j][0].elapsed_time(events[k][j][1]) for k in range(args.steps))
+        times = sorted(events[k][j].elapsed_time(events[k][j + 1]) for k in range(args.steps))
         row = op_row(op, sum(times) / args.steps)
         row["us_min"], row["us_median"] = round(times[0] * 1e3, 2), round(times[len(times) // 2] * 1e3, 2)
         per_op.append(row)
