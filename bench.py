@@ -254,13 +254,19 @@ def build_ops(torch, B):
     s3, o3d = sf.view(64, 4096, 512), osf.view(64, 4096, 512)
     extra("log_softmax_f32_dim1[64,4096,512]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(o3d, s3, 1, True))
     sC, oC = sf.view(512, 128, 2048), osf.view(512, 128, 2048)       # softmax over 128 channels
-    extra("softmax_f32_dim1[512,128,2048]", "f3", "softmax_cols_kernel", ns * 8, ns, lambda: B.tx_softmax(oC, sC, 1, False))
+    extra("softmax_f32_dim1[512,128,2048]", "f3", "softmax_cols_reg_kernel", ns * 8, ns, lambda: B.tx_softmax(oC, sC, 1, False))
+    extra("softmax_f32_dim1[512,128,2048]_two_reads", "f3", "softmax_cols_kernel", ns * 8, ns,
+          forced("softmax-cols", lambda: B.tx_softmax(oC, sC, 1, False)))
     wsc = B.workspace(max(B.tx_cumsum_workspace_bytes(oT, lx.view(4096, 32768), 0),
                           B.tx_cumsum_workspace_bytes(osf.view(65536, 2048), lx.view(65536, 2048), 0)))
-    extra("cumsum_f32_dim0[4096,32768]", "f3", "colscan_apply_kernel", ns * 8, ns,
+    extra("cumsum_f32_dim0[4096,32768]", "f3", "colscan_lookback_kernel", ns * 8, ns,
           lambda: B.tx_cumsum(oT, lx.view(4096, 32768), 0, wsc))
-    extra("cumsum_f32_dim0[65536,2048]", "f3", "colscan_apply_kernel", ns * 8, ns,
+    extra("cumsum_f32_dim0[65536,2048]", "f3", "colscan_lookback_kernel", ns * 8, ns,
           lambda: B.tx_cumsum(osf.view(65536, 2048), lx.view(65536, 2048), 0, wsc))
+    extra("cumsum_f32_dim0[4096,32768]_three_passes", "f3", "colscan_apply_kernel", ns * 8, ns,
+          forced("scan-cols-3pass", lambda: B.tx_cumsum(oT, lx.view(4096, 32768), 0, wsc)))
+    extra("cumsum_f32_dim0[65536,2048]_three_passes", "f3", "colscan_apply_kernel", ns * 8, ns,
+          forced("scan-cols-3pass", lambda: B.tx_cumsum(osf.view(65536, 2048), lx.view(65536, 2048), 0, wsc)))
 
     C = (4096, 65536)
     nc = C[0] * C[1]
@@ -473,7 +479,7 @@ PATH_KERNEL = {"vec": "ew_vec_kernel", "vec-bcast": "ew_bcast_kernel", "tile": "
                "rows-wave": "reduce_rows_kernel", "rows-block": "reduce_rows_kernel", "rows-split": "reduce_rows_kernel",
                "cols": "reduce_cols_kernel", "cols-split": "reduce_cols_kernel", "softmax-wave": "softmax_wave_kernel",
                "scan-lookback-wide": "cumsum_lookback_kernel", "scan-lookback": "cumsum_lookback_kernel",
-               "scan-carry": "cumsum_carry_kernel", "softmax-row": "softmax_row_kernel", "index-select-rows": "index_select_rows_kernel",
+               "scan-carry": "cumsum_carry_kernel", "scan-cols-lookback": "colscan_lookback_kernel", "scan-cols-3pass": "colscan_apply_kernel", "softmax-row": "softmax_row_kernel", "index-select-rows": "index_select_rows_kernel",
                "gather": "gather_kernel", "scatter-sort-rows": "seg_rows_kernel", "scatter-atomic": "scatter_add_atomic_kernel"}
 
 

@@ -651,7 +651,12 @@ tx_status tx_lookback_status(const void* ws, void* stream);
  * of up to 1024 16-byte vectors) and "softmax-row" (a 256-lane workgroup per
  * row, 65 to 4096 vectors) where the other would be chosen.  softmax / cumsum along a
  * non-innermost dim: "softmax-strided", "scan-strided" (one lane per slice
- * instead of the column kernels).  layer_norm: "layer-norm-block" (one
+ * instead of the column kernels); "softmax-cols" (the two-read column kernel
+ * also where the operated dim is short enough to stay in registers); cumsum along a non-innermost dim whose
+ * columns are cut into several tiles: "scan-cols-3pass" (tile sums, their
+ * prefixes and the scan as three kernels instead of the single pass with
+ * look-back between tiles, "scan-cols-lookback") and
+ * "scan-cols-lookback-giveup" (poll limit zero, as above).  layer_norm: "layer-norm-block" (one
  * workgroup per row), "layer-norm-generic" (three passes, any strides).
  * masked_select: "select-fused" (one pass with decoupled look-back instead of
  * the count, offsets and write passes).  binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace

@@ -47,7 +47,7 @@ def check_cumsum(x_cpu, dim=-1, out_dtype=None, what=""):
         xd = torch.where(xd.isfinite(), xd, torch.zeros_like(xd))
         scale = (xd * xd).cumsum(dim if x_cpu.dim() else 0).sqrt() if x_cpu.dim() else xd.abs()
         assert_rel(out, want, 1e-5 if want.dtype == F32 else 1e-2, scale, what)
-    if ws is not None and used.startswith("scan-lookback"):
+    if ws is not None and (used.startswith("scan-lookback") or used.startswith("scan-cols-lookback")):
         B.tx_lookback_status(ws)                       # raises if a bounded look-back wait gave up
     return used
 
@@ -217,17 +217,29 @@ def test_softmax_column_form(log):
         for shape, dim in COL_SHAPES:
             x = I.softmax_logits(shape, dt, seed=330 + len(shape))
             used = check_softmax(x, dim, log)
-            assert used == ("softmax-cols" if shape[dim] >= 2 else "softmax-strided"), (shape, dim, used)
+            L = shape[dim]
+            # an operated dim of at most 128 stays in registers (one read); longer ones take the two-read kernel
+            assert used.startswith("softmax-cols-reg" if 2 <= L <= 128 else "softmax-cols" if L >= 2 else "softmax-strided"), (shape, dim, used)
+            if 2 <= L <= 128:
+                B.tx_force_path("softmax-cols")
+                try:
+                    assert check_softmax(x, dim, log, what="two reads by name") == "softmax-cols"
+                finally:
+                    B.tx_force_path(None)
+        for L in (2, 16, 17, 32, 33, 64, 65, 128, 129):                 # every workgroup size of the register form, and just past it
+            x = I.softmax_logits((3, L, 132), dt, seed=334 + L)
+            assert check_softmax(x, 1, log) == ("softmax-cols-reg" if L <= 128 else "softmax-cols"), L
         x = I.softmax_logits((6, 70, 48), dt, seed=331)
-        assert check_softmax(x.transpose(0, 1), 1, log, what="outer stride") == "softmax-cols"
-        assert check_softmax(x[:, ::2], 1, log, what="strided L") == "softmax-cols"
-        assert check_softmax(x[..., 1:33], 1, log, what="offset columns") == "softmax-cols"
+        assert check_softmax(x.transpose(0, 1), 1, log, what="outer stride") == "softmax-cols-reg"
+        assert check_softmax(x[:, ::2], 1, log, what="strided L") == "softmax-cols-reg"
+        assert check_softmax(x[..., 1:33], 1, log, what="offset columns") == "softmax-cols-reg-scalar"
         assert check_softmax(x[..., ::2], 1, log, what="strided inner") == "softmax-strided"
     check_softmax(I.softmax_logits((300, 512), BF16, seed=332), 0, log, out_dtype=F32, what="fp32 out")
     inf, nan = float("inf"), float("nan")
     cols = torch.tensor([[0.0, -inf, 1.0, 2.0], [-inf, -inf, -inf, -inf], [0.0, inf, 1.0, 0.5], [0.0, nan, 1.0, 0.5],
                          [5.0, 5.0, 5.0, 5.0], [-inf, 1.0, inf, nan]]).t().contiguous()        # one case per column
     assert check_softmax(cols.repeat(40, 8), 0, log, what="special columns") == "softmax-cols"
+    assert check_softmax(cols.repeat(10, 8), 0, log, what="special columns, short") == "softmax-cols-reg"
     B.tx_force_path("softmax-strided")
     try:
         assert check_softmax(I.softmax_logits((40, 64), F32, seed=333), 0, log) == "softmax-strided"
@@ -244,25 +256,63 @@ def test_cumsum_column_form():
         x = I.cumsum_input((6, 70, 48), dt, seed=341) if dt != BOOL else I.booleans((6, 70, 48), 0.5, seed=341)
         assert check_cumsum(x.transpose(0, 1), 1, what="outer stride").startswith("scan-cols")
         assert check_cumsum(x[:, ::2], 1, what="strided L").startswith("scan-cols")
-        assert check_cumsum(x[..., 1:33], 1, what="offset columns") == "scan-cols-scalar"
+        assert check_cumsum(x[..., 1:33], 1, what="offset columns") == "scan-cols-lookback-scalar"
         assert check_cumsum(x[..., ::2], 1, what="strided inner") == "scan-strided"
     check_cumsum(I.cumsum_input((3000, 64), BF16, seed=342), 0, out_dtype=F32, what="fp32 out")
-    # long columns on few strips: several tiles per column (the three-pass form) and the workspace check
+    # long columns on few strips: several tiles per column (the single pass with look-back between the tiles, and the
+    # three-pass form by name, on every accumulator type and vector width) and the workspace check
+    paths = set()
+    for dt, shape in [(F32, (70000, 128)), (I64, (70000, 48)), (I32, (9000, 260)), (BOOL, (5000, 64)), (BF16, (4, 3000, 520)),
+                      (F16, (2500, 33)), (F32, (2, 129, 4100))]:
+        x = I.cumsum_input(shape, dt, seed=343) if dt != BOOL else I.booleans(shape, 0.5, seed=343)
+        dim = len(shape) - 2
+        paths.add(check_cumsum(x, dim, what="look-back"))
+        B.tx_force_path("scan-cols-3pass")
+        try:
+            paths.add(check_cumsum(x, dim, what="three passes"))
+        finally:
+            B.tx_force_path(None)
+    assert paths == {"scan-cols-lookback", "scan-cols-lookback-scalar", "scan-cols-3pass", "scan-cols-3pass-scalar"}, paths
     x = I.cumsum_input((70000, 128), F32, seed=343)
-    assert check_cumsum(x, 0) == "scan-cols"
     dx, out = x.cuda(), torch.empty(x.shape, device="cuda")
     assert B.tx_cumsum_workspace_bytes(out, dx, 0) > 0
     with pytest.raises(B.TxError) as e:
         B.tx_cumsum(out, dx, 0, None)
     assert e.value.kind == "WORKSPACE"
-    check_cumsum(I.cumsum_input((70000, 48), I64, seed=344), 0)
+    # a poll limit of zero (set by the host): every tile below the first gives up at once, ends normally and leaves the flag
+    ws = B.workspace(B.tx_cumsum_workspace_bytes(out, dx, 0))
+    B.tx_cumsum(out, dx, 0, ws)
+    B.tx_lookback_status(ws)
+    B.tx_force_path("scan-cols-lookback-giveup")
+    try:
+        B.tx_cumsum(out, dx, 0, ws)
+        assert B.tx_last_path() == "scan-cols-lookback"
+    finally:
+        B.tx_force_path(None)
+    with pytest.raises(B.TxError) as e:
+        B.tx_lookback_status(ws)
+    assert e.value.kind == "LAUNCH" and "gave up" in str(e.value)
+    B.tx_cumsum(out, dx, 0, ws)                                      # the next run clears the flag
+    B.tx_lookback_status(ws)
+
+
+def test_softmax_short_column_full_size():
+    x = I.softmax_logits((512, 128, 2048), F32, seed=351)             # softmax over 128 channels: rows stay in registers
+    for log in (False, True):
+        assert check_softmax(x, 1, log) == "softmax-cols-reg"
+    assert check_softmax(I.softmax_logits((512, 128, 2048), BF16, seed=352), 1, False) == "softmax-cols-reg"
 
 
 @pytest.mark.parametrize("shape,dim", [((4096, 32768), 0), ((64, 4096, 512), 1), ((65536, 2048), 0)])
 def test_column_forms_full_size(shape, dim):
     x = I.softmax_logits(shape, F32, seed=350)
     assert check_softmax(x, dim, False) == "softmax-cols"
-    assert check_cumsum(x, dim) == "scan-cols"
+    assert check_cumsum(x, dim) == "scan-cols-lookback"
+    B.tx_force_path("scan-cols-3pass")
+    try:
+        assert check_cumsum(x, dim) == "scan-cols-3pass"
+    finally:
+        B.tx_force_path(None)
 
 
 # --------------------------------------------------------------------------- cumprod, logcumsumexp
