@@ -219,6 +219,26 @@ template <class T> struct LsePolicy {
     a.s = __builtin_fmaf(e, le ? 1.0f : a.s, le ? a.s : 1.0f);
     a.m = __builtin_fmaxf(a.m, v);
   }
+  // N consecutive elements at once (the row kernels): the maximum moves first, the old sum is rescaled once, and the
+  // N exponentials are independent of each other - a lane's chain is one rescale and N additions per vector instead
+  // of N dependent steps.  The differences are taken against the maximum clamped to the finite range, so that an
+  // infinite maximum gives exp(+inf) = inf or exp(-inf) = 0 and never inf - inf (finish returns an infinite maximum as it
+  // is; only a NaN element makes s NaN).
+  template <int N> __device__ static void step_n(Acc& a, const Vec<T, N>& x) {
+    float v[N];
+    float M = a.m;
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      v[e] = cvt<float>(x.v[e]);
+      M = __builtin_fmaxf(M, v[e]);
+    }
+    const float Ms = __builtin_fminf(__builtin_fmaxf(M, -3.4028234663852886e38f), 3.4028234663852886e38f);
+    float s = a.s * __expf(a.m - Ms);
+#pragma unroll
+    for (int e = 0; e < N; ++e) s += __expf(v[e] - Ms);
+    a.s = s;
+    a.m = M;
+  }
   __device__ static Acc shfl(const Acc& a, int m) { return Acc{shfl_xor(a.m, m), shfl_xor(a.s, m)}; }
   __device__ static void finish(const Acc& a, int64_t, double, double, double* f, int64_t*) {
     const bool inf = a.m == __uint_as_float(0x7f800000u) || a.m == __uint_as_float(0xff800000u);
@@ -396,6 +416,19 @@ __device__ __forceinline__ void kept_offsets(const Args& a, int64_t o, int64_t* 
   *oo = y;
 }
 
+// one vector of a row: a policy may take the whole vector in one call (step_n), else its elements go one by one
+template <class P, int N, class = void> struct HasStepN : std::false_type {};
+template <class P, int N> struct HasStepN<P, N, std::void_t<decltype(&P::template step_n<N>)>> : std::true_type {};
+template <class P, class T, int VEC>
+__device__ __forceinline__ void step_vec(typename P::Acc& acc, const Vec<T, VEC>& v, int64_t pos, double K) {
+  if constexpr (HasStepN<P, VEC>::value) {
+    P::template step_n<VEC>(acc, v);
+  } else {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) P::step(acc, v.v[e], pos + e, K);
+  }
+}
+
 // ---------------------------------------------------------------------------
 // rows kernel: grid.x = ceil(nout / groups_per_block), grid.y = split
 // ---------------------------------------------------------------------------
@@ -433,22 +466,17 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const Args a) {
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) v[u] = vec_load<T, VEC, true>(x + roff(r + u * stride));
 #pragma unroll
-      for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) P::step(acc, v[u].v[e], r + u * stride + e, K);
+      for (int u = 0; u < kUnroll; ++u) step_vec<P, T, VEC>(acc, v[u], r + u * stride, K);
     }
     if (r + stride < end) {                    // two left (short rows never enter the loop above)
       Vec<T, VEC> v0 = vec_load<T, VEC, true>(x + roff(r)), v1 = vec_load<T, VEC, true>(x + roff(r + stride));
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) P::step(acc, v0.v[e], r + e, K);
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) P::step(acc, v1.v[e], r + stride + e, K);
+      step_vec<P, T, VEC>(acc, v0, r, K);
+      step_vec<P, T, VEC>(acc, v1, r + stride, K);
       r += 2 * stride;
     }
     for (; r < end; r += stride) {
       Vec<T, VEC> v = vec_load<T, VEC, true>(x + roff(r));
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) P::step(acc, v.v[e], r + e, K);
+      step_vec<P, T, VEC>(acc, v, r, K);
     }
   }
   // lanes of a wave
