@@ -27,7 +27,7 @@ __device__ __forceinline__ float heavy_f32(int op, float xf) {
     case TX_ASINH: y = asinh(x); break;
     case TX_ACOSH: y = acosh(x); break;
     case TX_ATANH: y = atanh(x); break;
-    case TX_ERF: y = erf(x); break;
+    case TX_ERF: return erf_f32(xf);
     case TX_ERFC: y = erfc(x); break;
     default: return mish_f32(xf);                                    // TX_MISH
   }
@@ -49,6 +49,14 @@ __device__ __forceinline__ float heavy_half(int op, float x) {
     default: return x * tanhf(log1pf(expf(x)));
   }
 }
+// erf and mish on a plain fp32 tensor: their own binary64 compositions, compiled apart from the library routines so
+// that they do not inherit those routines' register budget, two vectors per lane like the other composed functions
+template <int OP> struct OwnF32 {
+  using Out = float; using In0 = float; using In1 = void; using In2 = void;
+  static constexpr int NIN = 1;
+  static constexpr int VPL = 2;
+  __device__ __forceinline__ float operator()(float x) const { return OP == TX_ERF ? erf_f32(x) : mish_f32(x); }
+};
 template <class T> struct HeavyOp {
   using Out = T; using In0 = T; using In1 = void; using In2 = void;
   static constexpr int NIN = 1;
@@ -292,6 +300,8 @@ tx_status ew_unary_fourth(const Iter& it, int op, int in_dtype, int rd, hipStrea
     return launch_ew(it, CheapOp<f16>{op}, s);
   }
   if (!plain) return launch_ew(it, HeavyOpDyn{op, rd}, s);
+  if (rd == TX_F32 && op == TX_ERF) return launch_ew(it, OwnF32<TX_ERF>{}, s);
+  if (rd == TX_F32 && op == TX_MISH) return launch_ew(it, OwnF32<TX_MISH>{}, s);
   if (rd == TX_F32) return launch_ew(it, HeavyOp<float>{op}, s);
   if (rd == TX_BF16) return launch_ew(it, HeavyOp<bf16>{op}, s);
   return launch_ew(it, HeavyOp<f16>{op}, s);

@@ -130,6 +130,19 @@ __device__ __forceinline__ float param_op_half(const Params& a, float x) {
     default: return x != x ? p0 : (__builtin_fabsf(x) == __builtin_inff() ? (x > 0.0f ? p1 : p2) : x);
   }
 }
+// softplus on a plain fp32 tensor, compiled apart from the other parametrised operators (no run-time operator code,
+// the reciprocal of beta computed by the host), two vectors per lane like the other composed functions
+struct SoftplusF32 {
+  using Out = float; using In0 = float; using In1 = void; using In2 = void;
+  static constexpr int NIN = 1;
+  static constexpr int VPL = 2;
+  double beta, inv_beta, threshold;
+  __device__ __forceinline__ float operator()(float xf) const {
+    const double x = (double)xf;
+    const double t = x * beta;
+    return (float)(t > threshold ? x : (t != t ? t : softplus_d(t) * inv_beta));
+  }
+};
 struct ParamOpF32 {
   using Out = float; using In0 = float; using In1 = void; using In2 = void;
   static constexpr int NIN = 1;
@@ -287,6 +300,7 @@ tx_status tx_unary_param(int op, const tx_tensor* out, const tx_tensor* a, doubl
   if (op == TX_ROUND_DECIMALS) pa.p1 = (double)(float)std::pow(10.0, std::fabs(p0));
   if (op == TX_NAN_TO_NUM) { pa.p0 = (double)host_round_half(p0, rd); pa.p1 = (double)host_round_half(p1, rd); pa.p2 = (double)host_round_half(p2, rd); }
   if (a->dtype == rd) {
+    if (rd == TX_F32 && op == TX_SOFTPLUS) return launch_ew(it, SoftplusF32{p0, 1.0 / p0, p1}, s);
     if (rd == TX_F32) return launch_ew(it, ParamOpF32{pa}, s);
     if (rd == TX_BF16) return launch_ew(it, ParamOpHalf<bf16>{pa}, s);
     return launch_ew(it, ParamOpHalf<f16>{pa}, s);

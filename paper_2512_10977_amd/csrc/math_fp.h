@@ -261,9 +261,8 @@ __device__ __forceinline__ GeluLead gelu_lead() {
   asm("" : "+v"(k.p9), "+v"(k.q5));
   return k;
 }
-__device__ __forceinline__ float gelu_erf_f32(float xf, const GeluLead k = GeluLead{-1.96476019080543929e-04, 1.53707048334774087e-04}) {
-  const double x = (double)xf;
-  const double w = __builtin_fabs(x) * 8.49321800288019069e-01;
+// The two factors of h = erfc(z) / 2 = 2^(-w^2) (P(t) r) for w = z sqrt(log2 e) >= 0: P(t) with r = 1 / (w + K) ...
+__device__ __forceinline__ double half_erfc_poly_w(double w, const GeluLead k, double* r_out) {
   const double r = rcp_d(w + 3.60336722635934947e+00);
   const double t = fma_k1(r, -7.20673445271869895e+00);
   double p = k.p9;
@@ -276,6 +275,12 @@ __device__ __forceinline__ float gelu_erf_f32(float xf, const GeluLead k = GeluL
   p = fma_k(p, t, 3.54468249028774052e-01);
   p = fma_k(p, t, -5.30532458571298382e-01);
   p = fma_k(p, t, 6.45006881663682696e-01);
+  *r_out = r;
+  return p;
+}
+// ... and 2^(-w^2); a result below the normal range goes to 0 gradually, and a huge finite w needs no clamp: -w^2 is
+// then an integer, f = 0, the conversion of n saturates and ldexp returns 0
+__device__ __forceinline__ double exp2_neg_sq_w(double w, const GeluLead k) {
   const double y = -w * w;
   const double nf = __builtin_rint(y);
   const double f = y - nf;
@@ -285,9 +290,14 @@ __device__ __forceinline__ float gelu_erf_f32(float xf, const GeluLead k = GeluL
   q = fma_k(q, f, 5.55032903515319184e-02);
   q = fma_k(q, f, 2.40226484622816677e-01);
   q = fma_k(q, f, 6.93147205577100745e-01);
-  // exp(-z^2); a result below the normal range goes to 0 gradually, and a huge w needs no clamp: -w^2 is then an
-  // integer, f = 0, the conversion of n saturates and ldexp returns 0
-  const double e = __builtin_ldexp(fma_1(q, f), (int)nf);
+  return __builtin_ldexp(fma_1(q, f), (int)nf);
+}
+__device__ __forceinline__ float gelu_erf_f32(float xf, const GeluLead k = GeluLead{-1.96476019080543929e-04, 1.53707048334774087e-04}) {
+  const double x = (double)xf;
+  const double w = __builtin_fabs(x) * 8.49321800288019069e-01;
+  double r;
+  const double p = half_erfc_poly_w(w, k, &r);
+  const double e = exp2_neg_sq_w(w, k);
   // max(x, 0); a NaN x gives 0, and the product below is NaN.  (One instruction: the builtin first canonicalises x
   // with a max of its own, which a value that comes from a conversion does not need.)
   double m;
@@ -296,6 +306,32 @@ __device__ __forceinline__ float gelu_erf_f32(float xf, const GeluLead k = GeluL
   // gelu(x) has the sign of x everywhere, also where it rounds to zero; copying the sign settles -0 + +0
   const float res = __builtin_copysignf((float)__builtin_fma(-a, p * r, m), xf);
   return xf == __builtin_inff() ? xf : (xf == -__builtin_inff() ? __uint_as_float(0x7fc00000u) : res);
+}
+
+// erf(x) from the same two factors with z = |x| (so w = |x| sqrt(log2 e)): 1 - 2 h, with the sign of x, from
+// |x| = 1/4 on, where h <= 0.37 carries its 3.2e-9 relative error into 1 - 2 h as at most 8e-9 of the result; below
+// that the Maclaurin series x (c0 + c1 x^2 + ... + c6 x^12), whose first dropped term is 5e-14 of the result there.
+// |x| is clamped at 6 (erf rounds to 1 in fp32 from 3.93 on; the clamp also keeps the infinities out of -w^2 - n);
+// a NaN x is returned as it is.
+__device__ __forceinline__ float erf_f32(float xf, const GeluLead k = GeluLead{-1.96476019080543929e-04, 1.53707048334774087e-04}) {
+  const double x = (double)xf;
+  double ax = __builtin_fabs(x);
+  ax = ax < 6.0 ? ax : 6.0;
+  const double w = ax * 1.20112240878644982e+00;
+  double r;
+  const double p = half_erfc_poly_w(w, k, &r);
+  const double e = exp2_neg_sq_w(w, k);
+  const double tail = __builtin_fma(-2.0 * e, p * r, 1.0);
+  const double u = ax * ax;
+  double c = 1.20553329817896636e-04;
+  c = fma_k(c, u, -8.54832702345085333e-04);
+  c = fma_k(c, u, 5.22397762544218793e-03);
+  c = fma_k(c, u, -2.68661706451312522e-02);
+  c = fma_k(c, u, 1.12837916709551261e-01);
+  c = fma_k(c, u, -3.76126389031837538e-01);
+  c = fma_k(c, u, 1.12837916709551256e+00);
+  const float res = __builtin_copysignf((float)(ax < 0.25 ? ax * c : tail), xf);
+  return xf != xf ? xf : res;
 }
 
 // log(sigmoid(x)) = min(x, 0) - log1p(e), e = exp(-|x|) in (0, 1], composed in binary64 like the functions above.
