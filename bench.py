@@ -284,6 +284,8 @@ def build_ops(torch, B):
         finally:
             B.tx_force_path(None)
     extra("cumsum_f32_row_carry", "a11", "cumsum_carry_kernel", nc * 8, nc, carry_f32)
+    extra("cumsum_f32_look_back_16KiB_tiles", "a11", "cumsum_lookback_kernel", nc * 8, nc,
+          forced("scan-lookback-narrow", lambda: B.tx_cumsum(ocf, cf, -1, wsf)))
     wsp = B.workspace(B.tx_scan_workspace_bytes("cumprod", ocf, cf, -1))
     extra("cumprod_f32", "f3", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_scan("cumprod", ocf, cf, -1, wsp))
     extra("logcumsumexp_f32", "f3", "cumsum_lookback_kernel", nc * 8, nc, lambda: B.tx_scan("logcumsumexp", ocf, cf, -1, wsp))
