@@ -59,7 +59,7 @@ __device__ __forceinline__ void ms_merge(float& m, float& s, float m2, float s2)
 // VEC columns per lane, CPW column-lanes per wave (the other 64 / CPW lanes of a wave take further rows)
 template <class T, class O, int VEC, int CPW>
 __global__ __launch_bounds__(kColBlock) void softmax_cols_kernel(const ColArgs a) {
-  constexpr int RL = kWave / CPW, CW = CPW * VEC, RS = kColWaves * RL, U = 4;
+  constexpr int RL = kWave / CPW, CW = CPW * VEC, RS = kColWaves * RL, U = VEC == 1 ? 16 : 4;
   __shared__ float lm[kColWaves][CW], ls[kColWaves][CW];
   const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
   const int cl = lane % CPW, rl = lane / CPW;
@@ -642,6 +642,9 @@ tx_status softmax_cols_typed(const tx_tensor* out, const tx_tensor* x, const Col
   set_path("softmax-cols");
   const dim3 grid((unsigned)blocks);
   if (cw == kWave * V) hipLaunchKernelGGL((softmax_cols_kernel<T, O, V, kWave>), grid, dim3(kColBlock), 0, stream, a);
+  // a 64-column strip of an aligned tensor: 16 column-lanes of 4 columns, so that a wave's load still moves 1 KiB
+  // (four row segments of 256 bytes) and a lane holds 64 bytes in flight instead of 16
+  else if (cw == kWave && al) hipLaunchKernelGGL((softmax_cols_kernel<T, O, V, kWave / V>), grid, dim3(kColBlock), 0, stream, a);
   else if (cw == kWave) hipLaunchKernelGGL((softmax_cols_kernel<T, O, 1, kWave>), grid, dim3(kColBlock), 0, stream, a);
   else hipLaunchKernelGGL((softmax_cols_kernel<T, O, 1, 16>), grid, dim3(kColBlock), 0, stream, a);
   return check_launch("softmax column kernel");
