@@ -516,6 +516,19 @@ def time_launches(torch, fn, count, warm):
     return e0.elapsed_time(e1) / count
 
 
+def time_median(torch, fn, count):
+    """Median time in ms of `count` launches in a row, one event after each (a host stall between two launches then
+    lengthens one sample, not the figure)."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(count + 1)]
+    ev[0].record()
+    for i in range(count):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    t = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(count))
+    return t[count // 2]
+
+
 def measurement_detail(torch, B):
     """Numbers beside the step: workload 1 with rotating and with one output buffer and as a single launch;
     1 GiB probes (copy, pure read, pure write) that show what this GPU sustains on the simplest kernels."""
@@ -625,8 +638,8 @@ def main():
             events[k][j + 1].record()
     torch.cuda.synchronize()
     wall_marked = time.perf_counter() - t0
-    mean_ms = [sum(events[k][j].elapsed_time(events[k][j + 1]) for k in range(args.steps)) / args.steps for j in range(len(ops))]
-    jdom = max(range(len(ops)), key=lambda j: mean_ms[j]) if ops else -1
+    med_ms = [sorted(events[k][j].elapsed_time(events[k][j + 1]) for k in range(args.steps))[args.steps // 2] for j in range(len(ops))]
+    jdom = max(range(len(ops)), key=lambda j: med_ms[j]) if ops else -1
     # Timed pass: exactly `steps` steps between two synchronisations, with one pair of events per step, around the
     # operator that takes the largest share of the step (the roofline object of the headline is measured here).
     dom_events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -642,17 +655,20 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     outside = []
-    for op in extras:                        # alternatives the dispatcher did not choose: one warm-up, four timed launches
+    for op in extras:                        # alternatives the dispatcher did not choose: one warm-up, the median of five launches
         op["fn"]()
         label(op)
-        outside.append(op_row(op, time_launches(torch, op["fn"], 4, 0)))
+        outside.append(op_row(op, time_median(torch, op["fn"], 5)))
     step_bytes = sum(op["bytes"] for op in ops)
     step_elems = sum(op["elems"] for op in ops)
     per_op = []
     for j, op in enumerate(ops):
+        # the table's figure is the median over the steps: the distance between two events also holds any time the
+        # stream sat idle because the host fell behind (one such stall, about 1 ms, in one step of ten, doubled an
+        # operator's mean in one run); the mean and the minimum are kept beside it
         times = sorted(events[k][j].elapsed_time(events[k][j + 1]) for k in range(args.steps))
-        row = op_row(op, sum(times) / args.steps)
-        row["us_min"], row["us_median"] = round(times[0] * 1e3, 2), round(times[len(times) // 2] * 1e3, 2)
+        row = op_row(op, times[len(times) // 2])
+        row["us_min"], row["us_mean"] = round(times[0] * 1e3, 2), round(sum(times) / args.steps * 1e3, 2)
         per_op.append(row)
     for r in per_op:                         # stored counter readings: traffic and the rate in bytes actually moved
         if r["op"] in PMC_TRAFFIC_BYTES:
