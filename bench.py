@@ -384,8 +384,10 @@ def build_ops(torch, B):
     sparse = torch.where(mask, src, torch.zeros((), device=dev))
     onz = torch.empty((NS * W // 2, 2), device=dev, dtype=I64)
     wsn = B.workspace(B.tx_nonzero_workspace_bytes(onz, cnt, sparse))
-    extra("nonzero_f32_p0.3", "f3", "select_write_kernel", NS * W * 4 + nsel * 16, NS * W,
+    extra("nonzero_f32_p0.3", "f3", "nonzero_fused_kernel", NS * W * 4 + nsel * 16, NS * W,
           lambda: B.tx_nonzero(onz, cnt, sparse, wsn))
+    extra("nonzero_f32_p0.3_three_passes", "f3", "select_write_kernel", NS * W * 4 + nsel * 16, NS * W,
+          forced("select-3pass", lambda: B.tx_nonzero(onz, cnt, sparse, wsn)))
     # 1 GiB probes: the simplest kernels of the library on known traffic (what a copy, a pure read and a pure write sustain)
     pn = 1 << 28
     px1 = rf.view(-1)[:pn]

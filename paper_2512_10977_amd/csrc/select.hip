@@ -530,6 +530,120 @@ __global__ __launch_bounds__(kFusedBlock) void select_fused_quad_kernel(const Se
   }
 }
 
+// nonzero in one pass: the flags are read once (for nonzero they are the input itself, so the count pass of the
+// three-pass form costs a whole read of x), the tile's output offset comes from the same look-back as above, and the
+// coordinates are written by consecutive lanes to consecutive output rows: every wave first parks the tile-local
+// index of each of its non-zero elements in LDS, in output order (16 bits each: a wave covers 2048 elements), and
+// then walks that list 64 entries at a time.  With two coordinates per row and dense rows a lane's row is one
+// 16-byte store.  (The quad form of the three-pass write kernel, whose lanes each store the rows of their own
+// four elements, wrote four interleaved streams: 1013 us against 758 us for one element per lane.)
+typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
+template <int FES>
+__global__ __launch_bounds__(kFusedBlock) void nonzero_fused_kernel(const SelectArgs a, int64_t ntiles, int pair_rows) {
+  constexpr int kPerWave = kFusedQuads * 4 * kWave;                      // 2048
+  __shared__ uint32_t wave_count[kFusedWaves];
+  __shared__ unsigned int my_ticket;
+  __shared__ uint32_t tile_offset;
+  __shared__ uint16_t ids[kFusedWaves][kPerWave];
+  SelectHeader* hdr = (SelectHeader*)a.offsets;
+  unsigned long long* status = (unsigned long long*)((char*)a.offsets + 256);
+  if (threadIdx.x == 0) my_ticket = atomicAdd(&hdr->ticket, 1u);
+  __syncthreads();
+  const int64_t tile = my_ticket;
+  if (tile >= ntiles) return;
+  const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+  const int64_t wave_base = tile * kFusedTile + (int64_t)w * kPerWave;
+  uint32_t f[kFusedQuads];
+#pragma unroll
+  for (int q = 0; q < kFusedQuads; ++q) {
+    const int64_t i = wave_base + q * (4 * kWave) + lane * 4;
+    f[q] = quad_flags<FES, true>(a.flag, i < a.shape.numel ? i : 0, a.zmask);      // clamped: unconditional load
+  }
+  const unsigned long long below = (1ull << lane) - 1ull;
+  uint32_t c = 0;
+#pragma unroll
+  for (int q = 0; q < kFusedQuads; ++q) {
+    const int64_t i = wave_base + q * (4 * kWave) + lane * 4;
+    f[q] = i < a.shape.numel ? f[q] : 0u;
+    const uint32_t n = (uint32_t)__popc(f[q]);
+    const unsigned long long b0 = __ballot(n & 1u), b1 = __ballot(n & 2u), b2 = __ballot(n & 4u);
+    const uint32_t lane_prefix = (uint32_t)(__popcll(b0 & below) + 2 * __popcll(b1 & below) + 4 * __popcll(b2 & below));
+    const uint32_t quad_total = (uint32_t)(__popcll(b0) + 2 * __popcll(b1) + 4 * __popcll(b2));
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if ((f[q] >> j) & 1u) ids[w][c + lane_prefix + __popc(f[q] & ((1u << j) - 1u))] = (uint16_t)(q * (4 * kWave) + lane * 4 + j);
+    c += quad_total;
+  }
+  if (lane == 0) wave_count[w] = c;
+  __syncthreads();
+  if (w == 0) {
+    uint32_t total = lane < kFusedWaves ? wave_count[lane] : 0u;
+#pragma unroll
+    for (int m = kWave / 2; m >= 1; m >>= 1) total += shfl_xor(total, m);
+    uint32_t prefix = 0;
+    auto publish = [&](uint32_t flag, uint32_t v) {
+      __hip_atomic_store(status + tile, ((unsigned long long)flag << 32) | v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    if (tile == 0) {
+      if (lane == 0) publish(kTilePrefix, total);
+    } else {
+      if (lane == 0) publish(kTileAggregate, total);
+      int64_t look = tile - 1;
+      bool done = false;
+      while (!done) {
+        const int64_t mine = look - lane;                  // lane i inspects predecessor look - i
+        uint32_t val = 0, flag = kTilePrefix;              // before the first tile: an empty prefix
+        if (mine >= 0) {
+          int spins = 0;
+          do {
+            const unsigned long long word = __hip_atomic_load(status + mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            flag = (uint32_t)(word >> 32);
+            val = (uint32_t)word;
+            if (flag != kTileEmpty) break;
+            __builtin_amdgcn_s_sleep(2);
+          } while (++spins < kSelectSpinLimit);
+          if (flag == kTileEmpty) { hdr->error = 1; flag = kTilePrefix; val = 0; }
+        }
+        const unsigned long long has_prefix = __ballot(flag == kTilePrefix);
+        const int stop = __ffsll((long long)has_prefix) - 1;             // nearest predecessor holding a full prefix
+        uint32_t contrib = (mine >= 0 && (stop < 0 || lane <= stop)) ? val : 0u;
+#pragma unroll
+        for (int m = kWave / 2; m >= 1; m >>= 1) contrib += shfl_xor(contrib, m);
+        prefix += contrib;
+        if (stop >= 0) done = true;
+        else look -= kWave;
+      }
+      if (lane == 0) publish(kTilePrefix, prefix + total);
+    }
+    if (lane == 0) {
+      tile_offset = prefix;
+      if (tile == ntiles - 1) *a.count = (int64_t)prefix + (int64_t)total;
+    }
+  }
+  __syncthreads();
+  int64_t pos = tile_offset;
+  for (int i = 0; i < w; ++i) pos += wave_count[i];
+  for (uint32_t t = lane; t < c; t += kWave) {
+    const int64_t dst = pos + t;
+    if (dst >= a.capacity) break;                          // later entries of this lane lie further on still
+    uint32_t rem = (uint32_t)(wave_base + ids[w][t]);
+    if (pair_rows) {
+      uint32_t q, m;
+      a.shape.div[1].divmod(rem, q, m);
+      const u64x2 row = {(unsigned long long)q, (unsigned long long)m};
+      __builtin_nontemporal_store(row, (u64x2*)a.out + dst);
+    } else {
+      int64_t* row = (int64_t*)a.out + dst * a.ostride0;
+      for (int d = a.shape.n - 1; d >= 0; --d) {
+        uint32_t q, m;
+        a.shape.div[d].divmod(rem, q, m);
+        rem = q;
+        row[d * a.ostride1] = (int64_t)m;
+      }
+    }
+  }
+}
+
 inline int64_t fused_tiles(int64_t n) { return (n + kFusedTile - 1) / kFusedTile; }
 inline size_t fused_ws_bytes(int64_t n) { return 256 + (size_t)fused_tiles(n) * 8; }
 
@@ -553,6 +667,20 @@ tx_status run_select(SelectArgs& a, void* ws, hipStream_t stream) {
       hipLaunchKernelGGL((select_fused_quad_kernel<FES, PES>), dim3((unsigned)ntiles), dim3(kFusedBlock), 0, stream, a, ntiles);
       set_path("select-fused");
       return check_launch("single-pass compaction kernel");
+    }
+  }
+  if constexpr (NONZERO) {
+    // the input is its own flag tensor here, so the single pass saves a whole read of it ("select-3pass" keeps the
+    // count, offsets and write kernels)
+    if (quad && a.shape.numel > 0 && strcmp(forced_path(), "select-3pass") != 0) {
+      const int64_t ntiles = fused_tiles(a.shape.numel);
+      const int64_t words = (int64_t)(fused_ws_bytes(a.shape.numel) / 8);
+      const int pair_rows = a.shape.n == 2 && a.ostride0 == 2 && a.ostride1 == 1 && (uintptr_t)a.out % 16 == 0;
+      hipLaunchKernelGGL(select_clear_kernel, dim3((unsigned)((words + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream,
+                         (unsigned long long*)ws, words);
+      hipLaunchKernelGGL((nonzero_fused_kernel<FES>), dim3((unsigned)ntiles), dim3(kFusedBlock), 0, stream, a, ntiles, pair_rows);
+      set_path("nonzero-fused");
+      return check_launch("single-pass nonzero kernel");
     }
   }
   if (a.shape.numel > 0) {

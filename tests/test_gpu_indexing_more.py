@@ -140,7 +140,7 @@ def run_select(fn_bytes, fn, out, what):
     fn(out, count, ws)
     used = B.tx_last_path()
     torch.cuda.synchronize()
-    if used == "select-fused":
+    if used in ("select-fused", "nonzero-fused"):
         B.tx_lookback_status(ws)                       # raises if a bounded look-back wait gave up
     return int(count.item()), used
 
@@ -213,7 +213,14 @@ def test_nonzero_sweep():
                 keep = I.bernoulli_mask(shape, p, seed=430)
                 x = (I.typed(shape, dt, seed=431) if dt != BOOL else torch.ones(shape, dtype=BOOL))
                 x = torch.where(keep, x, torch.zeros((), dtype=dt))
-                assert check_nonzero(x, what="p=%g" % p) == ("select" if x.numel() % 4 == 0 else "select-slab")
+                # whole vectors of 4 elements: the single pass; anything else: one element per lane, three passes
+                assert check_nonzero(x, what="p=%g" % p) == ("nonzero-fused" if x.numel() % 4 == 0 else "select-slab")
+                if x.numel() % 4 == 0:
+                    B.tx_force_path("select-3pass")
+                    try:
+                        assert check_nonzero(x, what="three passes, p=%g" % p) == "select"
+                    finally:
+                        B.tx_force_path(None)
         x = torch.where(I.bernoulli_mask((6, 50, 7), 0.3, seed=432), I.typed((6, 50, 7), dt, seed=433) if dt != BOOL
                         else torch.ones((6, 50, 7), dtype=BOOL), torch.zeros((), dtype=dt))
         assert check_nonzero(x.permute(2, 0, 1), what="permuted") == "select-strided"
@@ -236,7 +243,7 @@ def test_compaction_both_contiguous_forms_agree_with_oracle():
         x = I.typed((300, 1024), dt, seed=445) if dt != BOOL else I.booleans((300, 1024), 0.5, seed=445)
         m = I.bernoulli_mask((300, 1024), 0.3, seed=446)
         xs = torch.where(m, x, torch.zeros((), dtype=dt))
-        assert check_masked_select(x, m) == "select" and check_nonzero(xs) == "select"
+        assert check_masked_select(x, m) == "select" and check_nonzero(xs) == "nonzero-fused"
         B.tx_force_path("select-fused")
         try:
             assert check_masked_select(x, m) == "select-fused"
@@ -266,7 +273,17 @@ def test_compaction_full_size():
     finally:
         B.tx_force_path(None)
     xs = torch.where(I.bernoulli_mask((8192, 4096), 0.1, seed=442), x[:, :4096], torch.zeros(()))
-    assert check_nonzero(xs) == "select"
+    assert check_nonzero(xs) == "nonzero-fused"
+    assert check_nonzero(xs, capacity=1000003, what="small buffer") == "nonzero-fused"
+    assert check_nonzero(xs.view(64, 128, 4096), what="three coordinates") == "nonzero-fused"
+    for p in (0.0, 1.0):                                                # nothing / everything non-zero, many tiles
+        assert check_nonzero(torch.full((1024, 4100), p), what="all %g" % p) == "nonzero-fused"
+    assert check_nonzero(xs.to(I64)[:3000], what="8-byte elements") == "nonzero-fused"
+    B.tx_force_path("select-3pass")
+    try:
+        assert check_nonzero(xs) == "select"
+    finally:
+        B.tx_force_path(None)
 
 
 # --------------------------------------------------------------------------- scatter_reduce_, index_put_
