@@ -483,7 +483,8 @@ PATH_KERNEL = {"vec": "ew_vec_kernel", "vec-bcast": "ew_bcast_kernel", "tile": "
                "rows-wave": "reduce_rows_kernel", "rows-block": "reduce_rows_kernel", "rows-split": "reduce_rows_kernel",
                "cols": "reduce_cols_kernel", "cols-split": "reduce_cols_kernel", "softmax-wave": "softmax_wave_kernel",
                "scan-lookback-wide": "cumsum_lookback_kernel", "scan-lookback": "cumsum_lookback_kernel",
-               "scan-carry": "cumsum_carry_kernel", "scan-cols-lookback": "colscan_lookback_kernel", "scan-cols-3pass": "colscan_apply_kernel", "softmax-row": "softmax_row_kernel", "index-select-rows": "index_select_rows_kernel",
+               "scan-carry": "cumsum_carry_kernel", "scan-cols-lookback": "colscan_lookback_kernel", "index-put-rows": "index_put_rows_kernel", "nonzero-fused": "nonzero_fused_kernel",
+               "softmax-cols-reg": "softmax_cols_reg_kernel", "softmax-cols": "softmax_cols_kernel", "scan-cols-3pass": "colscan_apply_kernel", "softmax-row": "softmax_row_kernel", "index-select-rows": "index_select_rows_kernel",
                "gather": "gather_kernel", "scatter-sort-rows": "seg_rows_kernel", "scatter-atomic": "scatter_add_atomic_kernel"}
 
 

@@ -610,6 +610,55 @@ __global__ __launch_bounds__(kBlock) void index_put_kernel(const PutArgs a) {
   }
 }
 
+// index_put_ without accumulation, one 1-D index over dim 0 and whole contiguous rows: index_select_rows_kernel the
+// other way round - source rows in order, destination rows picked by the index (negative indices wrap).  A row is
+// `vecs` 16-byte vectors.  With duplicate indices the destination row receives one of the candidate rows' vectors,
+// vector by vector, as it receives one of the candidates element by element on the general path.
+struct RowPutArgs {
+  const char* index;
+  const char* src;
+  char* dst;
+  int index_is64;
+  int64_t istride;
+  int64_t rows;               // number of indices = source rows
+  int64_t extent;             // self.size(0)
+  int64_t src_row, dst_row;   // byte strides of dim 0
+  int64_t vecs;
+};
+__global__ __launch_bounds__(kBlock) void index_put_rows_kernel(const RowPutArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t wave = (int64_t)blockIdx.x * (kBlock / kWave) + __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+  const int64_t r0 = wave * kRowsPerWave;
+  if (r0 >= a.rows) return;
+  int64_t so, d_o;
+  {
+    const int64_t r = std::min<int64_t>(r0 + (lane < kRowsPerWave ? lane : 0), a.rows - 1);    // clamped: the last row twice
+    int64_t k = load_index(a.index, r * a.istride, a.index_is64);
+    k += k < 0 ? a.extent : 0;
+    so = r * a.src_row;
+    d_o = k * a.dst_row;
+  }
+  auto lane_value = [&](int64_t v, int i) -> int64_t {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, i);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), i);
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+  };
+  const u32x4* sp[kRowsPerWave];
+  u32x4* dp[kRowsPerWave];
+#pragma unroll
+  for (int i = 0; i < kRowsPerWave; ++i) {
+    sp[i] = (const u32x4*)(a.src + lane_value(so, i));
+    dp[i] = (u32x4*)(a.dst + lane_value(d_o, i));
+  }
+  for (int64_t v = lane; v < a.vecs; v += kWave) {
+    u32x4 t[kRowsPerWave];
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) t[i] = __builtin_nontemporal_load(sp[i] + v);   // the values are read once
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i) dp[i][v] = t[i];
+  }
+}
+
 constexpr int kMaxChunk = 256;              // sorted rows per wave, at most
 constexpr int64_t kIntRowModeMin = 4096;    // integer row mode pays for its sort from about this many rows
 constexpr int kShortRun = 8;                // continuation pieces that one wave of the combine pass adds by itself
@@ -1655,6 +1704,36 @@ tx_status tx_index_put_(const tx_tensor* self, const tx_tensor* const* indices, 
   if (accumulate && index_put_as_rows(self, indices, nidx, values, &view))
     return scatter_core("index_put_", self, 0, &view, values, Alpha{1.0f, 1, self->sizes[0]}, 1, ws, ws_bytes, s);
   const dim3 grid((unsigned)((n + kBlock - 1) / kBlock));
+  if (!accumulate && index_put_as_rows(self, indices, nidx, values, &view) && self->ndim >= 2 && strcmp(forced_path(), "index-put") != 0) {
+    // whole rows: trailing dims dense in both tensors, rows of whole 16-byte vectors at 16-byte-aligned addresses
+    const int es = dtype_size(self->dtype);
+    int64_t row_elems = 1;
+    bool dense = true;
+    for (int d = self->ndim - 1; d >= 1; --d) {
+      if (self->sizes[d] != 1 && (self->strides[d] != row_elems || values->strides[d] != row_elems)) dense = false;
+      row_elems *= self->sizes[d];
+    }
+    const int64_t row_bytes = row_elems * es;
+    if (dense && row_bytes > 0 && row_bytes % 16 == 0 && (uintptr_t)self->data % 16 == 0 && (uintptr_t)values->data % 16 == 0 &&
+        (self->strides[0] * es) % 16 == 0 && (values->strides[0] * es) % 16 == 0 && self->strides[0] >= 0 && values->sizes[0] < (1ll << 31)) {
+      RowPutArgs r;
+      r.index = (const char*)indices[0]->data;
+      r.index_is64 = indices[0]->dtype == TX_I64;
+      r.istride = indices[0]->strides[0];
+      r.src = (const char*)values->data;
+      r.dst = (char*)self->data;
+      r.rows = values->sizes[0];
+      r.extent = self->sizes[0];
+      r.src_row = values->strides[0] * es;
+      r.dst_row = self->strides[0] * es;
+      r.vecs = row_bytes / 16;
+      const int64_t waves = (r.rows + kRowsPerWave - 1) / kRowsPerWave;
+      const int64_t blocks = (waves + (kBlock / kWave) - 1) / (kBlock / kWave);
+      set_path("index-put-rows");
+      hipLaunchKernelGGL(index_put_rows_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, s, r);
+      return check_launch("index_put row kernel");
+    }
+  }
   if (!accumulate) {
     set_path("index-put");
     switch (dtype_size(self->dtype)) {

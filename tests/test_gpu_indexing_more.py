@@ -394,7 +394,19 @@ def test_index_put_sweep():
         perm = torch.randperm(12 * 9, generator=g)[:50]
         u0, u1 = perm // 9, perm % 9 - 9                                       # second index given as negatives
         assert check_index_put(s, [u0, u1], mk((50, 16), 470), False) == "index-put"
-        check_index_put(s, [torch.randperm(12, generator=g)[:7]], mk((7, 9, 16), 471), False, what="rows")
+        # whole dense rows over dim 0: the row-copy kernel (negative indices wrap); by name, sliced or shifted: one lane per element
+        rp = torch.randperm(12, generator=g)[:7]
+        rp[::2] -= 12
+        used = check_index_put(s, [rp], mk((7, 9, 16), 471), False, what="rows")
+        assert used == ("index-put" if dt == BOOL else "index-put-rows"), (dt, used)
+        B.tx_force_path("index-put")
+        try:
+            assert check_index_put(s, [rp], mk((7, 9, 16), 471), False, what="rows, by name") == "index-put"
+        finally:
+            B.tx_force_path(None)
+        assert check_index_put(s[:, :, 1:], [rp], mk((7, 9, 15), 474), False, what="rows of a slice") == "index-put"
+        assert check_index_put(s, [rp[:5].to(I32)], mk((9, 9, 16), 475)[::2], False, what="strided values rows") == (
+            "index-put" if dt == BOOL else "index-put-rows")
         check_index_put(s, [u0, u1], mk((1, 16), 472), False, what="broadcast values")
         check_index_put(s, [u0[:0], u1[:0]], mk((0, 16), 473), True, what="no positions")
     d = lambda *s, dt=F32: torch.zeros(s, dtype=dt, device="cuda")
@@ -452,4 +464,5 @@ def test_scatter_reduce_and_index_put_larger():
     si = I.typed((4096, 256), I64, seed=483)
     check_index_put(si, [rows, torch.randint(0, 256, (65536,), generator=g)], I.typed((65536,), I64, seed=484), True)
     perm = torch.randperm(4096, generator=g)
-    assert check_index_put(s, [perm], I.typed((4096, 256), F32, seed=485), False) == "index-put"
+    assert check_index_put(s, [perm], I.typed((4096, 256), F32, seed=485), False) == "index-put-rows"
+    assert check_index_put(s, [perm[:4095] - 4096], I.typed((4095, 256), F32, seed=486), False, what="odd row count") == "index-put-rows"
