@@ -64,6 +64,19 @@ template <int OP, class T> struct BinFloat {
     return cvt<T>(r);
   }
 };
+// add / mul of one fp32 operand and one half operand into an fp32 result (the promoted dtype): static operand types,
+// so the loads carry no run-time dtype switch (the run-time-typed functor reaches 0.71 of peak on this pair)
+template <int OP, class TA, class TB> struct BinMixedF32 {
+  using Out = float; using In0 = TA; using In1 = TB; using In2 = void;
+  static constexpr int NIN = 2;
+  float alpha;
+  int flag;                 // kAdd: alpha == 1 (plain add)
+  __device__ __forceinline__ float operator()(TA xa, TB xb) const {
+    const float a = cvt<float>(xa), b = cvt<float>(xb);
+    if constexpr (OP == kAdd) return flag ? a + b : __fmaf_rn(alpha, b, a);
+    else return a * b;
+  }
+};
 template <class T> struct EqStatic {
   using Out = uint8_t; using In0 = T; using In1 = T; using In2 = void;
   static constexpr int NIN = 2;
@@ -215,6 +228,14 @@ template <int OP> tx_status dispatch_binary(const Iter& it, int da, int db, int 
         if (common == TX_F32) return launch_ew(it, BinFloat<OP, float>{(float)ad, fflag}, s);
         if (common == TX_BF16) return launch_ew(it, BinFloat<OP, bf16>{(float)ad, fflag}, s);
         return launch_ew(it, BinFloat<OP, f16>{(float)ad, fflag}, s);
+      }
+      if constexpr (OP == kAdd || OP == kMul) {
+        if (common == TX_F32 && !cast) {
+          if (da == TX_BF16 && db == TX_F32) return launch_ew(it, BinMixedF32<OP, bf16, float>{(float)ad, fflag}, s);
+          if (da == TX_F32 && db == TX_BF16) return launch_ew(it, BinMixedF32<OP, float, bf16>{(float)ad, fflag}, s);
+          if (da == TX_F16 && db == TX_F32) return launch_ew(it, BinMixedF32<OP, f16, float>{(float)ad, fflag}, s);
+          if (da == TX_F32 && db == TX_F16) return launch_ew(it, BinMixedF32<OP, float, f16>{(float)ad, fflag}, s);
+        }
       }
       return launch_ew(it, BinDynFloat<OP>{(float)ad, fflag, common}, s);
     }

@@ -220,7 +220,7 @@ namespace {
 // host-side stand-in; the device address comes from hipGetSymbolAddress, once per device, and only that address is
 // handed to kernels.
 constexpr size_t kStaticScratchBytes = TX_REDUCE_STATIC_SCRATCH_BYTES;
-__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices] = {nullptr};

@@ -25,12 +25,13 @@ def both(op, x_cpu, dims, keepdim=False):
     B.tx_reduce(op, ref, x, dims, keepdim, 1.0, B.workspace(nbytes) if nbytes else None)
     path = B.tx_last_path()
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
     got = torch.full(want.shape, 7, dtype=want.dtype, device="cuda")
-    held = torch.cuda.memory_allocated()
+    # the allocator's running count of allocation requests: it only grows, whatever the garbage collector frees meanwhile
+    # (bytes in use can drop inside the call when a collection releases tensors of earlier tests)
+    requests = torch.cuda.memory_stats()["allocation.all.allocated"]
     B.tx_reduce_static(op, got, x, dims, keepdim, 1.0)
     assert B.tx_last_path() == path
-    assert torch.cuda.memory_allocated() == held > before - 1          # nothing was allocated through torch by the call
+    assert torch.cuda.memory_stats()["allocation.all.allocated"] == requests        # nothing was allocated through torch by the call
     torch.cuda.synchronize()
     return got, ref, want, path, nbytes
 
