@@ -480,7 +480,7 @@ def cpu_baseline(torch, budget_s=2.0):
 
 # Kernel behind each dispatch path the step takes (paths are what the library reports for its last launch).
 PATH_KERNEL = {"vec": "ew_vec_kernel", "vec-bcast": "ew_bcast_kernel", "tile": "ew_tile_vec_kernel", "tile-scalar": "ew_tile_kernel", "generic": "ew_generic_kernel",
-               "rows-wave": "reduce_rows_kernel", "rows-block": "reduce_rows_kernel", "rows-split": "reduce_rows_kernel",
+               "rows-wave": "reduce_rows_kernel", "rows-half": "reduce_rows_kernel", "rows-block": "reduce_rows_kernel", "rows-split": "reduce_rows_kernel",
                "cols": "reduce_cols_kernel", "cols-split": "reduce_cols_kernel", "softmax-wave": "softmax_wave_kernel",
                "scan-lookback-wide": "cumsum_lookback_kernel", "scan-lookback": "cumsum_lookback_kernel",
                "scan-carry": "cumsum_carry_kernel", "scan-cols-lookback": "colscan_lookback_kernel", "index-put-rows": "index_put_rows_kernel", "nonzero-fused": "nonzero_fused_kernel",

@@ -644,7 +644,8 @@ tx_status tx_lookback_status(const void* ws, void* stream);
  * and "scan-lookback-giveup" (the look-back kernel with a poll limit of zero:
  * every wait gives up at once, for testing tx_lookback_status).
  * Reduction with lanes along the kept dim: "cols-nv1", "cols-nv2", "cols-nv4"
- * (vectors per thread).  Integer scatter_add_: "scatter-atomic" (one atomic
+ * (vectors per thread); over rows of 1 to 2 KiB: "rows-wave" (a wave per row
+ * instead of half a wave, "rows-half").  Integer scatter_add_: "scatter-atomic" (one atomic
  * per element even when a workspace is given).  scatter_reduce_:
  * "scatter-reduce-sort" (element keys even for a broadcast row index).
  * softmax along a contiguous last dim: "softmax-wave" (a wave per row, for rows

@@ -88,6 +88,11 @@ void plan_launch(Plan* p, const tx_tensor* x, int esize, bool) {
     // loads a lane keeps in flight would sit a whole outer stride apart, and a wave per output reads them as
     // one contiguous piece instead
     p->group = (p->rsize[p->nr - 1] * esize >= 16384) ? kBlock : kWave;
+    // rows of 1 to 2 KiB, and many of them: half a wave per row, so that a lane still has four vectors in flight and
+    // a workgroup covers 8 rows (a wave per 2 KiB row leaves two loads per lane and twice the workgroups)
+    if (p->vec > 1 && p->nr == 1 && p->nred * esize > 1024 && p->nred * esize <= 2048 && p->nout >= 65536 &&
+        strcmp(forced_path(), "rows-wave") != 0)
+      p->group = kWave / 2;
     const int gpb = kBlock / p->group;
     p->blocks_x = (p->nout + gpb - 1) / gpb;
     const int64_t step = (int64_t)p->group * p->vec;

@@ -37,7 +37,7 @@ struct Plan {
   int64_t nout, nred;
   int single_dim;                   // argmax position = coordinate along the one reduced dim (== r)
   int vec;                          // elements per load (1 or 16/sizeof(T))
-  int group;                        // rows: lanes per output (64 or 256)
+  int group;                        // rows: lanes per output (32, 64 or 256)
   int nv;                           // cols: vectors per thread (1, 2 or 4)
   double aux;                       // per-op switch handed to Policy::finish (std: 1 = square root; any / all: 1 = all)
   int split;                        // S
@@ -479,9 +479,11 @@ __global__ __launch_bounds__(kBlock) void reduce_rows_kernel(const Args a) {
       step_vec<P, T, VEC>(acc, v, r, K);
     }
   }
-  // lanes of a wave
+  // lanes of a group (a wave, or half a wave for short rows: the exchange then stays inside each half)
 #pragma unroll
-  for (int m = kWave / 2; m >= 1; m >>= 1) { Acc other = P::shfl(acc, m); P::merge(acc, other); }
+  for (int m = kWave / 2; m >= 1; m >>= 1) {
+    if (m < G) { Acc other = P::shfl(acc, m); P::merge(acc, other); }
+  }
   if (G == kBlock) {
     const int w = threadIdx.x / kWave;
     if ((threadIdx.x & (kWave - 1)) == 0) lds[w] = acc;
@@ -657,7 +659,7 @@ template <class P> tx_status launch(const Plan& p, const tx_tensor* x, const tx_
   dim3 grid((unsigned)p.blocks_x, (unsigned)p.split);
   const bool one = p.nr == 1;
   if (p.kind == 0) {
-    set_path(p.split > 1 ? "rows-split" : (p.group == kBlock ? "rows-block" : "rows-wave"));
+    set_path(p.split > 1 ? "rows-split" : (p.group == kBlock ? "rows-block" : p.group < kWave ? "rows-half" : "rows-wave"));
     if (p.vec > 1 && one) hipLaunchKernelGGL((reduce_rows_kernel<P, V, true>), grid, dim3(kBlock), 0, stream, a);
     else if (p.vec > 1) hipLaunchKernelGGL((reduce_rows_kernel<P, V, false>), grid, dim3(kBlock), 0, stream, a);
     else hipLaunchKernelGGL((reduce_rows_kernel<P, 1, false>), grid, dim3(kBlock), 0, stream, a);

@@ -96,6 +96,21 @@ def check_reduce_keepdim_form(op, x_cpu, dims):
 DIMSETS = [0, -1, 1, (0, 2), None]
 
 
+@pytest.mark.parametrize("op", ["sum", "argmax", "var", "amin", "logsumexp"])
+def test_reduce_short_rows_half_a_wave_per_row(op):
+    """Many rows of 1 to 2 KiB: half a wave per row; the same rows with a wave each, by name."""
+    for dt, shape in ((BF16, (70000, 1024)), (F32, (66000, 512)), (F32, (65536, 260)), (BF16, (2, 33000, 520))):
+        x = I.reduction_input(shape, dt, seed=77)
+        assert check_reduce(op, x, -1) == "rows-half", (dt, shape)
+        B.tx_force_path("rows-wave")
+        try:
+            assert check_reduce(op, x, -1, what="a wave per row") == "rows-wave"
+        finally:
+            B.tx_force_path(None)
+    assert check_reduce(op, I.reduction_input((66000, 256), F32, seed=78), -1) == "rows-wave"        # 1 KiB: a wave
+    assert check_reduce(op, I.reduction_input((1000, 512), F32, seed=79), -1) == "rows-wave"         # too few rows
+
+
 @pytest.mark.parametrize("op", OPS)
 def test_reduce_small_sweep(op):
     for dt, dims, keepdim in itertools.product([F32, BF16, F16, I32, I64, BOOL], DIMSETS, [False, True]):
