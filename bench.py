@@ -218,12 +218,20 @@ def build_ops(torch, B):
     lwb, lbb = lw.to(BF16), lb.to(BF16)
     lx = randn(S, std=2.0)
     lxb = lx.to(BF16)
-    extra("layer_norm_f32[32768,4096]", "f2", "layer_norm_wave_kernel", ns * 8, ns, lambda: B.tx_layer_norm(osf, lx, 1, lw, lb))
-    extra("layer_norm_bf16[32768,4096]", "f2", "layer_norm_wave_kernel", ns * 4, ns,
+    extra("layer_norm_f32[32768,4096]", "f2", "layer_norm_row_kernel", ns * 8, ns, lambda: B.tx_layer_norm(osf, lx, 1, lw, lb))
+    extra("layer_norm_bf16[32768,4096]", "f2", "layer_norm_row_kernel", ns * 4, ns,
           lambda: B.tx_layer_norm(osb, lxb, 1, lwb, lbb))
+    extra("layer_norm_f32[32768,4096]_workgroup_per_row", "f2", "layer_norm_rows_kernel", ns * 8, ns,
+          forced("layer-norm-block", lambda: B.tx_layer_norm(osf, lx, 1, lw, lb)))
+    extra("layer_norm_bf16[32768,4096]_workgroup_per_row", "f2", "layer_norm_rows_kernel", ns * 4, ns,
+          forced("layer-norm-block", lambda: B.tx_layer_norm(osb, lxb, 1, lwb, lbb)))
+    extra("layer_norm_f32[32768,4096]_wave_per_row", "f2", "layer_norm_rows_kernel", ns * 8, ns,
+          forced("layer-norm-wave", lambda: B.tx_layer_norm(osf, lx, 1, lw, lb)))
+    extra("layer_norm_bf16[32768,4096]_wave_per_row", "f2", "layer_norm_rows_kernel", ns * 4, ns,
+          forced("layer-norm-wave", lambda: B.tx_layer_norm(osb, lxb, 1, lwb, lbb)))
     l2 = lx.view(131072, 1024)
     o2 = osf.view(131072, 1024)
-    extra("layer_norm_f32[131072,1024]", "f2", "layer_norm_wave_kernel", ns * 8, ns,
+    extra("layer_norm_f32[131072,1024]", "f2", "layer_norm_rows_kernel", ns * 8, ns,
           lambda: B.tx_layer_norm(o2, l2, 1, lw[:1024], lb[:1024]))
     l3 = lx.view(8192, 16384)
     o3 = osf.view(8192, 16384)

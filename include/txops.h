@@ -657,8 +657,11 @@ tx_status tx_lookback_status(const void* ws, void* stream);
  * columns are cut into several tiles: "scan-cols-3pass" (tile sums, their
  * prefixes and the scan as three kernels instead of the single pass with
  * look-back between tiles, "scan-cols-lookback") and
- * "scan-cols-lookback-giveup" (poll limit zero, as above).  layer_norm: "layer-norm-block" (one
- * workgroup per row), "layer-norm-generic" (three passes, any strides).
+ * "scan-cols-lookback-giveup" (poll limit zero, as above).  layer_norm:
+ * "layer-norm-wave" (a wave per row also for rows of 257 to 1024 vectors,
+ * which otherwise take a workgroup per row, "layer-norm-row"), "layer-norm-block"
+ * (the general workgroup-per-row kernel), "layer-norm-generic" (three passes,
+ * any strides).
  * masked_select: "select-fused" (one pass with decoupled look-back instead of
  * the count, offsets and write passes); nonzero: "select-3pass" (those three
  * passes instead of its single pass, "nonzero-fused").  binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace

@@ -57,15 +57,20 @@ def check_layer_norm(x_cpu, k, w_cpu=None, b_cpu=None, eps=1e-5, path=None, out_
 @pytest.mark.parametrize("dt", [F32, BF16, F16])
 def test_layer_norm_row_lengths_and_paths(dt):
     V = 16 // torch.empty(0, dtype=dt).element_size()
-    for rows, length in [(37, 4), (5, 64 * V), (9, 64 * V + V), (6, 200 * V), (5, 512 * V), (3, 1024 * V), (2, 1024 * V + V),
+    for rows, length in [(37, 4), (5, 64 * V), (9, 64 * V + V), (6, 200 * V), (7, 256 * V), (4, 256 * V + V), (5, 512 * V),
+                         (6, 512 * V + V), (5, 700 * V), (3, 1024 * V), (2, 1024 * V + V),
                          (2, 2048 * V), (2, 4096 * V), (2, 4096 * V + V), (7, 333), (3, 5000), (1, 1), (4, 2)]:
         x = I.typed((rows, length), dt, seed=300 + length) * 2 + 0.5
         w, b = I.typed((length,), dt, seed=301), I.typed((length,), dt, seed=302)
         used = check_layer_norm(x, 1, w, b)
+        # a wave per row up to 256 vectors, a 256-lane workgroup per row with 2 or 4 vectors per lane up to 1024,
+        # the general workgroup form up to 4096
         expect = "layer-norm-generic" if length % V or length > 4096 * V else \
-            "layer-norm-wave" if length <= 1024 * V else "layer-norm-block"
+            "layer-norm-wave" if length <= 256 * V else "layer-norm-row" if length <= 1024 * V else "layer-norm-block"
         assert used == expect, (rows, length, used)
         check_layer_norm(x, 1, w, b, path="layer-norm-generic", what="forced generic")
+        if expect == "layer-norm-row":
+            assert check_layer_norm(x, 1, w, b, path="layer-norm-wave", what="forced wave") == "layer-norm-wave"
         if length % V == 0 and length <= 4096 * V:
             assert check_layer_norm(x, 1, w, b, path="layer-norm-block", what="forced block") == "layer-norm-block"
         check_layer_norm(x, 1, None, None, what="no affine")
@@ -125,7 +130,8 @@ def test_layer_norm_full_size(dt, shape):
     x = I.typed(shape, dt, seed=330) * 2 + 0.25
     w, b = I.typed(shape[-1:], dt, seed=331), I.typed(shape[-1:], dt, seed=332)
     used = check_layer_norm(x, 1, w, b)
-    assert used == ("layer-norm-wave" if shape[1] <= 4096 else "layer-norm-block")
+    V = 16 // x.element_size()
+    assert used == ("layer-norm-wave" if shape[1] <= 256 * V else "layer-norm-row" if shape[1] <= 1024 * V else "layer-norm-block")
 
 
 # --------------------------------------------------------------------------- binary_cross_entropy
