@@ -238,7 +238,9 @@ __global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs
   if (ticket >= a.total_tiles) return;
   // tickets walk the rows round-robin (tile t of every row, then tile t + 1, ...): a tile's predecessors in its row
   // still have smaller tickets, and the workgroups resident at one time are spread over all rows instead of sitting
-  // in one or two of them, which shortens every look-back chain
+  // in one or two of them, which shortens every look-back chain (row-major tickets - a contiguous window of resident
+  // tiles, but each waiting on the tile just before it - measured 365 against 355 us on [4096,65536] fp32, 745 against
+  // 685 us on int64, 241 against 200 us on 8 rows of 16 Mi)
   const int64_t t = ticket / a.rows, row = ticket - t * a.rows;
   const int64_t slot = row * a.tiles_per_row + t;      // status word of this tile (row-major)
   const T* x = (const T*)a.x + row * a.xrow + t * kTileElems;
