@@ -60,6 +60,8 @@ template <class T, class V> __device__ __forceinline__ V scaled(V v, float alpha
 
 // Each lane handles kGatherU elements (a workgroup covers kGatherU consecutive runs of 256): all index loads
 // are issued first, then all data-dependent source loads, so several random accesses are in flight per lane.
+// (Every random 4-byte element costs a 128-byte read from HBM; loading it with system scope - the sc0 sc1 bits, an
+// L2 bypass - changes neither the request size, still 4.44 M requests of 128 bytes for 4.19 M elements, nor the time.)
 constexpr int kGatherU = 4;
 template <class B>
 __global__ __launch_bounds__(kBlock) void gather_kernel(const ElemArgs a, int index_1d) {
