@@ -23,8 +23,8 @@ MiB = 1 << 20
 # HBM bytes per launch from the hardware counters (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE; the text summary under
 # profiles/ has the commands and the copy calibration: bytes = 2.0 x FETCH_SIZE KiB + 1.0 x WRITE_SIZE KiB).  An entry
 # is valid only for the kernel version it was measured on: remove it when that kernel changes.
-PMC_TRAFFIC_BYTES = {"index_select_f32": (2 * 2122808 + 4194429) * 1024,
-                     "gather_f32": (2 * 277626 + 16384) * 1024}
+PMC_TRAFFIC_BYTES = {"index_select_f32": (2 * 2122803 + 4194442) * 1024,
+                     "gather_f32": (2 * 277623 + 16384) * 1024}
 
 
 def build_ops(torch, B):
