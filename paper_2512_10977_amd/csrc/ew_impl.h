@@ -658,9 +658,12 @@ __global__ __launch_bounds__(kBlock) void ew_tile_vec_kernel(const F f, const Ti
   using V1 = typename ValueOf<typename F::In1>::type;
   using V2 = typename ValueOf<typename F::In2>::type;
   using VO = typename ValueOf<typename F::Out>::type;
-  __shared__ V0 l0[TV::T * TV::PITCH];
-  __shared__ V1 l1[F::NIN >= 2 ? TV::T * TV::PITCH : 1];
-  __shared__ V2 l2[F::NIN >= 3 ? TV::T * TV::PITCH : 1];
+  // LDS only for the operands that are staged: an array per input whether transposed or not left a binary operator
+  // with one transposed input half the resident workgroups of the transposed copy
+  constexpr bool t0 = (TMASK & 1) != 0, t1 = (TMASK & 2) != 0, t2 = (TMASK & 4) != 0;
+  __shared__ V0 l0[t0 ? TV::T * TV::PITCH : 1];
+  __shared__ V1 l1[t1 ? TV::T * TV::PITCH : 1];
+  __shared__ V2 l2[t2 ? TV::T * TV::PITCH : 1];
   uint32_t rest, tc, batch, tr;
   // diagonal walk over the tile grid (see ew_tile_kernel): 180 us -> 148 us for fp32 [8192,8192]
   a.tiles_r.divmod(blockIdx.x, rest, tr);
@@ -675,7 +678,6 @@ __global__ __launch_bounds__(kBlock) void ew_tile_vec_kernel(const F f, const Ti
   Vec<V0, TV::V> g0[TV::PASSES];
   Vec<V1, TV::V> g1[TV::PASSES];
   Vec<V2, TV::V> g2[TV::PASSES];
-  constexpr bool t0 = (TMASK & 1) != 0, t1 = (TMASK & 2) != 0, t2 = (TMASK & 4) != 0;
   if constexpr (t0) tilev_stage_load<typename F::In0, F>(a, 1, boff[1], r0, c0, g0);
   else tilev_straight_load<typename F::In0, F>(a, 1, boff[1], r0, c0, g0);
   if constexpr (F::NIN >= 2) {
@@ -702,11 +704,14 @@ __global__ __launch_bounds__(kBlock) void ew_tile_vec_kernel(const F f, const Ti
     V2 x2[TV::V];
 #pragma unroll
     for (int j = 0; j < TV::V; ++j) {
-      x0[j] = t0 ? l0[(lc + j) * TV::PITCH + lr] : g0[k].v[j];
-      if constexpr (F::NIN >= 2) x1[j] = t1 ? l1[(lc + j) * TV::PITCH + lr] : g1[k].v[j];
-      else x1[j] = V1();
-      if constexpr (F::NIN >= 3) x2[j] = t2 ? l2[(lc + j) * TV::PITCH + lr] : g2[k].v[j];
-      else x2[j] = V2();
+      if constexpr (t0) x0[j] = l0[(lc + j) * TV::PITCH + lr];
+      else x0[j] = g0[k].v[j];
+      if constexpr (F::NIN < 2) x1[j] = V1();
+      else if constexpr (t1) x1[j] = l1[(lc + j) * TV::PITCH + lr];
+      else x1[j] = g1[k].v[j];
+      if constexpr (F::NIN < 3) x2[j] = V2();
+      else if constexpr (t2) x2[j] = l2[(lc + j) * TV::PITCH + lr];
+      else x2[j] = g2[k].v[j];
     }
     if (r < a.rows && c < a.cols) {             // cols is a multiple of V on this path
       Vec<VO, TV::V> y;
