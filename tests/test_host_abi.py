@@ -129,6 +129,18 @@ def test_workspace_queries_are_host_only():
     oi = torch.zeros((4, 65536), dtype=torch.int64)
     assert B.tx_cumsum_workspace_bytes(oi, xi, -1) == 256 + 4 * 32 * 32         # 32 tiles of 2048, 4 words each
     assert B.tx_cumsum_workspace_bytes(out.t(), x.t(), 0) > 0                   # still rows after merging? (strided rows)
+    # columns cut into tiles: the query covers both forms, so a path forced by name never finds the workspace short.
+    # [4096, 512] over dim 0: 2 strips of 256 columns, 32 look-back tiles of 128 rows each (one 8-byte status word per
+    # column and tile, after the 256-byte header), against 64 tile sums per column for the three-pass form
+    xc, oc = torch.zeros((4096, 512)), torch.zeros((4096, 512))
+    look = 256 + 2 * 32 * 256 * 8
+    three = 64 * 512 * 4
+    assert B.tx_cumsum_workspace_bytes(oc, xc, 0) == max(look, three)
+    # int64 accumulators: 128-column strips, four status words per column and tile
+    xl, ol = torch.zeros((4096, 512), dtype=torch.int32), torch.zeros((4096, 512), dtype=torch.int64)
+    assert B.tx_cumsum_workspace_bytes(ol, xl, 0) == max(256 + 4 * 32 * 128 * 32, 64 * 512 * 8)
+    # enough strips to fill the chip: every workgroup walks its whole column, no workspace
+    assert B.tx_cumsum_workspace_bytes(torch.zeros((64, 1 << 20)), torch.zeros((64, 1 << 20)), 0) == 0
     big = torch.zeros((1 << 22,))
     assert B.tx_reduce_workspace_bytes("sum", torch.zeros(()), big, None) > 0
     assert B.tx_reduce_workspace_bytes("sum", torch.zeros((4096,)), torch.zeros((4096, 1024)), 1) == 0
