@@ -398,8 +398,12 @@ struct ScanPlan {
   size_t ws_bytes;
 };
 
+// elements per vector: 16 bytes of input, but at most 8 elements (a bool input with its 8-byte accumulators would
+// otherwise hold 64 accumulators per lane and spill them)
+template <class T> constexpr int scan_vec() { return sizeof(T) == 1 ? 8 : 16 / (int)sizeof(T); }
+
 template <class T, class O, class Acc> ScanPlan scan_plan(const tx_tensor* out, const tx_tensor* x, int dim, const Slices& sl) {
-  constexpr int V = 16 / sizeof(T);
+  constexpr int V = scan_vec<T>();
   ScanPlan p;
   memset(&p, 0, sizeof(p));
   const int nd = x->ndim;
@@ -425,7 +429,7 @@ template <class T, class O, class Acc> ScanPlan scan_plan(const tx_tensor* out, 
 template <class T, class O, class Acc, class OP = ScanAdd>
 tx_status cumsum_launch(const tx_tensor* out, const tx_tensor* x, int dim, void* ws, size_t ws_bytes, hipStream_t stream,
                         size_t* query) {
-  constexpr int V = 16 / sizeof(T);
+  constexpr int V = scan_vec<T>();
   Slices sl;
   build_slices(&sl, x, out, x->ndim ? dim : -1);
   ScanPlan p = scan_plan<T, O, Acc>(out, x, dim, sl);
