@@ -384,6 +384,31 @@ __global__ __launch_bounds__(kBlock) void select_write_quad_kernel(const SelectA
   }
   if (lane == 0) wave_count[w] = c;
   __syncthreads();
+  if constexpr (!NONZERO) {
+    // The selected elements are first put in output order in LDS, then written by consecutive lanes to consecutive
+    // addresses (stored straight from the registers they form four interleaved streams with gaps between the lanes).
+    __shared__ P ordered[kTile];
+    uint32_t local = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i) {
+      if (i < w) local += wave_count[i];
+      total += wave_count[i];
+    }
+#pragma unroll
+    for (int q = 0; q < kQuads; ++q) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if ((f[q] >> j) & 1u) ordered[local + lane_prefix[q] + __popc(f[q] & ((1u << j) - 1u))] = pv[q].v[j];
+      local += quad_total[q];
+    }
+    __syncthreads();
+    const int64_t first = a.offsets[blockIdx.x];
+    for (uint32_t i = threadIdx.x; i < total; i += kBlock) {
+      const int64_t dst = first + i;
+      if (dst < a.capacity) ((P*)a.out)[dst * a.ostride0] = ordered[i];
+    }
+    return;
+  }
   int64_t pos = a.offsets[blockIdx.x];
   for (int i = 0; i < w; ++i) pos += wave_count[i];
 #pragma unroll
