@@ -664,7 +664,9 @@ tx_status tx_lookback_status(const void* ws, void* stream);
  * any strides).
  * masked_select: "select-fused" (one pass with decoupled look-back instead of
  * the count, offsets and write passes); nonzero: "select-3pass" (those three
- * passes instead of its single pass, "nonzero-fused").  binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
+ * passes instead of its single pass, "nonzero-fused").  index_put_ without
+ * accumulation: "index-put" (one lane per element also where whole dense rows
+ * would be copied by "index-put-rows").  binary_cross_entropy sum / mean: "bce-two-pass" (losses into the workspace
  * first; the workspace query then reports that form's size); tx_loss:
  * "loss-two-pass" likewise.  searchsorted: "searchsorted" (every probe from
  * memory, also where the first levels would be walked in LDS).  Requests that a path cannot
