@@ -52,12 +52,14 @@ struct ScanMul {
 };
 struct ScanLse {                                 // on LsePair accumulators
   template <class A> __device__ __forceinline__ static A id() { return LsePair{-__builtin_inff(), 0.0f}; }
-  // both sums are rescaled to the larger exponent.  The exponent difference is taken as 0 when the two are equal, so
-  // equal infinities do not produce inf - inf; exp(-inf) = 0 removes the side that has met nothing (or only -inf)
+  // the sum with the smaller exponent is rescaled to the larger one: one exponential (the other side's factor is 1).
+  // The exponent difference is taken as 0 when the two are equal, so equal infinities do not produce inf - inf;
+  // exp(-inf) = 0 removes a side that has met nothing (or only -inf), and a NaN sum on either side stays (NaN * 0)
   template <class A> __device__ __forceinline__ static A op(A a, A b) {
-    const float M = a.m > b.m ? a.m : b.m;
-    const float da = a.m == M ? 0.0f : a.m - M, db = b.m == M ? 0.0f : b.m - M;
-    return LsePair{M, a.s * __expf(da) + b.s * __expf(db)};
+    const float d = a.m == b.m ? 0.0f : -__builtin_fabsf(a.m - b.m);
+    const float e = __expf(d);
+    const bool a_big = a.m >= b.m;
+    return LsePair{a_big ? a.m : b.m, __builtin_fmaf(a_big ? b.s : a.s, e, a_big ? a.s : b.s)};
   }
 };
 
@@ -154,6 +156,28 @@ struct ScanArgs {
 
 template <class OP, class Acc> __device__ __forceinline__ Acc wave_inclusive(Acc v) {
   const int lane = threadIdx.x & (kWave - 1);
+  if constexpr (std::is_same<OP, ScanLse>::value) {
+    // logcumsumexp: when the exponents of the wave's lanes lie within 64 of each other (and are finite), every lane
+    // rescales its sum to the wave's largest exponent once and the scan is a plain running sum - one exponential per
+    // lane instead of two per lane and step.  A lane that has met nothing yet (-inf, 0) rescales to 0 and does not
+    // count for the spread; a NaN sum passes through the running sum as it passes through the general form.  Anything
+    // else (infinite exponents, a wider spread, where the small sums would lose their bits) takes the general form.
+    float M = v.m, lo = v.s == 0.0f ? __builtin_inff() : v.m;
+#pragma unroll
+    for (int d = kWave / 2; d >= 1; d >>= 1) {
+      M = __builtin_fmaxf(M, shfl_xor(M, d));
+      lo = __builtin_fminf(lo, shfl_xor(lo, d));
+    }
+    if (__builtin_fabsf(M) < __builtin_inff() && M - lo <= 64.0f) {          // the same verdict in every lane
+      float s = v.s * __expf(v.m - M);
+#pragma unroll
+      for (int d = 1; d < kWave; d <<= 1) {
+        const float o = shfl_up(s, d);
+        if (lane >= d) s += o;
+      }
+      return Acc{M, s};
+    }
+  }
 #pragma unroll
   for (int d = 1; d < kWave; d <<= 1) {
     Acc o = shfl_up(v, d);
@@ -219,8 +243,11 @@ __device__ __forceinline__ void scan_tile_store(O* ot, int64_t left, const Acc (
 // smaller tile is kept for inputs with too few tiles to fill the chip.  (A ticket counter per row instead - workgroup
 // b on row b mod rows - measured no better on [4096,65536] fp32 (352 against 358 us) and worse everywhere else: int64
 // 731 against 682 us, 8 rows of 16 Mi 251 against 200 us, cumprod 466 against 351 us.)
+// (A 1024-lane workgroup is four waves per SIMD: two of them fit a CU only up to 64 vector registers, and the
+// logcumsumexp instance came to 65 with its faster wave scan, which left one workgroup per CU and took 805 us instead
+// of 625 us; the second launch bound asks the compiler for 8 waves per SIMD where the accumulators are small enough.)
 template <class T, class O, class Acc, int VEC, int THREADS, int NV, class OP = ScanAdd>
-__global__ __launch_bounds__(THREADS) void cumsum_lookback_kernel(const ScanArgs a) {
+__global__ __launch_bounds__(THREADS, (THREADS == 1024 && sizeof(Acc) * VEC <= 32) ? 8 : 1) void cumsum_lookback_kernel(const ScanArgs a) {
   const Acc kId = OP::template id<Acc>();
   constexpr int kTileElems = THREADS * NV * VEC;
   constexpr int kWaves = THREADS / kWave;
