@@ -683,7 +683,8 @@ tx_status run_select(SelectArgs& a, void* ws, hipStream_t stream) {
   if constexpr (!NONZERO) {
     // an alternative kept for comparison: on [1048576,256] fp32 at 30 % selected it measured 391 us against 370 us
     // for the three passes (count 67, offsets 20, write 281) - what the look-back costs a 1024-lane workgroup that
-    // holds its tile in registers meanwhile is more than the second read of the mask
+    // holds its tile in registers meanwhile is more than the second read of the mask (the fp32 instance needs 78
+    // vector registers, so a CU holds one such workgroup; capped at 64 it spills 20 of them and takes 708 us)
     if (quad && a.shape.numel > 0 && !strcmp(forced_path(), "select-fused")) {
       const int64_t ntiles = fused_tiles(a.shape.numel);
       const int64_t words = (int64_t)(fused_ws_bytes(a.shape.numel) / 8);
