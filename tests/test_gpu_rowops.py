@@ -296,6 +296,25 @@ def test_cumsum_column_form():
     B.tx_lookback_status(ws)
 
 
+def test_cumsum_column_look_back_seeded_shapes():
+    """Seeded random shapes on the look-back form (ragged last tiles in rows and columns, one to five outer slices, every
+    accumulator type), each scanned three times: the association of the column sums depends on which tiles have
+    published by the time a tile looks back, and must stay inside the tolerance every time (integers exactly)."""
+    import random
+    rnd = random.Random(360)
+    seen = set()
+    for case in range(24):
+        outer = rnd.choice([1, 1, 2, 3, 5])
+        L = rnd.choice([129, 200, 257, 1000, 4097, 9000])
+        inner = rnd.choice([16, 33, 64, 100, 256, 260, 512, 1000])
+        dt = rnd.choice([F32, I64, I32, BF16, BOOL])
+        shape = (outer, L, inner) if outer > 1 else (L, inner)
+        x = I.cumsum_input(shape, dt, seed=361 + case) if dt != BOOL else I.booleans(shape, 0.5, seed=361 + case)
+        for rep in range(3):
+            seen.add(check_cumsum(x, len(shape) - 2, what="case %d call %d" % (case, rep)))
+    assert {"scan-cols-lookback", "scan-cols-lookback-scalar"} <= seen, seen
+
+
 def test_softmax_short_column_full_size():
     x = I.softmax_logits((512, 128, 2048), F32, seed=351)             # softmax over 128 channels: rows stay in registers
     for log in (False, True):
